@@ -1,0 +1,321 @@
+/*
+ * CPU oracle for the inference-time linear-angular attention layer of
+ * Castling-ViT (arXiv 2211.10526).  TEST INFRASTRUCTURE ONLY: this file is the
+ * slow, plain reference that the HIP library is checked against.  It shares no
+ * code with the HIP path and must never be on the product path.
+ *
+ * Everything is fp64, row-major, and written in the order the paper states it.
+ *
+ * Tensor layout (same as the library): q, k, v, out are [B][heads][N][d],
+ * token n = y*grid_w + x on a grid_h x grid_w grid; depthwise filters are
+ * [heads][d][ks][ks]; bias is [heads][d] or NULL.
+ *
+ * What each function follows:
+ *   oracle_l2_normalize     unit row vectors along the feature axis (Sec. 3.1
+ *                           text before Eq. 3; Sec. 3.2.1 after Eq. 8 and Eq. 9)
+ *   oracle_sim_angular      Eq. 4 (spectral angle) and Eq. 5 (angular kernel)
+ *   oracle_series_coeff     coefficient of the k-th residual term of Eq. 8
+ *   oracle_sim_series       partial sum of Eq. 8
+ *   oracle_sim_linear       the linear-angular terms of Eq. 8
+ *   oracle_dwconv           the DWConv term of Eq. 9 (M_DW * V), direct loops
+ *   oracle_forward_explicit the definition: explicit N x N similarity (Eq. 8
+ *                           linear terms) times V, row-normalised as in Eq. 3,
+ *                           plus DWConv (Eq. 9)
+ *   oracle_forward_explicit_rows  same definition, selected output rows only
+ *   oracle_state            reassociated K^T V state (Sec. 3.1, kernel-based
+ *                           linear attention; Eq. 3 sums)
+ *   oracle_forward          fast path: Eq. 3 with phi(x) = [x/|x| / sqrt(pi);
+ *                           1/sqrt(2)] so that phi(q).phi(k) = 1/2 + q.k/pi
+ *
+ * Readings taken where the paper is silent (also listed in the design notes):
+ *   - the 1/2 term multiplies the column sum of V (Eq. 8 gives Sim_ij = 1/2 +
+ *     ..., so Sim*V has 1/2 * sum_j V_j in every row);
+ *   - norm_mode 0 divides by the row sum of the similarity (Eq. 3's
+ *     denominator); norm_mode 1 is the literal Eq. 9 with no denominator;
+ *   - DWConv: zero "same" padding, stride 1, cross-correlation (no flip),
+ *     added outside the division;
+ *   - x / max(|x|, eps).
+ *
+ * Pins (tests/test_oracle_pins.py): closed forms for tiny cases, arccos /
+ * arcsin identities, textbook arcsin series coefficients, row-stochastic
+ * invariants, invariances, torch's grouped conv2d for the DWConv, explicit vs
+ * reassociated agreement.  The whole layer has no closed form: it is pinned by
+ * the sum of those (explicit form on tiny inputs + per-branch pins).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_BRANCH_LINEAR 1u
+#define ORACLE_BRANCH_DWCONV 2u
+
+static const double ORACLE_PI = 3.14159265358979323846264338327950288;
+
+/* x_hat = x / max(||x||_2, eps), row by row. */
+void oracle_l2_normalize(const double* x, int64_t rows, int d, double eps, double* out)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        double ss = 0.0;
+        for (int c = 0; c < d; ++c) ss += x[r * d + c] * x[r * d + c];
+        double nrm = sqrt(ss);
+        if (nrm < eps) nrm = eps;
+        for (int c = 0; c < d; ++c) out[r * d + c] = x[r * d + c] / nrm;
+    }
+}
+
+/* Eq. 4 + Eq. 5: A[t][j] = 1 - arccos(<q_t,k_j>/(|q_t||k_j|)) / pi, one head. */
+void oracle_sim_angular(const double* q, const double* k, int N, int d, double eps, double* A)
+{
+    double* qh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    oracle_l2_normalize(q, N, d, eps, qh);
+    oracle_l2_normalize(k, N, d, eps, kh);
+    for (int t = 0; t < N; ++t)
+        for (int j = 0; j < N; ++j) {
+            double x = 0.0;
+            for (int c = 0; c < d; ++c) x += qh[t * d + c] * kh[j * d + c];
+            if (x > 1.0) x = 1.0;
+            if (x < -1.0) x = -1.0;
+            A[(size_t)t * N + j] = 1.0 - acos(x) / ORACLE_PI;
+        }
+    free(qh);
+    free(kh);
+}
+
+/* Eq. 8 residual coefficient: (2k)! / (2^{2k} (k!)^2 (2k+1)), k >= 1. */
+double oracle_series_coeff(int k)
+{
+    /* (2k)!/(k!)^2 = C(2k,k), built as a running product to stay in range */
+    double binom = 1.0;
+    for (int i = 1; i <= k; ++i) binom *= (double)(k + i) / (double)i;
+    return binom / (pow(4.0, (double)k) * (2.0 * k + 1.0));
+}
+
+/* Eq. 8 truncated after `order` residual terms (order = 0: linear terms only). */
+double oracle_sim_series(double x, int order)
+{
+    double s = 0.5 + x / ORACLE_PI;
+    for (int k = 1; k <= order; ++k)
+        s += oracle_series_coeff(k) * pow(x, 2.0 * k + 1.0) / ORACLE_PI;
+    return s;
+}
+
+/* Linear-angular terms of Eq. 8: A[t][j] = 1/2 + (q_hat_t . k_hat_j) / pi, one head. */
+void oracle_sim_linear(const double* q, const double* k, int N, int d, double eps, double* A)
+{
+    double* qh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    oracle_l2_normalize(q, N, d, eps, qh);
+    oracle_l2_normalize(k, N, d, eps, kh);
+    for (int t = 0; t < N; ++t)
+        for (int j = 0; j < N; ++j) {
+            double x = 0.0;
+            for (int c = 0; c < d; ++c) x += qh[t * d + c] * kh[j * d + c];
+            A[(size_t)t * N + j] = 0.5 + x / ORACLE_PI;
+        }
+    free(qh);
+    free(kh);
+}
+
+/* One output value of the DWConv term of Eq. 9 at (b, h, y, x, c). */
+static double dwconv_at(const double* v, const double* w, const double* bias,
+                        int heads, int H, int W, int d, int ks,
+                        int b, int h, int y, int x, int c)
+{
+    const int r = ks / 2;
+    double acc = bias ? bias[h * d + c] : 0.0;
+    for (int dy = 0; dy < ks; ++dy)
+        for (int dx = 0; dx < ks; ++dx) {
+            int yy = y + dy - r, xx = x + dx - r;
+            if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
+            size_t tok = (size_t)yy * W + xx;
+            double val = v[(((size_t)b * heads + h) * ((size_t)H * W) + tok) * d + c];
+            acc += w[(((size_t)h * d + c) * ks + dy) * ks + dx] * val;
+        }
+    return acc;
+}
+
+/* DWConv on the value tokens over the token grid, direct loops. */
+void oracle_dwconv(const double* v, const double* w, const double* bias,
+                   int B, int heads, int H, int W, int d, int ks, double* out)
+{
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < heads; ++h)
+            for (int y = 0; y < H; ++y)
+                for (int x = 0; x < W; ++x)
+                    for (int c = 0; c < d; ++c) {
+                        size_t tok = (size_t)y * W + x;
+                        out[(((size_t)b * heads + h) * ((size_t)H * W) + tok) * d + c] =
+                            dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, y, x, c);
+                    }
+}
+
+/* Linear branch of one output row by the definition: sum_j A_tj v_j [/ sum_j A_tj]. */
+static void explicit_row(const double* qrow, const double* kh, const double* vu,
+                         int N, int d, int norm_mode, double eps, double* lin)
+{
+    double ss = 0.0;
+    for (int c = 0; c < d; ++c) ss += qrow[c] * qrow[c];
+    double nrm = sqrt(ss);
+    if (nrm < eps) nrm = eps;
+    double rowsum = 0.0;
+    for (int c = 0; c < d; ++c) lin[c] = 0.0;
+    for (int j = 0; j < N; ++j) {
+        double x = 0.0;
+        for (int c = 0; c < d; ++c) x += (qrow[c] / nrm) * kh[(size_t)j * d + c];
+        double a = 0.5 + x / ORACLE_PI;
+        rowsum += a;
+        for (int c = 0; c < d; ++c) lin[c] += a * vu[(size_t)j * d + c];
+    }
+    if (norm_mode == 0)
+        for (int c = 0; c < d; ++c) lin[c] /= rowsum;
+}
+
+/* The definition of the layer, all rows.  O(N^2 d) per head: small inputs only. */
+void oracle_forward_explicit(const double* q, const double* k, const double* v,
+                             const double* w, const double* bias,
+                             int B, int heads, int H, int W, int d, int ks,
+                             int norm_mode, unsigned branches, double eps, double* out)
+{
+    const int N = H * W;
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* lin = (double*)malloc(sizeof(double) * d);
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < heads; ++h) {
+            size_t base = ((size_t)b * heads + h) * (size_t)N * d;
+            oracle_l2_normalize(k + base, N, d, eps, kh);
+            for (int t = 0; t < N; ++t) {
+                for (int c = 0; c < d; ++c) lin[c] = 0.0;
+                if (branches & ORACLE_BRANCH_LINEAR)
+                    explicit_row(q + base + (size_t)t * d, kh, v + base, N, d, norm_mode, eps, lin);
+                for (int c = 0; c < d; ++c) {
+                    double dw = 0.0;
+                    if (branches & ORACLE_BRANCH_DWCONV)
+                        dw = dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, t / W, t % W, c);
+                    out[base + (size_t)t * d + c] = lin[c] + dw;
+                }
+            }
+        }
+    free(kh);
+    free(lin);
+}
+
+/* The definition on selected rows: row i is token tokens[i] of unit units[i]
+ * (unit = b*heads + h); out is [nrows][d].  O(N d) per row, any N. */
+void oracle_forward_explicit_rows(const double* q, const double* k, const double* v,
+                                  const double* w, const double* bias,
+                                  int B, int heads, int H, int W, int d, int ks,
+                                  int norm_mode, unsigned branches, double eps,
+                                  const int64_t* units, const int64_t* tokens, int64_t nrows,
+                                  double* out)
+{
+    const int N = H * W;
+    (void)B;
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* lin = (double*)malloc(sizeof(double) * d);
+    int64_t cached_unit = -1;
+    for (int64_t i = 0; i < nrows; ++i) {
+        int64_t u = units[i];
+        int t = (int)tokens[i];
+        int b = (int)(u / heads), h = (int)(u % heads);
+        size_t base = (size_t)u * (size_t)N * d;
+        if (u != cached_unit) {
+            oracle_l2_normalize(k + base, N, d, eps, kh);
+            cached_unit = u;
+        }
+        for (int c = 0; c < d; ++c) lin[c] = 0.0;
+        if (branches & ORACLE_BRANCH_LINEAR)
+            explicit_row(q + base + (size_t)t * d, kh, v + base, N, d, norm_mode, eps, lin);
+        for (int c = 0; c < d; ++c) {
+            double dw = 0.0;
+            if (branches & ORACLE_BRANCH_DWCONV)
+                dw = dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, t / W, t % W, c);
+            out[(size_t)i * d + c] = lin[c] + dw;
+        }
+    }
+    free(kh);
+    free(lin);
+}
+
+/* Reassociated state per unit, (d+1) x (d+1) row-major = [K_hat | 1]^T [V | 1]:
+ *   M[i][j] = sum_n k_hat[n][i] v[n][j]   (i, j < d)    K_hat^T V
+ *   M[i][d] = sum_n k_hat[n][i]                          K_hat column sum
+ *   M[d][j] = sum_n v[n][j]                              V column sum
+ *   M[d][d] = N                                                          */
+void oracle_state(const double* k, const double* v, int B, int heads, int N, int d,
+                  double eps, double* state)
+{
+    const int d1 = d + 1;
+    const int64_t units = (int64_t)B * heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; ++u) {
+        double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+        const double* vu = v + (size_t)u * N * d;
+        double* M = state + (size_t)u * d1 * d1;
+        oracle_l2_normalize(k + (size_t)u * N * d, N, d, eps, kh);
+        memset(M, 0, sizeof(double) * d1 * d1);
+        for (int n = 0; n < N; ++n) {
+            for (int i = 0; i < d; ++i) {
+                double ki = kh[(size_t)n * d + i];
+                for (int j = 0; j < d; ++j) M[i * d1 + j] += ki * vu[(size_t)n * d + j];
+                M[i * d1 + d] += ki;
+            }
+            for (int j = 0; j < d; ++j) M[d * d1 + j] += vu[(size_t)n * d + j];
+            M[d * d1 + d] += 1.0;
+        }
+        free(kh);
+    }
+}
+
+/* Fast path: Eq. 3 with the reassociated state; equals oracle_forward_explicit
+ * up to fp64 rounding order. */
+void oracle_forward(const double* q, const double* k, const double* v,
+                    const double* w, const double* bias,
+                    int B, int heads, int H, int W, int d, int ks,
+                    int norm_mode, unsigned branches, double eps, double* out)
+{
+    const int N = H * W;
+    const int d1 = d + 1;
+    const int64_t units = (int64_t)B * heads;
+    double* state = (double*)malloc(sizeof(double) * (size_t)units * d1 * d1);
+    if (branches & ORACLE_BRANCH_LINEAR) oracle_state(k, v, B, heads, N, d, eps, state);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; ++u) {
+        const int b = (int)(u / heads), h = (int)(u % heads);
+        const size_t base = (size_t)u * N * d;
+        const double* M = state + (size_t)u * d1 * d1;
+        double* qh = (double*)malloc(sizeof(double) * d);
+        for (int t = 0; t < N; ++t) {
+            double* o = out + base + (size_t)t * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            if (branches & ORACLE_BRANCH_LINEAR) {
+                oracle_l2_normalize(q + base + (size_t)t * d, 1, d, eps, qh);
+                /* den = phi(q) . sum_j phi(k_j) = N/2 + q_hat . ksum / pi */
+                double den = 0.5 * M[d * d1 + d];
+                for (int i = 0; i < d; ++i) den += qh[i] * M[i * d1 + d] / ORACLE_PI;
+                for (int j = 0; j < d; ++j) {
+                    /* num = phi(q) . sum_j phi(k_j)^T v_j = vsum/2 + q_hat . S / pi */
+                    double num = 0.5 * M[d * d1 + j];
+                    for (int i = 0; i < d; ++i) num += qh[i] * M[i * d1 + j] / ORACLE_PI;
+                    o[j] = (norm_mode == 0) ? num / den : num;
+                }
+            }
+            if (branches & ORACLE_BRANCH_DWCONV)
+                for (int c = 0; c < d; ++c)
+                    o[c] += dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, t / W, t % W, c);
+        }
+        free(qh);
+    }
+    free(state);
+}
+
+/* Number of threads the parallel-for above will use (1 without OpenMP). */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+void oracle_set_num_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int oracle_num_threads(void) { return 1; }
+void oracle_set_num_threads(int n) { (void)n; }
+#endif

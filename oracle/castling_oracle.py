@@ -1,0 +1,171 @@
+"""ctypes front end of oracle/castling_oracle.c (test infrastructure only).
+
+All arrays are float64 numpy arrays, C-contiguous:
+  q, k, v, out : [B, heads, N, d]  (N = grid_h * grid_w, token n = y*grid_w + x)
+  w            : [heads, d, ks, ks]
+  bias         : [heads, d] or None
+See the C file's header for which passage of the paper each function follows.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+BRANCH_LINEAR = 1
+BRANCH_DWCONV = 2
+BRANCH_ALL = 3
+NORM_ROWSUM = 0
+NORM_NONE = 1
+DEFAULT_EPS = 1e-12
+
+_lib = None
+_dp = C.POINTER(C.c_double)
+_ip = C.POINTER(C.c_int64)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.oracle_l2_normalize.argtypes = [_dp, C.c_int64, C.c_int, C.c_double, _dp]
+        L.oracle_sim_angular.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_double, _dp]
+        L.oracle_sim_linear.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_double, _dp]
+        L.oracle_series_coeff.argtypes = [C.c_int]
+        L.oracle_series_coeff.restype = C.c_double
+        L.oracle_sim_series.argtypes = [C.c_double, C.c_int]
+        L.oracle_sim_series.restype = C.c_double
+        L.oracle_dwconv.argtypes = [_dp, _dp, _dp] + [C.c_int] * 6 + [_dp]
+        fwd = [_dp] * 5 + [C.c_int] * 6 + [C.c_int, C.c_uint, C.c_double]
+        L.oracle_forward_explicit.argtypes = fwd + [_dp]
+        L.oracle_forward.argtypes = fwd + [_dp]
+        L.oracle_forward_explicit_rows.argtypes = fwd + [_ip, _ip, C.c_int64, _dp]
+        L.oracle_state.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _dp]
+        L.oracle_num_threads.restype = C.c_int
+        L.oracle_set_num_threads.argtypes = [C.c_int]
+        for name in ("oracle_l2_normalize", "oracle_sim_angular", "oracle_sim_linear",
+                     "oracle_dwconv", "oracle_forward_explicit", "oracle_forward",
+                     "oracle_forward_explicit_rows", "oracle_state", "oracle_set_num_threads"):
+            getattr(L, name).restype = None
+        _lib = L
+    return _lib
+
+
+def _f64(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_dp)
+
+
+def l2_normalize(x, eps=DEFAULT_EPS):
+    x = _f64(x)
+    out = np.empty_like(x)
+    d = x.shape[-1]
+    lib().oracle_l2_normalize(_p(x), x.size // d, d, eps, _p(out))
+    return out
+
+
+def sim_angular(q, k, eps=DEFAULT_EPS):
+    """Eq. 5 similarity matrix of one head: q, k are [N, d] -> [N, N]."""
+    q, k = _f64(q), _f64(k)
+    N, d = q.shape
+    A = np.empty((N, N), dtype=np.float64)
+    lib().oracle_sim_angular(_p(q), _p(k), N, d, eps, _p(A))
+    return A
+
+
+def sim_linear(q, k, eps=DEFAULT_EPS):
+    """Linear-angular terms of Eq. 8 for one head: [N, d], [N, d] -> [N, N]."""
+    q, k = _f64(q), _f64(k)
+    N, d = q.shape
+    A = np.empty((N, N), dtype=np.float64)
+    lib().oracle_sim_linear(_p(q), _p(k), N, d, eps, _p(A))
+    return A
+
+
+def series_coeff(k: int) -> float:
+    return lib().oracle_series_coeff(int(k))
+
+
+def sim_series(x: float, order: int) -> float:
+    return lib().oracle_sim_series(float(x), int(order))
+
+
+def dwconv(v, w, bias, grid_h, grid_w):
+    v, w = _f64(v), _f64(w)
+    bias = None if bias is None else _f64(bias)
+    B, heads, N, d = v.shape
+    assert N == grid_h * grid_w and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    out = np.empty_like(v)
+    lib().oracle_dwconv(_p(v), _p(w), _p(bias), B, heads, grid_h, grid_w, d, w.shape[2], _p(out))
+    return out
+
+
+def _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps):
+    q, k, v, w = _f64(q), _f64(k), _f64(v), _f64(w)
+    bias = None if bias is None else _f64(bias)
+    B, heads, N, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape
+    assert N == grid_h * grid_w and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    keep = (q, k, v, w, bias)
+    args = [_p(q), _p(k), _p(v), _p(w), _p(bias), B, heads, grid_h, grid_w, d, w.shape[2],
+            int(norm), int(branches), float(eps)]
+    return keep, args, q.shape
+
+
+def forward_explicit(q, k, v, w, bias, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_ALL,
+                     eps=DEFAULT_EPS):
+    """The layer by its definition (explicit N x N similarity); small N only."""
+    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps)
+    out = np.empty(shape, dtype=np.float64)
+    lib().oracle_forward_explicit(*args, _p(out))
+    return out
+
+
+def forward(q, k, v, w, bias, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_ALL,
+            eps=DEFAULT_EPS):
+    """The layer by the reassociated (K^T V state) form; any N."""
+    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps)
+    out = np.empty(shape, dtype=np.float64)
+    lib().oracle_forward(*args, _p(out))
+    return out
+
+
+def forward_explicit_rows(q, k, v, w, bias, grid_h, grid_w, units, tokens, norm=NORM_ROWSUM,
+                          branches=BRANCH_ALL, eps=DEFAULT_EPS):
+    """Definition on selected rows (unit = b*heads + h, token); returns [nrows, d]."""
+    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps)
+    units = np.ascontiguousarray(units, dtype=np.int64)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int64)
+    order = np.argsort(units, kind="stable")      # group rows of one unit together
+    us, ts = np.ascontiguousarray(units[order]), np.ascontiguousarray(tokens[order])
+    out_sorted = np.empty((len(us), shape[-1]), dtype=np.float64)
+    lib().oracle_forward_explicit_rows(*args, us.ctypes.data_as(_ip), ts.ctypes.data_as(_ip),
+                                       len(us), _p(out_sorted))
+    out = np.empty_like(out_sorted)
+    out[order] = out_sorted
+    return out
+
+
+def state(k, v, eps=DEFAULT_EPS):
+    """[B, heads, d+1, d+1] = [K_hat | 1]^T [V | 1] per unit."""
+    k, v = _f64(k), _f64(v)
+    B, heads, N, d = k.shape
+    st = np.empty((B, heads, d + 1, d + 1), dtype=np.float64)
+    lib().oracle_state(_p(k), _p(v), B, heads, N, d, eps, _p(st))
+    return st
+
+
+def num_threads() -> int:
+    return lib().oracle_num_threads()
+
+
+def set_num_threads(n: int) -> None:
+    lib().oracle_set_num_threads(int(n))
