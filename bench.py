@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Throughput of the linear-angular attention layer on one MI355X.
+
+A step is one whole forward of the layer (reduce + apply: every kernel of the
+path) over one batch of synthetic, seeded inputs that are already resident in
+HBM.  The bench rotates over several distinct input sets so the loop cannot be
+served from the last-level cache.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 4]
+
+Prints one JSON line: tokens/s, the roofline of the dominant kernel (algorithmic
+bytes over its HIP-event-timed duration against the 8 TB/s HBM peak) and the CPU
+oracle timed on the host cores (a baseline, not the target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs (scaled by a copy kernel of known size); see profiles/.
+# workload name -> bytes, filled in from the committed summaries.
+MEASURED_TRAFFIC_BYTES: dict[str, float] = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="4",
+                    help="index (0-4) or name prefix of the benchmark workload; default the "
+                         "largest one (bf16, B=2, heads=12, d=64, 128x128 grid, 9x9 DWConv)")
+    ap.add_argument("--sets", type=int, default=6, help="distinct input sets to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the layer's units are independent; "
+              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2211_10526_amd import binding, inputs
+
+    wl = inputs.workload(int(args.workload) if args.workload.isdigit() else args.workload)
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    # distinct seeded input sets, all resident before timing starts
+    sets = []
+    for s in range(args.sets):
+        x = inputs.make_inputs(wl, seed=wl.seed + s)
+        t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+        t["out"] = torch.empty_like(t["q"])
+        sets.append(t)
+        if s == 0:
+            host0 = x
+    attn = binding.CastlingAttn.for_workload(wl)
+    stream = torch.cuda.Stream()
+
+    def fwd(t):
+        attn.forward(t["q"], t["k"], t["v"], t["w"], None, t["out"], stream=stream)
+
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            fwd(sets[i % len(sets)])
+        stream.synchronize()
+        torch.cuda.synchronize()
+
+        # ---- timed region: exactly K whole forwards
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            fwd(sets[i % len(sets)])
+        stream.synchronize()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+
+        # ---- the same K steps again, split at the reduce/apply boundary with HIP
+        # events recorded on the launch stream, for per-kernel durations
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        for i in range(args.steps):
+            t = sets[i % len(sets)]
+            ev[i][0].record(stream)
+            attn.reduce(t["k"], t["v"], stream=stream)
+            ev[i][1].record(stream)
+            attn.apply(t["q"], t["v"], t["w"], None, t["out"], stream=stream)
+            ev[i][2].record(stream)
+        stream.synchronize()
+        reduce_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        apply_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+        staged_ms = float(np.mean([e[0].elapsed_time(e[2]) for e in ev]))
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = wl.tokens * args.steps / elapsed
+    tensor_bytes = wl.elems * wl.itemsize
+    # algorithmic bytes: apply reads Q and V and writes out (3 tensors); reduce reads K and V
+    kernels = {"apply": (3 * tensor_bytes, apply_ms), "reduce": (2 * tensor_bytes, reduce_ms)}
+    dominant = max(kernels, key=lambda n: kernels[n][1])
+    dom_bytes, dom_ms = kernels[dominant]
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+        "algorithmic_bytes": dom_bytes, "kernel_ms": round(dom_ms, 5),
+        "reduce_ms": round(reduce_ms, 5), "apply_ms": round(apply_ms, 5),
+        "staged_step_ms": round(staged_ms, 5),
+        "layer_algorithmic_gbs_4tensor": round(4 * tensor_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "layer_frac_of_peak_4tensor": round(4 * tensor_bytes / (ms_per_step * 1e-3) / 1e9
+                                            / HBM_PEAK_GBS, 4),
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: as many whole (batch) images of the workload as fit ~10-30 s
+        flops_per_unit = wl.N * wl.d * (4.0 * wl.d + 2.0 * wl.dw_kernel ** 2)
+        est_s = flops_per_unit * wl.units / (0.4e9 * max(1, oracle.num_threads()))
+        nb = max(1, min(wl.B, int(wl.B * 20.0 / max(est_s, 1e-9))))
+        xs = {n: inputs.to_f64(host0[n][:nb]) for n in ("q", "k", "v")}
+        w64 = inputs.to_f64(host0["w"])
+        c0 = time.perf_counter()
+        oracle.forward(xs["q"], xs["k"], xs["v"], w64, None, wl.grid_h, wl.grid_w)
+        c1 = time.perf_counter() - c0
+        cpu_baseline = {
+            "value": round(nb * wl.N / c1, 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": f"{nb} of {wl.B} batch images of the workload ({nb * wl.heads} of "
+                      f"{wl.units} units), one pass, fp64, {c1:.2f} s",
+        }
+
+    n_split = attn.num_splits()
+    attn.destroy()
+    line = {
+        "metric": "linear-angular attention tokens/s per layer",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype if wl.dtype != "f32" else "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "d": wl.d, "N": wl.N,
+                   "grid": [wl.grid_h, wl.grid_w], "dw_kernel": wl.dw_kernel,
+                   "input_sets_rotated": len(sets), "reduce_splits": n_split},
+        "roofline": roofline, "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,117 @@
+/*
+ * castling_attn.h -- C ABI of the MI355X (gfx950) linear-angular attention layer.
+ *
+ * The layer is the inference-time attention of Castling-ViT (arXiv 2211.10526,
+ * Sec. 3.2.1).  Per (batch, head) unit with N tokens of width d it computes
+ *
+ *     q_hat_t = q_t / max(|q_t|, eps),  k_hat_j = k_j / max(|k_j|, eps)
+ *     A_tj    = 1/2 + (q_hat_t . k_hat_j) / pi          linear terms of Eq. 8
+ *     lin_t   = sum_j A_tj v_j / sum_j A_tj             Eq. 3 (row-sum normaliser)
+ *     out_t   = lin_t + DWConv(V)_t                     Eq. 9 (sparse branch is 0 at inference)
+ *
+ * without ever forming A: it is reassociated (Sec. 3.1, kernel-based linear
+ * attention) into the (d+1) x (d+1) state [K_hat | 1]^T [V | 1], i.e. K_hat^T V,
+ * the K_hat column sum, the V column sum and N, followed by one q_hat . state
+ * product per token.
+ *
+ * Conventions
+ *   - All tensor pointers are DEVICE pointers unless a parameter says "host".
+ *   - q, k, v, out: [B][heads][N][d] contiguous, N = grid_h * grid_w, token
+ *     n = y * grid_w + x (row-major grid, no class token).
+ *   - dw_weight: [heads][d][ks][ks] contiguous (one ks x ks filter per channel,
+ *     shared over the batch); dw_bias: [heads][d] or NULL.
+ *   - DWConv: zero "same" padding, stride 1, cross-correlation (no flip).
+ *   - io_dtype is the type of q, k, v, dw_weight, dw_bias and out.  Accumulation
+ *     is fp32 in all cases; bf16 outputs are rounded to nearest even.
+ *   - The caller owns every tensor.  A handle owns only its workspace (partial
+ *     states + final state), allocated by create and freed by destroy.
+ *   - forward / reduce / apply only enqueue work on `stream` (a hipStream_t, NULL
+ *     = the default stream) and never synchronise the host.  They may be called
+ *     from several handles concurrently; one handle is not thread-safe.
+ *   - Every function returns a castling_status_t (0 = OK).  Arguments are checked
+ *     on the host before anything is launched; no exception crosses the boundary.
+ *   - Results are run-to-run bitwise deterministic (no floating-point atomics).
+ */
+#ifndef CASTLING_ATTN_H
+#define CASTLING_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct castling_attn* castling_attn_t; /* opaque, owned by the library */
+
+typedef enum {
+    CASTLING_OK = 0,
+    CASTLING_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, N != grid_h*grid_w, even ks, misalignment */
+    CASTLING_ERR_UNSUPPORTED = 2, /* d, ks or dtype outside what the kernels are built for */
+    CASTLING_ERR_HIP = 3,         /* a HIP runtime call failed (allocation, launch) */
+    CASTLING_ERR_ALIAS = 4        /* out overlaps an input */
+} castling_status_t;
+
+typedef enum { CASTLING_F32 = 0, CASTLING_BF16 = 1 } castling_dtype_t;
+
+typedef enum {
+    CASTLING_NORM_ROWSUM = 0, /* divide by sum_j A_tj: the denominator of Eq. 3 (default) */
+    CASTLING_NORM_NONE = 1    /* literal Eq. 9: Sim(Q,K) V with no denominator */
+} castling_norm_t;
+
+enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_ALL = 3 };
+
+typedef struct {
+    int32_t B, heads, N, d;   /* d in {32, 64} */
+    int32_t grid_h, grid_w;   /* N must equal grid_h * grid_w */
+    int32_t dw_kernel;        /* odd, 1..9 */
+    int32_t io_dtype;         /* castling_dtype_t */
+    int32_t norm;             /* castling_norm_t */
+    uint32_t branches;        /* bitmask of CASTLING_BRANCH_*; 0 is read as CASTLING_BRANCH_ALL */
+    float eps;                /* floor of the L2 norm; 0 is read as 1e-12 */
+} castling_attn_desc_t;
+
+/* Host-only check of a descriptor (no GPU needed).  Sec. 3.2.1 fixes the shapes:
+ * per head Q, K, V in R^{N x d}, DWConv over the token grid. */
+int castling_attn_validate(const castling_attn_desc_t* desc);
+
+/* Validates desc, allocates the workspace on the current device, returns a handle. */
+int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_handle);
+
+/* Whole layer (Eq. 9 with the readings above): reduce followed by apply.
+ * q, k, v, dw_weight, out must be 16-byte aligned; out must not overlap q, k or v. */
+int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
+                          const void* dw_weight, const void* dw_bias, void* out, void* stream);
+
+/* First half: normalise K per token and reduce over tokens to the per-unit state
+ * K_hat^T V, sum_j k_hat_j, sum_j v_j (Sec. 3.1 reassociation; sums of Eq. 3).
+ * The state stays in the handle's workspace. */
+int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream);
+
+/* Second half: normalise Q per token, apply the state held in the handle
+ * (Eq. 3 with the linear terms of Eq. 8), add DWConv(V) (Eq. 9), store out. */
+int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
+                        const void* dw_bias, void* out, void* stream);
+
+/* NULL is a no-op returning CASTLING_OK. */
+int castling_attn_destroy(castling_attn_t h);
+
+/* Bytes of device workspace the handle holds. */
+size_t castling_attn_workspace_bytes(castling_attn_t h);
+
+/* Test/debug: copies the state of the last reduce to HOST memory as fp32
+ * [B*heads][d+1][d+1] = [K_hat | 1]^T [V | 1] (row i < d: K_hat^T V row i then
+ * ksum_i; row d: vsum then N).  Synchronises `stream`.  `bytes` must be exactly
+ * B*heads*(d+1)*(d+1)*4. */
+int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream);
+
+/* Number of token splits per unit the reduce uses for this handle (>= 1). */
+int castling_attn_num_splits(castling_attn_t h);
+
+/* Static string for a status code. */
+const char* castling_attn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASTLING_ATTN_H */

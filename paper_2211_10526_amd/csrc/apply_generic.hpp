@@ -1,0 +1,208 @@
+// Pass 2 (any dtype, fp32 vector ALU): normalise Q per token, apply the state
+// (Eq. 3 with the linear terms of Eq. 8), add the depthwise convolution of V
+// over the token grid (DWConv term of Eq. 9), store.
+#pragma once
+
+#include "common.hpp"
+
+namespace castling {
+
+struct ApplyParams {
+    int N, grid_h, grid_w;
+    int tiles_x;     // tiles per grid row
+    int norm_none;   // 1: no denominator (literal Eq. 9)
+    int do_linear;   // branch mask
+    int do_dwconv;
+    float eps;
+};
+
+constexpr int kApplyTH = 4;   // tile rows
+constexpr int kApplyTW = 16;  // tile columns
+constexpr int kApplyTokens = kApplyTH * kApplyTW;
+constexpr int kQtStride = kApplyTokens + 4;  // floats; keeps float4 rows aligned
+
+// Dynamic LDS the kernel needs, in bytes.
+template <typename T, int D, int KS>
+constexpr size_t apply_generic_lds_bytes()
+{
+    using L = StateLayout<D>;
+    const size_t phase_a = sizeof(float) * (L::SIZE + D * kQtStride);
+    const size_t halo = sizeof(T) * (kApplyTH + KS - 1) * (kApplyTW + KS - 1) * D;
+    const size_t phase_b = ((halo + 15) / 16) * 16 + sizeof(float) * KS * KS * D;
+    return phase_a > phase_b ? phase_a : phase_b;
+}
+
+// grid = (tiles_x * tiles_y, units), block = 256.  A block owns a 4 x 16 tile of
+// the token grid of one unit; thread (tt, tj) = (tid / 16, tid % 16) owns tokens
+// (row tt/4, columns 4*(tt%4)..+3) and channels tj*D/16..+D/16-1.
+template <typename T, int D, int KS>
+__global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict__ q,
+                                                             const T* __restrict__ v,
+                                                             const T* __restrict__ w,
+                                                             const T* __restrict__ bias,
+                                                             const float* __restrict__ state,
+                                                             T* __restrict__ out, int heads,
+                                                             ApplyParams p)
+{
+    constexpr int VEC = IO<T>::VEC;
+    constexpr int LPR = D / VEC;
+    constexpr int RJ = D / 16;  // channels per thread
+    constexpr int RAD = KS / 2;
+    constexpr int HH = kApplyTH + KS - 1;  // halo tile rows
+    constexpr int HW = kApplyTW + KS - 1;  // halo tile columns
+    using L = StateLayout<D>;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+
+    const int tid = threadIdx.x;
+    const int unit = blockIdx.y;
+    const int head = unit % heads;
+    const int ty0 = (blockIdx.x / p.tiles_x) * kApplyTH;
+    const int tx0 = (blockIdx.x % p.tiles_x) * kApplyTW;
+    const int tt = tid / 16, tj = tid % 16;
+    const int my_row = tt / 4, my_col0 = (tt % 4) * 4;
+    const size_t unit_off = static_cast<size_t>(unit) * p.N * D;
+
+    float res[4][RJ];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int j = 0; j < RJ; ++j) res[t][j] = 0.f;
+
+    // ---------------------------------------------------------------- linear branch
+    if (p.do_linear) {
+        float* st = reinterpret_cast<float*>(lds_raw);  // state, pre-scaled
+        float* qt = st + L::SIZE;                       // q_hat transposed: [D][kQtStride]
+        const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
+        for (int i = tid; i < L::SIZE; i += 256)
+            st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
+
+        constexpr int ROWS = 256 / LPR;
+        const int lcol = (tid % LPR) * VEC;
+#pragma unroll
+        for (int pass = 0; pass < kApplyTokens / ROWS; ++pass) {
+            const int tl = pass * ROWS + tid / LPR;
+            const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
+            float qx[VEC];
+            if (y < p.grid_h && x < p.grid_w) {
+                IO<T>::load16(q + unit_off + (static_cast<size_t>(y) * p.grid_w + x) * D + lcol, qx);
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) qx[e] = 0.f;
+            }
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) ss += qx[e] * qx[e];
+            ss = group_sum<LPR>(ss);
+            const float inv = 1.0f / fmaxf(sqrtf(ss), p.eps);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) qt[(lcol + e) * kQtStride + tl] = qx[e] * inv;
+        }
+        __syncthreads();
+
+        float den[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+        for (int i = 0; i < D; ++i) {
+            const float4 a4 = *reinterpret_cast<const float4*>(qt + i * kQtStride + tt * 4);
+            const float a[4] = {a4.x, a4.y, a4.z, a4.w};
+            const float ksi = st[L::KSUM + i];
+            float b[RJ];
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) b[j] = st[L::S + i * D + tj * RJ + j];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                den[t] = fmaf(a[t], ksi, den[t]);
+#pragma unroll
+                for (int j = 0; j < RJ; ++j) res[t][j] = fmaf(a[t], b[j], res[t][j]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float rden = p.norm_none ? 1.0f : 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) res[t][j] = (st[L::VSUM + tj * RJ + j] + res[t][j]) * rden;
+        }
+        __syncthreads();  // LDS is reused below
+    }
+
+    // ---------------------------------------------------------------- DWConv branch
+    if (p.do_dwconv) {
+        T* vh = reinterpret_cast<T*>(lds_raw);  // [HH][HW][D], zero outside the grid
+        constexpr size_t halo_bytes = ((sizeof(T) * HH * HW * D + 15) / 16) * 16;
+        float* wt = reinterpret_cast<float*>(lds_raw + halo_bytes);  // [KS*KS][D]
+
+        for (int idx = tid; idx < HH * HW * LPR; idx += 256) {
+            const int tok = idx / LPR, part = idx % LPR;
+            const int y = ty0 - RAD + tok / HW, x = tx0 - RAD + tok % HW;
+            uint4 val = make_uint4(0u, 0u, 0u, 0u);
+            if (y >= 0 && y < p.grid_h && x >= 0 && x < p.grid_w)
+                val = *reinterpret_cast<const uint4*>(
+                    v + unit_off + (static_cast<size_t>(y) * p.grid_w + x) * D + part * VEC);
+            *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tok) * D + part * VEC) = val;
+        }
+        const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
+        for (int idx = tid; idx < D * KS * KS; idx += 256) {
+            const int c = idx / (KS * KS), tap = idx % (KS * KS);
+            wt[tap * D + c] = IO<T>::to_f32(wh[idx]);
+        }
+        __syncthreads();
+
+        float dw[4][RJ];
+#pragma unroll
+        for (int j = 0; j < RJ; ++j) {
+            const float b0 = bias ? IO<T>::to_f32(bias[head * D + tj * RJ + j]) : 0.f;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) dw[t][j] = b0;
+        }
+#pragma unroll 1
+        for (int dy = 0; dy < KS; ++dy) {
+            float wr[KS][RJ];
+#pragma unroll
+            for (int dx = 0; dx < KS; ++dx)
+#pragma unroll
+                for (int j = 0; j < RJ; ++j) wr[dx][j] = wt[(dy * KS + dx) * D + tj * RJ + j];
+            const T* row = vh + (static_cast<size_t>(my_row + dy) * HW + my_col0) * D + tj * RJ;
+#pragma unroll
+            for (int xx = 0; xx < KS + 3; ++xx) {
+                float vin[RJ];
+#pragma unroll
+                for (int j = 0; j < RJ; ++j) vin[j] = IO<T>::to_f32(row[xx * D + j]);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int dx = xx - t;
+                    if (dx >= 0 && dx < KS) {
+#pragma unroll
+                        for (int j = 0; j < RJ; ++j) dw[t][j] = fmaf(wr[dx][j], vin[j], dw[t][j]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) res[t][j] += dw[t][j];
+    }
+
+    // ---------------------------------------------------------------- store
+    const int y = ty0 + my_row;
+    if (y < p.grid_h) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int x = tx0 + my_col0 + t;
+            if (x < p.grid_w) {
+                T* o = out + unit_off + (static_cast<size_t>(y) * p.grid_w + x) * D + tj * RJ;
+                T tmp[RJ];
+#pragma unroll
+                for (int j = 0; j < RJ; ++j) tmp[j] = IO<T>::from_f32(res[t][j]);
+                if constexpr (sizeof(T) * RJ == 16)
+                    *reinterpret_cast<uint4*>(o) = *reinterpret_cast<const uint4*>(tmp);
+                else if constexpr (sizeof(T) * RJ == 8)
+                    *reinterpret_cast<uint2*>(o) = *reinterpret_cast<const uint2*>(tmp);
+                else
+                    *reinterpret_cast<uint32_t*>(o) = *reinterpret_cast<const uint32_t*>(tmp);
+            }
+        }
+    }
+}
+
+}  // namespace castling

@@ -1,0 +1,333 @@
+// C ABI of the linear-angular attention layer: argument checks, workspace,
+// kernel dispatch.  See include/castling_attn.h for the contract.
+#include "../../include/castling_attn.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "apply_generic.hpp"
+#include "common.hpp"
+#include "reduce_generic.hpp"
+
+using namespace castling;
+
+namespace {
+
+constexpr int kTargetReduceBlocks = 512;  // about two blocks per compute unit
+constexpr int kMinChunkTokens = 128;
+
+thread_local char g_hip_error[256] = "HIP runtime error";
+
+int hip_fail(hipError_t e)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "HIP runtime error: %s", hipGetErrorString(e));
+    return CASTLING_ERR_HIP;
+}
+
+#define HIP_TRY(expr)                                \
+    do {                                             \
+        hipError_t e_ = (expr);                      \
+        if (e_ != hipSuccess) return hip_fail(e_);   \
+    } while (0)
+
+typedef void (*reduce_fn_t)(const void*, const void*, float*, int, int, int, float, int, int,
+                            hipStream_t);
+typedef void (*combine_fn_t)(const float*, float*, int, int, hipStream_t);
+typedef hipError_t (*apply_fn_t)(const void*, const void*, const void*, const void*, const float*,
+                                 void*, int, int, ApplyParams, hipStream_t);
+typedef hipError_t (*apply_prepare_fn_t)(size_t* lds_bytes);
+
+template <typename T, int D>
+void launch_reduce(const void* k, const void* v, float* partial, int N, int n_split, int chunk,
+                   float eps, int units, int, hipStream_t s)
+{
+    hipLaunchKernelGGL((reduce_generic_kernel<T, D>), dim3(n_split, units), dim3(256), 0, s,
+                       static_cast<const T*>(k), static_cast<const T*>(v), partial, N, n_split,
+                       chunk, eps);
+}
+
+template <int D>
+void launch_combine(const float* partial, float* state, int n_split, int units, hipStream_t s)
+{
+    using L = StateLayout<D>;
+    hipLaunchKernelGGL((combine_kernel<D>), dim3((L::SIZE + 255) / 256, units), dim3(256), 0, s,
+                       partial, state, n_split);
+}
+
+template <typename T, int D, int KS>
+hipError_t prepare_apply(size_t* lds_bytes)
+{
+    *lds_bytes = apply_generic_lds_bytes<T, D, KS>();
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_generic_kernel<T, D, KS>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                               static_cast<int>(*lds_bytes));
+}
+
+template <typename T, int D, int KS>
+hipError_t launch_apply(const void* q, const void* v, const void* w, const void* bias,
+                        const float* state, void* out, int heads, int units, ApplyParams p,
+                        hipStream_t s)
+{
+    const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
+    constexpr size_t lds = apply_generic_lds_bytes<T, D, KS>();
+    hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, units),
+                       dim3(256), lds, s,
+                       static_cast<const T*>(q), static_cast<const T*>(v),
+                       static_cast<const T*>(w), static_cast<const T*>(bias), state,
+                       static_cast<T*>(out), heads, p);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+bool pick_apply(int ks, apply_fn_t* fn, apply_prepare_fn_t* prep)
+{
+    switch (ks) {
+        case 1: *fn = launch_apply<T, D, 1>; *prep = prepare_apply<T, D, 1>; return true;
+        case 3: *fn = launch_apply<T, D, 3>; *prep = prepare_apply<T, D, 3>; return true;
+        case 5: *fn = launch_apply<T, D, 5>; *prep = prepare_apply<T, D, 5>; return true;
+        case 7: *fn = launch_apply<T, D, 7>; *prep = prepare_apply<T, D, 7>; return true;
+        case 9: *fn = launch_apply<T, D, 9>; *prep = prepare_apply<T, D, 9>; return true;
+        default: return false;
+    }
+}
+
+size_t dtype_size(int dt) { return dt == CASTLING_F32 ? 4 : 2; }
+
+}  // namespace
+
+struct castling_attn {
+    castling_attn_desc_t desc;
+    int device;
+    int units;
+    int n_split;
+    int chunk;
+    int state_size;       // floats per unit
+    float* partial;       // [units][n_split][state_size]
+    float* state;         // [units][state_size]
+    size_t workspace_bytes;
+    reduce_fn_t reduce;
+    combine_fn_t combine;
+    apply_fn_t apply;
+    size_t apply_lds;
+};
+
+extern "C" {
+
+const char* castling_attn_strerror(int status)
+{
+    switch (status) {
+        case CASTLING_OK: return "ok";
+        case CASTLING_ERR_INVALID_ARG: return "invalid argument";
+        case CASTLING_ERR_UNSUPPORTED: return "unsupported shape or dtype";
+        case CASTLING_ERR_HIP: return g_hip_error;
+        case CASTLING_ERR_ALIAS: return "output overlaps an input";
+        default: return "unknown status";
+    }
+}
+
+int castling_attn_validate(const castling_attn_desc_t* d)
+{
+    if (!d) return CASTLING_ERR_INVALID_ARG;
+    if (d->B <= 0 || d->heads <= 0 || d->N <= 0 || d->d <= 0 || d->grid_h <= 0 || d->grid_w <= 0 ||
+        d->dw_kernel <= 0)
+        return CASTLING_ERR_INVALID_ARG;
+    if (static_cast<int64_t>(d->grid_h) * d->grid_w != d->N) return CASTLING_ERR_INVALID_ARG;
+    if (d->dw_kernel % 2 == 0) return CASTLING_ERR_INVALID_ARG;
+    if (d->norm != CASTLING_NORM_ROWSUM && d->norm != CASTLING_NORM_NONE)
+        return CASTLING_ERR_INVALID_ARG;
+    if (d->branches & ~static_cast<uint32_t>(CASTLING_BRANCH_ALL)) return CASTLING_ERR_INVALID_ARG;
+    if (!(d->eps >= 0.0f)) return CASTLING_ERR_INVALID_ARG;
+    if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16) return CASTLING_ERR_UNSUPPORTED;
+    if (d->d != 32 && d->d != 64) return CASTLING_ERR_UNSUPPORTED;
+    if (d->dw_kernel > 9) return CASTLING_ERR_UNSUPPORTED;
+    // grid.y carries the unit index; keep element offsets inside int64 comfortably
+    if (static_cast<int64_t>(d->B) * d->heads > 65535) return CASTLING_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(d->B) * d->heads * d->N * d->d > (int64_t(1) << 40))
+        return CASTLING_ERR_UNSUPPORTED;
+    return CASTLING_OK;
+}
+
+int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_handle)
+{
+    if (!out_handle) return CASTLING_ERR_INVALID_ARG;
+    *out_handle = nullptr;
+    int st = castling_attn_validate(desc);
+    if (st != CASTLING_OK) return st;
+
+    castling_attn* h = new (std::nothrow) castling_attn();
+    if (!h) return CASTLING_ERR_INVALID_ARG;
+    h->desc = *desc;
+    if (h->desc.branches == 0) h->desc.branches = CASTLING_BRANCH_ALL;
+    if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
+    h->units = desc->B * desc->heads;
+    h->state_size = desc->d * desc->d + 2 * desc->d;
+
+    const bool f32 = desc->io_dtype == CASTLING_F32;
+    apply_prepare_fn_t prep = nullptr;
+    bool ok;
+    if (desc->d == 32) {
+        h->reduce = f32 ? launch_reduce<float, 32> : launch_reduce<bf16_t, 32>;
+        h->combine = launch_combine<32>;
+        ok = f32 ? pick_apply<float, 32>(desc->dw_kernel, &h->apply, &prep)
+                 : pick_apply<bf16_t, 32>(desc->dw_kernel, &h->apply, &prep);
+    } else {
+        h->reduce = f32 ? launch_reduce<float, 64> : launch_reduce<bf16_t, 64>;
+        h->combine = launch_combine<64>;
+        ok = f32 ? pick_apply<float, 64>(desc->dw_kernel, &h->apply, &prep)
+                 : pick_apply<bf16_t, 64>(desc->dw_kernel, &h->apply, &prep);
+    }
+    if (!ok) {
+        delete h;
+        return CASTLING_ERR_UNSUPPORTED;
+    }
+
+    // token split: enough blocks to fill the chip, chunks a multiple of 64 tokens
+    int n_split = (kTargetReduceBlocks + h->units - 1) / h->units;
+    const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
+    if (n_split > max_split) n_split = max_split;
+    if (n_split < 1) n_split = 1;
+    int chunk = (desc->N + n_split - 1) / n_split;
+    chunk = ((chunk + 63) / 64) * 64;
+    h->chunk = chunk;
+    h->n_split = (desc->N + chunk - 1) / chunk;
+
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess) e = prep(&h->apply_lds);
+    if (e == hipSuccess) {
+        int max_lds = 0;
+        e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
+        if (e == hipSuccess && h->apply_lds > static_cast<size_t>(max_lds)) {
+            delete h;
+            return CASTLING_ERR_UNSUPPORTED;
+        }
+    }
+    const size_t partial_bytes =
+        sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size;
+    const size_t state_bytes = sizeof(float) * static_cast<size_t>(h->units) * h->state_size;
+    h->workspace_bytes = partial_bytes + state_bytes;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->partial), h->workspace_bytes);
+    if (e != hipSuccess) {
+        delete h;
+        return hip_fail(e);
+    }
+    h->state = h->partial + static_cast<size_t>(h->units) * h->n_split * h->state_size;
+    *out_handle = h;
+    return CASTLING_OK;
+}
+
+int castling_attn_destroy(castling_attn_t h)
+{
+    if (!h) return CASTLING_OK;
+    hipError_t e = h->partial ? hipFree(h->partial) : hipSuccess;
+    delete h;
+    return e == hipSuccess ? CASTLING_OK : hip_fail(e);
+}
+
+size_t castling_attn_workspace_bytes(castling_attn_t h) { return h ? h->workspace_bytes : 0; }
+
+int castling_attn_num_splits(castling_attn_t h) { return h ? h->n_split : 0; }
+
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+static bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
+{
+    if (!h || !k || !v) return CASTLING_ERR_INVALID_ARG;
+    if (misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const castling_attn_desc_t& d = h->desc;
+    h->reduce(k, v, h->partial, d.N, h->n_split, h->chunk, d.eps, h->units, 0, s);
+    HIP_TRY(hipGetLastError());
+    h->combine(h->partial, h->state, h->n_split, h->units, s);
+    HIP_TRY(hipGetLastError());
+    return CASTLING_OK;
+}
+
+static int check_apply_args(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
+                            void* out)
+{
+    if (!h || !out) return CASTLING_ERR_INVALID_ARG;
+    const castling_attn_desc_t& d = h->desc;
+    const bool lin = d.branches & CASTLING_BRANCH_LINEAR, dw = d.branches & CASTLING_BRANCH_DWCONV;
+    if ((lin && !q) || (dw && (!v || !dw_weight))) return CASTLING_ERR_INVALID_ARG;
+    if (misaligned(out) || (lin && misaligned(q)) || (dw && (misaligned(v) || misaligned(dw_weight))))
+        return CASTLING_ERR_INVALID_ARG;
+    const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
+    if ((lin && overlaps(out, bytes, q, bytes)) || (dw && overlaps(out, bytes, v, bytes)))
+        return CASTLING_ERR_ALIAS;
+    return CASTLING_OK;
+}
+
+int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
+                        const void* dw_bias, void* out, void* stream)
+{
+    int st = check_apply_args(h, q, v, dw_weight, out);
+    if (st != CASTLING_OK) return st;
+    const castling_attn_desc_t& d = h->desc;
+    ApplyParams p;
+    p.N = d.N;
+    p.grid_h = d.grid_h;
+    p.grid_w = d.grid_w;
+    p.tiles_x = (d.grid_w + kApplyTW - 1) / kApplyTW;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    p.eps = d.eps;
+    HIP_TRY(h->apply(q, v, dw_weight, dw_bias, h->state, out, d.heads, h->units, p,
+                     static_cast<hipStream_t>(stream)));
+    return CASTLING_OK;
+}
+
+int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
+                          const void* dw_weight, const void* dw_bias, void* out, void* stream)
+{
+    // every argument is checked before anything is enqueued
+    int st = check_apply_args(h, q, v, dw_weight, out);
+    if (st != CASTLING_OK) return st;
+    const castling_attn_desc_t& d = h->desc;
+    if (d.branches & CASTLING_BRANCH_LINEAR) {
+        if (!k || !v || misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
+        const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
+        if (overlaps(out, bytes, k, bytes) || overlaps(out, bytes, v, bytes))
+            return CASTLING_ERR_ALIAS;
+        st = castling_attn_reduce(h, k, v, stream);
+        if (st != CASTLING_OK) return st;
+    }
+    return castling_attn_apply(h, q, v, dw_weight, dw_bias, out, stream);
+}
+
+int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream)
+{
+    if (!h || !host_f32) return CASTLING_ERR_INVALID_ARG;
+    const int D = h->desc.d, D1 = D + 1;
+    if (bytes != sizeof(float) * static_cast<size_t>(h->units) * D1 * D1)
+        return CASTLING_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<float> raw(static_cast<size_t>(h->units) * h->state_size);
+    HIP_TRY(hipStreamSynchronize(s));
+    HIP_TRY(hipMemcpy(raw.data(), h->state, raw.size() * sizeof(float), hipMemcpyDeviceToHost));
+    float* dst = static_cast<float*>(host_f32);
+    for (int u = 0; u < h->units; ++u) {
+        const float* r = raw.data() + static_cast<size_t>(u) * h->state_size;
+        float* m = dst + static_cast<size_t>(u) * D1 * D1;
+        for (int i = 0; i < D; ++i) {
+            for (int j = 0; j < D; ++j) m[i * D1 + j] = r[i * D + j];
+            m[i * D1 + D] = r[D * D + i];
+        }
+        for (int j = 0; j < D; ++j) m[D * D1 + j] = r[D * D + D + j];
+        m[D * D1 + D] = static_cast<float>(h->desc.N);
+    }
+    return CASTLING_OK;
+}
+
+}  // extern "C"

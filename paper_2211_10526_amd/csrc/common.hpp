@@ -1,0 +1,79 @@
+// Shared device helpers of the linear-angular attention kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace castling {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+constexpr float kInvPi = 0.31830988618379067154f;
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t b)
+{
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return static_cast<bf16_t>(u >> 16);
+}
+
+// 16-byte global access of the I/O type, widened to fp32 in registers.
+template <typename T>
+struct IO;
+
+template <>
+struct IO<float> {
+    static constexpr int VEC = 4;
+    __device__ static __forceinline__ void load16(const float* p, float (&x)[4])
+    {
+        const float4 r = *reinterpret_cast<const float4*>(p);
+        x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
+    }
+    __device__ static __forceinline__ float to_f32(float a) { return a; }
+    __device__ static __forceinline__ float from_f32(float a) { return a; }
+};
+
+template <>
+struct IO<bf16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ void load16(const bf16_t* p, float (&x)[8])
+    {
+        const uint4 r = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __uint_as_float(w[i] << 16);
+            x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ static __forceinline__ float to_f32(bf16_t a) { return bf16_to_f32(a); }
+    __device__ static __forceinline__ bf16_t from_f32(float a) { return f32_to_bf16(a); }
+};
+
+// Sum over groups of LANES consecutive lanes (LANES a power of two <= 64).
+template <int LANES>
+__device__ __forceinline__ float group_sum(float x)
+{
+#pragma unroll
+    for (int m = LANES / 2; m >= 1; m >>= 1) x += __shfl_xor(x, m, 64);
+    return x;
+}
+
+// Floats per unit of the internal state: S = K_hat^T V (D x D, row-major), then
+// the K_hat column sum (D), then the V column sum (D).  N is known to the host.
+template <int D>
+struct StateLayout {
+    static constexpr int S = 0;
+    static constexpr int KSUM = D * D;
+    static constexpr int VSUM = D * D + D;
+    static constexpr int SIZE = D * D + 2 * D;
+};
+
+}  // namespace castling

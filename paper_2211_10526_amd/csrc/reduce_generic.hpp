@@ -1,0 +1,121 @@
+// Pass 1 (any dtype, fp32 vector ALU): normalise K per token and reduce over a
+// chunk of tokens to a partial state (K_hat^T V, K_hat column sum, V column sum),
+// then a fixed-order combine of the partials.  Sec. 3.1 (reassociation of
+// kernel-based linear attention) and the sums of Eq. 3 of the paper.
+#pragma once
+
+#include "common.hpp"
+
+namespace castling {
+
+// grid = (n_split, units), block = 256.
+// Block (s, u) reduces tokens [s*chunk, min(N, (s+1)*chunk)) of unit u and writes
+// partial[u][s][StateLayout<D>::SIZE].
+template <typename T, int D>
+__global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict__ k,
+                                                              const T* __restrict__ v,
+                                                              float* __restrict__ partial, int N,
+                                                              int n_split, int chunk, float eps)
+{
+    constexpr int VEC = IO<T>::VEC;  // elements per 16-byte load
+    constexpr int LPR = D / VEC;     // lanes that share one token row
+    constexpr int TILE = 256 / LPR;  // tokens staged per iteration
+    constexpr int R = D / 16;        // each thread owns an R x R block of S
+    using L = StateLayout<D>;
+
+    __shared__ __attribute__((aligned(16))) float kh[TILE][D];
+    __shared__ __attribute__((aligned(16))) float vv[TILE][D];
+
+    const int tid = threadIdx.x;
+    const int unit = blockIdx.y;
+    const int split = blockIdx.x;
+    const int n_begin = split * chunk;
+    const int n_end = min(N, n_begin + chunk);
+    const int ti = tid / 16, tj = tid % 16;
+    const int lrow = tid / LPR, lcol = (tid % LPR) * VEC;
+
+    const T* kb = k + static_cast<size_t>(unit) * N * D;
+    const T* vb = v + static_cast<size_t>(unit) * N * D;
+
+    float acc[R][R];
+    float ks[R], vs[R];
+#pragma unroll
+    for (int a = 0; a < R; ++a) {
+        ks[a] = 0.f;
+        vs[a] = 0.f;
+#pragma unroll
+        for (int b = 0; b < R; ++b) acc[a][b] = 0.f;
+    }
+
+    for (int n0 = n_begin; n0 < n_end; n0 += TILE) {
+        const int n = n0 + lrow;
+        float kx[VEC], vx[VEC];
+        if (n < n_end) {
+            IO<T>::load16(kb + static_cast<size_t>(n) * D + lcol, kx);
+            IO<T>::load16(vb + static_cast<size_t>(n) * D + lcol, vx);
+        } else {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) kx[e] = vx[e] = 0.f;
+        }
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) ss += kx[e] * kx[e];
+        ss = group_sum<LPR>(ss);
+        const float inv = 1.0f / fmaxf(sqrtf(ss), eps);
+
+        __syncthreads();  // the previous tile has been consumed
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            kh[lrow][lcol + e] = kx[e] * inv;
+            vv[lrow][lcol + e] = vx[e];
+        }
+        __syncthreads();
+
+#pragma unroll 4
+        for (int t = 0; t < TILE; ++t) {
+            float a[R], b[R];
+#pragma unroll
+            for (int e = 0; e < R; ++e) {
+                a[e] = kh[t][ti * R + e];
+                b[e] = vv[t][tj * R + e];
+            }
+#pragma unroll
+            for (int x = 0; x < R; ++x) {
+#pragma unroll
+                for (int y = 0; y < R; ++y) acc[x][y] = fmaf(a[x], b[y], acc[x][y]);
+                ks[x] += a[x];
+                vs[x] += b[x];
+            }
+        }
+    }
+
+    float* out = partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE;
+#pragma unroll
+    for (int x = 0; x < R; ++x)
+#pragma unroll
+        for (int y = 0; y < R; ++y) out[L::S + (ti * R + x) * D + tj * R + y] = acc[x][y];
+    if (tj == 0)
+#pragma unroll
+        for (int x = 0; x < R; ++x) out[L::KSUM + ti * R + x] = ks[x];
+    if (ti == 0)
+#pragma unroll
+        for (int x = 0; x < R; ++x) out[L::VSUM + tj * R + x] = vs[x];
+}
+
+// grid = (ceil(SIZE/256), units), block = 256.  state[u][i] = sum over splits in
+// index order: the order never depends on which block finished first.
+template <int D>
+__global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ partial,
+                                                       float* __restrict__ state, int n_split)
+{
+    using L = StateLayout<D>;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int unit = blockIdx.y;
+    if (i >= L::SIZE) return;
+    const float* p = partial + static_cast<size_t>(unit) * n_split * L::SIZE + i;
+    float s = 0.f;
+    for (int sp = 0; sp < n_split; ++sp) s += p[static_cast<size_t>(sp) * L::SIZE];
+    state[static_cast<size_t>(unit) * L::SIZE + i] = s;
+}
+
+}  // namespace castling

@@ -1,0 +1,37 @@
+"""Helpers shared by the GPU parity tests (no method arithmetic here)."""
+import numpy as np
+import torch
+
+from paper_2211_10526_amd import binding as b
+from paper_2211_10526_amd import inputs
+
+TOL = {"f32": 1e-4, "bf16": 1e-2}
+
+
+def rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    """max_i |g_i - o_i| / max(|o_i|, rms(o)): the layer's parity metric."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(want * want)))
+    if rms == 0.0:
+        return float(np.max(np.abs(got - want)))
+    return float(np.max(np.abs(got - want) / np.maximum(np.abs(want), rms)))
+
+
+def gpu_forward(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0, want_state=False):
+    """Runs the HIP layer through the C ABI; returns float64 numpy [B,heads,N,d]."""
+    dev = torch.device("cuda:0")
+    t = {n: (None if x[n] is None else x[n].to(dev)) for n in ("q", "k", "v", "w", "bias")}
+    out = torch.empty_like(t["q"])
+    out.fill_(float("nan"))
+    attn = b.CastlingAttn.for_workload(wl, norm=norm, branches=branches, eps=eps)
+    attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], out)
+    torch.cuda.synchronize()
+    res = inputs.to_f64(out)
+    st = attn.get_state() if want_state else None
+    attn.destroy()
+    return (res, st) if want_state else res
+
+
+def oracle_inputs(x):
+    return tuple(inputs.to_f64(x[n]) for n in ("q", "k", "v", "w", "bias"))

@@ -1,0 +1,203 @@
+"""GPU parity: the HIP layer (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Tolerances: max relative error 1e-4 (fp32 I/O) and 1e-2
+(bf16 I/O, fp32 accumulation), error = max |g-o| / max(|o|, rms(o)), checked for
+the whole layer and for each branch alone."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2211_10526_amd import binding as b
+from paper_2211_10526_amd import inputs
+from paper_2211_10526_amd.inputs import Workload
+from parity_util import TOL, gpu_forward, oracle_inputs, rel_err
+
+pytestmark = pytest.mark.gpu
+
+# small shapes the oracle's explicit N x N form finishes quickly; they span several
+# 4x16 tiles, ragged right/bottom edges, grids narrower than the filter, both
+# dtypes, both head widths and every filter size
+SMALL = [
+    Workload("s_f32_d32_14x14_k3", "f32", 1, 4, 32, 14, 14, 3),
+    Workload("s_f32_d64_10x17_k9", "f32", 2, 2, 64, 10, 17, 9),
+    Workload("s_f32_d32_5x33_k5", "f32", 1, 3, 32, 5, 33, 5),
+    Workload("s_bf16_d64_13x19_k5", "bf16", 2, 3, 64, 13, 19, 5),
+    Workload("s_bf16_d32_7x9_k7", "bf16", 3, 2, 32, 7, 9, 7),
+    Workload("s_bf16_d64_3x3_k9", "bf16", 1, 2, 64, 3, 3, 9),
+    Workload("s_bf16_d64_1x40_k3", "bf16", 1, 1, 64, 1, 40, 3),
+    Workload("s_f32_d32_37x1_k3", "f32", 1, 2, 32, 37, 1, 3),
+    Workload("s_bf16_d64_1x1_k1", "bf16", 2, 2, 64, 1, 1, 1),
+    Workload("s_bf16_d64_24x24_k3_outl", "bf16", 2, 2, 64, 24, 24, 3, 0.05, 8.0),
+]
+
+
+@pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
+def test_small_against_definition(oracle, wl, norm):
+    x = inputs.make_inputs(wl, seed=11, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    for branches in (b.BRANCH_ALL, b.BRANCH_LINEAR, b.BRANCH_DWCONV):
+        print(f"case {wl.name} norm={norm} branches={branches}", flush=True)
+        want = oracle.forward_explicit(q, k, v, w, bias, wl.grid_h, wl.grid_w, norm=norm,
+                                       branches=branches)
+        got = gpu_forward(wl, x, norm=norm, branches=branches)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) <= TOL[wl.dtype], (wl.name, norm, branches)
+
+
+@pytest.mark.parametrize("wl", SMALL[:6], ids=lambda w: w.name)
+def test_state_against_oracle(oracle, wl):
+    x = inputs.make_inputs(wl, seed=12)
+    _, k, v, _, _ = oracle_inputs(x)
+    print(f"case state {wl.name}", flush=True)
+    _, st = gpu_forward(wl, x, want_state=True)
+    want = oracle.state(k, v)
+    d = wl.d
+    # compare each part of the state against its own rms
+    for name, sl in (("KtV", (slice(0, d), slice(0, d))), ("ksum", (slice(0, d), d)),
+                     ("vsum", (d, slice(0, d))), ("count", (d, d))):
+        g, o = st[(..., *sl)], want[(..., *sl)]
+        assert rel_err(g, o) <= TOL[wl.dtype], (wl.name, name)
+
+
+@pytest.mark.parametrize("idx", range(5))
+def test_benchmark_workload_full_size(oracle, idx):
+    """The five benchmark workloads at full size: every element against the oracle's
+    reassociated form (itself pinned to the definition), sampled rows against the
+    definition, per branch, plus the exported state."""
+    wl = inputs.WORKLOADS[idx]
+    print(f"case full {wl.name}", flush=True)
+    x = inputs.make_inputs(wl)
+    q, k, v, w, bias = oracle_inputs(x)
+    tol = TOL[wl.dtype]
+    rs = np.random.default_rng(100 + idx)
+    units = rs.integers(0, wl.units, size=48)
+    tokens = rs.integers(0, wl.N, size=48)
+    # corners and edges of the grid are always among the samples
+    tokens[:4] = [0, wl.grid_w - 1, wl.N - wl.grid_w, wl.N - 1]
+    for branches in (b.BRANCH_ALL, b.BRANCH_LINEAR, b.BRANCH_DWCONV):
+        got = gpu_forward(wl, x, branches=branches)
+        want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w, branches=branches)
+        assert rel_err(got, want) <= tol, (wl.name, branches)
+        rows = oracle.forward_explicit_rows(q, k, v, w, bias, wl.grid_h, wl.grid_w, units, tokens,
+                                            branches=branches)
+        rms = float(np.sqrt(np.mean(want * want)))
+        g = got.reshape(wl.units, wl.N, wl.d)[units, tokens]
+        err = np.max(np.abs(g - rows) / np.maximum(np.abs(rows), rms))
+        assert err <= tol, (wl.name, branches, "sampled rows vs definition")
+        print(f"  branches={branches} rel_err={rel_err(got, want):.3e} sampled={err:.3e}", flush=True)
+    _, st = gpu_forward(wl, x, want_state=True)
+    want_st = oracle.state(k, v)
+    d = wl.d
+    assert rel_err(st[..., :d, :d], want_st[..., :d, :d]) <= tol
+    assert rel_err(st[..., :d, d], want_st[..., :d, d]) <= tol
+    assert rel_err(st[..., d, :d], want_st[..., d, :d]) <= tol
+
+
+def test_outlier_scaling_leaves_weights_unchanged(oracle):
+    """Scaling q and k rows by positive factors must not change the linear branch."""
+    wl = Workload("inv_bf16", "bf16", 1, 2, 64, 12, 20, 3)
+    x = inputs.make_inputs(wl, seed=5)
+    base = gpu_forward(wl, x, branches=b.BRANCH_LINEAR)
+    x2 = dict(x)
+    scale = torch.where(torch.rand(1, 1, wl.N, 1, generator=torch.Generator().manual_seed(1)) < 0.2,
+                        torch.tensor(8.0), torch.tensor(1.0))          # powers of two: exact in bf16
+    x2["q"] = (x["q"].float() * scale).to(torch.bfloat16)
+    x2["k"] = (x["k"].float() * scale).to(torch.bfloat16)
+    got = gpu_forward(wl, x2, branches=b.BRANCH_LINEAR)
+    assert rel_err(got, base) <= 1e-3
+
+
+def test_zero_rows_and_constant_v(oracle):
+    wl = Workload("edge_f32", "f32", 1, 2, 32, 6, 10, 3)
+    x = inputs.make_inputs(wl, seed=6)
+    x["q"][0, 0, 7] = 0.0          # zero query: uniform weights -> mean of V
+    x["k"][0, 1, 3] = 0.0          # zero key: weight exactly 1/2
+    q, k, v, w, bias = oracle_inputs(x)
+    got = gpu_forward(wl, x, branches=b.BRANCH_LINEAR)
+    want = oracle.forward_explicit(q, k, v, w, None, wl.grid_h, wl.grid_w, branches=1)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= 1e-4
+    np.testing.assert_allclose(got[0, 0, 7], v[0, 0].mean(axis=0), rtol=1e-4, atol=1e-6)
+    x["v"][...] = 2.5
+    got = gpu_forward(wl, x, branches=b.BRANCH_LINEAR)
+    np.testing.assert_allclose(got, 2.5, rtol=1e-5)
+
+
+@pytest.mark.parametrize("idx", [0, 2, 4])
+def test_bitwise_deterministic(idx):
+    wl = inputs.WORKLOADS[idx]
+    print(f"case determinism {wl.name}", flush=True)
+    x = inputs.make_inputs(wl)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    attn = b.CastlingAttn.for_workload(wl)
+    outs = []
+    for _ in range(3):
+        out = torch.empty_like(t["q"])
+        attn.forward(t["q"], t["k"], t["v"], t["w"], None, out)
+        torch.cuda.synchronize()
+        outs.append(out.view(torch.int16 if wl.dtype == "bf16" else torch.int32).cpu())
+    attn.destroy()
+    assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_reduce_then_apply_equals_forward():
+    wl = Workload("split_bf16", "bf16", 2, 2, 64, 9, 21, 5)
+    x = inputs.make_inputs(wl, seed=8)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    attn = b.CastlingAttn.for_workload(wl)
+    o1, o2 = torch.empty_like(t["q"]), torch.empty_like(t["q"])
+    attn.forward(t["q"], t["k"], t["v"], t["w"], None, o1)
+    attn.reduce(t["k"], t["v"])
+    attn.apply(t["q"], t["v"], t["w"], None, o2)
+    torch.cuda.synchronize()
+    assert attn.workspace_bytes() > 0 and attn.num_splits() >= 1
+    attn.destroy()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+def test_runs_on_a_side_stream(oracle):
+    wl = SMALL[3]
+    x = inputs.make_inputs(wl, seed=9)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    out = torch.empty_like(t["q"])
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    attn = b.CastlingAttn.for_workload(wl)
+    attn.forward(t["q"], t["k"], t["v"], t["w"], None, out, stream=s)
+    s.synchronize()
+    attn.destroy()
+    q, k, v, w, _ = oracle_inputs(x)
+    want = oracle.forward(q, k, v, w, None, wl.grid_h, wl.grid_w)
+    assert rel_err(inputs.to_f64(out), want) <= TOL[wl.dtype]
+
+
+def test_argument_errors_on_device():
+    wl = SMALL[0]
+    x = inputs.make_inputs(wl)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    out = torch.empty_like(t["q"])
+    attn = b.CastlingAttn.for_workload(wl)
+    with pytest.raises(b.CastlingError) as e:
+        attn.forward(t["q"], t["k"], t["v"], t["w"], None, t["v"])
+    assert e.value.status == b.ERR_ALIAS
+    with pytest.raises(b.CastlingError) as e:
+        attn.forward(t["q"], t["k"], t["v"], t["w"], None, t["q"])
+    assert e.value.status == b.ERR_ALIAS
+    with pytest.raises(b.CastlingError) as e:
+        attn.forward(None, t["k"], t["v"], t["w"], None, out)
+    assert e.value.status == b.ERR_INVALID_ARG
+    mis = t["q"].reshape(-1)[1:].clone()           # a fresh buffer, then a view 4 bytes in
+    mis_view = torch.empty(t["q"].numel() + 1, dtype=t["q"].dtype, device=dev)[1:]
+    with pytest.raises(b.CastlingError) as e:
+        attn.forward(mis_view, t["k"], t["v"], t["w"], None, out)
+    assert e.value.status == b.ERR_INVALID_ARG
+    del mis
+    # the handle still works after the refusals
+    attn.forward(t["q"], t["k"], t["v"], t["w"], None, out)
+    torch.cuda.synchronize()
+    attn.destroy()
+    assert torch.isfinite(out).all()
