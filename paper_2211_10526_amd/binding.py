@@ -52,6 +52,9 @@ def lib():
             raise RuntimeError(
                 f"{LIB_PATH} is not built; run `python -m paper_2211_10526_amd.build` "
                 "(needs hipcc). The layer has no other implementation.")
+        # torch ships its own HIP runtime; load it first so that this library binds to
+        # the same runtime instance that owns torch's device memory and streams
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.castling_attn_validate.argtypes = [C.POINTER(Desc)]
