@@ -13,6 +13,7 @@
 #include "apply_generic.hpp"
 #include "common.hpp"
 #include "reduce_generic.hpp"
+#include "reduce_mfma.hpp"
 
 using namespace castling;
 
@@ -49,6 +50,15 @@ void launch_reduce(const void* k, const void* v, float* partial, int N, int n_sp
     hipLaunchKernelGGL((reduce_generic_kernel<T, D>), dim3(n_split, units), dim3(256), 0, s,
                        static_cast<const T*>(k), static_cast<const T*>(v), partial, N, n_split,
                        chunk, eps);
+}
+
+template <int D>
+void launch_reduce_mfma(const void* k, const void* v, float* partial, int N, int n_split, int chunk,
+                        float eps, int units, int, hipStream_t s)
+{
+    hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(n_split, units), dim3(64 * kReduceWaves), 0, s,
+                       static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), partial, N,
+                       n_split, chunk, eps);
 }
 
 template <int D>
@@ -168,15 +178,20 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->state_size = desc->d * desc->d + 2 * desc->d;
 
     const bool f32 = desc->io_dtype == CASTLING_F32;
+    // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 on the vector-ALU kernels (A/B measurements)
+    const char* force = getenv("CASTLING_ATTN_FORCE_GENERIC");
+    const bool mfma = !f32 && !(force && force[0] == '1');
     apply_prepare_fn_t prep = nullptr;
     bool ok;
     if (desc->d == 32) {
-        h->reduce = f32 ? launch_reduce<float, 32> : launch_reduce<bf16_t, 32>;
+        h->reduce = f32 ? launch_reduce<float, 32>
+                        : (mfma ? launch_reduce_mfma<32> : launch_reduce<bf16_t, 32>);
         h->combine = launch_combine<32>;
         ok = f32 ? pick_apply<float, 32>(desc->dw_kernel, &h->apply, &prep)
                  : pick_apply<bf16_t, 32>(desc->dw_kernel, &h->apply, &prep);
     } else {
-        h->reduce = f32 ? launch_reduce<float, 64> : launch_reduce<bf16_t, 64>;
+        h->reduce = f32 ? launch_reduce<float, 64>
+                        : (mfma ? launch_reduce_mfma<64> : launch_reduce<bf16_t, 64>);
         h->combine = launch_combine<64>;
         ok = f32 ? pick_apply<float, 64>(desc->dw_kernel, &h->apply, &prep)
                  : pick_apply<bf16_t, 64>(desc->dw_kernel, &h->apply, &prep);
@@ -186,13 +201,15 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         return CASTLING_ERR_UNSUPPORTED;
     }
 
-    // token split: enough blocks to fill the chip, chunks a multiple of 64 tokens
+    // token split: enough blocks to fill the chip; chunks a multiple of what one block
+    // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
     int n_split = (kTargetReduceBlocks + h->units - 1) / h->units;
     const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;
     int chunk = (desc->N + n_split - 1) / n_split;
-    chunk = ((chunk + 63) / 64) * 64;
+    const int chunk_mult = kReduceWaves * kReduceIterTokens;
+    chunk = ((chunk + chunk_mult - 1) / chunk_mult) * chunk_mult;
     h->chunk = chunk;
     h->n_split = (desc->N + chunk - 1) / chunk;
 

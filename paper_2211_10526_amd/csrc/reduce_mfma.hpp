@@ -1,0 +1,282 @@
+// Pass 1 for bf16 I/O on the matrix cores: K_hat^T V as a token-contraction on
+// v_mfma_f32_32x32x16_bf16, the two column sums on the vector ALU.  Sec. 3.1
+// (reassociation of kernel-based linear attention) and the sums of Eq. 3.
+//
+// Every wave streams its own slice of the block's tokens: 16-byte global loads
+// (one token row = D/8 lanes), per-token 1/|k| with DPP adds, k_hat rounded to
+// bf16 and staged with V in a wave-private LDS region in [token][feature] order,
+// read back with the transposing LDS read so that each lane holds 8 consecutive
+// tokens of one feature (the MFMA operand order), then MFMA.  No block barrier
+// is needed inside the token loop.  The waves' accumulators are summed in a fixed
+// tree through LDS, so the result does not depend on timing.
+#pragma once
+
+#include "common.hpp"
+
+namespace castling {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(8))) short s16x8_t;
+
+constexpr int kReduceWaves = 4;
+constexpr int kReduceIterTokens = 32;  // tokens one wave stages per iteration
+
+// x + (value of x in another lane chosen by a DPP control)
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x)
+{
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+    return x + __int_as_float(y);
+}
+
+constexpr int kDppQuadXor1 = 0xB1;       // quad_perm [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;       // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141; // lane i <-> 7-i inside each group of 8
+constexpr int kDppRowRor8 = 0x128;       // rotate by 8 inside each row of 16
+
+// Sum over LANES consecutive lanes (4, 8 or 16); every lane of the group gets the sum.
+template <int LANES>
+__device__ __forceinline__ float row_group_sum(float x)
+{
+    x = dpp_add<kDppQuadXor1>(x);
+    x = dpp_add<kDppQuadXor2>(x);
+    if constexpr (LANES >= 8) x = dpp_add<kDppRowHalfMirror>(x);
+    if constexpr (LANES >= 16) x = dpp_add<kDppRowRor8>(x);
+    return x;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    bf16x2_t r;
+    r[0] = static_cast<__bf16>(lo);
+    r[1] = static_cast<__bf16>(hi);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// One MFMA operand (8 consecutive tokens of one feature per lane) from a
+// [token][feature] bf16 tile in LDS with `pitch` bytes per token row.
+// tok0: first of the 16 tokens of this k-step; feat0: first of the 32 features.
+__device__ __forceinline__ bf16x8_t lds_operand_tr(const unsigned char* tile, int pitch, int tok0,
+                                                   int feat0, int lane)
+{
+    const int g = lane >> 4, e = (lane >> 2) & 3, p = lane & 3;
+    const int tok = tok0 + 8 * (g >> 1) + e;
+    const int feat = feat0 + 16 * (g & 1) + 4 * p;
+    const unsigned char* a = tile + tok * pitch + feat * 2;
+    typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
+    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(a));
+    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(a + 4 * pitch));
+    s16x8_t r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return __builtin_bit_cast(bf16x8_t, r);
+}
+
+// grid = (n_split, units), block = 64 * kReduceWaves.  Same partial layout as the
+// generic kernel: partial[u][s][StateLayout<D>::SIZE].
+template <int D>
+__global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
+    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
+    int n_split, int chunk, float eps)
+{
+    constexpr int NW = kReduceWaves;
+    constexpr int MT = D / 32;               // 32-wide tiles per side of S
+    constexpr int LPR = D / 8;               // lanes per token row
+    constexpr int TPL = 64 / LPR;            // tokens per wave-wide load
+    constexpr int LOADS = kReduceIterTokens / TPL;
+    constexpr int PITCH = D * 2 + 32;        // bytes per staged token row (bank spread)
+    constexpr int TILE_BYTES = kReduceIterTokens * PITCH;
+    constexpr int ACC_BYTES = MT * MT * 16 * 64 * 4;  // one wave's accumulators
+    constexpr int STAGE_BYTES = NW * 2 * TILE_BYTES;
+    constexpr int TREE_BYTES = (NW / 2) * ACC_BYTES;
+    constexpr int SUMS_BYTES = NW * 64 * 16 * 4;
+    constexpr int LDS_BYTES = (STAGE_BYTES > TREE_BYTES ? STAGE_BYTES : TREE_BYTES) >
+                                      SUMS_BYTES
+                                  ? (STAGE_BYTES > TREE_BYTES ? STAGE_BYTES : TREE_BYTES)
+                                  : SUMS_BYTES;
+    using L = StateLayout<D>;
+
+    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int unit = blockIdx.y;
+    const int split = blockIdx.x;
+    const int n_begin = split * chunk;
+    const int n_end = min(N, n_begin + chunk);
+    // each wave takes a contiguous slice, a multiple of the iteration size
+    const int per_wave = ((chunk + NW * kReduceIterTokens - 1) / (NW * kReduceIterTokens)) *
+                         kReduceIterTokens;
+    const int w_begin = n_begin + wave * per_wave;
+    const int w_end = min(n_end, w_begin + per_wave);
+
+    const bf16_t* kb = k + static_cast<size_t>(unit) * N * D;
+    const bf16_t* vb = v + static_cast<size_t>(unit) * N * D;
+    unsigned char* ks_tile = lds + wave * 2 * TILE_BYTES;
+    unsigned char* vs_tile = ks_tile + TILE_BYTES;
+
+    const int lrow = lane / LPR;         // token inside one wave-wide load
+    const int lcol = (lane % LPR) * 8;   // first of this lane's 8 features
+
+    f32x16_t acc[MT][MT];
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int b = 0; b < MT; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+    float ksum[8], vsum[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ksum[e] = vsum[e] = 0.f;
+
+    uint4 kraw[LOADS], vraw[LOADS];
+    auto issue_loads = [&](int n0) {
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const int n = n0 + j * TPL + lrow;
+            if (n < w_end) {
+                kraw[j] = *reinterpret_cast<const uint4*>(kb + static_cast<size_t>(n) * D + lcol);
+                vraw[j] = *reinterpret_cast<const uint4*>(vb + static_cast<size_t>(n) * D + lcol);
+            } else {
+                kraw[j] = make_uint4(0u, 0u, 0u, 0u);
+                vraw[j] = make_uint4(0u, 0u, 0u, 0u);
+            }
+        }
+    };
+
+    if (w_begin < w_end) issue_loads(w_begin);
+    for (int n0 = w_begin; n0 < w_end; n0 += kReduceIterTokens) {
+        uint4 kcur[LOADS], vcur[LOADS];
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            kcur[j] = kraw[j];
+            vcur[j] = vraw[j];
+        }
+        if (n0 + kReduceIterTokens < w_end) issue_loads(n0 + kReduceIterTokens);
+
+        // normalise, accumulate the column sums, stage k_hat and v
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) {
+            const uint32_t kw[4] = {kcur[j].x, kcur[j].y, kcur[j].z, kcur[j].w};
+            const uint32_t vw[4] = {vcur[j].x, vcur[j].y, vcur[j].z, vcur[j].w};
+            float kf[8];
+            float ss = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                kf[2 * i] = __uint_as_float(kw[i] << 16);
+                kf[2 * i + 1] = __uint_as_float(kw[i] & 0xffff0000u);
+                ss = fmaf(kf[2 * i], kf[2 * i], ss);
+                ss = fmaf(kf[2 * i + 1], kf[2 * i + 1], ss);
+                vsum[2 * i] += __uint_as_float(vw[i] << 16);
+                vsum[2 * i + 1] += __uint_as_float(vw[i] & 0xffff0000u);
+            }
+            ss = row_group_sum<LPR>(ss);
+            const float inv = 1.0f / fmaxf(sqrtf(ss), eps);
+            uint4 kh;
+            uint32_t* khw = reinterpret_cast<uint32_t*>(&kh);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float a = kf[2 * i] * inv, b = kf[2 * i + 1] * inv;
+                ksum[2 * i] += a;
+                ksum[2 * i + 1] += b;
+                khw[i] = pack_bf16x2(a, b);
+            }
+            const int row = j * TPL + lrow;
+            *reinterpret_cast<uint4*>(ks_tile + row * PITCH + lcol * 2) = kh;
+            *reinterpret_cast<uint4*>(vs_tile + row * PITCH + lcol * 2) = vcur[j];
+        }
+        // LDS operations of one wave complete in issue order, and the staging tiles are
+        // private to this wave: the reads below see the writes above without a barrier.
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int s = 0; s < kReduceIterTokens / 16; ++s) {
+            bf16x8_t a[MT], b[MT];
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                a[t] = lds_operand_tr(ks_tile, PITCH, 16 * s, 32 * t, lane);
+                b[t] = lds_operand_tr(vs_tile, PITCH, 16 * s, 32 * t, lane);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt],
+                                                                          0, 0, 0);
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+
+    // ---- column sums: every lane's 16 partial sums go through LDS, summed in lane order
+    __syncthreads();  // staging tiles are dead from here on
+    {
+        float* sums = reinterpret_cast<float*>(lds);  // [wave][lane][16]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sums[(wave * 64 + lane) * 16 + e] = ksum[e];
+            sums[(wave * 64 + lane) * 16 + 8 + e] = vsum[e];
+        }
+        __syncthreads();
+        float* out = partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE;
+        if (tid < 2 * D) {
+            const int which = tid / D;          // 0: ksum, 1: vsum
+            const int f = tid % D;              // feature
+            const int lc = f / 8, e = f % 8;    // lanes with lane % LPR == lc hold it
+            float s = 0.f;
+            for (int w = 0; w < NW; ++w)
+                for (int r = 0; r < TPL; ++r)
+                    s += sums[(w * 64 + r * LPR + lc) * 16 + which * 8 + e];
+            out[(which ? L::VSUM : L::KSUM) + f] = s;
+        }
+        __syncthreads();
+    }
+
+    // ---- K_hat^T V: fixed tree over the waves, (w0 + w2) + (w1 + w3)
+    {
+        float* tree = reinterpret_cast<float*>(lds);  // [slot][reg][lane]
+#pragma unroll
+        for (int half = NW / 2; half >= 1; half >>= 1) {
+            if (wave >= half && wave < 2 * half) {
+                float* dst = tree + (wave - half) * (ACC_BYTES / 4);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            dst[((mt * MT + nt) * 16 + r) * 64 + lane] = acc[mt][nt][r];
+            }
+            __syncthreads();
+            if (wave < half) {
+                const float* src = tree + wave * (ACC_BYTES / 4);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            acc[mt][nt][r] += src[((mt * MT + nt) * 16 + r) * 64 + lane];
+            }
+            __syncthreads();
+        }
+        if (wave == 0) {
+            float* out = partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE + L::S;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int i = 32 * mt + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
+                        const int j = 32 * nt + (lane % 32);
+                        out[i * D + j] = acc[mt][nt][r];
+                    }
+        }
+    }
+}
+
+}  // namespace castling
