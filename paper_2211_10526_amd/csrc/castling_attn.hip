@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "apply_generic.hpp"
+#include "apply_mfma.hpp"
 #include "common.hpp"
 #include "reduce_generic.hpp"
 #include "reduce_mfma.hpp"
@@ -30,83 +31,14 @@ int hip_fail(hipError_t e)
     return CASTLING_ERR_HIP;
 }
 
-#define HIP_TRY(expr)                                \
-    do {                                             \
-        hipError_t e_ = (expr);                      \
-        if (e_ != hipSuccess) return hip_fail(e_);   \
+#define HIP_TRY(expr)                              \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) return hip_fail(e_); \
     } while (0)
 
-typedef void (*reduce_fn_t)(const void*, const void*, float*, int, int, int, float, int, int,
-                            hipStream_t);
-typedef void (*combine_fn_t)(const float*, float*, int, int, hipStream_t);
-typedef hipError_t (*apply_fn_t)(const void*, const void*, const void*, const void*, const float*,
-                                 void*, int, int, ApplyParams, hipStream_t);
-typedef hipError_t (*apply_prepare_fn_t)(size_t* lds_bytes);
-
-template <typename T, int D>
-void launch_reduce(const void* k, const void* v, float* partial, int N, int n_split, int chunk,
-                   float eps, int units, int, hipStream_t s)
-{
-    hipLaunchKernelGGL((reduce_generic_kernel<T, D>), dim3(n_split, units), dim3(256), 0, s,
-                       static_cast<const T*>(k), static_cast<const T*>(v), partial, N, n_split,
-                       chunk, eps);
-}
-
-template <int D>
-void launch_reduce_mfma(const void* k, const void* v, float* partial, int N, int n_split, int chunk,
-                        float eps, int units, int, hipStream_t s)
-{
-    hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(n_split, units), dim3(64 * kReduceWaves), 0, s,
-                       static_cast<const bf16_t*>(k), static_cast<const bf16_t*>(v), partial, N,
-                       n_split, chunk, eps);
-}
-
-template <int D>
-void launch_combine(const float* partial, float* state, int n_split, int units, hipStream_t s)
-{
-    using L = StateLayout<D>;
-    hipLaunchKernelGGL((combine_kernel<D>), dim3((L::SIZE + 255) / 256, units), dim3(256), 0, s,
-                       partial, state, n_split);
-}
-
-template <typename T, int D, int KS>
-hipError_t prepare_apply(size_t* lds_bytes)
-{
-    *lds_bytes = apply_generic_lds_bytes<T, D, KS>();
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_generic_kernel<T, D, KS>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                               static_cast<int>(*lds_bytes));
-}
-
-template <typename T, int D, int KS>
-hipError_t launch_apply(const void* q, const void* v, const void* w, const void* bias,
-                        const float* state, void* out, int heads, int units, ApplyParams p,
-                        hipStream_t s)
-{
-    const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
-    constexpr size_t lds = apply_generic_lds_bytes<T, D, KS>();
-    hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, units),
-                       dim3(256), lds, s,
-                       static_cast<const T*>(q), static_cast<const T*>(v),
-                       static_cast<const T*>(w), static_cast<const T*>(bias), state,
-                       static_cast<T*>(out), heads, p);
-    return hipGetLastError();
-}
-
-template <typename T, int D>
-bool pick_apply(int ks, apply_fn_t* fn, apply_prepare_fn_t* prep)
-{
-    switch (ks) {
-        case 1: *fn = launch_apply<T, D, 1>; *prep = prepare_apply<T, D, 1>; return true;
-        case 3: *fn = launch_apply<T, D, 3>; *prep = prepare_apply<T, D, 3>; return true;
-        case 5: *fn = launch_apply<T, D, 5>; *prep = prepare_apply<T, D, 5>; return true;
-        case 7: *fn = launch_apply<T, D, 7>; *prep = prepare_apply<T, D, 7>; return true;
-        case 9: *fn = launch_apply<T, D, 9>; *prep = prepare_apply<T, D, 9>; return true;
-        default: return false;
-    }
-}
-
 size_t dtype_size(int dt) { return dt == CASTLING_F32 ? 4 : 2; }
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
@@ -116,15 +48,201 @@ struct castling_attn {
     int units;
     int n_split;
     int chunk;
-    int state_size;       // floats per unit
-    float* partial;       // [units][n_split][state_size]
-    float* state;         // [units][state_size]
+    int state_size;     // floats per unit
+    bool mfma_reduce;   // bf16: K_hat^T V on the matrix cores
+    bool mfma_apply;    // bf16, d = 64: q.S and the DWConv on the matrix cores
+    int band_rows;      // rows of the token grid per apply block (MFMA path)
+    size_t apply_lds;   // dynamic LDS of the apply kernel
+    // workspace (one allocation)
+    unsigned char* workspace;
     size_t workspace_bytes;
-    reduce_fn_t reduce;
-    combine_fn_t combine;
-    apply_fn_t apply;
-    size_t apply_lds;
+    float* partial;     // [units][n_split][state_size]
+    float* state;       // [units][state_size]
+    bf16_t* sfrag;      // MFMA path: operand tables, see apply_mfma.hpp
+    bf16_t* kfrag;
+    float* vhalf;
+    bf16_t* wfrag;
 };
+
+namespace {
+
+// ------------------------------------------------------------------ reduce
+template <typename T, int D>
+void launch_reduce_generic(castling_attn* h, const void* k, const void* v, hipStream_t s)
+{
+    hipLaunchKernelGGL((reduce_generic_kernel<T, D>), dim3(h->n_split, h->units), dim3(256), 0, s,
+                       static_cast<const T*>(k), static_cast<const T*>(v), h->partial, h->desc.N,
+                       h->n_split, h->chunk, h->desc.eps);
+}
+
+template <int D>
+void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, hipStream_t s)
+{
+    hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(h->n_split, h->units),
+                       dim3(64 * kReduceWaves), 0, s, static_cast<const bf16_t*>(k),
+                       static_cast<const bf16_t*>(v), h->partial, h->desc.N, h->n_split, h->chunk,
+                       h->desc.eps);
+}
+
+template <int D>
+void launch_combine(castling_attn* h, hipStream_t s)
+{
+    using L = StateLayout<D>;
+    hipLaunchKernelGGL((combine_kernel<D>), dim3((L::SIZE + 255) / 256, h->units), dim3(256), 0, s,
+                       h->partial, h->state, h->n_split);
+}
+
+int do_reduce(castling_attn* h, const void* k, const void* v, hipStream_t s)
+{
+    const bool f32 = h->desc.io_dtype == CASTLING_F32;
+    const int d = h->desc.d;
+    if (h->mfma_reduce) {
+        if (d == 32) launch_reduce_mfma<32>(h, k, v, s);
+        else launch_reduce_mfma<64>(h, k, v, s);
+    } else if (f32) {
+        if (d == 32) launch_reduce_generic<float, 32>(h, k, v, s);
+        else launch_reduce_generic<float, 64>(h, k, v, s);
+    } else {
+        if (d == 32) launch_reduce_generic<bf16_t, 32>(h, k, v, s);
+        else launch_reduce_generic<bf16_t, 64>(h, k, v, s);
+    }
+    HIP_TRY(hipGetLastError());
+    if (h->mfma_apply) {
+        hipLaunchKernelGGL(combine_frag_kernel, dim3((kCombineFragThreads + 255) / 256, h->units),
+                           dim3(256), 0, s, h->partial, h->state, h->sfrag, h->kfrag, h->vhalf,
+                           h->n_split);
+    } else if (d == 32) {
+        launch_combine<32>(h, s);
+    } else {
+        launch_combine<64>(h, s);
+    }
+    HIP_TRY(hipGetLastError());
+    return CASTLING_OK;
+}
+
+// ------------------------------------------------------------------ apply
+// launch = false: set the kernel's LDS attribute and record its LDS size (create time)
+template <typename T, int D, int KS>
+hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const void* v,
+                         const void* w, const void* bias, void* out, hipStream_t s)
+{
+    constexpr size_t lds = apply_generic_lds_bytes<T, D, KS>();
+    if (!launch) {
+        h->apply_lds = lds;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_generic_kernel<T, D, KS>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   static_cast<int>(lds));
+    }
+    const castling_attn_desc_t& d = h->desc;
+    ApplyParams p;
+    p.N = d.N;
+    p.grid_h = d.grid_h;
+    p.grid_w = d.grid_w;
+    p.tiles_x = (d.grid_w + kApplyTW - 1) / kApplyTW;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    p.eps = d.eps;
+    const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
+    hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, h->units),
+                       dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
+                       static_cast<const T*>(w), static_cast<const T*>(bias), h->state,
+                       static_cast<T*>(out), d.heads, p);
+    return hipGetLastError();
+}
+
+template <int KS>
+hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
+                      const void* bias, void* out, hipStream_t s)
+{
+    if (!launch) {
+        h->apply_lds = kApplyMfmaLdsBytes;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma_kernel<KS>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kApplyMfmaLdsBytes);
+    }
+    const castling_attn_desc_t& d = h->desc;
+    ApplyMfmaParams p;
+    p.N = d.N;
+    p.grid_h = d.grid_h;
+    p.grid_w = d.grid_w;
+    p.strips = (d.grid_w + kStripW - 1) / kStripW;
+    p.band_rows = h->band_rows;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    p.eps = d.eps;
+    if (p.do_dwconv) {
+        const int threads = d.heads * 4 * KS * 3 * 64;
+        hipLaunchKernelGGL((dwconv_weight_frag_kernel<KS>), dim3((threads + 255) / 256), dim3(256),
+                           0, s, static_cast<const bf16_t*>(w), h->wfrag, d.heads);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    const int bands = (d.grid_h + p.band_rows - 1) / p.band_rows;
+    hipLaunchKernelGGL((apply_mfma_kernel<KS>), dim3(p.strips * bands, h->units), dim3(256),
+                       kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
+                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(bias), h->sfrag,
+                       h->kfrag, h->vhalf, h->wfrag, static_cast<bf16_t*>(out), d.heads, p);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t apply_generic_ks(castling_attn* h, bool launch, const void* q, const void* v,
+                            const void* w, const void* bias, void* out, hipStream_t s)
+{
+    switch (h->desc.dw_kernel) {
+        case 1: return apply_generic<T, D, 1>(h, launch, q, v, w, bias, out, s);
+        case 3: return apply_generic<T, D, 3>(h, launch, q, v, w, bias, out, s);
+        case 5: return apply_generic<T, D, 5>(h, launch, q, v, w, bias, out, s);
+        case 7: return apply_generic<T, D, 7>(h, launch, q, v, w, bias, out, s);
+        default: return apply_generic<T, D, 9>(h, launch, q, v, w, bias, out, s);
+    }
+}
+
+hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
+                    const void* bias, void* out, hipStream_t s)
+{
+    if (h->mfma_apply) {
+        switch (h->desc.dw_kernel) {
+            case 1: return apply_mfma<1>(h, launch, q, v, w, bias, out, s);
+            case 3: return apply_mfma<3>(h, launch, q, v, w, bias, out, s);
+            case 5: return apply_mfma<5>(h, launch, q, v, w, bias, out, s);
+            case 7: return apply_mfma<7>(h, launch, q, v, w, bias, out, s);
+            default: return apply_mfma<9>(h, launch, q, v, w, bias, out, s);
+        }
+    }
+    const bool f32 = h->desc.io_dtype == CASTLING_F32;
+    if (h->desc.d == 32)
+        return f32 ? apply_generic_ks<float, 32>(h, launch, q, v, w, bias, out, s)
+                   : apply_generic_ks<bf16_t, 32>(h, launch, q, v, w, bias, out, s);
+    return f32 ? apply_generic_ks<float, 64>(h, launch, q, v, w, bias, out, s)
+               : apply_generic_ks<bf16_t, 64>(h, launch, q, v, w, bias, out, s);
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
+int check_apply_args(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
+                     void* out)
+{
+    if (!h || !out) return CASTLING_ERR_INVALID_ARG;
+    const castling_attn_desc_t& d = h->desc;
+    const bool lin = d.branches & CASTLING_BRANCH_LINEAR, dw = d.branches & CASTLING_BRANCH_DWCONV;
+    if ((lin && !q) || (dw && (!v || !dw_weight))) return CASTLING_ERR_INVALID_ARG;
+    if (misaligned(out) || (lin && misaligned(q)) || (dw && (misaligned(v) || misaligned(dw_weight))))
+        return CASTLING_ERR_INVALID_ARG;
+    const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
+    if ((lin && overlaps(out, bytes, q, bytes)) || (dw && overlaps(out, bytes, v, bytes)))
+        return CASTLING_ERR_ALIAS;
+    return CASTLING_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -177,28 +295,15 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->units = desc->B * desc->heads;
     h->state_size = desc->d * desc->d + 2 * desc->d;
 
-    const bool f32 = desc->io_dtype == CASTLING_F32;
     // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 on the vector-ALU kernels (A/B measurements)
     const char* force = getenv("CASTLING_ATTN_FORCE_GENERIC");
-    const bool mfma = !f32 && !(force && force[0] == '1');
-    apply_prepare_fn_t prep = nullptr;
-    bool ok;
-    if (desc->d == 32) {
-        h->reduce = f32 ? launch_reduce<float, 32>
-                        : (mfma ? launch_reduce_mfma<32> : launch_reduce<bf16_t, 32>);
-        h->combine = launch_combine<32>;
-        ok = f32 ? pick_apply<float, 32>(desc->dw_kernel, &h->apply, &prep)
-                 : pick_apply<bf16_t, 32>(desc->dw_kernel, &h->apply, &prep);
-    } else {
-        h->reduce = f32 ? launch_reduce<float, 64>
-                        : (mfma ? launch_reduce_mfma<64> : launch_reduce<bf16_t, 64>);
-        h->combine = launch_combine<64>;
-        ok = f32 ? pick_apply<float, 64>(desc->dw_kernel, &h->apply, &prep)
-                 : pick_apply<bf16_t, 64>(desc->dw_kernel, &h->apply, &prep);
-    }
-    if (!ok) {
-        delete h;
-        return CASTLING_ERR_UNSUPPORTED;
+    const bool allow_mfma = desc->io_dtype == CASTLING_BF16 && !(force && force[0] == '1');
+    h->mfma_reduce = allow_mfma;
+    h->mfma_apply = allow_mfma && desc->d == 64;
+    h->band_rows = 32;
+    if (const char* br = getenv("CASTLING_ATTN_BAND_ROWS")) {
+        const int v = atoi(br);
+        if (v >= 4 && v % 4 == 0) h->band_rows = v;
     }
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
@@ -214,7 +319,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->n_split = (desc->N + chunk - 1) / chunk;
 
     hipError_t e = hipGetDevice(&h->device);
-    if (e == hipSuccess) e = prep(&h->apply_lds);
+    if (e == hipSuccess) e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
     if (e == hipSuccess) {
         int max_lds = 0;
         e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
@@ -223,16 +328,38 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
             return CASTLING_ERR_UNSUPPORTED;
         }
     }
+    // one allocation, 256-byte aligned parts
     const size_t partial_bytes =
-        sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size;
-    const size_t state_bytes = sizeof(float) * static_cast<size_t>(h->units) * h->state_size;
-    h->workspace_bytes = partial_bytes + state_bytes;
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->partial), h->workspace_bytes);
+        align_up(sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size, 256);
+    const size_t state_bytes =
+        align_up(sizeof(float) * static_cast<size_t>(h->units) * h->state_size, 256);
+    size_t sfrag_bytes = 0, kfrag_bytes = 0, vhalf_bytes = 0, wfrag_bytes = 0;
+    if (h->mfma_apply) {
+        sfrag_bytes = align_up(sizeof(bf16_t) * static_cast<size_t>(h->units) * kSfragPerUnit, 256);
+        kfrag_bytes = align_up(sizeof(bf16_t) * static_cast<size_t>(h->units) * kKfragPerUnit, 256);
+        vhalf_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * 64, 256);
+        wfrag_bytes =
+            align_up(static_cast<size_t>(desc->heads) * 4 * desc->dw_kernel * 3 * 64 * 8, 256);
+    }
+    h->workspace_bytes =
+        partial_bytes + state_bytes + sfrag_bytes + kfrag_bytes + vhalf_bytes + wfrag_bytes;
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->workspace), h->workspace_bytes);
     if (e != hipSuccess) {
         delete h;
         return hip_fail(e);
     }
-    h->state = h->partial + static_cast<size_t>(h->units) * h->n_split * h->state_size;
+    unsigned char* p = h->workspace;
+    h->partial = reinterpret_cast<float*>(p);
+    p += partial_bytes;
+    h->state = reinterpret_cast<float*>(p);
+    p += state_bytes;
+    h->sfrag = reinterpret_cast<bf16_t*>(p);
+    p += sfrag_bytes;
+    h->kfrag = reinterpret_cast<bf16_t*>(p);
+    p += kfrag_bytes;
+    h->vhalf = reinterpret_cast<float*>(p);
+    p += vhalf_bytes;
+    h->wfrag = reinterpret_cast<bf16_t*>(p);
     *out_handle = h;
     return CASTLING_OK;
 }
@@ -240,7 +367,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
 int castling_attn_destroy(castling_attn_t h)
 {
     if (!h) return CASTLING_OK;
-    hipError_t e = h->partial ? hipFree(h->partial) : hipSuccess;
+    hipError_t e = h->workspace ? hipFree(h->workspace) : hipSuccess;
     delete h;
     return e == hipSuccess ? CASTLING_OK : hip_fail(e);
 }
@@ -249,40 +376,11 @@ size_t castling_attn_workspace_bytes(castling_attn_t h) { return h ? h->workspac
 
 int castling_attn_num_splits(castling_attn_t h) { return h ? h->n_split : 0; }
 
-static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
-
-static bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
-{
-    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
-    return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
-}
-
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
 {
     if (!h || !k || !v) return CASTLING_ERR_INVALID_ARG;
     if (misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const castling_attn_desc_t& d = h->desc;
-    h->reduce(k, v, h->partial, d.N, h->n_split, h->chunk, d.eps, h->units, 0, s);
-    HIP_TRY(hipGetLastError());
-    h->combine(h->partial, h->state, h->n_split, h->units, s);
-    HIP_TRY(hipGetLastError());
-    return CASTLING_OK;
-}
-
-static int check_apply_args(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
-                            void* out)
-{
-    if (!h || !out) return CASTLING_ERR_INVALID_ARG;
-    const castling_attn_desc_t& d = h->desc;
-    const bool lin = d.branches & CASTLING_BRANCH_LINEAR, dw = d.branches & CASTLING_BRANCH_DWCONV;
-    if ((lin && !q) || (dw && (!v || !dw_weight))) return CASTLING_ERR_INVALID_ARG;
-    if (misaligned(out) || (lin && misaligned(q)) || (dw && (misaligned(v) || misaligned(dw_weight))))
-        return CASTLING_ERR_INVALID_ARG;
-    const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
-    if ((lin && overlaps(out, bytes, q, bytes)) || (dw && overlaps(out, bytes, v, bytes)))
-        return CASTLING_ERR_ALIAS;
-    return CASTLING_OK;
+    return do_reduce(h, k, v, static_cast<hipStream_t>(stream));
 }
 
 int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
@@ -290,18 +388,7 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
 {
     int st = check_apply_args(h, q, v, dw_weight, out);
     if (st != CASTLING_OK) return st;
-    const castling_attn_desc_t& d = h->desc;
-    ApplyParams p;
-    p.N = d.N;
-    p.grid_h = d.grid_h;
-    p.grid_w = d.grid_w;
-    p.tiles_x = (d.grid_w + kApplyTW - 1) / kApplyTW;
-    p.norm_none = d.norm == CASTLING_NORM_NONE;
-    p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
-    p.eps = d.eps;
-    HIP_TRY(h->apply(q, v, dw_weight, dw_bias, h->state, out, d.heads, h->units, p,
-                     static_cast<hipStream_t>(stream)));
+    HIP_TRY(do_apply(h, true, q, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
     return CASTLING_OK;
 }
 
