@@ -17,6 +17,8 @@
 // in registers, so each staged row is read from LDS once per wave.
 #pragma once
 
+#include <type_traits>
+
 #include "common.hpp"
 #include "reduce_mfma.hpp"
 
@@ -27,7 +29,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 struct ApplyMfmaParams {
     int N, grid_h, grid_w;
     int strips;     // 16-column strips per grid row
-    int band_rows;  // output rows per block (multiple of 4)
     int norm_none, do_linear, do_dwconv;
     float eps;
 };
@@ -50,8 +51,8 @@ constexpr int kApplyMfmaLdsBytes = 2 * (kVtBytes + kLinBytes);
 constexpr int kSfragPerUnit = 4 * 2 * 64 * 8;  // bf16 elements
 constexpr int kKfragPerUnit = 2 * 64 * 8;
 
-// grid = (ceil(units * 4096 / 2 / 256) ...) see launch; one thread sums the partials of
-// two adjacent-i elements of S, writes the fp32 state and the bf16 fragment pair.
+// grid = (ceil(kCombineFragThreads / 256), units).  Fixed-order sum of the partial
+// states; writes the fp32 state and the bf16 MFMA operand tables of the apply kernel.
 __global__ __launch_bounds__(256) void combine_frag_kernel(const float* __restrict__ partial,
                                                             float* __restrict__ state,
                                                             bf16_t* __restrict__ sfrag,
@@ -68,11 +69,8 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(const float* __restri
         const int e2 = t & 3, lane = (t >> 2) & 63, ks = (t >> 8) & 1, nt = t >> 9;
         const int i0 = 32 * ks + 8 * (lane >> 4) + 2 * e2;
         const int j = 16 * nt + (lane & 15);
-        float s0 = 0.f, s1 = 0.f;
-        for (int sp = 0; sp < n_split; ++sp) {
-            s0 += p[static_cast<size_t>(sp) * L::SIZE + i0 * 64 + j];
-            s1 += p[static_cast<size_t>(sp) * L::SIZE + (i0 + 1) * 64 + j];
-        }
+        const float s0 = sum_partials(p + i0 * 64 + j, n_split, L::SIZE);
+        const float s1 = sum_partials(p + (i0 + 1) * 64 + j, n_split, L::SIZE);
         st[i0 * 64 + j] = s0;
         st[(i0 + 1) * 64 + j] = s1;
         uint32_t* dst = reinterpret_cast<uint32_t*>(sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
@@ -80,8 +78,7 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(const float* __restri
     } else if (t < 2048 + 128) {
         // column sums into the fp32 state; vsum / 2 for the apply kernel
         const int f = t - 2048;  // 0..63 ksum, 64..127 vsum
-        float s = 0.f;
-        for (int sp = 0; sp < n_split; ++sp) s += p[static_cast<size_t>(sp) * L::SIZE + L::KSUM + f];
+        const float s = sum_partials(p + L::KSUM + f, n_split, L::SIZE);
         st[L::KSUM + f] = s;
         if (f >= 64) vhalf[unit * 64 + (f - 64)] = 0.5f * s;
     } else if (t < 2048 + 128 + 512) {
@@ -89,11 +86,8 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(const float* __restri
         const int u = t - (2048 + 128);
         const int e2 = u & 3, lane = (u >> 2) & 63, ks = u >> 8;
         const int i0 = 32 * ks + 8 * (lane >> 4) + 2 * e2;
-        float s0 = 0.f, s1 = 0.f;
-        for (int sp = 0; sp < n_split; ++sp) {
-            s0 += p[static_cast<size_t>(sp) * L::SIZE + L::KSUM + i0];
-            s1 += p[static_cast<size_t>(sp) * L::SIZE + L::KSUM + i0 + 1];
-        }
+        const float s0 = sum_partials(p + L::KSUM + i0, n_split, L::SIZE);
+        const float s1 = sum_partials(p + L::KSUM + i0 + 1, n_split, L::SIZE);
         uint32_t* dst = reinterpret_cast<uint32_t*>(kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
         dst[u] = pack_bf16x2(s0 * kInvPi, s1 * kInvPi);
     }
@@ -127,150 +121,183 @@ __global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* _
     reinterpret_cast<uint2*>(wfrag)[t] = o;
 }
 
-// grid = (strips * bands, units), block = 256.
+// ---------------------------------------------------------------------------
+// Work is cut into "steps" of 4 output rows of one 16-column strip of one unit.
+// Steps are numbered unit-major, then strip, then top to bottom; block b of G
+// takes the contiguous range [b*T/G, (b+1)*T/G) of the T steps, so every compute
+// unit gets the same amount of work whatever the grid shape.  A maximal run of
+// steps inside one strip column is a segment; a segment first primes the DWConv
+// window (NCH - 1 stages that only stage V rows) and then emits one step per stage.
+struct StageCursor {
+    int g_begin, g_end;  // steps [g_begin, g_end) of the current segment
+    int t;               // stage inside the segment
+    int range_end;       // end of this block's step range
+
+    __device__ __forceinline__ void start(int s0, int s1, int spc)
+    {
+        range_end = s1;
+        g_begin = s0;
+        g_end = min(s1, (s0 / spc + 1) * spc);
+        t = 0;
+    }
+    __device__ __forceinline__ bool done() const { return g_begin >= range_end; }
+    __device__ __forceinline__ void advance(int spc, int nch)
+    {
+        if (++t == (g_end - g_begin) + nch - 1) {
+            g_begin = g_end;
+            g_end = min(range_end, (g_begin / spc + 1) * spc);
+            t = 0;
+        }
+    }
+};
+
+// LDS-only workgroup barrier: global loads that are still in flight stay in flight.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+constexpr int kApplyPrefetch = 2;  // stages whose global loads are in flight
+
+// grid = (G), block = 512: waves 0..3 consume (DWConv MFMAs + store), waves 4..7 produce
+// (global loads, V transposition into LDS, linear branch).
 template <int KS>
-__global__ __launch_bounds__(256) void apply_mfma_kernel(
+__global__ __launch_bounds__(512) void apply_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ v, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ sfrag, const bf16_t* __restrict__ kfrag,
     const float* __restrict__ vhalf, const bf16_t* __restrict__ wfrag, bf16_t* __restrict__ out,
-    int heads, ApplyMfmaParams p)
+    int heads, int total_steps, ApplyMfmaParams p)
 {
     constexpr int D = 64;
     constexpr int RAD = KS / 2;
     constexpr int NCH = (KS + 3 + 3) / 4;  // 4-row chunks that cover the window
     constexpr int WR = 4 * NCH;            // window rows held in registers
+    constexpr int PD = kApplyPrefetch;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int c = tid >> 6;  // wave = channel group = row inside a step
-    const int unit = blockIdx.y;
-    const int head = unit % heads;
-    const int strip = blockIdx.x % p.strips;
-    const int band = blockIdx.x / p.strips;
-    const int xs0 = strip * kStripW;
-    const int y0 = band * p.band_rows;
-    const int y_end = min(p.grid_h, y0 + p.band_rows);
+    const int wave = tid >> 6;
+    const bool producer = wave >= 4;
+    const int c = wave & 3;    // consumer: channel group; producer: row inside the step
+    const int ptid = tid & 255;  // index among the 256 producer threads
     const int W = p.grid_w, H = p.grid_h;
-    const size_t unit_off = static_cast<size_t>(unit) * p.N * D;
-    const bf16_t* vu = v + unit_off;
-    const bf16_t* qu = q + unit_off;
+    const int spc = (H + 3) / 4;  // steps per strip column
+
+    const int s_begin = static_cast<int>(static_cast<long long>(blockIdx.x) * total_steps / gridDim.x);
+    const int s_end = static_cast<int>(static_cast<long long>(blockIdx.x + 1) * total_steps / gridDim.x);
 
     auto vt_buf = [&](int b) { return lds + b * (kVtBytes + kLinBytes); };
-    auto lin_buf = [&](int b) { return reinterpret_cast<float*>(lds + b * (kVtBytes + kLinBytes) + kVtBytes); };
+    auto lin_buf = [&](int b) {
+        return reinterpret_cast<float*>(lds + b * (kVtBytes + kLinBytes) + kVtBytes);
+    };
+    // cursor -> coordinates
+    auto col_of = [&](const StageCursor& cu) { return cu.g_begin / spc; };
+    auto y0_of = [&](const StageCursor& cu) { return 4 * (cu.g_begin % spc); };
 
-    // ---- per-wave constants
-    // DWConv lane roles: channel ch_dw, quad j (output x = xs0 + 4 j + i)
+    // ------------------------------------------------------------ consumer state
     const int blk = lane >> 2, j = lane & 3;
     const int ch_dw = 16 * c + blk;
     s16x4_t tw[KS][3];
-    if (p.do_dwconv) {
-        const uint2* wf = reinterpret_cast<const uint2*>(wfrag) +
-                          ((static_cast<size_t>(head) * 4 + c) * KS * 3) * 64 + lane;
+    s16x4_t win[WR][3];
+    float bias_dw = 0.f;
+    int cons_head = -1;
 #pragma unroll
-        for (int dy = 0; dy < KS; ++dy)
+    for (int a = 0; a < WR; ++a)
 #pragma unroll
-            for (int m = 0; m < 3; ++m) {
-                const uint2 t = wf[(dy * 3 + m) * 64];
-                tw[dy][m] = __builtin_bit_cast(s16x4_t, t);
-            }
-    }
-    const float bias_dw = (bias && p.do_dwconv) ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
+        for (int m = 0; m < 3; ++m) win[a][m] = s16x4_t{0, 0, 0, 0};
+#pragma unroll
+    for (int a = 0; a < KS; ++a)
+#pragma unroll
+        for (int m = 0; m < 3; ++m) tw[a][m] = s16x4_t{0, 0, 0, 0};
 
-    // linear lane roles: token tl (A operand row), feature group g; D layout: column n, tokens 4 g + r
+    // ------------------------------------------------------------ producer state
     const int tl = lane & 15, g = lane >> 4;
     bf16x8_t sf[4][2], kf[2];
-    float vh[4];
-    if (p.do_linear) {
-        const uint4* s4 = reinterpret_cast<const uint4*>(sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
-        const uint4* k4 = reinterpret_cast<const uint4*>(kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
-            vh[nt] = vhalf[unit * D + 16 * nt + tl];
-        }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
-    }
+    float vh[4] = {0.f, 0.f, 0.f, 0.f};
+    int prod_unit = -1;
+    uint4 vreg[PD][3], qreg[PD][2];
 
-    // ---- cooperative V staging: 4 rows x 24 columns x 8 octets = 768 16-byte items
-    uint4 vreg[3];
-    auto load_v_rows = [&](int row_base) {
+    auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
+        constexpr int slot = decltype(slot_c)::value;
+        const int col = col_of(cu);
+        const int unit = col / p.strips, xs0 = (col % p.strips) * kStripW;
+        const int y0 = y0_of(cu);
+        const size_t unit_off = static_cast<size_t>(unit) * p.N * D;
+        const int row_base = y0 - RAD + 4 * cu.t;
+        if (p.do_dwconv) {
 #pragma unroll
-        for (int it = 0; it < 3; ++it) {
-            const int item = tid + 256 * it;
-            const int r = item / 192, rem = item % 192;
-            const int x = rem >> 3, oct = rem & 7;
-            const int gy = row_base + r, gx = xs0 - 4 + x;
-            vreg[it] = make_uint4(0u, 0u, 0u, 0u);
-            if (gy >= 0 && gy < H && gx >= 0 && gx < W)
-                vreg[it] = *reinterpret_cast<const uint4*>(vu + (static_cast<size_t>(gy) * W + gx) * D + oct * 8);
+            for (int it = 0; it < 3; ++it) {
+                const int item = ptid + 256 * it;
+                const int r = item / 192, rem = item % 192;
+                const int x = rem >> 3, oct = rem & 7;
+                const int gy = row_base + r, gx = xs0 - 4 + x;
+                vreg[slot][it] = make_uint4(0u, 0u, 0u, 0u);
+                if (gy >= 0 && gy < H && gx >= 0 && gx < W)
+                    vreg[slot][it] = *reinterpret_cast<const uint4*>(
+                        v + unit_off + (static_cast<size_t>(gy) * W + gx) * D + oct * 8);
+            }
         }
-    };
-    auto write_v_rows = [&](unsigned char* vt) {
-#pragma unroll
-        for (int it = 0; it < 3; ++it) {
-            const int item = tid + 256 * it;
-            const int r = item / 192, rem = item % 192;
-            const int x = rem >> 3, oct = rem & 7;
-            unsigned char* dst = vt + (r * 6 + (x >> 2)) * kVtQuadStride + oct * kVtOctetStride + (x & 3) * 2;
-            const uint32_t wd[4] = {vreg[it].x, vreg[it].y, vreg[it].z, vreg[it].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                *reinterpret_cast<uint16_t*>(dst + (2 * e) * 8) = static_cast<uint16_t>(wd[e] & 0xffffu);
-                *reinterpret_cast<uint16_t*>(dst + (2 * e + 1) * 8) = static_cast<uint16_t>(wd[e] >> 16);
+        if (p.do_linear && cu.t >= NCH - 1) {
+            const int y = y0 + 4 * (cu.t - (NCH - 1)) + c, x = xs0 + tl;
+            qreg[slot][0] = qreg[slot][1] = make_uint4(0u, 0u, 0u, 0u);
+            if (y < H && x < W) {
+                const uint4* src = reinterpret_cast<const uint4*>(
+                    q + unit_off + (static_cast<size_t>(y) * W + x) * D + 8 * g);
+                qreg[slot][0] = src[0];
+                qreg[slot][1] = src[4];
             }
         }
     };
 
-    // sliding window of DWConv data operands: win[idx][m], idx <-> input row (yo - RAD + idx)
-    s16x4_t win[WR][3];
-    auto read_window_rows = [&](const unsigned char* vt, int idx0) {
-        const unsigned char* base = vt + (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int m = 0; m < 3; ++m) {
-                const uint2 t = *reinterpret_cast<const uint2*>(base + (r * 6 + m + j) * kVtQuadStride);
-                win[idx0 + r][m] = __builtin_bit_cast(s16x4_t, t);
-            }
-    };
-
-    if (p.do_dwconv) {
-#pragma unroll
-        for (int chunk = 0; chunk < NCH; ++chunk) {
-            load_v_rows(y0 - RAD + 4 * chunk);
-            write_v_rows(vt_buf(0));
-            __syncthreads();
-            read_window_rows(vt_buf(0), 4 * chunk);
-            __syncthreads();
-        }
-    }
-
-    // ---- main loop over 4-row steps
-    int buf = 0;
-    for (int yo = y0; yo < y_end; yo += 4, buf ^= 1) {
+    auto produce = [&](auto slot_c, const StageCursor& cu, int buf) {
+        constexpr int slot = decltype(slot_c)::value;
         unsigned char* vt = vt_buf(buf);
         float* lin = lin_buf(buf);
-
-        if (p.do_dwconv && yo > y0) {
-            load_v_rows(yo - RAD + WR - 4);
-            write_v_rows(vt);
-        }
-
-        // linear branch for row yo + c (all 64 channels of 16 tokens)
-        if (p.do_linear) {
-            const int y = yo + c, x = xs0 + tl;
-            bf16x8_t a[2];
-            a[0] = a[1] = __builtin_bit_cast(bf16x8_t, make_uint4(0u, 0u, 0u, 0u));
-            if (y < H && x < W) {
-                const uint4* src = reinterpret_cast<const uint4*>(qu + (static_cast<size_t>(y) * W + x) * D + 8 * g);
-                a[0] = __builtin_bit_cast(bf16x8_t, src[0]);
-                a[1] = __builtin_bit_cast(bf16x8_t, src[4]);
+        if (p.do_dwconv) {
+#pragma unroll
+            for (int it = 0; it < 3; ++it) {
+                const int item = ptid + 256 * it;
+                const int r = item / 192, rem = item % 192;
+                const int x = rem >> 3, oct = rem & 7;
+                unsigned char* dst =
+                    vt + (r * 6 + (x >> 2)) * kVtQuadStride + oct * kVtOctetStride + (x & 3) * 2;
+                const uint32_t wd[4] = {vreg[slot][it].x, vreg[slot][it].y, vreg[slot][it].z,
+                                        vreg[slot][it].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    *reinterpret_cast<uint16_t*>(dst + (2 * e) * 8) =
+                        static_cast<uint16_t>(wd[e] & 0xffffu);
+                    *reinterpret_cast<uint16_t*>(dst + (2 * e + 1) * 8) =
+                        static_cast<uint16_t>(wd[e] >> 16);
+                }
             }
+        }
+        if (p.do_linear && cu.t >= NCH - 1) {
+            const int unit = col_of(cu) / p.strips;
+            if (unit != prod_unit) {  // uniform per block: operand tables of the new unit
+                prod_unit = unit;
+                const uint4* s4 =
+                    reinterpret_cast<const uint4*>(sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
+                const uint4* k4 =
+                    reinterpret_cast<const uint4*>(kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
+                    vh[nt] = vhalf[unit * D + 16 * nt + tl];
+                }
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
+            }
+            bf16x8_t a[2];
+            a[0] = __builtin_bit_cast(bf16x8_t, qreg[slot][0]);
+            a[1] = __builtin_bit_cast(bf16x8_t, qreg[slot][1]);
             float ss = 0.f;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
@@ -321,40 +348,118 @@ __global__ __launch_bounds__(256) void apply_mfma_kernel(
                 *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
             }
         }
-        __syncthreads();
+    };
 
-        if (p.do_dwconv && yo > y0) {
-            // slide the window down by four rows and take in the four new ones
-#pragma unroll
-            for (int idx = 0; idx < WR - 4; ++idx)
-#pragma unroll
-                for (int m = 0; m < 3; ++m) win[idx][m] = win[idx + 4][m];
-            read_window_rows(vt, WR - 4);
-        }
-
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            f32x4_t acc;
-            if (p.do_linear) {
-                const float4 l4 = *reinterpret_cast<const float4*>(lin + ((rr * 64 + ch_dw) * kLinTokPitch + 4 * j));
-                acc[0] = l4.x + bias_dw; acc[1] = l4.y + bias_dw; acc[2] = l4.z + bias_dw; acc[3] = l4.w + bias_dw;
-            } else {
-                acc[0] = acc[1] = acc[2] = acc[3] = bias_dw;
-            }
-            if (p.do_dwconv) {
+    auto consume = [&](const StageCursor& cu, int buf) {
+        const unsigned char* vt = vt_buf(buf);
+        const float* lin = lin_buf(buf);
+        const int col = col_of(cu);
+        const int unit = col / p.strips, xs0 = (col % p.strips) * kStripW;
+        const int head = unit % heads;
+        if (p.do_dwconv) {
+            if (head != cons_head) {  // uniform per block: Toeplitz operands of the new head
+                cons_head = head;
+                const uint2* wf = reinterpret_cast<const uint2*>(wfrag) +
+                                  ((static_cast<size_t>(head) * 4 + c) * KS * 3) * 64 + lane;
 #pragma unroll
                 for (int dy = 0; dy < KS; ++dy)
 #pragma unroll
                     for (int m = 0; m < 3; ++m)
-                        acc = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(tw[dy][m], win[rr + dy][m], acc, 0, 0, 0);
+                        tw[dy][m] = __builtin_bit_cast(s16x4_t, wf[(dy * 3 + m) * 64]);
+                bias_dw = bias ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
             }
+            // slide the window down by four rows and take in the four staged ones
+#pragma unroll
+            for (int idx = 0; idx < WR - 4; ++idx)
+#pragma unroll
+                for (int m = 0; m < 3; ++m) win[idx][m] = win[idx + 4][m];
+            const unsigned char* base = vt + (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int m = 0; m < 3; ++m)
+                    win[WR - 4 + r][m] = __builtin_bit_cast(
+                        s16x4_t, *reinterpret_cast<const uint2*>(base + (r * 6 + m + j) * kVtQuadStride));
+        }
+        if (cu.t < NCH - 1) return;
+
+        const int yo = y0_of(cu) + 4 * (cu.t - (NCH - 1));
+        f32x4_t acc[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            if (p.do_linear) {
+                const float4 l4 = *reinterpret_cast<const float4*>(
+                    lin + ((rr * 64 + ch_dw) * kLinTokPitch + 4 * j));
+                acc[rr][0] = l4.x + bias_dw;
+                acc[rr][1] = l4.y + bias_dw;
+                acc[rr][2] = l4.z + bias_dw;
+                acc[rr][3] = l4.w + bias_dw;
+            } else {
+                acc[rr][0] = acc[rr][1] = acc[rr][2] = acc[rr][3] = bias_dw;
+            }
+        }
+        if (p.do_dwconv) {
+#pragma unroll
+            for (int dy = 0; dy < KS; ++dy)
+#pragma unroll
+                for (int m = 0; m < 3; ++m)
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr)
+                        acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(tw[dy][m], win[rr + dy][m],
+                                                                         acc[rr], 0, 0, 0);
+        }
+        bf16_t* ou = out + static_cast<size_t>(unit) * p.N * D;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
             const int y = yo + rr;
-            if (y < y_end) {
-                bf16_t* o = out + unit_off + (static_cast<size_t>(y) * W + xs0 + 4 * j) * D + ch_dw;
+            if (y < H) {
+                bf16_t* o = ou + (static_cast<size_t>(y) * W + xs0 + 4 * j) * D + ch_dw;
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    if (xs0 + 4 * j + i < W) o[i * D] = f32_to_bf16(acc[i]);
+                    if (xs0 + 4 * j + i < W) o[i * D] = f32_to_bf16(acc[rr][i]);
             }
+        }
+    };
+
+    // ------------------------------------------------------------ pipeline
+    // Producers fill buffer s & 1 with stage s while consumers work on stage s - 1; one
+    // LDS barrier per stage.  The two roles run separate loops (so that neither carries
+    // the other's registers) with the same number of barriers.
+    int n_stages = 0;
+    {
+        StageCursor cu;
+        cu.start(s_begin, s_end, spc);
+        while (!cu.done()) {
+            n_stages += (cu.g_end - cu.g_begin) + NCH - 1;
+            cu.g_begin = cu.g_end;
+            cu.g_end = min(cu.range_end, (cu.g_begin / spc + 1) * spc);
+        }
+    }
+    if (producer) {
+        StageCursor ld, pr;
+        ld.start(s_begin, s_end, spc);
+        pr.start(s_begin, s_end, spc);
+        if (!ld.done()) { issue_loads(std::integral_constant<int, 0>{}, ld); ld.advance(spc, NCH); }
+        if (!ld.done()) { issue_loads(std::integral_constant<int, 1>{}, ld); ld.advance(spc, NCH); }
+        for (int s = 0; s < n_stages; s += 2) {
+            produce(std::integral_constant<int, 0>{}, pr, 0);
+            pr.advance(spc, NCH);
+            if (!ld.done()) { issue_loads(std::integral_constant<int, 0>{}, ld); ld.advance(spc, NCH); }
+            lds_barrier();
+            if (s + 1 >= n_stages) break;
+            produce(std::integral_constant<int, 1>{}, pr, 1);
+            pr.advance(spc, NCH);
+            if (!ld.done()) { issue_loads(std::integral_constant<int, 1>{}, ld); ld.advance(spc, NCH); }
+            lds_barrier();
+        }
+    } else {
+        StageCursor cs;
+        cs.start(s_begin, s_end, spc);
+        if (n_stages > 0) lds_barrier();
+        for (int s = 0; s < n_stages; ++s) {
+            consume(cs, s & 1);
+            cs.advance(spc, NCH);
+            if (s + 1 < n_stages) lds_barrier();
         }
     }
 }

@@ -51,7 +51,7 @@ struct castling_attn {
     int state_size;     // floats per unit
     bool mfma_reduce;   // bf16: K_hat^T V on the matrix cores
     bool mfma_apply;    // bf16, d = 64: q.S and the DWConv on the matrix cores
-    int band_rows;      // rows of the token grid per apply block (MFMA path)
+    int num_cus;        // compute units of the device
     size_t apply_lds;   // dynamic LDS of the apply kernel
     // workspace (one allocation)
     unsigned char* workspace;
@@ -166,7 +166,6 @@ hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* 
     p.grid_h = d.grid_h;
     p.grid_w = d.grid_w;
     p.strips = (d.grid_w + kStripW - 1) / kStripW;
-    p.band_rows = h->band_rows;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
     p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
     p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
@@ -178,11 +177,13 @@ hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* 
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
-    const int bands = (d.grid_h + p.band_rows - 1) / p.band_rows;
-    hipLaunchKernelGGL((apply_mfma_kernel<KS>), dim3(p.strips * bands, h->units), dim3(256),
-                       kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
-                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(bias), h->sfrag,
-                       h->kfrag, h->vhalf, h->wfrag, static_cast<bf16_t*>(out), d.heads, p);
+    // one persistent block per compute unit; every block takes an equal share of the steps
+    const int total_steps = h->units * p.strips * ((d.grid_h + 3) / 4);
+    const int blocks = total_steps < h->num_cus ? total_steps : h->num_cus;
+    hipLaunchKernelGGL((apply_mfma_kernel<KS>), dim3(blocks), dim3(512), kApplyMfmaLdsBytes, s,
+                       static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(v),
+                       static_cast<const bf16_t*>(bias), h->sfrag, h->kfrag, h->vhalf, h->wfrag,
+                       static_cast<bf16_t*>(out), d.heads, total_steps, p);
     return hipGetLastError();
 }
 
@@ -300,15 +301,10 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     const bool allow_mfma = desc->io_dtype == CASTLING_BF16 && !(force && force[0] == '1');
     h->mfma_reduce = allow_mfma;
     h->mfma_apply = allow_mfma && desc->d == 64;
-    h->band_rows = 32;
-    if (const char* br = getenv("CASTLING_ATTN_BAND_ROWS")) {
-        const int v = atoi(br);
-        if (v >= 4 && v % 4 == 0) h->band_rows = v;
-    }
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
     // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
-    int n_split = (kTargetReduceBlocks + h->units - 1) / h->units;
+    int n_split = kTargetReduceBlocks / h->units;  // never one block more than fits at once
     const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;
@@ -319,6 +315,9 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->n_split = (desc->N + chunk - 1) / chunk;
 
     hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess)
+        e = hipDeviceGetAttribute(&h->num_cus, hipDeviceAttributeMultiprocessorCount, h->device);
+    if (e == hipSuccess && h->num_cus < 1) h->num_cus = 1;
     if (e == hipSuccess) e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
     if (e == hipSuccess) {
         int max_lds = 0;

@@ -76,4 +76,21 @@ struct StateLayout {
     static constexpr int SIZE = D * D + 2 * D;
 };
 
+// Sum of `n` partials that lie `stride` floats apart, in index order, with the loads
+// of eight partials in flight at a time (the order of the additions is fixed).
+__device__ __forceinline__ float sum_partials(const float* p, int n, size_t stride)
+{
+    float s = 0.f;
+    int sp = 0;
+    for (; sp + 8 <= n; sp += 8) {
+        float t[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t[u] = p[(sp + u) * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += t[u];
+    }
+    for (; sp < n; ++sp) s += p[sp * stride];
+    return s;
+}
+
 }  // namespace castling

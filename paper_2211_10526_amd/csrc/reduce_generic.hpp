@@ -113,9 +113,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     const int unit = blockIdx.y;
     if (i >= L::SIZE) return;
     const float* p = partial + static_cast<size_t>(unit) * n_split * L::SIZE + i;
-    float s = 0.f;
-    for (int sp = 0; sp < n_split; ++sp) s += p[static_cast<size_t>(sp) * L::SIZE];
-    state[static_cast<size_t>(unit) * L::SIZE + i] = s;
+    state[static_cast<size_t>(unit) * L::SIZE + i] = sum_partials(p, n_split, L::SIZE);
 }
 
 }  // namespace castling
