@@ -18,9 +18,14 @@
 #pragma once
 
 #include <type_traits>
+#include <utility>
 
 #include "common.hpp"
 #include "reduce_mfma.hpp"
+
+#ifndef TRACE_POINT
+#define TRACE_POINT(id)
+#endif
 
 namespace castling {
 
@@ -40,7 +45,9 @@ constexpr int kVtRowStride = 6 * kVtQuadStride;
 constexpr int kVtBytes = 4 * kVtRowStride;
 constexpr int kLinTokPitch = 20;    // floats per (row, channel) line: 16 tokens + pad
 constexpr int kLinBytes = 4 * 64 * kLinTokPitch * 4;
-constexpr int kApplyMfmaLdsBytes = 2 * (kVtBytes + kLinBytes);
+constexpr int kOutTokPitch = 144;   // bytes per token of the output tile: 64 channels + pad
+constexpr int kOutBytes = 64 * kOutTokPitch;
+constexpr int kApplyMfmaLdsBytes = 2 * (kVtBytes + kLinBytes + kOutBytes);
 
 // Fragment tables prepared once per forward (see prepare kernels below):
 //   sfrag [unit][nt 4][ks 2][lane 64] 8 x bf16 : S[i][j] / pi, i = 32 ks + 8 (lane/16) + e, j = 16 nt + lane%16
@@ -132,24 +139,48 @@ struct StageCursor {
     int g_begin, g_end;  // steps [g_begin, g_end) of the current segment
     int t;               // stage inside the segment
     int range_end;       // end of this block's step range
+    int unit, strip;     // strip column of the segment
+    int y0;              // first output row of the segment
 
-    __device__ __forceinline__ void start(int s0, int s1, int spc)
+    // divisions happen here only; the loop advances with adds and compares
+    __device__ __forceinline__ void start(int s0, int s1, int spc, int strips)
     {
         range_end = s1;
         g_begin = s0;
-        g_end = min(s1, (s0 / spc + 1) * spc);
+        const int col = s0 / spc;
+        g_end = min(s1, (col + 1) * spc);
+        unit = col / strips;
+        strip = col - unit * strips;
+        y0 = 4 * (s0 - col * spc);
         t = 0;
     }
     __device__ __forceinline__ bool done() const { return g_begin >= range_end; }
-    __device__ __forceinline__ void advance(int spc, int nch)
+    __device__ __forceinline__ void advance(int spc, int strips, int nch)
     {
-        if (++t == (g_end - g_begin) + nch - 1) {
+        if (++t == (g_end - g_begin) + nch - 1) {  // next segment starts a new strip column
             g_begin = g_end;
-            g_end = min(range_end, (g_begin / spc + 1) * spc);
+            g_end = min(range_end, g_begin + spc);
+            y0 = 0;
             t = 0;
+            if (++strip == strips) {
+                strip = 0;
+                ++unit;
+            }
         }
     }
 };
+
+template <int N, typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>), fully unrolled
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
+}
 
 // LDS-only workgroup barrier: global loads that are still in flight stay in flight.
 __device__ __forceinline__ void lds_barrier()
@@ -159,7 +190,10 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-constexpr int kApplyPrefetch = 2;  // stages whose global loads are in flight
+#ifndef CASTLING_APPLY_PREFETCH
+#define CASTLING_APPLY_PREFETCH 4
+#endif
+constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
 
 // grid = (G), block = 512: waves 0..3 consume (DWConv MFMAs + store), waves 4..7 produce
 // (global loads, V transposition into LDS, linear branch).
@@ -194,17 +228,14 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
     auto lin_buf = [&](int b) {
         return reinterpret_cast<float*>(lds + b * (kVtBytes + kLinBytes) + kVtBytes);
     };
-    // cursor -> coordinates
-    auto col_of = [&](const StageCursor& cu) { return cu.g_begin / spc; };
-    auto y0_of = [&](const StageCursor& cu) { return 4 * (cu.g_begin % spc); };
-
+    auto out_buf = [&](int b) { return lds + 2 * (kVtBytes + kLinBytes) + b * kOutBytes; };
     // ------------------------------------------------------------ consumer state
     const int blk = lane >> 2, j = lane & 3;
     const int ch_dw = 16 * c + blk;
     s16x4_t tw[KS][3];
     s16x4_t win[WR][3];
     float bias_dw = 0.f;
-    int cons_head = -1;
+    int cons_unit = -1;
 #pragma unroll
     for (int a = 0; a < WR; ++a)
 #pragma unroll
@@ -216,6 +247,7 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
 
     // ------------------------------------------------------------ producer state
     const int tl = lane & 15, g = lane >> 4;
+    const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
     bf16x8_t sf[4][2], kf[2];
     float vh[4] = {0.f, 0.f, 0.f, 0.f};
     int prod_unit = -1;
@@ -223,9 +255,8 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
 
     auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
         constexpr int slot = decltype(slot_c)::value;
-        const int col = col_of(cu);
-        const int unit = col / p.strips, xs0 = (col % p.strips) * kStripW;
-        const int y0 = y0_of(cu);
+        const int unit = cu.unit, xs0 = cu.strip * kStripW;
+        const int y0 = cu.y0;
         const size_t unit_off = static_cast<size_t>(unit) * p.N * D;
         const int row_base = y0 - RAD + 4 * cu.t;
         if (p.do_dwconv) {
@@ -276,8 +307,9 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
                 }
             }
         }
+        TRACE_POINT(3);
         if (p.do_linear && cu.t >= NCH - 1) {
-            const int unit = col_of(cu) / p.strips;
+            const int unit = cu.unit;
             if (unit != prod_unit) {  // uniform per block: operand tables of the new unit
                 prod_unit = unit;
                 const uint4* s4 =
@@ -298,16 +330,11 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
             bf16x8_t a[2];
             a[0] = __builtin_bit_cast(bf16x8_t, qreg[slot][0]);
             a[1] = __builtin_bit_cast(bf16x8_t, qreg[slot][1]);
-            float ss = 0.f;
+            // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
+            f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float f = static_cast<float>(a[ks][e]);
-                    ss = fmaf(f, f, ss);
-                }
-            ss += __shfl_xor(ss, 16, 64);
-            ss += __shfl_xor(ss, 32, 64);
+                gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
             f32x4_t acc[4], dk;
 #pragma unroll
             for (int r = 0; r < 4; ++r) dk[r] = 0.f;
@@ -325,15 +352,16 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
             float alpha[4], beta[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                // |q|^2 of token 4 g + r lives in the lanes whose low four bits are that token
+                // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
                 const float ssr = __int_as_float(
-                    __builtin_amdgcn_ds_bpermute((16 * g + 4 * g + r) * 4, __float_as_int(ss)));
-                const float inv = 1.0f / fmaxf(sqrtf(ssr), p.eps);
+                    __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
+                // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
+                const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
                 if (p.norm_none) {
                     alpha[r] = inv;
                     beta[r] = 1.0f;
                 } else {
-                    const float rden = 1.0f / (0.5f * static_cast<float>(p.N) + inv * dk[r]);
+                    const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
                     alpha[r] = inv * rden;
                     beta[r] = rden;
                 }
@@ -353,12 +381,11 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
     auto consume = [&](const StageCursor& cu, int buf) {
         const unsigned char* vt = vt_buf(buf);
         const float* lin = lin_buf(buf);
-        const int col = col_of(cu);
-        const int unit = col / p.strips, xs0 = (col % p.strips) * kStripW;
-        const int head = unit % heads;
+        const int unit = cu.unit;
         if (p.do_dwconv) {
-            if (head != cons_head) {  // uniform per block: Toeplitz operands of the new head
-                cons_head = head;
+            if (unit != cons_unit) {  // uniform per block: Toeplitz operands of the unit's head
+                cons_unit = unit;
+                const int head = unit % heads;
                 const uint2* wf = reinterpret_cast<const uint2*>(wfrag) +
                                   ((static_cast<size_t>(head) * 4 + c) * KS * 3) * 64 + lane;
 #pragma unroll
@@ -381,9 +408,9 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
                     win[WR - 4 + r][m] = __builtin_bit_cast(
                         s16x4_t, *reinterpret_cast<const uint2*>(base + (r * 6 + m + j) * kVtQuadStride));
         }
+        TRACE_POINT(12);
         if (cu.t < NCH - 1) return;
 
-        const int yo = y0_of(cu) + 4 * (cu.t - (NCH - 1));
         f32x4_t acc[4];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
@@ -398,6 +425,7 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
                 acc[rr][0] = acc[rr][1] = acc[rr][2] = acc[rr][3] = bias_dw;
             }
         }
+        TRACE_POINT(13);
         if (p.do_dwconv) {
 #pragma unroll
             for (int dy = 0; dy < KS; ++dy)
@@ -408,16 +436,33 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
                         acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(tw[dy][m], win[rr + dy][m],
                                                                          acc[rr], 0, 0, 0);
         }
+        TRACE_POINT(14);
+        // results go to the LDS output tile [row][token][channel]; the producers store
+        // it with full 128-byte rows one stage later
+        unsigned char* ot = out_buf(buf) + (4 * j) * kOutTokPitch + ch_dw * 2;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<uint16_t*>(ot + (rr * 16 + i) * kOutTokPitch) =
+                    __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[rr][i]));
+    };
+
+    // producers: store the output tile of a finished stage, 16 bytes per lane
+    auto flush = [&](const StageCursor& cu, int buf) {
+        if (cu.t < NCH - 1) return;
+        const int unit = cu.unit, xs0 = cu.strip * kStripW;
+        const int yo = cu.y0 + 4 * (cu.t - (NCH - 1));
         bf16_t* ou = out + static_cast<size_t>(unit) * p.N * D;
+        const unsigned char* ot = out_buf(buf);
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            const int y = yo + rr;
-            if (y < H) {
-                bf16_t* o = ou + (static_cast<size_t>(y) * W + xs0 + 4 * j) * D + ch_dw;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (xs0 + 4 * j + i < W) o[i * D] = f32_to_bf16(acc[rr][i]);
-            }
+        for (int it = 0; it < 2; ++it) {
+            const int item = ptid + 256 * it;
+            const int tok = item >> 3, oct = item & 7;
+            const int y = yo + (tok >> 4), x = xs0 + (tok & 15);
+            const uint4 val = *reinterpret_cast<const uint4*>(ot + tok * kOutTokPitch + oct * 16);
+            if (y < H && x < W)
+                *reinterpret_cast<uint4*>(ou + (static_cast<size_t>(y) * W + x) * D + oct * 8) = val;
         }
     };
 
@@ -428,38 +473,66 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
     int n_stages = 0;
     {
         StageCursor cu;
-        cu.start(s_begin, s_end, spc);
+        cu.start(s_begin, s_end, spc, p.strips);
         while (!cu.done()) {
             n_stages += (cu.g_end - cu.g_begin) + NCH - 1;
             cu.g_begin = cu.g_end;
-            cu.g_end = min(cu.range_end, (cu.g_begin / spc + 1) * spc);
+            cu.g_end = min(cu.range_end, cu.g_begin + spc);
         }
     }
     if (producer) {
-        StageCursor ld, pr;
-        ld.start(s_begin, s_end, spc);
-        pr.start(s_begin, s_end, spc);
-        if (!ld.done()) { issue_loads(std::integral_constant<int, 0>{}, ld); ld.advance(spc, NCH); }
-        if (!ld.done()) { issue_loads(std::integral_constant<int, 1>{}, ld); ld.advance(spc, NCH); }
-        for (int s = 0; s < n_stages; s += 2) {
-            produce(std::integral_constant<int, 0>{}, pr, 0);
-            pr.advance(spc, NCH);
-            if (!ld.done()) { issue_loads(std::integral_constant<int, 0>{}, ld); ld.advance(spc, NCH); }
+        StageCursor ld, pr, fl;
+        ld.start(s_begin, s_end, spc, p.strips);
+        pr.start(s_begin, s_end, spc, p.strips);
+        fl.start(s_begin, s_end, spc, p.strips);
+        static_for<PD>([&](auto slot) {
+            if (!ld.done()) {
+                issue_loads(slot, ld);
+                ld.advance(spc, p.strips, NCH);
+            }
+        });
+        for (int s = 0; s < n_stages; s += PD) {
+            static_for<PD>([&](auto slot) {
+                if (s + decltype(slot)::value < n_stages) {
+                    TRACE_POINT(1);
+                    if (s + decltype(slot)::value >= 2) {  // the tile two stages back is complete
+                        flush(fl, (s + decltype(slot)::value) & 1);
+                        fl.advance(spc, p.strips, NCH);
+                    }
+                    TRACE_POINT(2);
+                    produce(slot, pr, (s + decltype(slot)::value) & 1);
+                    TRACE_POINT(4);
+                    pr.advance(spc, p.strips, NCH);
+                    if (!ld.done()) {  // refill the slot that was just drained
+                        issue_loads(slot, ld);
+                        ld.advance(spc, p.strips, NCH);
+                    }
+                    TRACE_POINT(5);
+                    lds_barrier();
+                    TRACE_POINT(6);
+                }
+            });
+        }
+        // the last two tiles
+        if (n_stages >= 2) {
+            flush(fl, n_stages & 1);
+            fl.advance(spc, p.strips, NCH);
+        }
+        if (n_stages >= 1) {
             lds_barrier();
-            if (s + 1 >= n_stages) break;
-            produce(std::integral_constant<int, 1>{}, pr, 1);
-            pr.advance(spc, NCH);
-            if (!ld.done()) { issue_loads(std::integral_constant<int, 1>{}, ld); ld.advance(spc, NCH); }
-            lds_barrier();
+            flush(fl, (n_stages - 1) & 1);
         }
     } else {
         StageCursor cs;
-        cs.start(s_begin, s_end, spc);
+        cs.start(s_begin, s_end, spc, p.strips);
         if (n_stages > 0) lds_barrier();
         for (int s = 0; s < n_stages; ++s) {
+            TRACE_POINT(11);
             consume(cs, s & 1);
-            cs.advance(spc, NCH);
-            if (s + 1 < n_stages) lds_barrier();
+            TRACE_POINT(15);
+            cs.advance(spc, p.strips, NCH);
+            lds_barrier();
+            TRACE_POINT(16);
         }
     }
 }
