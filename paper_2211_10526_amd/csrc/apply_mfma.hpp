@@ -25,6 +25,8 @@
 
 #ifndef TRACE_POINT
 #define TRACE_POINT(id)
+#define TRACE_DECL
+#define TRACE_DUMP
 #endif
 
 namespace castling {
@@ -135,12 +137,15 @@ __global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* _
 // unit gets the same amount of work whatever the grid shape.  A maximal run of
 // steps inside one strip column is a segment; a segment first primes the DWConv
 // window (NCH - 1 stages that only stage V rows) and then emits one step per stage.
+// After the last stage the cursor stays where it is with live = false: such
+// padding stages move (clamped) data but never produce output.
 struct StageCursor {
     int g_begin, g_end;  // steps [g_begin, g_end) of the current segment
     int t;               // stage inside the segment
     int range_end;       // end of this block's step range
     int unit, strip;     // strip column of the segment
     int y0;              // first output row of the segment
+    bool live;
 
     // divisions happen here only; the loop advances with adds and compares
     __device__ __forceinline__ void start(int s0, int s1, int spc, int strips)
@@ -153,11 +158,17 @@ struct StageCursor {
         strip = col - unit * strips;
         y0 = 4 * (s0 - col * spc);
         t = 0;
+        live = s0 < s1;
     }
-    __device__ __forceinline__ bool done() const { return g_begin >= range_end; }
     __device__ __forceinline__ void advance(int spc, int strips, int nch)
     {
+        if (!live) return;
         if (++t == (g_end - g_begin) + nch - 1) {  // next segment starts a new strip column
+            if (g_end >= range_end) {
+                live = false;
+                --t;
+                return;
+            }
             g_begin = g_end;
             g_end = min(range_end, g_begin + spc);
             y0 = 0;
@@ -168,6 +179,9 @@ struct StageCursor {
             }
         }
     }
+    // first output row of the stage (valid when computes(nch))
+    __device__ __forceinline__ int yo(int nch) const { return y0 + 4 * (t - (nch - 1)); }
+    __device__ __forceinline__ bool computes(int nch) const { return live && t >= nch - 1; }
 };
 
 template <int N, typename F, int... I>
@@ -190,14 +204,40 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Global loads whose completion this code tracks itself.  The compiler's own wait
+// insertion has to assume the worst across the software pipeline's loop (it waits for
+// every load in flight, which serialises the prefetch); these loads are invisible to
+// it and are followed, before the first use of their registers, by wait_async_loads
+// with the number of younger loads that may still be in flight.  Memory operations
+// complete in issue order, and any further operation issued in between only makes
+// the wait stricter, never too weak.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+__device__ __forceinline__ void async_load16(u32x4_t& dst, const void* ptr)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(ptr) : "memory");
+}
+template <int YOUNGER>
+__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t& c)
+{
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(YOUNGER) : "memory");
+}
+template <int YOUNGER>
+__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b)
+{
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(YOUNGER) : "memory");
+}
+
 #ifndef CASTLING_APPLY_PREFETCH
 #define CASTLING_APPLY_PREFETCH 4
 #endif
 constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
 
-// grid = (G), block = 512: waves 0..3 consume (DWConv MFMAs + store), waves 4..7 produce
-// (global loads, V transposition into LDS, linear branch).
-template <int KS>
+// grid = (G), block = 512: waves 0..3 consume (DWConv MFMAs + output tile), waves 4..7
+// produce (global loads, V transposition into LDS, linear branch, output stores).
+template <int KS, bool LIN, bool DW>
 __global__ __launch_bounds__(512) void apply_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ v, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ sfrag, const bf16_t* __restrict__ kfrag,
@@ -209,14 +249,17 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
     constexpr int NCH = (KS + 3 + 3) / 4;  // 4-row chunks that cover the window
     constexpr int WR = 4 * NCH;            // window rows held in registers
     constexpr int PD = kApplyPrefetch;
+    constexpr int LOADS_PER_STAGE = (DW ? 3 : 0) + (LIN ? 2 : 0);
+    constexpr int YOUNGER = (PD - 1) * LOADS_PER_STAGE;  // loads issued after a stage's own
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    TRACE_DECL
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const bool producer = wave >= 4;
-    const int c = wave & 3;    // consumer: channel group; producer: row inside the step
+    const int c = wave & 3;      // consumer: channel group; producer: row inside the step
     const int ptid = tid & 255;  // index among the 256 producer threads
     const int W = p.grid_w, H = p.grid_h;
     const int spc = (H + 3) / 4;  // steps per strip column
@@ -229,304 +272,318 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
         return reinterpret_cast<float*>(lds + b * (kVtBytes + kLinBytes) + kVtBytes);
     };
     auto out_buf = [&](int b) { return lds + 2 * (kVtBytes + kLinBytes) + b * kOutBytes; };
-    // ------------------------------------------------------------ consumer state
-    const int blk = lane >> 2, j = lane & 3;
-    const int ch_dw = 16 * c + blk;
-    s16x4_t tw[KS][3];
-    s16x4_t win[WR][3];
-    float bias_dw = 0.f;
-    int cons_unit = -1;
-#pragma unroll
-    for (int a = 0; a < WR; ++a)
-#pragma unroll
-        for (int m = 0; m < 3; ++m) win[a][m] = s16x4_t{0, 0, 0, 0};
-#pragma unroll
-    for (int a = 0; a < KS; ++a)
-#pragma unroll
-        for (int m = 0; m < 3; ++m) tw[a][m] = s16x4_t{0, 0, 0, 0};
 
-    // ------------------------------------------------------------ producer state
-    const int tl = lane & 15, g = lane >> 4;
-    const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
-    bf16x8_t sf[4][2], kf[2];
-    float vh[4] = {0.f, 0.f, 0.f, 0.f};
-    int prod_unit = -1;
-    uint4 vreg[PD][3], qreg[PD][2];
-
-    auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
-        constexpr int slot = decltype(slot_c)::value;
-        const int unit = cu.unit, xs0 = cu.strip * kStripW;
-        const int y0 = cu.y0;
-        const size_t unit_off = static_cast<size_t>(unit) * p.N * D;
-        const int row_base = y0 - RAD + 4 * cu.t;
-        if (p.do_dwconv) {
-#pragma unroll
-            for (int it = 0; it < 3; ++it) {
-                const int item = ptid + 256 * it;
-                const int r = item / 192, rem = item % 192;
-                const int x = rem >> 3, oct = rem & 7;
-                const int gy = row_base + r, gx = xs0 - 4 + x;
-                vreg[slot][it] = make_uint4(0u, 0u, 0u, 0u);
-                if (gy >= 0 && gy < H && gx >= 0 && gx < W)
-                    vreg[slot][it] = *reinterpret_cast<const uint4*>(
-                        v + unit_off + (static_cast<size_t>(gy) * W + gx) * D + oct * 8);
-            }
-        }
-        if (p.do_linear && cu.t >= NCH - 1) {
-            const int y = y0 + 4 * (cu.t - (NCH - 1)) + c, x = xs0 + tl;
-            qreg[slot][0] = qreg[slot][1] = make_uint4(0u, 0u, 0u, 0u);
-            if (y < H && x < W) {
-                const uint4* src = reinterpret_cast<const uint4*>(
-                    q + unit_off + (static_cast<size_t>(y) * W + x) * D + 8 * g);
-                qreg[slot][0] = src[0];
-                qreg[slot][1] = src[4];
-            }
-        }
-    };
-
-    auto produce = [&](auto slot_c, const StageCursor& cu, int buf) {
-        constexpr int slot = decltype(slot_c)::value;
-        unsigned char* vt = vt_buf(buf);
-        float* lin = lin_buf(buf);
-        if (p.do_dwconv) {
-#pragma unroll
-            for (int it = 0; it < 3; ++it) {
-                const int item = ptid + 256 * it;
-                const int r = item / 192, rem = item % 192;
-                const int x = rem >> 3, oct = rem & 7;
-                unsigned char* dst =
-                    vt + (r * 6 + (x >> 2)) * kVtQuadStride + oct * kVtOctetStride + (x & 3) * 2;
-                const uint32_t wd[4] = {vreg[slot][it].x, vreg[slot][it].y, vreg[slot][it].z,
-                                        vreg[slot][it].w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    *reinterpret_cast<uint16_t*>(dst + (2 * e) * 8) =
-                        static_cast<uint16_t>(wd[e] & 0xffffu);
-                    *reinterpret_cast<uint16_t*>(dst + (2 * e + 1) * 8) =
-                        static_cast<uint16_t>(wd[e] >> 16);
-                }
-            }
-        }
-        TRACE_POINT(3);
-        if (p.do_linear && cu.t >= NCH - 1) {
-            const int unit = cu.unit;
-            if (unit != prod_unit) {  // uniform per block: operand tables of the new unit
-                prod_unit = unit;
-                const uint4* s4 =
-                    reinterpret_cast<const uint4*>(sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
-                const uint4* k4 =
-                    reinterpret_cast<const uint4*>(kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
-                    vh[nt] = vhalf[unit * D + 16 * nt + tl];
-                }
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
-            }
-            bf16x8_t a[2];
-            a[0] = __builtin_bit_cast(bf16x8_t, qreg[slot][0]);
-            a[1] = __builtin_bit_cast(bf16x8_t, qreg[slot][1]);
-            // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
-            f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
-            f32x4_t acc[4], dk;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) dk[r] = 0.f;
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc[nt][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], acc[nt], 0, 0, 0);
-            }
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-                dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
-            float alpha[4], beta[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
-                const float ssr = __int_as_float(
-                    __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
-                // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
-                const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
-                if (p.norm_none) {
-                    alpha[r] = inv;
-                    beta[r] = 1.0f;
-                } else {
-                    const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
-                    alpha[r] = inv * rden;
-                    beta[r] = rden;
-                }
-            }
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                float4 o;
-                o.x = fmaf(alpha[0], acc[nt][0], beta[0] * vh[nt]);
-                o.y = fmaf(alpha[1], acc[nt][1], beta[1] * vh[nt]);
-                o.z = fmaf(alpha[2], acc[nt][2], beta[2] * vh[nt]);
-                o.w = fmaf(alpha[3], acc[nt][3], beta[3] * vh[nt]);
-                *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
-            }
-        }
-    };
-
-    auto consume = [&](const StageCursor& cu, int buf) {
-        const unsigned char* vt = vt_buf(buf);
-        const float* lin = lin_buf(buf);
-        const int unit = cu.unit;
-        if (p.do_dwconv) {
-            if (unit != cons_unit) {  // uniform per block: Toeplitz operands of the unit's head
-                cons_unit = unit;
-                const int head = unit % heads;
-                const uint2* wf = reinterpret_cast<const uint2*>(wfrag) +
-                                  ((static_cast<size_t>(head) * 4 + c) * KS * 3) * 64 + lane;
-#pragma unroll
-                for (int dy = 0; dy < KS; ++dy)
-#pragma unroll
-                    for (int m = 0; m < 3; ++m)
-                        tw[dy][m] = __builtin_bit_cast(s16x4_t, wf[(dy * 3 + m) * 64]);
-                bias_dw = bias ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
-            }
-            // slide the window down by four rows and take in the four staged ones
-#pragma unroll
-            for (int idx = 0; idx < WR - 4; ++idx)
-#pragma unroll
-                for (int m = 0; m < 3; ++m) win[idx][m] = win[idx + 4][m];
-            const unsigned char* base = vt + (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8;
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int m = 0; m < 3; ++m)
-                    win[WR - 4 + r][m] = __builtin_bit_cast(
-                        s16x4_t, *reinterpret_cast<const uint2*>(base + (r * 6 + m + j) * kVtQuadStride));
-        }
-        TRACE_POINT(12);
-        if (cu.t < NCH - 1) return;
-
-        f32x4_t acc[4];
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-            if (p.do_linear) {
-                const float4 l4 = *reinterpret_cast<const float4*>(
-                    lin + ((rr * 64 + ch_dw) * kLinTokPitch + 4 * j));
-                acc[rr][0] = l4.x + bias_dw;
-                acc[rr][1] = l4.y + bias_dw;
-                acc[rr][2] = l4.z + bias_dw;
-                acc[rr][3] = l4.w + bias_dw;
-            } else {
-                acc[rr][0] = acc[rr][1] = acc[rr][2] = acc[rr][3] = bias_dw;
-            }
-        }
-        TRACE_POINT(13);
-        if (p.do_dwconv) {
-#pragma unroll
-            for (int dy = 0; dy < KS; ++dy)
-#pragma unroll
-                for (int m = 0; m < 3; ++m)
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(tw[dy][m], win[rr + dy][m],
-                                                                         acc[rr], 0, 0, 0);
-        }
-        TRACE_POINT(14);
-        // results go to the LDS output tile [row][token][channel]; the producers store
-        // it with full 128-byte rows one stage later
-        unsigned char* ot = out_buf(buf) + (4 * j) * kOutTokPitch + ch_dw * 2;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                *reinterpret_cast<uint16_t*>(ot + (rr * 16 + i) * kOutTokPitch) =
-                    __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[rr][i]));
-    };
-
-    // producers: store the output tile of a finished stage, 16 bytes per lane
-    auto flush = [&](const StageCursor& cu, int buf) {
-        if (cu.t < NCH - 1) return;
-        const int unit = cu.unit, xs0 = cu.strip * kStripW;
-        const int yo = cu.y0 + 4 * (cu.t - (NCH - 1));
-        bf16_t* ou = out + static_cast<size_t>(unit) * p.N * D;
-        const unsigned char* ot = out_buf(buf);
-#pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int item = ptid + 256 * it;
-            const int tok = item >> 3, oct = item & 7;
-            const int y = yo + (tok >> 4), x = xs0 + (tok & 15);
-            const uint4 val = *reinterpret_cast<const uint4*>(ot + tok * kOutTokPitch + oct * 16);
-            if (y < H && x < W)
-                *reinterpret_cast<uint4*>(ou + (static_cast<size_t>(y) * W + x) * D + oct * 8) = val;
-        }
-    };
-
-    // ------------------------------------------------------------ pipeline
-    // Producers fill buffer s & 1 with stage s while consumers work on stage s - 1; one
-    // LDS barrier per stage.  The two roles run separate loops (so that neither carries
-    // the other's registers) with the same number of barriers.
+    // stages of this block, padded to a multiple of the prefetch depth so that the
+    // unrolled software pipeline needs no tail code
     int n_stages = 0;
     {
         StageCursor cu;
         cu.start(s_begin, s_end, spc, p.strips);
-        while (!cu.done()) {
-            n_stages += (cu.g_end - cu.g_begin) + NCH - 1;
-            cu.g_begin = cu.g_end;
-            cu.g_end = min(cu.range_end, cu.g_begin + spc);
+        int gb = cu.g_begin, ge = cu.g_end;
+        while (gb < s_end) {
+            n_stages += (ge - gb) + NCH - 1;
+            gb = ge;
+            ge = min(s_end, gb + spc);
         }
     }
+    const int n_padded = (n_stages + PD - 1) / PD * PD;
+    if (n_stages == 0) return;  // uniform per block; the host never launches such a block
+
     if (producer) {
+        // ======================================================== producer waves
+        const int tl = lane & 15, g = lane >> 4;
+        const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
+        bf16x8_t sf[4][2], kf[2];
+        float vh[4] = {0.f, 0.f, 0.f, 0.f};
+        int prod_unit = -1;
+        u32x4_t vreg[PD][3], qreg[PD][2];
+        uint32_t okmask[PD];  // bit it: V item it lies inside the grid; bit 3: the Q token does
+
+        // this thread's three V items (of 4 rows x 24 columns x 8 octets) and two output items
+        int v_r[3], v_x[3], v_lds[3], v_goff[3];
+#pragma unroll
+        for (int it = 0; it < 3; ++it) {
+            const int item = ptid + 256 * it;
+            const int r = item / 192, rem = item % 192;
+            const int x = rem >> 3, oct = rem & 7;
+            v_r[it] = r;
+            v_x[it] = x - 4;
+            v_goff[it] = oct * 8;
+            v_lds[it] = (r * 6 + (x >> 2)) * kVtQuadStride + oct * kVtOctetStride + (x & 3) * 2;
+        }
+
+        auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
+            constexpr int slot = decltype(slot_c)::value;
+            const int xs0 = cu.strip * kStripW;
+            const size_t unit_off = static_cast<size_t>(cu.unit) * p.N * D;
+            const int row_base = cu.y0 - RAD + 4 * cu.t;
+            uint32_t ok = 0;
+            if constexpr (DW) {
+#pragma unroll
+                for (int it = 0; it < 3; ++it) {
+                    const int gy = row_base + v_r[it], gx = xs0 + v_x[it];
+                    if (gy >= 0 && gy < H && gx >= 0 && gx < W) ok |= 1u << it;
+                    const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), W - 1);
+                    async_load16(vreg[slot][it],
+                                 v + unit_off + (static_cast<size_t>(cy) * W + cx) * D + v_goff[it]);
+                }
+            }
+            if constexpr (LIN) {
+                const int y = cu.yo(NCH) + c, x = xs0 + tl;
+                if (cu.computes(NCH) && y < H && x < W) ok |= 8u;
+                const int cy = min(max(y, 0), H - 1), cx = min(x, W - 1);
+                const bf16_t* src = q + unit_off + (static_cast<size_t>(cy) * W + cx) * D + 8 * g;
+                async_load16(qreg[slot][0], src);
+                async_load16(qreg[slot][1], src + 32);
+            }
+            okmask[slot] = ok;
+        };
+
+        auto produce = [&](auto slot_c, const StageCursor& cu, int buf) {
+            constexpr int slot = decltype(slot_c)::value;
+            unsigned char* vt = vt_buf(buf);
+            float* lin = lin_buf(buf);
+            const uint32_t ok = okmask[slot];
+            if constexpr (DW) {
+                if constexpr (LIN)
+                    wait_async_loads<YOUNGER + 2>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+                else
+                    wait_async_loads<YOUNGER>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+#pragma unroll
+                for (int it = 0; it < 3; ++it) {
+                    unsigned char* dst = vt + v_lds[it];
+                    const bool in = (ok >> it) & 1u;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t wd = in ? vreg[slot][it][e] : 0u;
+                        *reinterpret_cast<uint16_t*>(dst + (2 * e) * 8) = static_cast<uint16_t>(wd & 0xffffu);
+                        *reinterpret_cast<uint16_t*>(dst + (2 * e + 1) * 8) = static_cast<uint16_t>(wd >> 16);
+                    }
+                }
+            }
+            TRACE_POINT(3);
+            if constexpr (LIN) {
+                wait_async_loads<YOUNGER>(qreg[slot][0], qreg[slot][1]);
+                if (cu.computes(NCH)) {
+                    const int unit = cu.unit;
+                    if (unit != prod_unit) {  // uniform per block: operand tables of the new unit
+                        prod_unit = unit;
+                        const uint4* s4 = reinterpret_cast<const uint4*>(
+                            sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
+                        const uint4* k4 = reinterpret_cast<const uint4*>(
+                            kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+                            for (int ks = 0; ks < 2; ++ks)
+                                sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
+                            vh[nt] = vhalf[unit * D + 16 * nt + tl];
+                        }
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks)
+                            kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
+                    }
+                    const bool in = (ok & 8u) != 0;
+                    const u32x4_t zero = {0u, 0u, 0u, 0u};
+                    bf16x8_t a[2];
+                    a[0] = __builtin_bit_cast(bf16x8_t, in ? qreg[slot][0] : zero);
+                    a[1] = __builtin_bit_cast(bf16x8_t, in ? qreg[slot][1] : zero);
+                    // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
+                    f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
+                    f32x4_t acc[4], dk;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) dk[r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[nt][r] = 0.f;
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks)
+                            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], acc[nt], 0, 0, 0);
+                    }
+                    float alpha[4], beta[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
+                        const float ssr = __int_as_float(
+                            __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
+                        // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
+                        const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                        if (p.norm_none) {
+                            alpha[r] = inv;
+                            beta[r] = 1.0f;
+                        } else {
+                            const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
+                            alpha[r] = inv * rden;
+                            beta[r] = rden;
+                        }
+                    }
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) {
+                        float4 o;
+                        o.x = fmaf(alpha[0], acc[nt][0], beta[0] * vh[nt]);
+                        o.y = fmaf(alpha[1], acc[nt][1], beta[1] * vh[nt]);
+                        o.z = fmaf(alpha[2], acc[nt][2], beta[2] * vh[nt]);
+                        o.w = fmaf(alpha[3], acc[nt][3], beta[3] * vh[nt]);
+                        *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
+                    }
+                }
+            }
+        };
+
+        // store the output tile of a finished stage, 16 bytes per lane (full 128-byte rows)
+        auto flush = [&](const StageCursor& cu, int buf) {
+            if (!cu.computes(NCH)) return;
+            const int xs0 = cu.strip * kStripW;
+            const int yo = cu.yo(NCH);
+            bf16_t* ou = out + static_cast<size_t>(cu.unit) * p.N * D;
+            const unsigned char* ot = out_buf(buf);
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int item = ptid + 256 * it;
+                const int tok = item >> 3, oct = item & 7;
+                const int y = yo + (tok >> 4), x = xs0 + (tok & 15);
+                const uint4 val = *reinterpret_cast<const uint4*>(ot + tok * kOutTokPitch + oct * 16);
+                if (y < H && x < W)
+                    *reinterpret_cast<uint4*>(ou + (static_cast<size_t>(y) * W + x) * D + oct * 8) = val;
+            }
+        };
+
         StageCursor ld, pr, fl;
         ld.start(s_begin, s_end, spc, p.strips);
         pr.start(s_begin, s_end, spc, p.strips);
         fl.start(s_begin, s_end, spc, p.strips);
         static_for<PD>([&](auto slot) {
-            if (!ld.done()) {
-                issue_loads(slot, ld);
-                ld.advance(spc, p.strips, NCH);
-            }
+            issue_loads(slot, ld);
+            ld.advance(spc, p.strips, NCH);
         });
-        for (int s = 0; s < n_stages; s += PD) {
+        for (int s = 0; s < n_padded; s += PD) {
             static_for<PD>([&](auto slot) {
-                if (s + decltype(slot)::value < n_stages) {
-                    TRACE_POINT(1);
-                    if (s + decltype(slot)::value >= 2) {  // the tile two stages back is complete
-                        flush(fl, (s + decltype(slot)::value) & 1);
-                        fl.advance(spc, p.strips, NCH);
-                    }
-                    TRACE_POINT(2);
-                    produce(slot, pr, (s + decltype(slot)::value) & 1);
-                    TRACE_POINT(4);
-                    pr.advance(spc, p.strips, NCH);
-                    if (!ld.done()) {  // refill the slot that was just drained
-                        issue_loads(slot, ld);
-                        ld.advance(spc, p.strips, NCH);
-                    }
-                    TRACE_POINT(5);
-                    lds_barrier();
-                    TRACE_POINT(6);
+                constexpr int buf = decltype(slot)::value & 1;  // PD is even
+                TRACE_POINT(1);
+                if (s + decltype(slot)::value >= 2) {  // the tile two stages back is complete
+                    flush(fl, buf);
+                    fl.advance(spc, p.strips, NCH);
                 }
+                TRACE_POINT(2);
+                produce(slot, pr, buf);
+                TRACE_POINT(4);
+                pr.advance(spc, p.strips, NCH);
+                issue_loads(slot, ld);  // refill the slot that was just drained
+                ld.advance(spc, p.strips, NCH);
+                TRACE_POINT(5);
+                lds_barrier();
+                TRACE_POINT(6);
             });
         }
         // the last two tiles
-        if (n_stages >= 2) {
-            flush(fl, n_stages & 1);
+        if (n_padded >= 2) {
+            flush(fl, 0);
             fl.advance(spc, p.strips, NCH);
-        }
-        if (n_stages >= 1) {
             lds_barrier();
-            flush(fl, (n_stages - 1) & 1);
+            flush(fl, 1);
         }
+        // drain the padding loads before the registers die
+        static_for<PD>([&](auto slot) {
+            if constexpr (DW) wait_async_loads<0>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+            if constexpr (LIN) wait_async_loads<0>(qreg[slot][0], qreg[slot][1]);
+        });
     } else {
+        // ======================================================== consumer waves
+        const int blk = lane >> 2, j = lane & 3;
+        const int ch_dw = 16 * c + blk;
+        s16x4_t tw[KS][3];
+        s16x4_t win[WR][3];
+        float bias_dw = 0.f;
+        int cons_unit = -1;
+#pragma unroll
+        for (int a = 0; a < WR; ++a)
+#pragma unroll
+            for (int m = 0; m < 3; ++m) win[a][m] = s16x4_t{0, 0, 0, 0};
+#pragma unroll
+        for (int a = 0; a < KS; ++a)
+#pragma unroll
+            for (int m = 0; m < 3; ++m) tw[a][m] = s16x4_t{0, 0, 0, 0};
+
+        auto consume = [&](const StageCursor& cu, int buf) {
+            const unsigned char* vt = vt_buf(buf);
+            const float* lin = lin_buf(buf);
+            if constexpr (DW) {
+                if (cu.unit != cons_unit) {  // uniform per block: Toeplitz operands of the unit's head
+                    cons_unit = cu.unit;
+                    const int head = cu.unit % heads;
+                    const uint2* wf = reinterpret_cast<const uint2*>(wfrag) +
+                                      ((static_cast<size_t>(head) * 4 + c) * KS * 3) * 64 + lane;
+#pragma unroll
+                    for (int dy = 0; dy < KS; ++dy)
+#pragma unroll
+                        for (int m = 0; m < 3; ++m)
+                            tw[dy][m] = __builtin_bit_cast(s16x4_t, wf[(dy * 3 + m) * 64]);
+                    bias_dw = bias ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
+                }
+                // slide the window down by four rows and take in the four staged ones
+#pragma unroll
+                for (int idx = 0; idx < WR - 4; ++idx)
+#pragma unroll
+                    for (int m = 0; m < 3; ++m) win[idx][m] = win[idx + 4][m];
+                const unsigned char* base = vt + (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int m = 0; m < 3; ++m)
+                        win[WR - 4 + r][m] = __builtin_bit_cast(
+                            s16x4_t, *reinterpret_cast<const uint2*>(base + (r * 6 + m + j) * kVtQuadStride));
+            }
+            TRACE_POINT(12);
+            if (!cu.computes(NCH)) return;
+
+            f32x4_t acc[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                if constexpr (LIN) {
+                    const float4 l4 = *reinterpret_cast<const float4*>(
+                        lin + ((rr * 64 + ch_dw) * kLinTokPitch + 4 * j));
+                    acc[rr][0] = l4.x + bias_dw;
+                    acc[rr][1] = l4.y + bias_dw;
+                    acc[rr][2] = l4.z + bias_dw;
+                    acc[rr][3] = l4.w + bias_dw;
+                } else {
+                    acc[rr][0] = acc[rr][1] = acc[rr][2] = acc[rr][3] = bias_dw;
+                }
+            }
+            TRACE_POINT(13);
+            if constexpr (DW) {
+#pragma unroll
+                for (int dy = 0; dy < KS; ++dy)
+#pragma unroll
+                    for (int m = 0; m < 3; ++m)
+#pragma unroll
+                        for (int rr = 0; rr < 4; ++rr)
+                            acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(tw[dy][m], win[rr + dy][m],
+                                                                             acc[rr], 0, 0, 0);
+            }
+            TRACE_POINT(14);
+            // results go to the LDS output tile [row][token][channel]; the producers store
+            // it with full 128-byte rows one stage later
+            unsigned char* ot = out_buf(buf) + (4 * j) * kOutTokPitch + ch_dw * 2;
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    *reinterpret_cast<uint16_t*>(ot + (rr * 16 + i) * kOutTokPitch) =
+                        __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[rr][i]));
+        };
+
         StageCursor cs;
         cs.start(s_begin, s_end, spc, p.strips);
-        if (n_stages > 0) lds_barrier();
-        for (int s = 0; s < n_stages; ++s) {
+        if (n_padded > 0) lds_barrier();
+        for (int s = 0; s < n_padded; ++s) {
             TRACE_POINT(11);
             consume(cs, s & 1);
             TRACE_POINT(15);
@@ -535,6 +592,7 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
             TRACE_POINT(16);
         }
     }
+    TRACE_DUMP
 }
 
 }  // namespace castling

@@ -151,13 +151,13 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     return hipGetLastError();
 }
 
-template <int KS>
-hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
-                      const void* bias, void* out, hipStream_t s)
+template <int KS, bool LIN, bool DW>
+hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, const void* v,
+                               const void* w, const void* bias, void* out, hipStream_t s)
 {
     if (!launch) {
         h->apply_lds = kApplyMfmaLdsBytes;
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma_kernel<KS>),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma_kernel<KS, LIN, DW>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kApplyMfmaLdsBytes);
     }
     const castling_attn_desc_t& d = h->desc;
@@ -167,10 +167,10 @@ hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* 
     p.grid_w = d.grid_w;
     p.strips = (d.grid_w + kStripW - 1) / kStripW;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
-    p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    p.do_linear = LIN;
+    p.do_dwconv = DW;
     p.eps = d.eps;
-    if (p.do_dwconv) {
+    if (DW) {
         const int threads = d.heads * 4 * KS * 3 * 64;
         hipLaunchKernelGGL((dwconv_weight_frag_kernel<KS>), dim3((threads + 255) / 256), dim3(256),
                            0, s, static_cast<const bf16_t*>(w), h->wfrag, d.heads);
@@ -180,11 +180,23 @@ hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* 
     // one persistent block per compute unit; every block takes an equal share of the steps
     const int total_steps = h->units * p.strips * ((d.grid_h + 3) / 4);
     const int blocks = total_steps < h->num_cus ? total_steps : h->num_cus;
-    hipLaunchKernelGGL((apply_mfma_kernel<KS>), dim3(blocks), dim3(512), kApplyMfmaLdsBytes, s,
-                       static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(v),
-                       static_cast<const bf16_t*>(bias), h->sfrag, h->kfrag, h->vhalf, h->wfrag,
-                       static_cast<bf16_t*>(out), d.heads, total_steps, p);
+    hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW>), dim3(blocks), dim3(512),
+                       kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
+                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(bias), h->sfrag,
+                       h->kfrag, h->vhalf, h->wfrag, static_cast<bf16_t*>(out), d.heads,
+                       total_steps, p);
     return hipGetLastError();
+}
+
+template <int KS>
+hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
+                      const void* bias, void* out, hipStream_t s)
+{
+    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
+    if (lin && dw) return apply_mfma_branches<KS, true, true>(h, launch, q, v, w, bias, out, s);
+    if (lin) return apply_mfma_branches<KS, true, false>(h, launch, q, v, w, bias, out, s);
+    return apply_mfma_branches<KS, false, true>(h, launch, q, v, w, bias, out, s);
 }
 
 template <typename T, int D>
