@@ -10,11 +10,16 @@
 //       of one channel.  The linear branch enters as the C operand, so the sum of
 //       Eq. 9 costs nothing.
 //
-// A block owns a strip of 16 grid columns x R rows of one (batch, head) unit.
-// Wave c owns channels 16c..16c+15 for the DWConv and row (4s + c) of every
-// 4-row step for the linear branch.  V rows enter LDS once, transposed to
-// [quad][channel][4 tokens]; every wave keeps a sliding window of MFMA operands
-// in registers, so each staged row is read from LDS once per wave.
+// Work unit: a strip of 16 grid columns of one (batch, head) unit, four output rows per
+// stage, walked top to bottom by a persistent block (one per compute unit).
+// A block has twelve waves, three per SIMD:
+//   waves 0..7   consumers: wave (c, h) owns channels 16c..16c+15 and output rows 2h, 2h+1 of
+//                every stage; it keeps a sliding window of DWConv operands in registers and
+//                feeds the 4x4x4 MFMAs, then writes its results to an LDS output tile;
+//   waves 8..11  producers: asynchronous global loads (several stages ahead), transposition of
+//                the V rows into the MFMA operand order (transposing LDS reads), the linear
+//                branch for row p of the stage, and the coalesced stores of finished tiles.
+// Producers and consumers meet at one LDS-only barrier per stage.
 #pragma once
 
 #include <type_traits>
@@ -41,15 +46,25 @@ struct ApplyMfmaParams {
 };
 
 constexpr int kStripW = 16;
-constexpr int kVtQuadStride = 672;  // bytes per (row, quad) line: 8 octets * 80 B + pad
-constexpr int kVtOctetStride = 80;  // 8 channels * 8 B + pad
+// V operand tile of one stage: [row 4][quad 6][channel 64] units of 8 bytes (4 consecutive
+// tokens of one channel); octets of channels are 80 bytes apart, quads 672 (bank spread)
+constexpr int kVtQuadStride = 672;
+constexpr int kVtOctetStride = 80;
 constexpr int kVtRowStride = 6 * kVtQuadStride;
 constexpr int kVtBytes = 4 * kVtRowStride;
-constexpr int kLinTokPitch = 20;    // floats per (row, channel) line: 16 tokens + pad
+constexpr int kVtBuffers = 3;        // consumers also read the previous stage's rows
+// linear-branch tile of one stage: [row 4][channel 64][token 16 + pad] fp32
+constexpr int kLinTokPitch = 20;
 constexpr int kLinBytes = 4 * 64 * kLinTokPitch * 4;
-constexpr int kOutTokPitch = 144;   // bytes per token of the output tile: 64 channels + pad
-constexpr int kOutBytes = 64 * kOutTokPitch;
-constexpr int kApplyMfmaLdsBytes = 2 * (kVtBytes + kLinBytes + kOutBytes);
+// output tile of one stage: [row 4][channel 64][token 16 + pad] bf16
+constexpr int kOutTokPitch = 20;
+constexpr int kOutBytes = 4 * 64 * kOutTokPitch * 2;
+// per producer wave: 8 tokens x 64 channels in global (token-major) order, 144 bytes a token
+constexpr int kNatTokPitch = 144;
+constexpr int kNatBytes = 8 * kNatTokPitch;
+constexpr int kApplyWaves = 12;
+constexpr int kApplyMfmaLdsBytes =
+    kVtBuffers * kVtBytes + 2 * kLinBytes + 2 * kOutBytes + 4 * kNatBytes;
 
 // Fragment tables prepared once per forward (see prepare kernels below):
 //   sfrag [unit][nt 4][ks 2][lane 64] 8 x bf16 : S[i][j] / pi, i = 32 ks + 8 (lane/16) + e, j = 16 nt + lane%16
@@ -208,14 +223,15 @@ __device__ __forceinline__ void lds_barrier()
 // insertion has to assume the worst across the software pipeline's loop (it waits for
 // every load in flight, which serialises the prefetch); these loads are invisible to
 // it and are followed, before the first use of their registers, by wait_async_loads
-// with the number of younger loads that may still be in flight.  Memory operations
-// complete in issue order, and any further operation issued in between only makes
-// the wait stricter, never too weak.
+// with the number of younger loads that may still be in flight.  Loads complete in
+// issue order, and any further memory operation issued in between only makes the
+// wait stricter, never too weak.
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-__device__ __forceinline__ void async_load16(u32x4_t& dst, const void* ptr)
+// base: wave-uniform pointer (scalar registers), offset: per-lane byte offset
+__device__ __forceinline__ void async_load16(u32x4_t& dst, const void* base, uint32_t offset)
 {
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(ptr) : "memory");
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(offset), "s"(base) : "memory");
 }
 template <int YOUNGER>
 __device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t& c)
@@ -230,15 +246,28 @@ __device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b)
     asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(YOUNGER) : "memory");
 }
 
+// 8-byte transposing LDS read (see lds_operand_tr in reduce_mfma.hpp for the lane roles)
+__device__ __forceinline__ uint2 lds_read_tr8(const unsigned char* addr)
+{
+    typedef s16x4_t __attribute__((address_space(3))) * lds_ptr_t;
+    const s16x4_t r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr_t)(addr));
+    return __builtin_bit_cast(uint2, r);
+}
+
 #ifndef CASTLING_APPLY_PREFETCH
 #define CASTLING_APPLY_PREFETCH 4
 #endif
 constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
 
-// grid = (G), block = 512: waves 0..3 consume (DWConv MFMAs + output tile), waves 4..7
-// produce (global loads, V transposition into LDS, linear branch, output stores).
+// what a producer needs to know about a stage after its cursor has moved on
+struct StageSnap {
+    int unit, xs0, yo;
+    bool computes;
+};
+
+// grid = (G), block = 64 * kApplyWaves.
 template <int KS, bool LIN, bool DW>
-__global__ __launch_bounds__(512) void apply_mfma_kernel(
+__global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ v, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ sfrag, const bf16_t* __restrict__ kfrag,
     const float* __restrict__ vhalf, const bf16_t* __restrict__ wfrag, bf16_t* __restrict__ out,
@@ -246,9 +275,12 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
 {
     constexpr int D = 64;
     constexpr int RAD = KS / 2;
-    constexpr int NCH = (KS + 3 + 3) / 4;  // 4-row chunks that cover the window
-    constexpr int WR = 4 * NCH;            // window rows held in registers
+    constexpr int NCH = (KS + 3 + 3) / 4;        // stages until a segment's first output
+    constexpr int A0 = 4 * (NCH - 1) - RAD;      // first staged row of a stage, relative to yo
+    constexpr int WL = KS + 1 > 4 ? KS + 1 : 4;  // window rows a consumer wave holds
+    constexpr int WOFF = WL - KS - 1;            // window index of input row (yo + 2h - RAD)
     constexpr int PD = kApplyPrefetch;
+    static_assert(PD % 2 == 0, "the two-deep LDS rings assume an even prefetch depth");
     constexpr int LOADS_PER_STAGE = (DW ? 3 : 0) + (LIN ? 2 : 0);
     constexpr int YOUNGER = (PD - 1) * LOADS_PER_STAGE;  // loads issued after a stage's own
 
@@ -257,21 +289,21 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const bool producer = wave >= 4;
-    const int c = wave & 3;      // consumer: channel group; producer: row inside the step
-    const int ptid = tid & 255;  // index among the 256 producer threads
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool producer = wave >= 8;
+    const int c = wave & 3;       // consumer: channel group; producer: row inside the stage
+    const int half = (wave >> 2) & 1;  // consumer: output rows 2*half, 2*half+1 of the stage
+    const int ptid = tid & 255;   // index among the 256 producer threads
     const int W = p.grid_w, H = p.grid_h;
     const int spc = (H + 3) / 4;  // steps per strip column
 
     const int s_begin = static_cast<int>(static_cast<long long>(blockIdx.x) * total_steps / gridDim.x);
     const int s_end = static_cast<int>(static_cast<long long>(blockIdx.x + 1) * total_steps / gridDim.x);
 
-    auto vt_buf = [&](int b) { return lds + b * (kVtBytes + kLinBytes); };
-    auto lin_buf = [&](int b) {
-        return reinterpret_cast<float*>(lds + b * (kVtBytes + kLinBytes) + kVtBytes);
-    };
-    auto out_buf = [&](int b) { return lds + 2 * (kVtBytes + kLinBytes) + b * kOutBytes; };
+    unsigned char* const vt_base = lds;
+    unsigned char* const lin_base = lds + kVtBuffers * kVtBytes;
+    unsigned char* const out_base = lin_base + 2 * kLinBytes;
+    unsigned char* const nat_base = out_base + 2 * kOutBytes;
 
     // stages of this block, padded to a multiple of the prefetch depth so that the
     // unrolled software pipeline needs no tail code
@@ -298,19 +330,29 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
         int prod_unit = -1;
         u32x4_t vreg[PD][3], qreg[PD][2];
         uint32_t okmask[PD];  // bit it: V item it lies inside the grid; bit 3: the Q token does
+        StageSnap snap[PD];   // stage held by each register slot
+        StageSnap fsnap[2];   // stages whose output tiles wait to be stored
 
-        // this thread's three V items (of 4 rows x 24 columns x 8 octets) and two output items
-        int v_r[3], v_x[3], v_lds[3], v_goff[3];
+        // this thread's three V items (of 4 rows x 24 columns x 8 octets): a wave covers,
+        // per item, 8 consecutive columns (two quads) of one row with all 64 channels
+        int v_r[3], v_x[3];
 #pragma unroll
         for (int it = 0; it < 3; ++it) {
             const int item = ptid + 256 * it;
-            const int r = item / 192, rem = item % 192;
-            const int x = rem >> 3, oct = rem & 7;
-            v_r[it] = r;
-            v_x[it] = x - 4;
-            v_goff[it] = oct * 8;
-            v_lds[it] = (r * 6 + (x >> 2)) * kVtQuadStride + oct * kVtOctetStride + (x & 3) * 2;
+            v_r[it] = item / 192;
+            v_x[it] = ((item % 192) >> 3) - 4;
         }
+        const int v_oct = lane & 7;
+        unsigned char* const nat = nat_base + c * kNatBytes;
+        // transposition roles: natural write (token lane/8, octet lane%8); transposing read
+        // source (token 4 qd + (lane/4)%4, channels 16 (lane/16) + 4 (lane%4)..+3); afterwards
+        // lane l holds channel l, 4 tokens of quad qd
+        unsigned char* const nat_wr = nat + (lane >> 3) * kNatTokPitch + v_oct * 16;
+        const unsigned char* const nat_rd =
+            nat + ((lane >> 2) & 3) * kNatTokPitch + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
+        const int vt_lane = (lane >> 3) * kVtOctetStride + (lane & 7) * 8;
+        // output-tile roles: 16 lanes store one (row, octet) pair; lane%16 is the token
+        const int fl_e = (lane >> 2) & 3, fl_p = lane & 3;
 
         auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
             constexpr int slot = decltype(slot_c)::value;
@@ -319,53 +361,61 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
             const int row_base = cu.y0 - RAD + 4 * cu.t;
             uint32_t ok = 0;
             if constexpr (DW) {
+                const bf16_t* vb = v + unit_off;
 #pragma unroll
                 for (int it = 0; it < 3; ++it) {
                     const int gy = row_base + v_r[it], gx = xs0 + v_x[it];
                     if (gy >= 0 && gy < H && gx >= 0 && gx < W) ok |= 1u << it;
                     const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), W - 1);
-                    async_load16(vreg[slot][it],
-                                 v + unit_off + (static_cast<size_t>(cy) * W + cx) * D + v_goff[it]);
+                    async_load16(vreg[slot][it], vb,
+                                 static_cast<uint32_t>((cy * W + cx) * (D * 2) + v_oct * 16));
                 }
             }
             if constexpr (LIN) {
                 const int y = cu.yo(NCH) + c, x = xs0 + tl;
                 if (cu.computes(NCH) && y < H && x < W) ok |= 8u;
                 const int cy = min(max(y, 0), H - 1), cx = min(x, W - 1);
-                const bf16_t* src = q + unit_off + (static_cast<size_t>(cy) * W + cx) * D + 8 * g;
-                async_load16(qreg[slot][0], src);
-                async_load16(qreg[slot][1], src + 32);
+                const uint32_t off = static_cast<uint32_t>((cy * W + cx) * (D * 2) + g * 16);
+                const bf16_t* qb = q + unit_off;
+                async_load16(qreg[slot][0], qb, off);
+                async_load16(qreg[slot][1], qb, off + 64);
             }
             okmask[slot] = ok;
+            snap[slot].unit = cu.unit;
+            snap[slot].xs0 = xs0;
+            snap[slot].yo = cu.yo(NCH);
+            snap[slot].computes = cu.computes(NCH);
         };
 
-        auto produce = [&](auto slot_c, const StageCursor& cu, int buf) {
+        auto produce = [&](auto slot_c, unsigned char* vt, float* lin) {
             constexpr int slot = decltype(slot_c)::value;
-            unsigned char* vt = vt_buf(buf);
-            float* lin = lin_buf(buf);
             const uint32_t ok = okmask[slot];
             if constexpr (DW) {
-                if constexpr (LIN)
-                    wait_async_loads<YOUNGER + 2>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
-                else
-                    wait_async_loads<YOUNGER>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+                wait_async_loads<YOUNGER + (LIN ? 2 : 0)>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
 #pragma unroll
                 for (int it = 0; it < 3; ++it) {
-                    unsigned char* dst = vt + v_lds[it];
-                    const bool in = (ok >> it) & 1u;
+                    const u32x4_t zero = {0u, 0u, 0u, 0u};
+                    const u32x4_t val = ((ok >> it) & 1u) ? vreg[slot][it] : zero;
+                    // token-major staging, private to this wave; LDS operations of one wave
+                    // complete in issue order, so no barrier is needed around it
+                    *reinterpret_cast<u32x4_t*>(nat_wr) = val;
+                    __builtin_amdgcn_wave_barrier();
+                    const int item0 = (wave - 8) * 64 + 256 * it;  // first item of this wave
+                    const int r = item0 / 192, x0 = (item0 % 192) >> 3;
+                    unsigned char* dst = vt + (r * 6 + (x0 >> 2)) * kVtQuadStride + vt_lane;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const uint32_t wd = in ? vreg[slot][it][e] : 0u;
-                        *reinterpret_cast<uint16_t*>(dst + (2 * e) * 8) = static_cast<uint16_t>(wd & 0xffffu);
-                        *reinterpret_cast<uint16_t*>(dst + (2 * e + 1) * 8) = static_cast<uint16_t>(wd >> 16);
+                    for (int qd = 0; qd < 2; ++qd) {
+                        const uint2 u = lds_read_tr8(nat_rd + qd * 4 * kNatTokPitch);
+                        *reinterpret_cast<uint2*>(dst + qd * kVtQuadStride) = u;
                     }
+                    __builtin_amdgcn_wave_barrier();
                 }
             }
             TRACE_POINT(3);
             if constexpr (LIN) {
                 wait_async_loads<YOUNGER>(qreg[slot][0], qreg[slot][1]);
-                if (cu.computes(NCH)) {
-                    const int unit = cu.unit;
+                if (snap[slot].computes) {
+                    const int unit = snap[slot].unit;
                     if (unit != prod_unit) {  // uniform per block: operand tables of the new unit
                         prod_unit = unit;
                         const uint4* s4 = reinterpret_cast<const uint4*>(
@@ -437,44 +487,43 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
             }
         };
 
-        // store the output tile of a finished stage, 16 bytes per lane (full 128-byte rows)
-        auto flush = [&](const StageCursor& cu, int buf) {
-            if (!cu.computes(NCH)) return;
-            const int xs0 = cu.strip * kStripW;
-            const int yo = cu.yo(NCH);
-            bf16_t* ou = out + static_cast<size_t>(cu.unit) * p.N * D;
-            const unsigned char* ot = out_buf(buf);
+        // store the output tile of a finished stage: a transposing read turns the
+        // [channel][token] tile into 8 channels of one token per lane (16 bytes)
+        auto flush = [&](const StageSnap& sn, const unsigned char* ot) {
+            if (!sn.computes) return;
+            unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(sn.unit) * p.N * D);
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
-                const int item = ptid + 256 * it;
-                const int tok = item >> 3, oct = item & 7;
-                const int y = yo + (tok >> 4), x = xs0 + (tok & 15);
-                const uint4 val = *reinterpret_cast<const uint4*>(ot + tok * kOutTokPitch + oct * 16);
+                const int pair = (ptid >> 4) + 16 * it;  // (row, octet) pair of this 16-lane group
+                const int row = pair >> 3, oct = pair & 7;
+                const unsigned char* src = ot + ((row * 64 + 8 * oct + fl_e) * kOutTokPitch + 4 * fl_p) * 2;
+                const uint2 lo = lds_read_tr8(src);
+                const uint2 hi = lds_read_tr8(src + 4 * kOutTokPitch * 2);
+                const int y = sn.yo + row, x = sn.xs0 + tl;
                 if (y < H && x < W)
-                    *reinterpret_cast<uint4*>(ou + (static_cast<size_t>(y) * W + x) * D + oct * 8) = val;
+                    *reinterpret_cast<uint4*>(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + oct * 16)) =
+                        make_uint4(lo.x, lo.y, hi.x, hi.y);
             }
         };
 
-        StageCursor ld, pr, fl;
+        StageCursor ld;
         ld.start(s_begin, s_end, spc, p.strips);
-        pr.start(s_begin, s_end, spc, p.strips);
-        fl.start(s_begin, s_end, spc, p.strips);
         static_for<PD>([&](auto slot) {
             issue_loads(slot, ld);
             ld.advance(spc, p.strips, NCH);
         });
+        fsnap[0].computes = fsnap[1].computes = false;
+        int vt_i = 0;  // V ring index of the stage being produced
         for (int s = 0; s < n_padded; s += PD) {
             static_for<PD>([&](auto slot) {
-                constexpr int buf = decltype(slot)::value & 1;  // PD is even
+                constexpr int b2 = decltype(slot)::value & 1;
                 TRACE_POINT(1);
-                if (s + decltype(slot)::value >= 2) {  // the tile two stages back is complete
-                    flush(fl, buf);
-                    fl.advance(spc, p.strips, NCH);
-                }
+                flush(fsnap[b2], out_base + b2 * kOutBytes);  // the tile two stages back is complete
+                fsnap[b2] = snap[decltype(slot)::value];
                 TRACE_POINT(2);
-                produce(slot, pr, buf);
+                produce(slot, vt_base + vt_i * kVtBytes, reinterpret_cast<float*>(lin_base + b2 * kLinBytes));
+                vt_i = vt_i == kVtBuffers - 1 ? 0 : vt_i + 1;
                 TRACE_POINT(4);
-                pr.advance(spc, p.strips, NCH);
                 issue_loads(slot, ld);  // refill the slot that was just drained
                 ld.advance(spc, p.strips, NCH);
                 TRACE_POINT(5);
@@ -483,12 +532,9 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
             });
         }
         // the last two tiles
-        if (n_padded >= 2) {
-            flush(fl, 0);
-            fl.advance(spc, p.strips, NCH);
-            lds_barrier();
-            flush(fl, 1);
-        }
+        flush(fsnap[0], out_base);
+        lds_barrier();
+        flush(fsnap[1], out_base + kOutBytes);
         // drain the padding loads before the registers die
         static_for<PD>([&](auto slot) {
             if constexpr (DW) wait_async_loads<0>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
@@ -499,21 +545,24 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
         const int blk = lane >> 2, j = lane & 3;
         const int ch_dw = 16 * c + blk;
         s16x4_t tw[KS][3];
-        s16x4_t win[WR][3];
+        s16x4_t win[WL][3];
         float bias_dw = 0.f;
         int cons_unit = -1;
 #pragma unroll
-        for (int a = 0; a < WR; ++a)
+        for (int a = 0; a < WL; ++a)
 #pragma unroll
             for (int m = 0; m < 3; ++m) win[a][m] = s16x4_t{0, 0, 0, 0};
 #pragma unroll
         for (int a = 0; a < KS; ++a)
 #pragma unroll
             for (int m = 0; m < 3; ++m) tw[a][m] = s16x4_t{0, 0, 0, 0};
+        // this wave's four new window rows are staged rows rel0..rel0+3 of the stage
+        // (negative: rows of the previous stage's buffer)
+        const int rel0 = 2 * half + RAD - 2 - A0;
+        const int vt_lane = (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8 + j * kVtQuadStride;
 
-        auto consume = [&](const StageCursor& cu, int buf) {
-            const unsigned char* vt = vt_buf(buf);
-            const float* lin = lin_buf(buf);
+        auto consume = [&](const StageCursor& cu, const unsigned char* vt_cur,
+                           const unsigned char* vt_prev, const float* lin, unsigned char* ot) {
             if constexpr (DW) {
                 if (cu.unit != cons_unit) {  // uniform per block: Toeplitz operands of the unit's head
                     cons_unit = cu.unit;
@@ -527,28 +576,31 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
                             tw[dy][m] = __builtin_bit_cast(s16x4_t, wf[(dy * 3 + m) * 64]);
                     bias_dw = bias ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
                 }
-                // slide the window down by four rows and take in the four staged ones
+                // slide the window down by four rows and take in this wave's four new ones
 #pragma unroll
-                for (int idx = 0; idx < WR - 4; ++idx)
+                for (int idx = 0; idx + 4 < WL; ++idx)
 #pragma unroll
                     for (int m = 0; m < 3; ++m) win[idx][m] = win[idx + 4][m];
-                const unsigned char* base = vt + (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
+                for (int r = 0; r < 4; ++r) {
+                    const int rel = rel0 + r;
+                    const unsigned char* rowp =
+                        (rel < 0 ? vt_prev : vt_cur) + (rel & 3) * kVtRowStride + vt_lane;
 #pragma unroll
                     for (int m = 0; m < 3; ++m)
-                        win[WR - 4 + r][m] = __builtin_bit_cast(
-                            s16x4_t, *reinterpret_cast<const uint2*>(base + (r * 6 + m + j) * kVtQuadStride));
+                        win[WL - 4 + r][m] = __builtin_bit_cast(
+                            s16x4_t, *reinterpret_cast<const uint2*>(rowp + m * kVtQuadStride));
+                }
             }
             TRACE_POINT(12);
             if (!cu.computes(NCH)) return;
 
-            f32x4_t acc[4];
+            f32x4_t acc[2];
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
+            for (int rr = 0; rr < 2; ++rr) {
                 if constexpr (LIN) {
                     const float4 l4 = *reinterpret_cast<const float4*>(
-                        lin + ((rr * 64 + ch_dw) * kLinTokPitch + 4 * j));
+                        lin + (((2 * half + rr) * 64 + ch_dw) * kLinTokPitch + 4 * j));
                     acc[rr][0] = l4.x + bias_dw;
                     acc[rr][1] = l4.y + bias_dw;
                     acc[rr][2] = l4.z + bias_dw;
@@ -564,30 +616,34 @@ __global__ __launch_bounds__(512) void apply_mfma_kernel(
 #pragma unroll
                     for (int m = 0; m < 3; ++m)
 #pragma unroll
-                        for (int rr = 0; rr < 4; ++rr)
-                            acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(tw[dy][m], win[rr + dy][m],
-                                                                             acc[rr], 0, 0, 0);
+                        for (int rr = 0; rr < 2; ++rr)
+                            acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(
+                                tw[dy][m], win[rr + dy + WOFF][m], acc[rr], 0, 0, 0);
             }
             TRACE_POINT(14);
-            // results go to the LDS output tile [row][token][channel]; the producers store
-            // it with full 128-byte rows one stage later
-            unsigned char* ot = out_buf(buf) + (4 * j) * kOutTokPitch + ch_dw * 2;
+            // results go to the LDS output tile [row][channel][token]
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    *reinterpret_cast<uint16_t*>(ot + (rr * 16 + i) * kOutTokPitch) =
-                        __builtin_bit_cast(uint16_t, static_cast<__bf16>(acc[rr][i]));
+            for (int rr = 0; rr < 2; ++rr) {
+                uint2 o;
+                o.x = pack_bf16x2(acc[rr][0], acc[rr][1]);
+                o.y = pack_bf16x2(acc[rr][2], acc[rr][3]);
+                *reinterpret_cast<uint2*>(ot + (((2 * half + rr) * 64 + ch_dw) * kOutTokPitch + 4 * j) * 2) = o;
+            }
         };
 
         StageCursor cs;
         cs.start(s_begin, s_end, spc, p.strips);
-        if (n_padded > 0) lds_barrier();
+        int vt_i = 0, vt_p = kVtBuffers - 1;
+        lds_barrier();
         for (int s = 0; s < n_padded; ++s) {
             TRACE_POINT(11);
-            consume(cs, s & 1);
+            consume(cs, vt_base + vt_i * kVtBytes, vt_base + vt_p * kVtBytes,
+                    reinterpret_cast<const float*>(lin_base + (s & 1) * kLinBytes),
+                    out_base + (s & 1) * kOutBytes);
             TRACE_POINT(15);
             cs.advance(spc, p.strips, NCH);
+            vt_p = vt_i;
+            vt_i = vt_i == kVtBuffers - 1 ? 0 : vt_i + 1;
             lds_barrier();
             TRACE_POINT(16);
         }

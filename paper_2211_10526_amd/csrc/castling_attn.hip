@@ -180,7 +180,7 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     // one persistent block per compute unit; every block takes an equal share of the steps
     const int total_steps = h->units * p.strips * ((d.grid_h + 3) / 4);
     const int blocks = total_steps < h->num_cus ? total_steps : h->num_cus;
-    hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW>), dim3(blocks), dim3(512),
+    hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW>), dim3(blocks), dim3(64 * kApplyWaves),
                        kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
                        static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(bias), h->sfrag,
                        h->kfrag, h->vhalf, h->wfrag, static_cast<bf16_t*>(out), d.heads,
