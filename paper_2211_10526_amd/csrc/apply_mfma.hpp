@@ -12,14 +12,17 @@
 //
 // Work unit: a strip of 16 grid columns of one (batch, head) unit, four output rows per
 // stage, walked top to bottom by a persistent block (one per compute unit).
-// A block has twelve waves, three per SIMD:
-//   waves 0..7   consumers: wave (c, h) owns channels 16c..16c+15 and output rows 2h, 2h+1 of
-//                every stage; it keeps a sliding window of DWConv operands in registers and
-//                feeds the 4x4x4 MFMAs, then writes its results to an LDS output tile;
-//   waves 8..11  producers: asynchronous global loads (several stages ahead), transposition of
-//                the V rows into the MFMA operand order (transposing LDS reads), the linear
-//                branch for row p of the stage, and the coalesced stores of finished tiles.
-// Producers and consumers meet at one LDS-only barrier per stage.
+// A block has twelve waves, three per SIMD, one of each role:
+//   waves 0..3   consumers: wave c owns channels 16c..16c+15; it keeps a ring of DWConv data
+//                operands (12 grid rows for a 9x9 filter) in registers, runs the 4x4x4 MFMAs
+//                for the four output rows of the stage with the linear branch as the C
+//                operand, and writes its results to an LDS output tile;
+//   waves 4..7   stagers: asynchronous V loads (several stages ahead), transposition of the V
+//                rows into the MFMA operand order (transposing LDS reads), and the coalesced
+//                stores of finished output tiles;
+//   waves 8..11  linear: asynchronous Q loads and the linear branch of row p of the stage.
+// Stagers and linear waves work one stage ahead of the consumers; all meet at one LDS-only
+// barrier per stage.
 #pragma once
 
 #include <type_traits>
@@ -52,16 +55,16 @@ constexpr int kVtQuadStride = 672;
 constexpr int kVtOctetStride = 80;
 constexpr int kVtRowStride = 6 * kVtQuadStride;
 constexpr int kVtBytes = 4 * kVtRowStride;
-constexpr int kVtBuffers = 3;        // consumers also read the previous stage's rows
+constexpr int kVtBuffers = 2;
 // linear-branch tile of one stage: [row 4][channel 64][token 16 + pad] fp32
 constexpr int kLinTokPitch = 20;
 constexpr int kLinBytes = 4 * 64 * kLinTokPitch * 4;
 // output tile of one stage: [row 4][channel 64][token 16 + pad] bf16
 constexpr int kOutTokPitch = 20;
 constexpr int kOutBytes = 4 * 64 * kOutTokPitch * 2;
-// per producer wave: 8 tokens x 64 channels in global (token-major) order, 144 bytes a token
+// per stager wave and V item: 8 tokens x 64 channels in global (token-major) order
 constexpr int kNatTokPitch = 144;
-constexpr int kNatBytes = 8 * kNatTokPitch;
+constexpr int kNatBytes = 3 * 8 * kNatTokPitch;
 constexpr int kApplyWaves = 12;
 constexpr int kApplyMfmaLdsBytes =
     kVtBuffers * kVtBytes + 2 * kLinBytes + 2 * kOutBytes + 4 * kNatBytes;
@@ -259,7 +262,7 @@ __device__ __forceinline__ uint2 lds_read_tr8(const unsigned char* addr)
 #endif
 constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
 
-// what a producer needs to know about a stage after its cursor has moved on
+// what a wave needs to know about a stage after its cursor has moved on
 struct StageSnap {
     int unit, xs0, yo;
     bool computes;
@@ -275,14 +278,10 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
 {
     constexpr int D = 64;
     constexpr int RAD = KS / 2;
-    constexpr int NCH = (KS + 3 + 3) / 4;        // stages until a segment's first output
-    constexpr int A0 = 4 * (NCH - 1) - RAD;      // first staged row of a stage, relative to yo
-    constexpr int WL = KS + 1 > 4 ? KS + 1 : 4;  // window rows a consumer wave holds
-    constexpr int WOFF = WL - KS - 1;            // window index of input row (yo + 2h - RAD)
+    constexpr int NCH = (KS + 3 + 3) / 4;  // stages until a segment's first output
+    constexpr int WR = 4 * NCH;            // rows in a consumer's operand ring
     constexpr int PD = kApplyPrefetch;
     static_assert(PD % 2 == 0, "the two-deep LDS rings assume an even prefetch depth");
-    constexpr int LOADS_PER_STAGE = (DW ? 3 : 0) + (LIN ? 2 : 0);
-    constexpr int YOUNGER = (PD - 1) * LOADS_PER_STAGE;  // loads issued after a stage's own
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     TRACE_DECL
@@ -290,10 +289,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const bool producer = wave >= 8;
-    const int c = wave & 3;       // consumer: channel group; producer: row inside the stage
-    const int half = (wave >> 2) & 1;  // consumer: output rows 2*half, 2*half+1 of the stage
-    const int ptid = tid & 255;   // index among the 256 producer threads
+    const int role = wave >> 2;   // 0 consumer, 1 stager, 2 linear
+    const int c = wave & 3;       // channel group / stager index / row inside the stage
     const int W = p.grid_w, H = p.grid_h;
     const int spc = (H + 3) / 4;  // steps per strip column
 
@@ -306,7 +303,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     unsigned char* const nat_base = out_base + 2 * kOutBytes;
 
     // stages of this block, padded to a multiple of the prefetch depth so that the
-    // unrolled software pipeline needs no tail code
+    // unrolled software pipelines need no tail code
     int n_stages = 0;
     {
         StageCursor cu;
@@ -321,30 +318,31 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const int n_padded = (n_stages + PD - 1) / PD * PD;
     if (n_stages == 0) return;  // uniform per block; the host never launches such a block
 
-    if (producer) {
-        // ======================================================== producer waves
-        const int tl = lane & 15, g = lane >> 4;
-        const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
-        bf16x8_t sf[4][2], kf[2];
-        float vh[4] = {0.f, 0.f, 0.f, 0.f};
-        int prod_unit = -1;
-        u32x4_t vreg[PD][3], qreg[PD][2];
-        uint32_t okmask[PD];  // bit it: V item it lies inside the grid; bit 3: the Q token does
+    if (role == 1) {
+        // ======================================================== stager waves
+        constexpr int YOUNGER = (PD - 1) * 3;  // loads issued after a stage's own
+        const int stid = tid & 255;            // index among the 256 stager threads
+        const int tl = lane & 15;
+        u32x4_t vreg[PD][3];
+        uint32_t okmask[PD];  // bit it: V item it lies inside the grid
         StageSnap snap[PD];   // stage held by each register slot
         StageSnap fsnap[2];   // stages whose output tiles wait to be stored
+        fsnap[0].computes = fsnap[1].computes = false;
+        fsnap[0].unit = fsnap[1].unit = 0;
+        fsnap[0].xs0 = fsnap[1].xs0 = fsnap[0].yo = fsnap[1].yo = 0;
 
         // this thread's three V items (of 4 rows x 24 columns x 8 octets): a wave covers,
         // per item, 8 consecutive columns (two quads) of one row with all 64 channels
         int v_r[3], v_x[3];
 #pragma unroll
         for (int it = 0; it < 3; ++it) {
-            const int item = ptid + 256 * it;
+            const int item = stid + 256 * it;
             v_r[it] = item / 192;
             v_x[it] = ((item % 192) >> 3) - 4;
         }
         const int v_oct = lane & 7;
         unsigned char* const nat = nat_base + c * kNatBytes;
-        // transposition roles: natural write (token lane/8, octet lane%8); transposing read
+        // transposition roles: token-major write (token lane/8, octet lane%8); transposing read
         // source (token 4 qd + (lane/4)%4, channels 16 (lane/16) + 4 (lane%4)..+3); afterwards
         // lane l holds channel l, 4 tokens of quad qd
         unsigned char* const nat_wr = nat + (lane >> 3) * kNatTokPitch + v_oct * 16;
@@ -352,16 +350,15 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             nat + ((lane >> 2) & 3) * kNatTokPitch + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
         const int vt_lane = (lane >> 3) * kVtOctetStride + (lane & 7) * 8;
         // output-tile roles: 16 lanes store one (row, octet) pair; lane%16 is the token
-        const int fl_e = (lane >> 2) & 3, fl_p = lane & 3;
+        const int fl_off = (((lane >> 2) & 3) * kOutTokPitch + 4 * (lane & 3)) * 2;
 
         auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
             constexpr int slot = decltype(slot_c)::value;
             const int xs0 = cu.strip * kStripW;
-            const size_t unit_off = static_cast<size_t>(cu.unit) * p.N * D;
+            const bf16_t* vb = v + static_cast<size_t>(cu.unit) * p.N * D;
             const int row_base = cu.y0 - RAD + 4 * cu.t;
             uint32_t ok = 0;
             if constexpr (DW) {
-                const bf16_t* vb = v + unit_off;
 #pragma unroll
                 for (int it = 0; it < 3; ++it) {
                     const int gy = row_base + v_r[it], gx = xs0 + v_x[it];
@@ -371,15 +368,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                                  static_cast<uint32_t>((cy * W + cx) * (D * 2) + v_oct * 16));
                 }
             }
-            if constexpr (LIN) {
-                const int y = cu.yo(NCH) + c, x = xs0 + tl;
-                if (cu.computes(NCH) && y < H && x < W) ok |= 8u;
-                const int cy = min(max(y, 0), H - 1), cx = min(x, W - 1);
-                const uint32_t off = static_cast<uint32_t>((cy * W + cx) * (D * 2) + g * 16);
-                const bf16_t* qb = q + unit_off;
-                async_load16(qreg[slot][0], qb, off);
-                async_load16(qreg[slot][1], qb, off + 64);
-            }
             okmask[slot] = ok;
             snap[slot].unit = cu.unit;
             snap[slot].xs0 = xs0;
@@ -387,122 +375,59 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             snap[slot].computes = cu.computes(NCH);
         };
 
-        auto produce = [&](auto slot_c, unsigned char* vt, float* lin) {
+        auto stage_v = [&](auto slot_c, const StageSnap& fs, const unsigned char* ot, unsigned char* vt) {
             constexpr int slot = decltype(slot_c)::value;
-            const uint32_t ok = okmask[slot];
+            // finished output tile: a transposing read turns [channel][token] into 8 channels
+            // of one token per lane (16 bytes); the stores follow once the V work is issued
+            uint2 f_lo[2], f_hi[2];
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int pair = (stid >> 4) + 16 * it;  // (row, octet) pair of this 16-lane group
+                const unsigned char* src = ot + ((pair >> 3) * 64 + 8 * (pair & 7)) * (kOutTokPitch * 2) + fl_off;
+                f_lo[it] = lds_read_tr8(src);
+                f_hi[it] = lds_read_tr8(src + 4 * kOutTokPitch * 2);
+            }
             if constexpr (DW) {
-                wait_async_loads<YOUNGER + (LIN ? 2 : 0)>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+                const uint32_t ok = okmask[slot];
+                wait_async_loads<YOUNGER>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+                // token-major staging, private to this wave; LDS operations of one wave
+                // complete in issue order, so no barrier is needed around it
 #pragma unroll
                 for (int it = 0; it < 3; ++it) {
                     const u32x4_t zero = {0u, 0u, 0u, 0u};
-                    const u32x4_t val = ((ok >> it) & 1u) ? vreg[slot][it] : zero;
-                    // token-major staging, private to this wave; LDS operations of one wave
-                    // complete in issue order, so no barrier is needed around it
-                    *reinterpret_cast<u32x4_t*>(nat_wr) = val;
-                    __builtin_amdgcn_wave_barrier();
-                    const int item0 = (wave - 8) * 64 + 256 * it;  // first item of this wave
+                    *reinterpret_cast<u32x4_t*>(nat_wr + it * 8 * kNatTokPitch) =
+                        ((ok >> it) & 1u) ? vreg[slot][it] : zero;
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            if (fs.computes) {
+                unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(fs.unit) * p.N * D);
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    const int pair = (stid >> 4) + 16 * it;
+                    const int y = fs.yo + (pair >> 3), x = fs.xs0 + tl;
+                    if (y < H && x < W)
+                        *reinterpret_cast<uint4*>(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16)) =
+                            make_uint4(f_lo[it].x, f_lo[it].y, f_hi[it].x, f_hi[it].y);
+                }
+            }
+            if constexpr (DW) {
+                uint2 u[3][2];
+#pragma unroll
+                for (int it = 0; it < 3; ++it)
+#pragma unroll
+                    for (int qd = 0; qd < 2; ++qd)
+                        u[it][qd] = lds_read_tr8(nat_rd + (it * 8 + qd * 4) * kNatTokPitch);
+#pragma unroll
+                for (int it = 0; it < 3; ++it) {
+                    const int item0 = c * 64 + 256 * it;  // first item of this wave
                     const int r = item0 / 192, x0 = (item0 % 192) >> 3;
                     unsigned char* dst = vt + (r * 6 + (x0 >> 2)) * kVtQuadStride + vt_lane;
 #pragma unroll
-                    for (int qd = 0; qd < 2; ++qd) {
-                        const uint2 u = lds_read_tr8(nat_rd + qd * 4 * kNatTokPitch);
-                        *reinterpret_cast<uint2*>(dst + qd * kVtQuadStride) = u;
-                    }
-                    __builtin_amdgcn_wave_barrier();
+                    for (int qd = 0; qd < 2; ++qd)
+                        *reinterpret_cast<uint2*>(dst + qd * kVtQuadStride) = u[it][qd];
                 }
-            }
-            TRACE_POINT(3);
-            if constexpr (LIN) {
-                wait_async_loads<YOUNGER>(qreg[slot][0], qreg[slot][1]);
-                if (snap[slot].computes) {
-                    const int unit = snap[slot].unit;
-                    if (unit != prod_unit) {  // uniform per block: operand tables of the new unit
-                        prod_unit = unit;
-                        const uint4* s4 = reinterpret_cast<const uint4*>(
-                            sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
-                        const uint4* k4 = reinterpret_cast<const uint4*>(
-                            kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
-#pragma unroll
-                        for (int nt = 0; nt < 4; ++nt) {
-#pragma unroll
-                            for (int ks = 0; ks < 2; ++ks)
-                                sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
-                            vh[nt] = vhalf[unit * D + 16 * nt + tl];
-                        }
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks)
-                            kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
-                    }
-                    const bool in = (ok & 8u) != 0;
-                    const u32x4_t zero = {0u, 0u, 0u, 0u};
-                    bf16x8_t a[2];
-                    a[0] = __builtin_bit_cast(bf16x8_t, in ? qreg[slot][0] : zero);
-                    a[1] = __builtin_bit_cast(bf16x8_t, in ? qreg[slot][1] : zero);
-                    // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
-                    f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
-                    f32x4_t acc[4], dk;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) dk[r] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
-#pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[nt][r] = 0.f;
-#pragma unroll
-                        for (int ks = 0; ks < 2; ++ks)
-                            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], acc[nt], 0, 0, 0);
-                    }
-                    float alpha[4], beta[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
-                        const float ssr = __int_as_float(
-                            __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
-                        // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
-                        const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
-                        if (p.norm_none) {
-                            alpha[r] = inv;
-                            beta[r] = 1.0f;
-                        } else {
-                            const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
-                            alpha[r] = inv * rden;
-                            beta[r] = rden;
-                        }
-                    }
-#pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) {
-                        float4 o;
-                        o.x = fmaf(alpha[0], acc[nt][0], beta[0] * vh[nt]);
-                        o.y = fmaf(alpha[1], acc[nt][1], beta[1] * vh[nt]);
-                        o.z = fmaf(alpha[2], acc[nt][2], beta[2] * vh[nt]);
-                        o.w = fmaf(alpha[3], acc[nt][3], beta[3] * vh[nt]);
-                        *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
-                    }
-                }
-            }
-        };
-
-        // store the output tile of a finished stage: a transposing read turns the
-        // [channel][token] tile into 8 channels of one token per lane (16 bytes)
-        auto flush = [&](const StageSnap& sn, const unsigned char* ot) {
-            if (!sn.computes) return;
-            unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(sn.unit) * p.N * D);
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int pair = (ptid >> 4) + 16 * it;  // (row, octet) pair of this 16-lane group
-                const int row = pair >> 3, oct = pair & 7;
-                const unsigned char* src = ot + ((row * 64 + 8 * oct + fl_e) * kOutTokPitch + 4 * fl_p) * 2;
-                const uint2 lo = lds_read_tr8(src);
-                const uint2 hi = lds_read_tr8(src + 4 * kOutTokPitch * 2);
-                const int y = sn.yo + row, x = sn.xs0 + tl;
-                if (y < H && x < W)
-                    *reinterpret_cast<uint4*>(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + oct * 16)) =
-                        make_uint4(lo.x, lo.y, hi.x, hi.y);
+                __builtin_amdgcn_wave_barrier();
             }
         };
 
@@ -512,17 +437,13 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             issue_loads(slot, ld);
             ld.advance(spc, p.strips, NCH);
         });
-        fsnap[0].computes = fsnap[1].computes = false;
-        int vt_i = 0;  // V ring index of the stage being produced
         for (int s = 0; s < n_padded; s += PD) {
             static_for<PD>([&](auto slot) {
                 constexpr int b2 = decltype(slot)::value & 1;
                 TRACE_POINT(1);
-                flush(fsnap[b2], out_base + b2 * kOutBytes);  // the tile two stages back is complete
+                // the output tile two stages back is complete
+                stage_v(slot, fsnap[b2], out_base + b2 * kOutBytes, vt_base + b2 * kVtBytes);
                 fsnap[b2] = snap[decltype(slot)::value];
-                TRACE_POINT(2);
-                produce(slot, vt_base + vt_i * kVtBytes, reinterpret_cast<float*>(lin_base + b2 * kLinBytes));
-                vt_i = vt_i == kVtBuffers - 1 ? 0 : vt_i + 1;
                 TRACE_POINT(4);
                 issue_loads(slot, ld);  // refill the slot that was just drained
                 ld.advance(spc, p.strips, NCH);
@@ -531,38 +452,178 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 TRACE_POINT(6);
             });
         }
-        // the last two tiles
-        flush(fsnap[0], out_base);
+        // the last two tiles: a pass with nothing to stage but the stores
+        auto flush_only = [&](const StageSnap& fs, const unsigned char* ot) {
+            if (!fs.computes) return;
+            unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(fs.unit) * p.N * D);
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int pair = (stid >> 4) + 16 * it;
+                const unsigned char* src = ot + ((pair >> 3) * 64 + 8 * (pair & 7)) * (kOutTokPitch * 2) + fl_off;
+                const uint2 lo = lds_read_tr8(src);
+                const uint2 hi = lds_read_tr8(src + 4 * kOutTokPitch * 2);
+                const int y = fs.yo + (pair >> 3), x = fs.xs0 + tl;
+                if (y < H && x < W)
+                    *reinterpret_cast<uint4*>(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16)) =
+                        make_uint4(lo.x, lo.y, hi.x, hi.y);
+            }
+        };
+        flush_only(fsnap[0], out_base);
         lds_barrier();
-        flush(fsnap[1], out_base + kOutBytes);
+        flush_only(fsnap[1], out_base + kOutBytes);
         // drain the padding loads before the registers die
+        if constexpr (DW)
+            static_for<PD>([&](auto slot) {
+                wait_async_loads<0>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
+            });
+    } else if (role == 2) {
+        // ======================================================== linear waves
+        constexpr int YOUNGER = (PD - 1) * 2;
+        const int tl = lane & 15, g = lane >> 4;
+        const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
+        bf16x8_t sf[4][2], kf[2];
+        float vh[4] = {0.f, 0.f, 0.f, 0.f};
+        int lin_unit = -1;
+        u32x4_t qreg[PD][2];
+        bool qok[PD];
+        StageSnap snap[PD];
+
+        auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
+            constexpr int slot = decltype(slot_c)::value;
+            const int xs0 = cu.strip * kStripW;
+            if constexpr (LIN) {
+                const int y = cu.yo(NCH) + c, x = xs0 + tl;
+                qok[slot] = cu.computes(NCH) && y < H && x < W;
+                const int cy = min(max(y, 0), H - 1), cx = min(x, W - 1);
+                const uint32_t off = static_cast<uint32_t>((cy * W + cx) * (D * 2) + g * 16);
+                const bf16_t* qb = q + static_cast<size_t>(cu.unit) * p.N * D;
+                async_load16(qreg[slot][0], qb, off);
+                async_load16(qreg[slot][1], qb, off + 64);
+            }
+            snap[slot].unit = cu.unit;
+            snap[slot].xs0 = xs0;
+            snap[slot].yo = cu.yo(NCH);
+            snap[slot].computes = cu.computes(NCH);
+        };
+
+        auto linear = [&](auto slot_c, float* lin) {
+            constexpr int slot = decltype(slot_c)::value;
+            if constexpr (LIN) {
+                wait_async_loads<YOUNGER>(qreg[slot][0], qreg[slot][1]);
+                if (!snap[slot].computes) return;
+                const int unit = snap[slot].unit;
+                if (unit != lin_unit) {  // uniform per block: operand tables of the new unit
+                    lin_unit = unit;
+                    const uint4* s4 = reinterpret_cast<const uint4*>(
+                        sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
+                    const uint4* k4 = reinterpret_cast<const uint4*>(
+                        kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+                        for (int ks = 0; ks < 2; ++ks)
+                            sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
+                        vh[nt] = vhalf[unit * D + 16 * nt + tl];
+                    }
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
+                }
+                const u32x4_t zero = {0u, 0u, 0u, 0u};
+                bf16x8_t a[2];
+                a[0] = __builtin_bit_cast(bf16x8_t, qok[slot] ? qreg[slot][0] : zero);
+                a[1] = __builtin_bit_cast(bf16x8_t, qok[slot] ? qreg[slot][1] : zero);
+                // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
+                f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
+                f32x4_t acc[4], dk;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) dk[r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[nt][r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], acc[nt], 0, 0, 0);
+                }
+                float alpha[4], beta[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
+                    const float ssr = __int_as_float(
+                        __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
+                    // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
+                    const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                    if (p.norm_none) {
+                        alpha[r] = inv;
+                        beta[r] = 1.0f;
+                    } else {
+                        const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
+                        alpha[r] = inv * rden;
+                        beta[r] = rden;
+                    }
+                }
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+                    float4 o;
+                    o.x = fmaf(alpha[0], acc[nt][0], beta[0] * vh[nt]);
+                    o.y = fmaf(alpha[1], acc[nt][1], beta[1] * vh[nt]);
+                    o.z = fmaf(alpha[2], acc[nt][2], beta[2] * vh[nt]);
+                    o.w = fmaf(alpha[3], acc[nt][3], beta[3] * vh[nt]);
+                    *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
+                }
+            }
+        };
+
+        StageCursor ld;
+        ld.start(s_begin, s_end, spc, p.strips);
         static_for<PD>([&](auto slot) {
-            if constexpr (DW) wait_async_loads<0>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
-            if constexpr (LIN) wait_async_loads<0>(qreg[slot][0], qreg[slot][1]);
+            issue_loads(slot, ld);
+            ld.advance(spc, p.strips, NCH);
         });
+        for (int s = 0; s < n_padded; s += PD) {
+            static_for<PD>([&](auto slot) {
+                constexpr int b2 = decltype(slot)::value & 1;
+                TRACE_POINT(2);
+                linear(slot, reinterpret_cast<float*>(lin_base + b2 * kLinBytes));
+                TRACE_POINT(4);
+                issue_loads(slot, ld);
+                ld.advance(spc, p.strips, NCH);
+                TRACE_POINT(5);
+                lds_barrier();
+                TRACE_POINT(6);
+            });
+        }
+        lds_barrier();
+        if constexpr (LIN)
+            static_for<PD>([&](auto slot) { wait_async_loads<0>(qreg[slot][0], qreg[slot][1]); });
     } else {
         // ======================================================== consumer waves
         const int blk = lane >> 2, j = lane & 3;
         const int ch_dw = 16 * c + blk;
         s16x4_t tw[KS][3];
-        s16x4_t win[WL][3];
+        s16x4_t win[WR][3];  // ring: stage s writes rows 4 (s % NCH) .. +3
         float bias_dw = 0.f;
         int cons_unit = -1;
 #pragma unroll
-        for (int a = 0; a < WL; ++a)
+        for (int a = 0; a < WR; ++a)
 #pragma unroll
             for (int m = 0; m < 3; ++m) win[a][m] = s16x4_t{0, 0, 0, 0};
 #pragma unroll
         for (int a = 0; a < KS; ++a)
 #pragma unroll
             for (int m = 0; m < 3; ++m) tw[a][m] = s16x4_t{0, 0, 0, 0};
-        // this wave's four new window rows are staged rows rel0..rel0+3 of the stage
-        // (negative: rows of the previous stage's buffer)
-        const int rel0 = 2 * half + RAD - 2 - A0;
         const int vt_lane = (ch_dw >> 3) * kVtOctetStride + (ch_dw & 7) * 8 + j * kVtQuadStride;
 
-        auto consume = [&](const StageCursor& cu, const unsigned char* vt_cur,
-                           const unsigned char* vt_prev, const float* lin, unsigned char* ot) {
+        auto consume = [&](auto ph_c, const StageCursor& cu, const unsigned char* vt, const float* lin,
+                           unsigned char* ot) {
+            constexpr int ph = decltype(ph_c)::value;  // stage index modulo NCH: ring phase
             if constexpr (DW) {
                 if (cu.unit != cons_unit) {  // uniform per block: Toeplitz operands of the unit's head
                     cons_unit = cu.unit;
@@ -576,31 +637,24 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                             tw[dy][m] = __builtin_bit_cast(s16x4_t, wf[(dy * 3 + m) * 64]);
                     bias_dw = bias ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
                 }
-                // slide the window down by four rows and take in this wave's four new ones
+                // the four staged rows replace the oldest four of the ring
 #pragma unroll
-                for (int idx = 0; idx + 4 < WL; ++idx)
-#pragma unroll
-                    for (int m = 0; m < 3; ++m) win[idx][m] = win[idx + 4][m];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int rel = rel0 + r;
-                    const unsigned char* rowp =
-                        (rel < 0 ? vt_prev : vt_cur) + (rel & 3) * kVtRowStride + vt_lane;
+                for (int r = 0; r < 4; ++r)
 #pragma unroll
                     for (int m = 0; m < 3; ++m)
-                        win[WL - 4 + r][m] = __builtin_bit_cast(
-                            s16x4_t, *reinterpret_cast<const uint2*>(rowp + m * kVtQuadStride));
-                }
+                        win[4 * ph + r][m] = __builtin_bit_cast(
+                            s16x4_t,
+                            *reinterpret_cast<const uint2*>(vt + r * kVtRowStride + m * kVtQuadStride + vt_lane));
             }
             TRACE_POINT(12);
             if (!cu.computes(NCH)) return;
 
-            f32x4_t acc[2];
+            f32x4_t acc[4];
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
+            for (int rr = 0; rr < 4; ++rr) {
                 if constexpr (LIN) {
                     const float4 l4 = *reinterpret_cast<const float4*>(
-                        lin + (((2 * half + rr) * 64 + ch_dw) * kLinTokPitch + 4 * j));
+                        lin + ((rr * 64 + ch_dw) * kLinTokPitch + 4 * j));
                     acc[rr][0] = l4.x + bias_dw;
                     acc[rr][1] = l4.y + bias_dw;
                     acc[rr][2] = l4.z + bias_dw;
@@ -611,41 +665,44 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             }
             TRACE_POINT(13);
             if constexpr (DW) {
+                // input row (yo - RAD + i) is ring row (4 (ph + 1) + i) mod WR
 #pragma unroll
                 for (int dy = 0; dy < KS; ++dy)
 #pragma unroll
                     for (int m = 0; m < 3; ++m)
 #pragma unroll
-                        for (int rr = 0; rr < 2; ++rr)
+                        for (int rr = 0; rr < 4; ++rr)
                             acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(
-                                tw[dy][m], win[rr + dy + WOFF][m], acc[rr], 0, 0, 0);
+                                tw[dy][m], win[(4 * (ph + 1) + rr + dy) % WR][m], acc[rr], 0, 0, 0);
             }
             TRACE_POINT(14);
             // results go to the LDS output tile [row][channel][token]
 #pragma unroll
-            for (int rr = 0; rr < 2; ++rr) {
+            for (int rr = 0; rr < 4; ++rr) {
                 uint2 o;
                 o.x = pack_bf16x2(acc[rr][0], acc[rr][1]);
                 o.y = pack_bf16x2(acc[rr][2], acc[rr][3]);
-                *reinterpret_cast<uint2*>(ot + (((2 * half + rr) * 64 + ch_dw) * kOutTokPitch + 4 * j) * 2) = o;
+                *reinterpret_cast<uint2*>(ot + ((rr * 64 + ch_dw) * kOutTokPitch + 4 * j) * 2) = o;
             }
         };
 
         StageCursor cs;
         cs.start(s_begin, s_end, spc, p.strips);
-        int vt_i = 0, vt_p = kVtBuffers - 1;
         lds_barrier();
-        for (int s = 0; s < n_padded; ++s) {
-            TRACE_POINT(11);
-            consume(cs, vt_base + vt_i * kVtBytes, vt_base + vt_p * kVtBytes,
-                    reinterpret_cast<const float*>(lin_base + (s & 1) * kLinBytes),
-                    out_base + (s & 1) * kOutBytes);
-            TRACE_POINT(15);
-            cs.advance(spc, p.strips, NCH);
-            vt_p = vt_i;
-            vt_i = vt_i == kVtBuffers - 1 ? 0 : vt_i + 1;
-            lds_barrier();
-            TRACE_POINT(16);
+        for (int s = 0; s < n_padded; s += NCH) {
+            static_for<NCH>([&](auto ph) {
+                if (s + decltype(ph)::value < n_padded) {
+                    const int b2 = (s + decltype(ph)::value) & 1;
+                    TRACE_POINT(11);
+                    consume(ph, cs, vt_base + b2 * kVtBytes,
+                            reinterpret_cast<const float*>(lin_base + b2 * kLinBytes),
+                            out_base + b2 * kOutBytes);
+                    TRACE_POINT(15);
+                    cs.advance(spc, p.strips, NCH);
+                    lds_barrier();
+                    TRACE_POINT(16);
+                }
+            });
         }
     }
     TRACE_DUMP
