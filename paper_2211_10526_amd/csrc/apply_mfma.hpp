@@ -318,6 +318,10 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const int n_padded = (n_stages + PD - 1) / PD * PD;
     if (n_stages == 0) return;  // uniform per block; the host never launches such a block
 
+    // The stager and linear waves have little work per stage, but the consumers' MFMA
+    // stream would starve them of issue slots; they run at a raised wave priority.
+    if (role != 0) __builtin_amdgcn_s_setprio(2);
+
     if (role == 1) {
         // ======================================================== stager waves
         constexpr int YOUNGER = (PD - 1) * 3;  // loads issued after a stage's own
