@@ -78,15 +78,24 @@ constexpr int kApplyMfmaLdsBytes =
 constexpr int kSfragPerUnit = 4 * 2 * 64 * 8;  // bf16 elements
 constexpr int kKfragPerUnit = 2 * 64 * 8;
 
-// grid = (ceil(kCombineFragThreads / 256), units).  Fixed-order sum of the partial
-// states; writes the fp32 state and the bf16 MFMA operand tables of the apply kernel.
-__global__ __launch_bounds__(256) void combine_frag_kernel(const float* __restrict__ partial,
-                                                            float* __restrict__ state,
-                                                            bf16_t* __restrict__ sfrag,
-                                                            bf16_t* __restrict__ kfrag,
-                                                            float* __restrict__ vhalf, int n_split)
+__device__ __forceinline__ void dwconv_weight_frag(int t, const bf16_t* __restrict__ w,
+                                                   bf16_t* __restrict__ wfrag, int heads, int ks);
+
+// grid = (ceil(kCombineFragThreads / 256), units + weight_rows).  Rows < units: fixed-order
+// sum of the partial states of one unit; writes the fp32 state and the bf16 MFMA operand
+// tables of the apply kernel.  Rows >= units (only when w != nullptr): the DWConv weight
+// operand table, so that a whole forward needs no separate launch for it.
+__global__ __launch_bounds__(256) void combine_frag_kernel(
+    const float* __restrict__ partial, float* __restrict__ state, bf16_t* __restrict__ sfrag,
+    bf16_t* __restrict__ kfrag, float* __restrict__ vhalf, int n_split, int units,
+    const bf16_t* __restrict__ w, bf16_t* __restrict__ wfrag, int heads, int ks)
 {
     using L = StateLayout<64>;
+    if (static_cast<int>(blockIdx.y) >= units) {
+        const int row = blockIdx.y - units;
+        dwconv_weight_frag((row * gridDim.x + blockIdx.x) * 256 + threadIdx.x, w, wfrag, heads, ks);
+        return;
+    }
     const int unit = blockIdx.y;
     const float* p = partial + static_cast<size_t>(unit) * n_split * L::SIZE;
     float* st = state + static_cast<size_t>(unit) * L::SIZE;
@@ -121,31 +130,38 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(const float* __restri
 }
 constexpr int kCombineFragThreads = 2048 + 128 + 512;
 
-// One thread per (head, c, dy, m, lane): the Toeplitz operand of the DWConv MFMA.
-template <int KS>
-__global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* __restrict__ w,
-                                                                 bf16_t* __restrict__ wfrag,
-                                                                 int heads)
+// Thread t of heads * 4 * ks * 3 * 64 builds one 8-byte entry of wfrag: the Toeplitz operand
+// of the DWConv MFMA for (head, c, dy, m, lane).
+__device__ __forceinline__ void dwconv_weight_frag(int t, const bf16_t* __restrict__ w,
+                                                   bf16_t* __restrict__ wfrag, int heads, int ks)
 {
-    const int t = blockIdx.x * 256 + threadIdx.x;
-    if (t >= heads * 4 * KS * 3 * 64) return;
+    if (t >= heads * 4 * ks * 3 * 64) return;
     const int lane = t & 63;
     const int m = (t >> 6) % 3;
-    const int dy = (t / (64 * 3)) % KS;
-    const int c = (t / (64 * 3 * KS)) & 3;
-    const int head = t / (64 * 3 * KS * 4);
+    const int dy = (t / (64 * 3)) % ks;
+    const int c = (t / (64 * 3 * ks)) & 3;
+    const int head = t / (64 * 3 * ks * 4);
     const int ch = 16 * c + (lane >> 2), i = lane & 3;
-    const bf16_t* wr = w + ((static_cast<size_t>(head) * 64 + ch) * KS + dy) * KS;
+    const bf16_t* wr = w + ((static_cast<size_t>(head) * 64 + ch) * ks + dy) * ks;
     bf16_t v[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const int dx = 4 * m - 4 + k - i + KS / 2;
-        v[k] = (dx >= 0 && dx < KS) ? wr[dx] : static_cast<bf16_t>(0);
+        const int dx = 4 * m - 4 + k - i + ks / 2;
+        const int dxc = min(max(dx, 0), ks - 1);
+        const bf16_t val = wr[dxc];
+        v[k] = (dx == dxc) ? val : static_cast<bf16_t>(0);
     }
     uint2 o;
     o.x = static_cast<uint32_t>(v[0]) | (static_cast<uint32_t>(v[1]) << 16);
     o.y = static_cast<uint32_t>(v[2]) | (static_cast<uint32_t>(v[3]) << 16);
     reinterpret_cast<uint2*>(wfrag)[t] = o;
+}
+
+__global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* __restrict__ w,
+                                                                 bf16_t* __restrict__ wfrag,
+                                                                 int heads, int ks)
+{
+    dwconv_weight_frag(blockIdx.x * 256 + threadIdx.x, w, wfrag, heads, ks);
 }
 
 // ---------------------------------------------------------------------------
@@ -258,7 +274,7 @@ __device__ __forceinline__ uint2 lds_read_tr8(const unsigned char* addr)
 }
 
 #ifndef CASTLING_APPLY_PREFETCH
-#define CASTLING_APPLY_PREFETCH 4
+#define CASTLING_APPLY_PREFETCH 2
 #endif
 constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
 

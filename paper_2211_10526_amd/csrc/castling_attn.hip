@@ -92,7 +92,8 @@ void launch_combine(castling_attn* h, hipStream_t s)
                        h->partial, h->state, h->n_split);
 }
 
-int do_reduce(castling_attn* h, const void* k, const void* v, hipStream_t s)
+// w != nullptr: also prepare the DWConv weight operands of the MFMA apply kernel
+int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hipStream_t s)
 {
     const bool f32 = h->desc.io_dtype == CASTLING_F32;
     const int d = h->desc.d;
@@ -108,9 +109,13 @@ int do_reduce(castling_attn* h, const void* k, const void* v, hipStream_t s)
     }
     HIP_TRY(hipGetLastError());
     if (h->mfma_apply) {
-        hipLaunchKernelGGL(combine_frag_kernel, dim3((kCombineFragThreads + 255) / 256, h->units),
-                           dim3(256), 0, s, h->partial, h->state, h->sfrag, h->kfrag, h->vhalf,
-                           h->n_split);
+        const int gx = (kCombineFragThreads + 255) / 256;
+        const int ks = h->desc.dw_kernel;
+        const int wthreads = h->desc.heads * 4 * ks * 3 * 64;
+        const int wrows = w ? (wthreads + gx * 256 - 1) / (gx * 256) : 0;
+        hipLaunchKernelGGL(combine_frag_kernel, dim3(gx, h->units + wrows), dim3(256), 0, s,
+                           h->partial, h->state, h->sfrag, h->kfrag, h->vhalf, h->n_split, h->units,
+                           static_cast<const bf16_t*>(w), h->wfrag, h->desc.heads, ks);
     } else if (d == 32) {
         launch_combine<32>(h, s);
     } else {
@@ -151,6 +156,7 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     return hipGetLastError();
 }
 
+// w == nullptr: the weight operand table has already been prepared on this stream
 template <int KS, bool LIN, bool DW>
 hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, const void* v,
                                const void* w, const void* bias, void* out, hipStream_t s)
@@ -170,10 +176,10 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     p.do_linear = LIN;
     p.do_dwconv = DW;
     p.eps = d.eps;
-    if (DW) {
+    if (DW && w) {
         const int threads = d.heads * 4 * KS * 3 * 64;
-        hipLaunchKernelGGL((dwconv_weight_frag_kernel<KS>), dim3((threads + 255) / 256), dim3(256),
-                           0, s, static_cast<const bf16_t*>(w), h->wfrag, d.heads);
+        hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
+                           static_cast<const bf16_t*>(w), h->wfrag, d.heads, KS);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -391,7 +397,7 @@ int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* 
 {
     if (!h || !k || !v) return CASTLING_ERR_INVALID_ARG;
     if (misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
-    return do_reduce(h, k, v, static_cast<hipStream_t>(stream));
+    return do_reduce(h, k, v, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
@@ -415,8 +421,14 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
         const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
         if (overlaps(out, bytes, k, bytes) || overlaps(out, bytes, v, bytes))
             return CASTLING_ERR_ALIAS;
-        st = castling_attn_reduce(h, k, v, stream);
+        // the combine launch also prepares the weight operands of the MFMA apply kernel
+        const bool fuse_w = h->mfma_apply && (d.branches & CASTLING_BRANCH_DWCONV);
+        st = do_reduce(h, k, v, fuse_w ? dw_weight : nullptr, static_cast<hipStream_t>(stream));
         if (st != CASTLING_OK) return st;
+        if (fuse_w) {
+            HIP_TRY(do_apply(h, true, q, v, nullptr, dw_bias, out, static_cast<hipStream_t>(stream)));
+            return CASTLING_OK;
+        }
     }
     return castling_attn_apply(h, q, v, dw_weight, dw_bias, out, stream);
 }

@@ -77,19 +77,24 @@ struct StateLayout {
 };
 
 // Sum of `n` partials that lie `stride` floats apart, in index order, with the loads
-// of eight partials in flight at a time (the order of the additions is fixed).
+// of sixteen partials in flight at a time (the order of the additions is fixed).
 __device__ __forceinline__ float sum_partials(const float* p, int n, size_t stride)
 {
     float s = 0.f;
     int sp = 0;
-    for (; sp + 8 <= n; sp += 8) {
-        float t[8];
+    for (; sp + 16 <= n; sp += 16) {
+        float t[16];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = p[(sp + u) * stride];
+        for (int u = 0; u < 16; ++u) t[u] = p[(sp + u) * stride];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += t[u];
+        for (int u = 0; u < 16; ++u) s += t[u];
     }
-    for (; sp < n; ++sp) s += p[sp * stride];
+    float t[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) t[u] = (sp + u < n) ? p[(sp + u) * stride] : 0.f;
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+        if (sp + u < n) s += t[u];
     return s;
 }
 
