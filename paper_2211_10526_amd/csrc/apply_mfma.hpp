@@ -218,51 +218,12 @@ struct StageCursor {
     __device__ __forceinline__ bool computes(int nch) const { return live && t >= nch - 1; }
 };
 
-template <int N, typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>), fully unrolled
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
-}
-
 // LDS-only workgroup barrier: global loads that are still in flight stay in flight.
 __device__ __forceinline__ void lds_barrier()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Global loads whose completion this code tracks itself.  The compiler's own wait
-// insertion has to assume the worst across the software pipeline's loop (it waits for
-// every load in flight, which serialises the prefetch); these loads are invisible to
-// it and are followed, before the first use of their registers, by wait_async_loads
-// with the number of younger loads that may still be in flight.  Loads complete in
-// issue order, and any further memory operation issued in between only makes the
-// wait stricter, never too weak.
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
-
-// base: wave-uniform pointer (scalar registers), offset: per-lane byte offset
-__device__ __forceinline__ void async_load16(u32x4_t& dst, const void* base, uint32_t offset)
-{
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(offset), "s"(base) : "memory");
-}
-template <int YOUNGER>
-__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t& c)
-{
-    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(YOUNGER) : "memory");
-}
-template <int YOUNGER>
-__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b)
-{
-    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(YOUNGER) : "memory");
 }
 
 // 8-byte transposing LDS read (see lds_operand_tr in reduce_mfma.hpp for the lane roles)

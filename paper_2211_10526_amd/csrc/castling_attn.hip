@@ -20,7 +20,7 @@ using namespace castling;
 
 namespace {
 
-constexpr int kTargetReduceBlocks = 512;  // about two blocks per compute unit
+constexpr int kTargetReduceBlocks = 256;  // one block per compute unit
 constexpr int kMinChunkTokens = 128;
 
 thread_local char g_hip_error[256] = "HIP runtime error";
@@ -322,7 +322,12 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
     // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
-    int n_split = kTargetReduceBlocks / h->units;  // never one block more than fits at once
+    int target_blocks = kTargetReduceBlocks;
+    if (const char* tb = getenv("CASTLING_ATTN_REDUCE_BLOCKS")) {  // tuning aid
+        const int v = atoi(tb);
+        if (v > 0) target_blocks = v;
+    }
+    int n_split = target_blocks / h->units;  // never one block more than fits at once
     const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;

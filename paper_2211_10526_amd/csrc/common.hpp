@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace castling {
 
 typedef uint16_t bf16_t;  // raw bfloat16 bits
@@ -96,6 +99,51 @@ __device__ __forceinline__ float sum_partials(const float* p, int n, size_t stri
     for (int u = 0; u < 16; ++u)
         if (sp + u < n) s += t[u];
     return s;
+}
+
+template <int N, typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>), fully unrolled
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl<N>(f, std::make_integer_sequence<int, N>{});
+}
+
+// Global loads whose completion this code tracks itself.  The compiler's own wait
+// insertion has to assume the worst across the software pipeline's loop (it waits for
+// every load in flight, which serialises the prefetch); these loads are invisible to
+// it and are followed, before the first use of their registers, by wait_async_loads
+// with the number of younger loads that may still be in flight.  Loads complete in
+// issue order, and any further memory operation issued in between only makes the
+// wait stricter, never too weak.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+// base: wave-uniform pointer (scalar registers), offset: per-lane byte offset
+__device__ __forceinline__ void async_load16(u32x4_t& dst, const void* base, uint32_t offset)
+{
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(offset), "s"(base) : "memory");
+}
+template <int YOUNGER>
+__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t& c)
+{
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%3)" : "+v"(a), "+v"(b), "+v"(c) : "n"(YOUNGER) : "memory");
+}
+template <int YOUNGER>
+__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t& c, u32x4_t& d)
+{
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(YOUNGER) : "memory");
+}
+template <int YOUNGER>
+__device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b)
+{
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%2)" : "+v"(a), "+v"(b) : "n"(YOUNGER) : "memory");
 }
 
 }  // namespace castling

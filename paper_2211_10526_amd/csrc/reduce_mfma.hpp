@@ -23,6 +23,10 @@ typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 
 constexpr int kReduceWaves = 4;
 constexpr int kReduceIterTokens = 32;  // tokens one wave stages per iteration
+#ifndef CASTLING_REDUCE_PREFETCH
+#define CASTLING_REDUCE_PREFETCH 2
+#endif
+constexpr int kReducePrefetch = CASTLING_REDUCE_PREFETCH;  // iterations whose loads are in flight
 
 // x + (value of x in another lane chosen by a DPP control)
 template <int CTRL>
@@ -134,36 +138,50 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
 #pragma unroll
     for (int e = 0; e < 8; ++e) ksum[e] = vsum[e] = 0.f;
 
-    uint4 kraw[LOADS], vraw[LOADS];
-    auto issue_loads = [&](int n0) {
+    // software pipeline: the global loads of RPD iterations are in flight (see async_load16)
+    constexpr int RPD = kReducePrefetch;
+    static_assert(LOADS == 2 || LOADS == 4, "wait_async_loads takes 2 or 4 registers");
+    u32x4_t kraw[RPD][LOADS], vraw[RPD][LOADS];
+    const int n_iter = w_end > w_begin ? (w_end - w_begin + kReduceIterTokens - 1) / kReduceIterTokens : 0;
+    const uint32_t lane_off = static_cast<uint32_t>(lcol * 2);
+    const float inv_eps = 1.0f / eps;
+
+    // rows past the slice are loaded from a clamped (valid) address and zeroed when used
+    auto issue_loads = [&](auto slot_c, int n0) {
+        constexpr int slot = decltype(slot_c)::value;
+        uint32_t off[LOADS];
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            const int n = n0 + j * TPL + lrow;
-            if (n < w_end) {
-                kraw[j] = *reinterpret_cast<const uint4*>(kb + static_cast<size_t>(n) * D + lcol);
-                vraw[j] = *reinterpret_cast<const uint4*>(vb + static_cast<size_t>(n) * D + lcol);
-            } else {
-                kraw[j] = make_uint4(0u, 0u, 0u, 0u);
-                vraw[j] = make_uint4(0u, 0u, 0u, 0u);
-            }
-        }
+        for (int j = 0; j < LOADS; ++j)
+            off[j] = static_cast<uint32_t>(min(n0 + j * TPL + lrow, N - 1)) * (D * 2) + lane_off;
+        // all K loads first, then all V loads: process() waits for them in this order
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) async_load16(kraw[slot][j], kb, off[j]);
+#pragma unroll
+        for (int j = 0; j < LOADS; ++j) async_load16(vraw[slot][j], vb, off[j]);
     };
 
-    if (w_begin < w_end) issue_loads(w_begin);
-    for (int n0 = w_begin; n0 < w_end; n0 += kReduceIterTokens) {
-        uint4 kcur[LOADS], vcur[LOADS];
-#pragma unroll
-        for (int j = 0; j < LOADS; ++j) {
-            kcur[j] = kraw[j];
-            vcur[j] = vraw[j];
-        }
-        if (n0 + kReduceIterTokens < w_end) issue_loads(n0 + kReduceIterTokens);
-
+    // ahead: iterations whose loads were issued after this slot's (fewer near the end)
+    auto process = [&](auto slot_c, int n0, int ahead) {
+        constexpr int slot = decltype(slot_c)::value;
+        static_for<RPD>([&](auto a_c) {
+            constexpr int Y = decltype(a_c)::value * 2 * LOADS;
+            if (ahead == decltype(a_c)::value) {
+                if constexpr (LOADS == 4) {
+                    wait_async_loads<Y + LOADS>(kraw[slot][0], kraw[slot][1], kraw[slot][2], kraw[slot][3]);
+                    wait_async_loads<Y>(vraw[slot][0], vraw[slot][1], vraw[slot][2], vraw[slot][3]);
+                } else {
+                    wait_async_loads<Y + LOADS>(kraw[slot][0], kraw[slot][1]);
+                    wait_async_loads<Y>(vraw[slot][0], vraw[slot][1]);
+                }
+            }
+        });
         // normalise, accumulate the column sums, stage k_hat and v
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) {
-            const uint32_t kw[4] = {kcur[j].x, kcur[j].y, kcur[j].z, kcur[j].w};
-            const uint32_t vw[4] = {vcur[j].x, vcur[j].y, vcur[j].z, vcur[j].w};
+            const bool in = n0 + j * TPL + lrow < w_end;
+            const u32x4_t zero = {0u, 0u, 0u, 0u};
+            const u32x4_t kw = in ? kraw[slot][j] : zero;
+            const u32x4_t vw = in ? vraw[slot][j] : zero;
             float kf[8];
             float ss = 0.f;
 #pragma unroll
@@ -176,19 +194,19 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                 vsum[2 * i + 1] += __uint_as_float(vw[i] & 0xffff0000u);
             }
             ss = row_group_sum<LPR>(ss);
-            const float inv = 1.0f / fmaxf(sqrtf(ss), eps);
-            uint4 kh;
-            uint32_t* khw = reinterpret_cast<uint32_t*>(&kh);
+            // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
+            const float inv = fminf(__builtin_amdgcn_rsqf(ss), inv_eps);
+            u32x4_t kh;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float a = kf[2 * i] * inv, b = kf[2 * i + 1] * inv;
                 ksum[2 * i] += a;
                 ksum[2 * i + 1] += b;
-                khw[i] = pack_bf16x2(a, b);
+                kh[i] = pack_bf16x2(a, b);
             }
             const int row = j * TPL + lrow;
-            *reinterpret_cast<uint4*>(ks_tile + row * PITCH + lcol * 2) = kh;
-            *reinterpret_cast<uint4*>(vs_tile + row * PITCH + lcol * 2) = vcur[j];
+            *reinterpret_cast<u32x4_t*>(ks_tile + row * PITCH + lcol * 2) = kh;
+            *reinterpret_cast<u32x4_t*>(vs_tile + row * PITCH + lcol * 2) = vw;
         }
         // LDS operations of one wave complete in issue order, and the staging tiles are
         // private to this wave: the reads below see the writes above without a barrier.
@@ -209,6 +227,21 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                                                                           0, 0, 0);
         }
         __builtin_amdgcn_wave_barrier();
+    };
+
+    static_for<RPD>([&](auto slot) {
+        if (decltype(slot)::value < n_iter)
+            issue_loads(slot, w_begin + decltype(slot)::value * kReduceIterTokens);
+    });
+    for (int it = 0; it < n_iter; it += RPD) {
+        static_for<RPD>([&](auto slot) {
+            const int i = it + decltype(slot)::value;
+            if (i < n_iter) {
+                const int n0 = w_begin + i * kReduceIterTokens;
+                process(slot, n0, min(RPD - 1, n_iter - 1 - i));
+                if (i + RPD < n_iter) issue_loads(slot, n0 + RPD * kReduceIterTokens);
+            }
+        });
     }
 
     // ---- column sums: every lane's 16 partial sums go through LDS, summed in lane order
