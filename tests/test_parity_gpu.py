@@ -27,6 +27,10 @@ SMALL = [
     Workload("s_f32_d32_37x1_k3", "f32", 1, 2, 32, 37, 1, 3),
     Workload("s_bf16_d64_1x1_k1", "bf16", 2, 2, 64, 1, 1, 1),
     Workload("s_bf16_d64_24x24_k3_outl", "bf16", 2, 2, 64, 24, 24, 3, 0.05, 8.0),
+    Workload("s_bf16_d64_20x36_k7", "bf16", 1, 7, 64, 20, 36, 7),
+    Workload("s_bf16_d64_33x17_k9", "bf16", 3, 1, 64, 33, 17, 9),
+    Workload("s_bf16_d32_18x18_k9", "bf16", 1, 2, 32, 18, 18, 9),
+    Workload("s_f32_d64_6x6_k7", "f32", 1, 2, 64, 6, 6, 7),
 ]
 
 
@@ -44,7 +48,7 @@ def test_small_against_definition(oracle, wl, norm):
         assert rel_err(got, want) <= TOL[wl.dtype], (wl.name, norm, branches)
 
 
-@pytest.mark.parametrize("wl", SMALL[:6], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", SMALL[:6] + SMALL[10:12], ids=lambda w: w.name)
 def test_state_against_oracle(oracle, wl):
     x = inputs.make_inputs(wl, seed=12)
     _, k, v, _, _ = oracle_inputs(x)
@@ -139,6 +143,31 @@ def test_bitwise_deterministic(idx):
         outs.append(out.view(torch.int16 if wl.dtype == "bf16" else torch.int32).cpu())
     attn.destroy()
     assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2])
+
+
+def test_zero_rows_bf16(oracle):
+    """bf16 path: a zero query gives uniform weights, a zero key has weight exactly 1/2."""
+    wl = Workload("edge_bf16", "bf16", 2, 2, 64, 9, 18, 5)
+    x = inputs.make_inputs(wl, seed=16)
+    x["q"][1, 0, 40] = 0.0
+    x["k"][0, 1, 3] = 0.0
+    q, k, v, w, bias = oracle_inputs(x)
+    got = gpu_forward(wl, x, branches=b.BRANCH_LINEAR)
+    want = oracle.forward_explicit(q, k, v, w, None, wl.grid_h, wl.grid_w, branches=1)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= 1e-2
+    np.testing.assert_allclose(got[1, 0, 40], v[1, 0].mean(axis=0), rtol=2e-2, atol=2e-3)
+
+
+def test_forced_generic_bf16_matches_oracle(oracle, monkeypatch):
+    """The vector-ALU kernels stay reachable for bf16 (they are the fallback path)."""
+    monkeypatch.setenv("CASTLING_ATTN_FORCE_GENERIC", "1")
+    wl = SMALL[3]
+    x = inputs.make_inputs(wl, seed=17, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    got = gpu_forward(wl, x)
+    want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
+    assert rel_err(got, want) <= TOL[wl.dtype]
 
 
 def test_reduce_then_apply_equals_forward():
