@@ -89,9 +89,18 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream);
 
 /* Second half: normalise Q per token, apply the state held in the handle
- * (Eq. 3 with the linear terms of Eq. 8), add DWConv(V) (Eq. 9), store out. */
+ * (Eq. 3 with the linear terms of Eq. 8), add DWConv(V) (Eq. 9), store out.
+ * dw_weight may be NULL after castling_attn_prepare_weights: the filters registered
+ * there are used. */
 int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
                         const void* dw_bias, void* out, void* stream);
+
+/* Registers the DWConv filters (the M_DW of Eq. 9) for later castling_attn_apply calls that
+ * pass dw_weight = NULL, so that repeated applies with fixed filters skip their per-call
+ * preparation.  The matrix-core path converts the filters into its operand table on
+ * `stream` now (later changes to the buffer are not seen); the other paths keep the
+ * pointer, which must stay valid and unchanged.  forward() never uses this registration. */
+int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void* stream);
 
 /* NULL is a no-op returning CASTLING_OK. */
 int castling_attn_destroy(castling_attn_t h);

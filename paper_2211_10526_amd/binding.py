@@ -22,7 +22,8 @@ BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
 
 EXPORTS = (
     "castling_attn_validate", "castling_attn_create", "castling_attn_forward",
-    "castling_attn_reduce", "castling_attn_apply", "castling_attn_destroy",
+    "castling_attn_reduce", "castling_attn_apply", "castling_attn_prepare_weights",
+    "castling_attn_destroy",
     "castling_attn_workspace_bytes", "castling_attn_get_state", "castling_attn_num_splits",
     "castling_attn_strerror",
 )
@@ -62,6 +63,7 @@ def lib():
         L.castling_attn_forward.argtypes = [vp] * 8
         L.castling_attn_reduce.argtypes = [vp] * 4
         L.castling_attn_apply.argtypes = [vp] * 7
+        L.castling_attn_prepare_weights.argtypes = [vp] * 3
         L.castling_attn_destroy.argtypes = [vp]
         L.castling_attn_workspace_bytes.argtypes = [vp]
         L.castling_attn_workspace_bytes.restype = C.c_size_t
@@ -130,6 +132,9 @@ class CastlingAttn:
         _check(lib().castling_attn_apply(self._h, _ptr(q), _ptr(v), _ptr(w), _ptr(bias),
                                          _ptr(out), _stream_ptr(stream)))
         return out
+
+    def prepare_weights(self, w, stream=None):
+        _check(lib().castling_attn_prepare_weights(self._h, _ptr(w), _stream_ptr(stream)))
 
     def workspace_bytes(self) -> int:
         return lib().castling_attn_workspace_bytes(self._h)

@@ -62,6 +62,7 @@ struct castling_attn {
     bf16_t* kfrag;
     float* vhalf;
     bf16_t* wfrag;
+    const void* prepared_w;  // filters registered by castling_attn_prepare_weights
 };
 
 namespace {
@@ -405,12 +406,32 @@ int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* 
     return do_reduce(h, k, v, nullptr, static_cast<hipStream_t>(stream));
 }
 
+int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void* stream)
+{
+    if (!h || !dw_weight || misaligned(dw_weight)) return CASTLING_ERR_INVALID_ARG;
+    if (h->mfma_apply && (h->desc.branches & CASTLING_BRANCH_DWCONV)) {
+        const castling_attn_desc_t& d = h->desc;
+        const int threads = d.heads * 4 * d.dw_kernel * 3 * 64;
+        hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(dw_weight),
+                           h->wfrag, d.heads, d.dw_kernel);
+        HIP_TRY(hipGetLastError());
+    }
+    h->prepared_w = dw_weight;
+    return CASTLING_OK;
+}
+
 int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
                         const void* dw_bias, void* out, void* stream)
 {
-    int st = check_apply_args(h, q, v, dw_weight, out);
+    if (!h) return CASTLING_ERR_INVALID_ARG;
+    const bool registered = !dw_weight && h->prepared_w;
+    const void* w = registered ? h->prepared_w : dw_weight;
+    int st = check_apply_args(h, q, v, w, out);
     if (st != CASTLING_OK) return st;
-    HIP_TRY(do_apply(h, true, q, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
+    // the matrix-core path already holds the registered filters in its operand table
+    HIP_TRY(do_apply(h, true, q, v, (registered && h->mfma_apply) ? nullptr : w, dw_bias, out,
+                     static_cast<hipStream_t>(stream)));
     return CASTLING_OK;
 }
 

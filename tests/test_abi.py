@@ -74,4 +74,5 @@ def test_validate_null_and_strerror():
     assert L.castling_attn_forward(None, None, None, None, None, None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_reduce(None, None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_apply(None, None, None, None, None, None, None) == b.ERR_INVALID_ARG
+    assert L.castling_attn_prepare_weights(None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_get_state(None, None, 0, None) == b.ERR_INVALID_ARG

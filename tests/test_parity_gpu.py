@@ -186,6 +186,25 @@ def test_reduce_then_apply_equals_forward():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
 
 
+@pytest.mark.parametrize("wl", [SMALL[0], SMALL[3]], ids=lambda w: w.name)
+def test_apply_with_registered_weights(wl):
+    x = inputs.make_inputs(wl, seed=18)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    attn = b.CastlingAttn.for_workload(wl)
+    o1, o2 = torch.empty_like(t["q"]), torch.empty_like(t["q"])
+    attn.forward(t["q"], t["k"], t["v"], t["w"], None, o1)
+    with pytest.raises(b.CastlingError) as e:          # nothing registered yet
+        attn.apply(t["q"], t["v"], None, None, o2)
+    assert e.value.status == b.ERR_INVALID_ARG
+    attn.prepare_weights(t["w"])
+    attn.apply(t["q"], t["v"], None, None, o2)
+    torch.cuda.synchronize()
+    attn.destroy()
+    view = torch.int16 if wl.dtype == "bf16" else torch.int32
+    assert torch.equal(o1.view(view), o2.view(view))
+
+
 def test_runs_on_a_side_stream(oracle):
     wl = SMALL[3]
     x = inputs.make_inputs(wl, seed=9)
