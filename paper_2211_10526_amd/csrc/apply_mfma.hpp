@@ -39,7 +39,6 @@
 
 namespace castling {
 
-typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 struct ApplyMfmaParams {
     int N, grid_h, grid_w;

@@ -18,6 +18,7 @@ namespace castling {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
 typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 
@@ -270,29 +271,38 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
 
     // ---- K_hat^T V: fixed tree over the waves, (w0 + w2) + (w1 + w3)
     {
-        float* tree = reinterpret_cast<float*>(lds);  // [slot][reg][lane]
+        // [slot][tile][register quad][lane] x 4 floats: 16-byte LDS accesses, lanes contiguous
+        f32x4_t* tree = reinterpret_cast<f32x4_t*>(lds);
+        constexpr int SLOT = MT * MT * 4 * 64;  // float4 per slot
 #pragma unroll
         for (int half = NW / 2; half >= 1; half >>= 1) {
             if (wave >= half && wave < 2 * half) {
-                float* dst = tree + (wave - half) * (ACC_BYTES / 4);
+                f32x4_t* dst = tree + (wave - half) * SLOT + lane;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < MT; ++nt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            dst[((mt * MT + nt) * 16 + r) * 64 + lane] = acc[mt][nt][r];
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            f32x4_t q4;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) q4[e] = acc[mt][nt][4 * r4 + e];
+                            dst[((mt * MT + nt) * 4 + r4) * 64] = q4;
+                        }
             }
             __syncthreads();
             if (wave < half) {
-                const float* src = tree + wave * (ACC_BYTES / 4);
+                const f32x4_t* src = tree + wave * SLOT + lane;
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < MT; ++nt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            acc[mt][nt][r] += src[((mt * MT + nt) * 16 + r) * 64 + lane];
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const f32x4_t q4 = src[((mt * MT + nt) * 4 + r4) * 64];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[mt][nt][4 * r4 + e] += q4[e];
+                        }
             }
             __syncthreads();
         }
