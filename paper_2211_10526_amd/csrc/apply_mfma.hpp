@@ -225,6 +225,18 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// 16-byte store of output that is not read again by this layer (non-temporal)
+__device__ __forceinline__ void store16_stream(void* p, uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    typedef __attribute__((ext_vector_type(4))) uint32_t v4;
+    const v4 val = {a, b, c, d};
+#ifdef CASTLING_NO_NT
+    *reinterpret_cast<v4*>(p) = val;
+#else
+    __builtin_nontemporal_store(val, reinterpret_cast<v4*>(p));
+#endif
+}
+
 // 8-byte transposing LDS read (see lds_operand_tr in reduce_mfma.hpp for the lane roles)
 __device__ __forceinline__ uint2 lds_read_tr8(const unsigned char* addr)
 {
@@ -387,8 +399,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     const int pair = (stid >> 4) + 16 * it;
                     const int y = fs.yo + (pair >> 3), x = fs.xs0 + tl;
                     if (y < H && x < W)
-                        *reinterpret_cast<uint4*>(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16)) =
-                            make_uint4(f_lo[it].x, f_lo[it].y, f_hi[it].x, f_hi[it].y);
+                        store16_stream(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16),
+                                       f_lo[it].x, f_lo[it].y, f_hi[it].x, f_hi[it].y);
                 }
             }
             if constexpr (DW) {
@@ -444,8 +456,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 const uint2 hi = lds_read_tr8(src + 4 * kOutTokPitch * 2);
                 const int y = fs.yo + (pair >> 3), x = fs.xs0 + tl;
                 if (y < H && x < W)
-                    *reinterpret_cast<uint4*>(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16)) =
-                        make_uint4(lo.x, lo.y, hi.x, hi.y);
+                    store16_stream(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16), lo.x,
+                                   lo.y, hi.x, hi.y);
             }
         };
         flush_only(fsnap[0], out_base);
@@ -477,8 +489,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 const int cy = min(max(y, 0), H - 1), cx = min(x, W - 1);
                 const uint32_t off = static_cast<uint32_t>((cy * W + cx) * (D * 2) + g * 16);
                 const bf16_t* qb = q + static_cast<size_t>(cu.unit) * p.N * D;
-                async_load16(qreg[slot][0], qb, off);
-                async_load16(qreg[slot][1], qb, off + 64);
+                async_load16_stream(qreg[slot][0], qb, off);
+                async_load16_stream(qreg[slot][1], qb, off + 64);
             }
             snap[slot].unit = cu.unit;
             snap[slot].xs0 = xs0;

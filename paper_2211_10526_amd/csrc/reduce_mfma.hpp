@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
             off[j] = static_cast<uint32_t>(min(n0 + j * TPL + lrow, N - 1)) * (D * 2) + lane_off;
         // all K loads first, then all V loads: process() waits for them in this order
 #pragma unroll
-        for (int j = 0; j < LOADS; ++j) async_load16(kraw[slot][j], kb, off[j]);
+        for (int j = 0; j < LOADS; ++j) async_load16_stream(kraw[slot][j], kb, off[j]);
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) async_load16(vraw[slot][j], vb, off[j]);
     };
