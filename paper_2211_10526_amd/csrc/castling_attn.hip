@@ -76,13 +76,29 @@ void launch_reduce_generic(castling_attn* h, const void* k, const void* v, hipSt
                        h->n_split, h->chunk, h->desc.eps);
 }
 
+// w != nullptr: extra grid rows build the DWConv weight operand table.
+// direct: the blocks' results are final (n_split == 1); they write state and tables themselves.
 template <int D>
-void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, hipStream_t s)
+void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const void* w, bool direct,
+                        hipStream_t s)
 {
-    hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(h->n_split, h->units),
+    ReduceExtras ex;
+    ex.state = direct ? h->state : nullptr;
+    ex.sfrag = h->sfrag;
+    ex.kfrag = h->kfrag;
+    ex.vhalf = h->vhalf;
+    ex.w = static_cast<const bf16_t*>(w);
+    ex.wfrag = h->wfrag;
+    ex.units = h->units;
+    ex.heads = h->desc.heads;
+    ex.ks = h->desc.dw_kernel;
+    const int per_row = h->n_split * 64 * kReduceWaves;
+    const int wthreads = h->desc.heads * 4 * ex.ks * 3 * 64;
+    const int wrows = w ? (wthreads + per_row - 1) / per_row : 0;
+    hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(h->n_split, h->units + wrows),
                        dim3(64 * kReduceWaves), 0, s, static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), h->partial, h->desc.N, h->n_split, h->chunk,
-                       h->desc.eps);
+                       h->desc.eps, ex);
 }
 
 template <int D>
@@ -98,9 +114,12 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
 {
     const bool f32 = h->desc.io_dtype == CASTLING_F32;
     const int d = h->desc.d;
+    // with one split per unit the reduce kernel's result is final: it writes the state and
+    // the apply kernel's operand tables itself, and no combine is launched
+    const bool direct = h->mfma_apply && h->n_split == 1;
     if (h->mfma_reduce) {
-        if (d == 32) launch_reduce_mfma<32>(h, k, v, s);
-        else launch_reduce_mfma<64>(h, k, v, s);
+        if (d == 32) launch_reduce_mfma<32>(h, k, v, nullptr, false, s);
+        else launch_reduce_mfma<64>(h, k, v, direct ? w : nullptr, direct, s);
     } else if (f32) {
         if (d == 32) launch_reduce_generic<float, 32>(h, k, v, s);
         else launch_reduce_generic<float, 64>(h, k, v, s);
@@ -109,6 +128,7 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
         else launch_reduce_generic<bf16_t, 64>(h, k, v, s);
     }
     HIP_TRY(hipGetLastError());
+    if (direct) return CASTLING_OK;
     if (h->mfma_apply) {
         const int gx = (kCombineFragThreads + 255) / 256;
         const int ks = h->desc.dw_kernel;

@@ -12,6 +12,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "tables.hpp"
 
 namespace castling {
 
@@ -81,13 +82,33 @@ __device__ __forceinline__ bf16x8_t lds_operand_tr(const unsigned char* tile, in
     return __builtin_bit_cast(bf16x8_t, r);
 }
 
-// grid = (n_split, units), block = 64 * kReduceWaves.  Same partial layout as the
-// generic kernel: partial[u][s][StateLayout<D>::SIZE].
+// Optional extra outputs of the reduce kernel.
+//  - state != nullptr (only with n_split == 1 and D == 64): the block's result is final, so it
+//    writes the fp32 state and the apply kernel's operand tables itself; no combine launch.
+//  - w != nullptr: grid rows >= units build the DWConv weight operand table.
+struct ReduceExtras {
+    float* state;
+    bf16_t* sfrag;
+    bf16_t* kfrag;
+    float* vhalf;
+    const bf16_t* w;
+    bf16_t* wfrag;
+    int units, heads, ks;
+};
+
+// grid = (n_split, units [+ weight rows]), block = 64 * kReduceWaves.  Same partial layout
+// as the generic kernel: partial[u][s][StateLayout<D>::SIZE].
 template <int D>
 __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
-    int n_split, int chunk, float eps)
+    int n_split, int chunk, float eps, ReduceExtras ex)
 {
+    if (static_cast<int>(blockIdx.y) >= ex.units) {  // weight rows (uniform per block)
+        const int row = blockIdx.y - ex.units;
+        dwconv_weight_frag((row * gridDim.x + blockIdx.x) * (64 * kReduceWaves) + threadIdx.x, ex.w,
+                           ex.wfrag, ex.heads, ex.ks);
+        return;
+    }
     constexpr int NW = kReduceWaves;
     constexpr int MT = D / 32;               // 32-wide tiles per side of S
     constexpr int LPR = D / 8;               // lanes per token row
@@ -98,7 +119,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     constexpr int ACC_BYTES = MT * MT * 16 * 64 * 4;  // one wave's accumulators
     constexpr int STAGE_BYTES = NW * 2 * TILE_BYTES;
     constexpr int TREE_BYTES = (NW / 2) * ACC_BYTES;
-    constexpr int SUMS_BYTES = NW * 64 * 16 * 4;
+    constexpr int SUMS_BYTES = NW * 64 * 16 * 4 + D * 4;  // + the block's final ksum
     constexpr int LDS_BYTES = (STAGE_BYTES > TREE_BYTES ? STAGE_BYTES : TREE_BYTES) >
                                       SUMS_BYTES
                                   ? (STAGE_BYTES > TREE_BYTES ? STAGE_BYTES : TREE_BYTES)
@@ -265,8 +286,27 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                 for (int r = 0; r < TPL; ++r)
                     s += sums[(w * 64 + r * LPR + lc) * 16 + which * 8 + e];
             out[(which ? L::VSUM : L::KSUM) + f] = s;
+            if constexpr (D == 64) {
+                if (ex.state) {  // final result: fp32 state, vsum / 2, and ksum kept for the table below
+                    ex.state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f] = s;
+                    if (which) ex.vhalf[unit * 64 + f] = 0.5f * s;
+                    else sums[NW * 64 * 16 + f] = s;
+                }
+            }
         }
         __syncthreads();
+        if constexpr (D == 64) {
+            if (ex.state) {
+                // ksum operand table: entry (ks, lane, e2) holds ksum[32 ks + 8 (lane / 16) + 2 e2 .. +1] / pi
+                uint32_t* dst = reinterpret_cast<uint32_t*>(ex.kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
+                for (int u = tid; u < kKfragPerUnit / 2; u += 64 * NW) {
+                    const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
+                    const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
+                    dst[u] = pack_bf16x2(sums[NW * 64 * 16 + i0] * kInvPi, sums[NW * 64 * 16 + i0 + 1] * kInvPi);
+                }
+                __syncthreads();
+            }
+        }
     }
 
     // ---- K_hat^T V: fixed tree over the waves, (w0 + w2) + (w1 + w3)
@@ -318,6 +358,29 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                         const int j = 32 * nt + (lane % 32);
                         out[i * D + j] = acc[mt][nt][r];
                     }
+            if constexpr (D == 64) {
+                if (ex.state) {
+                    // final result: fp32 state and the S operand table (bf16 pairs of S / pi)
+                    float* st = ex.state + static_cast<size_t>(unit) * L::SIZE + L::S;
+                    uint32_t* sf = reinterpret_cast<uint32_t*>(ex.sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < MT; ++nt)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int i = 32 * mt + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
+                                const int j = 32 * nt + (lane % 32);
+                                st[i * D + j] = acc[mt][nt][r];
+                                if ((r & 1) == 0) {
+                                    // table entry ((j/16)*2 + i/32, lane' = ((i%32)/8)*16 + j%16, (i%8)/2)
+                                    const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
+                                                  ((i & 7) >> 1);
+                                    sf[t] = pack_bf16x2(acc[mt][nt][r] * kInvPi, acc[mt][nt][r + 1] * kInvPi);
+                                }
+                            }
+                }
+            }
         }
     }
 }
