@@ -126,13 +126,15 @@ __global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* _
 
 // ---------------------------------------------------------------------------
 // Work is cut into "steps" of 4 output rows of one 16-column strip of one unit.
-// Steps are numbered unit-major, then strip, then top to bottom; block b of G
+// Steps are numbered unit-major, then strip, then top to bottom; logical block b of G
 // takes the contiguous range [b*T/G, (b+1)*T/G) of the T steps, so every compute
-// unit gets the same amount of work whatever the grid shape.  A maximal run of
+// unit gets the same amount of work whatever the grid shape.  Workgroups are handed to
+// the 8 XCDs in turn, so workgroup i is logical block (i % 8) * (G / 8) + i / 8: the
+// blocks of one XCD then cover neighbouring strips, whose halo columns meet in its L2.  A maximal run of
 // steps inside one strip column is a segment; a segment first primes the DWConv
 // window (NCH - 1 stages that only stage V rows) and then emits one step per stage.
-// After the last stage the cursor stays where it is with live = false: such
-// padding stages move (clamped) data but never produce output.
+// After the last stage the cursor stays where it is with live = false: the prefetches
+// issued past the end repeat the last stage's loads and are never consumed.
 struct StageCursor {
     int g_begin, g_end;  // steps [g_begin, g_end) of the current segment
     int t;               // stage inside the segment
@@ -243,16 +245,22 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const int W = p.grid_w, H = p.grid_h;
     const int spc = (H + 3) / 4;  // steps per strip column
 
-    const int s_begin = static_cast<int>(static_cast<long long>(blockIdx.x) * total_steps / gridDim.x);
-    const int s_end = static_cast<int>(static_cast<long long>(blockIdx.x + 1) * total_steps / gridDim.x);
+#ifndef CASTLING_NO_XCD_REMAP
+    // consecutive workgroups go to the 8 XCDs in turn: give each XCD a contiguous step range
+    const int lblock = (gridDim.x % 8 == 0) ? (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8
+                                            : static_cast<int>(blockIdx.x);
+#else
+    const int lblock = blockIdx.x;
+#endif
+    const int s_begin = static_cast<int>(static_cast<long long>(lblock) * total_steps / gridDim.x);
+    const int s_end = static_cast<int>(static_cast<long long>(lblock + 1) * total_steps / gridDim.x);
 
     unsigned char* const vt_base = lds;
     unsigned char* const lin_base = lds + kVtBuffers * kVtBytes;
     unsigned char* const out_base = lin_base + 2 * kLinBytes;
     unsigned char* const nat_base = out_base + 2 * kOutBytes;
 
-    // stages of this block, padded to a multiple of the prefetch depth so that the
-    // unrolled software pipelines need no tail code
+    // stages of this block
     int n_stages = 0;
     {
         StageCursor cu;
@@ -264,7 +272,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             ge = min(s_end, gb + spc);
         }
     }
-    const int n_padded = (n_stages + PD - 1) / PD * PD;
     if (n_stages == 0) return;  // uniform per block; the host never launches such a block
 
     // The stager and linear waves have little work per stage, but the consumers' MFMA
@@ -390,15 +397,18 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             issue_loads(slot, ld);
             ld.advance(spc, p.strips, NCH);
         });
-        for (int s = 0; s < n_padded; s += PD) {
+        for (int s = 0; s < n_stages; s += PD) {
             static_for<PD>([&](auto slot) {
+                if (s + decltype(slot)::value >= n_stages) return;
                 constexpr int b2 = decltype(slot)::value & 1;
                 TRACE_POINT(1);
                 // the output tile two stages back is complete
                 stage_v(slot, fsnap[b2], out_base + b2 * kOutBytes, vt_base + b2 * kVtBytes);
                 fsnap[b2] = snap[decltype(slot)::value];
                 TRACE_POINT(4);
-                issue_loads(slot, ld);  // refill the slot that was just drained
+                // refill the slot that was just drained (past the end the cursor stands still and
+                // the loads repeat the last stage's: the count of loads in flight stays fixed)
+                issue_loads(slot, ld);
                 ld.advance(spc, p.strips, NCH);
                 TRACE_POINT(5);
                 lds_barrier();
@@ -421,10 +431,17 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                                    lo.y, hi.x, hi.y);
             }
         };
-        flush_only(fsnap[0], out_base);
-        lds_barrier();
-        flush_only(fsnap[1], out_base + kOutBytes);
-        // drain the padding loads before the registers die
+        // stage n - 2 (tile parity n % 2) is complete; stage n - 1 is after one more barrier
+        if (n_stages & 1) {
+            flush_only(fsnap[1], out_base + kOutBytes);
+            lds_barrier();
+            flush_only(fsnap[0], out_base);
+        } else {
+            flush_only(fsnap[0], out_base);
+            lds_barrier();
+            flush_only(fsnap[1], out_base + kOutBytes);
+        }
+        // drain the loads issued past the end before the registers die
         if constexpr (DW)
             static_for<PD>([&](auto slot) {
                 wait_async_loads<0>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
@@ -540,8 +557,9 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             issue_loads(slot, ld);
             ld.advance(spc, p.strips, NCH);
         });
-        for (int s = 0; s < n_padded; s += PD) {
+        for (int s = 0; s < n_stages; s += PD) {
             static_for<PD>([&](auto slot) {
+                if (s + decltype(slot)::value >= n_stages) return;
                 constexpr int b2 = decltype(slot)::value & 1;
                 TRACE_POINT(2);
                 linear(slot, reinterpret_cast<float*>(lin_base + b2 * kLinBytes));
@@ -642,9 +660,9 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         StageCursor cs;
         cs.start(s_begin, s_end, spc, p.strips);
         lds_barrier();
-        for (int s = 0; s < n_padded; s += NCH) {
+        for (int s = 0; s < n_stages; s += NCH) {
             static_for<NCH>([&](auto ph) {
-                if (s + decltype(ph)::value < n_padded) {
+                if (s + decltype(ph)::value < n_stages) {
                     const int b2 = (s + decltype(ph)::value) & 1;
                     TRACE_POINT(11);
                     consume(ph, cs, vt_base + b2 * kVtBytes,
