@@ -64,9 +64,11 @@ constexpr int kOutBytes = 4 * 64 * kOutTokPitch * 2;
 // per stager wave and V item: 8 tokens x 64 channels in global (token-major) order
 constexpr int kNatTokPitch = 144;
 constexpr int kNatBytes = 3 * 8 * kNatTokPitch;
+// per stager wave: one finished output row of the strip, 16 tokens x 64 channels token-major
+constexpr int kRowBytes = 16 * kNatTokPitch;
 constexpr int kApplyWaves = 12;
 constexpr int kApplyMfmaLdsBytes =
-    kVtBuffers * kVtBytes + 2 * kLinBytes + 2 * kOutBytes + 4 * kNatBytes;
+    kVtBuffers * kVtBytes + 2 * kLinBytes + 2 * kOutBytes + 4 * kNatBytes + 4 * kRowBytes;
 
 // grid = (ceil(kCombineFragThreads / 256), units + weight_rows).  Rows < units: fixed-order
 // sum of the partial states of one unit; writes the fp32 state and the bf16 MFMA operand
@@ -193,7 +195,7 @@ __device__ __forceinline__ void store16_stream(void* p, uint32_t a, uint32_t b, 
 {
     typedef __attribute__((ext_vector_type(4))) uint32_t v4;
     const v4 val = {a, b, c, d};
-#ifdef CASTLING_NO_NT
+#if defined(CASTLING_NO_NT) || defined(CASTLING_NO_NT_STORE)
     *reinterpret_cast<v4*>(p) = val;
 #else
     __builtin_nontemporal_store(val, reinterpret_cast<v4*>(p));
@@ -309,8 +311,15 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         const unsigned char* const nat_rd =
             nat + ((lane >> 2) & 3) * kNatTokPitch + (16 * (lane >> 4) + 4 * (lane & 3)) * 2;
         const int vt_lane = (lane >> 3) * kVtOctetStride + (lane & 7) * 8;
-        // output-tile roles: 16 lanes store one (row, octet) pair; lane%16 is the token
+        // output tile: stager c stores row c of the stage.  A transposing read gives lane l token
+        // l % 16 and octet l / 16 (+ 4 in the second pass); the row then goes through a
+        // wave-private token-major copy so that each store instruction writes 8 whole 128-byte
+        // lines (lane l: token l / 8 (+ 8), octet l % 8).  Half-line non-temporal stores cost
+        // extra memory writes.
         const int fl_off = (((lane >> 2) & 3) * kOutTokPitch + 4 * (lane & 3)) * 2;
+        unsigned char* const orow = nat_base + 4 * kNatBytes + c * kRowBytes;
+        unsigned char* const orow_wr = orow + tl * kNatTokPitch + (lane >> 4) * 16;
+        const unsigned char* const orow_rd = orow + (lane >> 3) * kNatTokPitch + (lane & 7) * 16;
 
         auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
             constexpr int slot = decltype(slot_c)::value;
@@ -335,18 +344,43 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             snap[slot].computes = cu.computes(NCH);
         };
 
-        auto stage_v = [&](auto slot_c, const StageSnap& fs, const unsigned char* ot, unsigned char* vt) {
-            constexpr int slot = decltype(slot_c)::value;
-            // finished output tile: a transposing read turns [channel][token] into 8 channels
-            // of one token per lane (16 bytes); the stores follow once the V work is issued
+        // row c of output tile `ot` -> this lane's 16 bytes of two groups of 8 whole token rows
+        auto load_out_row = [&](const unsigned char* ot, u32x4_t (&line)[2]) {
             uint2 f_lo[2], f_hi[2];
 #pragma unroll
             for (int it = 0; it < 2; ++it) {
-                const int pair = (stid >> 4) + 16 * it;  // (row, octet) pair of this 16-lane group
-                const unsigned char* src = ot + ((pair >> 3) * 64 + 8 * (pair & 7)) * (kOutTokPitch * 2) + fl_off;
+                const int oct = (lane >> 4) + 4 * it;
+                const unsigned char* src = ot + (c * 64 + 8 * oct) * (kOutTokPitch * 2) + fl_off;
                 f_lo[it] = lds_read_tr8(src);
                 f_hi[it] = lds_read_tr8(src + 4 * kOutTokPitch * 2);
             }
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const u32x4_t val = {f_lo[it].x, f_lo[it].y, f_hi[it].x, f_hi[it].y};
+                *reinterpret_cast<u32x4_t*>(orow_wr + it * 64) = val;
+            }
+            __builtin_amdgcn_wave_barrier();  // wave-private: LDS operations complete in issue order
+#pragma unroll
+            for (int it = 0; it < 2; ++it)
+                line[it] = *reinterpret_cast<const u32x4_t*>(orow_rd + it * 8 * kNatTokPitch);
+            __builtin_amdgcn_wave_barrier();
+        };
+        auto store_out_row = [&](unsigned char* ou, const StageSnap& fs, const u32x4_t (&line)[2]) {
+            const int y = fs.yo + c;
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {
+                const int x = fs.xs0 + (lane >> 3) + 8 * it;
+                if (y < H && x < W)
+                    store16_stream(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (lane & 7) * 16),
+                                   line[it][0], line[it][1], line[it][2], line[it][3]);
+            }
+        };
+
+        auto stage_v = [&](auto slot_c, const StageSnap& fs, const unsigned char* ot, unsigned char* vt) {
+            constexpr int slot = decltype(slot_c)::value;
+            // finished output tile: fetched and re-laid now, stored once the V work is issued
+            u32x4_t line[2];
+            load_out_row(ot, line);
             if constexpr (DW) {
                 const uint32_t ok = okmask[slot];
                 wait_async_loads<YOUNGER>(vreg[slot][0], vreg[slot][1], vreg[slot][2]);
@@ -362,14 +396,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             }
             if (fs.computes) {
                 unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(fs.unit) * p.N * D);
-#pragma unroll
-                for (int it = 0; it < 2; ++it) {
-                    const int pair = (stid >> 4) + 16 * it;
-                    const int y = fs.yo + (pair >> 3), x = fs.xs0 + tl;
-                    if (y < H && x < W)
-                        store16_stream(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16),
-                                       f_lo[it].x, f_lo[it].y, f_hi[it].x, f_hi[it].y);
-                }
+                store_out_row(ou, fs, line);
             }
             if constexpr (DW) {
                 uint2 u[3][2];
@@ -419,17 +446,9 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         auto flush_only = [&](const StageSnap& fs, const unsigned char* ot) {
             if (!fs.computes) return;
             unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(fs.unit) * p.N * D);
-#pragma unroll
-            for (int it = 0; it < 2; ++it) {
-                const int pair = (stid >> 4) + 16 * it;
-                const unsigned char* src = ot + ((pair >> 3) * 64 + 8 * (pair & 7)) * (kOutTokPitch * 2) + fl_off;
-                const uint2 lo = lds_read_tr8(src);
-                const uint2 hi = lds_read_tr8(src + 4 * kOutTokPitch * 2);
-                const int y = fs.yo + (pair >> 3), x = fs.xs0 + tl;
-                if (y < H && x < W)
-                    store16_stream(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (pair & 7) * 16), lo.x,
-                                   lo.y, hi.x, hi.y);
-            }
+            u32x4_t line[2];
+            load_out_row(ot, line);
+            store_out_row(ou, fs, line);
         };
         // stage n - 2 (tile parity n % 2) is complete; stage n - 1 is after one more barrier
         if (n_stages & 1) {
