@@ -45,6 +45,9 @@ def parse_args():
                     help="index (0-4) or name prefix of the benchmark workload; default the "
                          "largest one (bf16, B=2, heads=12, d=64, 128x128 grid, 9x9 DWConv)")
     ap.add_argument("--sets", type=int, default=6, help="distinct input sets to rotate over")
+    ap.add_argument("--layout", choices=("dense", "fused"), default="dense",
+                    help="dense: q, k, v, out contiguous [B,heads,N,d] (the benchmark configs); "
+                         "fused: q, k, v slices of one [B,N,3,heads,d] tensor, out [B,N,heads*d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three 256 MiB device-to-device copies: a kernel of known "
@@ -72,8 +75,16 @@ def main():
     sets = []
     for s in range(args.sets):
         x = inputs.make_inputs(wl, seed=wl.seed + s)
-        t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
-        t["out"] = torch.empty_like(t["q"])
+        if args.layout == "fused":
+            qkv = torch.empty((wl.B, wl.N, 3, wl.heads, wl.d), dtype=x["q"].dtype, device=dev)
+            for i, n in enumerate(("q", "k", "v")):
+                qkv[:, :, i] = x[n].to(dev).permute(0, 2, 1, 3)
+            t = {n: qkv[:, :, i] for i, n in enumerate(("q", "k", "v"))}
+            t["w"] = x["w"].to(dev)
+            t["out"] = torch.empty((wl.B, wl.N, wl.heads * wl.d), dtype=x["q"].dtype, device=dev)
+        else:
+            t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+            t["out"] = torch.empty_like(t["q"])
         sets.append(t)
         if s == 0:
             host0 = x
@@ -84,7 +95,12 @@ def main():
             cy.copy_(cx)
         torch.cuda.synchronize()
         del cx, cy
-    attn = binding.CastlingAttn.for_workload(wl)
+    if args.layout == "fused":
+        attn = binding.CastlingAttn.for_workload(
+            wl, in_strides=binding.fused_qkv_strides(wl.heads, wl.N, wl.d),
+            out_strides=binding.token_major_strides(wl.heads, wl.N, wl.d))
+    else:
+        attn = binding.CastlingAttn.for_workload(wl)
     stream = torch.cuda.Stream()
 
     def fwd(t):
@@ -181,6 +197,7 @@ def main():
         "dtype": wl.dtype if wl.dtype != "f32" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "d": wl.d, "N": wl.N,
                    "grid": [wl.grid_h, wl.grid_w], "dw_kernel": wl.dw_kernel,
+                   "layout": args.layout,
                    "input_sets_rotated": len(sets), "reduce_splits": n_split},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }

@@ -16,8 +16,13 @@
  *
  * Conventions
  *   - All tensor pointers are DEVICE pointers unless a parameter says "host".
- *   - q, k, v, out: [B][heads][N][d] contiguous, N = grid_h * grid_w, token
- *     n = y * grid_w + x (row-major grid, no class token).
+ *   - q, k, v, out: logical shape [B][heads][N][d], N = grid_h * grid_w, token
+ *     n = y * grid_w + x (row-major grid, no class token).  The d axis is always
+ *     contiguous.  By default the tensors are contiguous in that order; the stride
+ *     fields of the descriptor place them elsewhere, e.g. q, k, v as the three
+ *     slices of a fused projection output [B][N][3][heads][d] (Sec. 3.1: Q, K, V are
+ *     per-head linear projections of the same tokens) and out as [B][N][heads*d],
+ *     the layout the output projection reads -- no permute copies on either side.
  *   - dw_weight: [heads][d][ks][ks] contiguous (one ks x ks filter per channel,
  *     shared over the batch); dw_bias: [heads][d] or NULL.
  *   - DWConv: zero "same" padding, stride 1, cross-correlation (no flip).
@@ -69,6 +74,13 @@ typedef struct {
     int32_t norm;             /* castling_norm_t */
     uint32_t branches;        /* bitmask of CASTLING_BRANCH_*; 0 is read as CASTLING_BRANCH_ALL */
     float eps;                /* floor of the L2 norm; 0 is read as 1e-12 */
+    /* Element strides between consecutive batches, heads and tokens of q, k, v (one set for
+     * all three) and of out.  All three of a set 0 = contiguous [B][heads][N][d], i.e.
+     * {heads*N*d, N*d, d}.  Each must be a positive multiple of 16 bytes, the token stride at
+     * least d, and N * token stride must stay below 4 GiB in bytes.  The rows a set of strides
+     * addresses must not overlap each other. */
+    int64_t in_stride_b, in_stride_h, in_stride_n;
+    int64_t out_stride_b, out_stride_h, out_stride_n;
 } castling_attn_desc_t;
 
 /* Host-only check of a descriptor (no GPU needed).  Sec. 3.2.1 fixes the shapes:
@@ -79,7 +91,8 @@ int castling_attn_validate(const castling_attn_desc_t* desc);
 int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_handle);
 
 /* Whole layer (Eq. 9 with the readings above): reduce followed by apply.
- * q, k, v, dw_weight, out must be 16-byte aligned; out must not overlap q, k or v. */
+ * q, k, v, dw_weight, out must be 16-byte aligned; out must not overlap q, k or v (with
+ * strides the check compares the address ranges the tensors span, first to last byte). */
 int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
                           const void* dw_weight, const void* dw_bias, void* out, void* stream);
 

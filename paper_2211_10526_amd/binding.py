@@ -33,7 +33,10 @@ class Desc(C.Structure):
     _fields_ = [("B", C.c_int32), ("heads", C.c_int32), ("N", C.c_int32), ("d", C.c_int32),
                 ("grid_h", C.c_int32), ("grid_w", C.c_int32), ("dw_kernel", C.c_int32),
                 ("io_dtype", C.c_int32), ("norm", C.c_int32), ("branches", C.c_uint32),
-                ("eps", C.c_float)]
+                ("eps", C.c_float),
+                ("in_stride_b", C.c_int64), ("in_stride_h", C.c_int64), ("in_stride_n", C.c_int64),
+                ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64),
+                ("out_stride_n", C.c_int64)]
 
 
 class CastlingError(RuntimeError):
@@ -84,11 +87,27 @@ def _check(status: int):
         raise CastlingError(status, strerror(status))
 
 
+def fused_qkv_strides(heads, N, d):
+    """(batch, head, token) element strides of q, k, v taken as the slices [:, :, i] of a
+    fused projection output [B][N][3][heads][d]."""
+    return (N * 3 * heads * d, d, 3 * heads * d)
+
+
+def token_major_strides(heads, N, d):
+    """(batch, head, token) element strides of a [B][N][heads * d] tensor."""
+    return (N * heads * d, d, heads * d)
+
+
 def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROWSUM,
-              branches=BRANCH_ALL, eps=0.0) -> Desc:
+              branches=BRANCH_ALL, eps=0.0, in_strides=None, out_strides=None) -> Desc:
+    """in_strides / out_strides: (batch, head, token) element strides of q, k, v and of out;
+    None = contiguous [B][heads][N][d]."""
     if isinstance(io_dtype, str):
         io_dtype = {"f32": F32, "bf16": BF16}[io_dtype]
-    return Desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm, branches, eps)
+    ins = tuple(in_strides) if in_strides is not None else (0, 0, 0)
+    outs = tuple(out_strides) if out_strides is not None else (0, 0, 0)
+    return Desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm, branches, eps,
+                *ins, *outs)
 
 
 def validate(desc: Desc) -> int:
@@ -116,9 +135,10 @@ class CastlingAttn:
         _check(lib().castling_attn_create(C.byref(desc), C.byref(self._h)))
 
     @classmethod
-    def for_workload(cls, wl, norm=NORM_ROWSUM, branches=BRANCH_ALL, eps=0.0):
+    def for_workload(cls, wl, norm=NORM_ROWSUM, branches=BRANCH_ALL, eps=0.0, in_strides=None,
+                     out_strides=None):
         return cls(make_desc(wl.B, wl.heads, wl.N, wl.d, wl.grid_h, wl.grid_w, wl.dw_kernel,
-                             wl.dtype, norm, branches, eps))
+                             wl.dtype, norm, branches, eps, in_strides, out_strides))
 
     def forward(self, q, k, v, w, bias, out, stream=None):
         _check(lib().castling_attn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(w),

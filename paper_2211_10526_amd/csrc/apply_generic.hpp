@@ -14,6 +14,7 @@ struct ApplyParams {
     int do_linear;   // branch mask
     int do_dwconv;
     float eps;
+    TensorStrides in, out;  // of q and v; of out
 };
 
 constexpr int kApplyTH = 4;   // tile rows
@@ -61,7 +62,8 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
     const int tx0 = (blockIdx.x % p.tiles_x) * kApplyTW;
     const int tt = tid / 16, tj = tid % 16;
     const int my_row = tt / 4, my_col0 = (tt % 4) * 4;
-    const size_t unit_off = static_cast<size_t>(unit) * p.N * D;
+    const long long in_off = unit_offset(unit, heads, p.in);
+    const long long out_off = unit_offset(unit, heads, p.out);
 
     float res[4][RJ];
 #pragma unroll
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
             const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
             float qx[VEC];
             if (y < p.grid_h && x < p.grid_w) {
-                IO<T>::load16(q + unit_off + (static_cast<size_t>(y) * p.grid_w + x) * D + lcol, qx);
+                IO<T>::load16(q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol, qx);
             } else {
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) qx[e] = 0.f;
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
             uint4 val = make_uint4(0u, 0u, 0u, 0u);
             if (y >= 0 && y < p.grid_h && x >= 0 && x < p.grid_w)
                 val = *reinterpret_cast<const uint4*>(
-                    v + unit_off + (static_cast<size_t>(y) * p.grid_w + x) * D + part * VEC);
+                    v + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + part * VEC);
             *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tok) * D + part * VEC) = val;
         }
         const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
         for (int t = 0; t < 4; ++t) {
             const int x = tx0 + my_col0 + t;
             if (x < p.grid_w) {
-                T* o = out + unit_off + (static_cast<size_t>(y) * p.grid_w + x) * D + tj * RJ;
+                T* o = out + out_off + (static_cast<long long>(y) * p.grid_w + x) * p.out.n + tj * RJ;
                 T tmp[RJ];
 #pragma unroll
                 for (int j = 0; j < RJ; ++j) tmp[j] = IO<T>::from_f32(res[t][j]);

@@ -45,6 +45,7 @@ struct ApplyMfmaParams {
     int strips;     // 16-column strips per grid row
     int norm_none, do_linear, do_dwconv;
     float eps;
+    TensorStrides in, out;  // of q and v; of out.  N * token stride * 2 stays below 4 GiB
 };
 
 constexpr int kStripW = 16;
@@ -219,6 +220,7 @@ constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global 
 struct StageSnap {
     int unit, xs0, yo;
     bool computes;
+    long long obase;  // element offset of the unit in out (stagers only)
 };
 
 // grid = (G), block = 64 * kApplyWaves.
@@ -246,6 +248,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const int c = wave & 3;       // channel group / stager index / row inside the stage
     const int W = p.grid_w, H = p.grid_h;
     const int spc = (H + 3) / 4;  // steps per strip column
+    const uint32_t in_tok = static_cast<uint32_t>(p.in.n) * 2;    // bytes between tokens
+    const uint32_t out_tok = static_cast<uint32_t>(p.out.n) * 2;
 
 #ifndef CASTLING_NO_XCD_REMAP
     // consecutive workgroups go to the 8 XCDs in turn: give each XCD a contiguous step range
@@ -292,6 +296,9 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         fsnap[0].computes = fsnap[1].computes = false;
         fsnap[0].unit = fsnap[1].unit = 0;
         fsnap[0].xs0 = fsnap[1].xs0 = fsnap[0].yo = fsnap[1].yo = 0;
+        fsnap[0].obase = fsnap[1].obase = 0;
+        int base_unit = -1;  // unit whose offsets are cached (uniform per block)
+        long long v_base = 0, o_base = 0;
 
         // this thread's three V items (of 4 rows x 24 columns x 8 octets): a wave covers,
         // per item, 8 consecutive columns (two quads) of one row with all 64 channels
@@ -324,7 +331,12 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
             constexpr int slot = decltype(slot_c)::value;
             const int xs0 = cu.strip * kStripW;
-            const bf16_t* vb = v + static_cast<size_t>(cu.unit) * p.N * D;
+            if (cu.unit != base_unit) {
+                base_unit = cu.unit;
+                v_base = unit_offset(cu.unit, heads, p.in);
+                o_base = unit_offset(cu.unit, heads, p.out);
+            }
+            const bf16_t* vb = v + v_base;
             const int row_base = cu.y0 - RAD + 4 * cu.t;
             uint32_t ok = 0;
             if constexpr (DW) {
@@ -334,10 +346,11 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     if (gy >= 0 && gy < H && gx >= 0 && gx < W) ok |= 1u << it;
                     const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), W - 1);
                     async_load16(vreg[slot][it], vb,
-                                 static_cast<uint32_t>((cy * W + cx) * (D * 2) + v_oct * 16));
+                                 static_cast<uint32_t>(cy * W + cx) * in_tok + v_oct * 16);
                 }
             }
             okmask[slot] = ok;
+            snap[slot].obase = o_base;
             snap[slot].unit = cu.unit;
             snap[slot].xs0 = xs0;
             snap[slot].yo = cu.yo(NCH);
@@ -371,7 +384,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             for (int it = 0; it < 2; ++it) {
                 const int x = fs.xs0 + (lane >> 3) + 8 * it;
                 if (y < H && x < W)
-                    store16_stream(ou + static_cast<uint32_t>((y * W + x) * (D * 2) + (lane & 7) * 16),
+                    store16_stream(ou + (static_cast<uint32_t>(y * W + x) * out_tok + (lane & 7) * 16),
                                    line[it][0], line[it][1], line[it][2], line[it][3]);
             }
         };
@@ -395,7 +408,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 __builtin_amdgcn_wave_barrier();
             }
             if (fs.computes) {
-                unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(fs.unit) * p.N * D);
+                unsigned char* ou = reinterpret_cast<unsigned char*>(out + fs.obase);
                 store_out_row(ou, fs, line);
             }
             if constexpr (DW) {
@@ -445,7 +458,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         // the last two tiles: a pass with nothing to stage but the stores
         auto flush_only = [&](const StageSnap& fs, const unsigned char* ot) {
             if (!fs.computes) return;
-            unsigned char* ou = reinterpret_cast<unsigned char*>(out + static_cast<size_t>(fs.unit) * p.N * D);
+            unsigned char* ou = reinterpret_cast<unsigned char*>(out + fs.obase);
             u32x4_t line[2];
             load_out_row(ot, line);
             store_out_row(ou, fs, line);
@@ -476,6 +489,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         u32x4_t qreg[PD][2];
         bool qok[PD];
         StageSnap snap[PD];
+        int base_unit = -1;
+        long long q_base = 0;
 
         auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
             constexpr int slot = decltype(slot_c)::value;
@@ -484,8 +499,12 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 const int y = cu.yo(NCH) + c, x = xs0 + tl;
                 qok[slot] = cu.computes(NCH) && y < H && x < W;
                 const int cy = min(max(y, 0), H - 1), cx = min(x, W - 1);
-                const uint32_t off = static_cast<uint32_t>((cy * W + cx) * (D * 2) + g * 16);
-                const bf16_t* qb = q + static_cast<size_t>(cu.unit) * p.N * D;
+                const uint32_t off = static_cast<uint32_t>(cy * W + cx) * in_tok + g * 16;
+                if (cu.unit != base_unit) {
+                    base_unit = cu.unit;
+                    q_base = unit_offset(cu.unit, heads, p.in);
+                }
+                const bf16_t* qb = q + q_base;
                 async_load16_stream(qreg[slot][0], qb, off);
                 async_load16_stream(qreg[slot][1], qb, off + 64);
             }

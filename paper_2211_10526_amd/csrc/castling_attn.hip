@@ -48,6 +48,8 @@ struct castling_attn {
     int units;
     int n_split;
     int chunk;
+    TensorStrides in_st, out_st;  // element strides of q/k/v and of out (defaults resolved)
+    size_t in_span, out_span;     // bytes from the first to one past the last element addressed
     int state_size;     // floats per unit
     bool mfma_reduce;   // bf16: K_hat^T V on the matrix cores
     bool mfma_apply;    // bf16, d = 64: q.S and the DWConv on the matrix cores
@@ -73,7 +75,7 @@ void launch_reduce_generic(castling_attn* h, const void* k, const void* v, hipSt
 {
     hipLaunchKernelGGL((reduce_generic_kernel<T, D>), dim3(h->n_split, h->units), dim3(256), 0, s,
                        static_cast<const T*>(k), static_cast<const T*>(v), h->partial, h->desc.N,
-                       h->n_split, h->chunk, h->desc.eps);
+                       h->n_split, h->chunk, h->desc.eps, h->desc.heads, h->in_st);
 }
 
 // w != nullptr: extra grid rows build the DWConv weight operand table.
@@ -98,7 +100,7 @@ void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const vo
     hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(h->n_split, h->units + wrows),
                        dim3(64 * kReduceWaves), 0, s, static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), h->partial, h->desc.N, h->n_split, h->chunk,
-                       h->desc.eps, ex);
+                       h->desc.eps, h->desc.heads, h->in_st, ex);
 }
 
 template <int D>
@@ -169,6 +171,8 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
     p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
     p.eps = d.eps;
+    p.in = h->in_st;
+    p.out = h->out_st;
     const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
     hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, h->units),
                        dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
@@ -197,6 +201,8 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     p.do_linear = LIN;
     p.do_dwconv = DW;
     p.eps = d.eps;
+    p.in = h->in_st;
+    p.out = h->out_st;
     if (DW && w) {
         const int threads = d.heads * 4 * KS * 3 * 64;
         hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
@@ -276,8 +282,8 @@ int check_apply_args(castling_attn_t h, const void* q, const void* v, const void
     if ((lin && !q) || (dw && (!v || !dw_weight))) return CASTLING_ERR_INVALID_ARG;
     if (misaligned(out) || (lin && misaligned(q)) || (dw && (misaligned(v) || misaligned(dw_weight))))
         return CASTLING_ERR_INVALID_ARG;
-    const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
-    if ((lin && overlaps(out, bytes, q, bytes)) || (dw && overlaps(out, bytes, v, bytes)))
+    if ((lin && overlaps(out, h->out_span, q, h->in_span)) ||
+        (dw && overlaps(out, h->out_span, v, h->in_span)))
         return CASTLING_ERR_ALIAS;
     return CASTLING_OK;
 }
@@ -317,6 +323,19 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     if (static_cast<int64_t>(d->B) * d->heads > 65535) return CASTLING_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(d->B) * d->heads * d->N * d->d > (int64_t(1) << 40))
         return CASTLING_ERR_UNSUPPORTED;
+    const int64_t es = static_cast<int64_t>(dtype_size(d->io_dtype));
+    const int64_t sets[2][3] = {{d->in_stride_b, d->in_stride_h, d->in_stride_n},
+                                {d->out_stride_b, d->out_stride_h, d->out_stride_n}};
+    for (const auto& s : sets) {
+        if (s[0] == 0 && s[1] == 0 && s[2] == 0) continue;  // contiguous default
+        for (int i = 0; i < 3; ++i)
+            if (s[i] <= 0 || (s[i] * es) % 16 != 0) return CASTLING_ERR_INVALID_ARG;
+        if (s[2] < d->d) return CASTLING_ERR_INVALID_ARG;
+        // the kernels address tokens of one unit with 32-bit byte offsets
+        if (s[2] > (int64_t(1) << 32) || d->N * s[2] * es >= (int64_t(1) << 32))
+            return CASTLING_ERR_UNSUPPORTED;
+        if (s[0] > (int64_t(1) << 40) || s[1] > (int64_t(1) << 40)) return CASTLING_ERR_UNSUPPORTED;
+    }
     return CASTLING_OK;
 }
 
@@ -333,6 +352,20 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     if (h->desc.branches == 0) h->desc.branches = CASTLING_BRANCH_ALL;
     if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
     h->units = desc->B * desc->heads;
+    {
+        const castling_attn_desc_t& d = h->desc;
+        const TensorStrides dense = {static_cast<long long>(d.heads) * d.N * d.d,
+                                     static_cast<long long>(d.N) * d.d, d.d};
+        h->in_st = d.in_stride_n ? TensorStrides{d.in_stride_b, d.in_stride_h, d.in_stride_n} : dense;
+        h->out_st =
+            d.out_stride_n ? TensorStrides{d.out_stride_b, d.out_stride_h, d.out_stride_n} : dense;
+        auto span = [&](const TensorStrides& s) {
+            return static_cast<size_t>((d.B - 1) * s.b + (d.heads - 1) * s.h + (d.N - 1) * s.n + d.d) *
+                   dtype_size(d.io_dtype);
+        };
+        h->in_span = span(h->in_st);
+        h->out_span = span(h->out_st);
+    }
     h->state_size = desc->d * desc->d + 2 * desc->d;
 
     // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 on the vector-ALU kernels (A/B measurements)
@@ -464,8 +497,7 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
     const castling_attn_desc_t& d = h->desc;
     if (d.branches & CASTLING_BRANCH_LINEAR) {
         if (!k || !v || misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
-        const size_t bytes = static_cast<size_t>(h->units) * d.N * d.d * dtype_size(d.io_dtype);
-        if (overlaps(out, bytes, k, bytes) || overlaps(out, bytes, v, bytes))
+        if (overlaps(out, h->out_span, k, h->in_span) || overlaps(out, h->out_span, v, h->in_span))
             return CASTLING_ERR_ALIAS;
         // the combine launch also prepares the weight operands of the MFMA apply kernel
         const bool fuse_w = h->mfma_apply && (d.branches & CASTLING_BRANCH_DWCONV);

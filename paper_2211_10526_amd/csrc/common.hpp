@@ -69,6 +69,17 @@ __device__ __forceinline__ float group_sum(float x)
     return x;
 }
 
+// Element strides of a [B][heads][N][d] tensor view; the d axis is contiguous.
+struct TensorStrides {
+    long long b, h, n;
+};
+
+// element offset of token 0 of unit = b * heads + h
+__device__ __forceinline__ long long unit_offset(int unit, int heads, const TensorStrides& s)
+{
+    return (unit / heads) * s.b + (unit % heads) * s.h;
+}
+
 // Floats per unit of the internal state: S = K_hat^T V (D x D, row-major), then
 // the K_hat column sum (D), then the V column sum (D).  N is known to the host.
 template <int D>

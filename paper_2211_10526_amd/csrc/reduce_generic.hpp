@@ -15,7 +15,8 @@ template <typename T, int D>
 __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict__ k,
                                                               const T* __restrict__ v,
                                                               float* __restrict__ partial, int N,
-                                                              int n_split, int chunk, float eps)
+                                                              int n_split, int chunk, float eps,
+                                                              int heads, TensorStrides st)
 {
     constexpr int VEC = IO<T>::VEC;  // elements per 16-byte load
     constexpr int LPR = D / VEC;     // lanes that share one token row
@@ -34,8 +35,8 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
     const int ti = tid / 16, tj = tid % 16;
     const int lrow = tid / LPR, lcol = (tid % LPR) * VEC;
 
-    const T* kb = k + static_cast<size_t>(unit) * N * D;
-    const T* vb = v + static_cast<size_t>(unit) * N * D;
+    const T* kb = k + unit_offset(unit, heads, st);
+    const T* vb = v + unit_offset(unit, heads, st);
 
     float acc[R][R];
     float ks[R], vs[R];
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
         const int n = n0 + lrow;
         float kx[VEC], vx[VEC];
         if (n < n_end) {
-            IO<T>::load16(kb + static_cast<size_t>(n) * D + lcol, kx);
-            IO<T>::load16(vb + static_cast<size_t>(n) * D + lcol, vx);
+            IO<T>::load16(kb + n * st.n + lcol, kx);
+            IO<T>::load16(vb + n * st.n + lcol, vx);
         } else {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) kx[e] = vx[e] = 0.f;

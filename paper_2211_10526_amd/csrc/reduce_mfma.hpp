@@ -101,7 +101,7 @@ struct ReduceExtras {
 template <int D>
 __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
-    int n_split, int chunk, float eps, ReduceExtras ex)
+    int n_split, int chunk, float eps, int heads, TensorStrides st, ReduceExtras ex)
 {
     if (static_cast<int>(blockIdx.y) >= ex.units) {  // weight rows (uniform per block)
         const int row = blockIdx.y - ex.units;
@@ -141,8 +141,9 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     const int w_begin = n_begin + wave * per_wave;
     const int w_end = min(n_end, w_begin + per_wave);
 
-    const bf16_t* kb = k + static_cast<size_t>(unit) * N * D;
-    const bf16_t* vb = v + static_cast<size_t>(unit) * N * D;
+    const bf16_t* kb = k + unit_offset(unit, heads, st);
+    const bf16_t* vb = v + unit_offset(unit, heads, st);
+    const uint32_t tok_bytes = static_cast<uint32_t>(st.n) * 2;  // the host keeps N * tok_bytes below 4 GiB
     unsigned char* ks_tile = lds + wave * 2 * TILE_BYTES;
     unsigned char* vs_tile = ks_tile + TILE_BYTES;
 
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
         uint32_t off[LOADS];
 #pragma unroll
         for (int j = 0; j < LOADS; ++j)
-            off[j] = static_cast<uint32_t>(min(n0 + j * TPL + lrow, N - 1)) * (D * 2) + lane_off;
+            off[j] = static_cast<uint32_t>(min(n0 + j * TPL + lrow, N - 1)) * tok_bytes + lane_off;
         // all K loads first, then all V loads: process() waits for them in this order
 #pragma unroll
         for (int j = 0; j < LOADS; ++j) async_load16_stream(kraw[slot][j], kb, off[j]);

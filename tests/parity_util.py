@@ -33,5 +33,31 @@ def gpu_forward(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0, want_
     return (res, st) if want_state else res
 
 
+def gpu_forward_fused(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0, want_state=False,
+                      pad=0):
+    """As gpu_forward, with projection-adjacent layouts: q, k, v are the slices of one fused
+    [B][N][3][heads][d (+ pad)] tensor and out is [B][N][heads * d].  Only data movement
+    happens here; the result comes back as float64 [B,heads,N,d]."""
+    dev = torch.device("cuda:0")
+    B, H, N, d = wl.B, wl.heads, wl.N, wl.d
+    dp = d + pad
+    qkv = torch.full((B, N, 3, H, dp), float("nan"), dtype=x["q"].dtype, device=dev)
+    for i, n in enumerate(("q", "k", "v")):
+        qkv[:, :, i, :, :d] = x[n].to(dev).permute(0, 2, 1, 3)  # [B,H,N,d] -> [B,N,H,d]
+    q, k, v = (qkv[:, :, i, :, :d] for i in range(3))
+    w = x["w"].to(dev)
+    bias = None if x["bias"] is None else x["bias"].to(dev)
+    out = torch.full((B, N, H * d), float("nan"), dtype=x["q"].dtype, device=dev)
+    attn = b.CastlingAttn.for_workload(
+        wl, norm=norm, branches=branches, eps=eps,
+        in_strides=(N * 3 * H * dp, dp, 3 * H * dp), out_strides=b.token_major_strides(H, N, d))
+    attn.forward(q, k, v, w, bias, out)
+    torch.cuda.synchronize()
+    res = inputs.to_f64(out.view(B, N, H, d).permute(0, 2, 1, 3).contiguous())
+    st = attn.get_state() if want_state else None
+    attn.destroy()
+    return (res, st) if want_state else res
+
+
 def oracle_inputs(x):
     return tuple(inputs.to_f64(x[n]) for n in ("q", "k", "v", "w", "bias"))

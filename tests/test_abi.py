@@ -55,6 +55,28 @@ def test_validate_rejects(field, value, status):
     assert b.validate(d) == status
 
 
+def test_validate_strides():
+    B, H, N, d = 2, 4, 196, 64
+    fused = b.fused_qkv_strides(H, N, d)
+    tok = b.token_major_strides(H, N, d)
+    mk = lambda ins, outs: b.make_desc(B, H, N, d, 14, 14, 3, "bf16", in_strides=ins, out_strides=outs)
+    assert b.validate(mk(fused, tok)) == b.OK
+    assert b.validate(mk(fused, None)) == b.OK
+    assert b.validate(mk(None, tok)) == b.OK
+    assert b.validate(mk((H * N * d, N * d, d), (H * N * d, N * d, d))) == b.OK
+    # not a multiple of 16 bytes, negative, partly zero, token stride below d
+    assert b.validate(mk((fused[0], fused[1], fused[2] + 4), None)) == b.ERR_INVALID_ARG
+    assert b.validate(mk((fused[0], -64, fused[2]), None)) == b.ERR_INVALID_ARG
+    assert b.validate(mk((0, fused[1], fused[2]), None)) == b.ERR_INVALID_ARG
+    assert b.validate(mk(None, (tok[0], tok[1], 32))) == b.ERR_INVALID_ARG
+    # fp32 rows need 4-element multiples only
+    f = b.make_desc(B, H, N, 32, 14, 14, 3, "f32", in_strides=(N * 3 * H * 36, 36, 3 * H * 36))
+    assert b.validate(f) == b.OK
+    # one unit's tokens must stay inside 32-bit byte offsets
+    big = b.make_desc(1, 1, 16384, 64, 128, 128, 3, "bf16", in_strides=(1 << 34, 64, 1 << 18))
+    assert b.validate(big) == b.ERR_UNSUPPORTED
+
+
 def test_validate_null_and_strerror():
     L = b.lib()
     assert L.castling_attn_validate(None) == b.ERR_INVALID_ARG

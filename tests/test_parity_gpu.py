@@ -9,7 +9,7 @@ import torch
 from paper_2211_10526_amd import binding as b
 from paper_2211_10526_amd import inputs
 from paper_2211_10526_amd.inputs import Workload
-from parity_util import TOL, gpu_forward, oracle_inputs, rel_err
+from parity_util import TOL, gpu_forward, gpu_forward_fused, oracle_inputs, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -46,6 +46,39 @@ def test_small_against_definition(oracle, wl, norm):
         got = gpu_forward(wl, x, norm=norm, branches=branches)
         assert np.isfinite(got).all()
         assert rel_err(got, want) <= TOL[wl.dtype], (wl.name, norm, branches)
+
+
+# projection-adjacent layouts: q, k, v as slices of a fused [B][N][3][heads][d] tensor, out
+# as [B][N][heads * d]; every kernel family (fp32 / bf16 vector-ALU, matrix-core) is covered
+STRIDED = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[9], SMALL[10], SMALL[11],
+           Workload("s_bf16_d64_40x40_k5_b3", "bf16", 3, 5, 64, 40, 40, 5)]
+
+
+@pytest.mark.parametrize("wl", STRIDED, ids=lambda w: w.name)
+def test_fused_qkv_layout(oracle, wl):
+    x = inputs.make_inputs(wl, seed=21, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    print(f"case fused layout {wl.name}", flush=True)
+    want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
+    got, st = gpu_forward_fused(wl, x, want_state=True)
+    assert np.isfinite(got).all()
+    assert rel_err(got, want) <= TOL[wl.dtype]
+    # the same kernels in the same order: bitwise equal to the contiguous layout
+    dense, st_dense = gpu_forward(wl, x, want_state=True)
+    assert np.array_equal(got, dense)
+    assert np.array_equal(st, st_dense)
+    for branches in (b.BRANCH_LINEAR, b.BRANCH_DWCONV):
+        assert np.array_equal(gpu_forward_fused(wl, x, branches=branches),
+                              gpu_forward(wl, x, branches=branches))
+
+
+def test_padded_token_rows(oracle):
+    # token stride larger than the packed row; the padding holds NaN and must never be read
+    for wl in (SMALL[3], SMALL[0]):
+        x = inputs.make_inputs(wl, seed=22)
+        print(f"case padded rows {wl.name}", flush=True)
+        got = gpu_forward_fused(wl, x, pad=8)
+        assert np.array_equal(got, gpu_forward(wl, x))
 
 
 @pytest.mark.parametrize("wl", SMALL[:6] + SMALL[10:12], ids=lambda w: w.name)
