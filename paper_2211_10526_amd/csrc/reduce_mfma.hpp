@@ -23,7 +23,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 
-constexpr int kReduceWaves = 4;
+#ifndef CASTLING_REDUCE_WAVES
+#define CASTLING_REDUCE_WAVES 4
+#endif
+constexpr int kReduceWaves = CASTLING_REDUCE_WAVES;
 constexpr int kReduceIterTokens = 32;  // tokens one wave stages per iteration
 #ifndef CASTLING_REDUCE_PREFETCH
 #define CASTLING_REDUCE_PREFETCH 2
