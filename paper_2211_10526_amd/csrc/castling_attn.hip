@@ -13,6 +13,7 @@
 #include "apply_generic.hpp"
 #include "apply_mfma.hpp"
 #include "common.hpp"
+#include "fused_small.hpp"
 #include "reduce_generic.hpp"
 #include "reduce_mfma.hpp"
 
@@ -53,6 +54,7 @@ struct castling_attn {
     int state_size;     // floats per unit
     bool mfma_reduce;   // bf16: K_hat^T V on the matrix cores
     bool mfma_apply;    // bf16, d = 64: q.S and the DWConv on the matrix cores
+    bool fused;         // forward() runs the one-kernel path (small N)
     int num_cus;        // compute units of the device
     size_t apply_lds;   // dynamic LDS of the apply kernel
     // workspace (one allocation)
@@ -265,6 +267,52 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
                : apply_generic_ks<bf16_t, 64>(h, launch, q, v, w, bias, out, s);
 }
 
+// ------------------------------------------------------------------ one-kernel path
+template <int KS, bool LIN, bool DW>
+hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const void* k,
+                          const void* v, const void* w, const void* bias, void* out, hipStream_t s)
+{
+    if (!launch)
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_small_kernel<KS, LIN, DW>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    const castling_attn_desc_t& d = h->desc;
+    FusedParams p;
+    p.N = d.N;
+    p.grid_h = d.grid_h;
+    p.grid_w = d.grid_w;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.eps = d.eps;
+    p.in = h->in_st;
+    p.out = h->out_st;
+    hipLaunchKernelGGL((fused_small_kernel<KS, LIN, DW>), dim3(h->units), dim3(256), kFusedLdsBytes,
+                       s, static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(w),
+                       static_cast<const bf16_t*>(bias), h->state, static_cast<bf16_t*>(out),
+                       d.heads, p);
+    return hipGetLastError();
+}
+
+template <int KS>
+hipError_t fused_ks(castling_attn* h, bool launch, const void* q, const void* k, const void* v,
+                    const void* w, const void* bias, void* out, hipStream_t s)
+{
+    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
+    if (lin && dw) return fused_branches<KS, true, true>(h, launch, q, k, v, w, bias, out, s);
+    if (lin) return fused_branches<KS, true, false>(h, launch, q, k, v, w, bias, out, s);
+    return fused_branches<KS, false, true>(h, launch, q, k, v, w, bias, out, s);
+}
+
+hipError_t do_fused(castling_attn* h, bool launch, const void* q, const void* k, const void* v,
+                    const void* w, const void* bias, void* out, hipStream_t s)
+{
+    switch (h->desc.dw_kernel) {
+        case 1: return fused_ks<1>(h, launch, q, k, v, w, bias, out, s);
+        case 3: return fused_ks<3>(h, launch, q, k, v, w, bias, out, s);
+        default: return fused_ks<5>(h, launch, q, k, v, w, bias, out, s);
+    }
+}
+
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
@@ -373,6 +421,10 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     const bool allow_mfma = desc->io_dtype == CASTLING_BF16 && !(force && force[0] == '1');
     h->mfma_reduce = allow_mfma;
     h->mfma_apply = allow_mfma && desc->d == 64;
+    // CASTLING_ATTN_NO_FUSED=1 keeps forward() on the two-pass path at small N (A/B measurements)
+    const char* nofuse = getenv("CASTLING_ATTN_NO_FUSED");
+    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs &&
+               !(nofuse && nofuse[0] == '1');
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
     // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
@@ -396,6 +448,8 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         e = hipDeviceGetAttribute(&h->num_cus, hipDeviceAttributeMultiprocessorCount, h->device);
     if (e == hipSuccess && h->num_cus < 1) h->num_cus = 1;
     if (e == hipSuccess) e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    if (e == hipSuccess && h->fused)
+        e = do_fused(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
     if (e == hipSuccess) {
         int max_lds = 0;
         e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
@@ -499,6 +553,10 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
         if (!k || !v || misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
         if (overlaps(out, h->out_span, k, h->in_span) || overlaps(out, h->out_span, v, h->in_span))
             return CASTLING_ERR_ALIAS;
+        if (h->fused) {
+            HIP_TRY(do_fused(h, true, q, k, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
+            return CASTLING_OK;
+        }
         // the combine launch also prepares the weight operands of the MFMA apply kernel
         const bool fuse_w = h->mfma_apply && (d.branches & CASTLING_BRANCH_DWCONV);
         st = do_reduce(h, k, v, fuse_w ? dw_weight : nullptr, static_cast<hipStream_t>(stream));
@@ -507,6 +565,10 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
             HIP_TRY(do_apply(h, true, q, v, nullptr, dw_bias, out, static_cast<hipStream_t>(stream)));
             return CASTLING_OK;
         }
+    }
+    if (h->fused) {  // convolution branch alone
+        HIP_TRY(do_fused(h, true, q, k, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
+        return CASTLING_OK;
     }
     return castling_attn_apply(h, q, v, dw_weight, dw_bias, out, stream);
 }

@@ -161,6 +161,12 @@ __device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t
     asm volatile("s_waitcnt vmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(YOUNGER) : "memory");
 }
 template <int YOUNGER>
+__device__ __forceinline__ void wait_async_loads(u32x4_t& a)
+{
+    static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%1)" : "+v"(a) : "n"(YOUNGER) : "memory");
+}
+template <int YOUNGER>
 __device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b)
 {
     static_assert(YOUNGER >= 0 && YOUNGER < 64, "vmcnt is a 6-bit counter");

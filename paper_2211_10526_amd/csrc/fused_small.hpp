@@ -1,0 +1,458 @@
+// The whole layer in one kernel for units whose tokens fit on chip (bf16, d = 64,
+// N <= 256, filter size <= 5): one block per unit loads K, V, Q once, builds the state
+// K_hat^T V, sum k_hat, sum v on the matrix cores (Sec. 3.1 reassociation, sums of Eq. 3),
+// keeps it in LDS as MFMA operands, applies it to the unit's own queries (Eq. 3 with the
+// linear terms of Eq. 8) and adds the depthwise convolution of V read from LDS (Eq. 9).
+// At these sizes the state (17 KB fp32 + 10 KB of operands per unit) is as large as a
+// tensor of the unit (25 KB at N = 196), so keeping it on chip and launching once halves
+// the time of the two-pass path.
+//
+// Block = 4 waves, two blocks per compute unit.  Every global load of the unit is issued at
+// the start (inline global_load, explicit s_waitcnt vmcnt) and consumed in issue order:
+//   phase 1  wave w normalises and stages tokens 64 w .. 64 w + 63 (V rows stay in LDS for
+//            the convolution), accumulates K_hat^T V with v_mfma_f32_32x32x16_bf16;
+//            column sums and a fixed tree over the waves as in reduce_mfma_kernel;
+//   phase 2  S / pi, ksum / pi, vsum / 2, filters and bias go to LDS tables;
+//   phase 3  per chunk of 64 tokens: wave w computes the linear branch of 16 tokens
+//            (v_mfma_f32_16x16x32_bf16) into an fp32 LDS tile; then every thread adds the
+//            convolution for 8 channels of a token on the vector ALU and stores 16 bytes,
+//            8 lanes per 128-byte output line.
+#pragma once
+
+#include "apply_mfma.hpp"
+#include "common.hpp"
+#include "reduce_mfma.hpp"
+#include "tables.hpp"
+
+namespace castling {
+
+constexpr int kFusedMaxTokens = 256;
+constexpr int kFusedMaxKs = 5;
+constexpr int kFusedPitch = 160;  // bytes per token row of the V and k_hat tiles (bank spread)
+constexpr int kFusedVBytes = kFusedMaxTokens * kFusedPitch;
+constexpr int kFusedKtileBytes = 32 * kFusedPitch;  // per wave
+constexpr int kFusedLinPitch = 68;                  // floats per token row of the linear tile
+// k_hat staging, then column-sum scratch, then the linear tile share one region
+constexpr int kFusedUnionBytes = 4 * kFusedKtileBytes;
+static_assert(kFusedUnionBytes >= 64 * kFusedLinPitch * 4, "linear tile");
+static_assert(kFusedUnionBytes >= 4 * 64 * 16 * 4, "column-sum scratch");
+constexpr int kFusedSfragOff = kFusedVBytes + kFusedUnionBytes;  // 4 x 2 x 64 x 16 bytes
+constexpr int kFusedKfragOff = kFusedSfragOff + 8192;            // 2 x 64 x 16 bytes
+constexpr int kFusedVhalfOff = kFusedKfragOff + 2048;            // 64 floats
+constexpr int kFusedBiasOff = kFusedVhalfOff + 256;              // 64 floats
+constexpr int kFusedWOff = kFusedBiasOff + 256;                  // [tap][channel] floats
+constexpr int kFusedLdsBytes = kFusedWOff + kFusedMaxKs * kFusedMaxKs * 64 * 4;
+// the reduction tree (2 slots of one wave's accumulators) overlays the union region and the
+// tables behind it, all of which are written only after the tree
+static_assert(kFusedVBytes + 2 * 16384 <= kFusedLdsBytes, "tree scratch");
+static_assert(2 * kFusedLdsBytes <= 160 * 1024, "two blocks per compute unit");
+
+struct FusedParams {
+    int N, grid_h, grid_w;
+    int norm_none;
+    float eps;
+    TensorStrides in, out;
+};
+
+// grid = (units), block = 256, dynamic LDS = kFusedLdsBytes.
+// state: [units][StateLayout<64>::SIZE] fp32 copy of the state (nullptr = not wanted).
+template <int KS, bool LIN, bool DW>
+__global__ __launch_bounds__(256, 2) void fused_small_kernel(
+    const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
+    const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias, float* __restrict__ state,
+    bf16_t* __restrict__ out, int heads, FusedParams p)
+{
+    static_assert(KS <= kFusedMaxKs && (KS & 1), "filter size");
+    constexpr int D = 64;
+    constexpr int RAD = KS / 2;
+    constexpr int PITCH = kFusedPitch;
+    constexpr int LP = kFusedLinPitch;
+    using L = StateLayout<D>;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    unsigned char* const vtile = lds;
+    unsigned char* const un = lds + kFusedVBytes;
+    float* const wl = reinterpret_cast<float*>(lds + kFusedWOff);
+    float* const bl = reinterpret_cast<float*>(lds + kFusedBiasOff);
+    float* const vhalf = reinterpret_cast<float*>(lds + kFusedVhalfOff);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int unit = blockIdx.x;
+    const int head = unit % heads;
+    const int N = p.N, W = p.grid_w, H = p.grid_h;
+    const uint32_t in_tok = static_cast<uint32_t>(p.in.n) * 2;
+    const uint32_t out_tok = static_cast<uint32_t>(p.out.n) * 2;
+    const long long in_off = unit_offset(unit, heads, p.in);
+    const bf16_t* const qb = q + in_off;
+    const bf16_t* const kb = k + in_off;
+    const bf16_t* const vb = v + in_off;
+
+    const int lrow = lane >> 3;        // token inside one wave-wide load of 8 token rows
+    const int lcol = (lane & 7) * 8;   // first of this lane's 8 features
+    const int tl = lane & 15, g = lane >> 4;
+
+    // ---- every global load of the unit, in the order in which it is consumed.  Addresses
+    // past the unit are clamped to valid ones, so each wave issues the same number of loads
+    // and the counts below hold.
+    constexpr int NK = LIN ? 4 : 0;          // K loads per iteration of 32 tokens
+    constexpr int PER_IT = NK + 4;
+    constexpr int NWB = DW ? 2 : 0;          // filters, bias
+    constexpr int NQ = LIN ? 8 : 0;          // 2 per chunk of 64 tokens
+    u32x4_t kraw[2][4], vraw[2][4], qraw[4][2], wraw, braw;
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int n0 = 64 * wave + 32 * it;
+        uint32_t off[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            off[j] = static_cast<uint32_t>(min(n0 + 8 * j + lrow, N - 1)) * in_tok + lcol * 2;
+        if constexpr (LIN) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) async_load16_stream(kraw[it][j], kb, off[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) async_load16(vraw[it][j], vb, off[j]);
+    }
+    constexpr int W_CHUNKS = KS * KS * 8;  // 16-byte pieces of one head's filters
+    if constexpr (DW) {
+        const bf16_t* wh = w + static_cast<size_t>(head) * D * KS * KS;
+        async_load16(wraw, wh, static_cast<uint32_t>(min(tid, W_CHUNKS - 1)) * 16);
+        // without a bias the load still happens (from the filters) and its value is dropped
+        const bf16_t* bh = bias ? bias + head * D : wh;
+        async_load16(braw, bh, static_cast<uint32_t>(tid & 7) * 16);
+    }
+    if constexpr (LIN) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int tok = min(64 * c + 16 * wave + tl, N - 1);
+            const uint32_t off = static_cast<uint32_t>(tok) * in_tok + g * 16;
+            async_load16_stream(qraw[c][0], qb, off);
+            async_load16_stream(qraw[c][1], qb, off + 64);
+        }
+    }
+
+    // ---- phase 1: normalise K, stage k_hat and V, accumulate K_hat^T V
+    f32x16_t acc[2][2];
+    float ksum[8], vsum[8];
+    if constexpr (LIN) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ksum[e] = vsum[e] = 0.f;
+    }
+    const float inv_eps = 1.0f / p.eps;
+    unsigned char* const ktile = un + wave * kFusedKtileBytes;
+
+    static_for<2>([&](auto it_c) {
+        constexpr int it = decltype(it_c)::value;
+        constexpr int YOUNGER = (1 - it) * PER_IT + NWB + NQ;  // loads issued after this iteration's
+        const int n0 = 64 * wave + 32 * it;
+        if constexpr (LIN)
+            wait_async_loads<YOUNGER + 4>(kraw[it][0], kraw[it][1], kraw[it][2], kraw[it][3]);
+        wait_async_loads<YOUNGER>(vraw[it][0], vraw[it][1], vraw[it][2], vraw[it][3]);
+        if (n0 >= N) return;  // uniform per wave
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = 8 * j + lrow;
+            const bool in = n0 + row < N;
+            const u32x4_t zero = {0u, 0u, 0u, 0u};
+            const u32x4_t vw = in ? vraw[it][j] : zero;
+            *reinterpret_cast<u32x4_t*>(vtile + (n0 + row) * PITCH + lcol * 2) = vw;
+            if constexpr (LIN) {
+                const u32x4_t kw = in ? kraw[it][j] : zero;
+                float kf[8];
+                float ss = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    kf[2 * i] = __uint_as_float(kw[i] << 16);
+                    kf[2 * i + 1] = __uint_as_float(kw[i] & 0xffff0000u);
+                    ss = fmaf(kf[2 * i], kf[2 * i], ss);
+                    ss = fmaf(kf[2 * i + 1], kf[2 * i + 1], ss);
+                    vsum[2 * i] += __uint_as_float(vw[i] << 16);
+                    vsum[2 * i + 1] += __uint_as_float(vw[i] & 0xffff0000u);
+                }
+                ss = row_group_sum<8>(ss);
+                // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
+                const float inv = fminf(__builtin_amdgcn_rsqf(ss), inv_eps);
+                u32x4_t kh;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float a = kf[2 * i] * inv, b = kf[2 * i + 1] * inv;
+                    ksum[2 * i] += a;
+                    ksum[2 * i + 1] += b;
+                    kh[i] = pack_bf16x2(a, b);
+                }
+                *reinterpret_cast<u32x4_t*>(ktile + row * PITCH + lcol * 2) = kh;
+            }
+        }
+        if constexpr (LIN) {
+            // LDS operations of one wave complete in issue order; these 32 rows of both tiles
+            // are written by this wave only
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                bf16x8_t a[2], b[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    a[t] = lds_operand_tr(ktile, PITCH, 16 * s, 32 * t, lane);
+                    b[t] = lds_operand_tr(vtile + n0 * PITCH, PITCH, 16 * s, 32 * t, lane);
+                }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[mt][nt] =
+                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    });
+    __syncthreads();  // V is staged; the k_hat tiles are dead
+
+    if constexpr (LIN) {
+        // ---- column sums: every lane's 16 partial sums go through LDS, summed in lane order
+        float* sums = reinterpret_cast<float*>(un);  // [wave][lane][16]
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            sums[(wave * 64 + lane) * 16 + e] = ksum[e];
+            sums[(wave * 64 + lane) * 16 + 8 + e] = vsum[e];
+        }
+        __syncthreads();
+        float colsum = 0.f;  // tid < 64: ksum[tid]; tid < 128: vsum[tid - 64]
+        if (tid < 2 * D) {
+            const int which = tid / D, f = tid % D;
+            const int lc = f / 8, e = f % 8;
+            for (int wv = 0; wv < 4; ++wv)
+                for (int r = 0; r < 8; ++r)
+                    colsum += sums[(wv * 64 + r * 8 + lc) * 16 + which * 8 + e];
+            if (state)
+                state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f] = colsum;
+        }
+        __syncthreads();
+
+        // ---- K_hat^T V: fixed tree over the waves, (w0 + w2) + (w1 + w3)
+        f32x4_t* tree = reinterpret_cast<f32x4_t*>(un);
+        constexpr int SLOT = 2 * 2 * 4 * 64;  // float4 per slot
+#pragma unroll
+        for (int half = 2; half >= 1; half >>= 1) {
+            if (wave >= half && wave < 2 * half) {
+                f32x4_t* dst = tree + (wave - half) * SLOT + lane;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            f32x4_t q4;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) q4[e] = acc[mt][nt][4 * r4 + e];
+                            dst[((mt * 2 + nt) * 4 + r4) * 64] = q4;
+                        }
+            }
+            __syncthreads();
+            if (wave < half) {
+                const f32x4_t* src = tree + wave * SLOT + lane;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const f32x4_t q4 = src[((mt * 2 + nt) * 4 + r4) * 64];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[mt][nt][4 * r4 + e] += q4[e];
+                        }
+            }
+            __syncthreads();
+        }
+
+        // ---- phase 2: operand tables of the linear branch (same layouts as sfrag / kfrag)
+        float* ksumf = reinterpret_cast<float*>(un);
+        if (tid < D) ksumf[tid] = colsum;
+        else if (tid < 2 * D) vhalf[tid - D] = 0.5f * colsum;
+        if (wave == 0) {
+            uint32_t* sf = reinterpret_cast<uint32_t*>(lds + kFusedSfragOff);
+            float* st = state ? state + static_cast<size_t>(unit) * L::SIZE + L::S : nullptr;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int i = 32 * mt + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
+                        const int j = 32 * nt + (lane % 32);
+                        if (st) st[i * D + j] = acc[mt][nt][r];
+                        if ((r & 1) == 0) {
+                            const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
+                                          ((i & 7) >> 1);
+                            sf[t] = pack_bf16x2(acc[mt][nt][r] * kInvPi, acc[mt][nt][r + 1] * kInvPi);
+                        }
+                    }
+        }
+    }
+    if constexpr (DW) {
+        // filters [channel][tap] bf16 -> LDS [tap][channel] fp32; bias -> fp32
+        wait_async_loads<NQ + 1>(wraw);
+        if (tid < W_CHUNKS) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = 8 * tid + i;
+                const uint32_t word = wraw[i >> 1];
+                const float val = __uint_as_float((i & 1) ? (word & 0xffff0000u) : (word << 16));
+                wl[(e % (KS * KS)) * D + e / (KS * KS)] = val;
+            }
+        }
+        wait_async_loads<NQ>(braw);
+        if (tid < 8) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t word = braw[i >> 1];
+                const float val = __uint_as_float((i & 1) ? (word & 0xffff0000u) : (word << 16));
+                bl[8 * tid + i] = bias ? val : 0.f;
+            }
+        }
+    }
+    __syncthreads();
+    if constexpr (LIN) {
+        const float* ksumf = reinterpret_cast<const float*>(un);
+        uint32_t* kfr = reinterpret_cast<uint32_t*>(lds + kFusedKfragOff);
+        for (int u = tid; u < kKfragPerUnit / 2; u += 256) {
+            const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
+            const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
+            kfr[u] = pack_bf16x2(ksumf[i0] * kInvPi, ksumf[i0 + 1] * kInvPi);
+        }
+        __syncthreads();
+    }
+
+    // ---- phase 3
+    bf16x8_t sf[4][2], kf[2];
+    float vh[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (LIN) {
+        const uint4* s4 = reinterpret_cast<const uint4*>(lds + kFusedSfragOff);
+        const uint4* k4 = reinterpret_cast<const uint4*>(lds + kFusedKfragOff);
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
+            vh[nt] = vhalf[16 * nt + tl];
+        }
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
+    }
+    const float half_n = 0.5f * static_cast<float>(N);
+    float* const lin = reinterpret_cast<float*>(un);
+    unsigned char* const ob = reinterpret_cast<unsigned char*>(out + unit_offset(unit, heads, p.out));
+    const int oct = tid & 7;
+
+    static_for<4>([&](auto c_c) {
+        constexpr int c = decltype(c_c)::value;
+        if (64 * c >= N) return;  // uniform per block
+        if constexpr (LIN) {
+            wait_async_loads<2 * (3 - c)>(qraw[c][0], qraw[c][1]);
+            if (64 * c + 16 * wave < N) {  // uniform per wave
+                const bool qok = 64 * c + 16 * wave + tl < N;
+                const u32x4_t zero = {0u, 0u, 0u, 0u};
+                bf16x8_t a[2];
+                a[0] = __builtin_bit_cast(bf16x8_t, qok ? qraw[c][0] : zero);
+                a[1] = __builtin_bit_cast(bf16x8_t, qok ? qraw[c][1] : zero);
+                // |q_t|^2 on the matrix cores: the diagonal of Q Q^T
+                f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
+                f32x4_t ac[4], dk = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks)
+                    dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) ac[nt][r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        ac[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], ac[nt], 0, 0, 0);
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
+                    const float ssr = __int_as_float(
+                        __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
+                    const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                    float alpha, beta;
+                    if (p.norm_none) {
+                        alpha = inv;
+                        beta = 1.0f;
+                    } else {
+                        beta = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
+                        alpha = inv * beta;
+                    }
+                    float* row = lin + (16 * wave + 4 * g + r) * LP + tl;
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) row[16 * nt] = fmaf(alpha, ac[nt][r], beta * vh[nt]);
+                }
+            }
+            __syncthreads();
+        }
+        // convolution, sum of Eq. 9 and store: item = (token, 8 channels)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+            const int tloc = (tid >> 3) + 32 * h2;
+            const int t = 64 * c + tloc;
+            if (t < N) {
+                float o[8];
+                if constexpr (LIN) {
+                    const float4 l0 = *reinterpret_cast<const float4*>(lin + tloc * LP + 8 * oct);
+                    const float4 l1 = *reinterpret_cast<const float4*>(lin + tloc * LP + 8 * oct + 4);
+                    o[0] = l0.x; o[1] = l0.y; o[2] = l0.z; o[3] = l0.w;
+                    o[4] = l1.x; o[5] = l1.y; o[6] = l1.z; o[7] = l1.w;
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) o[i] = 0.f;
+                }
+                if constexpr (DW) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) o[i] += bl[8 * oct + i];
+                    const int y = t / W, x = t - y * W;
+#pragma unroll
+                    for (int dy = 0; dy < KS; ++dy) {
+                        const int yy = y + dy - RAD;
+#pragma unroll
+                        for (int dx = 0; dx < KS; ++dx) {
+                            const int xx = x + dx - RAD;
+                            const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
+                            const int tn = ok ? yy * W + xx : t;
+                            u32x4_t vw = *reinterpret_cast<const u32x4_t*>(vtile + tn * PITCH + oct * 16);
+                            const float* wt = wl + (dy * KS + dx) * D + 8 * oct;
+                            const float4 w0 = *reinterpret_cast<const float4*>(wt);
+                            const float4 w1 = *reinterpret_cast<const float4*>(wt + 4);
+                            const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+                            if (!ok) vw = u32x4_t{0u, 0u, 0u, 0u};
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                o[2 * i] = fmaf(wv[2 * i], __uint_as_float(vw[i] << 16), o[2 * i]);
+                                o[2 * i + 1] =
+                                    fmaf(wv[2 * i + 1], __uint_as_float(vw[i] & 0xffff0000u), o[2 * i + 1]);
+                            }
+                        }
+                    }
+                }
+                store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16), pack_bf16x2(o[0], o[1]),
+                               pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
+            }
+        }
+        if constexpr (LIN) {
+            if (64 * (c + 1) < N) __syncthreads();  // the next chunk overwrites the linear tile
+        }
+    });
+    // loads that were never waited for (chunks past N) must land before the registers die
+    if constexpr (LIN) wait_async_loads<0>(qraw[3][0], qraw[3][1]);
+}
+
+}  // namespace castling

@@ -31,7 +31,15 @@ SMALL = [
     Workload("s_bf16_d64_33x17_k9", "bf16", 3, 1, 64, 33, 17, 9),
     Workload("s_bf16_d32_18x18_k9", "bf16", 1, 2, 32, 18, 18, 9),
     Workload("s_f32_d64_6x6_k7", "f32", 1, 2, 64, 6, 6, 7),
+    # bf16, d = 64, N <= 256, k <= 5: forward() takes the one-kernel path; full and ragged
+    # chunks of 64 tokens, every filter size, a wave with no tokens at all
+    Workload("s_bf16_d64_16x16_k5", "bf16", 2, 3, 64, 16, 16, 5),
+    Workload("s_bf16_d64_14x14_k3", "bf16", 3, 3, 64, 14, 14, 3),
+    Workload("s_bf16_d64_8x9_k1", "bf16", 1, 2, 64, 8, 9, 1),
+    Workload("s_bf16_d64_5x13_k5", "bf16", 1, 5, 64, 5, 13, 5),
+    Workload("s_bf16_d64_2x50_k3", "bf16", 2, 1, 64, 2, 50, 3),
 ]
+ONE_KERNEL = [SMALL[3], SMALL[6], SMALL[8]] + SMALL[14:]
 
 
 @pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
@@ -50,7 +58,7 @@ def test_small_against_definition(oracle, wl, norm):
 
 # projection-adjacent layouts: q, k, v as slices of a fused [B][N][3][heads][d] tensor, out
 # as [B][N][heads * d]; every kernel family (fp32 / bf16 vector-ALU, matrix-core) is covered
-STRIDED = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[9], SMALL[10], SMALL[11],
+STRIDED = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[9], SMALL[10], SMALL[11], SMALL[15],
            Workload("s_bf16_d64_40x40_k5_b3", "bf16", 3, 5, 64, 40, 40, 5)]
 
 
@@ -81,7 +89,7 @@ def test_padded_token_rows(oracle):
         assert np.array_equal(got, gpu_forward(wl, x))
 
 
-@pytest.mark.parametrize("wl", SMALL[:6] + SMALL[10:12], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", SMALL[:6] + SMALL[10:12] + SMALL[14:16], ids=lambda w: w.name)
 def test_state_against_oracle(oracle, wl):
     x = inputs.make_inputs(wl, seed=12)
     _, k, v, _, _ = oracle_inputs(x)
@@ -203,8 +211,39 @@ def test_forced_generic_bf16_matches_oracle(oracle, monkeypatch):
     assert rel_err(got, want) <= TOL[wl.dtype]
 
 
+@pytest.mark.parametrize("wl", ONE_KERNEL, ids=lambda w: w.name)
+def test_two_pass_path_at_small_n(oracle, monkeypatch, wl):
+    """Shapes that forward() would run in one kernel, kept on the reduce + apply kernels."""
+    monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
+    x = inputs.make_inputs(wl, seed=23, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    print(f"case two-pass {wl.name}", flush=True)
+    want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
+    assert rel_err(gpu_forward(wl, x), want) <= TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("wl", ONE_KERNEL, ids=lambda w: w.name)
+def test_one_kernel_forward_agrees_with_reduce_apply(wl):
+    """forward() in one kernel against reduce() + apply() on the same handle: the same
+    arithmetic up to summation order, so they agree far inside the oracle tolerance."""
+    x = inputs.make_inputs(wl, seed=24, with_bias=True)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w", "bias")}
+    attn = b.CastlingAttn.for_workload(wl)
+    o1, o2 = torch.empty_like(t["q"]), torch.empty_like(t["q"])
+    print(f"case one-kernel vs two-pass {wl.name}", flush=True)
+    attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], o1)
+    s1 = attn.get_state()
+    attn.reduce(t["k"], t["v"])
+    attn.apply(t["q"], t["v"], t["w"], t["bias"], o2)
+    s2 = attn.get_state()
+    attn.destroy()
+    assert rel_err(inputs.to_f64(o1), inputs.to_f64(o2)) <= 2.0 ** -7  # two bf16 roundings apart
+    assert rel_err(s1, s2) <= 1e-5
+
+
 def test_reduce_then_apply_equals_forward():
-    wl = Workload("split_bf16", "bf16", 2, 2, 64, 9, 21, 5)
+    wl = Workload("split_bf16", "bf16", 2, 2, 64, 19, 21, 5)
     x = inputs.make_inputs(wl, seed=8)
     dev = torch.device("cuda:0")
     t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
@@ -219,7 +258,7 @@ def test_reduce_then_apply_equals_forward():
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
 
 
-@pytest.mark.parametrize("wl", [SMALL[0], SMALL[3]], ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", [SMALL[0], SMALL[10]], ids=lambda w: w.name)
 def test_apply_with_registered_weights(wl):
     x = inputs.make_inputs(wl, seed=18)
     dev = torch.device("cuda:0")
