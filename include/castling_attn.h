@@ -66,6 +66,11 @@ typedef enum {
 
 enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_ALL = 3 };
 
+/* desc.flags.  KEEP_STATE: castling_attn_forward always leaves the fp32 state in the workspace
+ * for castling_attn_get_state.  Without it a forward that keeps the state on chip (small N)
+ * does not spend memory writes on a copy nobody reads. */
+enum { CASTLING_FLAG_KEEP_STATE = 1 };
+
 typedef struct {
     int32_t B, heads, N, d;   /* d in {32, 64} */
     int32_t grid_h, grid_w;   /* N must equal grid_h * grid_w */
@@ -81,6 +86,7 @@ typedef struct {
      * addresses must not overlap each other. */
     int64_t in_stride_b, in_stride_h, in_stride_n;
     int64_t out_stride_b, out_stride_h, out_stride_n;
+    uint32_t flags;           /* bitmask of CASTLING_FLAG_* */
 } castling_attn_desc_t;
 
 /* Host-only check of a descriptor (no GPU needed).  Sec. 3.2.1 fixes the shapes:
@@ -124,7 +130,9 @@ size_t castling_attn_workspace_bytes(castling_attn_t h);
 /* Test/debug: copies the state of the last reduce to HOST memory as fp32
  * [B*heads][d+1][d+1] = [K_hat | 1]^T [V | 1] (row i < d: K_hat^T V row i then
  * ksum_i; row d: vsum then N).  Synchronises `stream`.  `bytes` must be exactly
- * B*heads*(d+1)*(d+1)*4. */
+ * B*heads*(d+1)*(d+1)*4.  CASTLING_ERR_INVALID_ARG if the workspace holds no state: nothing
+ * has run yet, or the last call was a forward that kept the state on chip and the handle
+ * was created without CASTLING_FLAG_KEEP_STATE. */
 int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream);
 
 /* Number of token splits per unit the reduce uses for this handle (>= 1). */

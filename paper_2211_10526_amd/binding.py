@@ -19,6 +19,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_ALIAS = 0, 1, 2, 3, 4
 F32, BF16 = 0, 1
 NORM_ROWSUM, NORM_NONE = 0, 1
 BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
+FLAG_KEEP_STATE = 1
 
 EXPORTS = (
     "castling_attn_validate", "castling_attn_create", "castling_attn_forward",
@@ -36,7 +37,7 @@ class Desc(C.Structure):
                 ("eps", C.c_float),
                 ("in_stride_b", C.c_int64), ("in_stride_h", C.c_int64), ("in_stride_n", C.c_int64),
                 ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64),
-                ("out_stride_n", C.c_int64)]
+                ("out_stride_n", C.c_int64), ("flags", C.c_uint32)]
 
 
 class CastlingError(RuntimeError):
@@ -99,7 +100,7 @@ def token_major_strides(heads, N, d):
 
 
 def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROWSUM,
-              branches=BRANCH_ALL, eps=0.0, in_strides=None, out_strides=None) -> Desc:
+              branches=BRANCH_ALL, eps=0.0, in_strides=None, out_strides=None, flags=0) -> Desc:
     """in_strides / out_strides: (batch, head, token) element strides of q, k, v and of out;
     None = contiguous [B][heads][N][d]."""
     if isinstance(io_dtype, str):
@@ -107,7 +108,7 @@ def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROW
     ins = tuple(in_strides) if in_strides is not None else (0, 0, 0)
     outs = tuple(out_strides) if out_strides is not None else (0, 0, 0)
     return Desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm, branches, eps,
-                *ins, *outs)
+                *ins, *outs, flags)
 
 
 def validate(desc: Desc) -> int:
@@ -136,9 +137,9 @@ class CastlingAttn:
 
     @classmethod
     def for_workload(cls, wl, norm=NORM_ROWSUM, branches=BRANCH_ALL, eps=0.0, in_strides=None,
-                     out_strides=None):
+                     out_strides=None, flags=0):
         return cls(make_desc(wl.B, wl.heads, wl.N, wl.d, wl.grid_h, wl.grid_w, wl.dw_kernel,
-                             wl.dtype, norm, branches, eps, in_strides, out_strides))
+                             wl.dtype, norm, branches, eps, in_strides, out_strides, flags))
 
     def forward(self, q, k, v, w, bias, out, stream=None):
         _check(lib().castling_attn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(w),

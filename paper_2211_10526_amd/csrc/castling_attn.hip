@@ -55,6 +55,7 @@ struct castling_attn {
     bool mfma_reduce;   // bf16: K_hat^T V on the matrix cores
     bool mfma_apply;    // bf16, d = 64: q.S and the DWConv on the matrix cores
     bool fused;         // forward() runs the one-kernel path (small N)
+    bool state_valid;   // the workspace holds the state of the last reduce
     int num_cus;        // compute units of the device
     size_t apply_lds;   // dynamic LDS of the apply kernel
     // workspace (one allocation)
@@ -118,6 +119,7 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
 {
     const bool f32 = h->desc.io_dtype == CASTLING_F32;
     const int d = h->desc.d;
+    h->state_valid = true;
     // with one split per unit the reduce kernel's result is final: it writes the state and
     // the apply kernel's operand tables itself, and no combine is launched
     const bool direct = h->mfma_apply && h->n_split == 1;
@@ -287,8 +289,10 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
     hipLaunchKernelGGL((fused_small_kernel<KS, LIN, DW>), dim3(h->units), dim3(256), kFusedLdsBytes,
                        s, static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(w),
-                       static_cast<const bf16_t*>(bias), h->state, static_cast<bf16_t*>(out),
-                       d.heads, p);
+                       static_cast<const bf16_t*>(bias),
+                       (d.flags & CASTLING_FLAG_KEEP_STATE) ? h->state : nullptr,
+                       static_cast<bf16_t*>(out), d.heads, p);
+    h->state_valid = (d.flags & CASTLING_FLAG_KEEP_STATE) != 0;
     return hipGetLastError();
 }
 
@@ -364,6 +368,7 @@ int castling_attn_validate(const castling_attn_desc_t* d)
         return CASTLING_ERR_INVALID_ARG;
     if (d->branches & ~static_cast<uint32_t>(CASTLING_BRANCH_ALL)) return CASTLING_ERR_INVALID_ARG;
     if (!(d->eps >= 0.0f)) return CASTLING_ERR_INVALID_ARG;
+    if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE)) return CASTLING_ERR_INVALID_ARG;
     if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16) return CASTLING_ERR_UNSUPPORTED;
     if (d->d != 32 && d->d != 64) return CASTLING_ERR_UNSUPPORTED;
     if (d->dw_kernel > 9) return CASTLING_ERR_UNSUPPORTED;
@@ -400,6 +405,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     if (h->desc.branches == 0) h->desc.branches = CASTLING_BRANCH_ALL;
     if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
     h->units = desc->B * desc->heads;
+    h->state_valid = false;
     {
         const castling_attn_desc_t& d = h->desc;
         const TensorStrides dense = {static_cast<long long>(d.heads) * d.N * d.d,
@@ -575,7 +581,7 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
 
 int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream)
 {
-    if (!h || !host_f32) return CASTLING_ERR_INVALID_ARG;
+    if (!h || !host_f32 || !h->state_valid) return CASTLING_ERR_INVALID_ARG;
     const int D = h->desc.d, D1 = D + 1;
     if (bytes != sizeof(float) * static_cast<size_t>(h->units) * D1 * D1)
         return CASTLING_ERR_INVALID_ARG;

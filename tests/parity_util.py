@@ -24,7 +24,8 @@ def gpu_forward(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0, want_
     t = {n: (None if x[n] is None else x[n].to(dev)) for n in ("q", "k", "v", "w", "bias")}
     out = torch.empty_like(t["q"])
     out.fill_(float("nan"))
-    attn = b.CastlingAttn.for_workload(wl, norm=norm, branches=branches, eps=eps)
+    attn = b.CastlingAttn.for_workload(wl, norm=norm, branches=branches, eps=eps,
+                                       flags=b.FLAG_KEEP_STATE if want_state else 0)
     attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], out)
     torch.cuda.synchronize()
     res = inputs.to_f64(out)
@@ -50,7 +51,8 @@ def gpu_forward_fused(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0,
     out = torch.full((B, N, H * d), float("nan"), dtype=x["q"].dtype, device=dev)
     attn = b.CastlingAttn.for_workload(
         wl, norm=norm, branches=branches, eps=eps,
-        in_strides=(N * 3 * H * dp, dp, 3 * H * dp), out_strides=b.token_major_strides(H, N, d))
+        in_strides=(N * 3 * H * dp, dp, 3 * H * dp), out_strides=b.token_major_strides(H, N, d),
+        flags=b.FLAG_KEEP_STATE if want_state else 0)
     attn.forward(q, k, v, w, bias, out)
     torch.cuda.synchronize()
     res = inputs.to_f64(out.view(B, N, H, d).permute(0, 2, 1, 3).contiguous())

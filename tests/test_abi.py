@@ -48,6 +48,7 @@ def test_validate_accepts_benchmark_workloads():
     ("d", 48, b.ERR_UNSUPPORTED), ("d", 0, b.ERR_INVALID_ARG), ("io_dtype", 7, b.ERR_UNSUPPORTED),
     ("norm", 2, b.ERR_INVALID_ARG), ("branches", 8, b.ERR_INVALID_ARG),
     ("eps", -1.0, b.ERR_INVALID_ARG), ("eps", float("nan"), b.ERR_INVALID_ARG),
+    ("flags", 2, b.ERR_INVALID_ARG),
 ])
 def test_validate_rejects(field, value, status):
     d = good()

@@ -229,7 +229,14 @@ def test_one_kernel_forward_agrees_with_reduce_apply(wl):
     x = inputs.make_inputs(wl, seed=24, with_bias=True)
     dev = torch.device("cuda:0")
     t = {n: x[n].to(dev) for n in ("q", "k", "v", "w", "bias")}
-    attn = b.CastlingAttn.for_workload(wl)
+    plain = b.CastlingAttn.for_workload(wl)
+    with pytest.raises(b.CastlingError):      # nothing has run yet
+        plain.get_state()
+    plain.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], torch.empty_like(t["q"]))
+    with pytest.raises(b.CastlingError):      # the state stayed on chip
+        plain.get_state()
+    plain.destroy()
+    attn = b.CastlingAttn.for_workload(wl, flags=b.FLAG_KEEP_STATE)
     o1, o2 = torch.empty_like(t["q"]), torch.empty_like(t["q"])
     print(f"case one-kernel vs two-pass {wl.name}", flush=True)
     attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], o1)
