@@ -27,7 +27,10 @@
  *     shared over the batch); dw_bias: [heads][d] or NULL.
  *   - DWConv: zero "same" padding, stride 1, cross-correlation (no flip).
  *   - io_dtype is the type of q, k, v, dw_weight, dw_bias and out.  Accumulation
- *     is fp32 in all cases; bf16 outputs are rounded to nearest even.
+ *     is fp32 in all cases; bf16 and fp16 outputs are rounded to nearest even (fp16
+ *     results beyond 65504 in magnitude become infinity).  bf16 with d = 64 (and d = 32
+ *     for the first half) runs on the matrix cores; fp32, fp16 and the other head
+ *     widths run on the vector ALUs.
  *   - The caller owns every tensor.  A handle owns only its workspace (partial
  *     states + final state), allocated by create and freed by destroy.
  *   - forward / reduce / apply only enqueue work on `stream` (a hipStream_t, NULL
@@ -57,7 +60,7 @@ typedef enum {
     CASTLING_ERR_ALIAS = 4        /* out overlaps an input */
 } castling_status_t;
 
-typedef enum { CASTLING_F32 = 0, CASTLING_BF16 = 1 } castling_dtype_t;
+typedef enum { CASTLING_F32 = 0, CASTLING_BF16 = 1, CASTLING_F16 = 2 } castling_dtype_t;
 
 typedef enum {
     CASTLING_NORM_ROWSUM = 0, /* divide by sum_j A_tj: the denominator of Eq. 3 (default) */
@@ -72,7 +75,7 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
 enum { CASTLING_FLAG_KEEP_STATE = 1 };
 
 typedef struct {
-    int32_t B, heads, N, d;   /* d in {32, 64} */
+    int32_t B, heads, N, d;   /* d in {16, 32, 64, 128} */
     int32_t grid_h, grid_w;   /* N must equal grid_h * grid_w */
     int32_t dw_kernel;        /* odd, 1..9 */
     int32_t io_dtype;         /* castling_dtype_t */

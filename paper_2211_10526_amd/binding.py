@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcastling_attn.so")
 
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_ALIAS = 0, 1, 2, 3, 4
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 NORM_ROWSUM, NORM_NONE = 0, 1
 BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
 FLAG_KEEP_STATE = 1
@@ -104,7 +104,7 @@ def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROW
     """in_strides / out_strides: (batch, head, token) element strides of q, k, v and of out;
     None = contiguous [B][heads][N][d]."""
     if isinstance(io_dtype, str):
-        io_dtype = {"f32": F32, "bf16": BF16}[io_dtype]
+        io_dtype = {"f32": F32, "bf16": BF16, "f16": F16}[io_dtype]
     ins = tuple(in_strides) if in_strides is not None else (0, 0, 0)
     outs = tuple(out_strides) if out_strides is not None else (0, 0, 0)
     return Desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm, branches, eps,

@@ -79,11 +79,13 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
         for (int i = tid; i < L::SIZE; i += 256)
             st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
 
-        constexpr int ROWS = 256 / LPR;
+        constexpr int ROWS = 256 / LPR;  // token rows one pass of the block loads
+        constexpr int PASSES = (kApplyTokens + ROWS - 1) / ROWS;
         const int lcol = (tid % LPR) * VEC;
 #pragma unroll
-        for (int pass = 0; pass < kApplyTokens / ROWS; ++pass) {
+        for (int pass = 0; pass < PASSES; ++pass) {
             const int tl = pass * ROWS + tid / LPR;
+            if (tl >= kApplyTokens) break;  // narrow rows: fewer threads than 256 are needed
             const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
             float qx[VEC];
             if (y < p.grid_h && x < p.grid_w) {
@@ -193,15 +195,22 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
             const int x = tx0 + my_col0 + t;
             if (x < p.grid_w) {
                 T* o = out + out_off + (static_cast<long long>(y) * p.grid_w + x) * p.out.n + tj * RJ;
-                T tmp[RJ];
+                __attribute__((aligned(16))) T tmp[RJ];
 #pragma unroll
                 for (int j = 0; j < RJ; ++j) tmp[j] = IO<T>::from_f32(res[t][j]);
-                if constexpr (sizeof(T) * RJ == 16)
-                    *reinterpret_cast<uint4*>(o) = *reinterpret_cast<const uint4*>(tmp);
-                else if constexpr (sizeof(T) * RJ == 8)
+                constexpr int BYTES = sizeof(T) * RJ;
+                if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+                    for (int c = 0; c < BYTES / 16; ++c)
+                        reinterpret_cast<uint4*>(o)[c] = reinterpret_cast<const uint4*>(tmp)[c];
+                } else if constexpr (BYTES == 8) {
                     *reinterpret_cast<uint2*>(o) = *reinterpret_cast<const uint2*>(tmp);
-                else
+                } else if constexpr (BYTES == 4) {
                     *reinterpret_cast<uint32_t*>(o) = *reinterpret_cast<const uint32_t*>(tmp);
+                } else {
+                    static_assert(BYTES == 2, "output piece of one thread");
+                    *o = tmp[0];
+                }
             }
         }
     }

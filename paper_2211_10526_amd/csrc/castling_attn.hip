@@ -39,6 +39,23 @@ int hip_fail(hipError_t e)
     } while (0)
 
 size_t dtype_size(int dt) { return dt == CASTLING_F32 ? 4 : 2; }
+
+// f(T{}, integral_constant<int, D>{}) for the handle's I/O type and head width
+template <typename F>
+auto dispatch_type_width(int dtype, int d, F&& f)
+{
+    auto with_t = [&](auto t) {
+        switch (d) {
+            case 16: return f(t, std::integral_constant<int, 16>{});
+            case 32: return f(t, std::integral_constant<int, 32>{});
+            case 64: return f(t, std::integral_constant<int, 64>{});
+            default: return f(t, std::integral_constant<int, 128>{});
+        }
+    };
+    if (dtype == CASTLING_F32) return with_t(float{});
+    if (dtype == CASTLING_F16) return with_t(f16_t{});
+    return with_t(bf16_t{});
+}
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
@@ -117,7 +134,6 @@ void launch_combine(castling_attn* h, hipStream_t s)
 // w != nullptr: also prepare the DWConv weight operands of the MFMA apply kernel
 int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hipStream_t s)
 {
-    const bool f32 = h->desc.io_dtype == CASTLING_F32;
     const int d = h->desc.d;
     h->state_valid = true;
     // with one split per unit the reduce kernel's result is final: it writes the state and
@@ -126,12 +142,11 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
     if (h->mfma_reduce) {
         if (d == 32) launch_reduce_mfma<32>(h, k, v, nullptr, false, s);
         else launch_reduce_mfma<64>(h, k, v, direct ? w : nullptr, direct, s);
-    } else if (f32) {
-        if (d == 32) launch_reduce_generic<float, 32>(h, k, v, s);
-        else launch_reduce_generic<float, 64>(h, k, v, s);
     } else {
-        if (d == 32) launch_reduce_generic<bf16_t, 32>(h, k, v, s);
-        else launch_reduce_generic<bf16_t, 64>(h, k, v, s);
+        dispatch_type_width(h->desc.io_dtype, d, [&](auto t, auto dc) {
+            launch_reduce_generic<decltype(t), decltype(dc)::value>(h, k, v, s);
+            return 0;
+        });
     }
     HIP_TRY(hipGetLastError());
     if (direct) return CASTLING_OK;
@@ -143,10 +158,11 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
         hipLaunchKernelGGL(combine_frag_kernel, dim3(gx, h->units + wrows), dim3(256), 0, s,
                            h->partial, h->state, h->sfrag, h->kfrag, h->vhalf, h->n_split, h->units,
                            static_cast<const bf16_t*>(w), h->wfrag, h->desc.heads, ks);
-    } else if (d == 32) {
-        launch_combine<32>(h, s);
     } else {
-        launch_combine<64>(h, s);
+        dispatch_type_width(CASTLING_F32, d, [&](auto, auto dc) {
+            launch_combine<decltype(dc)::value>(h, s);
+            return 0;
+        });
     }
     HIP_TRY(hipGetLastError());
     return CASTLING_OK;
@@ -261,12 +277,9 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
             default: return apply_mfma<9>(h, launch, q, v, w, bias, out, s);
         }
     }
-    const bool f32 = h->desc.io_dtype == CASTLING_F32;
-    if (h->desc.d == 32)
-        return f32 ? apply_generic_ks<float, 32>(h, launch, q, v, w, bias, out, s)
-                   : apply_generic_ks<bf16_t, 32>(h, launch, q, v, w, bias, out, s);
-    return f32 ? apply_generic_ks<float, 64>(h, launch, q, v, w, bias, out, s)
-               : apply_generic_ks<bf16_t, 64>(h, launch, q, v, w, bias, out, s);
+    return dispatch_type_width(h->desc.io_dtype, h->desc.d, [&](auto t, auto dc) {
+        return apply_generic_ks<decltype(t), decltype(dc)::value>(h, launch, q, v, w, bias, out, s);
+    });
 }
 
 // ------------------------------------------------------------------ one-kernel path
@@ -369,8 +382,9 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     if (d->branches & ~static_cast<uint32_t>(CASTLING_BRANCH_ALL)) return CASTLING_ERR_INVALID_ARG;
     if (!(d->eps >= 0.0f)) return CASTLING_ERR_INVALID_ARG;
     if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE)) return CASTLING_ERR_INVALID_ARG;
-    if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16) return CASTLING_ERR_UNSUPPORTED;
-    if (d->d != 32 && d->d != 64) return CASTLING_ERR_UNSUPPORTED;
+    if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16 && d->io_dtype != CASTLING_F16)
+        return CASTLING_ERR_UNSUPPORTED;
+    if (d->d != 16 && d->d != 32 && d->d != 64 && d->d != 128) return CASTLING_ERR_UNSUPPORTED;
     if (d->dw_kernel > 9) return CASTLING_ERR_UNSUPPORTED;
     // grid.y carries the unit index; keep element offsets inside int64 comfortably
     if (static_cast<int64_t>(d->B) * d->heads > 65535) return CASTLING_ERR_UNSUPPORTED;
@@ -425,7 +439,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 on the vector-ALU kernels (A/B measurements)
     const char* force = getenv("CASTLING_ATTN_FORCE_GENERIC");
     const bool allow_mfma = desc->io_dtype == CASTLING_BF16 && !(force && force[0] == '1');
-    h->mfma_reduce = allow_mfma;
+    h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
     h->mfma_apply = allow_mfma && desc->d == 64;
     // CASTLING_ATTN_NO_FUSED=1 keeps forward() on the two-pass path at small N (A/B measurements)
     const char* nofuse = getenv("CASTLING_ATTN_NO_FUSED");

@@ -60,6 +60,24 @@ struct IO<bf16_t> {
     __device__ static __forceinline__ bf16_t from_f32(float a) { return f32_to_bf16(a); }
 };
 
+typedef _Float16 f16_t;
+
+template <>
+struct IO<f16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ void load16(const f16_t* p, float (&x)[8])
+    {
+        typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+        const uint4 r = *reinterpret_cast<const uint4*>(p);
+        const f16x8_t h = __builtin_bit_cast(f16x8_t, r);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = static_cast<float>(h[i]);
+    }
+    __device__ static __forceinline__ float to_f32(f16_t a) { return static_cast<float>(a); }
+    // round to nearest even; values beyond the fp16 range become infinity
+    __device__ static __forceinline__ f16_t from_f32(float a) { return static_cast<f16_t>(a); }
+};
+
 // Sum over groups of LANES consecutive lanes (LANES a power of two <= 64).
 template <int LANES>
 __device__ __forceinline__ float group_sum(float x)

@@ -24,7 +24,7 @@ import torch
 @dataclass(frozen=True)
 class Workload:
     name: str
-    dtype: str            # "f32" | "bf16"
+    dtype: str            # "f32" | "bf16" | "f16"
     B: int
     heads: int
     d: int
@@ -82,7 +82,7 @@ def workload(index_or_name) -> Workload:
 
 
 def torch_dtype(name: str) -> torch.dtype:
-    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+    return {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[name]
 
 
 def make_inputs(wl: Workload, seed: int | None = None, with_bias: bool = False) -> dict:
@@ -112,7 +112,7 @@ def make_inputs(wl: Workload, seed: int | None = None, with_bias: bool = False) 
 
 
 def to_f64(t) -> np.ndarray | None:
-    """Exact upcast of a stored tensor (fp32 or bf16) to a float64 numpy array."""
+    """Exact upcast of a stored tensor (fp32, bf16 or fp16) to a float64 numpy array."""
     if t is None:
         return None
     return t.detach().to("cpu").to(torch.float64).contiguous().numpy()

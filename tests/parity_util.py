@@ -5,7 +5,9 @@ import torch
 from paper_2211_10526_amd import binding as b
 from paper_2211_10526_amd import inputs
 
-TOL = {"f32": 1e-4, "bf16": 1e-2}
+# fp16 I/O (fp32 products and accumulation): the output rounding, 2^-11 = 4.9e-4 relative,
+# dominates; 1e-3 leaves a factor of two
+TOL = {"f32": 1e-4, "bf16": 1e-2, "f16": 1e-3}
 
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:

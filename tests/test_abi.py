@@ -45,7 +45,8 @@ def test_validate_accepts_benchmark_workloads():
     ("B", 0, b.ERR_INVALID_ARG), ("heads", -1, b.ERR_INVALID_ARG), ("N", 195, b.ERR_INVALID_ARG),
     ("grid_w", 13, b.ERR_INVALID_ARG), ("dw_kernel", 4, b.ERR_INVALID_ARG),
     ("dw_kernel", 0, b.ERR_INVALID_ARG), ("dw_kernel", 11, b.ERR_UNSUPPORTED),
-    ("d", 48, b.ERR_UNSUPPORTED), ("d", 0, b.ERR_INVALID_ARG), ("io_dtype", 7, b.ERR_UNSUPPORTED),
+    ("d", 48, b.ERR_UNSUPPORTED), ("d", 256, b.ERR_UNSUPPORTED), ("d", 0, b.ERR_INVALID_ARG),
+    ("io_dtype", 7, b.ERR_UNSUPPORTED),
     ("norm", 2, b.ERR_INVALID_ARG), ("branches", 8, b.ERR_INVALID_ARG),
     ("eps", -1.0, b.ERR_INVALID_ARG), ("eps", float("nan"), b.ERR_INVALID_ARG),
     ("flags", 2, b.ERR_INVALID_ARG),

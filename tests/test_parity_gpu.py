@@ -41,6 +41,39 @@ SMALL = [
 ]
 ONE_KERNEL = [SMALL[3], SMALL[6], SMALL[8]] + SMALL[14:]
 
+# head widths 16 and 128 and fp16 I/O (vector-ALU kernels)
+WIDE = [
+    Workload("w_f32_d16_14x14_k3", "f32", 2, 3, 16, 14, 14, 3),
+    Workload("w_bf16_d16_9x21_k5", "bf16", 1, 4, 16, 9, 21, 5),
+    Workload("w_f16_d16_7x7_k7", "f16", 2, 2, 16, 7, 7, 7),
+    Workload("w_f32_d128_10x12_k3", "f32", 1, 2, 128, 10, 12, 3),
+    Workload("w_bf16_d128_14x14_k5", "bf16", 2, 2, 128, 14, 14, 5),
+    Workload("w_f16_d128_6x20_k3", "f16", 1, 3, 128, 6, 20, 3),
+    Workload("w_f16_d64_14x14_k3", "f16", 2, 4, 64, 14, 14, 3),
+    Workload("w_f16_d32_13x19_k9", "f16", 1, 3, 32, 13, 19, 9),
+    Workload("w_f16_d64_33x40_k5", "f16", 1, 2, 64, 33, 40, 5),
+]
+
+
+@pytest.mark.parametrize("wl", WIDE, ids=lambda w: w.name)
+@pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
+def test_wide_shapes_and_fp16(oracle, wl, norm):
+    x = inputs.make_inputs(wl, seed=31, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    for branches in (b.BRANCH_ALL, b.BRANCH_LINEAR, b.BRANCH_DWCONV):
+        print(f"case {wl.name} norm={norm} branches={branches}", flush=True)
+        want = oracle.forward_explicit(q, k, v, w, bias, wl.grid_h, wl.grid_w, norm=norm,
+                                       branches=branches)
+        if branches & b.BRANCH_LINEAR:
+            got, st = gpu_forward(wl, x, norm=norm, branches=branches, want_state=True)
+            assert rel_err(st, oracle.state(k, v)) <= TOL[wl.dtype]
+        else:  # the convolution alone reduces nothing: there is no state to fetch
+            got = gpu_forward(wl, x, norm=norm, branches=branches)
+        assert np.isfinite(got).all()
+        assert rel_err(got, want) <= TOL[wl.dtype], (wl.name, norm, branches)
+    # strided views work for every kernel family
+    assert np.array_equal(gpu_forward_fused(wl, x, norm=norm), gpu_forward(wl, x, norm=norm))
+
 
 @pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
 @pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
