@@ -141,6 +141,10 @@ int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, voi
 /* Number of token splits per unit the reduce uses for this handle (>= 1). */
 int castling_attn_num_splits(castling_attn_t h);
 
+/* Number of kernels one castling_attn_forward enqueues for this handle: 1 = the whole layer in
+ * one kernel (state kept on chip), 2 = reduce + apply, 3 = reduce + combine + apply. */
+int castling_attn_num_launches(castling_attn_t h);
+
 /* Static string for a status code. */
 const char* castling_attn_strerror(int status);
 

@@ -26,6 +26,7 @@ EXPORTS = (
     "castling_attn_reduce", "castling_attn_apply", "castling_attn_prepare_weights",
     "castling_attn_destroy",
     "castling_attn_workspace_bytes", "castling_attn_get_state", "castling_attn_num_splits",
+    "castling_attn_num_launches",
     "castling_attn_strerror",
 )
 
@@ -73,6 +74,7 @@ def lib():
         L.castling_attn_workspace_bytes.restype = C.c_size_t
         L.castling_attn_get_state.argtypes = [vp, vp, C.c_size_t, vp]
         L.castling_attn_num_splits.argtypes = [vp]
+        L.castling_attn_num_launches.argtypes = [vp]
         L.castling_attn_strerror.argtypes = [C.c_int]
         L.castling_attn_strerror.restype = C.c_char_p
         _lib = L
@@ -162,6 +164,9 @@ class CastlingAttn:
 
     def num_splits(self) -> int:
         return lib().castling_attn_num_splits(self._h)
+
+    def num_launches(self) -> int:
+        return lib().castling_attn_num_launches(self._h)
 
     def get_state(self, stream=None) -> np.ndarray:
         d = self.desc

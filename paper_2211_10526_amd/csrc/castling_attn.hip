@@ -526,6 +526,14 @@ size_t castling_attn_workspace_bytes(castling_attn_t h) { return h ? h->workspac
 
 int castling_attn_num_splits(castling_attn_t h) { return h ? h->n_split : 0; }
 
+int castling_attn_num_launches(castling_attn_t h)
+{
+    if (!h) return 0;
+    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
+    if (h->fused || !lin) return 1;
+    return (h->mfma_apply && h->n_split == 1) ? 2 : 3;
+}
+
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
 {
     if (!h || !k || !v) return CASTLING_ERR_INVALID_ARG;

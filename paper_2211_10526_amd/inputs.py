@@ -72,10 +72,21 @@ WORKLOADS = (
 )
 
 
+# Further shapes for measurements beyond the five benchmark workloads (bench.py --workload NAME):
+# the dtypes and head widths of the wider coverage, at the size of cfg4 / cfg5.
+EXTRA_WORKLOADS = (
+    Workload("x_f16_b8_h8_d64_n4096_k5", "f16", 8, 8, 64, 64, 64, 5),
+    Workload("x_f16_b2_h12_d64_n16384_k9", "f16", 2, 12, 64, 128, 128, 9),
+    Workload("x_bf16_b8_h4_d128_n4096_k5", "bf16", 8, 4, 128, 64, 64, 5),
+    Workload("x_bf16_b8_h32_d16_n4096_k5", "bf16", 8, 32, 16, 64, 64, 5),
+    Workload("x_f16_b64_h8_d64_n196_k3", "f16", 64, 8, 64, 14, 14, 3),
+)
+
+
 def workload(index_or_name) -> Workload:
     if isinstance(index_or_name, int):
         return WORKLOADS[index_or_name]
-    for w in WORKLOADS:
+    for w in WORKLOADS + EXTRA_WORKLOADS:
         if w.name == index_or_name or w.name.startswith(str(index_or_name) + "_"):
             return w
     raise KeyError(index_or_name)
