@@ -75,10 +75,11 @@ constexpr int kApplyMfmaLdsBytes =
 // sum of the partial states of one unit; writes the fp32 state and the bf16 MFMA operand
 // tables of the apply kernel.  Rows >= units (only when w != nullptr): the DWConv weight
 // operand table, so that a whole forward needs no separate launch for it.
+template <typename X>
 __global__ __launch_bounds__(256) void combine_frag_kernel(
     const float* __restrict__ partial, float* __restrict__ state, bf16_t* __restrict__ sfrag,
     bf16_t* __restrict__ kfrag, float* __restrict__ vhalf, int n_split, int units,
-    const bf16_t* __restrict__ w, bf16_t* __restrict__ wfrag, int heads, int ks)
+    const bf16_t* __restrict__ w, bf16_t* __restrict__ wfrag, int heads, int ks, float tscale)
 {
     using L = StateLayout<64>;
     if (static_cast<int>(blockIdx.y) >= units) {
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(
         st[i0 * 64 + j] = s0;
         st[(i0 + 1) * 64 + j] = s1;
         uint32_t* dst = reinterpret_cast<uint32_t*>(sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
-        dst[t] = pack_bf16x2(s0 * kInvPi, s1 * kInvPi);
+        dst[t] = X::pack(s0 * tscale, s1 * tscale);
     } else if (t < 2048 + 128) {
         // column sums into the fp32 state; vsum / 2 for the apply kernel
         const int f = t - 2048;  // 0..63 ksum, 64..127 vsum
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(
         const float s0 = sum_partials(p + L::KSUM + i0, n_split, L::SIZE);
         const float s1 = sum_partials(p + L::KSUM + i0 + 1, n_split, L::SIZE);
         uint32_t* dst = reinterpret_cast<uint32_t*>(kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
-        dst[u] = pack_bf16x2(s0 * kInvPi, s1 * kInvPi);
+        dst[u] = X::pack(s0 * tscale, s1 * tscale);
     }
 }
 constexpr int kCombineFragThreads = 2048 + 128 + 512;
@@ -224,7 +225,7 @@ struct StageSnap {
 };
 
 // grid = (G), block = 64 * kApplyWaves.
-template <int KS, bool LIN, bool DW>
+template <int KS, bool LIN, bool DW, typename X>
 __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ v, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ sfrag, const bf16_t* __restrict__ kfrag,
@@ -483,7 +484,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         constexpr int YOUNGER = (PD - 1) * 2;
         const int tl = lane & 15, g = lane >> 4;
         const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
-        bf16x8_t sf[4][2], kf[2];
+        u32x4_t sf[4][2], kf[2];
+        const float unsc = X::table_unscale(p.N);
         float vh[4] = {0.f, 0.f, 0.f, 0.f};
         int lin_unit = -1;
         u32x4_t qreg[PD][2];
@@ -530,35 +532,35 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     for (int nt = 0; nt < 4; ++nt) {
 #pragma unroll
                         for (int ks = 0; ks < 2; ++ks)
-                            sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
+                            sf[nt][ks] = __builtin_bit_cast(u32x4_t, s4[(nt * 2 + ks) * 64 + lane]);
                         vh[nt] = vhalf[unit * D + 16 * nt + tl];
                     }
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
-                        kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
+                        kf[ks] = __builtin_bit_cast(u32x4_t, k4[ks * 64 + lane]);
                 }
                 const u32x4_t zero = {0u, 0u, 0u, 0u};
-                bf16x8_t a[2];
-                a[0] = __builtin_bit_cast(bf16x8_t, qok[slot] ? qreg[slot][0] : zero);
-                a[1] = __builtin_bit_cast(bf16x8_t, qok[slot] ? qreg[slot][1] : zero);
+                u32x4_t a[2];
+                a[0] = qok[slot] ? qreg[slot][0] : zero;
+                a[1] = qok[slot] ? qreg[slot][1] : zero;
                 // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
                 f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
-                    gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
+                    gram = X::mfma16(a[ks], a[ks], gram);
                 f32x4_t acc[4], dk;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) dk[r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
-                    dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
+                    dk = X::mfma16(a[ks], kf[ks], dk);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) acc[nt][r] = 0.f;
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
-                        acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], acc[nt], 0, 0, 0);
+                        acc[nt] = X::mfma16(a[ks], sf[nt][ks], acc[nt]);
                 }
                 float alpha[4], beta[4];
 #pragma unroll
@@ -567,7 +569,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     const float ssr = __int_as_float(
                         __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
                     // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
-                    const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                    float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                    if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
                     if (p.norm_none) {
                         alpha[r] = inv;
                         beta[r] = 1.0f;
@@ -644,7 +647,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
 #pragma unroll
                         for (int m = 0; m < 3; ++m)
                             tw[dy][m] = __builtin_bit_cast(s16x4_t, wf[(dy * 3 + m) * 64]);
-                    bias_dw = bias ? bf16_to_f32(bias[head * D + ch_dw]) : 0.f;
+                    bias_dw = bias ? X::one(bias[head * D + ch_dw]) : 0.f;
                 }
                 // the four staged rows replace the oldest four of the ring
 #pragma unroll
@@ -681,16 +684,15 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     for (int m = 0; m < 3; ++m)
 #pragma unroll
                         for (int rr = 0; rr < 4; ++rr)
-                            acc[rr] = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(
-                                tw[dy][m], win[(4 * (ph + 1) + rr + dy) % WR][m], acc[rr], 0, 0, 0);
+                            acc[rr] = X::mfma4(tw[dy][m], win[(4 * (ph + 1) + rr + dy) % WR][m], acc[rr]);
             }
             TRACE_POINT(14);
             // results go to the LDS output tile [row][channel][token]
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 uint2 o;
-                o.x = pack_bf16x2(acc[rr][0], acc[rr][1]);
-                o.y = pack_bf16x2(acc[rr][2], acc[rr][3]);
+                o.x = X::pack(acc[rr][0], acc[rr][1]);
+                o.y = X::pack(acc[rr][2], acc[rr][3]);
                 *reinterpret_cast<uint2*>(ot + ((rr * 64 + ch_dw) * kOutTokPitch + 4 * j) * 2) = o;
             }
         };

@@ -69,8 +69,9 @@ struct castling_attn {
     TensorStrides in_st, out_st;  // element strides of q/k/v and of out (defaults resolved)
     size_t in_span, out_span;     // bytes from the first to one past the last element addressed
     int state_size;     // floats per unit
-    bool mfma_reduce;   // bf16: K_hat^T V on the matrix cores
-    bool mfma_apply;    // bf16, d = 64: q.S and the DWConv on the matrix cores
+    bool mfma_reduce;   // bf16 / fp16, d = 32 or 64: K_hat^T V on the matrix cores
+    bool mfma_apply;    // bf16 / fp16, d = 64: q.S and the DWConv on the matrix cores
+    bool half16;        // the 16-bit format is fp16 (else bf16)
     bool fused;         // forward() runs the one-kernel path (small N)
     bool state_valid;   // the workspace holds the state of the last reduce
     int num_cus;        // compute units of the device
@@ -100,7 +101,7 @@ void launch_reduce_generic(castling_attn* h, const void* k, const void* v, hipSt
 
 // w != nullptr: extra grid rows build the DWConv weight operand table.
 // direct: the blocks' results are final (n_split == 1); they write state and tables themselves.
-template <int D>
+template <int D, typename X>
 void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const void* w, bool direct,
                         hipStream_t s)
 {
@@ -114,10 +115,11 @@ void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const vo
     ex.units = h->units;
     ex.heads = h->desc.heads;
     ex.ks = h->desc.dw_kernel;
+    ex.tscale = X::table_scale(h->desc.N);
     const int per_row = h->n_split * 64 * kReduceWaves;
     const int wthreads = h->desc.heads * 4 * ex.ks * 3 * 64;
     const int wrows = w ? (wthreads + per_row - 1) / per_row : 0;
-    hipLaunchKernelGGL((reduce_mfma_kernel<D>), dim3(h->n_split, h->units + wrows),
+    hipLaunchKernelGGL((reduce_mfma_kernel<D, X>), dim3(h->n_split, h->units + wrows),
                        dim3(64 * kReduceWaves), 0, s, static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), h->partial, h->desc.N, h->n_split, h->chunk,
                        h->desc.eps, h->desc.heads, h->in_st, ex);
@@ -140,8 +142,13 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
     // the apply kernel's operand tables itself, and no combine is launched
     const bool direct = h->mfma_apply && h->n_split == 1;
     if (h->mfma_reduce) {
-        if (d == 32) launch_reduce_mfma<32>(h, k, v, nullptr, false, s);
-        else launch_reduce_mfma<64>(h, k, v, direct ? w : nullptr, direct, s);
+        if (h->half16) {
+            if (d == 32) launch_reduce_mfma<32, F16Fmt>(h, k, v, nullptr, false, s);
+            else launch_reduce_mfma<64, F16Fmt>(h, k, v, direct ? w : nullptr, direct, s);
+        } else {
+            if (d == 32) launch_reduce_mfma<32, Bf16Fmt>(h, k, v, nullptr, false, s);
+            else launch_reduce_mfma<64, Bf16Fmt>(h, k, v, direct ? w : nullptr, direct, s);
+        }
     } else {
         dispatch_type_width(h->desc.io_dtype, d, [&](auto t, auto dc) {
             launch_reduce_generic<decltype(t), decltype(dc)::value>(h, k, v, s);
@@ -155,9 +162,16 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
         const int ks = h->desc.dw_kernel;
         const int wthreads = h->desc.heads * 4 * ks * 3 * 64;
         const int wrows = w ? (wthreads + gx * 256 - 1) / (gx * 256) : 0;
-        hipLaunchKernelGGL(combine_frag_kernel, dim3(gx, h->units + wrows), dim3(256), 0, s,
-                           h->partial, h->state, h->sfrag, h->kfrag, h->vhalf, h->n_split, h->units,
-                           static_cast<const bf16_t*>(w), h->wfrag, h->desc.heads, ks);
+        if (h->half16)
+            hipLaunchKernelGGL(combine_frag_kernel<F16Fmt>, dim3(gx, h->units + wrows), dim3(256), 0,
+                               s, h->partial, h->state, h->sfrag, h->kfrag, h->vhalf, h->n_split,
+                               h->units, static_cast<const bf16_t*>(w), h->wfrag, h->desc.heads, ks,
+                               F16Fmt::table_scale(h->desc.N));
+        else
+            hipLaunchKernelGGL(combine_frag_kernel<Bf16Fmt>, dim3(gx, h->units + wrows), dim3(256), 0,
+                               s, h->partial, h->state, h->sfrag, h->kfrag, h->vhalf, h->n_split,
+                               h->units, static_cast<const bf16_t*>(w), h->wfrag, h->desc.heads, ks,
+                               Bf16Fmt::table_scale(h->desc.N));
     } else {
         dispatch_type_width(CASTLING_F32, d, [&](auto, auto dc) {
             launch_combine<decltype(dc)::value>(h, s);
@@ -202,13 +216,13 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
 }
 
 // w == nullptr: the weight operand table has already been prepared on this stream
-template <int KS, bool LIN, bool DW>
+template <int KS, bool LIN, bool DW, typename X>
 hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, const void* v,
                                const void* w, const void* bias, void* out, hipStream_t s)
 {
     if (!launch) {
         h->apply_lds = kApplyMfmaLdsBytes;
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma_kernel<KS, LIN, DW>),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma_kernel<KS, LIN, DW, X>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kApplyMfmaLdsBytes);
     }
     const castling_attn_desc_t& d = h->desc;
@@ -233,7 +247,7 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     // one persistent block per compute unit; every block takes an equal share of the steps
     const int total_steps = h->units * p.strips * ((d.grid_h + 3) / 4);
     const int blocks = total_steps < h->num_cus ? total_steps : h->num_cus;
-    hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW>), dim3(blocks), dim3(64 * kApplyWaves),
+    hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW, X>), dim3(blocks), dim3(64 * kApplyWaves),
                        kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
                        static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(bias), h->sfrag,
                        h->kfrag, h->vhalf, h->wfrag, static_cast<bf16_t*>(out), d.heads,
@@ -241,15 +255,23 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     return hipGetLastError();
 }
 
+template <int KS, typename X>
+hipError_t apply_mfma_fmt(castling_attn* h, bool launch, const void* q, const void* v,
+                          const void* w, const void* bias, void* out, hipStream_t s)
+{
+    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
+    if (lin && dw) return apply_mfma_branches<KS, true, true, X>(h, launch, q, v, w, bias, out, s);
+    if (lin) return apply_mfma_branches<KS, true, false, X>(h, launch, q, v, w, bias, out, s);
+    return apply_mfma_branches<KS, false, true, X>(h, launch, q, v, w, bias, out, s);
+}
+
 template <int KS>
 hipError_t apply_mfma(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
                       const void* bias, void* out, hipStream_t s)
 {
-    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
-    if (lin && dw) return apply_mfma_branches<KS, true, true>(h, launch, q, v, w, bias, out, s);
-    if (lin) return apply_mfma_branches<KS, true, false>(h, launch, q, v, w, bias, out, s);
-    return apply_mfma_branches<KS, false, true>(h, launch, q, v, w, bias, out, s);
+    return h->half16 ? apply_mfma_fmt<KS, F16Fmt>(h, launch, q, v, w, bias, out, s)
+                     : apply_mfma_fmt<KS, Bf16Fmt>(h, launch, q, v, w, bias, out, s);
 }
 
 template <typename T, int D>
@@ -283,12 +305,12 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
 }
 
 // ------------------------------------------------------------------ one-kernel path
-template <int KS, bool LIN, bool DW>
+template <int KS, bool LIN, bool DW, typename X>
 hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const void* k,
                           const void* v, const void* w, const void* bias, void* out, hipStream_t s)
 {
     if (!launch)
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_small_kernel<KS, LIN, DW>),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_small_kernel<KS, LIN, DW, X>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
     const castling_attn_desc_t& d = h->desc;
     FusedParams p;
@@ -299,7 +321,7 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
     p.eps = d.eps;
     p.in = h->in_st;
     p.out = h->out_st;
-    hipLaunchKernelGGL((fused_small_kernel<KS, LIN, DW>), dim3(h->units), dim3(256), kFusedLdsBytes,
+    hipLaunchKernelGGL((fused_small_kernel<KS, LIN, DW, X>), dim3(h->units), dim3(256), kFusedLdsBytes,
                        s, static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(w),
                        static_cast<const bf16_t*>(bias),
@@ -309,15 +331,23 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
     return hipGetLastError();
 }
 
+template <int KS, typename X>
+hipError_t fused_fmt(castling_attn* h, bool launch, const void* q, const void* k, const void* v,
+                     const void* w, const void* bias, void* out, hipStream_t s)
+{
+    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
+    if (lin && dw) return fused_branches<KS, true, true, X>(h, launch, q, k, v, w, bias, out, s);
+    if (lin) return fused_branches<KS, true, false, X>(h, launch, q, k, v, w, bias, out, s);
+    return fused_branches<KS, false, true, X>(h, launch, q, k, v, w, bias, out, s);
+}
+
 template <int KS>
 hipError_t fused_ks(castling_attn* h, bool launch, const void* q, const void* k, const void* v,
                     const void* w, const void* bias, void* out, hipStream_t s)
 {
-    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
-    if (lin && dw) return fused_branches<KS, true, true>(h, launch, q, k, v, w, bias, out, s);
-    if (lin) return fused_branches<KS, true, false>(h, launch, q, k, v, w, bias, out, s);
-    return fused_branches<KS, false, true>(h, launch, q, k, v, w, bias, out, s);
+    return h->half16 ? fused_fmt<KS, F16Fmt>(h, launch, q, k, v, w, bias, out, s)
+                     : fused_fmt<KS, Bf16Fmt>(h, launch, q, k, v, w, bias, out, s);
 }
 
 hipError_t do_fused(castling_attn* h, bool launch, const void* q, const void* k, const void* v,
@@ -436,9 +466,11 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     }
     h->state_size = desc->d * desc->d + 2 * desc->d;
 
-    // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 on the vector-ALU kernels (A/B measurements)
+    // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 / fp16 on the vector-ALU kernels (A/B measurements)
     const char* force = getenv("CASTLING_ATTN_FORCE_GENERIC");
-    const bool allow_mfma = desc->io_dtype == CASTLING_BF16 && !(force && force[0] == '1');
+    const bool allow_mfma = (desc->io_dtype == CASTLING_BF16 || desc->io_dtype == CASTLING_F16) &&
+                            !(force && force[0] == '1');
+    h->half16 = desc->io_dtype == CASTLING_F16;
     h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
     h->mfma_apply = allow_mfma && desc->d == 64;
     // CASTLING_ATTN_NO_FUSED=1 keeps forward() on the two-pass path at small N (A/B measurements)

@@ -1,4 +1,4 @@
-// The whole layer in one kernel for units whose tokens fit on chip (bf16, d = 64,
+// The whole layer in one kernel for units whose tokens fit on chip (bf16 or fp16, d = 64,
 // N <= 256, filter size <= 5): one block per unit loads K, V, Q once, builds the state
 // K_hat^T V, sum k_hat, sum v on the matrix cores (Sec. 3.1 reassociation, sums of Eq. 3),
 // keeps it in LDS as MFMA operands, applies it to the unit's own queries (Eq. 3 with the
@@ -56,7 +56,7 @@ struct FusedParams {
 
 // grid = (units), block = 256, dynamic LDS = kFusedLdsBytes.
 // state: [units][StateLayout<64>::SIZE] fp32 copy of the state (nullptr = not wanted).
-template <int KS, bool LIN, bool DW>
+template <int KS, bool LIN, bool DW, typename X>
 __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias, float* __restrict__ state,
@@ -147,6 +147,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         for (int e = 0; e < 8; ++e) ksum[e] = vsum[e] = 0.f;
     }
     const float inv_eps = 1.0f / p.eps;
+    const float tscale = X::table_scale(N), unsc = X::table_unscale(N);
     unsigned char* const ktile = un + wave * kFusedKtileBytes;
 
     static_for<2>([&](auto it_c) {
@@ -170,12 +171,12 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                 float ss = 0.f;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    kf[2 * i] = __uint_as_float(kw[i] << 16);
-                    kf[2 * i + 1] = __uint_as_float(kw[i] & 0xffff0000u);
+                    kf[2 * i] = X::lo(kw[i]);
+                    kf[2 * i + 1] = X::hi(kw[i]);
                     ss = fmaf(kf[2 * i], kf[2 * i], ss);
                     ss = fmaf(kf[2 * i + 1], kf[2 * i + 1], ss);
-                    vsum[2 * i] += __uint_as_float(vw[i] << 16);
-                    vsum[2 * i + 1] += __uint_as_float(vw[i] & 0xffff0000u);
+                    vsum[2 * i] += X::lo(vw[i]);
+                    vsum[2 * i + 1] += X::hi(vw[i]);
                 }
                 ss = row_group_sum<8>(ss);
                 // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                     const float a = kf[2 * i] * inv, b = kf[2 * i + 1] * inv;
                     ksum[2 * i] += a;
                     ksum[2 * i + 1] += b;
-                    kh[i] = pack_bf16x2(a, b);
+                    kh[i] = X::pack(a, b);
                 }
                 *reinterpret_cast<u32x4_t*>(ktile + row * PITCH + lcol * 2) = kh;
             }
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int s = 0; s < 2; ++s) {
-                bf16x8_t a[2], b[2];
+                u32x4_t a[2], b[2];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     a[t] = lds_operand_tr(ktile, PITCH, 16 * s, 32 * t, lane);
@@ -207,8 +208,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] =
-                            __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = X::mfma32(a[mt], b[nt], acc[mt][nt]);
             }
             __builtin_amdgcn_wave_barrier();
         }
@@ -291,7 +291,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                         if ((r & 1) == 0) {
                             const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
                                           ((i & 7) >> 1);
-                            sf[t] = pack_bf16x2(acc[mt][nt][r] * kInvPi, acc[mt][nt][r + 1] * kInvPi);
+                            sf[t] = X::pack(acc[mt][nt][r] * tscale, acc[mt][nt][r + 1] * tscale);
                         }
                     }
         }
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             for (int i = 0; i < 8; ++i) {
                 const int e = 8 * tid + i;
                 const uint32_t word = wraw[i >> 1];
-                const float val = __uint_as_float((i & 1) ? (word & 0xffff0000u) : (word << 16));
+                const float val = (i & 1) ? X::hi(word) : X::lo(word);
                 wl[(e % (KS * KS)) * D + e / (KS * KS)] = val;
             }
         }
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const uint32_t word = braw[i >> 1];
-                const float val = __uint_as_float((i & 1) ? (word & 0xffff0000u) : (word << 16));
+                const float val = (i & 1) ? X::hi(word) : X::lo(word);
                 bl[8 * tid + i] = bias ? val : 0.f;
             }
         }
@@ -325,13 +325,13 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         for (int u = tid; u < kKfragPerUnit / 2; u += 256) {
             const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
             const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
-            kfr[u] = pack_bf16x2(ksumf[i0] * kInvPi, ksumf[i0 + 1] * kInvPi);
+            kfr[u] = X::pack(ksumf[i0] * tscale, ksumf[i0 + 1] * tscale);
         }
         __syncthreads();
     }
 
     // ---- phase 3
-    bf16x8_t sf[4][2], kf[2];
+    u32x4_t sf[4][2], kf[2];
     float vh[4] = {0.f, 0.f, 0.f, 0.f};
     if constexpr (LIN) {
         const uint4* s4 = reinterpret_cast<const uint4*>(lds + kFusedSfragOff);
@@ -340,11 +340,11 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         for (int nt = 0; nt < 4; ++nt) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                sf[nt][ks] = __builtin_bit_cast(bf16x8_t, s4[(nt * 2 + ks) * 64 + lane]);
+                sf[nt][ks] = __builtin_bit_cast(u32x4_t, s4[(nt * 2 + ks) * 64 + lane]);
             vh[nt] = vhalf[16 * nt + tl];
         }
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) kf[ks] = __builtin_bit_cast(bf16x8_t, k4[ks * 64 + lane]);
+        for (int ks = 0; ks < 2; ++ks) kf[ks] = __builtin_bit_cast(u32x4_t, k4[ks * 64 + lane]);
     }
     const float half_n = 0.5f * static_cast<float>(N);
     float* const lin = reinterpret_cast<float*>(un);
@@ -359,32 +359,33 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             if (64 * c + 16 * wave < N) {  // uniform per wave
                 const bool qok = 64 * c + 16 * wave + tl < N;
                 const u32x4_t zero = {0u, 0u, 0u, 0u};
-                bf16x8_t a[2];
-                a[0] = __builtin_bit_cast(bf16x8_t, qok ? qraw[c][0] : zero);
-                a[1] = __builtin_bit_cast(bf16x8_t, qok ? qraw[c][1] : zero);
+                u32x4_t a[2];
+                a[0] = qok ? qraw[c][0] : zero;
+                a[1] = qok ? qraw[c][1] : zero;
                 // |q_t|^2 on the matrix cores: the diagonal of Q Q^T
                 f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
-                    gram = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], a[ks], gram, 0, 0, 0);
+                    gram = X::mfma16(a[ks], a[ks], gram);
                 f32x4_t ac[4], dk = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks)
-                    dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], kf[ks], dk, 0, 0, 0);
+                    dk = X::mfma16(a[ks], kf[ks], dk);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) ac[nt][r] = 0.f;
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
-                        ac[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[ks], sf[nt][ks], ac[nt], 0, 0, 0);
+                        ac[nt] = X::mfma16(a[ks], sf[nt][ks], ac[nt]);
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
                     const float ssr = __int_as_float(
                         __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
-                    const float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                    float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                    if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
                     float alpha, beta;
                     if (p.norm_none) {
                         alpha = inv;
@@ -436,15 +437,15 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                             if (!ok) vw = u32x4_t{0u, 0u, 0u, 0u};
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                o[2 * i] = fmaf(wv[2 * i], __uint_as_float(vw[i] << 16), o[2 * i]);
+                                o[2 * i] = fmaf(wv[2 * i], X::lo(vw[i]), o[2 * i]);
                                 o[2 * i + 1] =
-                                    fmaf(wv[2 * i + 1], __uint_as_float(vw[i] & 0xffff0000u), o[2 * i + 1]);
+                                    fmaf(wv[2 * i + 1], X::hi(vw[i]), o[2 * i + 1]);
                             }
                         }
                     }
                 }
-                store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16), pack_bf16x2(o[0], o[1]),
-                               pack_bf16x2(o[2], o[3]), pack_bf16x2(o[4], o[5]), pack_bf16x2(o[6], o[7]));
+                store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16), X::pack(o[0], o[1]),
+                               X::pack(o[2], o[3]), X::pack(o[4], o[5]), X::pack(o[6], o[7]));
             }
         }
         if constexpr (LIN) {

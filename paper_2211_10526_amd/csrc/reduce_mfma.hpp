@@ -66,10 +66,76 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, r);
 }
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(4))) _Float16 f16x4_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+
+// The two 16-bit I/O formats of the matrix-core kernels.  Values travel as raw bits (u32x4_t =
+// 8 values, s16x4_t = 4 values, uint32_t = 2 values) and are typed only where they are converted
+// or multiplied.  The operand tables hold S * table_scale and ksum * table_scale; the apply
+// side multiplies its products by table_unscale.  fp16 tables are scaled by 1 / N: |S_ij| and
+// |ksum_i| are at most N max|v| resp. N, so the scaled entries cannot overflow fp16 unless the
+// inputs themselves are at its limit.
+struct Bf16Fmt {
+    static constexpr bool kHalf = false;
+    static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+    static __device__ __forceinline__ float one(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+    static __device__ __forceinline__ uint32_t pack(float a, float b) { return pack_bf16x2(a, b); }
+    static __host__ __device__ __forceinline__ float table_scale(int) { return kInvPi; }
+    static __host__ __device__ __forceinline__ float table_unscale(int) { return 1.0f; }
+    static __device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4_t mfma16(u32x4_t a, u32x4_t b, f32x4_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4_t mfma4(s16x4_t a, s16x4_t b, f32x4_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
+    }
+};
+
+struct F16Fmt {
+    static constexpr bool kHalf = true;
+    static __device__ __forceinline__ float one(uint16_t b) { return static_cast<float>(__builtin_bit_cast(_Float16, b)); }
+    static __device__ __forceinline__ float lo(uint32_t w) { return one(static_cast<uint16_t>(w)); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return one(static_cast<uint16_t>(w >> 16)); }
+    // round to nearest even; beyond the fp16 range the result is infinity
+    static __device__ __forceinline__ uint32_t pack(float a, float b)
+    {
+        f16x2_t r;
+        r[0] = static_cast<_Float16>(a);
+        r[1] = static_cast<_Float16>(b);
+        return __builtin_bit_cast(uint32_t, r);
+    }
+    static __host__ __device__ __forceinline__ float table_scale(int N) { return kInvPi / static_cast<float>(N); }
+    static __host__ __device__ __forceinline__ float table_unscale(int N) { return static_cast<float>(N); }
+    static __device__ __forceinline__ f32x16_t mfma32(u32x4_t a, u32x4_t b, f32x16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4_t mfma16(u32x4_t a, u32x4_t b, f32x4_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a),
+                                                      __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ f32x4_t mfma4(s16x4_t a, s16x4_t b, f32x4_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a),
+                                                  __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
+    }
+};
+
 // One MFMA operand (8 consecutive tokens of one feature per lane) from a
 // [token][feature] bf16 tile in LDS with `pitch` bytes per token row.
 // tok0: first of the 16 tokens of this k-step; feat0: first of the 32 features.
-__device__ __forceinline__ bf16x8_t lds_operand_tr(const unsigned char* tile, int pitch, int tok0,
+__device__ __forceinline__ u32x4_t lds_operand_tr(const unsigned char* tile, int pitch, int tok0,
                                                    int feat0, int lane)
 {
     const int g = lane >> 4, e = (lane >> 2) & 3, p = lane & 3;
@@ -82,7 +148,7 @@ __device__ __forceinline__ bf16x8_t lds_operand_tr(const unsigned char* tile, in
     s16x8_t r;
     r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
     r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
-    return __builtin_bit_cast(bf16x8_t, r);
+    return __builtin_bit_cast(u32x4_t, r);
 }
 
 // Optional extra outputs of the reduce kernel.
@@ -97,11 +163,12 @@ struct ReduceExtras {
     const bf16_t* w;
     bf16_t* wfrag;
     int units, heads, ks;
+    float tscale;  // table scale of the I/O format for this N
 };
 
 // grid = (n_split, units [+ weight rows]), block = 64 * kReduceWaves.  Same partial layout
 // as the generic kernel: partial[u][s][StateLayout<D>::SIZE].
-template <int D>
+template <int D, typename X>
 __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
     int n_split, int chunk, float eps, int heads, TensorStrides st, ReduceExtras ex)
@@ -212,12 +279,12 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
             float ss = 0.f;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                kf[2 * i] = __uint_as_float(kw[i] << 16);
-                kf[2 * i + 1] = __uint_as_float(kw[i] & 0xffff0000u);
+                kf[2 * i] = X::lo(kw[i]);
+                kf[2 * i + 1] = X::hi(kw[i]);
                 ss = fmaf(kf[2 * i], kf[2 * i], ss);
                 ss = fmaf(kf[2 * i + 1], kf[2 * i + 1], ss);
-                vsum[2 * i] += __uint_as_float(vw[i] << 16);
-                vsum[2 * i + 1] += __uint_as_float(vw[i] & 0xffff0000u);
+                vsum[2 * i] += X::lo(vw[i]);
+                vsum[2 * i + 1] += X::hi(vw[i]);
             }
             ss = row_group_sum<LPR>(ss);
             // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
@@ -228,7 +295,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                 const float a = kf[2 * i] * inv, b = kf[2 * i + 1] * inv;
                 ksum[2 * i] += a;
                 ksum[2 * i + 1] += b;
-                kh[i] = pack_bf16x2(a, b);
+                kh[i] = X::pack(a, b);
             }
             const int row = j * TPL + lrow;
             *reinterpret_cast<u32x4_t*>(ks_tile + row * PITCH + lcol * 2) = kh;
@@ -239,7 +306,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int s = 0; s < kReduceIterTokens / 16; ++s) {
-            bf16x8_t a[MT], b[MT];
+            u32x4_t a[MT], b[MT];
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
                 a[t] = lds_operand_tr(ks_tile, PITCH, 16 * s, 32 * t, lane);
@@ -249,8 +316,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < MT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt],
-                                                                          0, 0, 0);
+                    acc[mt][nt] = X::mfma32(a[mt], b[nt], acc[mt][nt]);
         }
         __builtin_amdgcn_wave_barrier();
     };
@@ -301,12 +367,12 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
         __syncthreads();
         if constexpr (D == 64) {
             if (ex.state) {
-                // ksum operand table: entry (ks, lane, e2) holds ksum[32 ks + 8 (lane / 16) + 2 e2 .. +1] / pi
+                // ksum operand table: entry (ks, lane, e2) holds ksum[32 ks + 8 (lane / 16) + 2 e2 .. +1] * scale
                 uint32_t* dst = reinterpret_cast<uint32_t*>(ex.kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
                 for (int u = tid; u < kKfragPerUnit / 2; u += 64 * NW) {
                     const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
                     const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
-                    dst[u] = pack_bf16x2(sums[NW * 64 * 16 + i0] * kInvPi, sums[NW * 64 * 16 + i0 + 1] * kInvPi);
+                    dst[u] = X::pack(sums[NW * 64 * 16 + i0] * ex.tscale, sums[NW * 64 * 16 + i0 + 1] * ex.tscale);
                 }
                 __syncthreads();
             }
@@ -364,7 +430,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                     }
             if constexpr (D == 64) {
                 if (ex.state) {
-                    // final result: fp32 state and the S operand table (bf16 pairs of S / pi)
+                    // final result: fp32 state and the S operand table (16-bit pairs of S * scale)
                     float* st = ex.state + static_cast<size_t>(unit) * L::SIZE + L::S;
                     uint32_t* sf = reinterpret_cast<uint32_t*>(ex.sfrag + static_cast<size_t>(unit) * kSfragPerUnit);
 #pragma unroll
@@ -380,7 +446,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                                     // table entry ((j/16)*2 + i/32, lane' = ((i%32)/8)*16 + j%16, (i%8)/2)
                                     const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
                                                   ((i & 7) >> 1);
-                                    sf[t] = pack_bf16x2(acc[mt][nt][r] * kInvPi, acc[mt][nt][r + 1] * kInvPi);
+                                    sf[t] = X::pack(acc[mt][nt][r] * ex.tscale, acc[mt][nt][r + 1] * ex.tscale);
                                 }
                             }
                 }

@@ -8,6 +8,12 @@ from paper_2211_10526_amd import inputs
 # fp16 I/O (fp32 products and accumulation): the output rounding, 2^-11 = 4.9e-4 relative,
 # dominates; 1e-3 leaves a factor of two
 TOL = {"f32": 1e-4, "bf16": 1e-2, "f16": 1e-3}
+# The exported state K_hat^T V: the matrix-core kernels round k_hat to the I/O format before
+# the contraction, so every product carries up to half an ulp (2^-11 for fp16) of relative
+# error; against rms(S) that is about 2^-11 / sqrt(3) per element and about 4.5 times as much
+# at the maximum over 10^6 elements: 1.3e-3 for fp16 (bf16, 8 times coarser, stays inside its
+# 1e-2).  The state is an intermediate, not an output of the layer.
+STATE_TOL = {"f32": 1e-4, "bf16": 1e-2, "f16": 2.5e-3}
 
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:

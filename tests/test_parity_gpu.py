@@ -9,7 +9,7 @@ import torch
 from paper_2211_10526_amd import binding as b
 from paper_2211_10526_amd import inputs
 from paper_2211_10526_amd.inputs import Workload
-from parity_util import TOL, gpu_forward, gpu_forward_fused, oracle_inputs, rel_err
+from parity_util import STATE_TOL, TOL, gpu_forward, gpu_forward_fused, oracle_inputs, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,9 @@ WIDE = [
     Workload("w_f16_d64_14x14_k3", "f16", 2, 4, 64, 14, 14, 3),
     Workload("w_f16_d32_13x19_k9", "f16", 1, 3, 32, 13, 19, 9),
     Workload("w_f16_d64_33x40_k5", "f16", 1, 2, 64, 33, 40, 5),
+    Workload("w_f16_d64_24x24_k9_outl", "f16", 2, 2, 64, 24, 24, 9, 0.05, 8.0),
+    Workload("w_f16_d64_20x36_k7", "f16", 1, 3, 64, 20, 36, 7),
+    Workload("w_f16_d64_1x40_k1", "f16", 1, 2, 64, 1, 40, 1),
 ]
 
 
@@ -66,7 +69,7 @@ def test_wide_shapes_and_fp16(oracle, wl, norm):
                                        branches=branches)
         if branches & b.BRANCH_LINEAR:
             got, st = gpu_forward(wl, x, norm=norm, branches=branches, want_state=True)
-            assert rel_err(st, oracle.state(k, v)) <= TOL[wl.dtype]
+            assert rel_err(st, oracle.state(k, v)) <= STATE_TOL[wl.dtype]
         else:  # the convolution alone reduces nothing: there is no state to fetch
             got = gpu_forward(wl, x, norm=norm, branches=branches)
         assert np.isfinite(got).all()
@@ -134,15 +137,20 @@ def test_state_against_oracle(oracle, wl):
     for name, sl in (("KtV", (slice(0, d), slice(0, d))), ("ksum", (slice(0, d), d)),
                      ("vsum", (d, slice(0, d))), ("count", (d, d))):
         g, o = st[(..., *sl)], want[(..., *sl)]
-        assert rel_err(g, o) <= TOL[wl.dtype], (wl.name, name)
+        assert rel_err(g, o) <= STATE_TOL[wl.dtype], (wl.name, name)
 
 
-@pytest.mark.parametrize("idx", range(5))
+FULL_SIZE = list(inputs.WORKLOADS) + [inputs.workload("x_f16_b2_h12_d64_n16384_k9"),
+                                      inputs.workload("x_f16_b64_h8_d64_n196_k3")]
+
+
+@pytest.mark.parametrize("idx", range(len(FULL_SIZE)), ids=lambda i: FULL_SIZE[i].name)
 def test_benchmark_workload_full_size(oracle, idx):
-    """The five benchmark workloads at full size: every element against the oracle's
-    reassociated form (itself pinned to the definition), sampled rows against the
-    definition, per branch, plus the exported state."""
-    wl = inputs.WORKLOADS[idx]
+    """The five benchmark workloads (and the fp16 twins of the largest and of the one-kernel
+    case) at full size: every element against the oracle's reassociated form (itself pinned
+    to the definition), sampled rows against the definition, per branch, plus the exported
+    state."""
+    wl = FULL_SIZE[idx]
     print(f"case full {wl.name}", flush=True)
     x = inputs.make_inputs(wl)
     q, k, v, w, bias = oracle_inputs(x)
@@ -166,9 +174,10 @@ def test_benchmark_workload_full_size(oracle, idx):
     _, st = gpu_forward(wl, x, want_state=True)
     want_st = oracle.state(k, v)
     d = wl.d
-    assert rel_err(st[..., :d, :d], want_st[..., :d, :d]) <= tol
-    assert rel_err(st[..., :d, d], want_st[..., :d, d]) <= tol
-    assert rel_err(st[..., d, :d], want_st[..., d, :d]) <= tol
+    stol = STATE_TOL[wl.dtype]
+    assert rel_err(st[..., :d, :d], want_st[..., :d, :d]) <= stol
+    assert rel_err(st[..., :d, d], want_st[..., :d, d]) <= stol
+    assert rel_err(st[..., d, :d], want_st[..., d, :d]) <= stol
 
 
 def test_outlier_scaling_leaves_weights_unchanged(oracle):
