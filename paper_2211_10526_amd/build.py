@@ -32,12 +32,28 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + [SRC, "-o", LIB]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", SRC, "-o", LIB]
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass does not know the target feature and says so; that is harmless
-    log = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+    lines = [l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l]
+    # Kernels here issue global loads whose landing they track themselves; the compiler must
+    # never spill such a register while the load is in flight, so no kernel may use scratch.
+    spilled, name = [], ""
+    for l in lines:
+        if "Function Name:" in l:
+            name = l.split("Function Name:")[1].split("[")[0].strip()
+        elif "ScratchSize [bytes/lane]:" in l:
+            if int(l.split("ScratchSize [bytes/lane]:")[1].split("[")[0].strip()) != 0:
+                spilled.append(name)
+    import re
+    noise = re.compile(r"remark:|-Rpass-analysis|^In file included from|^\s*\d*\s*\|")
+    log = "\n".join(l for l in lines if l.strip() and not noise.search(l))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + log)
+    if spilled:
+        os.remove(LIB)
+        raise RuntimeError("kernels with register spills (not allowed, see build.py):\n  " +
+                           "\n  ".join(spilled))
     if verbose and log.strip():
         print(log)
     return LIB
