@@ -26,6 +26,9 @@
  *                           linear attention; Eq. 3 sums)
  *   oracle_forward          fast path: Eq. 3 with phi(x) = [x/|x| / sqrt(pi);
  *                           1/sqrt(2)] so that phi(q).phi(k) = 1/2 + q.k/pi
+ *   oracle_softmax_probs    the softmax attention map inside Eq. 10
+ *   oracle_sparse_attn      Eq. 10 (masked softmax attention) applied to V
+ *   oracle_angular_attn     attention with the exact angular kernel, Eq. 4-5
  *
  * Readings taken where the paper is silent (also listed in the design notes):
  *   - the 1/2 term multiplies the column sum of V (Eq. 8 gives Sim_ij = 1/2 +
@@ -308,6 +311,105 @@ void oracle_forward(const double* q, const double* k, const double* v,
         free(qh);
     }
     free(state);
+}
+
+/* ------------------------------------------------------------------------
+ * Training-time companions of the layer (Sec. 3.2.2, Eq. 10) and the exact
+ * angular kernel it approximates (Eq. 4-5), as O(N^2) attention.
+ *
+ * Readings where the paper is silent: Eq. 10 prints Softmax(Q K^T) with no
+ * scale; `normalize` chooses unit rows (the Q, K the angular branch uses) or the
+ * raw ones, `scale` multiplies the logits (1 = as printed, 1/sqrt(d) = Eq. 1's
+ * convention).  Mask_thr(x) = x if x > thr else 0 (strict, as printed).
+ * ---------------------------------------------------------------------- */
+
+/* P[t][j] = Softmax_j(scale * <a_t, b_j>), one head; a, b = q, k or their unit rows. */
+void oracle_softmax_probs(const double* q, const double* k, int N, int d, int normalize,
+                          double scale, double eps, double* P)
+{
+    double* qh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    if (normalize) {
+        oracle_l2_normalize(q, N, d, eps, qh);
+        oracle_l2_normalize(k, N, d, eps, kh);
+    } else {
+        memcpy(qh, q, sizeof(double) * (size_t)N * d);
+        memcpy(kh, k, sizeof(double) * (size_t)N * d);
+    }
+    for (int t = 0; t < N; ++t) {
+        double* row = P + (size_t)t * N;
+        double mx = -INFINITY;
+        for (int j = 0; j < N; ++j) {
+            double x = 0.0;
+            for (int c = 0; c < d; ++c) x += qh[t * d + c] * kh[j * d + c];
+            row[j] = scale * x;
+            if (row[j] > mx) mx = row[j];
+        }
+        double sum = 0.0;
+        for (int j = 0; j < N; ++j) {
+            row[j] = exp(row[j] - mx);
+            sum += row[j];
+        }
+        for (int j = 0; j < N; ++j) row[j] /= sum;
+    }
+    free(qh);
+    free(kh);
+}
+
+/* Eq. 10 applied to V for every unit: out_t = sum_j Mask_thr(P_tj) v_j;
+ * nnz[unit] = number of entries the mask keeps. */
+void oracle_sparse_attn(const double* q, const double* k, const double* v, int B, int heads,
+                        int N, int d, int normalize, double scale, double thr, double eps,
+                        double* out, int64_t* nnz)
+{
+    const int units = B * heads;
+#pragma omp parallel for schedule(dynamic)
+    for (int u = 0; u < units; ++u) {
+        const size_t off = (size_t)u * N * d;
+        double* P = (double*)malloc(sizeof(double) * (size_t)N * N);
+        oracle_softmax_probs(q + off, k + off, N, d, normalize, scale, eps, P);
+        int64_t kept = 0;
+        for (int t = 0; t < N; ++t) {
+            double* o = out + off + (size_t)t * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                const double p = P[(size_t)t * N + j];
+                if (p > thr) {
+                    ++kept;
+                    for (int c = 0; c < d; ++c) o[c] += p * v[off + (size_t)j * d + c];
+                }
+            }
+        }
+        nnz[u] = kept;
+        free(P);
+    }
+}
+
+/* Attention with the exact angular kernel (Eq. 5) in place of its linear terms:
+ * out_t = sum_j A_tj v_j / sum_j A_tj (norm_mode 0, Eq. 3's form) or the bare sum. */
+void oracle_angular_attn(const double* q, const double* k, const double* v, int B, int heads,
+                         int N, int d, int norm_mode, double eps, double* out)
+{
+    const int units = B * heads;
+#pragma omp parallel for schedule(dynamic)
+    for (int u = 0; u < units; ++u) {
+        const size_t off = (size_t)u * N * d;
+        double* A = (double*)malloc(sizeof(double) * (size_t)N * N);
+        oracle_sim_angular(q + off, k + off, N, d, eps, A);
+        for (int t = 0; t < N; ++t) {
+            double* o = out + off + (size_t)t * d;
+            double den = 0.0;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                const double a = A[(size_t)t * N + j];
+                den += a;
+                for (int c = 0; c < d; ++c) o[c] += a * v[off + (size_t)j * d + c];
+            }
+            if (norm_mode == 0)
+                for (int c = 0; c < d; ++c) o[c] /= den;
+        }
+        free(A);
+    }
 }
 
 /* Number of threads the parallel-for above will use (1 without OpenMP). */

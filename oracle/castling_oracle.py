@@ -45,6 +45,13 @@ def lib():
         L.oracle_forward.argtypes = fwd + [_dp]
         L.oracle_forward_explicit_rows.argtypes = fwd + [_ip, _ip, C.c_int64, _dp]
         L.oracle_state.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _dp]
+        L.oracle_softmax_probs.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_double,
+                                           C.c_double, _dp]
+        L.oracle_sparse_attn.argtypes = [_dp, _dp, _dp] + [C.c_int] * 5 + [C.c_double] * 3 + \
+            [_dp, C.POINTER(C.c_int64)]
+        L.oracle_angular_attn.argtypes = [_dp, _dp, _dp] + [C.c_int] * 5 + [C.c_double, _dp]
+        for name in ("oracle_softmax_probs", "oracle_sparse_attn", "oracle_angular_attn"):
+            getattr(L, name).restype = None
         L.oracle_num_threads.restype = C.c_int
         L.oracle_set_num_threads.argtypes = [C.c_int]
         for name in ("oracle_l2_normalize", "oracle_sim_angular", "oracle_sim_linear",
@@ -161,6 +168,35 @@ def state(k, v, eps=DEFAULT_EPS):
     st = np.empty((B, heads, d + 1, d + 1), dtype=np.float64)
     lib().oracle_state(_p(k), _p(v), B, heads, N, d, eps, _p(st))
     return st
+
+
+def softmax_probs(q, k, normalize=True, scale=1.0, eps=DEFAULT_EPS):
+    """One head: q, k [N, d] -> P [N, N], the softmax attention map inside Eq. 10."""
+    q, k = _f64(q), _f64(k)
+    N, d = q.shape
+    P = np.empty((N, N), dtype=np.float64)
+    lib().oracle_softmax_probs(_p(q), _p(k), N, d, int(bool(normalize)), scale, eps, _p(P))
+    return P
+
+
+def sparse_attn(q, k, v, thr, normalize=True, scale=1.0, eps=DEFAULT_EPS):
+    """Eq. 10 applied to V: (out [B, heads, N, d], kept entries per unit [B, heads])."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, heads, N, d = q.shape
+    out = np.empty_like(q)
+    nnz = np.zeros((B, heads), dtype=np.int64)
+    lib().oracle_sparse_attn(_p(q), _p(k), _p(v), B, heads, N, d, int(bool(normalize)), scale,
+                             thr, eps, _p(out), nnz.ctypes.data_as(C.POINTER(C.c_int64)))
+    return out, nnz
+
+
+def angular_attn(q, k, v, norm=NORM_ROWSUM, eps=DEFAULT_EPS):
+    """Attention with the exact angular kernel of Eq. 5 instead of its linear terms."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, heads, N, d = q.shape
+    out = np.empty_like(q)
+    lib().oracle_angular_attn(_p(q), _p(k), _p(v), B, heads, N, d, norm, eps, _p(out))
+    return out
 
 
 def num_threads() -> int:
