@@ -124,6 +124,30 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
  * pointer, which must stay valid and unchanged.  forward() never uses this registration. */
 int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void* stream);
 
+/* Training-time companions of the layer as O(N^2) attention on the matrix cores (16-bit I/O
+ * with d = 64 only, else CASTLING_ERR_UNSUPPORTED).  Shapes, strides and eps come from the handle.
+ *   CASTLING_PAIR_SPARSE_SOFTMAX  out = Mask_thr(Softmax(scale * A B^T)) V, the auxiliary branch
+ *       of Eq. 10 (Sec. 3.2.2).  Mask_thr(x) = x if x > thr else 0.  A, B = unit rows of q, k
+ *       (normalize = 1, the rows the angular branch uses) or q, k themselves (normalize = 0);
+ *       scale multiplies the logits (Eq. 10 prints none, Eq. 1 uses 1/sqrt(d)).
+ *   CASTLING_PAIR_ANGULAR  out_t = sum_j A_tj v_j / sum_j A_tj with the exact angular kernel
+ *       A_tj = 1 - arccos(q_hat_t . k_hat_j) / pi of Eq. 4-5 (the handle's norm: with
+ *       CASTLING_NORM_NONE the division is left out); scale, threshold, normalize are ignored.
+ * kept: DEVICE pointer to B*heads counters, or NULL; SPARSE_SOFTMAX writes the number of entries
+ * the mask keeps per unit (the quantity whose decay to zero lets the branch be dropped at
+ * inference).  out must not overlap q, k or v. */
+typedef enum { CASTLING_PAIR_SPARSE_SOFTMAX = 0, CASTLING_PAIR_ANGULAR = 1 } castling_pair_mode_t;
+
+typedef struct {
+    int32_t mode;       /* castling_pair_mode_t */
+    int32_t normalize;  /* SPARSE_SOFTMAX: 1 = unit rows, 0 = raw rows */
+    float scale;        /* SPARSE_SOFTMAX: logit scale */
+    float threshold;    /* SPARSE_SOFTMAX: mask threshold, in [0, 1] */
+} castling_pair_params_t;
+
+int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* params, const void* q,
+                           const void* k, const void* v, void* out, uint64_t* kept, void* stream);
+
 /* NULL is a no-op returning CASTLING_OK. */
 int castling_attn_destroy(castling_attn_t h);
 

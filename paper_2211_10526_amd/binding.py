@@ -26,7 +26,7 @@ EXPORTS = (
     "castling_attn_reduce", "castling_attn_apply", "castling_attn_prepare_weights",
     "castling_attn_destroy",
     "castling_attn_workspace_bytes", "castling_attn_get_state", "castling_attn_num_splits",
-    "castling_attn_num_launches",
+    "castling_attn_num_launches", "castling_attn_pairwise",
     "castling_attn_strerror",
 )
 
@@ -39,6 +39,14 @@ class Desc(C.Structure):
                 ("in_stride_b", C.c_int64), ("in_stride_h", C.c_int64), ("in_stride_n", C.c_int64),
                 ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64),
                 ("out_stride_n", C.c_int64), ("flags", C.c_uint32)]
+
+
+PAIR_SPARSE_SOFTMAX, PAIR_ANGULAR = 0, 1
+
+
+class PairParams(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("normalize", C.c_int32), ("scale", C.c_float),
+                ("threshold", C.c_float)]
 
 
 class CastlingError(RuntimeError):
@@ -75,6 +83,7 @@ def lib():
         L.castling_attn_get_state.argtypes = [vp, vp, C.c_size_t, vp]
         L.castling_attn_num_splits.argtypes = [vp]
         L.castling_attn_num_launches.argtypes = [vp]
+        L.castling_attn_pairwise.argtypes = [vp, C.POINTER(PairParams)] + [vp] * 6
         L.castling_attn_strerror.argtypes = [C.c_int]
         L.castling_attn_strerror.restype = C.c_char_p
         _lib = L
@@ -154,6 +163,14 @@ class CastlingAttn:
     def apply(self, q, v, w, bias, out, stream=None):
         _check(lib().castling_attn_apply(self._h, _ptr(q), _ptr(v), _ptr(w), _ptr(bias),
                                          _ptr(out), _stream_ptr(stream)))
+        return out
+
+    def pairwise(self, mode, q, k, v, out, kept=None, normalize=True, scale=1.0, threshold=0.0,
+                 stream=None):
+        """castling_attn_pairwise; kept: int64 / uint64 device tensor [B * heads] or None."""
+        params = PairParams(mode, int(bool(normalize)), scale, threshold)
+        _check(lib().castling_attn_pairwise(self._h, C.byref(params), _ptr(q), _ptr(k), _ptr(v),
+                                            _ptr(out), _ptr(kept), _stream_ptr(stream)))
         return out
 
     def prepare_weights(self, w, stream=None):

@@ -14,6 +14,7 @@
 #include "apply_mfma.hpp"
 #include "common.hpp"
 #include "fused_small.hpp"
+#include "pairwise.hpp"
 #include "reduce_generic.hpp"
 #include "reduce_mfma.hpp"
 
@@ -599,6 +600,66 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
     // the matrix-core path already holds the registered filters in its operand table
     HIP_TRY(do_apply(h, true, q, v, (registered && h->mfma_apply) ? nullptr : w, dw_bias, out,
                      static_cast<hipStream_t>(stream)));
+    return CASTLING_OK;
+}
+
+int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* params, const void* q,
+                           const void* k, const void* v, void* out, uint64_t* kept, void* stream)
+{
+    if (!h || !params || !q || !k || !v || !out) return CASTLING_ERR_INVALID_ARG;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(out))
+        return CASTLING_ERR_INVALID_ARG;
+    if (params->mode != CASTLING_PAIR_SPARSE_SOFTMAX && params->mode != CASTLING_PAIR_ANGULAR)
+        return CASTLING_ERR_INVALID_ARG;
+    const bool sparse = params->mode == CASTLING_PAIR_SPARSE_SOFTMAX;
+    if (sparse && (!(params->threshold >= 0.0f) || !(params->threshold <= 1.0f) ||
+                   !(params->scale == params->scale) || (params->normalize & ~1)))
+        return CASTLING_ERR_INVALID_ARG;
+    if (kept && (reinterpret_cast<uintptr_t>(kept) & 7u)) return CASTLING_ERR_INVALID_ARG;
+    if (overlaps(out, h->out_span, q, h->in_span) || overlaps(out, h->out_span, k, h->in_span) ||
+        overlaps(out, h->out_span, v, h->in_span))
+        return CASTLING_ERR_ALIAS;
+    const castling_attn_desc_t& d = h->desc;
+    const bool half = d.io_dtype == CASTLING_F16;
+    if ((d.io_dtype != CASTLING_BF16 && !half) || d.d != 64) return CASTLING_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    PairParams p;
+    p.N = d.N;
+    p.normalize = params->normalize;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.scale = params->scale;
+    p.threshold = params->threshold;
+    p.eps = d.eps;
+    p.in = h->in_st;
+    p.out = h->out_st;
+    unsigned long long* cnt = reinterpret_cast<unsigned long long*>(kept);
+    if (sparse && cnt) {
+        // counters start at zero; a fill kernel, so that the call can be captured in a graph
+        hipLaunchKernelGGL(zero_u64_kernel, dim3((h->units + 255) / 256), dim3(256), 0, s, cnt,
+                           h->units);
+        HIP_TRY(hipGetLastError());
+    }
+    const dim3 grid((d.N + 127) / 128, h->units), block(256);
+    const bf16_t* q16 = static_cast<const bf16_t*>(q);
+    const bf16_t* k16 = static_cast<const bf16_t*>(k);
+    const bf16_t* v16 = static_cast<const bf16_t*>(v);
+    bf16_t* o16 = static_cast<bf16_t*>(out);
+    if (sparse) {
+        if (half)
+            hipLaunchKernelGGL((pairwise_attn_kernel<kPairSparse, F16Fmt>), grid, block, 0, s, q16,
+                               k16, v16, o16, cnt, d.heads, p);
+        else
+            hipLaunchKernelGGL((pairwise_attn_kernel<kPairSparse, Bf16Fmt>), grid, block, 0, s, q16,
+                               k16, v16, o16, cnt, d.heads, p);
+    } else {
+        if (half)
+            hipLaunchKernelGGL((pairwise_attn_kernel<kPairAngular, F16Fmt>), grid, block, 0, s, q16,
+                               k16, v16, o16, nullptr, d.heads, p);
+        else
+            hipLaunchKernelGGL((pairwise_attn_kernel<kPairAngular, Bf16Fmt>), grid, block, 0, s,
+                               q16, k16, v16, o16, nullptr, d.heads, p);
+    }
+    HIP_TRY(hipGetLastError());
     return CASTLING_OK;
 }
 

@@ -1,0 +1,190 @@
+"""GPU parity of castling_attn_pairwise (through the C ABI) against the CPU oracle: the masked
+softmax branch of Eq. 10 and attention with the exact angular kernel of Eq. 4-5.
+
+The mask of Eq. 10 is a floating-point decision (p > thr).  The kernel takes it in fp32 (exact
+products of the stored q and k, fp32 norms, exp and sums), the oracle in fp64, so a probability
+within a relative distance `delta` = 1e-4 of the threshold may legitimately fall on either
+side: both outcomes are valid.  The checks therefore take the oracle's probabilities, call
+every entry with |p - thr| <= delta * thr "borderline", and allow each output element to differ
+by the usual tolerance plus the borderline terms of its row; the kept-entry counts may differ
+by at most the number of borderline entries."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2211_10526_amd import binding as b
+from paper_2211_10526_amd import inputs
+from paper_2211_10526_amd.inputs import Workload
+from parity_util import TOL, oracle_inputs, rel_err
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [
+    Workload("p_bf16_14x14", "bf16", 2, 3, 64, 14, 14, 3),
+    Workload("p_bf16_1x33", "bf16", 1, 2, 64, 1, 33, 3),
+    Workload("p_bf16_19x27", "bf16", 1, 2, 64, 19, 27, 3),      # 513 tokens: ragged tile and block
+    Workload("p_f16_16x16", "f16", 2, 2, 64, 16, 16, 3),
+    Workload("p_f16_9x15", "f16", 1, 3, 64, 9, 15, 3),
+    Workload("p_bf16_1x1", "bf16", 1, 1, 64, 1, 1, 3),
+    Workload("p_bf16_28x28_outl", "bf16", 1, 2, 64, 28, 28, 3, 0.05, 8.0),
+]
+
+
+def run_pairwise(wl, x, mode, fused_layout=False, **kw):
+    dev = torch.device("cuda:0")
+    B, H, N, d = wl.B, wl.heads, wl.N, wl.d
+    kept = torch.full((B * H,), -1, dtype=torch.int64, device=dev)
+    if fused_layout:
+        qkv = torch.empty((B, N, 3, H, d), dtype=x["q"].dtype, device=dev)
+        for i, n in enumerate(("q", "k", "v")):
+            qkv[:, :, i] = x[n].to(dev).permute(0, 2, 1, 3)
+        q, k, v = (qkv[:, :, i] for i in range(3))
+        out = torch.full((B, N, H * d), float("nan"), dtype=x["q"].dtype, device=dev)
+        attn = b.CastlingAttn.for_workload(wl, norm=kw.pop("norm", b.NORM_ROWSUM),
+                                           in_strides=b.fused_qkv_strides(H, N, d),
+                                           out_strides=b.token_major_strides(H, N, d))
+    else:
+        q, k, v = (x[n].to(dev) for n in ("q", "k", "v"))
+        out = torch.full_like(q, float("nan"))
+        attn = b.CastlingAttn.for_workload(wl, norm=kw.pop("norm", b.NORM_ROWSUM))
+    attn.pairwise(mode, q, k, v, out, kept=kept, **kw)
+    torch.cuda.synchronize()
+    attn.destroy()
+    if fused_layout:
+        out = out.view(B, N, H, d).permute(0, 2, 1, 3).contiguous()
+    return inputs.to_f64(out), kept.cpu().numpy().reshape(B, H)
+
+
+def check_sparse(oracle, wl, x, thr, normalize, scale, got, got_kept):
+    q, k, v, _, _ = oracle_inputs(x)
+    want, want_kept = oracle.sparse_attn(q, k, v, thr, normalize=normalize, scale=scale)
+    tol = TOL[wl.dtype]
+    delta = 1e-4
+    rms = float(np.sqrt(np.mean(want * want))) if want.any() else 0.0
+    for bi in range(wl.B):
+        for h in range(wl.heads):
+            P = oracle.softmax_probs(q[bi, h], k[bi, h], normalize=normalize, scale=scale)
+            border = np.abs(P - thr) <= delta * thr
+            slack = (np.where(border, P, 0.0) * (1.0 + delta)) @ np.abs(v[bi, h])
+            allowed = tol * np.maximum(np.abs(want[bi, h]), max(rms, 1e-30)) + slack
+            if thr == 0.0:
+                assert not border.any()
+            assert (np.abs(got[bi, h] - want[bi, h]) <= allowed).all(), (wl.name, thr, bi, h)
+            assert abs(int(got_kept[bi, h]) - int(want_kept[bi, h])) <= int(border.sum())
+    return want_kept
+
+
+@pytest.mark.parametrize("wl", SHAPES, ids=lambda w: w.name)
+@pytest.mark.parametrize("thr", [0.0, 0.004, 0.02])
+def test_sparse_softmax_unit_rows(oracle, wl, thr):
+    x = inputs.make_inputs(wl, seed=41)
+    for scale in (1.0, 8.0):
+        print(f"case sparse {wl.name} thr={thr} scale={scale}", flush=True)
+        got, kept = run_pairwise(wl, x, b.PAIR_SPARSE_SOFTMAX, normalize=True, scale=scale,
+                                 threshold=thr)
+        assert np.isfinite(got).all()
+        want_kept = check_sparse(oracle, wl, x, thr, True, scale, got, kept)
+        if thr == 0.0:
+            assert (kept == wl.N * wl.N).all() and (want_kept == wl.N * wl.N).all()
+
+
+@pytest.mark.parametrize("wl", SHAPES[:4], ids=lambda w: w.name)
+def test_sparse_softmax_raw_rows(oracle, wl):
+    x = inputs.make_inputs(wl, seed=42)
+    scale = wl.d ** -0.5                                   # Eq. 1's convention
+    for thr in (0.0, 0.02):
+        print(f"case sparse raw {wl.name} thr={thr}", flush=True)
+        got, kept = run_pairwise(wl, x, b.PAIR_SPARSE_SOFTMAX, normalize=False, scale=scale,
+                                 threshold=thr)
+        check_sparse(oracle, wl, x, thr, False, scale, got, kept)
+
+
+def test_sparse_threshold_one_keeps_nothing():
+    wl = SHAPES[0]
+    x = inputs.make_inputs(wl, seed=43)
+    got, kept = run_pairwise(wl, x, b.PAIR_SPARSE_SOFTMAX, threshold=1.0)
+    assert not got.any() and not kept.any()
+
+
+@pytest.mark.parametrize("wl", SHAPES, ids=lambda w: w.name)
+@pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
+def test_angular_kernel_attention(oracle, wl, norm):
+    x = inputs.make_inputs(wl, seed=44)
+    q, k, v, _, _ = oracle_inputs(x)
+    print(f"case angular {wl.name} norm={norm}", flush=True)
+    got, _ = run_pairwise(wl, x, b.PAIR_ANGULAR, norm=norm)
+    want = oracle.angular_attn(q, k, v, norm=norm)
+    assert rel_err(got, want) <= TOL[wl.dtype]
+
+
+def test_linear_angular_layer_approximates_the_angular_kernel(oracle):
+    """What the layer is for: its linear branch tracks attention with the exact kernel.  For
+    independent random rows in d = 64 the dot products are small (|x| ~ 1/8), where the dropped
+    odd terms of Eq. 8 are of order x^3 / (6 pi): the two agree to a few 1e-4 of the value scale,
+    and the same holds between the two GPU paths."""
+    wl = Workload("gap_bf16", "bf16", 1, 2, 64, 16, 16, 3)
+    x = inputs.make_inputs(wl, seed=45)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    exact, _ = run_pairwise(wl, x, b.PAIR_ANGULAR)
+    lin_attn = b.CastlingAttn.for_workload(wl, branches=b.BRANCH_LINEAR)
+    out = torch.empty_like(t["q"])
+    lin_attn.forward(t["q"], t["k"], t["v"], t["w"], None, out)
+    torch.cuda.synchronize()
+    lin_attn.destroy()
+    assert rel_err(inputs.to_f64(out), exact) <= 2e-2
+
+
+def test_pairwise_strided_layout_and_determinism():
+    wl = SHAPES[2]
+    x = inputs.make_inputs(wl, seed=46)
+    for mode, kw in ((b.PAIR_SPARSE_SOFTMAX, dict(threshold=0.004, scale=4.0)), (b.PAIR_ANGULAR, {})):
+        a, ka = run_pairwise(wl, x, mode, **dict(kw))
+        c, kc = run_pairwise(wl, x, mode, **dict(kw))
+        assert np.array_equal(a, c) and np.array_equal(ka, kc)          # run to run
+        f, kf = run_pairwise(wl, x, mode, fused_layout=True, **dict(kw))
+        assert np.array_equal(a, f) and np.array_equal(ka, kf)          # strided views
+
+
+def test_pairwise_larger_grid_sampled(oracle):
+    """64 x 64 tokens: a unit of the size of the fourth benchmark workload."""
+    wl = Workload("p_bf16_64x64", "bf16", 1, 2, 64, 64, 64, 3)
+    x = inputs.make_inputs(wl, seed=47)
+    q, k, v, _, _ = oracle_inputs(x)
+    got, kept = run_pairwise(wl, x, b.PAIR_SPARSE_SOFTMAX, normalize=True, scale=8.0,
+                             threshold=0.0005)
+    check_sparse(oracle, wl, x, 0.0005, True, 8.0, got, kept)
+    got, _ = run_pairwise(wl, x, b.PAIR_ANGULAR)
+    assert rel_err(got, oracle.angular_attn(q, k, v)) <= TOL[wl.dtype]
+
+
+def test_pairwise_argument_errors():
+    dev = torch.device("cuda:0")
+    wl = SHAPES[0]
+    x = inputs.make_inputs(wl)
+    q, k, v = (x[n].to(dev) for n in ("q", "k", "v"))
+    out = torch.empty_like(q)
+    attn = b.CastlingAttn.for_workload(wl)
+    for bad in (dict(threshold=-0.1), dict(threshold=1.5), dict(threshold=float("nan")),
+                dict(scale=float("nan"))):
+        with pytest.raises(b.CastlingError) as e:
+            attn.pairwise(b.PAIR_SPARSE_SOFTMAX, q, k, v, out, **bad)
+        assert e.value.status == b.ERR_INVALID_ARG
+    with pytest.raises(b.CastlingError) as e:
+        attn.pairwise(7, q, k, v, out)
+    assert e.value.status == b.ERR_INVALID_ARG
+    with pytest.raises(b.CastlingError) as e:
+        attn.pairwise(b.PAIR_ANGULAR, q, k, v, v)
+    assert e.value.status == b.ERR_ALIAS
+    with pytest.raises(b.CastlingError) as e:
+        attn.pairwise(b.PAIR_ANGULAR, None, k, v, out)
+    assert e.value.status == b.ERR_INVALID_ARG
+    attn.destroy()
+    for other in (Workload("e_f32", "f32", 1, 1, 64, 4, 4, 3), Workload("e_d32", "bf16", 1, 1, 32, 4, 4, 3)):
+        y = inputs.make_inputs(other)
+        q, k, v = (y[n].to(dev) for n in ("q", "k", "v"))
+        attn = b.CastlingAttn.for_workload(other)
+        with pytest.raises(b.CastlingError) as e:
+            attn.pairwise(b.PAIR_ANGULAR, q, k, v, torch.empty_like(q))
+        assert e.value.status == b.ERR_UNSUPPORTED
+        attn.destroy()
