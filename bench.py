@@ -48,11 +48,62 @@ def parse_args():
     ap.add_argument("--layout", choices=("dense", "fused"), default="dense",
                     help="dense: q, k, v, out contiguous [B,heads,N,d] (the benchmark configs); "
                          "fused: q, k, v slices of one [B,N,3,heads,d] tensor, out [B,N,heads*d]")
+    ap.add_argument("--pairwise", choices=("sparse", "angular"), default=None,
+                    help="time castling_attn_pairwise (masked softmax branch of Eq. 10 / exact "
+                         "angular-kernel attention) instead of the layer; MFMA roofline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three 256 MiB device-to-device copies: a kernel of known "
                          "traffic that scales the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     return ap.parse_args()
+
+
+def bench_pairwise(args, wl, sets, binding, inputs, torch):
+    """K calls of castling_attn_pairwise over the rotating input sets; one JSON line.  The
+    roofline is the dense bf16 / fp16 MFMA peak against the algorithmic flops 4 N^2 d per unit
+    (one Q K^T and one P V; the kernel itself runs Q K^T twice for the softmax and P V on a
+    two-part split of P)."""
+    mode = binding.PAIR_SPARSE_SOFTMAX if args.pairwise == "sparse" else binding.PAIR_ANGULAR
+    attn = binding.CastlingAttn.for_workload(wl)
+    stream = torch.cuda.Stream()
+    kept = torch.zeros(wl.units, dtype=torch.int64, device=sets[0]["q"].device)
+    kw = dict(normalize=True, scale=8.0, threshold=0.02)
+
+    def call(t):
+        attn.pairwise(mode, t["q"], t["k"], t["v"], t["out"], kept=kept, stream=stream, **kw)
+
+    steps = max(1, min(args.steps, int(2e8 // (wl.N * wl.N * wl.units // 1000 + 1)) + 1))
+    with torch.cuda.stream(stream):
+        for i in range(min(args.warmup, 3)):
+            call(sets[i % len(sets)])
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(steps):
+            call(sets[i % len(sets)])
+        e1.record(stream)
+        stream.synchronize()
+        elapsed = time.perf_counter() - t0
+        kernel_ms = e0.elapsed_time(e1) / steps
+    flops = 4.0 * wl.units * wl.N * wl.N * wl.d
+    achieved = flops / (kernel_ms * 1e-3) / 1e12
+    peak = 2500.0  # TFLOP/s, dense bf16 / fp16 MFMA
+    attn.destroy()
+    print(json.dumps({
+        "metric": f"pairwise {args.pairwise} attention tokens/s per layer",
+        "value": round(wl.tokens * steps / elapsed, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": min(args.warmup, 3), "ms_per_step": round(elapsed * 1e3 / steps, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "d": wl.d, "N": wl.N,
+                   "op": f"pairwise_{args.pairwise}", **kw,
+                   "kept_per_unit": float(kept.float().mean().item())},
+        "roofline": {"bound": "mfma", "kernel": "pairwise_attn_kernel", "achieved": round(achieved, 1),
+                     "peak": peak, "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "traffic": None, "algorithmic_flops": flops, "kernel_ms": round(kernel_ms, 5)},
+        "cpu_baseline": None,
+    }))
 
 
 def main():
@@ -95,6 +146,8 @@ def main():
             cy.copy_(cx)
         torch.cuda.synchronize()
         del cx, cy
+    if args.pairwise:
+        return bench_pairwise(args, wl, sets, binding, inputs, torch)
     if args.layout == "fused":
         attn = binding.CastlingAttn.for_workload(
             wl, in_strides=binding.fused_qkv_strides(wl.heads, wl.N, wl.d),

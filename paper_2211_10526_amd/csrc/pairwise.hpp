@@ -116,7 +116,9 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
             *reinterpret_cast<u32x4_t*>(vtile + skey * kPairTilePitch + soct * 16) = in ? vpre : zero;
     };
     // S^T tile of this wave: register r <-> key 8 (r / 4) + 4 hsel + r % 4, this lane's query;
-    // raw dot products from the matrix cores, then scaled by the two reciprocal norms
+    // raw dot products from the matrix cores, then scaled by the two reciprocal norms and, for
+    // the softmax, by scale * log2(e) (the exponentials below are base 2)
+    const float qfac = MODE == kPairSparse ? qinv * p.scale * 1.44269504088896340736f : qinv;
     auto scores = [&](f32x16_t& s) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = 0.f;
@@ -129,15 +131,17 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
 #pragma unroll
         for (int a4 = 0; a4 < 4; ++a4) {
             const float4 ki = *reinterpret_cast<const float4*>(kinv + 8 * a4 + 4 * hsel);
-            s[4 * a4] *= qinv * ki.x;
-            s[4 * a4 + 1] *= qinv * ki.y;
-            s[4 * a4 + 2] *= qinv * ki.z;
-            s[4 * a4 + 3] *= qinv * ki.w;
+            s[4 * a4] *= qfac * ki.x;
+            s[4 * a4 + 1] *= qfac * ki.y;
+            s[4 * a4 + 2] *= qfac * ki.z;
+            s[4 * a4 + 3] *= qfac * ki.w;
         }
     };
-    auto key_of = [&](int tile, int r) { return 32 * tile + 8 * (r >> 2) + 4 * hsel + (r & 3); };
+    // keys past N exist only in the last tile, and only if N is not a multiple of 32
+    const int ragged_tile = (N & 31) ? n_tiles - 1 : -1;
+    auto key_valid = [&](int r) { return 32 * (n_tiles - 1) + 8 * (r >> 2) + 4 * hsel + (r & 3) < N; };
 
-    float row_max = -INFINITY, row_sum = 0.f;
+    float row_max = -INFINITY, row_sum = 0.f;  // of the base-2 logits
     if constexpr (MODE == kPairSparse) {
         // ---- first sweep: maximum and sum of exp of every row (online, per lane, then the
         // two lanes that share a query are merged)
@@ -148,17 +152,18 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
             if (t + 1 < n_tiles) prefetch(t + 1, false);
             f32x16_t s;
             scores(s);
-            float tmax = -INFINITY;
+            if (t == ragged_tile) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                s[r] = key_of(t, r) < N ? s[r] * p.scale : -INFINITY;
-                tmax = fmaxf(tmax, s[r]);
+                for (int r = 0; r < 16; ++r) s[r] = key_valid(r) ? s[r] : -INFINITY;
             }
+            float tmax = s[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, s[r]);
             const float nmax = fmaxf(row_max, tmax);
             if (nmax > -INFINITY) {
-                float acc = row_sum * __expf(row_max - nmax);
+                float acc = row_sum * __builtin_amdgcn_exp2f(row_max - nmax);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc += __expf(s[r] - nmax);
+                for (int r = 0; r < 16; ++r) acc += __builtin_amdgcn_exp2f(s[r] - nmax);
                 row_sum = acc;
                 row_max = nmax;
             }
@@ -166,10 +171,11 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
         }
         const float omax = __shfl_xor(row_max, 32, 64), osum = __shfl_xor(row_sum, 32, 64);
         const float m = fmaxf(row_max, omax);
-        row_sum = row_sum * __expf(row_max - m) + osum * __expf(omax - m);
+        row_sum = row_sum * __builtin_amdgcn_exp2f(row_max - m) + osum * __builtin_amdgcn_exp2f(omax - m);
         row_max = m;
     }
-    const float inv_sum = 1.0f / row_sum;  // SPARSE only; every row has at least one key
+    // SPARSE: p = 2^(logit - off); every row has at least one key, so the sum is positive
+    const float off = row_max + __builtin_amdgcn_logf(row_sum);
 
     // ---- main sweep
     f32x16_t acc[2];
@@ -178,7 +184,8 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[mt][r] = 0.f;
     float den = 0.f;
-    unsigned int n_kept = 0;
+    unsigned int n_kept = 0;  // wave total, uniform
+    const bool q_valid = qi < N;
     // transposing reads of V: the 16-lane group (lane / 16) covers channels 16 (group % 2) .. + 15
     // of its k-half; source lane s of a group reads key K0 + s / 4, channels 4 (s % 4) .. + 3
     const int vsrc = ((lane >> 2) & 3) * kPairTilePitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
@@ -190,29 +197,37 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
         if (t + 1 < n_tiles) prefetch(t + 1, true);
         f32x16_t s;
         scores(s);
+        if constexpr (MODE == kPairSparse) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float x = __builtin_amdgcn_exp2f(s[r] - off);
+                const bool keep = x > p.threshold;
+                s[r] = keep ? x : 0.f;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                s[r] = 1.0f - acosf(fminf(fmaxf(s[r], -1.0f), 1.0f)) * kInvPi;
+        }
+        if (t == ragged_tile) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[r] = key_valid(r) ? s[r] : 0.f;
+        }
         u32x4_t pop[2], plo[2];  // probabilities and their rounding remainders, 16-bit pairs
 #pragma unroll
         for (int r = 0; r < 16; r += 2) {
-            float pr[2];
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                const bool valid = key_of(t, r + e) < N;
-                float x;
-                if constexpr (MODE == kPairSparse) {
-                    x = valid ? __expf(s[r + e] * p.scale - row_max) * inv_sum : 0.f;
-                    const bool keep = x > p.threshold;
-                    n_kept += (keep && valid) ? 1u : 0u;
-                    x = keep ? x : 0.f;
-                } else {
-                    const float c = fminf(fmaxf(s[r + e], -1.0f), 1.0f);
-                    x = valid ? 1.0f - acosf(c) * kInvPi : 0.f;
-                    den += x;
+            if constexpr (MODE == kPairSparse) {
+                // kept entries are exactly the nonzero ones (a kept probability is > thr >= 0)
+                if (kept) {
+                    n_kept += __builtin_popcountll(__ballot(q_valid && s[r] != 0.f));
+                    n_kept += __builtin_popcountll(__ballot(q_valid && s[r + 1] != 0.f));
                 }
-                pr[e] = x;
+            } else {
+                den += s[r] + s[r + 1];
             }
-            const uint32_t hi = X::pack(pr[0], pr[1]);
+            const uint32_t hi = X::pack(s[r], s[r + 1]);
             pop[r >> 3][(r >> 1) & 3] = hi;
-            plo[r >> 3][(r >> 1) & 3] = X::pack(pr[0] - X::lo(hi), pr[1] - X::hi(hi));
+            plo[r >> 3][(r >> 1) & 3] = X::pack(s[r] - X::lo(hi), s[r + 1] - X::hi(hi));
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -248,12 +263,7 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
             }
     }
     if constexpr (MODE == kPairSparse) {
-        if (kept) {
-            unsigned int c = (qi < N) ? n_kept : 0u;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) c += __shfl_xor(c, off, 64);
-            if (lane == 0) atomicAdd(kept + unit, static_cast<unsigned long long>(c));
-        }
+        if (kept && lane == 0) atomicAdd(kept + unit, static_cast<unsigned long long>(n_kept));
     }
 }
 
