@@ -37,7 +37,11 @@
  *     denominator); norm_mode 1 is the literal Eq. 9 with no denominator;
  *   - DWConv: zero "same" padding, stride 1, cross-correlation (no flip),
  *     added outside the division;
- *   - x / max(|x|, eps).
+ *   - x / max(|x|, eps);
+ *   - tokens that are not on the grid (`extra` class tokens in front of the H*W
+ *     grid tokens of a unit): they are keys and queries of the attention sums
+ *     like any other token, and the DWConv term, defined on the grid (Sec.
+ *     3.2.1), is zero for them and does not read them.
  *
  * Pins (tests/test_oracle_pins.py): closed forms for tiny cases, arccos /
  * arcsin identities, textbook arcsin series coefficients, row-stochastic
@@ -121,9 +125,10 @@ void oracle_sim_linear(const double* q, const double* k, int N, int d, double ep
     free(kh);
 }
 
-/* One output value of the DWConv term of Eq. 9 at (b, h, y, x, c). */
+/* One output value of the DWConv term of Eq. 9 at (b, h, y, x, c).  A unit holds `extra`
+ * tokens that are not on the grid (class tokens) before its H*W grid tokens. */
 static double dwconv_at(const double* v, const double* w, const double* bias,
-                        int heads, int H, int W, int d, int ks,
+                        int heads, int H, int W, int d, int ks, int extra,
                         int b, int h, int y, int x, int c)
 {
     const int r = ks / 2;
@@ -133,7 +138,7 @@ static double dwconv_at(const double* v, const double* w, const double* bias,
             int yy = y + dy - r, xx = x + dx - r;
             if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
             size_t tok = (size_t)yy * W + xx;
-            double val = v[(((size_t)b * heads + h) * ((size_t)H * W) + tok) * d + c];
+            double val = v[(((size_t)b * heads + h) * ((size_t)extra + (size_t)H * W) + extra + tok) * d + c];
             acc += w[(((size_t)h * d + c) * ks + dy) * ks + dx] * val;
         }
     return acc;
@@ -150,7 +155,7 @@ void oracle_dwconv(const double* v, const double* w, const double* bias,
                     for (int c = 0; c < d; ++c) {
                         size_t tok = (size_t)y * W + x;
                         out[(((size_t)b * heads + h) * ((size_t)H * W) + tok) * d + c] =
-                            dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, y, x, c);
+                            dwconv_at(v, w, bias, heads, H, W, d, ks, 0, b, h, y, x, c);
                     }
 }
 
@@ -179,9 +184,9 @@ static void explicit_row(const double* qrow, const double* kh, const double* vu,
 void oracle_forward_explicit(const double* q, const double* k, const double* v,
                              const double* w, const double* bias,
                              int B, int heads, int H, int W, int d, int ks,
-                             int norm_mode, unsigned branches, double eps, double* out)
+                             int norm_mode, unsigned branches, double eps, int extra, double* out)
 {
-    const int N = H * W;
+    const int N = extra + H * W;
     double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
     double* lin = (double*)malloc(sizeof(double) * d);
     for (int b = 0; b < B; ++b)
@@ -194,8 +199,9 @@ void oracle_forward_explicit(const double* q, const double* k, const double* v,
                     explicit_row(q + base + (size_t)t * d, kh, v + base, N, d, norm_mode, eps, lin);
                 for (int c = 0; c < d; ++c) {
                     double dw = 0.0;
-                    if (branches & ORACLE_BRANCH_DWCONV)
-                        dw = dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, t / W, t % W, c);
+                    if ((branches & ORACLE_BRANCH_DWCONV) && t >= extra)
+                        dw = dwconv_at(v, w, bias, heads, H, W, d, ks, extra, b, h, (t - extra) / W,
+                                       (t - extra) % W, c);
                     out[base + (size_t)t * d + c] = lin[c] + dw;
                 }
             }
@@ -209,11 +215,11 @@ void oracle_forward_explicit(const double* q, const double* k, const double* v,
 void oracle_forward_explicit_rows(const double* q, const double* k, const double* v,
                                   const double* w, const double* bias,
                                   int B, int heads, int H, int W, int d, int ks,
-                                  int norm_mode, unsigned branches, double eps,
+                                  int norm_mode, unsigned branches, double eps, int extra,
                                   const int64_t* units, const int64_t* tokens, int64_t nrows,
                                   double* out)
 {
-    const int N = H * W;
+    const int N = extra + H * W;
     (void)B;
     double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
     double* lin = (double*)malloc(sizeof(double) * d);
@@ -232,8 +238,9 @@ void oracle_forward_explicit_rows(const double* q, const double* k, const double
             explicit_row(q + base + (size_t)t * d, kh, v + base, N, d, norm_mode, eps, lin);
         for (int c = 0; c < d; ++c) {
             double dw = 0.0;
-            if (branches & ORACLE_BRANCH_DWCONV)
-                dw = dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, t / W, t % W, c);
+            if ((branches & ORACLE_BRANCH_DWCONV) && t >= extra)
+                dw = dwconv_at(v, w, bias, heads, H, W, d, ks, extra, b, h, (t - extra) / W,
+                               (t - extra) % W, c);
             out[(size_t)i * d + c] = lin[c] + dw;
         }
     }
@@ -276,9 +283,9 @@ void oracle_state(const double* k, const double* v, int B, int heads, int N, int
 void oracle_forward(const double* q, const double* k, const double* v,
                     const double* w, const double* bias,
                     int B, int heads, int H, int W, int d, int ks,
-                    int norm_mode, unsigned branches, double eps, double* out)
+                    int norm_mode, unsigned branches, double eps, int extra, double* out)
 {
-    const int N = H * W;
+    const int N = extra + H * W;
     const int d1 = d + 1;
     const int64_t units = (int64_t)B * heads;
     double* state = (double*)malloc(sizeof(double) * (size_t)units * d1 * d1);
@@ -304,9 +311,10 @@ void oracle_forward(const double* q, const double* k, const double* v,
                     o[j] = (norm_mode == 0) ? num / den : num;
                 }
             }
-            if (branches & ORACLE_BRANCH_DWCONV)
+            if ((branches & ORACLE_BRANCH_DWCONV) && t >= extra)
                 for (int c = 0; c < d; ++c)
-                    o[c] += dwconv_at(v, w, bias, heads, H, W, d, ks, b, h, t / W, t % W, c);
+                    o[c] += dwconv_at(v, w, bias, heads, H, W, d, ks, extra, b, h, (t - extra) / W,
+                                      (t - extra) % W, c);
         }
         free(qh);
     }

@@ -40,7 +40,7 @@ def lib():
         L.oracle_sim_series.argtypes = [C.c_double, C.c_int]
         L.oracle_sim_series.restype = C.c_double
         L.oracle_dwconv.argtypes = [_dp, _dp, _dp] + [C.c_int] * 6 + [_dp]
-        fwd = [_dp] * 5 + [C.c_int] * 6 + [C.c_int, C.c_uint, C.c_double]
+        fwd = [_dp] * 5 + [C.c_int] * 6 + [C.c_int, C.c_uint, C.c_double, C.c_int]
         L.oracle_forward_explicit.argtypes = fwd + [_dp]
         L.oracle_forward.argtypes = fwd + [_dp]
         L.oracle_forward_explicit_rows.argtypes = fwd + [_ip, _ip, C.c_int64, _dp]
@@ -115,40 +115,41 @@ def dwconv(v, w, bias, grid_h, grid_w):
     return out
 
 
-def _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps):
+def _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps, extra=0):
     q, k, v, w = _f64(q), _f64(k), _f64(v), _f64(w)
     bias = None if bias is None else _f64(bias)
     B, heads, N, d = q.shape
     assert k.shape == q.shape and v.shape == q.shape
-    assert N == grid_h * grid_w and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    assert N == extra + grid_h * grid_w and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
     keep = (q, k, v, w, bias)
     args = [_p(q), _p(k), _p(v), _p(w), _p(bias), B, heads, grid_h, grid_w, d, w.shape[2],
-            int(norm), int(branches), float(eps)]
+            int(norm), int(branches), float(eps), int(extra)]
     return keep, args, q.shape
 
 
 def forward_explicit(q, k, v, w, bias, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_ALL,
-                     eps=DEFAULT_EPS):
-    """The layer by its definition (explicit N x N similarity); small N only."""
-    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps)
+                     eps=DEFAULT_EPS, extra=0):
+    """The layer by its definition (explicit N x N similarity); small N only.  `extra` tokens in
+    front of each unit's grid tokens are not on the grid (class tokens)."""
+    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps, extra)
     out = np.empty(shape, dtype=np.float64)
     lib().oracle_forward_explicit(*args, _p(out))
     return out
 
 
 def forward(q, k, v, w, bias, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_ALL,
-            eps=DEFAULT_EPS):
+            eps=DEFAULT_EPS, extra=0):
     """The layer by the reassociated (K^T V state) form; any N."""
-    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps)
+    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps, extra)
     out = np.empty(shape, dtype=np.float64)
     lib().oracle_forward(*args, _p(out))
     return out
 
 
 def forward_explicit_rows(q, k, v, w, bias, grid_h, grid_w, units, tokens, norm=NORM_ROWSUM,
-                          branches=BRANCH_ALL, eps=DEFAULT_EPS):
+                          branches=BRANCH_ALL, eps=DEFAULT_EPS, extra=0):
     """Definition on selected rows (unit = b*heads + h, token); returns [nrows, d]."""
-    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps)
+    keep, args, shape = _fwd_args(q, k, v, w, bias, grid_h, grid_w, norm, branches, eps, extra)
     units = np.ascontiguousarray(units, dtype=np.int64)
     tokens = np.ascontiguousarray(tokens, dtype=np.int64)
     order = np.argsort(units, kind="stable")      # group rows of one unit together

@@ -152,3 +152,34 @@ def test_linear_terms_stay_within_the_truncation_gap(oracle):
     x = unit(q) @ unit(k).T
     assert np.abs(gap).max() <= 0.5 - 1 / np.pi + 1e-12
     assert (np.sign(gap[np.abs(x) > 1e-6]) == np.sign(x[np.abs(x) > 1e-6])).all()
+
+
+def test_class_tokens_join_the_sums_but_not_the_convolution(oracle):
+    """Tokens in front of the grid (class tokens): the linear branch treats all N = extra + H W
+    tokens alike (it has no notion of position), the DWConv term exists on the grid only."""
+    r = np.random.default_rng(11)
+    B, heads, H, W, d, ks, E = 1, 2, 5, 6, 4, 3, 2
+    N = E + H * W
+    q, k, v = (r.normal(size=(B, heads, N, d)) for _ in range(3))
+    w, bias = r.normal(size=(heads, d, ks, ks)), r.normal(size=(heads, d))
+    for norm in (oracle.NORM_ROWSUM, oracle.NORM_NONE):
+        full = oracle.forward_explicit(q, k, v, w, bias, H, W, norm=norm, extra=E)
+        fast = oracle.forward(q, k, v, w, bias, H, W, norm=norm, extra=E)
+        np.testing.assert_allclose(fast, full, rtol=1e-11, atol=1e-13)
+        lin = oracle.forward_explicit(q, k, v, w, bias, H, W, norm=norm, extra=E,
+                                      branches=oracle.BRANCH_LINEAR)
+        # the linear branch is blind to the grid: the same N tokens as a 1 x N grid give it too
+        flat = oracle.forward_explicit(q, k, v, np.zeros((heads, d, 1, 1)), None, 1, N, norm=norm,
+                                       branches=oracle.BRANCH_LINEAR)
+        np.testing.assert_allclose(lin, flat, rtol=1e-13, atol=1e-15)
+        # class tokens get the linear branch only; grid tokens add the convolution of the grid part
+        np.testing.assert_allclose(full[:, :, :E], lin[:, :, :E], rtol=1e-13)
+        dw = oracle.dwconv(np.ascontiguousarray(v[:, :, E:]), w, bias, H, W)
+        np.testing.assert_allclose(full[:, :, E:], lin[:, :, E:] + dw, rtol=1e-12, atol=1e-14)
+        rows = oracle.forward_explicit_rows(q, k, v, w, bias, H, W, [0, 1, 1, 0], [0, 1, 7, N - 1],
+                                            norm=norm, extra=E)
+        np.testing.assert_allclose(rows, full.reshape(heads, N, d)[[0, 1, 1, 0], [0, 1, 7, N - 1]],
+                                   rtol=1e-13)
+    # extra = 0 is the layer as before
+    np.testing.assert_array_equal(oracle.forward(q[:, :, E:], k[:, :, E:], v[:, :, E:], w, bias, H, W),
+                                  oracle.forward(q[:, :, E:], k[:, :, E:], v[:, :, E:], w, bias, H, W, extra=0))
