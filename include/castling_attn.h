@@ -16,8 +16,11 @@
  *
  * Conventions
  *   - All tensor pointers are DEVICE pointers unless a parameter says "host".
- *   - q, k, v, out: logical shape [B][heads][N][d], N = grid_h * grid_w, token
- *     n = y * grid_w + x (row-major grid, no class token).  The d axis is always
+ *   - q, k, v, out: logical shape [B][heads][N][d], N = extra_tokens + grid_h * grid_w;
+ *     the first extra_tokens tokens of a unit are not on the grid (class tokens), then
+ *     grid token (y, x) is token extra_tokens + y * grid_w + x (row-major grid).  Tokens
+ *     off the grid are keys and queries of the attention sums like any other; the DWConv
+ *     term, defined on the grid, is zero for them and does not read them.  The d axis is always
  *     contiguous.  By default the tensors are contiguous in that order; the stride
  *     fields of the descriptor place them elsewhere, e.g. q, k, v as the three
  *     slices of a fused projection output [B][N][3][heads][d] (Sec. 3.1: Q, K, V are
@@ -54,7 +57,7 @@ typedef struct castling_attn* castling_attn_t; /* opaque, owned by the library *
 
 typedef enum {
     CASTLING_OK = 0,
-    CASTLING_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, N != grid_h*grid_w, even ks, misalignment */
+    CASTLING_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, N != extra_tokens + grid_h*grid_w, even ks, misalignment */
     CASTLING_ERR_UNSUPPORTED = 2, /* d, ks or dtype outside what the kernels are built for */
     CASTLING_ERR_HIP = 3,         /* a HIP runtime call failed (allocation, launch) */
     CASTLING_ERR_ALIAS = 4        /* out overlaps an input */
@@ -76,7 +79,7 @@ enum { CASTLING_FLAG_KEEP_STATE = 1 };
 
 typedef struct {
     int32_t B, heads, N, d;   /* d in {16, 32, 64, 128} */
-    int32_t grid_h, grid_w;   /* N must equal grid_h * grid_w */
+    int32_t grid_h, grid_w;   /* N must equal extra_tokens + grid_h * grid_w */
     int32_t dw_kernel;        /* odd, 1..9 */
     int32_t io_dtype;         /* castling_dtype_t */
     int32_t norm;             /* castling_norm_t */
@@ -90,6 +93,7 @@ typedef struct {
     int64_t in_stride_b, in_stride_h, in_stride_n;
     int64_t out_stride_b, out_stride_h, out_stride_n;
     uint32_t flags;           /* bitmask of CASTLING_FLAG_* */
+    int32_t extra_tokens;     /* tokens in front of the grid (class tokens), 0..64 */
 } castling_attn_desc_t;
 
 /* Host-only check of a descriptor (no GPU needed).  Sec. 3.2.1 fixes the shapes:

@@ -38,7 +38,7 @@ class Desc(C.Structure):
                 ("eps", C.c_float),
                 ("in_stride_b", C.c_int64), ("in_stride_h", C.c_int64), ("in_stride_n", C.c_int64),
                 ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64),
-                ("out_stride_n", C.c_int64), ("flags", C.c_uint32)]
+                ("out_stride_n", C.c_int64), ("flags", C.c_uint32), ("extra_tokens", C.c_int32)]
 
 
 PAIR_SPARSE_SOFTMAX, PAIR_ANGULAR = 0, 1
@@ -111,7 +111,8 @@ def token_major_strides(heads, N, d):
 
 
 def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROWSUM,
-              branches=BRANCH_ALL, eps=0.0, in_strides=None, out_strides=None, flags=0) -> Desc:
+              branches=BRANCH_ALL, eps=0.0, in_strides=None, out_strides=None, flags=0,
+              extra_tokens=0) -> Desc:
     """in_strides / out_strides: (batch, head, token) element strides of q, k, v and of out;
     None = contiguous [B][heads][N][d]."""
     if isinstance(io_dtype, str):
@@ -119,7 +120,7 @@ def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROW
     ins = tuple(in_strides) if in_strides is not None else (0, 0, 0)
     outs = tuple(out_strides) if out_strides is not None else (0, 0, 0)
     return Desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm, branches, eps,
-                *ins, *outs, flags)
+                *ins, *outs, flags, extra_tokens)
 
 
 def validate(desc: Desc) -> int:
@@ -148,9 +149,10 @@ class CastlingAttn:
 
     @classmethod
     def for_workload(cls, wl, norm=NORM_ROWSUM, branches=BRANCH_ALL, eps=0.0, in_strides=None,
-                     out_strides=None, flags=0):
-        return cls(make_desc(wl.B, wl.heads, wl.N, wl.d, wl.grid_h, wl.grid_w, wl.dw_kernel,
-                             wl.dtype, norm, branches, eps, in_strides, out_strides, flags))
+                     out_strides=None, flags=0, extra_tokens=0):
+        return cls(make_desc(wl.B, wl.heads, wl.N + extra_tokens, wl.d, wl.grid_h, wl.grid_w,
+                             wl.dw_kernel, wl.dtype, norm, branches, eps, in_strides, out_strides,
+                             flags, extra_tokens))
 
     def forward(self, q, k, v, w, bias, out, stream=None):
         _check(lib().castling_attn_forward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(w),

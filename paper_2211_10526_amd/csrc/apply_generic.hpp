@@ -216,4 +216,18 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
     }
 }
 
+// grid = (ceil(rows * D / 8 / 256), units), block = 256: zero the first `rows` token rows of every
+// unit of out (16-byte pieces).  For tokens off the grid when only the DWConv branch is asked for.
+template <typename T>
+__global__ __launch_bounds__(256) void zero_rows_kernel(T* __restrict__ out, int rows, int d,
+                                                        int heads, TensorStrides st)
+{
+    constexpr int VEC = IO<T>::VEC;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int per_row = d / VEC;
+    if (i >= rows * per_row) return;
+    T* o = out + unit_offset(blockIdx.y, heads, st) + (i / per_row) * st.n + (i % per_row) * VEC;
+    *reinterpret_cast<uint4*>(o) = make_uint4(0u, 0u, 0u, 0u);
+}
+
 }  // namespace castling

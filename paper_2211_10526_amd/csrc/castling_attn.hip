@@ -61,8 +61,16 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
+// What one apply launch covers: the grid with the handle's branches and filter size, or the
+// tokens in front of the grid as a 1 x extra "grid" with the linear branch only.
+struct ApplyView {
+    int grid_h, grid_w, ks;
+    uint32_t branches;
+};
+
 struct castling_attn {
     castling_attn_desc_t desc;
+    ApplyView view;     // read by the apply launchers
     int device;
     int units;
     int n_split;
@@ -199,12 +207,12 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     const castling_attn_desc_t& d = h->desc;
     ApplyParams p;
     p.N = d.N;
-    p.grid_h = d.grid_h;
-    p.grid_w = d.grid_w;
-    p.tiles_x = (d.grid_w + kApplyTW - 1) / kApplyTW;
+    p.grid_h = h->view.grid_h;
+    p.grid_w = h->view.grid_w;
+    p.tiles_x = (p.grid_w + kApplyTW - 1) / kApplyTW;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
-    p.do_linear = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    p.do_dwconv = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    p.do_linear = (h->view.branches & CASTLING_BRANCH_LINEAR) != 0;
+    p.do_dwconv = (h->view.branches & CASTLING_BRANCH_DWCONV) != 0;
     p.eps = d.eps;
     p.in = h->in_st;
     p.out = h->out_st;
@@ -229,9 +237,9 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     const castling_attn_desc_t& d = h->desc;
     ApplyMfmaParams p;
     p.N = d.N;
-    p.grid_h = d.grid_h;
-    p.grid_w = d.grid_w;
-    p.strips = (d.grid_w + kStripW - 1) / kStripW;
+    p.grid_h = h->view.grid_h;
+    p.grid_w = h->view.grid_w;
+    p.strips = (p.grid_w + kStripW - 1) / kStripW;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
     p.do_linear = LIN;
     p.do_dwconv = DW;
@@ -246,7 +254,7 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
         if (e != hipSuccess) return e;
     }
     // one persistent block per compute unit; every block takes an equal share of the steps
-    const int total_steps = h->units * p.strips * ((d.grid_h + 3) / 4);
+    const int total_steps = h->units * p.strips * ((p.grid_h + 3) / 4);
     const int blocks = total_steps < h->num_cus ? total_steps : h->num_cus;
     hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW, X>), dim3(blocks), dim3(64 * kApplyWaves),
                        kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
@@ -260,8 +268,8 @@ template <int KS, typename X>
 hipError_t apply_mfma_fmt(castling_attn* h, bool launch, const void* q, const void* v,
                           const void* w, const void* bias, void* out, hipStream_t s)
 {
-    const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const bool dw = (h->desc.branches & CASTLING_BRANCH_DWCONV) != 0;
+    const bool lin = (h->view.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (h->view.branches & CASTLING_BRANCH_DWCONV) != 0;
     if (lin && dw) return apply_mfma_branches<KS, true, true, X>(h, launch, q, v, w, bias, out, s);
     if (lin) return apply_mfma_branches<KS, true, false, X>(h, launch, q, v, w, bias, out, s);
     return apply_mfma_branches<KS, false, true, X>(h, launch, q, v, w, bias, out, s);
@@ -279,7 +287,7 @@ template <typename T, int D>
 hipError_t apply_generic_ks(castling_attn* h, bool launch, const void* q, const void* v,
                             const void* w, const void* bias, void* out, hipStream_t s)
 {
-    switch (h->desc.dw_kernel) {
+    switch (h->view.ks) {
         case 1: return apply_generic<T, D, 1>(h, launch, q, v, w, bias, out, s);
         case 3: return apply_generic<T, D, 3>(h, launch, q, v, w, bias, out, s);
         case 5: return apply_generic<T, D, 5>(h, launch, q, v, w, bias, out, s);
@@ -288,11 +296,12 @@ hipError_t apply_generic_ks(castling_attn* h, bool launch, const void* q, const 
     }
 }
 
-hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
-                    const void* bias, void* out, hipStream_t s)
+// one launch for what h->view describes
+hipError_t do_apply_view(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
+                         const void* bias, void* out, hipStream_t s)
 {
     if (h->mfma_apply) {
-        switch (h->desc.dw_kernel) {
+        switch (h->view.ks) {
             case 1: return apply_mfma<1>(h, launch, q, v, w, bias, out, s);
             case 3: return apply_mfma<3>(h, launch, q, v, w, bias, out, s);
             case 5: return apply_mfma<5>(h, launch, q, v, w, bias, out, s);
@@ -303,6 +312,53 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
     return dispatch_type_width(h->desc.io_dtype, h->desc.d, [&](auto t, auto dc) {
         return apply_generic_ks<decltype(t), decltype(dc)::value>(h, launch, q, v, w, bias, out, s);
     });
+}
+
+// Pass 2 of a unit: the grid tokens with the handle's branches, then the tokens in front of the
+// grid (class tokens) with the linear branch alone -- as a 1 x extra grid through the same
+// kernels -- or zeros if the linear branch is off.
+hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
+                    const void* bias, void* out, hipStream_t s)
+{
+    const castling_attn_desc_t& d = h->desc;
+    const int extra = d.extra_tokens;
+    const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const ApplyView grid_view = {d.grid_h, d.grid_w, d.dw_kernel, d.branches};
+    const ApplyView extra_view = {1, extra, 1, CASTLING_BRANCH_LINEAR};
+    h->view = grid_view;
+    if (!launch) {
+        hipError_t e = do_apply_view(h, false, q, v, w, bias, out, s);
+        if (e == hipSuccess && extra > 0 && lin) {
+            const size_t lds = h->apply_lds;
+            h->view = extra_view;
+            e = do_apply_view(h, false, q, v, w, bias, out, s);
+            if (lds > h->apply_lds) h->apply_lds = lds;
+            h->view = grid_view;
+        }
+        return e;
+    }
+    const size_t es = dtype_size(d.io_dtype);
+    auto skip = [&](const void* p, long long tok_stride) -> const void* {
+        return p ? static_cast<const unsigned char*>(p) + static_cast<size_t>(extra) * tok_stride * es
+                 : nullptr;
+    };
+    hipError_t e = do_apply_view(h, true, skip(q, h->in_st.n), skip(v, h->in_st.n), w, bias,
+                                 const_cast<void*>(skip(out, h->out_st.n)), s);
+    if (e != hipSuccess || extra == 0) return e;
+    if (lin) {
+        h->view = extra_view;
+        e = do_apply_view(h, true, q, v, nullptr, nullptr, out, s);
+        h->view = grid_view;
+        return e;
+    }
+    dispatch_type_width(d.io_dtype, d.d, [&](auto t, auto) {
+        using T = decltype(t);
+        const int pieces = extra * d.d / IO<T>::VEC;
+        hipLaunchKernelGGL(zero_rows_kernel<T>, dim3((pieces + 255) / 256, h->units), dim3(256), 0, s,
+                           static_cast<T*>(out), extra, d.d, d.heads, h->out_st);
+        return 0;
+    });
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ one-kernel path
@@ -318,6 +374,7 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
     p.N = d.N;
     p.grid_h = d.grid_h;
     p.grid_w = d.grid_w;
+    p.extra = d.extra_tokens;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
     p.eps = d.eps;
     p.in = h->in_st;
@@ -406,7 +463,9 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     if (d->B <= 0 || d->heads <= 0 || d->N <= 0 || d->d <= 0 || d->grid_h <= 0 || d->grid_w <= 0 ||
         d->dw_kernel <= 0)
         return CASTLING_ERR_INVALID_ARG;
-    if (static_cast<int64_t>(d->grid_h) * d->grid_w != d->N) return CASTLING_ERR_INVALID_ARG;
+    if (d->extra_tokens < 0 || d->extra_tokens > 64) return CASTLING_ERR_INVALID_ARG;
+    if (static_cast<int64_t>(d->grid_h) * d->grid_w + d->extra_tokens != d->N)
+        return CASTLING_ERR_INVALID_ARG;
     if (d->dw_kernel % 2 == 0) return CASTLING_ERR_INVALID_ARG;
     if (d->norm != CASTLING_NORM_ROWSUM && d->norm != CASTLING_NORM_NONE)
         return CASTLING_ERR_INVALID_ARG;
@@ -563,8 +622,10 @@ int castling_attn_num_launches(castling_attn_t h)
 {
     if (!h) return 0;
     const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
-    if (h->fused || !lin) return 1;
-    return (h->mfma_apply && h->n_split == 1) ? 2 : 3;
+    const int extra = h->desc.extra_tokens > 0 ? 1 : 0;  // the tokens off the grid: one more launch
+    if (h->fused) return 1;
+    if (!lin) return 1 + extra;
+    return ((h->mfma_apply && h->n_split == 1) ? 2 : 3) + extra;
 }
 
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)

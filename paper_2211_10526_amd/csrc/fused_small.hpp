@@ -49,6 +49,7 @@ static_assert(2 * kFusedLdsBytes <= 160 * 1024, "two blocks per compute unit");
 
 struct FusedParams {
     int N, grid_h, grid_w;
+    int extra;  // tokens in front of the grid: no convolution term
     int norm_none;
     float eps;
     TensorStrides in, out;
@@ -417,10 +418,11 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
 #pragma unroll
                     for (int i = 0; i < 8; ++i) o[i] = 0.f;
                 }
-                if constexpr (DW) {
+                if (DW && t >= p.extra) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) o[i] += bl[8 * oct + i];
-                    const int y = t / W, x = t - y * W;
+                    const int tg = t - p.extra;  // position on the grid
+                    const int y = tg / W, x = tg - y * W;
 #pragma unroll
                     for (int dy = 0; dy < KS; ++dy) {
                         const int yy = y + dy - RAD;
@@ -428,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                         for (int dx = 0; dx < KS; ++dx) {
                             const int xx = x + dx - RAD;
                             const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
-                            const int tn = ok ? yy * W + xx : t;
+                            const int tn = ok ? p.extra + yy * W + xx : t;
                             u32x4_t vw = *reinterpret_cast<const u32x4_t*>(vtile + tn * PITCH + oct * 16);
                             const float* wt = wl + (dy * KS + dx) * D + 8 * oct;
                             const float4 w0 = *reinterpret_cast<const float4*>(wt);
