@@ -376,3 +376,45 @@ def test_argument_errors_on_device():
     torch.cuda.synchronize()
     attn.destroy()
     assert torch.isfinite(out).all()
+
+
+@pytest.mark.parametrize("wl", [SMALL[0], SMALL[15], SMALL[10]], ids=lambda w: w.name)
+def test_forward_in_a_captured_graph(oracle, wl):
+    """forward() only enqueues kernels (no allocation, no synchronisation, no memset), so it can
+    be captured in a HIP graph: three-launch fp32 path, one-kernel path, two-pass matrix-core
+    path.  Every replay, with eager work and synchronisations in between, must reproduce the
+    eager result bit for bit on new inputs written into the captured buffers."""
+    dev = torch.device("cuda:0")
+    xs = [inputs.make_inputs(wl, seed=60 + i, with_bias=True) for i in range(3)]
+    bufs = {n: torch.empty_like(xs[0][n], device=dev) for n in ("q", "k", "v", "w", "bias")}
+    out = torch.empty_like(bufs["q"])
+    eager_out = torch.empty_like(bufs["q"])
+    attn = b.CastlingAttn.for_workload(wl)
+    side = torch.cuda.Stream()
+    for n in bufs:
+        bufs[n].copy_(xs[0][n])
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        attn.forward(bufs["q"], bufs["k"], bufs["v"], bufs["w"], bufs["bias"], out, stream=side)  # warm-up
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            attn.forward(bufs["q"], bufs["k"], bufs["v"], bufs["w"], bufs["bias"], out,
+                         stream=torch.cuda.current_stream())
+    for i, x in enumerate(xs):
+        print(f"case graph replay {wl.name} #{i}", flush=True)
+        for n in bufs:
+            bufs[n].copy_(x[n])
+        torch.cuda.synchronize()
+        out.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        attn.forward(bufs["q"], bufs["k"], bufs["v"], bufs["w"], bufs["bias"], eager_out)
+        torch.cuda.synchronize()
+        view = torch.int32 if wl.dtype == "f32" else torch.int16
+        assert torch.equal(out.view(view), eager_out.view(view))
+        q, k, v, w, bias = oracle_inputs(x)
+        want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
+        assert rel_err(inputs.to_f64(out), want) <= TOL[wl.dtype]
+    del graph
+    attn.destroy()
