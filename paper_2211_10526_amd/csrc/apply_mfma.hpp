@@ -20,7 +20,9 @@
 //   waves 4..7   stagers: asynchronous V loads (several stages ahead), transposition of the V
 //                rows into the MFMA operand order (transposing LDS reads), and the coalesced
 //                stores of finished output tiles;
-//   waves 8..11  linear: asynchronous Q loads and the linear branch of row p of the stage.
+//   waves 8..11  linear: asynchronous Q loads and the linear branch of row p of the stage,
+//                software-pipelined over two stages (matrix products of the next stage are
+//                issued before the current one is finished).
 // Stagers and linear waves work one stage ahead of the consumers; all meet at one LDS-only
 // barrier per stage.
 #pragma once
@@ -216,6 +218,10 @@ __device__ __forceinline__ uint2 lds_read_tr8(const unsigned char* addr)
 #define CASTLING_APPLY_PREFETCH 2
 #endif
 constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
+#ifndef CASTLING_LINEAR_PREFETCH
+#define CASTLING_LINEAR_PREFETCH 4
+#endif
+constexpr int kLinearPrefetch = CASTLING_LINEAR_PREFETCH;  // the same for the linear waves' q
 
 // what a wave needs to know about a stage after its cursor has moved on
 struct StageSnap {
@@ -481,18 +487,28 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             });
     } else if (role == 2) {
         // ======================================================== linear waves
-        constexpr int YOUNGER = (PD - 1) * 2;
+        // Software pipeline over two stages: in the interval of stage s the wave first issues
+        // the matrix products of stage s + 1 (phase A: wait for its q, MFMAs into the other
+        // accumulator set) and then finishes stage s (phase B: norms, reciprocals, the linear
+        // tile) while those products run.  Its loads are LPD stages ahead.
+        constexpr int LPD = kLinearPrefetch;
+        static_assert(LPD % 2 == 0, "tile parity is taken from the slot index");
+        constexpr int YOUNGER = (LPD - 1) * 2;
         const int tl = lane & 15, g = lane >> 4;
         const float inv_eps = 1.0f / p.eps, half_n = 0.5f * static_cast<float>(p.N);
         u32x4_t sf[4][2], kf[2];
         const float unsc = X::table_unscale(p.N);
         float vh[4] = {0.f, 0.f, 0.f, 0.f};
         int lin_unit = -1;
-        u32x4_t qreg[PD][2];
-        bool qok[PD];
-        StageSnap snap[PD];
+        u32x4_t qreg[LPD][2];
+        bool qok[LPD];
+        StageSnap snap[LPD];
         int base_unit = -1;
         long long q_base = 0;
+        // products of two stages in flight: [parity]
+        f32x4_t gram[2], dk[2], acc[2][4];
+        float vhb[2][4];
+        bool busy[2] = {false, false};
 
         auto issue_loads = [&](auto slot_c, const StageCursor& cu) {
             constexpr int slot = decltype(slot_c)::value;
@@ -516,10 +532,14 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             snap[slot].computes = cu.computes(NCH);
         };
 
-        auto linear = [&](auto slot_c, float* lin) {
+        // phase A of the stage held in `slot`, into accumulator set PAR
+        auto products = [&](auto slot_c, auto par_c) {
             constexpr int slot = decltype(slot_c)::value;
+            constexpr int PAR = decltype(par_c)::value;
             if constexpr (LIN) {
                 wait_async_loads<YOUNGER>(qreg[slot][0], qreg[slot][1]);
+                TRACE_POINT(21);
+                busy[PAR] = snap[slot].computes;
                 if (!snap[slot].computes) return;
                 const int unit = snap[slot].unit;
                 if (unit != lin_unit) {  // uniform per block: operand tables of the new unit
@@ -539,35 +559,44 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     for (int ks = 0; ks < 2; ++ks)
                         kf[ks] = __builtin_bit_cast(u32x4_t, k4[ks * 64 + lane]);
                 }
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt) vhb[PAR][nt] = vh[nt];
                 const u32x4_t zero = {0u, 0u, 0u, 0u};
                 u32x4_t a[2];
                 a[0] = qok[slot] ? qreg[slot][0] : zero;
                 a[1] = qok[slot] ? qreg[slot][1] : zero;
-                // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers)
-                f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
+                // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers).
+                // Six independent accumulators, k-step outermost: no MFMA waits for the one
+                // issued just before it.
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    gram = X::mfma16(a[ks], a[ks], gram);
-                f32x4_t acc[4], dk;
+                for (int r = 0; r < 4; ++r) gram[PAR][r] = dk[PAR][r] = 0.f;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) dk[r] = 0.f;
+                for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    dk = X::mfma16(a[ks], kf[ks], dk);
+                    for (int r = 0; r < 4; ++r) acc[PAR][nt][r] = 0.f;
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
+                for (int ks = 0; ks < 2; ++ks) {
+                    gram[PAR] = X::mfma16(a[ks], a[ks], gram[PAR]);
+                    dk[PAR] = X::mfma16(a[ks], kf[ks], dk[PAR]);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[nt][r] = 0.f;
-#pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        acc[nt] = X::mfma16(a[ks], sf[nt][ks], acc[nt]);
+                    for (int nt = 0; nt < 4; ++nt)
+                        acc[PAR][nt] = X::mfma16(a[ks], sf[nt][ks], acc[PAR][nt]);
                 }
+                TRACE_POINT(22);
+            }
+        };
+
+        // phase B of the stage whose products sit in accumulator set PAR
+        auto finish = [&](auto par_c, float* lin) {
+            constexpr int PAR = decltype(par_c)::value;
+            if constexpr (LIN) {
+                if (!busy[PAR]) return;
                 float alpha[4], beta[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
                     const float ssr = __int_as_float(
-                        __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
+                        __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[PAR][r])));
                     // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
                     float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
                     if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
@@ -575,18 +604,19 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                         alpha[r] = inv;
                         beta[r] = 1.0f;
                     } else {
-                        const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
+                        const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[PAR][r]);
                         alpha[r] = inv * rden;
                         beta[r] = rden;
                     }
                 }
+                TRACE_POINT(23);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) {
                     float4 o;
-                    o.x = fmaf(alpha[0], acc[nt][0], beta[0] * vh[nt]);
-                    o.y = fmaf(alpha[1], acc[nt][1], beta[1] * vh[nt]);
-                    o.z = fmaf(alpha[2], acc[nt][2], beta[2] * vh[nt]);
-                    o.w = fmaf(alpha[3], acc[nt][3], beta[3] * vh[nt]);
+                    o.x = fmaf(alpha[0], acc[PAR][nt][0], beta[0] * vhb[PAR][nt]);
+                    o.y = fmaf(alpha[1], acc[PAR][nt][1], beta[1] * vhb[PAR][nt]);
+                    o.z = fmaf(alpha[2], acc[PAR][nt][2], beta[2] * vhb[PAR][nt]);
+                    o.w = fmaf(alpha[3], acc[PAR][nt][3], beta[3] * vhb[PAR][nt]);
                     *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
                 }
             }
@@ -594,19 +624,30 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
 
         StageCursor ld;
         ld.start(s_begin, s_end, spc, p.strips);
-        static_for<PD>([&](auto slot) {
+        static_for<LPD>([&](auto slot) {
             issue_loads(slot, ld);
             ld.advance(spc, p.strips, NCH);
         });
-        for (int s = 0; s < n_stages; s += PD) {
-            static_for<PD>([&](auto slot) {
-                if (s + decltype(slot)::value >= n_stages) return;
-                constexpr int b2 = decltype(slot)::value & 1;
+        // stage 0: its products, then the refill of its slot
+        products(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+        issue_loads(std::integral_constant<int, 0>{}, ld);
+        ld.advance(spc, p.strips, NCH);
+        for (int s = 0; s < n_stages; s += LPD) {
+            static_for<LPD>([&](auto i_c) {
+                constexpr int i = decltype(i_c)::value;          // stage s + i, slot i, parity i % 2
+                if (s + i >= n_stages) return;
+                constexpr int next = (i + 1) % LPD;
                 TRACE_POINT(2);
-                linear(slot, reinterpret_cast<float*>(lin_base + b2 * kLinBytes));
+                if (s + i + 1 < n_stages) {
+                    products(std::integral_constant<int, next>{}, std::integral_constant<int, next & 1>{});
+                    // refill the slot just read (past the end the cursor stands still and the
+                    // loads repeat the last stage's: the count of loads in flight stays fixed)
+                    issue_loads(std::integral_constant<int, next>{}, ld);
+                    ld.advance(spc, p.strips, NCH);
+                }
                 TRACE_POINT(4);
-                issue_loads(slot, ld);
-                ld.advance(spc, p.strips, NCH);
+                finish(std::integral_constant<int, i & 1>{},
+                       reinterpret_cast<float*>(lin_base + (i & 1) * kLinBytes));
                 TRACE_POINT(5);
                 lds_barrier();
                 TRACE_POINT(6);
@@ -614,7 +655,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         }
         lds_barrier();
         if constexpr (LIN)
-            static_for<PD>([&](auto slot) { wait_async_loads<0>(qreg[slot][0], qreg[slot][1]); });
+            static_for<LPD>([&](auto slot) { wait_async_loads<0>(qreg[slot][0], qreg[slot][1]); });
     } else {
         // ======================================================== consumer waves
         const int blk = lane >> 2, j = lane & 3;
