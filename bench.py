@@ -30,9 +30,9 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # WRITE_SIZE runs (scaled by a copy kernel of known size); see profiles/.
 # workload name -> bytes, filled in from the committed summaries.
 MEASURED_TRAFFIC_BYTES: dict[str, float] = {
-    # apply kernel: FETCH_SIZE 59600 KiB x 2.0 + WRITE_SIZE 49150 KiB x 1.0
+    # apply kernel: FETCH_SIZE 61360 KiB x 2.0 + WRITE_SIZE 49150 KiB x 1.0
     # (profiles/mfma_kernels_cfg5_pmc_traffic.md)
-    "cfg5_bf16_b2_h12_d64_n16384_k9": (59600 * 2.0 + 49150) * 1024.0,
+    "cfg5_bf16_b2_h12_d64_n16384_k9": (61360 * 2.0 + 49150) * 1024.0,
 }
 
 
