@@ -166,6 +166,9 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
     }
     HIP_TRY(hipGetLastError());
     if (direct) return CASTLING_OK;
+    // vector-ALU apply with one split per unit: the partial layout is the state layout and the
+    // handle points `partial` at `state`, so the reduce kernel's result is final as written
+    if (!h->mfma_apply && h->n_split == 1) return CASTLING_OK;
     if (h->mfma_apply) {
         const int gx = (kCombineFragThreads + 255) / 256;
         const int ks = h->desc.dw_kernel;
@@ -602,6 +605,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->vhalf = reinterpret_cast<float*>(p);
     p += vhalf_bytes;
     h->wfrag = reinterpret_cast<bf16_t*>(p);
+    if (!h->mfma_apply && h->n_split == 1) h->partial = h->state;  // see do_reduce
     *out_handle = h;
     return CASTLING_OK;
 }
@@ -625,7 +629,7 @@ int castling_attn_num_launches(castling_attn_t h)
     const int extra = h->desc.extra_tokens > 0 ? 1 : 0;  // the tokens off the grid: one more launch
     if (h->fused) return 1;
     if (!lin) return 1 + extra;
-    return ((h->mfma_apply && h->n_split == 1) ? 2 : 3) + extra;
+    return (h->n_split == 1 ? 2 : 3) + extra;
 }
 
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
