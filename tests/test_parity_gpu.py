@@ -418,3 +418,34 @@ def test_forward_in_a_captured_graph(oracle, wl):
         assert rel_err(inputs.to_f64(out), want) <= TOL[wl.dtype]
     del graph
     attn.destroy()
+
+
+def test_two_handles_on_two_streams(oracle):
+    """Handles are independent: forwards of two handles (different shapes and paths) enqueued
+    alternately on two streams give the same bits as each handle run alone."""
+    dev = torch.device("cuda:0")
+    wls = [SMALL[10], SMALL[15]]                      # two-pass matrix-core path, one-kernel path
+    xs = [inputs.make_inputs(wl, seed=70 + i, with_bias=True) for i, wl in enumerate(wls)]
+    ts = [{n: x[n].to(dev) for n in ("q", "k", "v", "w", "bias")} for x in xs]
+    handles = [b.CastlingAttn.for_workload(wl) for wl in wls]
+    alone = []
+    for h, t in zip(handles, ts):
+        o = torch.empty_like(t["q"])
+        h.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], o)
+        torch.cuda.synchronize()
+        alone.append(o)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.empty_like(t["q"]) for t in ts]
+    torch.cuda.synchronize()
+    for _ in range(20):
+        for h, t, o, s in zip(handles, ts, outs, streams):
+            h.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], o, stream=s)
+    for s in streams:
+        s.synchronize()
+    for h in handles:
+        h.destroy()
+    for o, a, wl, x in zip(outs, alone, wls, xs):
+        assert torch.equal(o.view(torch.int16), a.view(torch.int16))
+        q, k, v, w, bias = oracle_inputs(x)
+        want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
+        assert rel_err(inputs.to_f64(o), want) <= TOL[wl.dtype]
