@@ -139,7 +139,10 @@ int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void
  *       CASTLING_NORM_NONE the division is left out); scale, threshold, normalize are ignored.
  * kept: DEVICE pointer to B*heads counters, or NULL; SPARSE_SOFTMAX writes the number of entries
  * the mask keeps per unit (the quantity whose decay to zero lets the branch be dropped at
- * inference).  out must not overlap q, k or v. */
+ * inference).  out must not overlap q, k or v.
+ * accumulate = 1 adds the result to what out already holds: castling_attn_forward followed by
+ * SPARSE_SOFTMAX with accumulate = 1 on the same out gives the training-time attention with all
+ * four terms of Eq. 9 (linear-angular terms, DWConv, and the masked softmax branch). */
 typedef enum { CASTLING_PAIR_SPARSE_SOFTMAX = 0, CASTLING_PAIR_ANGULAR = 1 } castling_pair_mode_t;
 
 typedef struct {
@@ -147,6 +150,7 @@ typedef struct {
     int32_t normalize;  /* SPARSE_SOFTMAX: 1 = unit rows, 0 = raw rows */
     float scale;        /* SPARSE_SOFTMAX: logit scale */
     float threshold;    /* SPARSE_SOFTMAX: mask threshold, in [0, 1] */
+    int32_t accumulate; /* 0: out = result; 1: out += result (out is read, then rounded again) */
 } castling_pair_params_t;
 
 int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* params, const void* q,

@@ -46,7 +46,7 @@ PAIR_SPARSE_SOFTMAX, PAIR_ANGULAR = 0, 1
 
 class PairParams(C.Structure):
     _fields_ = [("mode", C.c_int32), ("normalize", C.c_int32), ("scale", C.c_float),
-                ("threshold", C.c_float)]
+                ("threshold", C.c_float), ("accumulate", C.c_int32)]
 
 
 class CastlingError(RuntimeError):
@@ -168,9 +168,9 @@ class CastlingAttn:
         return out
 
     def pairwise(self, mode, q, k, v, out, kept=None, normalize=True, scale=1.0, threshold=0.0,
-                 stream=None):
+                 accumulate=False, stream=None):
         """castling_attn_pairwise; kept: int64 / uint64 device tensor [B * heads] or None."""
-        params = PairParams(mode, int(bool(normalize)), scale, threshold)
+        params = PairParams(mode, int(bool(normalize)), scale, threshold, int(bool(accumulate)))
         _check(lib().castling_attn_pairwise(self._h, C.byref(params), _ptr(q), _ptr(k), _ptr(v),
                                             _ptr(out), _ptr(kept), _stream_ptr(stream)))
         return out

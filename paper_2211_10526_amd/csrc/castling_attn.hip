@@ -676,6 +676,7 @@ int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* para
         return CASTLING_ERR_INVALID_ARG;
     if (params->mode != CASTLING_PAIR_SPARSE_SOFTMAX && params->mode != CASTLING_PAIR_ANGULAR)
         return CASTLING_ERR_INVALID_ARG;
+    if (params->accumulate & ~1) return CASTLING_ERR_INVALID_ARG;
     const bool sparse = params->mode == CASTLING_PAIR_SPARSE_SOFTMAX;
     if (sparse && (!(params->threshold >= 0.0f) || !(params->threshold <= 1.0f) ||
                    !(params->scale == params->scale) || (params->normalize & ~1)))
@@ -691,6 +692,7 @@ int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* para
     PairParams p;
     p.N = d.N;
     p.normalize = params->normalize;
+    p.accumulate = params->accumulate;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
     p.scale = params->scale;
     p.threshold = params->threshold;

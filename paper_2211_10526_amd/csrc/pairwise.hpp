@@ -32,6 +32,7 @@ struct PairParams {
     int N;
     int normalize;    // SPARSE: unit rows of q and k
     int norm_none;    // ANGULAR: no division by the row sum
+    int accumulate;   // add the result to what `out` holds
     float scale, threshold, eps;
     TensorStrides in, out;
 };
@@ -256,10 +257,20 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
             for (int a = 0; a < 4; ++a) {
+                uint2* dst = reinterpret_cast<uint2*>(orow + (32 * mt + 8 * a + 4 * hsel) * 2);
+                float r0 = acc[mt][4 * a] * post, r1 = acc[mt][4 * a + 1] * post;
+                float r2 = acc[mt][4 * a + 2] * post, r3 = acc[mt][4 * a + 3] * post;
+                if (p.accumulate) {
+                    const uint2 old = *dst;
+                    r0 += X::lo(old.x);
+                    r1 += X::hi(old.x);
+                    r2 += X::lo(old.y);
+                    r3 += X::hi(old.y);
+                }
                 uint2 o;
-                o.x = X::pack(acc[mt][4 * a] * post, acc[mt][4 * a + 1] * post);
-                o.y = X::pack(acc[mt][4 * a + 2] * post, acc[mt][4 * a + 3] * post);
-                *reinterpret_cast<uint2*>(orow + (32 * mt + 8 * a + 4 * hsel) * 2) = o;
+                o.x = X::pack(r0, r1);
+                o.y = X::pack(r2, r3);
+                *dst = o;
             }
     }
     if constexpr (MODE == kPairSparse) {

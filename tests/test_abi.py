@@ -97,6 +97,7 @@ def test_validate_null_and_strerror():
     assert L.castling_attn_num_splits(None) == 0
     assert L.castling_attn_num_launches(None) == 0
     assert L.castling_attn_pairwise(None, None, None, None, None, None, None, None) == b.ERR_INVALID_ARG
+    assert C.sizeof(b.PairParams) == 20  # mode, normalize, scale, threshold, accumulate
     assert L.castling_attn_forward(None, None, None, None, None, None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_reduce(None, None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_apply(None, None, None, None, None, None, None) == b.ERR_INVALID_ARG

@@ -188,3 +188,40 @@ def test_pairwise_argument_errors():
             attn.pairwise(b.PAIR_ANGULAR, q, k, v, torch.empty_like(q))
         assert e.value.status == b.ERR_UNSUPPORTED
         attn.destroy()
+
+
+@pytest.mark.parametrize("wl", [SHAPES[0], SHAPES[2], SHAPES[3]], ids=lambda w: w.name)
+def test_training_time_attention_with_all_terms(oracle, wl):
+    """Eq. 9 with its four terms: forward() writes the linear-angular terms and the DWConv, the
+    masked softmax branch is added onto the same output with accumulate = 1.  The sum is rounded
+    to the I/O type twice (forward's result, then the total), hence twice the tolerance."""
+    x = inputs.make_inputs(wl, seed=47, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w", "bias")}
+    thr, scale, delta = 0.004, 8.0, 1e-4
+    attn = b.CastlingAttn.for_workload(wl)
+    out = torch.full_like(t["q"], float("nan"))
+    attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], out)
+    layer = out.clone()
+    attn.pairwise(b.PAIR_SPARSE_SOFTMAX, t["q"], t["k"], t["v"], out, scale=scale, threshold=thr,
+                  accumulate=True)
+    alone = torch.full_like(t["q"], float("nan"))
+    attn.pairwise(b.PAIR_SPARSE_SOFTMAX, t["q"], t["k"], t["v"], alone, scale=scale, threshold=thr)
+    torch.cuda.synchronize()
+    attn.destroy()
+    got = inputs.to_f64(out)
+    sparse, _ = oracle.sparse_attn(q, k, v, thr, normalize=True, scale=scale)
+    want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w) + sparse
+    tol = 2 * TOL[wl.dtype]
+    rms = float(np.sqrt(np.mean(want * want)))
+    for bi in range(wl.B):
+        for h in range(wl.heads):
+            P = oracle.softmax_probs(q[bi, h], k[bi, h], normalize=True, scale=scale)
+            border = np.abs(P - thr) <= delta * thr
+            slack = (np.where(border, P, 0.0) * (1.0 + delta)) @ np.abs(v[bi, h])
+            allowed = tol * np.maximum(np.abs(want[bi, h]), rms) + slack
+            assert (np.abs(got[bi, h] - want[bi, h]) <= allowed).all(), (wl.name, bi, h)
+    # the accumulated result is the rounded sum of the two results the kernels give alone
+    both = (layer.float() + alone.float()).to(out.dtype)
+    assert rel_err(got, inputs.to_f64(both)) <= 2.0 ** -7

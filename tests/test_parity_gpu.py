@@ -99,6 +99,28 @@ def test_small_against_definition(oracle, wl, norm):
 
 # projection-adjacent layouts: q, k, v as slices of a fused [B][N][3][heads][d] tensor, out
 # as [B][N][heads * d]; every kernel family (fp32 / bf16 vector-ALU, matrix-core) is covered
+# shapes in which the persistent blocks of pass 2 get uneven step ranges that start and end in
+# the middle of a strip column, with 3 and 5 strips per unit, and grids with more strips per
+# unit than the chip has compute units
+SCHEDULES = [
+    Workload("p_bf16_d64_40x36_k3_u9", "bf16", 3, 3, 64, 40, 36, 3),
+    Workload("p_f16_d64_29x72_k5_u8", "f16", 2, 4, 64, 29, 72, 5),
+    Workload("p_bf16_d64_1x4200_k3", "bf16", 1, 1, 64, 1, 4200, 3),
+    Workload("p_bf16_d64_2x4400_k9", "bf16", 1, 2, 64, 2, 4400, 9),
+]
+
+
+@pytest.mark.parametrize("wl", SCHEDULES, ids=lambda w: w.name)
+def test_block_schedules_of_pass_two(oracle, wl):
+    x = inputs.make_inputs(wl, seed=41, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    for branches in (b.BRANCH_ALL, b.BRANCH_DWCONV):
+        print(f"case {wl.name} branches={branches}", flush=True)
+        want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w, branches=branches)
+        got = gpu_forward(wl, x, branches=branches)
+        assert rel_err(got, want) <= TOL[wl.dtype], (wl.name, branches)
+
+
 STRIDED = [SMALL[0], SMALL[1], SMALL[3], SMALL[4], SMALL[9], SMALL[10], SMALL[11], SMALL[15],
            Workload("s_bf16_d64_40x40_k5_b3", "bf16", 3, 5, 64, 40, 40, 5)]
 
@@ -449,3 +471,26 @@ def test_two_handles_on_two_streams(oracle):
         q, k, v, w, bias = oracle_inputs(x)
         want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
         assert rel_err(inputs.to_f64(o), want) <= TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("dtype,C_,ks", [("bf16", 256, 3), ("f16", 384, 5), ("f32", 128, 3)])
+def test_dwconv_on_token_major_features(oracle, dtype, C_, ks):
+    """The DWConv branch alone on a token-major [B][N][C] tensor (the depthwise convolution the
+    paper also places between the two MLP layers, Sec. 4.3): C channels as C / 64 heads of 64,
+    input and output with (batch, head, token) strides (N C, 64, C)."""
+    B, H, W, d = 2, 12, 20, 64
+    heads, N = C_ // d, H * W
+    wl = Workload(f"mlp_{dtype}_c{C_}", dtype, B, heads, d, H, W, ks)
+    x = inputs.make_inputs(wl, seed=53, with_bias=True)
+    dev = torch.device("cuda:0")
+    feat = x["v"].to(dev).permute(0, 2, 1, 3).reshape(B, N, C_).contiguous()
+    out = torch.full_like(feat, float("nan"))
+    tm = b.token_major_strides(heads, N, d)
+    attn = b.CastlingAttn.for_workload(wl, branches=b.BRANCH_DWCONV, in_strides=tm, out_strides=tm)
+    attn.forward(feat, feat, feat, x["w"].to(dev), x["bias"].to(dev), out)
+    torch.cuda.synchronize()
+    attn.destroy()
+    q, k, v, w, bias = oracle_inputs(x)
+    want = oracle.forward(q, k, v, w, bias, H, W, branches=b.BRANCH_DWCONV)
+    got = inputs.to_f64(out.view(B, N, heads, d).permute(0, 2, 1, 3))
+    assert rel_err(got, want) <= TOL[dtype]
