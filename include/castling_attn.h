@@ -88,7 +88,8 @@ typedef struct {
     /* Element strides between consecutive batches, heads and tokens of q, k, v (one set for
      * all three) and of out.  All three of a set 0 = contiguous [B][heads][N][d], i.e.
      * {heads*N*d, N*d, d}.  Each must be a positive multiple of 16 bytes, the token stride at
-     * least d, and N * token stride must stay below 4 GiB in bytes.  The rows a set of strides
+     * least d.  N * token stride must stay below 4 GiB in bytes (with the default strides too: N * d
+     * elements of a unit), else CASTLING_ERR_UNSUPPORTED.  The rows a set of strides
      * addresses must not overlap each other. */
     int64_t in_stride_b, in_stride_h, in_stride_n;
     int64_t out_stride_b, out_stride_h, out_stride_n;
@@ -100,7 +101,10 @@ typedef struct {
  * per head Q, K, V in R^{N x d}, DWConv over the token grid. */
 int castling_attn_validate(const castling_attn_desc_t* desc);
 
-/* Validates desc, allocates the workspace on the current device, returns a handle. */
+/* Validates desc, allocates the workspace on the current device, returns a handle.  Every later
+ * call on the handle must be made with that device current and with pointers into its memory;
+ * calls on one handle must not overlap in time (its workspace holds the state between the two
+ * passes), calls on different handles may. */
 int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_handle);
 
 /* Whole layer (Eq. 9 with the readings above): reduce followed by apply.

@@ -7,8 +7,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <memory>
 #include <new>
-#include <vector>
 
 #include "apply_generic.hpp"
 #include "apply_mfma.hpp"
@@ -487,15 +487,23 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     const int64_t sets[2][3] = {{d->in_stride_b, d->in_stride_h, d->in_stride_n},
                                 {d->out_stride_b, d->out_stride_h, d->out_stride_n}};
     for (const auto& s : sets) {
-        if (s[0] == 0 && s[1] == 0 && s[2] == 0) continue;  // contiguous default
-        for (int i = 0; i < 3; ++i)
-            if (s[i] <= 0 || (s[i] * es) % 16 != 0) return CASTLING_ERR_INVALID_ARG;
-        if (s[2] < d->d) return CASTLING_ERR_INVALID_ARG;
+        const bool dense = s[0] == 0 && s[1] == 0 && s[2] == 0;  // contiguous default
+        if (!dense) {
+            for (int i = 0; i < 3; ++i)
+                if (s[i] <= 0 || (s[i] * es) % 16 != 0) return CASTLING_ERR_INVALID_ARG;
+            if (s[2] < d->d) return CASTLING_ERR_INVALID_ARG;
+            if (s[0] > (int64_t(1) << 40) || s[1] > (int64_t(1) << 40))
+                return CASTLING_ERR_UNSUPPORTED;
+        }
         // the kernels address tokens of one unit with 32-bit byte offsets
-        if (s[2] > (int64_t(1) << 32) || d->N * s[2] * es >= (int64_t(1) << 32))
+        const int64_t tok = dense ? d->d : s[2];
+        if (tok > (int64_t(1) << 32) || d->N * tok * es >= (int64_t(1) << 32))
             return CASTLING_ERR_UNSUPPORTED;
-        if (s[0] > (int64_t(1) << 40) || s[1] > (int64_t(1) << 40)) return CASTLING_ERR_UNSUPPORTED;
     }
+    // pass 2 counts its work items (4 rows x 16 columns of one unit) in 32 bits
+    const int64_t steps = static_cast<int64_t>(d->B) * d->heads * ((d->grid_w + 15) / 16) *
+                          ((d->grid_h + 3) / 4);
+    if (steps > (int64_t(1) << 30)) return CASTLING_ERR_UNSUPPORTED;
     return CASTLING_OK;
 }
 
@@ -507,7 +515,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     if (st != CASTLING_OK) return st;
 
     castling_attn* h = new (std::nothrow) castling_attn();
-    if (!h) return CASTLING_ERR_INVALID_ARG;
+    if (!h) return hip_fail(hipErrorOutOfMemory);
     h->desc = *desc;
     if (h->desc.branches == 0) h->desc.branches = CASTLING_BRANCH_ALL;
     if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
@@ -768,12 +776,15 @@ int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, voi
     if (bytes != sizeof(float) * static_cast<size_t>(h->units) * D1 * D1)
         return CASTLING_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    std::vector<float> raw(static_cast<size_t>(h->units) * h->state_size);
+    // no exception may leave through the C boundary: plain allocation, checked
+    const size_t raw_n = static_cast<size_t>(h->units) * h->state_size;
+    std::unique_ptr<float[]> raw(new (std::nothrow) float[raw_n]);
+    if (!raw) return hip_fail(hipErrorOutOfMemory);
     HIP_TRY(hipStreamSynchronize(s));
-    HIP_TRY(hipMemcpy(raw.data(), h->state, raw.size() * sizeof(float), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(raw.get(), h->state, raw_n * sizeof(float), hipMemcpyDeviceToHost));
     float* dst = static_cast<float*>(host_f32);
     for (int u = 0; u < h->units; ++u) {
-        const float* r = raw.data() + static_cast<size_t>(u) * h->state_size;
+        const float* r = raw.get() + static_cast<size_t>(u) * h->state_size;
         float* m = dst + static_cast<size_t>(u) * D1 * D1;
         for (int i = 0; i < D; ++i) {
             for (int j = 0; j < D; ++j) m[i * D1 + j] = r[i * D + j];

@@ -77,6 +77,11 @@ def test_validate_strides():
     # one unit's tokens must stay inside 32-bit byte offsets
     big = b.make_desc(1, 1, 16384, 64, 128, 128, 3, "bf16", in_strides=(1 << 34, 64, 1 << 18))
     assert b.validate(big) == b.ERR_UNSUPPORTED
+    # ... with the contiguous default strides as well: 2^25 tokens of 64 bf16 = 4 GiB per unit
+    assert b.validate(b.make_desc(1, 1, 1 << 25, 64, 4096, 8192, 3, "bf16")) == b.ERR_UNSUPPORTED
+    assert b.validate(b.make_desc(1, 1, 1 << 24, 64, 4096, 4096, 3, "bf16")) == b.OK
+    # pass 2 counts 4 x 16 pieces of the grid in 32 bits: 65535 units of a 262144 x 1 grid
+    assert b.validate(b.make_desc(255, 257, 1 << 18, 16, 1 << 18, 1, 3, "bf16")) == b.ERR_UNSUPPORTED
 
 
 def test_validate_null_and_strerror():
