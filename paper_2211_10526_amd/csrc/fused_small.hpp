@@ -29,7 +29,7 @@ namespace castling {
 constexpr int kFusedMaxTokens = 256;
 constexpr int kFusedMaxKs = 5;
 constexpr int kFusedPitch = 160;  // bytes per token row of the V and k_hat tiles (bank spread)
-constexpr int kFusedVBytes = kFusedMaxTokens * kFusedPitch;
+constexpr int kFusedVBytes = (kFusedMaxTokens + 1) * kFusedPitch;  // + one row of zeros
 constexpr int kFusedKtileBytes = 32 * kFusedPitch;  // per wave
 constexpr int kFusedLinPitch = 68;                  // floats per token row of the linear tile
 // k_hat staging, then column-sum scratch, then the linear tile share one region
@@ -73,9 +73,11 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     unsigned char* const vtile = lds;
     unsigned char* const un = lds + kFusedVBytes;
-    float* const wl = reinterpret_cast<float*>(lds + kFusedWOff);
+    uint32_t* const wl = reinterpret_cast<uint32_t*>(lds + kFusedWOff);
     float* const bl = reinterpret_cast<float*>(lds + kFusedBiasOff);
     float* const vhalf = reinterpret_cast<float*>(lds + kFusedVhalfOff);
+    TRACE_DECL
+    TRACE_POINT(1);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -124,17 +126,27 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         const bf16_t* bh = bias ? bias + head * D : wh;
         async_load16(braw, bh, static_cast<uint32_t>(tid & 7) * 16);
     }
-    if constexpr (LIN) {
+    // q is not needed before phase 3: its loads go out between the two iterations of phase 1,
+    // where their issue overlaps the arithmetic of the other waves
+    auto issue_q_loads = [&]() {
+        if constexpr (LIN) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int tok = min(64 * c + 16 * wave + tl, N - 1);
-            const uint32_t off = static_cast<uint32_t>(tok) * in_tok + g * 16;
-            async_load16_stream(qraw[c][0], qb, off);
-            async_load16_stream(qraw[c][1], qb, off + 64);
+            for (int c = 0; c < 4; ++c) {
+                const int tok = min(64 * c + 16 * wave + tl, N - 1);
+                const uint32_t off = static_cast<uint32_t>(tok) * in_tok + g * 16;
+                async_load16_stream(qraw[c][0], qb, off);
+                async_load16_stream(qraw[c][1], qb, off + 64);
+            }
         }
-    }
+    };
 
+    // the row of zeros behind the V tile: what a filter tap outside the grid reads
+    if (tid < 8) {
+        const u32x4_t zero = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4_t*>(vtile + kFusedMaxTokens * PITCH + tid * 16) = zero;
+    }
     // ---- phase 1: normalise K, stage k_hat and V, accumulate K_hat^T V
+    TRACE_POINT(2);
     f32x16_t acc[2][2];
     float ksum[8], vsum[8];
     if constexpr (LIN) {
@@ -153,12 +165,17 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
 
     static_for<2>([&](auto it_c) {
         constexpr int it = decltype(it_c)::value;
-        constexpr int YOUNGER = (1 - it) * PER_IT + NWB + NQ;  // loads issued after this iteration's
+        // loads issued after this iteration's: the q loads go out after iteration 0
+        constexpr int YOUNGER = it == 0 ? PER_IT + NWB : NWB + NQ;
         const int n0 = 64 * wave + 32 * it;
         if constexpr (LIN)
             wait_async_loads<YOUNGER + 4>(kraw[it][0], kraw[it][1], kraw[it][2], kraw[it][3]);
         wait_async_loads<YOUNGER>(vraw[it][0], vraw[it][1], vraw[it][2], vraw[it][3]);
-        if (n0 >= N) return;  // uniform per wave
+        TRACE_POINT(3);
+        if (n0 >= N) {  // uniform per wave
+            if constexpr (it == 0) issue_q_loads();
+            return;
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int row = 8 * j + lrow;
@@ -213,8 +230,10 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             }
             __builtin_amdgcn_wave_barrier();
         }
+        if constexpr (it == 0) issue_q_loads();
     });
     __syncthreads();  // V is staged; the k_hat tiles are dead
+    TRACE_POINT(4);
 
     if constexpr (LIN) {
         // ---- column sums: every lane's 16 partial sums go through LDS, summed in lane order
@@ -274,6 +293,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         }
 
         // ---- phase 2: operand tables of the linear branch (same layouts as sfrag / kfrag)
+        TRACE_POINT(5);
         float* ksumf = reinterpret_cast<float*>(un);
         if (tid < D) ksumf[tid] = colsum;
         else if (tid < 2 * D) vhalf[tid - D] = 0.5f * colsum;
@@ -298,15 +318,18 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         }
     }
     if constexpr (DW) {
-        // filters [channel][tap] bf16 -> LDS [tap][channel] fp32; bias -> fp32
+        // filters [channel][tap] -> LDS [tap][channel], one 32-bit word each: the 16-bit weight in
+        // the half its channel has inside a pair of channels, zero in the other half (the
+        // operand of the two-element dot product below); bias -> fp32
         wait_async_loads<NQ + 1>(wraw);
         if (tid < W_CHUNKS) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int e = 8 * tid + i;
                 const uint32_t word = wraw[i >> 1];
-                const float val = (i & 1) ? X::hi(word) : X::lo(word);
-                wl[(e % (KS * KS)) * D + e / (KS * KS)] = val;
+                const uint32_t raw = (i & 1) ? (word >> 16) : (word & 0xffffu);
+                const int ch = e / (KS * KS);
+                wl[(e % (KS * KS)) * D + ch] = (ch & 1) ? (raw << 16) : raw;
             }
         }
         wait_async_loads<NQ>(braw);
@@ -332,6 +355,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     }
 
     // ---- phase 3
+    TRACE_POINT(6);
     u32x4_t sf[4][2], kf[2];
     float vh[4] = {0.f, 0.f, 0.f, 0.f};
     if constexpr (LIN) {
@@ -351,12 +375,36 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     float* const lin = reinterpret_cast<float*>(un);
     unsigned char* const ob = reinterpret_cast<unsigned char*>(out + unit_offset(unit, heads, p.out));
     const int oct = tid & 7;
+    // this thread's 8 channels: bias, and for the small filters every tap, held in registers
+    // (the LDS reads of the filters were two thirds of the convolution's LDS traffic)
+    constexpr bool kRegW = DW && KS <= 3;
+    float breg[8];
+    uint32_t wreg[kRegW ? KS * KS * 8 : 1];
+    if constexpr (DW) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) breg[i] = bl[8 * oct + i];
+        if constexpr (kRegW) {
+#pragma unroll
+            for (int tap = 0; tap < KS * KS; ++tap) {
+                const uint4 w0 = *reinterpret_cast<const uint4*>(wl + tap * D + 8 * oct);
+                const uint4 w1 = *reinterpret_cast<const uint4*>(wl + tap * D + 8 * oct + 4);
+                wreg[tap * 8 + 0] = w0.x; wreg[tap * 8 + 1] = w0.y;
+                wreg[tap * 8 + 2] = w0.z; wreg[tap * 8 + 3] = w0.w;
+                wreg[tap * 8 + 4] = w1.x; wreg[tap * 8 + 5] = w1.y;
+                wreg[tap * 8 + 6] = w1.z; wreg[tap * 8 + 7] = w1.w;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) breg[i] = 0.f;
+    }
 
     static_for<4>([&](auto c_c) {
         constexpr int c = decltype(c_c)::value;
         if (64 * c >= N) return;  // uniform per block
         if constexpr (LIN) {
             wait_async_loads<2 * (3 - c)>(qraw[c][0], qraw[c][1]);
+            TRACE_POINT(7);
             if (64 * c + 16 * wave < N) {  // uniform per wave
                 const bool qok = 64 * c + 16 * wave + tl < N;
                 const u32x4_t zero = {0u, 0u, 0u, 0u};
@@ -402,60 +450,100 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             }
             __syncthreads();
         }
-        // convolution, sum of Eq. 9 and store: item = (token, 8 channels)
+        // convolution, sum of Eq. 9 and store: item = (token, 8 channels); a thread has the two
+        // tokens tid / 8 and tid / 8 + 32 of the chunk, and every filter tap serves both
+        {
+            const int tloc0 = tid >> 3;
+            float o[2][8];
+            int ty[2], tx[2];
+            bool live[2], conv[2];
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-            const int tloc = (tid >> 3) + 32 * h2;
-            const int t = 64 * c + tloc;
-            if (t < N) {
-                float o[8];
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int tloc = tloc0 + 32 * h2;
+                const int t = 64 * c + tloc;
+                live[h2] = t < N;
+                conv[h2] = DW && live[h2] && t >= p.extra;
+                const int tg = max(t - p.extra, 0);  // position on the grid
+                ty[h2] = tg / W;
+                tx[h2] = tg - ty[h2] * W;
                 if constexpr (LIN) {
                     const float4 l0 = *reinterpret_cast<const float4*>(lin + tloc * LP + 8 * oct);
                     const float4 l1 = *reinterpret_cast<const float4*>(lin + tloc * LP + 8 * oct + 4);
-                    o[0] = l0.x; o[1] = l0.y; o[2] = l0.z; o[3] = l0.w;
-                    o[4] = l1.x; o[5] = l1.y; o[6] = l1.z; o[7] = l1.w;
+                    o[h2][0] = l0.x; o[h2][1] = l0.y; o[h2][2] = l0.z; o[h2][3] = l0.w;
+                    o[h2][4] = l1.x; o[h2][5] = l1.y; o[h2][6] = l1.z; o[h2][7] = l1.w;
                 } else {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) o[i] = 0.f;
+                    for (int i = 0; i < 8; ++i) o[h2][i] = 0.f;
                 }
-                if (DW && t >= p.extra) {
+                if (conv[h2]) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) o[i] += bl[8 * oct + i];
-                    const int tg = t - p.extra;  // position on the grid
-                    const int y = tg / W, x = tg - y * W;
+                    for (int i = 0; i < 8; ++i) o[h2][i] += breg[i];
+                }
+            }
+            if constexpr (DW) {
+                // per token: which filter rows and columns fall on the grid, and the LDS address of
+                // the token's column in each of those rows; a tap off the grid reads the zero row
+                bool rok[2][KS], cok[2][KS];
+                int rbase[2][KS];
+                const int zero_addr = kFusedMaxTokens * PITCH + oct * 16;
 #pragma unroll
-                    for (int dy = 0; dy < KS; ++dy) {
-                        const int yy = y + dy - RAD;
+                for (int h2 = 0; h2 < 2; ++h2)
 #pragma unroll
-                        for (int dx = 0; dx < KS; ++dx) {
-                            const int xx = x + dx - RAD;
-                            const bool ok = yy >= 0 && yy < H && xx >= 0 && xx < W;
-                            const int tn = ok ? p.extra + yy * W + xx : t;
-                            u32x4_t vw = *reinterpret_cast<const u32x4_t*>(vtile + tn * PITCH + oct * 16);
-                            const float* wt = wl + (dy * KS + dx) * D + 8 * oct;
-                            const float4 w0 = *reinterpret_cast<const float4*>(wt);
-                            const float4 w1 = *reinterpret_cast<const float4*>(wt + 4);
-                            const float wv[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
-                            if (!ok) vw = u32x4_t{0u, 0u, 0u, 0u};
+                    for (int dd = 0; dd < KS; ++dd) {
+                        const int yy = ty[h2] + dd - RAD;
+                        rok[h2][dd] = conv[h2] && static_cast<unsigned>(yy) < static_cast<unsigned>(H);
+                        cok[h2][dd] = static_cast<unsigned>(tx[h2] + dd - RAD) < static_cast<unsigned>(W);
+                        rbase[h2][dd] = (p.extra + yy * W + tx[h2]) * PITCH + oct * 16;
+                    }
+#pragma unroll kRegW ? KS : 1
+                for (int dy = 0; dy < KS; ++dy) {
+#pragma unroll
+                    for (int dx = 0; dx < KS; ++dx) {
+                        uint32_t wv[8];
+                        if constexpr (kRegW) {
+#pragma unroll
+                            for (int i = 0; i < 8; ++i) wv[i] = wreg[(dy * KS + dx) * 8 + i];
+                        } else {
+                            const uint32_t* wt = wl + (dy * KS + dx) * D + 8 * oct;
+                            const uint4 w0 = *reinterpret_cast<const uint4*>(wt);
+                            const uint4 w1 = *reinterpret_cast<const uint4*>(wt + 4);
+                            wv[0] = w0.x; wv[1] = w0.y; wv[2] = w0.z; wv[3] = w0.w;
+                            wv[4] = w1.x; wv[5] = w1.y; wv[6] = w1.z; wv[7] = w1.w;
+                        }
+#pragma unroll
+                        for (int h2 = 0; h2 < 2; ++h2) {
+                            const bool ok = rok[h2][dy] && cok[h2][dx];
+                            const int addr = ok ? rbase[h2][dy] + (dx - RAD) * PITCH : zero_addr;
+                            const u32x4_t vw = *reinterpret_cast<const u32x4_t*>(vtile + addr);
 #pragma unroll
                             for (int i = 0; i < 4; ++i) {
-                                o[2 * i] = fmaf(wv[2 * i], X::lo(vw[i]), o[2 * i]);
-                                o[2 * i + 1] =
-                                    fmaf(wv[2 * i + 1], X::hi(vw[i]), o[2 * i + 1]);
+                                // one instruction per channel, no conversion: the zero half of
+                                // the weight word removes the pair's other channel
+                                o[h2][2 * i] = X::dot2(vw[i], wv[2 * i], o[h2][2 * i]);
+                                o[h2][2 * i + 1] = X::dot2(vw[i], wv[2 * i + 1], o[h2][2 * i + 1]);
                             }
                         }
                     }
                 }
-                store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16), X::pack(o[0], o[1]),
-                               X::pack(o[2], o[3]), X::pack(o[4], o[5]), X::pack(o[6], o[7]));
+            }
+#pragma unroll
+            for (int h2 = 0; h2 < 2; ++h2) {
+                const int t = 64 * c + tloc0 + 32 * h2;
+                if (live[h2])
+                    store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16),
+                                   X::pack(o[h2][0], o[h2][1]), X::pack(o[h2][2], o[h2][3]),
+                                   X::pack(o[h2][4], o[h2][5]), X::pack(o[h2][6], o[h2][7]));
             }
         }
         if constexpr (LIN) {
             if (64 * (c + 1) < N) __syncthreads();  // the next chunk overwrites the linear tile
         }
+        TRACE_POINT(9);
     });
     // loads that were never waited for (chunks past N) must land before the registers die
     if constexpr (LIN) wait_async_loads<0>(qraw[3][0], qraw[3][1]);
+    TRACE_POINT(10);
+    TRACE_DUMP
 }
 
 }  // namespace castling

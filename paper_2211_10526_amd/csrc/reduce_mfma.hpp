@@ -98,6 +98,13 @@ struct Bf16Fmt {
     {
         return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
     }
+    // a.lo * b.lo + a.hi * b.hi + c in fp32 (v_dot2c_f32_bf16)
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+    {
+        typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+        return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a),
+                                               __builtin_bit_cast(bf16x2_t, b), c, false);
+    }
 };
 
 struct F16Fmt {
@@ -129,6 +136,12 @@ struct F16Fmt {
     {
         return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a),
                                                   __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
+    }
+    // a.lo * b.lo + a.hi * b.hi + c in fp32 (v_dot2c_f32_f16)
+    static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
+    {
+        return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, a), __builtin_bit_cast(f16x2_t, b),
+                                      c, false);
     }
 };
 
