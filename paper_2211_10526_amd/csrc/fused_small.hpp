@@ -55,6 +55,30 @@ struct FusedParams {
     TensorStrides in, out;
 };
 
+// One 32 x 32 quadrant of a wave's accumulators to / from an exchange slot in LDS
+// ([register quad][lane] float4: 16-byte accesses, lanes contiguous).  By value: the accumulators
+// must stay in registers.
+__device__ __forceinline__ void put_quadrant(f32x4_t* dst, f32x16_t t)
+{
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4_t q4;
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) q4[e4] = t[4 * r4 + e4];
+        dst[r4 * 64] = q4;
+    }
+}
+__device__ __forceinline__ f32x16_t add_quadrant(const f32x4_t* src, f32x16_t t)
+{
+#pragma unroll
+    for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4_t q4 = src[r4 * 64];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) t[4 * r4 + e4] += q4[e4];
+    }
+    return t;
+}
+
 // grid = (units), block = 256, dynamic LDS = kFusedLdsBytes.
 // state: [units][StateLayout<64>::SIZE] fp32 copy of the state (nullptr = not wanted).
 template <int KS, bool LIN, bool DW, typename X>
@@ -235,86 +259,110 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     __syncthreads();  // V is staged; the k_hat tiles are dead
     TRACE_POINT(4);
 
+    // ---- between the passes: four block barriers.  Scratch, as byte offsets from `un`:
+    //   [0, 32 KB)   exchange slots of the tree (round 1: 8 KB per wave, round 2: 4 KB per wave)
+    //   [32 KB, +2K) per-wave column sums (inside the filter table, which is written last)
+    //   [16 KB, +256) ksum in fp32, for the ksum operand table
+    // The operand tables, vsum / 2, bias and filters lie inside the first 32 KB and behind it;
+    // each is written only after the last read of the scratch it overlays.
+    float colsum = 0.f;  // tid < 64: ksum[tid]; tid < 128: vsum[tid - 64]
+    f32x4_t* const xch = reinterpret_cast<f32x4_t*>(un);
+    float* const wsums = reinterpret_cast<float*>(un + 32768);
+    float* const ksumf = reinterpret_cast<float*>(un + 16384);
+    static_assert(kFusedVBytes + 32768 + 2048 <= kFusedLdsBytes, "per-wave column sums");
+    static_assert(kFusedWOff - kFusedVBytes <= 32768, "column sums overlay the filter table only");
+    // f(mt, nt) with the quadrant of S this wave ends up owning: wave = 2 mt + nt
+    auto own_quadrant = [&](auto&& f) {
+        static_for<4>([&](auto w_c) {
+            constexpr int WV = decltype(w_c)::value;
+            if (wave == WV)
+                f(std::integral_constant<int, (WV >> 1)>{}, std::integral_constant<int, (WV & 1)>{});
+        });
+    };
+    constexpr int QUAD = 4 * 64;  // float4 per quadrant of one wave
+
     if constexpr (LIN) {
-        // ---- column sums: every lane's 16 partial sums go through LDS, summed in lane order
-        float* sums = reinterpret_cast<float*>(un);  // [wave][lane][16]
+        // column sums of the wave: lanes with equal lane % 8 hold the same features
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            sums[(wave * 64 + lane) * 16 + e] = ksum[e];
-            sums[(wave * 64 + lane) * 16 + 8 + e] = vsum[e];
+        for (int e8 = 0; e8 < 8; ++e8) {
+            float a = dpp_add<kDppRowRor8>(ksum[e8]), b = dpp_add<kDppRowRor8>(vsum[e8]);
+            a += __shfl_xor(a, 16, 64);
+            b += __shfl_xor(b, 16, 64);
+            a += __shfl_xor(a, 32, 64);
+            b += __shfl_xor(b, 32, 64);
+            ksum[e8] = a;
+            vsum[e8] = b;
         }
-        __syncthreads();
-        float colsum = 0.f;  // tid < 64: ksum[tid]; tid < 128: vsum[tid - 64]
+        if (lane < 8) {
+#pragma unroll
+            for (int e8 = 0; e8 < 8; ++e8) {
+                wsums[(wave * 8 + lane) * 16 + e8] = ksum[e8];
+                wsums[(wave * 8 + lane) * 16 + 8 + e8] = vsum[e8];
+            }
+        }
+        // K_hat^T V: the four waves' 64 x 64 partial sums by recursive halving.  Round 1 pairs
+        // wave w with w ^ 2: each sends the two quadrants of the other's half of the rows.
+        own_quadrant([&](auto mt_c, auto) {
+            constexpr int MT = decltype(mt_c)::value;
+            f32x4_t* dst = xch + wave * 2 * QUAD + lane;
+            put_quadrant(dst, acc[1 - MT][0]);
+            put_quadrant(dst + QUAD, acc[1 - MT][1]);
+        });
+    }
+    __syncthreads();
+    if constexpr (LIN) {
         if (tid < 2 * D) {
             const int which = tid / D, f = tid % D;
-            const int lc = f / 8, e = f % 8;
-            for (int wv = 0; wv < 4; ++wv)
-                for (int r = 0; r < 8; ++r)
-                    colsum += sums[(wv * 64 + r * 8 + lc) * 16 + which * 8 + e];
+            const int lc = f / 8, e8 = f % 8;
+#pragma unroll
+            for (int wv = 0; wv < 4; ++wv) colsum += wsums[(wv * 8 + lc) * 16 + which * 8 + e8];
             if (state)
                 state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f] = colsum;
         }
-        __syncthreads();
-
-        // ---- K_hat^T V: fixed tree over the waves, (w0 + w2) + (w1 + w3)
-        f32x4_t* tree = reinterpret_cast<f32x4_t*>(un);
-        constexpr int SLOT = 2 * 2 * 4 * 64;  // float4 per slot
-#pragma unroll
-        for (int half = 2; half >= 1; half >>= 1) {
-            if (wave >= half && wave < 2 * half) {
-                f32x4_t* dst = tree + (wave - half) * SLOT + lane;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            f32x4_t q4;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) q4[e] = acc[mt][nt][4 * r4 + e];
-                            dst[((mt * 2 + nt) * 4 + r4) * 64] = q4;
-                        }
-            }
-            __syncthreads();
-            if (wave < half) {
-                const f32x4_t* src = tree + wave * SLOT + lane;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            const f32x4_t q4 = src[((mt * 2 + nt) * 4 + r4) * 64];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[mt][nt][4 * r4 + e] += q4[e];
-                        }
-            }
-            __syncthreads();
-        }
-
-        // ---- phase 2: operand tables of the linear branch (same layouts as sfrag / kfrag)
-        TRACE_POINT(5);
-        float* ksumf = reinterpret_cast<float*>(un);
+        own_quadrant([&](auto mt_c, auto) {
+            constexpr int MT = decltype(mt_c)::value;
+            const f32x4_t* src = xch + (wave ^ 2) * 2 * QUAD + lane;
+            acc[MT][0] = add_quadrant(src, acc[MT][0]);
+            acc[MT][1] = add_quadrant(src + QUAD, acc[MT][1]);
+        });
+    }
+    __syncthreads();
+    if constexpr (LIN) {
         if (tid < D) ksumf[tid] = colsum;
         else if (tid < 2 * D) vhalf[tid - D] = 0.5f * colsum;
-        if (wave == 0) {
+        // round 2 pairs wave w with w ^ 1: each sends the other's quadrant of its half
+        own_quadrant([&](auto mt_c, auto nt_c) {
+            constexpr int MT = decltype(mt_c)::value, NT = decltype(nt_c)::value;
+            put_quadrant(xch + wave * QUAD + lane, acc[MT][1 - NT]);
+        });
+    }
+    __syncthreads();
+    // ---- phase 2: operand tables of the linear branch (same layouts as sfrag / kfrag), each
+    // wave from its own quadrant; filters and bias
+    if constexpr (LIN) {
+        own_quadrant([&](auto mt_c, auto nt_c) {
+            constexpr int MT = decltype(mt_c)::value, NT = decltype(nt_c)::value;
+            // (w + w^2) + (w^1 + w^3)
+            acc[MT][NT] = add_quadrant(xch + (wave ^ 1) * QUAD + lane, acc[MT][NT]);
             uint32_t* sf = reinterpret_cast<uint32_t*>(lds + kFusedSfragOff);
             float* st = state ? state + static_cast<size_t>(unit) * L::SIZE + L::S : nullptr;
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int i = 32 * mt + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
-                        const int j = 32 * nt + (lane % 32);
-                        if (st) st[i * D + j] = acc[mt][nt][r];
-                        if ((r & 1) == 0) {
-                            const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
-                                          ((i & 7) >> 1);
-                            sf[t] = X::pack(acc[mt][nt][r] * tscale, acc[mt][nt][r + 1] * tscale);
-                        }
-                    }
+            for (int r = 0; r < 16; ++r) {
+                const int i = 32 * MT + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
+                const int j = 32 * NT + (lane % 32);
+                if (st) st[i * D + j] = acc[MT][NT][r];
+                if ((r & 1) == 0) {
+                    const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
+                                  ((i & 7) >> 1);
+                    sf[t] = X::pack(acc[MT][NT][r] * tscale, acc[MT][NT][r + 1] * tscale);
+                }
+            }
+        });
+        uint32_t* kfr = reinterpret_cast<uint32_t*>(lds + kFusedKfragOff);
+        for (int u = tid; u < kKfragPerUnit / 2; u += 256) {
+            const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
+            const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
+            kfr[u] = X::pack(ksumf[i0] * tscale, ksumf[i0 + 1] * tscale);
         }
     }
     if constexpr (DW) {
@@ -343,16 +391,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         }
     }
     __syncthreads();
-    if constexpr (LIN) {
-        const float* ksumf = reinterpret_cast<const float*>(un);
-        uint32_t* kfr = reinterpret_cast<uint32_t*>(lds + kFusedKfragOff);
-        for (int u = tid; u < kKfragPerUnit / 2; u += 256) {
-            const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
-            const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
-            kfr[u] = X::pack(ksumf[i0] * tscale, ksumf[i0 + 1] * tscale);
-        }
-        __syncthreads();
-    }
 
     // ---- phase 3
     TRACE_POINT(6);
