@@ -489,8 +489,10 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             __syncthreads();
         }
         // convolution, sum of Eq. 9 and store: item = (token, 8 channels); a thread has the two
-        // tokens tid / 8 and tid / 8 + 32 of the chunk, and every filter tap serves both
-        {
+        // tokens tid / 8 and tid / 8 + 32 of the chunk, and every filter tap serves both.
+        // (Uniform per wave) a wave whose first token is past the end has none: the ragged
+        // last chunk of N = 196 has work for one wave only.
+        if (64 * c + 8 * wave < N) {
             const int tloc0 = tid >> 3;
             float o[2][8];
             int ty[2], tx[2];
