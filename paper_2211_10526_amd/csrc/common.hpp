@@ -130,6 +130,15 @@ __device__ __forceinline__ float sum_partials(const float* p, int n, size_t stri
     return s;
 }
 
+// The value in a vector register the compiler knows nothing about.  Packed 16-bit operands
+// must not be folded into an instruction's inline constants: the encoding of "1.0" there is
+// not the bit pattern this code means.
+__device__ __forceinline__ uint32_t opaque_u32(uint32_t x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
 template <int N, typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
 {

@@ -184,6 +184,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         for (int e = 0; e < 8; ++e) ksum[e] = vsum[e] = 0.f;
     }
     const float inv_eps = 1.0f / p.eps;
+    const uint32_t one_lo = opaque_u32(X::kOneLo), one_hi = opaque_u32(X::kOneHi);
     const float tscale = X::table_scale(N), unsc = X::table_unscale(N);
     unsigned char* const ktile = un + wave * kFusedKtileBytes;
 
@@ -215,10 +216,9 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                 for (int i = 0; i < 4; ++i) {
                     kf[2 * i] = X::lo(kw[i]);
                     kf[2 * i + 1] = X::hi(kw[i]);
-                    ss = fmaf(kf[2 * i], kf[2 * i], ss);
-                    ss = fmaf(kf[2 * i + 1], kf[2 * i + 1], ss);
-                    vsum[2 * i] += X::lo(vw[i]);
-                    vsum[2 * i + 1] += X::hi(vw[i]);
+                    ss = X::dot2(kw[i], kw[i], ss);
+                    vsum[2 * i] = X::dot2(vw[i], one_lo, vsum[2 * i]);
+                    vsum[2 * i + 1] = X::dot2(vw[i], one_hi, vsum[2 * i + 1]);
                 }
                 ss = row_group_sum<8>(ss);
                 // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)

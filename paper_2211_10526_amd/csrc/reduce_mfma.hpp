@@ -98,6 +98,7 @@ struct Bf16Fmt {
     {
         return __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, c, 0, 0, 0);
     }
+    static constexpr uint32_t kOneLo = 0x00003f80u, kOneHi = 0x3f800000u;  // (1, 0) and (0, 1)
     // a.lo * b.lo + a.hi * b.hi + c in fp32 (v_dot2c_f32_bf16)
     static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
     {
@@ -137,6 +138,7 @@ struct F16Fmt {
         return __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(f16x4_t, a),
                                                   __builtin_bit_cast(f16x4_t, b), c, 0, 0, 0);
     }
+    static constexpr uint32_t kOneLo = 0x00003c00u, kOneHi = 0x3c000000u;  // (1, 0) and (0, 1)
     // a.lo * b.lo + a.hi * b.hi + c in fp32 (v_dot2c_f32_f16)
     static __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c)
     {
@@ -251,6 +253,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     const int n_iter = w_end > w_begin ? (w_end - w_begin + kReduceIterTokens - 1) / kReduceIterTokens : 0;
     const uint32_t lane_off = static_cast<uint32_t>(lcol * 2);
     const float inv_eps = 1.0f / eps;
+    const uint32_t one_lo = opaque_u32(X::kOneLo), one_hi = opaque_u32(X::kOneHi);
 
     // rows past the slice are loaded from a clamped (valid) address and zeroed when used
     auto issue_loads = [&](auto slot_c, int n0) {
@@ -294,10 +297,11 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
             for (int i = 0; i < 4; ++i) {
                 kf[2 * i] = X::lo(kw[i]);
                 kf[2 * i + 1] = X::hi(kw[i]);
-                ss = fmaf(kf[2 * i], kf[2 * i], ss);
-                ss = fmaf(kf[2 * i + 1], kf[2 * i + 1], ss);
-                vsum[2 * i] += X::lo(vw[i]);
-                vsum[2 * i + 1] += X::hi(vw[i]);
+                // two-element dot products on the raw pairs: |k|^2 two terms at a time, and the
+                // V column sums without a conversion (the other half meets a zero)
+                ss = X::dot2(kw[i], kw[i], ss);
+                vsum[2 * i] = X::dot2(vw[i], one_lo, vsum[2 * i]);
+                vsum[2 * i + 1] = X::dot2(vw[i], one_hi, vsum[2 * i + 1]);
             }
             ss = row_group_sum<LPR>(ss);
             // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
