@@ -48,6 +48,9 @@ struct ApplyMfmaParams {
     int norm_none, do_linear, do_dwconv;
     float eps;
     TensorStrides in, out;  // of q and v; of out.  N * token stride * 2 stays below 4 GiB
+    // Pairs of 32-wide heads run as one 64-channel unit: bytes to add to the address of the
+    // second half of a token row (channels 32..63 belong to the next head); 0 otherwise
+    uint32_t in_skew, out_skew;
 };
 
 constexpr int kStripW = 16;
@@ -122,6 +125,72 @@ __global__ __launch_bounds__(256) void combine_frag_kernel(
     }
 }
 constexpr int kCombineFragThreads = 2048 + 128 + 512;
+
+// The same for pairs of heads with d = 32 that pass 2 runs as one 64-channel unit: row `pu`
+// sums the partials of the pair, writes the fp32 states of units 2 pu and 2 pu + 1
+// (StateLayout<32>) and builds the pair's operand tables: S block diagonal (zero where row and
+// column belong to different heads), ksum and vsum / 2 one head after the other.
+// wide = 1: pass 1 ran on the pairs too (partials in StateLayout<64>, of whose S only the
+// diagonal 32 x 32 blocks are read); wide = 0: on the single heads (StateLayout<32>).
+template <typename X>
+__global__ __launch_bounds__(256) void combine_pair_frag_kernel(
+    const float* __restrict__ partial, float* __restrict__ state, bf16_t* __restrict__ sfrag,
+    bf16_t* __restrict__ kfrag, float* __restrict__ vhalf, int n_split, int pairs, int wide,
+    const bf16_t* __restrict__ w, bf16_t* __restrict__ wfrag, int pair_heads, int ks, float tscale)
+{
+    using L = StateLayout<32>;
+    using P = StateLayout<64>;
+    if (static_cast<int>(blockIdx.y) >= pairs) {
+        const int row = blockIdx.y - pairs;
+        dwconv_weight_frag((row * gridDim.x + blockIdx.x) * 256 + threadIdx.x, w, wfrag, pair_heads, ks);
+        return;
+    }
+    const int pu = blockIdx.y;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = wide ? P::SIZE : L::SIZE;
+    // entry (i, j) of the pair's S (same head on both sides), entry f of its ksum (f < 64) or
+    // vsum (f >= 64), summed over the splits
+    auto s_entry = [&](int i, int j) {
+        const float* p = wide ? partial + static_cast<size_t>(pu) * n_split * P::SIZE + i * 64 + j
+                              : partial + static_cast<size_t>(2 * pu + (i >> 5)) * n_split * L::SIZE +
+                                    (i & 31) * 32 + (j & 31);
+        return sum_partials(p, n_split, stride);
+    };
+    auto v_entry = [&](int f) {
+        const float* p = wide ? partial + static_cast<size_t>(pu) * n_split * P::SIZE + P::KSUM + f
+                              : partial + static_cast<size_t>(2 * pu + ((f >> 5) & 1)) * n_split * L::SIZE +
+                                    (f < 64 ? L::KSUM : L::VSUM) + (f & 31);
+        return sum_partials(p, n_split, stride);
+    };
+    auto stat = [&](int head) { return state + static_cast<size_t>(2 * pu + head) * L::SIZE; };
+    if (t < 2048) {
+        // S: t = ((nt*2 + ks)*64 + lane)*4 + e2 over the pair's 64 x 64 table
+        const int e2 = t & 3, lane = (t >> 2) & 63, kst = (t >> 8) & 1, nt = t >> 9;
+        const int i0 = 32 * kst + 8 * (lane >> 4) + 2 * e2;
+        const int j = 16 * nt + (lane & 15);
+        uint32_t word = 0u;
+        if ((i0 >> 5) == (j >> 5)) {
+            const int head = i0 >> 5, li = i0 & 31, lj = j & 31;
+            const float s0 = s_entry(i0, j), s1 = s_entry(i0 + 1, j);
+            stat(head)[li * 32 + lj] = s0;
+            stat(head)[(li + 1) * 32 + lj] = s1;
+            word = X::pack(s0 * tscale, s1 * tscale);
+        }
+        reinterpret_cast<uint32_t*>(sfrag + static_cast<size_t>(pu) * kSfragPerUnit)[t] = word;
+    } else if (t < 2048 + 128) {
+        const int f = t - 2048;  // 0..63 ksum of the pair, 64..127 vsum of the pair
+        const int head = (f >> 5) & 1, lf = f & 31;
+        const float s = v_entry(f);
+        stat(head)[(f < 64 ? L::KSUM : L::VSUM) + lf] = s;
+        if (f >= 64) vhalf[pu * 64 + (f - 64)] = 0.5f * s;
+    } else if (t < 2048 + 128 + 512) {
+        const int u = t - (2048 + 128);
+        const int e2 = u & 3, lane = (u >> 2) & 63, kst = u >> 8;
+        const int i0 = 32 * kst + 8 * (lane >> 4) + 2 * e2;
+        reinterpret_cast<uint32_t*>(kfrag + static_cast<size_t>(pu) * kKfragPerUnit)[u] =
+            X::pack(v_entry(i0) * tscale, v_entry(i0 + 1) * tscale);
+    }
+}
 
 __global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* __restrict__ w,
                                                                  bf16_t* __restrict__ wfrag,
@@ -231,7 +300,10 @@ struct StageSnap {
 };
 
 // grid = (G), block = 64 * kApplyWaves.
-template <int KS, bool LIN, bool DW, typename X>
+// PAIR: a unit is two heads of 32 channels.  Loads, stores and the convolution do not care; the
+// linear branch takes each half's norm, row sum and state from its own head (the S operand
+// table is then block diagonal, and only the matching half of q meets it).
+template <int KS, bool LIN, bool DW, typename X, bool PAIR = false>
 __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ v, const bf16_t* __restrict__ bias,
     const bf16_t* __restrict__ sfrag, const bf16_t* __restrict__ kfrag,
@@ -317,6 +389,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             v_x[it] = ((item % 192) >> 3) - 4;
         }
         const int v_oct = lane & 7;
+        const uint32_t v_oct_off = v_oct * 16 + (v_oct >> 2) * p.in_skew;
+        const uint32_t o_oct_off = v_oct * 16 + (v_oct >> 2) * p.out_skew;
         unsigned char* const nat = nat_base + c * kNatBytes;
         // transposition roles: token-major write (token lane/8, octet lane%8); transposing read
         // source (token 4 qd + (lane/4)%4, channels 16 (lane/16) + 4 (lane%4)..+3); afterwards
@@ -353,7 +427,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     if (gy >= 0 && gy < H && gx >= 0 && gx < W) ok |= 1u << it;
                     const int cy = min(max(gy, 0), H - 1), cx = min(max(gx, 0), W - 1);
                     async_load16(vreg[slot][it], vb,
-                                 static_cast<uint32_t>(cy * W + cx) * in_tok + v_oct * 16);
+                                 static_cast<uint32_t>(cy * W + cx) * in_tok + v_oct_off);
                 }
             }
             okmask[slot] = ok;
@@ -391,7 +465,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             for (int it = 0; it < 2; ++it) {
                 const int x = fs.xs0 + (lane >> 3) + 8 * it;
                 if (y < H && x < W)
-                    store16_stream(ou + (static_cast<uint32_t>(y * W + x) * out_tok + (lane & 7) * 16),
+                    store16_stream(ou + (static_cast<uint32_t>(y * W + x) * out_tok + o_oct_off),
                                    line[it][0], line[it][1], line[it][2], line[it][3]);
             }
         };
@@ -507,6 +581,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
         long long q_base = 0;
         // products of two stages in flight: [parity]
         f32x4_t gram[2], dk[2], acc[2][4];
+        f32x4_t gramb[2], dkb[2];  // PAIR: the same for the second head of the pair
         float vhb[2][4];
         bool busy[2] = {false, false};
 
@@ -524,7 +599,7 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 }
                 const bf16_t* qb = q + q_base;
                 async_load16_stream(qreg[slot][0], qb, off);
-                async_load16_stream(qreg[slot][1], qb, off + 64);
+                async_load16_stream(qreg[slot][1], qb, off + 64 + p.in_skew);
             }
             snap[slot].unit = cu.unit;
             snap[slot].xs0 = xs0;
@@ -568,19 +643,31 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 // |q_t|^2 on the matrix cores: the diagonal of Q Q^T (B operand = same registers).
                 // Six independent accumulators, k-step outermost: no MFMA waits for the one
                 // issued just before it.
-#pragma unroll
-                for (int r = 0; r < 4; ++r) gram[PAR][r] = dk[PAR][r] = 0.f;
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[PAR][nt][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    gram[PAR] = X::mfma16(a[ks], a[ks], gram[PAR]);
-                    dk[PAR] = X::mfma16(a[ks], kf[ks], dk[PAR]);
+                if constexpr (PAIR) {
+                    // k-step 0 holds the first head's 32 features, k-step 1 the second's
+                    const f32x4_t z = {0.f, 0.f, 0.f, 0.f};
+                    gram[PAR] = X::mfma16(a[0], a[0], z);
+                    gramb[PAR] = X::mfma16(a[1], a[1], z);
+                    dk[PAR] = X::mfma16(a[0], kf[0], z);
+                    dkb[PAR] = X::mfma16(a[1], kf[1], z);
 #pragma unroll
                     for (int nt = 0; nt < 4; ++nt)
-                        acc[PAR][nt] = X::mfma16(a[ks], sf[nt][ks], acc[PAR][nt]);
+                        acc[PAR][nt] = X::mfma16(a[nt >> 1], sf[nt][nt >> 1], z);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) gram[PAR][r] = dk[PAR][r] = 0.f;
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[PAR][nt][r] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) {
+                        gram[PAR] = X::mfma16(a[ks], a[ks], gram[PAR]);
+                        dk[PAR] = X::mfma16(a[ks], kf[ks], dk[PAR]);
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt)
+                            acc[PAR][nt] = X::mfma16(a[ks], sf[nt][ks], acc[PAR][nt]);
+                    }
                 }
                 TRACE_POINT(22);
             }
@@ -591,32 +678,38 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             constexpr int PAR = decltype(par_c)::value;
             if constexpr (LIN) {
                 if (!busy[PAR]) return;
-                float alpha[4], beta[4];
+                constexpr int NH = PAIR ? 2 : 1;  // heads in the unit
+                float alpha[NH][4], beta[NH][4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
-                    const float ssr = __int_as_float(
-                        __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[PAR][r])));
-                    // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
-                    float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
-                    if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
-                    if (p.norm_none) {
-                        alpha[r] = inv;
-                        beta[r] = 1.0f;
-                    } else {
-                        const float rden = __builtin_amdgcn_rcpf(half_n + inv * dk[PAR][r]);
-                        alpha[r] = inv * rden;
-                        beta[r] = rden;
+                for (int hh = 0; hh < NH; ++hh)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float gr = hh ? gramb[PAR][r] : gram[PAR][r];
+                        const float dr = hh ? dkb[PAR][r] : dk[PAR][r];
+                        // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
+                        const float ssr = __int_as_float(
+                            __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gr)));
+                        // 1 / max(|q|, eps) with the hardware reciprocal square root (1 ulp)
+                        float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                        if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
+                        if (p.norm_none) {
+                            alpha[hh][r] = inv;
+                            beta[hh][r] = 1.0f;
+                        } else {
+                            const float rden = __builtin_amdgcn_rcpf(half_n + inv * dr);
+                            alpha[hh][r] = inv * rden;
+                            beta[hh][r] = rden;
+                        }
                     }
-                }
                 TRACE_POINT(23);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) {
+                    const int hh = PAIR ? (nt >> 1) : 0;
                     float4 o;
-                    o.x = fmaf(alpha[0], acc[PAR][nt][0], beta[0] * vhb[PAR][nt]);
-                    o.y = fmaf(alpha[1], acc[PAR][nt][1], beta[1] * vhb[PAR][nt]);
-                    o.z = fmaf(alpha[2], acc[PAR][nt][2], beta[2] * vhb[PAR][nt]);
-                    o.w = fmaf(alpha[3], acc[PAR][nt][3], beta[3] * vhb[PAR][nt]);
+                    o.x = fmaf(alpha[hh][0], acc[PAR][nt][0], beta[hh][0] * vhb[PAR][nt]);
+                    o.y = fmaf(alpha[hh][1], acc[PAR][nt][1], beta[hh][1] * vhb[PAR][nt]);
+                    o.z = fmaf(alpha[hh][2], acc[PAR][nt][2], beta[hh][2] * vhb[PAR][nt]);
+                    o.w = fmaf(alpha[hh][3], acc[PAR][nt][3], beta[hh][3] * vhb[PAR][nt]);
                     *reinterpret_cast<float4*>(lin + ((c * 64 + 16 * nt + tl) * kLinTokPitch + 4 * g)) = o;
                 }
             }

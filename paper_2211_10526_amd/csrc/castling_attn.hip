@@ -81,6 +81,11 @@ struct castling_attn {
     bool mfma_reduce;   // bf16 / fp16, d = 32 or 64: K_hat^T V on the matrix cores
     bool mfma_apply;    // bf16 / fp16, d = 64: q.S and the DWConv on the matrix cores
     bool half16;        // the 16-bit format is fp16 (else bf16)
+    bool pair;          // d = 32: pass 2 runs two heads as one 64-channel unit (mfma_apply is set)
+    bool pair_reduce;   // ... and so does pass 1: the heads are neighbours in memory (whole rows)
+    int apply_units, apply_heads;         // units and heads as pass 2 counts them
+    TensorStrides apply_in, apply_out;    // strides of those units
+    uint32_t in_skew, out_skew;           // pair: see ApplyMfmaParams
     bool fused;         // forward() runs the one-kernel path (small N)
     bool state_valid;   // the workspace holds the state of the last reduce
     int num_cus;        // compute units of the device
@@ -110,10 +115,13 @@ void launch_reduce_generic(castling_attn* h, const void* k, const void* v, hipSt
 
 // w != nullptr: extra grid rows build the DWConv weight operand table.
 // direct: the blocks' results are final (n_split == 1); they write state and tables themselves.
-template <int D, typename X>
+// PAIR: the units are the pairs of 32-wide heads pass 2 works on.
+template <int D, typename X, bool PAIR = false>
 void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const void* w, bool direct,
                         hipStream_t s)
 {
+    const int units = PAIR ? h->apply_units : h->units;
+    const int heads = PAIR ? h->apply_heads : h->desc.heads;
     ReduceExtras ex;
     ex.state = direct ? h->state : nullptr;
     ex.sfrag = h->sfrag;
@@ -121,17 +129,18 @@ void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const vo
     ex.vhalf = h->vhalf;
     ex.w = static_cast<const bf16_t*>(w);
     ex.wfrag = h->wfrag;
-    ex.units = h->units;
-    ex.heads = h->desc.heads;
+    ex.units = units;
+    ex.heads = heads;
     ex.ks = h->desc.dw_kernel;
     ex.tscale = X::table_scale(h->desc.N);
+    ex.pair_skew = h->in_skew;
     const int per_row = h->n_split * 64 * kReduceWaves;
-    const int wthreads = h->desc.heads * 4 * ex.ks * 3 * 64;
+    const int wthreads = heads * 4 * ex.ks * 3 * 64;
     const int wrows = w ? (wthreads + per_row - 1) / per_row : 0;
-    hipLaunchKernelGGL((reduce_mfma_kernel<D, X>), dim3(h->n_split, h->units + wrows),
+    hipLaunchKernelGGL((reduce_mfma_kernel<D, X, PAIR>), dim3(h->n_split, units + wrows),
                        dim3(64 * kReduceWaves), 0, s, static_cast<const bf16_t*>(k),
                        static_cast<const bf16_t*>(v), h->partial, h->desc.N, h->n_split, h->chunk,
-                       h->desc.eps, h->desc.heads, h->in_st, ex);
+                       h->desc.eps, heads, PAIR ? h->apply_in : h->in_st, ex);
 }
 
 template <int D>
@@ -149,13 +158,15 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
     h->state_valid = true;
     // with one split per unit the reduce kernel's result is final: it writes the state and
     // the apply kernel's operand tables itself, and no combine is launched
-    const bool direct = h->mfma_apply && h->n_split == 1;
+    const bool direct = h->mfma_apply && !h->pair && h->n_split == 1;
     if (h->mfma_reduce) {
         if (h->half16) {
-            if (d == 32) launch_reduce_mfma<32, F16Fmt>(h, k, v, nullptr, false, s);
+            if (h->pair_reduce) launch_reduce_mfma<64, F16Fmt, true>(h, k, v, nullptr, false, s);
+            else if (d == 32) launch_reduce_mfma<32, F16Fmt>(h, k, v, nullptr, false, s);
             else launch_reduce_mfma<64, F16Fmt>(h, k, v, direct ? w : nullptr, direct, s);
         } else {
-            if (d == 32) launch_reduce_mfma<32, Bf16Fmt>(h, k, v, nullptr, false, s);
+            if (h->pair_reduce) launch_reduce_mfma<64, Bf16Fmt, true>(h, k, v, nullptr, false, s);
+            else if (d == 32) launch_reduce_mfma<32, Bf16Fmt>(h, k, v, nullptr, false, s);
             else launch_reduce_mfma<64, Bf16Fmt>(h, k, v, direct ? w : nullptr, direct, s);
         }
     } else {
@@ -169,7 +180,24 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
     // vector-ALU apply with one split per unit: the partial layout is the state layout and the
     // handle points `partial` at `state`, so the reduce kernel's result is final as written
     if (!h->mfma_apply && h->n_split == 1) return CASTLING_OK;
-    if (h->mfma_apply) {
+    if (h->pair) {
+        const int gx = (kCombineFragThreads + 255) / 256;
+        const int ks = h->desc.dw_kernel;
+        const int wthreads = h->apply_heads * 4 * ks * 3 * 64;
+        const int wrows = w ? (wthreads + gx * 256 - 1) / (gx * 256) : 0;
+        if (h->half16)
+            hipLaunchKernelGGL(combine_pair_frag_kernel<F16Fmt>, dim3(gx, h->apply_units + wrows),
+                               dim3(256), 0, s, h->partial, h->state, h->sfrag, h->kfrag, h->vhalf,
+                               h->n_split, h->apply_units, h->pair_reduce ? 1 : 0,
+                               static_cast<const bf16_t*>(w), h->wfrag, h->apply_heads, ks,
+                               F16Fmt::table_scale(h->desc.N));
+        else
+            hipLaunchKernelGGL(combine_pair_frag_kernel<Bf16Fmt>, dim3(gx, h->apply_units + wrows),
+                               dim3(256), 0, s, h->partial, h->state, h->sfrag, h->kfrag, h->vhalf,
+                               h->n_split, h->apply_units, h->pair_reduce ? 1 : 0,
+                               static_cast<const bf16_t*>(w), h->wfrag, h->apply_heads, ks,
+                               Bf16Fmt::table_scale(h->desc.N));
+    } else if (h->mfma_apply) {
         const int gx = (kCombineFragThreads + 255) / 256;
         const int ks = h->desc.dw_kernel;
         const int wthreads = h->desc.heads * 4 * ks * 3 * 64;
@@ -232,10 +260,15 @@ template <int KS, bool LIN, bool DW, typename X>
 hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, const void* v,
                                const void* w, const void* bias, void* out, hipStream_t s)
 {
+    // only the linear branch tells a pair of heads from one head
+    constexpr bool kPairKernel = LIN;
+    const bool pair = kPairKernel && h->pair;
     if (!launch) {
         h->apply_lds = kApplyMfmaLdsBytes;
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_mfma_kernel<KS, LIN, DW, X>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kApplyMfmaLdsBytes);
+        const void* fn = reinterpret_cast<const void*>(&apply_mfma_kernel<KS, LIN, DW, X, false>);
+        if constexpr (kPairKernel)
+            if (pair) fn = reinterpret_cast<const void*>(&apply_mfma_kernel<KS, LIN, DW, X, true>);
+        return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kApplyMfmaLdsBytes);
     }
     const castling_attn_desc_t& d = h->desc;
     ApplyMfmaParams p;
@@ -247,23 +280,32 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     p.do_linear = LIN;
     p.do_dwconv = DW;
     p.eps = d.eps;
-    p.in = h->in_st;
-    p.out = h->out_st;
+    p.in = h->apply_in;
+    p.out = h->apply_out;
+    p.in_skew = h->in_skew;
+    p.out_skew = h->out_skew;
     if (DW && w) {
-        const int threads = d.heads * 4 * KS * 3 * 64;
+        const int threads = h->apply_heads * 4 * KS * 3 * 64;
         hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
-                           static_cast<const bf16_t*>(w), h->wfrag, d.heads, KS);
+                           static_cast<const bf16_t*>(w), h->wfrag, h->apply_heads, KS);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     // one persistent block per compute unit; every block takes an equal share of the steps
-    const int total_steps = h->units * p.strips * ((p.grid_h + 3) / 4);
+    const int total_steps = h->apply_units * p.strips * ((p.grid_h + 3) / 4);
     const int blocks = total_steps < h->num_cus ? total_steps : h->num_cus;
-    hipLaunchKernelGGL((apply_mfma_kernel<KS, LIN, DW, X>), dim3(blocks), dim3(64 * kApplyWaves),
-                       kApplyMfmaLdsBytes, s, static_cast<const bf16_t*>(q),
-                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(bias), h->sfrag,
-                       h->kfrag, h->vhalf, h->wfrag, static_cast<bf16_t*>(out), d.heads,
-                       total_steps, p);
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64 * kApplyWaves), kApplyMfmaLdsBytes, s,
+                           static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(v),
+                           static_cast<const bf16_t*>(bias), h->sfrag, h->kfrag, h->vhalf, h->wfrag,
+                           static_cast<bf16_t*>(out), h->apply_heads, total_steps, p);
+    };
+    if constexpr (kPairKernel) {
+        if (pair) go(apply_mfma_kernel<KS, LIN, DW, X, true>);
+        else go(apply_mfma_kernel<KS, LIN, DW, X, false>);
+    } else {
+        go(apply_mfma_kernel<KS, LIN, DW, X, false>);
+    }
     return hipGetLastError();
 }
 
@@ -544,9 +586,33 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->half16 = desc->io_dtype == CASTLING_F16;
     h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
     h->mfma_apply = allow_mfma && desc->d == 64;
+    h->apply_units = h->units;
+    h->apply_heads = desc->heads;
+    h->apply_in = h->in_st;
+    h->apply_out = h->out_st;
+    h->in_skew = h->out_skew = 0;
+    h->pair = h->pair_reduce = false;
+    if (allow_mfma && desc->d == 32 && desc->heads % 2 == 0) {
+        // two neighbouring heads of 32 channels as one unit of 64 for pass 2: the second half of
+        // a token row lies one head stride further on instead of 64 bytes
+        const long long in_skew = h->in_st.h * 2 - 64, out_skew = h->out_st.h * 2 - 64;
+        const long long lim = (1ll << 32) - 256;
+        if (in_skew >= 0 && out_skew >= 0 && desc->N * h->in_st.n * 2 + in_skew < lim &&
+            desc->N * h->out_st.n * 2 + out_skew < lim) {
+            h->pair = h->mfma_apply = true;
+            h->apply_units = h->units / 2;
+            h->apply_heads = desc->heads / 2;
+            h->apply_in.h *= 2;
+            h->apply_out.h *= 2;
+            h->in_skew = static_cast<uint32_t>(in_skew);
+            h->out_skew = static_cast<uint32_t>(out_skew);
+            // pass 1 gains from pairs only where they make its loads whole 128-byte rows
+            h->pair_reduce = in_skew == 0;
+        }
+    }
     // CASTLING_ATTN_NO_FUSED=1 keeps forward() on the two-pass path at small N (A/B measurements)
     const char* nofuse = getenv("CASTLING_ATTN_NO_FUSED");
-    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs &&
+    h->fused = h->mfma_apply && !h->pair && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs &&
                !(nofuse && nofuse[0] == '1');
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
@@ -556,7 +622,8 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         const int v = atoi(tb);
         if (v > 0) target_blocks = v;
     }
-    int n_split = target_blocks / h->units;  // never one block more than fits at once
+    const int reduce_units = h->pair_reduce ? h->apply_units : h->units;
+    int n_split = target_blocks / reduce_units;  // never one block more than fits at once
     const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
     if (n_split > max_split) n_split = max_split;
     if (n_split < 1) n_split = 1;
@@ -583,7 +650,9 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     }
     // one allocation, 256-byte aligned parts
     const size_t partial_bytes =
-        align_up(sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size, 256);
+        h->pair_reduce ? align_up(sizeof(float) * static_cast<size_t>(h->apply_units) * h->n_split *
+                               StateLayout<64>::SIZE, 256)
+                : align_up(sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size, 256);
     const size_t state_bytes =
         align_up(sizeof(float) * static_cast<size_t>(h->units) * h->state_size, 256);
     size_t sfrag_bytes = 0, kfrag_bytes = 0, vhalf_bytes = 0, wfrag_bytes = 0;
@@ -637,7 +706,7 @@ int castling_attn_num_launches(castling_attn_t h)
     const int extra = h->desc.extra_tokens > 0 ? 1 : 0;  // the tokens off the grid: one more launch
     if (h->fused) return 1;
     if (!lin) return 1 + extra;
-    return (h->n_split == 1 ? 2 : 3) + extra;
+    return ((h->n_split == 1 && !h->pair) ? 2 : 3) + extra;
 }
 
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
@@ -652,10 +721,10 @@ int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void
     if (!h || !dw_weight || misaligned(dw_weight)) return CASTLING_ERR_INVALID_ARG;
     if (h->mfma_apply && (h->desc.branches & CASTLING_BRANCH_DWCONV)) {
         const castling_attn_desc_t& d = h->desc;
-        const int threads = d.heads * 4 * d.dw_kernel * 3 * 64;
+        const int threads = h->apply_heads * 4 * d.dw_kernel * 3 * 64;
         hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0,
                            static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(dw_weight),
-                           h->wfrag, d.heads, d.dw_kernel);
+                           h->wfrag, h->apply_heads, d.dw_kernel);
         HIP_TRY(hipGetLastError());
     }
     h->prepared_w = dw_weight;

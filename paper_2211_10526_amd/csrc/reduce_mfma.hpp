@@ -179,11 +179,15 @@ struct ReduceExtras {
     bf16_t* wfrag;
     int units, heads, ks;
     float tscale;  // table scale of the I/O format for this N
+    uint32_t pair_skew;  // PAIR: bytes to add to the address of channels 32..63 of a token row
 };
 
 // grid = (n_split, units [+ weight rows]), block = 64 * kReduceWaves.  Same partial layout
 // as the generic kernel: partial[u][s][StateLayout<D>::SIZE].
-template <int D, typename X>
+// PAIR (D = 64): a unit is two heads of 32 channels (whole 128-byte token rows when the heads
+// are neighbours in memory); each half of a K row is normalised on its own, and of the 64 x 64
+// product only the two diagonal 32 x 32 blocks mean anything.
+template <int D, typename X, bool PAIR = false>
 __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
     int n_split, int chunk, float eps, int heads, TensorStrides st, ReduceExtras ex)
@@ -251,7 +255,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
     static_assert(LOADS == 2 || LOADS == 4, "wait_async_loads takes 2 or 4 registers");
     u32x4_t kraw[RPD][LOADS], vraw[RPD][LOADS];
     const int n_iter = w_end > w_begin ? (w_end - w_begin + kReduceIterTokens - 1) / kReduceIterTokens : 0;
-    const uint32_t lane_off = static_cast<uint32_t>(lcol * 2);
+    const uint32_t lane_off = static_cast<uint32_t>(lcol * 2) + ((PAIR && lcol >= 32) ? ex.pair_skew : 0u);
     const float inv_eps = 1.0f / eps;
     const uint32_t one_lo = opaque_u32(X::kOneLo), one_hi = opaque_u32(X::kOneHi);
 
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
                 vsum[2 * i] = X::dot2(vw[i], one_lo, vsum[2 * i]);
                 vsum[2 * i + 1] = X::dot2(vw[i], one_hi, vsum[2 * i + 1]);
             }
-            ss = row_group_sum<LPR>(ss);
+            ss = row_group_sum<PAIR ? LPR / 2 : LPR>(ss);
             // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
             const float inv = fminf(__builtin_amdgcn_rsqf(ss), inv_eps);
             u32x4_t kh;

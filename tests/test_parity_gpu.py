@@ -134,8 +134,14 @@ def test_fused_qkv_layout(oracle, wl):
     got, st = gpu_forward_fused(wl, x, want_state=True)
     assert np.isfinite(got).all()
     assert rel_err(got, want) <= TOL[wl.dtype]
-    # the same kernels in the same order: bitwise equal to the contiguous layout
     dense, st_dense = gpu_forward(wl, x, want_state=True)
+    if wl.d == 32 and wl.dtype != "f32" and wl.heads % 2 == 0:
+        # pairs of narrow heads: pass 1 reduces whole pairs where their rows are adjacent (this
+        # layout) and single heads otherwise, so the sums are taken in another order
+        assert rel_err(st, st_dense) <= 1e-5
+        assert rel_err(got, dense) <= TOL[wl.dtype]
+        return
+    # the same kernels in the same order: bitwise equal to the contiguous layout
     assert np.array_equal(got, dense)
     assert np.array_equal(st, st_dense)
     for branches in (b.BRANCH_LINEAR, b.BRANCH_DWCONV):
@@ -494,3 +500,46 @@ def test_dwconv_on_token_major_features(oracle, dtype, C_, ks):
     want = oracle.forward(q, k, v, w, bias, H, W, branches=b.BRANCH_DWCONV)
     got = inputs.to_f64(out.view(B, N, heads, d).permute(0, 2, 1, 3))
     assert rel_err(got, want) <= TOL[dtype]
+
+
+# 16-bit heads of 32 channels: pass 2 runs two neighbouring heads as one 64-channel unit on the
+# matrix cores (even head counts); dense and fused layouts, several strips, ragged edges
+HEAD_PAIRS = [
+    Workload("hp_bf16_b2_h4_d32_20x24_k3", "bf16", 2, 4, 32, 20, 24, 3),
+    Workload("hp_f16_b1_h6_d32_33x17_k9", "f16", 1, 6, 32, 33, 17, 9),
+    Workload("hp_bf16_b3_h2_d32_14x14_k5", "bf16", 3, 2, 32, 14, 14, 5),
+    Workload("hp_bf16_b1_h8_d32_9x40_k7_outl", "bf16", 1, 8, 32, 9, 40, 7, 0.05, 8.0),
+    Workload("hp_bf16_b32_h8_d32_7x7_k3", "bf16", 32, 8, 32, 7, 7, 3),
+]
+
+
+@pytest.mark.parametrize("wl", HEAD_PAIRS, ids=lambda w: w.name)
+@pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
+def test_pairs_of_narrow_heads(oracle, wl, norm):
+    x = inputs.make_inputs(wl, seed=61, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    for branches in (b.BRANCH_ALL, b.BRANCH_LINEAR, b.BRANCH_DWCONV):
+        print(f"case {wl.name} norm={norm} branches={branches}", flush=True)
+        want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w, norm=norm, branches=branches)
+        if branches & b.BRANCH_LINEAR:
+            got, st = gpu_forward(wl, x, norm=norm, branches=branches, want_state=True)
+            assert rel_err(st, oracle.state(k, v)) <= STATE_TOL[wl.dtype]
+        else:
+            got = gpu_forward(wl, x, norm=norm, branches=branches)
+        assert rel_err(got, want) <= TOL[wl.dtype], (wl.name, norm, branches)
+        strided = gpu_forward_fused(wl, x, norm=norm, branches=branches)
+        assert rel_err(strided, want) <= TOL[wl.dtype], (wl.name, norm, branches, "fused layout")
+        # head rows of 40 elements: the two halves of a pair's token row are not adjacent
+        padded = gpu_forward_fused(wl, x, norm=norm, branches=branches, pad=8)
+        assert rel_err(padded, want) <= TOL[wl.dtype], (wl.name, norm, branches, "padded heads")
+
+
+def test_pairs_of_narrow_heads_take_the_matrix_core_path(monkeypatch):
+    """One split per unit: the vector-ALU path needs two launches, the pair path three (its
+    operand tables come from a combine launch of their own); an odd head count cannot pair."""
+    even = b.CastlingAttn.for_workload(HEAD_PAIRS[4])
+    odd = b.CastlingAttn.for_workload(Workload("hp_odd", "bf16", 32, 9, 32, 7, 7, 3))
+    n_even, n_odd, s_even = even.num_launches(), odd.num_launches(), even.num_splits()
+    even.destroy()
+    odd.destroy()
+    assert s_even == 1 and n_even == 3 and n_odd == 2
