@@ -411,9 +411,15 @@ template <int KS, bool LIN, bool DW, typename X>
 hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const void* k,
                           const void* v, const void* w, const void* bias, void* out, hipStream_t s)
 {
-    if (!launch)
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&fused_small_kernel<KS, LIN, DW, X>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    // only the linear branch tells a pair of heads from one head
+    constexpr bool kPairKernel = LIN;
+    const bool pair = kPairKernel && h->pair;
+    if (!launch) {
+        const void* fn = reinterpret_cast<const void*>(&fused_small_kernel<KS, LIN, DW, X, false>);
+        if constexpr (kPairKernel)
+            if (pair) fn = reinterpret_cast<const void*>(&fused_small_kernel<KS, LIN, DW, X, true>);
+        return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
+    }
     const castling_attn_desc_t& d = h->desc;
     FusedParams p;
     p.N = d.N;
@@ -422,14 +428,24 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
     p.extra = d.extra_tokens;
     p.norm_none = d.norm == CASTLING_NORM_NONE;
     p.eps = d.eps;
-    p.in = h->in_st;
-    p.out = h->out_st;
-    hipLaunchKernelGGL((fused_small_kernel<KS, LIN, DW, X>), dim3(h->units), dim3(256), kFusedLdsBytes,
-                       s, static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
-                       static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(w),
-                       static_cast<const bf16_t*>(bias),
-                       (d.flags & CASTLING_FLAG_KEEP_STATE) ? h->state : nullptr,
-                       static_cast<bf16_t*>(out), d.heads, p);
+    p.in = h->apply_in;
+    p.out = h->apply_out;
+    p.in_skew = h->in_skew;
+    p.out_skew = h->out_skew;
+    auto go = [&](auto kernel) {
+        hipLaunchKernelGGL(kernel, dim3(h->apply_units), dim3(256), kFusedLdsBytes, s,
+                           static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(k),
+                           static_cast<const bf16_t*>(v), static_cast<const bf16_t*>(w),
+                           static_cast<const bf16_t*>(bias),
+                           (d.flags & CASTLING_FLAG_KEEP_STATE) ? h->state : nullptr,
+                           static_cast<bf16_t*>(out), h->apply_heads, p);
+    };
+    if constexpr (kPairKernel) {
+        if (pair) go(fused_small_kernel<KS, LIN, DW, X, true>);
+        else go(fused_small_kernel<KS, LIN, DW, X, false>);
+    } else {
+        go(fused_small_kernel<KS, LIN, DW, X, false>);
+    }
     h->state_valid = (d.flags & CASTLING_FLAG_KEEP_STATE) != 0;
     return hipGetLastError();
 }
@@ -612,7 +628,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     }
     // CASTLING_ATTN_NO_FUSED=1 keeps forward() on the two-pass path at small N (A/B measurements)
     const char* nofuse = getenv("CASTLING_ATTN_NO_FUSED");
-    h->fused = h->mfma_apply && !h->pair && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs &&
+    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs &&
                !(nofuse && nofuse[0] == '1');
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block

@@ -53,6 +53,7 @@ struct FusedParams {
     int norm_none;
     float eps;
     TensorStrides in, out;
+    uint32_t in_skew, out_skew;  // pairs of heads: bytes added to the address of channels 32..63 of a row (else 0)
 };
 
 // One 32 x 32 quadrant of a wave's accumulators to / from an exchange slot in LDS
@@ -81,7 +82,10 @@ __device__ __forceinline__ f32x16_t add_quadrant(const f32x4_t* src, f32x16_t t)
 
 // grid = (units), block = 256, dynamic LDS = kFusedLdsBytes.
 // state: [units][StateLayout<64>::SIZE] fp32 copy of the state (nullptr = not wanted).
-template <int KS, bool LIN, bool DW, typename X>
+// PAIR: a unit is two neighbouring heads of 32 channels (see apply_mfma_kernel): each half of a
+// K or q row has its own norm, row sum and 32 x 32 state; the S operand table is block diagonal
+// and `state` takes two StateLayout<32> records per unit.
+template <int KS, bool LIN, bool DW, typename X, bool PAIR = false>
 __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, const bf16_t* __restrict__ v,
     const bf16_t* __restrict__ w, const bf16_t* __restrict__ bias, float* __restrict__ state,
@@ -134,7 +138,8 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         uint32_t off[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            off[j] = static_cast<uint32_t>(min(n0 + 8 * j + lrow, N - 1)) * in_tok + lcol * 2;
+            off[j] = static_cast<uint32_t>(min(n0 + 8 * j + lrow, N - 1)) * in_tok + lcol * 2 +
+                     (lcol >= 32 ? p.in_skew : 0u);
         if constexpr (LIN) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) async_load16_stream(kraw[it][j], kb, off[j]);
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                 const int tok = min(64 * c + 16 * wave + tl, N - 1);
                 const uint32_t off = static_cast<uint32_t>(tok) * in_tok + g * 16;
                 async_load16_stream(qraw[c][0], qb, off);
-                async_load16_stream(qraw[c][1], qb, off + 64);
+                async_load16_stream(qraw[c][1], qb, off + 64 + p.in_skew);
             }
         }
     };
@@ -220,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                     vsum[2 * i] = X::dot2(vw[i], one_lo, vsum[2 * i]);
                     vsum[2 * i + 1] = X::dot2(vw[i], one_hi, vsum[2 * i + 1]);
                 }
-                ss = row_group_sum<8>(ss);
+                ss = row_group_sum<PAIR ? 4 : 8>(ss);
                 // 1 / max(|k|, eps) with the hardware reciprocal square root (1 ulp)
                 const float inv = fminf(__builtin_amdgcn_rsqf(ss), inv_eps);
                 u32x4_t kh;
@@ -316,8 +321,15 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             const int lc = f / 8, e8 = f % 8;
 #pragma unroll
             for (int wv = 0; wv < 4; ++wv) colsum += wsums[(wv * 8 + lc) * 16 + which * 8 + e8];
-            if (state)
-                state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f] = colsum;
+            if (state) {
+                if constexpr (PAIR) {
+                    using L32 = StateLayout<32>;
+                    state[static_cast<size_t>(2 * unit + (f >> 5)) * L32::SIZE +
+                          (which ? L32::VSUM : L32::KSUM) + (f & 31)] = colsum;
+                } else {
+                    state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f] = colsum;
+                }
+            }
         }
         own_quadrant([&](auto mt_c, auto) {
             constexpr int MT = decltype(mt_c)::value;
@@ -345,16 +357,26 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             // (w + w^2) + (w^1 + w^3)
             acc[MT][NT] = add_quadrant(xch + (wave ^ 1) * QUAD + lane, acc[MT][NT]);
             uint32_t* sf = reinterpret_cast<uint32_t*>(lds + kFusedSfragOff);
-            float* st = state ? state + static_cast<size_t>(unit) * L::SIZE + L::S : nullptr;
+            // PAIR: the quadrants off the diagonal mix two heads; their table entries are zero
+            constexpr bool kZero = PAIR && MT != NT;
+            float* st = nullptr;
+            if (state) {
+                if constexpr (PAIR) st = state + static_cast<size_t>(2 * unit + MT) * StateLayout<32>::SIZE;
+                else st = state + static_cast<size_t>(unit) * L::SIZE + L::S;
+            }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int i = 32 * MT + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
                 const int j = 32 * NT + (lane % 32);
-                if (st) st[i * D + j] = acc[MT][NT][r];
+                if constexpr (PAIR) {
+                    if (st && !kZero) st[(i & 31) * 32 + (j & 31)] = acc[MT][NT][r];
+                } else {
+                    if (st) st[i * D + j] = acc[MT][NT][r];
+                }
                 if ((r & 1) == 0) {
                     const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
                                   ((i & 7) >> 1);
-                    sf[t] = X::pack(acc[MT][NT][r] * tscale, acc[MT][NT][r + 1] * tscale);
+                    sf[t] = kZero ? 0u : X::pack(acc[MT][NT][r] * tscale, acc[MT][NT][r + 1] * tscale);
                 }
             }
         });
@@ -449,41 +471,57 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
                 u32x4_t a[2];
                 a[0] = qok ? qraw[c][0] : zero;
                 a[1] = qok ? qraw[c][1] : zero;
-                // |q_t|^2 on the matrix cores: the diagonal of Q Q^T
-                f32x4_t gram = {0.f, 0.f, 0.f, 0.f};
+                // |q_t|^2 on the matrix cores: the diagonal of Q Q^T.  PAIR: k-step 0 holds the
+                // first head's features and k-step 1 the second's; each gets its own products.
+                constexpr int NH = PAIR ? 2 : 1;
+                const f32x4_t z4 = {0.f, 0.f, 0.f, 0.f};
+                f32x4_t gram[NH], dk[NH], ac[4];
+                if constexpr (PAIR) {
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    gram = X::mfma16(a[ks], a[ks], gram);
-                f32x4_t ac[4], dk = {0.f, 0.f, 0.f, 0.f};
+                    for (int hh = 0; hh < 2; ++hh) {
+                        gram[hh] = X::mfma16(a[hh], a[hh], z4);
+                        dk[hh] = X::mfma16(a[hh], kf[hh], z4);
+                    }
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
-                    dk = X::mfma16(a[ks], kf[ks], dk);
+                    for (int nt = 0; nt < 4; ++nt) ac[nt] = X::mfma16(a[nt >> 1], sf[nt][nt >> 1], z4);
+                } else {
+                    gram[0] = dk[0] = z4;
 #pragma unroll
-                for (int nt = 0; nt < 4; ++nt) {
+                    for (int ks = 0; ks < 2; ++ks) {
+                        gram[0] = X::mfma16(a[ks], a[ks], gram[0]);
+                        dk[0] = X::mfma16(a[ks], kf[ks], dk[0]);
+                    }
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) ac[nt][r] = 0.f;
+                    for (int nt = 0; nt < 4; ++nt) {
+                        ac[nt] = z4;
 #pragma unroll
-                    for (int ks = 0; ks < 2; ++ks)
-                        ac[nt] = X::mfma16(a[ks], sf[nt][ks], ac[nt]);
+                        for (int ks = 0; ks < 2; ++ks) ac[nt] = X::mfma16(a[ks], sf[nt][ks], ac[nt]);
+                    }
                 }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
-                    const float ssr = __int_as_float(
-                        __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[r])));
-                    float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
-                    if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
-                    float alpha, beta;
-                    if (p.norm_none) {
-                        alpha = inv;
-                        beta = 1.0f;
-                    } else {
-                        beta = __builtin_amdgcn_rcpf(half_n + inv * dk[r]);
-                        alpha = inv * beta;
+                    float alpha[NH], beta[NH];
+#pragma unroll
+                    for (int hh = 0; hh < NH; ++hh) {
+                        // entry (m, m) of the Gram tile, m = 4 g + r, sits in lane 16 (m / 4) + m, register m % 4
+                        const float ssr = __int_as_float(
+                            __builtin_amdgcn_ds_bpermute((20 * g + r) * 4, __float_as_int(gram[hh][r])));
+                        float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
+                        if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
+                        if (p.norm_none) {
+                            alpha[hh] = inv;
+                            beta[hh] = 1.0f;
+                        } else {
+                            beta[hh] = __builtin_amdgcn_rcpf(half_n + inv * dk[hh][r]);
+                            alpha[hh] = inv * beta[hh];
+                        }
                     }
                     float* row = lin + (16 * wave + 4 * g + r) * LP + tl;
 #pragma unroll
-                    for (int nt = 0; nt < 4; ++nt) row[16 * nt] = fmaf(alpha, ac[nt][r], beta * vh[nt]);
+                    for (int nt = 0; nt < 4; ++nt) {
+                        const int hh = PAIR ? (nt >> 1) : 0;
+                        row[16 * nt] = fmaf(alpha[hh], ac[nt][r], beta[hh] * vh[nt]);
+                    }
                 }
             }
             __syncthreads();
@@ -570,7 +608,8 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
             for (int h2 = 0; h2 < 2; ++h2) {
                 const int t = 64 * c + tloc0 + 32 * h2;
                 if (live[h2])
-                    store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16),
+                    store16_stream(ob + (static_cast<uint32_t>(t) * out_tok + oct * 16 +
+                                         (oct >= 4 ? p.out_skew : 0u)),
                                    X::pack(o[h2][0], o[h2][1]), X::pack(o[h2][2], o[h2][3]),
                                    X::pack(o[h2][4], o[h2][5]), X::pack(o[h2][6], o[h2][7]));
             }

@@ -46,6 +46,16 @@ SMALL = [
 ]
 ONE_KERNEL = [SMALL[3], SMALL[6], SMALL[8]] + SMALL[14:]
 
+# 16-bit heads of 32 channels: pass 2 runs two neighbouring heads as one 64-channel unit on the
+# matrix cores (even head counts); dense and fused layouts, several strips, ragged edges
+HEAD_PAIRS = [
+    Workload("hp_bf16_b2_h4_d32_20x24_k3", "bf16", 2, 4, 32, 20, 24, 3),
+    Workload("hp_f16_b1_h6_d32_33x17_k9", "f16", 1, 6, 32, 33, 17, 9),
+    Workload("hp_bf16_b3_h2_d32_14x14_k5", "bf16", 3, 2, 32, 14, 14, 5),
+    Workload("hp_bf16_b1_h8_d32_9x40_k7_outl", "bf16", 1, 8, 32, 9, 40, 7, 0.05, 8.0),
+    Workload("hp_bf16_b32_h8_d32_7x7_k3", "bf16", 32, 8, 32, 7, 7, 3),
+]
+
 # head widths 16 and 128 and fp16 I/O (vector-ALU kernels)
 WIDE = [
     Workload("w_f32_d16_14x14_k3", "f32", 2, 3, 16, 14, 14, 3),
@@ -286,7 +296,7 @@ def test_forced_generic_bf16_matches_oracle(oracle, monkeypatch):
     assert rel_err(got, want) <= TOL[wl.dtype]
 
 
-@pytest.mark.parametrize("wl", ONE_KERNEL, ids=lambda w: w.name)
+@pytest.mark.parametrize("wl", ONE_KERNEL + [HEAD_PAIRS[2], HEAD_PAIRS[4]], ids=lambda w: w.name)
 def test_two_pass_path_at_small_n(oracle, monkeypatch, wl):
     """Shapes that forward() would run in one kernel, kept on the reduce + apply kernels."""
     monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
@@ -502,17 +512,6 @@ def test_dwconv_on_token_major_features(oracle, dtype, C_, ks):
     assert rel_err(got, want) <= TOL[dtype]
 
 
-# 16-bit heads of 32 channels: pass 2 runs two neighbouring heads as one 64-channel unit on the
-# matrix cores (even head counts); dense and fused layouts, several strips, ragged edges
-HEAD_PAIRS = [
-    Workload("hp_bf16_b2_h4_d32_20x24_k3", "bf16", 2, 4, 32, 20, 24, 3),
-    Workload("hp_f16_b1_h6_d32_33x17_k9", "f16", 1, 6, 32, 33, 17, 9),
-    Workload("hp_bf16_b3_h2_d32_14x14_k5", "bf16", 3, 2, 32, 14, 14, 5),
-    Workload("hp_bf16_b1_h8_d32_9x40_k7_outl", "bf16", 1, 8, 32, 9, 40, 7, 0.05, 8.0),
-    Workload("hp_bf16_b32_h8_d32_7x7_k3", "bf16", 32, 8, 32, 7, 7, 3),
-]
-
-
 @pytest.mark.parametrize("wl", HEAD_PAIRS, ids=lambda w: w.name)
 @pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
 def test_pairs_of_narrow_heads(oracle, wl, norm):
@@ -535,11 +534,18 @@ def test_pairs_of_narrow_heads(oracle, wl, norm):
 
 
 def test_pairs_of_narrow_heads_take_the_matrix_core_path(monkeypatch):
-    """One split per unit: the vector-ALU path needs two launches, the pair path three (its
-    operand tables come from a combine launch of their own); an odd head count cannot pair."""
-    even = b.CastlingAttn.for_workload(HEAD_PAIRS[4])
-    odd = b.CastlingAttn.for_workload(Workload("hp_odd", "bf16", 32, 9, 32, 7, 7, 3))
-    n_even, n_odd, s_even = even.num_launches(), odd.num_launches(), even.num_splits()
-    even.destroy()
-    odd.destroy()
-    assert s_even == 1 and n_even == 3 and n_odd == 2
+    """Launch counts tell the paths apart.  Small units: one kernel for pairs, two launches on the
+    vector-ALU path an odd head count is left with.  Large units with one split each: the
+    vector-ALU path needs two launches, the pair path three (its operand tables come from a
+    combine launch of their own)."""
+    def launches(wl, **kw):
+        h = b.CastlingAttn.for_workload(wl, **kw)
+        n, s = h.num_launches(), h.num_splits()
+        h.destroy()
+        return n, s
+    assert launches(HEAD_PAIRS[4]) == (1, 1)
+    assert launches(Workload("hp_odd", "bf16", 32, 9, 32, 7, 7, 3)) == (2, 1)
+    assert launches(Workload("hp_big", "bf16", 32, 8, 32, 20, 20, 3)) == (3, 1)
+    assert launches(Workload("hp_big_odd", "bf16", 32, 9, 32, 20, 20, 3)) == (2, 1)
+    monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
+    assert launches(HEAD_PAIRS[4]) == (3, 1)
