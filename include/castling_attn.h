@@ -73,8 +73,8 @@ typedef enum {
 enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_ALL = 3 };
 
 /* desc.flags.  KEEP_STATE: castling_attn_forward always leaves the fp32 state in the workspace
- * for castling_attn_get_state.  Without it a forward that keeps the state on chip (small N)
- * does not spend memory writes on a copy nobody reads. */
+ * for castling_attn_get_state.  Without it a forward of a small problem does not spend memory
+ * writes, or a launch, on a copy nobody reads.  castling_attn_reduce always leaves the state. */
 enum { CASTLING_FLAG_KEEP_STATE = 1 };
 
 typedef struct {
@@ -170,7 +170,8 @@ size_t castling_attn_workspace_bytes(castling_attn_t h);
  * [B*heads][d+1][d+1] = [K_hat | 1]^T [V | 1] (row i < d: K_hat^T V row i then
  * ksum_i; row d: vsum then N).  Synchronises `stream`.  `bytes` must be exactly
  * B*heads*(d+1)*(d+1)*4.  CASTLING_ERR_INVALID_ARG if the workspace holds no state: nothing
- * has run yet, or the last call was a forward that kept the state on chip and the handle
+ * has run yet, or the last call was a forward that never wrote the state to memory (small
+ * problems keep it on chip, or sum its partial states inside the second pass) and the handle
  * was created without CASTLING_FLAG_KEEP_STATE. */
 int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream);
 

@@ -15,6 +15,10 @@ struct ApplyParams {
     int do_dwconv;
     float eps;
     TensorStrides in, out;  // of q and v; of out
+    // 1: `state` holds one final state per unit.  > 1: it holds that many partial states per
+    // unit ([unit][split][StateLayout::SIZE], as pass 1 leaves them); the block sums them in
+    // index order while it loads them (small problems: saves the combine launch)
+    int n_partials;
 };
 
 constexpr int kApplyTH = 4;   // tile rows
@@ -71,13 +75,47 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
 #pragma unroll
         for (int j = 0; j < RJ; ++j) res[t][j] = 0.f;
 
+    // The halo tile of V and the filters are needed after the linear branch only.  Where a thread
+    // holds few pieces of them, their loads go out now and overlap it; on small problems (a
+    // handful of blocks) the kernel is a chain of memory latencies otherwise.
+    constexpr int HALO_PIECES = (HH * HW * LPR + 255) / 256;
+    constexpr int W_PIECES = (D * KS * KS + 255) / 256;
+    constexpr bool kPrefetch = HALO_PIECES <= 8 && W_PIECES <= 4;
+    uint4 halo_pre[kPrefetch ? HALO_PIECES : 1];
+    T w_pre[kPrefetch ? W_PIECES : 1];
+    auto halo_piece = [&](int idx) {
+        const int tok = idx / LPR, part = idx % LPR;
+        const int y = ty0 - RAD + tok / HW, x = tx0 - RAD + tok % HW;
+        uint4 val = make_uint4(0u, 0u, 0u, 0u);
+        if (idx < HH * HW * LPR && y >= 0 && y < p.grid_h && x >= 0 && x < p.grid_w)
+            val = *reinterpret_cast<const uint4*>(
+                v + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + part * VEC);
+        return val;
+    };
+    if constexpr (kPrefetch) {
+        if (p.do_dwconv) {
+#pragma unroll
+            for (int i = 0; i < HALO_PIECES; ++i) halo_pre[i] = halo_piece(tid + 256 * i);
+            const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
+#pragma unroll
+            for (int i = 0; i < W_PIECES; ++i) {
+                const int idx = tid + 256 * i;
+                w_pre[i] = idx < D * KS * KS ? wh[idx] : T{};
+            }
+        }
+    }
+
     // ---------------------------------------------------------------- linear branch
     if (p.do_linear) {
         float* st = reinterpret_cast<float*>(lds_raw);  // state, pre-scaled
         float* qt = st + L::SIZE;                       // q_hat transposed: [D][kQtStride]
-        const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
-        for (int i = tid; i < L::SIZE; i += 256)
-            st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
+        const float* gs = state + static_cast<size_t>(unit) * p.n_partials * L::SIZE;
+        if (p.n_partials == 1) {
+            for (int i = tid; i < L::SIZE; i += 256) st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
+        } else {
+            for (int i = tid; i < L::SIZE; i += 256)
+                st[i] = sum_partials(gs + i, p.n_partials, L::SIZE) * (i < L::VSUM ? kInvPi : 0.5f);
+        }
 
         constexpr int ROWS = 256 / LPR;  // token rows one pass of the block loads
         constexpr int PASSES = (kApplyTokens + ROWS - 1) / ROWS;
@@ -135,19 +173,29 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
         constexpr size_t halo_bytes = ((sizeof(T) * HH * HW * D + 15) / 16) * 16;
         float* wt = reinterpret_cast<float*>(lds_raw + halo_bytes);  // [KS*KS][D]
 
-        for (int idx = tid; idx < HH * HW * LPR; idx += 256) {
-            const int tok = idx / LPR, part = idx % LPR;
-            const int y = ty0 - RAD + tok / HW, x = tx0 - RAD + tok % HW;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (y >= 0 && y < p.grid_h && x >= 0 && x < p.grid_w)
-                val = *reinterpret_cast<const uint4*>(
-                    v + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + part * VEC);
-            *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tok) * D + part * VEC) = val;
-        }
-        const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
-        for (int idx = tid; idx < D * KS * KS; idx += 256) {
-            const int c = idx / (KS * KS), tap = idx % (KS * KS);
-            wt[tap * D + c] = IO<T>::to_f32(wh[idx]);
+        if constexpr (kPrefetch) {
+#pragma unroll
+            for (int i = 0; i < HALO_PIECES; ++i) {
+                const int idx = tid + 256 * i;
+                if (idx < HH * HW * LPR)
+                    *reinterpret_cast<uint4*>(vh + static_cast<size_t>(idx / LPR) * D + (idx % LPR) * VEC) =
+                        halo_pre[i];
+            }
+#pragma unroll
+            for (int i = 0; i < W_PIECES; ++i) {
+                const int idx = tid + 256 * i;
+                if (idx < D * KS * KS)
+                    wt[(idx % (KS * KS)) * D + idx / (KS * KS)] = IO<T>::to_f32(w_pre[i]);
+            }
+        } else {
+            for (int idx = tid; idx < HH * HW * LPR; idx += 256)
+                *reinterpret_cast<uint4*>(vh + static_cast<size_t>(idx / LPR) * D + (idx % LPR) * VEC) =
+                    halo_piece(idx);
+            const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
+            for (int idx = tid; idx < D * KS * KS; idx += 256) {
+                const int c = idx / (KS * KS), tap = idx % (KS * KS);
+                wt[tap * D + c] = IO<T>::to_f32(wh[idx]);
+            }
         }
         __syncthreads();
 

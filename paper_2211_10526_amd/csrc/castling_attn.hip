@@ -88,6 +88,8 @@ struct castling_attn {
     uint32_t in_skew, out_skew;           // pair: see ApplyMfmaParams
     bool fused;         // forward() runs the one-kernel path (small N)
     bool state_valid;   // the workspace holds the state of the last reduce
+    bool sum_in_apply;  // forward(): the vector-ALU apply sums the partial states itself (no combine)
+    bool partials_pending;  // set by a reduce that left the combine to the apply launch
     int num_cus;        // compute units of the device
     size_t apply_lds;   // dynamic LDS of the apply kernel
     // workspace (one allocation)
@@ -152,10 +154,13 @@ void launch_combine(castling_attn* h, hipStream_t s)
 }
 
 // w != nullptr: also prepare the DWConv weight operands of the MFMA apply kernel
-int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hipStream_t s)
+// defer_combine: leave the partial states as they are for an apply launch that sums them
+int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hipStream_t s,
+              bool defer_combine = false)
 {
     const int d = h->desc.d;
     h->state_valid = true;
+    h->partials_pending = false;
     // with one split per unit the reduce kernel's result is final: it writes the state and
     // the apply kernel's operand tables itself, and no combine is launched
     const bool direct = h->mfma_apply && !h->pair && h->n_split == 1;
@@ -180,6 +185,11 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
     // vector-ALU apply with one split per unit: the partial layout is the state layout and the
     // handle points `partial` at `state`, so the reduce kernel's result is final as written
     if (!h->mfma_apply && h->n_split == 1) return CASTLING_OK;
+    if (defer_combine) {
+        h->state_valid = false;
+        h->partials_pending = true;
+        return CASTLING_OK;
+    }
     if (h->pair) {
         const int gx = (kCombineFragThreads + 255) / 256;
         const int ks = h->desc.dw_kernel;
@@ -247,11 +257,12 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     p.eps = d.eps;
     p.in = h->in_st;
     p.out = h->out_st;
+    p.n_partials = h->partials_pending ? h->n_split : 1;
     const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
     hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, h->units),
                        dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
-                       static_cast<const T*>(w), static_cast<const T*>(bias), h->state,
-                       static_cast<T*>(out), d.heads, p);
+                       static_cast<const T*>(w), static_cast<const T*>(bias),
+                       h->partials_pending ? h->partial : h->state, static_cast<T*>(out), d.heads, p);
     return hipGetLastError();
 }
 
@@ -699,6 +710,16 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     p += vhalf_bytes;
     h->wfrag = reinterpret_cast<bf16_t*>(p);
     if (!h->mfma_apply && h->n_split == 1) h->partial = h->state;  // see do_reduce
+    // Small vector-ALU problems: every apply block sums the few partial states itself instead of
+    // waiting for a combine launch (cfg1: three launches become two).  Not when the caller wants
+    // the state kept, and not where many blocks would each re-read many partials.
+    {
+        const long long tiles = static_cast<long long>((desc->grid_w + kApplyTW - 1) / kApplyTW) *
+                                ((desc->grid_h + kApplyTH - 1) / kApplyTH);
+        h->sum_in_apply = !h->mfma_apply && h->n_split > 1 && h->n_split <= 4 && tiles <= 16 &&
+                          !(desc->flags & CASTLING_FLAG_KEEP_STATE);
+    }
+    h->partials_pending = false;
     *out_handle = h;
     return CASTLING_OK;
 }
@@ -722,7 +743,7 @@ int castling_attn_num_launches(castling_attn_t h)
     const int extra = h->desc.extra_tokens > 0 ? 1 : 0;  // the tokens off the grid: one more launch
     if (h->fused) return 1;
     if (!lin) return 1 + extra;
-    return ((h->n_split == 1 && !h->pair) ? 2 : 3) + extra;
+    return ((h->n_split == 1 && !h->pair) || h->sum_in_apply ? 2 : 3) + extra;
 }
 
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
@@ -840,7 +861,8 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
         }
         // the combine launch also prepares the weight operands of the MFMA apply kernel
         const bool fuse_w = h->mfma_apply && (d.branches & CASTLING_BRANCH_DWCONV);
-        st = do_reduce(h, k, v, fuse_w ? dw_weight : nullptr, static_cast<hipStream_t>(stream));
+        st = do_reduce(h, k, v, fuse_w ? dw_weight : nullptr, static_cast<hipStream_t>(stream),
+                       h->sum_in_apply);
         if (st != CASTLING_OK) return st;
         if (fuse_w) {
             HIP_TRY(do_apply(h, true, q, v, nullptr, dw_bias, out, static_cast<hipStream_t>(stream)));

@@ -34,10 +34,15 @@ struct IO;
 template <>
 struct IO<float> {
     static constexpr int VEC = 4;
+    // 16 raw bytes -> VEC values in fp32
+    __device__ static __forceinline__ void widen16(const uint4& r, float (&x)[4])
+    {
+        x[0] = __uint_as_float(r.x); x[1] = __uint_as_float(r.y);
+        x[2] = __uint_as_float(r.z); x[3] = __uint_as_float(r.w);
+    }
     __device__ static __forceinline__ void load16(const float* p, float (&x)[4])
     {
-        const float4 r = *reinterpret_cast<const float4*>(p);
-        x[0] = r.x; x[1] = r.y; x[2] = r.z; x[3] = r.w;
+        widen16(*reinterpret_cast<const uint4*>(p), x);
     }
     __device__ static __forceinline__ float to_f32(float a) { return a; }
     __device__ static __forceinline__ float from_f32(float a) { return a; }
@@ -46,15 +51,18 @@ struct IO<float> {
 template <>
 struct IO<bf16_t> {
     static constexpr int VEC = 8;
-    __device__ static __forceinline__ void load16(const bf16_t* p, float (&x)[8])
+    __device__ static __forceinline__ void widen16(const uint4& r, float (&x)[8])
     {
-        const uint4 r = *reinterpret_cast<const uint4*>(p);
         const uint32_t w[4] = {r.x, r.y, r.z, r.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             x[2 * i] = __uint_as_float(w[i] << 16);
             x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
         }
+    }
+    __device__ static __forceinline__ void load16(const bf16_t* p, float (&x)[8])
+    {
+        widen16(*reinterpret_cast<const uint4*>(p), x);
     }
     __device__ static __forceinline__ float to_f32(bf16_t a) { return bf16_to_f32(a); }
     __device__ static __forceinline__ bf16_t from_f32(float a) { return f32_to_bf16(a); }
@@ -65,13 +73,16 @@ typedef _Float16 f16_t;
 template <>
 struct IO<f16_t> {
     static constexpr int VEC = 8;
-    __device__ static __forceinline__ void load16(const f16_t* p, float (&x)[8])
+    __device__ static __forceinline__ void widen16(const uint4& r, float (&x)[8])
     {
         typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
-        const uint4 r = *reinterpret_cast<const uint4*>(p);
         const f16x8_t h = __builtin_bit_cast(f16x8_t, r);
 #pragma unroll
         for (int i = 0; i < 8; ++i) x[i] = static_cast<float>(h[i]);
+    }
+    __device__ static __forceinline__ void load16(const f16_t* p, float (&x)[8])
+    {
+        widen16(*reinterpret_cast<const uint4*>(p), x);
     }
     __device__ static __forceinline__ float to_f32(f16_t a) { return static_cast<float>(a); }
     // round to nearest even; values beyond the fp16 range become infinity

@@ -8,6 +8,15 @@
 
 namespace castling {
 
+// This thread's 16 raw bytes of token row n (zeros for n >= n_end).
+template <typename T>
+__device__ __forceinline__ uint4 load_row_piece(const T* base, int n, int n_end, long long tok_stride,
+                                                int lcol)
+{
+    return n < n_end ? *reinterpret_cast<const uint4*>(base + n * tok_stride + lcol)
+                     : make_uint4(0u, 0u, 0u, 0u);
+}
+
 // grid = (n_split, units), block = 256.
 // Block (s, u) reduces tokens [s*chunk, min(N, (s+1)*chunk)) of unit u and writes
 // partial[u][s][StateLayout<D>::SIZE].
@@ -48,16 +57,14 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
         for (int b = 0; b < R; ++b) acc[a][b] = 0.f;
     }
 
+    // the rows of the next tile are loaded while this one is multiplied: with few tokens per
+    // block the loop is a chain of memory latencies otherwise
+    uint4 kraw = load_row_piece(kb, n_begin + lrow, n_end, st.n, lcol);
+    uint4 vraw = load_row_piece(vb, n_begin + lrow, n_end, st.n, lcol);
     for (int n0 = n_begin; n0 < n_end; n0 += TILE) {
-        const int n = n0 + lrow;
         float kx[VEC], vx[VEC];
-        if (n < n_end) {
-            IO<T>::load16(kb + n * st.n + lcol, kx);
-            IO<T>::load16(vb + n * st.n + lcol, vx);
-        } else {
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) kx[e] = vx[e] = 0.f;
-        }
+        IO<T>::widen16(kraw, kx);
+        IO<T>::widen16(vraw, vx);
         float ss = 0.f;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) ss += kx[e] * kx[e];
@@ -70,6 +77,8 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
             kh[lrow][lcol + e] = kx[e] * inv;
             vv[lrow][lcol + e] = vx[e];
         }
+        kraw = load_row_piece(kb, n0 + TILE + lrow, n_end, st.n, lcol);  // (zeros past the end)
+        vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, st.n, lcol);
         __syncthreads();
 
 #pragma unroll 4
