@@ -118,8 +118,10 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
  * The state stays in the handle's workspace. */
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream);
 
-/* Second half: normalise Q per token, apply the state held in the handle
- * (Eq. 3 with the linear terms of Eq. 8), add DWConv(V) (Eq. 9), store out.
+/* Second half: normalise Q per token, apply the state the last castling_attn_reduce left in
+ * the handle (Eq. 3 with the linear terms of Eq. 8), add DWConv(V) (Eq. 9), store out.
+ * CASTLING_ERR_INVALID_ARG if the linear branch is on and the handle holds nothing to apply:
+ * no reduce yet, or a castling_attn_forward since then that kept its state on chip.
  * dw_weight may be NULL after castling_attn_prepare_weights: the filters registered
  * there are used. */
 int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,

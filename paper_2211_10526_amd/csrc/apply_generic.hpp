@@ -37,17 +37,18 @@ constexpr size_t apply_generic_lds_bytes()
     return phase_a > phase_b ? phase_a : phase_b;
 }
 
-// grid = (tiles_x * tiles_y, units), block = 256.  A block owns a 4 x 16 tile of
-// the token grid of one unit; thread (tt, tj) = (tid / 16, tid % 16) owns tokens
-// (row tt/4, columns 4*(tt%4)..+3) and channels tj*D/16..+D/16-1.
+// The 256 threads of a block compute one 4 x 16 tile (index `tile`, row-major over the tiles of
+// the grid) of unit `unit`; thread (tt, tj) = (tid / 16, tid % 16) owns tokens
+// (row tt/4, columns 4*(tt%4)..+3) and channels tj*D/16..+D/16-1.  `state`: the unit's state
+// record(s), see ApplyParams::n_partials (global memory or LDS).  lds_raw: the block's dynamic
+// LDS of apply_generic_lds_bytes<T, D, KS>() bytes.
 template <typename T, int D, int KS>
-__global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict__ q,
-                                                             const T* __restrict__ v,
-                                                             const T* __restrict__ w,
-                                                             const T* __restrict__ bias,
-                                                             const float* __restrict__ state,
-                                                             T* __restrict__ out, int heads,
-                                                             ApplyParams p)
+__device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, const T* __restrict__ v,
+                                                   const T* __restrict__ w,
+                                                   const T* __restrict__ bias, const float* state,
+                                                   T* __restrict__ out, int heads,
+                                                   const ApplyParams& p, int unit, int tile,
+                                                   unsigned char* lds_raw)
 {
     constexpr int VEC = IO<T>::VEC;
     constexpr int LPR = D / VEC;
@@ -57,13 +58,10 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
     constexpr int HW = kApplyTW + KS - 1;  // halo tile columns
     using L = StateLayout<D>;
 
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-
     const int tid = threadIdx.x;
-    const int unit = blockIdx.y;
     const int head = unit % heads;
-    const int ty0 = (blockIdx.x / p.tiles_x) * kApplyTH;
-    const int tx0 = (blockIdx.x % p.tiles_x) * kApplyTW;
+    const int ty0 = (tile / p.tiles_x) * kApplyTH;
+    const int tx0 = (tile % p.tiles_x) * kApplyTW;
     const int tt = tid / 16, tj = tid % 16;
     const int my_row = tt / 4, my_col0 = (tt % 4) * 4;
     const long long in_off = unit_offset(unit, heads, p.in);
@@ -109,7 +107,7 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
     if (p.do_linear) {
         float* st = reinterpret_cast<float*>(lds_raw);  // state, pre-scaled
         float* qt = st + L::SIZE;                       // q_hat transposed: [D][kQtStride]
-        const float* gs = state + static_cast<size_t>(unit) * p.n_partials * L::SIZE;
+        const float* gs = state;
         if (p.n_partials == 1) {
             for (int i = tid; i < L::SIZE; i += 256) st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
         } else {
@@ -262,6 +260,23 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
             }
         }
     }
+}
+
+// grid = (tiles_x * tiles_y, units), block = 256, dynamic LDS = apply_generic_lds_bytes.
+template <typename T, int D, int KS>
+__global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict__ q,
+                                                             const T* __restrict__ v,
+                                                             const T* __restrict__ w,
+                                                             const T* __restrict__ bias,
+                                                             const float* __restrict__ state,
+                                                             T* __restrict__ out, int heads,
+                                                             ApplyParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    const int unit = blockIdx.y;
+    apply_generic_tile<T, D, KS>(q, v, w, bias,
+                                 state + static_cast<size_t>(unit) * p.n_partials * StateLayout<D>::SIZE,
+                                 out, heads, p, unit, blockIdx.x, lds_raw);
 }
 
 // grid = (ceil(rows * D / 8 / 256), units), block = 256: zero the first `rows` token rows of every

@@ -88,6 +88,7 @@ struct castling_attn {
     uint32_t in_skew, out_skew;           // pair: see ApplyMfmaParams
     bool fused;         // forward() runs the one-kernel path (small N)
     bool state_valid;   // the workspace holds the state of the last reduce
+    bool apply_ready;   // the workspace holds what apply() needs (state / tables / partials)
     bool sum_in_apply;  // forward(): the vector-ALU apply sums the partial states itself (no combine)
     bool partials_pending;  // set by a reduce that left the combine to the apply launch
     int num_cus;        // compute units of the device
@@ -160,6 +161,7 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
 {
     const int d = h->desc.d;
     h->state_valid = true;
+    h->apply_ready = true;
     h->partials_pending = false;
     // with one split per unit the reduce kernel's result is final: it writes the state and
     // the apply kernel's operand tables itself, and no combine is launched
@@ -458,6 +460,7 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
         go(fused_small_kernel<KS, LIN, DW, X, false>);
     }
     h->state_valid = (d.flags & CASTLING_FLAG_KEEP_STATE) != 0;
+    h->apply_ready = false;  // the operand tables stayed on chip
     return hipGetLastError();
 }
 
@@ -590,6 +593,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
     h->units = desc->B * desc->heads;
     h->state_valid = false;
+    h->apply_ready = false;
     {
         const castling_attn_desc_t& d = h->desc;
         const TensorStrides dense = {static_cast<long long>(d.heads) * d.N * d.d,
@@ -776,6 +780,8 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
     const void* w = registered ? h->prepared_w : dw_weight;
     int st = check_apply_args(h, q, v, w, out);
     if (st != CASTLING_OK) return st;
+    if ((h->desc.branches & CASTLING_BRANCH_LINEAR) && !h->apply_ready)
+        return CASTLING_ERR_INVALID_ARG;  // no reduce has left a state to apply
     // the matrix-core path already holds the registered filters in its operand table
     HIP_TRY(do_apply(h, true, q, v, (registered && h->mfma_apply) ? nullptr : w, dw_bias, out,
                      static_cast<hipStream_t>(stream)));

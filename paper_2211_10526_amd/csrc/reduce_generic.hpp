@@ -17,15 +17,18 @@ __device__ __forceinline__ uint4 load_row_piece(const T* base, int n, int n_end,
                      : make_uint4(0u, 0u, 0u, 0u);
 }
 
-// grid = (n_split, units), block = 256.
-// Block (s, u) reduces tokens [s*chunk, min(N, (s+1)*chunk)) of unit u and writes
-// partial[u][s][StateLayout<D>::SIZE].
+// Tokens per LDS tile of the reduce loop (256 threads, 16 bytes each).
 template <typename T, int D>
-__global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict__ k,
-                                                              const T* __restrict__ v,
-                                                              float* __restrict__ partial, int N,
-                                                              int n_split, int chunk, float eps,
-                                                              int heads, TensorStrides st)
+constexpr int reduce_generic_tile() { return 256 / (D / IO<T>::VEC); }
+
+// The 256 threads of a block reduce tokens [n_begin, n_end) of the unit whose K and V start
+// at kb, vb to one state record at `out` (StateLayout<D>; global memory or LDS).  kh, vv:
+// two LDS tiles of [reduce_generic_tile][D] floats.
+template <typename T, int D>
+__device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
+                                                      const T* __restrict__ vb, int n_begin,
+                                                      int n_end, long long tok_stride, float eps,
+                                                      float* out, float (*kh)[D], float (*vv)[D])
 {
     constexpr int VEC = IO<T>::VEC;  // elements per 16-byte load
     constexpr int LPR = D / VEC;     // lanes that share one token row
@@ -33,19 +36,9 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
     constexpr int R = D / 16;        // each thread owns an R x R block of S
     using L = StateLayout<D>;
 
-    __shared__ __attribute__((aligned(16))) float kh[TILE][D];
-    __shared__ __attribute__((aligned(16))) float vv[TILE][D];
-
     const int tid = threadIdx.x;
-    const int unit = blockIdx.y;
-    const int split = blockIdx.x;
-    const int n_begin = split * chunk;
-    const int n_end = min(N, n_begin + chunk);
     const int ti = tid / 16, tj = tid % 16;
     const int lrow = tid / LPR, lcol = (tid % LPR) * VEC;
-
-    const T* kb = k + unit_offset(unit, heads, st);
-    const T* vb = v + unit_offset(unit, heads, st);
 
     float acc[R][R];
     float ks[R], vs[R];
@@ -59,8 +52,8 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
 
     // the rows of the next tile are loaded while this one is multiplied: with few tokens per
     // block the loop is a chain of memory latencies otherwise
-    uint4 kraw = load_row_piece(kb, n_begin + lrow, n_end, st.n, lcol);
-    uint4 vraw = load_row_piece(vb, n_begin + lrow, n_end, st.n, lcol);
+    uint4 kraw = load_row_piece(kb, n_begin + lrow, n_end, tok_stride, lcol);
+    uint4 vraw = load_row_piece(vb, n_begin + lrow, n_end, tok_stride, lcol);
     for (int n0 = n_begin; n0 < n_end; n0 += TILE) {
         float kx[VEC], vx[VEC];
         IO<T>::widen16(kraw, kx);
@@ -77,8 +70,8 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
             kh[lrow][lcol + e] = kx[e] * inv;
             vv[lrow][lcol + e] = vx[e];
         }
-        kraw = load_row_piece(kb, n0 + TILE + lrow, n_end, st.n, lcol);  // (zeros past the end)
-        vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, st.n, lcol);
+        kraw = load_row_piece(kb, n0 + TILE + lrow, n_end, tok_stride, lcol);  // (zeros past the end)
+        vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, tok_stride, lcol);
         __syncthreads();
 
 #pragma unroll 4
@@ -99,7 +92,6 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
         }
     }
 
-    float* out = partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE;
 #pragma unroll
     for (int x = 0; x < R; ++x)
 #pragma unroll
@@ -110,6 +102,28 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
     if (ti == 0)
 #pragma unroll
         for (int x = 0; x < R; ++x) out[L::VSUM + tj * R + x] = vs[x];
+}
+
+// grid = (n_split, units), block = 256.
+// Block (s, u) reduces tokens [s*chunk, min(N, (s+1)*chunk)) of unit u and writes
+// partial[u][s][StateLayout<D>::SIZE].
+template <typename T, int D>
+__global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict__ k,
+                                                              const T* __restrict__ v,
+                                                              float* __restrict__ partial, int N,
+                                                              int n_split, int chunk, float eps,
+                                                              int heads, TensorStrides st)
+{
+    constexpr int TILE = reduce_generic_tile<T, D>();
+    using L = StateLayout<D>;
+    __shared__ __attribute__((aligned(16))) float kh[TILE][D];
+    __shared__ __attribute__((aligned(16))) float vv[TILE][D];
+    const int unit = blockIdx.y, split = blockIdx.x;
+    const int n_begin = split * chunk;
+    const long long off = unit_offset(unit, heads, st);
+    reduce_generic_tokens<T, D>(k + off, v + off, n_begin, min(N, n_begin + chunk), st.n, eps,
+                                partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE,
+                                kh, vv);
 }
 
 // grid = (ceil(SIZE/256), units), block = 256.  state[u][i] = sum over splits in

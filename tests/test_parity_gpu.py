@@ -358,7 +358,8 @@ def test_apply_with_registered_weights(wl):
     t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
     attn = b.CastlingAttn.for_workload(wl)
     o1, o2 = torch.empty_like(t["q"]), torch.empty_like(t["q"])
-    attn.forward(t["q"], t["k"], t["v"], t["w"], None, o1)
+    attn.reduce(t["k"], t["v"])
+    attn.apply(t["q"], t["v"], t["w"], None, o1)
     with pytest.raises(b.CastlingError) as e:          # nothing registered yet
         attn.apply(t["q"], t["v"], None, None, o2)
     assert e.value.status == b.ERR_INVALID_ARG
@@ -368,6 +369,29 @@ def test_apply_with_registered_weights(wl):
     attn.destroy()
     view = torch.int16 if wl.dtype == "bf16" else torch.int32
     assert torch.equal(o1.view(view), o2.view(view))
+
+
+@pytest.mark.parametrize("wl", [SMALL[0], SMALL[15], SMALL[10]], ids=lambda w: w.name)
+def test_apply_needs_a_reduce(wl):
+    """apply() uses what reduce() left in the handle; before any reduce, and after a forward that
+    kept its state on chip, there is nothing to apply: an error, not stale data."""
+    x = inputs.make_inputs(wl, seed=19)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    attn = b.CastlingAttn.for_workload(wl)
+    o = torch.empty_like(t["q"])
+    with pytest.raises(b.CastlingError) as e:
+        attn.apply(t["q"], t["v"], t["w"], None, o)
+    assert e.value.status == b.ERR_INVALID_ARG
+    attn.forward(t["q"], t["k"], t["v"], t["w"], None, o)
+    if attn.num_launches() == 1:
+        with pytest.raises(b.CastlingError) as e:
+            attn.apply(t["q"], t["v"], t["w"], None, o)
+        assert e.value.status == b.ERR_INVALID_ARG
+    attn.reduce(t["k"], t["v"])
+    attn.apply(t["q"], t["v"], t["w"], None, o)
+    torch.cuda.synchronize()
+    attn.destroy()
 
 
 def test_runs_on_a_side_stream(oracle):
