@@ -21,23 +21,39 @@ __device__ __forceinline__ uint4 load_row_piece(const T* base, int n, int n_end,
 template <typename T, int D>
 constexpr int reduce_generic_tile() { return 256 / (D / IO<T>::VEC); }
 
+// Register tiling of S = K_hat^T V: a thread owns an R x R block, (D / R)^2 threads cover S, and
+// the block's 256 threads form G such groups that take the tokens of a tile in turn (a 4 x 4
+// block needs one 16-byte LDS read per operand and token; with the whole block on one copy of
+// S, narrow heads would read LDS once per multiply).  Their sums meet in LDS in group order.
+template <int D>
+struct ReduceTiling {
+    static constexpr int R = D / 16 > 4 ? D / 16 : 4;
+    static constexpr int SIDE = D / R;
+    static constexpr int GROUP = SIDE * SIDE;  // threads per copy of S
+    static constexpr int G = 256 / GROUP;
+    static constexpr int RED_FLOATS = G > 1 ? G * StateLayout<D>::SIZE : 1;
+    static_assert(GROUP * G == 256, "head width");
+};
+
 // The 256 threads of a block reduce tokens [n_begin, n_end) of the unit whose K and V start
 // at kb, vb to one state record at `out` (StateLayout<D>; global memory or LDS).  kh, vv:
-// two LDS tiles of [reduce_generic_tile][D] floats.
+// two LDS tiles of [reduce_generic_tile][D] floats; red: ReduceTiling<D>::RED_FLOATS floats.
 template <typename T, int D>
 __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
                                                       const T* __restrict__ vb, int n_begin,
                                                       int n_end, long long tok_stride, float eps,
-                                                      float* out, float (*kh)[D], float (*vv)[D])
+                                                      float* out, float (*kh)[D], float (*vv)[D],
+                                                      float* red)
 {
     constexpr int VEC = IO<T>::VEC;  // elements per 16-byte load
     constexpr int LPR = D / VEC;     // lanes that share one token row
     constexpr int TILE = 256 / LPR;  // tokens staged per iteration
-    constexpr int R = D / 16;        // each thread owns an R x R block of S
+    using RT = ReduceTiling<D>;
+    constexpr int R = RT::R, G = RT::G;
     using L = StateLayout<D>;
 
     const int tid = threadIdx.x;
-    const int ti = tid / 16, tj = tid % 16;
+    const int grp = tid / RT::GROUP, ti = (tid % RT::GROUP) / RT::SIDE, tj = tid % RT::SIDE;
     const int lrow = tid / LPR, lcol = (tid % LPR) * VEC;
 
     float acc[R][R];
@@ -74,8 +90,9 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
         vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, tok_stride, lcol);
         __syncthreads();
 
+        static_assert(TILE % G == 0, "every group takes the same number of tokens of a tile");
 #pragma unroll 4
-        for (int t = 0; t < TILE; ++t) {
+        for (int t = grp; t < TILE; t += G) {
             float a[R], b[R];
 #pragma unroll
             for (int e = 0; e < R; ++e) {
@@ -92,16 +109,27 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
         }
     }
 
+    // this group's sums: straight to `out` if it is the only one, else through LDS
+    float* mine = G > 1 ? red + grp * L::SIZE : out;
 #pragma unroll
     for (int x = 0; x < R; ++x)
 #pragma unroll
-        for (int y = 0; y < R; ++y) out[L::S + (ti * R + x) * D + tj * R + y] = acc[x][y];
+        for (int y = 0; y < R; ++y) mine[L::S + (ti * R + x) * D + tj * R + y] = acc[x][y];
     if (tj == 0)
 #pragma unroll
-        for (int x = 0; x < R; ++x) out[L::KSUM + ti * R + x] = ks[x];
+        for (int x = 0; x < R; ++x) mine[L::KSUM + ti * R + x] = ks[x];
     if (ti == 0)
 #pragma unroll
-        for (int x = 0; x < R; ++x) out[L::VSUM + tj * R + x] = vs[x];
+        for (int x = 0; x < R; ++x) mine[L::VSUM + tj * R + x] = vs[x];
+    if constexpr (G > 1) {
+        __syncthreads();
+        for (int i = tid; i < L::SIZE; i += 256) {
+            float s = 0.f;
+#pragma unroll
+            for (int g = 0; g < G; ++g) s += red[g * L::SIZE + i];
+            out[i] = s;
+        }
+    }
 }
 
 // grid = (n_split, units), block = 256.
@@ -118,12 +146,13 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
     using L = StateLayout<D>;
     __shared__ __attribute__((aligned(16))) float kh[TILE][D];
     __shared__ __attribute__((aligned(16))) float vv[TILE][D];
+    __shared__ __attribute__((aligned(16))) float red[ReduceTiling<D>::RED_FLOATS];
     const int unit = blockIdx.y, split = blockIdx.x;
     const int n_begin = split * chunk;
     const long long off = unit_offset(unit, heads, st);
     reduce_generic_tokens<T, D>(k + off, v + off, n_begin, min(N, n_begin + chunk), st.n, eps,
                                 partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE,
-                                kh, vv);
+                                kh, vv, red);
 }
 
 // grid = (ceil(SIZE/256), units), block = 256.  state[u][i] = sum over splits in
