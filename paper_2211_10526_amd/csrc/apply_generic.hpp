@@ -4,6 +4,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "formats.hpp"
 
 namespace castling {
 
@@ -31,7 +32,10 @@ template <typename T, int D, int KS>
 constexpr size_t apply_generic_lds_bytes()
 {
     using L = StateLayout<D>;
-    const size_t phase_a = sizeof(float) * (L::SIZE + D * kQtStride);
+    // fp32: state and q_hat in fp32.  16-bit: both as pairs of 16-bit values (see the kernel)
+    const size_t phase_a =
+        sizeof(T) == 4 ? sizeof(float) * (L::SIZE + D * kQtStride)
+                       : 4 * (static_cast<size_t>(D / 2) * D + D / 2 + D + (D / 2) * kQtStride + kApplyTokens);
     const size_t halo = sizeof(T) * (kApplyTH + KS - 1) * (kApplyTW + KS - 1) * D;
     const size_t phase_b = ((halo + 15) / 16) * 16 + sizeof(float) * KS * KS * D;
     return phase_a > phase_b ? phase_a : phase_b;
@@ -105,64 +109,140 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
 
     // ---------------------------------------------------------------- linear branch
     if (p.do_linear) {
-        float* st = reinterpret_cast<float*>(lds_raw);  // state, pre-scaled
-        float* qt = st + L::SIZE;                       // q_hat transposed: [D][kQtStride]
-        const float* gs = state;
-        if (p.n_partials == 1) {
-            for (int i = tid; i < L::SIZE; i += 256) st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
-        } else {
-            for (int i = tid; i < L::SIZE; i += 256)
-                st[i] = sum_partials(gs + i, p.n_partials, L::SIZE) * (i < L::VSUM ? kInvPi : 0.5f);
-        }
-
-        constexpr int ROWS = 256 / LPR;  // token rows one pass of the block loads
-        constexpr int PASSES = (kApplyTokens + ROWS - 1) / ROWS;
-        const int lcol = (tid % LPR) * VEC;
-#pragma unroll
-        for (int pass = 0; pass < PASSES; ++pass) {
-            const int tl = pass * ROWS + tid / LPR;
-            if (tl >= kApplyTokens) break;  // narrow rows: fewer threads than 256 are needed
-            const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
-            float qx[VEC];
-            if (y < p.grid_h && x < p.grid_w) {
-                IO<T>::load16(q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol, qx);
+        if constexpr (std::is_same<T, float>::value) {
+            float* st = reinterpret_cast<float*>(lds_raw);  // state, pre-scaled
+            float* qt = st + L::SIZE;                       // q_hat transposed: [D][kQtStride]
+            const float* gs = state;
+            if (p.n_partials == 1) {
+                for (int i = tid; i < L::SIZE; i += 256) st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
             } else {
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) qx[e] = 0.f;
+                for (int i = tid; i < L::SIZE; i += 256)
+                    st[i] = sum_partials(gs + i, p.n_partials, L::SIZE) * (i < L::VSUM ? kInvPi : 0.5f);
             }
-            float ss = 0.f;
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) ss += qx[e] * qx[e];
-            ss = group_sum<LPR>(ss);
-            const float inv = 1.0f / fmaxf(sqrtf(ss), p.eps);
-#pragma unroll
-            for (int e = 0; e < VEC; ++e) qt[(lcol + e) * kQtStride + tl] = qx[e] * inv;
-        }
-        __syncthreads();
 
-        float den[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-        for (int i = 0; i < D; ++i) {
-            const float4 a4 = *reinterpret_cast<const float4*>(qt + i * kQtStride + tt * 4);
-            const float a[4] = {a4.x, a4.y, a4.z, a4.w};
-            const float ksi = st[L::KSUM + i];
-            float b[RJ];
+            constexpr int ROWS = 256 / LPR;  // token rows one pass of the block loads
+            constexpr int PASSES = (kApplyTokens + ROWS - 1) / ROWS;
+            const int lcol = (tid % LPR) * VEC;
+    #pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass) {
+                const int tl = pass * ROWS + tid / LPR;
+                if (tl >= kApplyTokens) break;  // narrow rows: fewer threads than 256 are needed
+                const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
+                float qx[VEC];
+                if (y < p.grid_h && x < p.grid_w) {
+                    IO<T>::load16(q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol, qx);
+                } else {
+    #pragma unroll
+                    for (int e = 0; e < VEC; ++e) qx[e] = 0.f;
+                }
+                float ss = 0.f;
+    #pragma unroll
+                for (int e = 0; e < VEC; ++e) ss += qx[e] * qx[e];
+                ss = group_sum<LPR>(ss);
+                const float inv = 1.0f / fmaxf(sqrtf(ss), p.eps);
+    #pragma unroll
+                for (int e = 0; e < VEC; ++e) qt[(lcol + e) * kQtStride + tl] = qx[e] * inv;
+            }
+            __syncthreads();
+
+            float den[4] = {0.f, 0.f, 0.f, 0.f};
+    #pragma unroll 4
+            for (int i = 0; i < D; ++i) {
+                const float4 a4 = *reinterpret_cast<const float4*>(qt + i * kQtStride + tt * 4);
+                const float a[4] = {a4.x, a4.y, a4.z, a4.w};
+                const float ksi = st[L::KSUM + i];
+                float b[RJ];
+    #pragma unroll
+                for (int j = 0; j < RJ; ++j) b[j] = st[L::S + i * D + tj * RJ + j];
+    #pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    den[t] = fmaf(a[t], ksi, den[t]);
+    #pragma unroll
+                    for (int j = 0; j < RJ; ++j) res[t][j] = fmaf(a[t], b[j], res[t][j]);
+                }
+            }
+    #pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float rden = p.norm_none ? 1.0f : 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
+    #pragma unroll
+                for (int j = 0; j < RJ; ++j) res[t][j] = (st[L::VSUM + tj * RJ + j] + res[t][j]) * rden;
+            }
+            __syncthreads();  // LDS is reused below
+        } else {
+            // 16-bit I/O: the products run as two-element dot products on pairs of 16-bit values,
+            // q as stored (exact) against S / pi and ksum / pi rounded once to the I/O format --
+            // the numerics of the matrix-core kernels -- and the per-token 1 / |q| multiplies
+            // the fp32 sums afterwards.  Half the multiplies and half the LDS traffic of the
+            // fp32 form.
+            using X = typename std::conditional<std::is_same<T, f16_t>::value, F16Fmt, Bf16Fmt>::type;
+            uint32_t* st2 = reinterpret_cast<uint32_t*>(lds_raw);   // [D/2][D]: (S[2i][j], S[2i+1][j])
+            uint32_t* ks2 = st2 + (D / 2) * D;                      // [D/2]: pairs of ksum
+            float* vh = reinterpret_cast<float*>(ks2 + D / 2);      // [D]: vsum / 2
+            uint32_t* qt2 = reinterpret_cast<uint32_t*>(vh + D);    // [D/2][kQtStride]: pairs of q
+            float* invl = reinterpret_cast<float*>(qt2 + (D / 2) * kQtStride);  // [tokens]: 1 / |q|
+            const float tscale = X::table_scale(p.N), unsc = X::table_unscale(p.N);
+            const float* gs = state;
+            auto entry = [&](int i) {
+                return p.n_partials == 1 ? gs[i] : sum_partials(gs + i, p.n_partials, L::SIZE);
+            };
+            for (int idx = tid; idx < (D / 2) * D; idx += 256) {
+                const int ip = idx / D, j = idx % D;
+                st2[idx] = X::pack(entry(L::S + (2 * ip) * D + j) * tscale,
+                                   entry(L::S + (2 * ip + 1) * D + j) * tscale);
+            }
+            for (int idx = tid; idx < D / 2; idx += 256)
+                ks2[idx] = X::pack(entry(L::KSUM + 2 * idx) * tscale, entry(L::KSUM + 2 * idx + 1) * tscale);
+            for (int idx = tid; idx < D; idx += 256) vh[idx] = 0.5f * entry(L::VSUM + idx);
+
+            constexpr int ROWS = 256 / LPR;  // token rows one pass of the block loads
+            constexpr int PASSES = (kApplyTokens + ROWS - 1) / ROWS;
+            const int lcol = (tid % LPR) * VEC;
 #pragma unroll
-            for (int j = 0; j < RJ; ++j) b[j] = st[L::S + i * D + tj * RJ + j];
+            for (int pass = 0; pass < PASSES; ++pass) {
+                const int tl = pass * ROWS + tid / LPR;
+                if (tl >= kApplyTokens) break;  // narrow rows: fewer threads than 256 are needed
+                const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
+                uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+                if (y < p.grid_h && x < p.grid_w)
+                    raw = *reinterpret_cast<const uint4*>(
+                        q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol);
+                const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
+                float ss = 0.f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) ss = X::dot2(rw[e], rw[e], ss);
+                ss = group_sum<LPR>(ss);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) qt2[(lcol / 2 + e) * kQtStride + tl] = rw[e];
+                if (tid % LPR == 0) invl[tl] = 1.0f / fmaxf(sqrtf(ss), p.eps);
+            }
+            __syncthreads();
+
+            float den[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+            for (int ip = 0; ip < D / 2; ++ip) {
+                const uint4 a4 = *reinterpret_cast<const uint4*>(qt2 + ip * kQtStride + tt * 4);
+                const uint32_t aw[4] = {a4.x, a4.y, a4.z, a4.w};
+                const uint32_t ksp = ks2[ip];
+                uint32_t bw[RJ];
+#pragma unroll
+                for (int j = 0; j < RJ; ++j) bw[j] = st2[ip * D + tj * RJ + j];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    den[t] = X::dot2(aw[t], ksp, den[t]);
+#pragma unroll
+                    for (int j = 0; j < RJ; ++j) res[t][j] = X::dot2(aw[t], bw[j], res[t][j]);
+                }
+            }
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                den[t] = fmaf(a[t], ksi, den[t]);
+                const float inv = invl[tt * 4 + t] * unsc;
+                const float rden =
+                    p.norm_none ? 1.0f : 1.0f / (0.5f * static_cast<float>(p.N) + inv * den[t]);
 #pragma unroll
-                for (int j = 0; j < RJ; ++j) res[t][j] = fmaf(a[t], b[j], res[t][j]);
+                for (int j = 0; j < RJ; ++j) res[t][j] = (vh[tj * RJ + j] + inv * res[t][j]) * rden;
             }
+            __syncthreads();  // LDS is reused below
         }
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const float rden = p.norm_none ? 1.0f : 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
-#pragma unroll
-            for (int j = 0; j < RJ; ++j) res[t][j] = (st[L::VSUM + tj * RJ + j] + res[t][j]) * rden;
-        }
-        __syncthreads();  // LDS is reused below
     }
 
     // ---------------------------------------------------------------- DWConv branch
