@@ -5,6 +5,7 @@
 #pragma once
 
 #include "common.hpp"
+#include "formats.hpp"
 
 namespace castling {
 
@@ -49,6 +50,9 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
     constexpr int LPR = D / VEC;     // lanes that share one token row
     constexpr int TILE = 256 / LPR;  // tokens staged per iteration
     using RT = ReduceTiling<D>;
+    // 16-bit I/O and wide heads: products on pairs of tokens (below); narrow heads do too little
+    // arithmetic per staged row to pay for the 2-byte LDS writes of that form
+    constexpr bool kPairs = sizeof(T) == 2 && D >= 64;
     constexpr int R = RT::R, G = RT::G;
     using L = StateLayout<D>;
 
@@ -70,8 +74,14 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
     // block the loop is a chain of memory latencies otherwise
     uint4 kraw = load_row_piece(kb, n_begin + lrow, n_end, tok_stride, lcol);
     uint4 vraw = load_row_piece(vb, n_begin + lrow, n_end, tok_stride, lcol);
+    uint32_t ones = 0u;  // (1, 1) in the 16-bit format
+    if constexpr (kPairs) {
+        using X = typename std::conditional<std::is_same<T, f16_t>::value, F16Fmt, Bf16Fmt>::type;
+        ones = opaque_u32(X::kOneLo | X::kOneHi);
+    }
     for (int n0 = n_begin; n0 < n_end; n0 += TILE) {
         float kx[VEC], vx[VEC];
+        const uint4 vraw_cur = vraw;
         IO<T>::widen16(kraw, kx);
         IO<T>::widen16(vraw, vx);
         float ss = 0.f;
@@ -81,30 +91,67 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
         const float inv = 1.0f / fmaxf(sqrtf(ss), eps);
 
         __syncthreads();  // the previous tile has been consumed
+        if constexpr (!kPairs) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            kh[lrow][lcol + e] = kx[e] * inv;
-            vv[lrow][lcol + e] = vx[e];
+            for (int e = 0; e < VEC; ++e) {
+                kh[lrow][lcol + e] = kx[e] * inv;
+                vv[lrow][lcol + e] = vx[e];
+            }
+        } else {
+            // 16-bit I/O: the tiles hold pairs of consecutive tokens, k_hat rounded once to the
+            // I/O format (as the matrix-core kernels round it) in the half its token has in
+            // the pair; the products below then take two tokens per instruction
+            T* kh16 = reinterpret_cast<T*>(&kh[0][0]) + ((lrow >> 1) * D + lcol) * 2 + (lrow & 1);
+            T* vv16 = reinterpret_cast<T*>(&vv[0][0]) + ((lrow >> 1) * D + lcol) * 2 + (lrow & 1);
+            const T* vsrc = reinterpret_cast<const T*>(&vraw_cur);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                kh16[2 * e] = IO<T>::from_f32(kx[e] * inv);
+                vv16[2 * e] = vsrc[e];
+            }
         }
         kraw = load_row_piece(kb, n0 + TILE + lrow, n_end, tok_stride, lcol);  // (zeros past the end)
         vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, tok_stride, lcol);
         __syncthreads();
 
-        static_assert(TILE % G == 0, "every group takes the same number of tokens of a tile");
+        if constexpr (!kPairs) {
+            static_assert(TILE % G == 0, "every group takes the same number of tokens of a tile");
 #pragma unroll 4
-        for (int t = grp; t < TILE; t += G) {
-            float a[R], b[R];
+            for (int t = grp; t < TILE; t += G) {
+                float a[R], b[R];
 #pragma unroll
-            for (int e = 0; e < R; ++e) {
-                a[e] = kh[t][ti * R + e];
-                b[e] = vv[t][tj * R + e];
+                for (int e = 0; e < R; ++e) {
+                    a[e] = kh[t][ti * R + e];
+                    b[e] = vv[t][tj * R + e];
+                }
+#pragma unroll
+                for (int x = 0; x < R; ++x) {
+#pragma unroll
+                    for (int y = 0; y < R; ++y) acc[x][y] = fmaf(a[x], b[y], acc[x][y]);
+                    ks[x] += a[x];
+                    vs[x] += b[x];
+                }
             }
+        } else {
+            using X = typename std::conditional<std::is_same<T, f16_t>::value, F16Fmt, Bf16Fmt>::type;
+            static_assert((TILE / 2) % G == 0, "every group takes the same number of token pairs");
+            const uint32_t* kh2 = reinterpret_cast<const uint32_t*>(&kh[0][0]);
+            const uint32_t* vv2 = reinterpret_cast<const uint32_t*>(&vv[0][0]);
+#pragma unroll 4
+            for (int tp = grp; tp < TILE / 2; tp += G) {
+                uint32_t a[R], b[R];
 #pragma unroll
-            for (int x = 0; x < R; ++x) {
+                for (int e = 0; e < R; ++e) {
+                    a[e] = kh2[tp * D + ti * R + e];
+                    b[e] = vv2[tp * D + tj * R + e];
+                }
 #pragma unroll
-                for (int y = 0; y < R; ++y) acc[x][y] = fmaf(a[x], b[y], acc[x][y]);
-                ks[x] += a[x];
-                vs[x] += b[x];
+                for (int x = 0; x < R; ++x) {
+#pragma unroll
+                    for (int y = 0; y < R; ++y) acc[x][y] = X::dot2(a[x], b[y], acc[x][y]);
+                    ks[x] = X::dot2(a[x], ones, ks[x]);
+                    vs[x] = X::dot2(b[x], ones, vs[x]);
+                }
             }
         }
     }
