@@ -125,7 +125,7 @@ void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const vo
 {
     const int units = PAIR ? h->apply_units : h->units;
     const int heads = PAIR ? h->apply_heads : h->desc.heads;
-    ReduceExtras ex;
+    ReduceExtras ex = {};
     ex.state = direct ? h->state : nullptr;
     ex.sfrag = h->sfrag;
     ex.kfrag = h->kfrag;
@@ -248,7 +248,7 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
                                    static_cast<int>(lds));
     }
     const castling_attn_desc_t& d = h->desc;
-    ApplyParams p;
+    ApplyParams p = {};
     p.N = d.N;
     p.grid_h = h->view.grid_h;
     p.grid_w = h->view.grid_w;
@@ -284,7 +284,7 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
         return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kApplyMfmaLdsBytes);
     }
     const castling_attn_desc_t& d = h->desc;
-    ApplyMfmaParams p;
+    ApplyMfmaParams p = {};
     p.N = d.N;
     p.grid_h = h->view.grid_h;
     p.grid_w = h->view.grid_w;
@@ -434,7 +434,7 @@ hipError_t fused_branches(castling_attn* h, bool launch, const void* q, const vo
         return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kFusedLdsBytes);
     }
     const castling_attn_desc_t& d = h->desc;
-    FusedParams p;
+    FusedParams p = {};
     p.N = d.N;
     p.grid_h = d.grid_h;
     p.grid_w = d.grid_w;
@@ -809,7 +809,7 @@ int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* para
     const bool half = d.io_dtype == CASTLING_F16;
     if ((d.io_dtype != CASTLING_BF16 && !half) || d.d != 64) return CASTLING_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    PairParams p;
+    PairParams p = {};
     p.N = d.N;
     p.normalize = params->normalize;
     p.accumulate = params->accumulate;
