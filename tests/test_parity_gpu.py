@@ -573,3 +573,23 @@ def test_pairs_of_narrow_heads_take_the_matrix_core_path(monkeypatch):
     assert launches(Workload("hp_big_odd", "bf16", 32, 9, 32, 20, 20, 3)) == (2, 1)
     monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
     assert launches(HEAD_PAIRS[4]) == (3, 1)
+
+
+@pytest.mark.parametrize("wl", [
+    Workload("one_unit_bf16_512x768_k5", "bf16", 1, 1, 64, 512, 768, 5),
+    Workload("one_unit_f32_d32_256x256_k3", "f32", 1, 1, 32, 256, 256, 3),
+    Workload("two_units_f16_d32_384x256_k7", "f16", 1, 2, 32, 384, 256, 7),
+], ids=lambda w: w.name)
+def test_one_unit_with_the_maximum_number_of_splits(oracle, wl):
+    """A single long unit: pass 1 splits it over every compute unit (256 partial states per unit,
+    summed in index order), pass 2 hands every block a stretch of one and the same unit."""
+    x = inputs.make_inputs(wl, seed=71, with_bias=True)
+    q, k, v, w, bias = oracle_inputs(x)
+    want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
+    h = b.CastlingAttn.for_workload(wl)
+    splits = h.num_splits()
+    h.destroy()
+    assert splits >= 128
+    got, st = gpu_forward(wl, x, want_state=True)
+    assert rel_err(st, oracle.state(k, v)) <= STATE_TOL[wl.dtype]
+    assert rel_err(got, want) <= TOL[wl.dtype]
