@@ -204,6 +204,21 @@ def main():
         stream.synchronize()
         forward_ms = e[0].elapsed_time(e[1]) / args.steps
 
+    # a plain device-to-device copy on the same box, after the timed region: the practical
+    # ceiling to read the fractions of the published peak against (256 MiB read + 256 MiB written)
+    with torch.cuda.stream(stream):
+        cx = torch.empty(128 * 1024 * 1024, dtype=torch.bfloat16, device=dev)
+        cy = torch.empty_like(cx)
+        cy.copy_(cx)
+        stream.synchronize()
+        e[0].record(stream)
+        for _ in range(5):
+            cy.copy_(cx)
+        e[1].record(stream)
+        stream.synchronize()
+        copy_gbs = 5 * 2 * cx.numel() * 2 / (e[0].elapsed_time(e[1]) * 1e-3) / 1e9
+        del cx, cy
+
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = wl.tokens * args.steps / elapsed
     tensor_bytes = wl.elems * wl.itemsize
@@ -226,6 +241,7 @@ def main():
         "layer_algorithmic_gbs_4tensor": round(4 * tensor_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "layer_frac_of_peak_4tensor": round(4 * tensor_bytes / (ms_per_step * 1e-3) / 1e9
                                             / HBM_PEAK_GBS, 4),
+        "d2d_copy_gbs_same_run": round(copy_gbs, 1),
     }
 
     cpu_baseline = None
