@@ -214,33 +214,44 @@ __global__ __launch_bounds__(256) void pairwise_attn_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[r] = key_valid(r) ? s[r] : 0.f;
         }
-        u32x4_t pop[2], plo[2];  // probabilities and their rounding remainders, 16-bit pairs
+        // SPARSE: (uniform per wave) a tile in which the mask kept nothing for any of the wave's
+        // queries adds nothing: the usual case once the threshold bites
+        bool tile_live = true;
+        if constexpr (MODE == kPairSparse) {
+            bool any = false;
 #pragma unroll
-        for (int r = 0; r < 16; r += 2) {
-            if constexpr (MODE == kPairSparse) {
-                // kept entries are exactly the nonzero ones (a kept probability is > thr >= 0)
-                if (kept) {
-                    n_kept += __builtin_popcountll(__ballot(q_valid && s[r] != 0.f));
-                    n_kept += __builtin_popcountll(__ballot(q_valid && s[r + 1] != 0.f));
-                }
-            } else {
-                den += s[r] + s[r + 1];
-            }
-            const uint32_t hi = X::pack(s[r], s[r + 1]);
-            pop[r >> 3][(r >> 1) & 3] = hi;
-            plo[r >> 3][(r >> 1) & 3] = X::pack(s[r] - X::lo(hi), s[r + 1] - X::hi(hi));
+            for (int r = 0; r < 16; ++r) any = any || s[r] != 0.f;
+            tile_live = __ballot(any) != 0ull;
         }
+        if (tile_live) {
+            u32x4_t pop[2], plo[2];  // probabilities and their rounding remainders, 16-bit pairs
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                const unsigned char* base = vtile + (16 * u + 4 * hsel) * kPairTilePitch + 64 * mt + vsrc;
-                const uint2 lo = lds_read_tr8(base);
-                const uint2 hi = lds_read_tr8(base + 8 * kPairTilePitch);
-                const u32x4_t a = {lo.x, lo.y, hi.x, hi.y};
-                acc[mt] = X::mfma32(a, pop[u], acc[mt]);
-                acc[mt] = X::mfma32(a, plo[u], acc[mt]);
+            for (int r = 0; r < 16; r += 2) {
+                if constexpr (MODE == kPairSparse) {
+                    // kept entries are exactly the nonzero ones (a kept probability is > thr >= 0)
+                    if (kept) {
+                        n_kept += __builtin_popcountll(__ballot(q_valid && s[r] != 0.f));
+                        n_kept += __builtin_popcountll(__ballot(q_valid && s[r + 1] != 0.f));
+                    }
+                } else {
+                    den += s[r] + s[r + 1];
+                }
+                const uint32_t hi = X::pack(s[r], s[r + 1]);
+                pop[r >> 3][(r >> 1) & 3] = hi;
+                plo[r >> 3][(r >> 1) & 3] = X::pack(s[r] - X::lo(hi), s[r + 1] - X::hi(hi));
             }
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    const unsigned char* base = vtile + (16 * u + 4 * hsel) * kPairTilePitch + 64 * mt + vsrc;
+                    const uint2 lo = lds_read_tr8(base);
+                    const uint2 hi = lds_read_tr8(base + 8 * kPairTilePitch);
+                    const u32x4_t a = {lo.x, lo.y, hi.x, hi.y};
+                    acc[mt] = X::mfma32(a, pop[u], acc[mt]);
+                    acc[mt] = X::mfma32(a, plo[u], acc[mt]);
+                }
+        }
         __syncthreads();
     }
 
