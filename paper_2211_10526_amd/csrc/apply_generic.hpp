@@ -1,6 +1,7 @@
-// Pass 2 (any dtype, fp32 vector ALU): normalise Q per token, apply the state
+// Pass 2 on the vector ALU (any dtype): normalise Q per token, apply the state
 // (Eq. 3 with the linear terms of Eq. 8), add the depthwise convolution of V
-// over the token grid (DWConv term of Eq. 9), store.
+// over the token grid (DWConv term of Eq. 9), store.  fp32 products; with 16-bit I/O the
+// linear branch runs on two-element dot products of 16-bit pairs.
 #pragma once
 
 #include "common.hpp"

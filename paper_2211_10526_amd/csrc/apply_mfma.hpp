@@ -1,4 +1,5 @@
-// Pass 2 for bf16 I/O, d = 64, on the matrix cores.
+// Pass 2 for bf16 / fp16 I/O on the matrix cores: heads of 64 channels, or two neighbouring
+// heads of 32 channels as one unit (PAIR).
 //
 //   linear branch  (Eq. 3 with the linear terms of Eq. 8): q . S as a dense
 //       16x16x32 bf16 MFMA per 16 tokens, per-token scalars on the vector ALU;

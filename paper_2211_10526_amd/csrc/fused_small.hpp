@@ -1,22 +1,25 @@
-// The whole layer in one kernel for units whose tokens fit on chip (bf16 or fp16, d = 64,
-// N <= 256, filter size <= 5): one block per unit loads K, V, Q once, builds the state
-// K_hat^T V, sum k_hat, sum v on the matrix cores (Sec. 3.1 reassociation, sums of Eq. 3),
-// keeps it in LDS as MFMA operands, applies it to the unit's own queries (Eq. 3 with the
-// linear terms of Eq. 8) and adds the depthwise convolution of V read from LDS (Eq. 9).
-// At these sizes the state (17 KB fp32 + 10 KB of operands per unit) is as large as a
-// tensor of the unit (25 KB at N = 196), so keeping it on chip and launching once halves
-// the time of the two-pass path.
+// The whole layer in one kernel for units whose tokens fit on chip (bf16 or fp16, d = 64 or two
+// neighbouring heads of d = 32, N <= 256, filter size <= 5): one block per unit loads K, V, Q
+// once, builds the state K_hat^T V, sum k_hat, sum v on the matrix cores (Sec. 3.1
+// reassociation, sums of Eq. 3), keeps it in LDS as MFMA operands, applies it to the unit's own
+// queries (Eq. 3 with the linear terms of Eq. 8) and adds the depthwise convolution of V read
+// from LDS (Eq. 9).  At these sizes the state (17 KB fp32 + 10 KB of operands per unit) is as
+// large as a tensor of the unit (25 KB at N = 196), so keeping it on chip and launching once
+// beats the two-pass path.
 //
-// Block = 4 waves, two blocks per compute unit.  Every global load of the unit is issued at
-// the start (inline global_load, explicit s_waitcnt vmcnt) and consumed in issue order:
+// Block = 4 waves, two blocks per compute unit.  The global loads are issued with inline
+// global_load and explicit s_waitcnt vmcnt and consumed in issue order: K, V, filters and bias
+// at the start, Q between the two iterations of phase 1.
 //   phase 1  wave w normalises and stages tokens 64 w .. 64 w + 63 (V rows stay in LDS for
-//            the convolution), accumulates K_hat^T V with v_mfma_f32_32x32x16_bf16;
-//            column sums and a fixed tree over the waves as in reduce_mfma_kernel;
-//   phase 2  S / pi, ksum / pi, vsum / 2, filters and bias go to LDS tables;
+//            the convolution), accumulates K_hat^T V with v_mfma_f32_32x32x16;
+//   between  column sums through lane shuffles; the four waves' 64 x 64 sums by recursive
+//            halving, after which wave w owns quadrant w of S;
+//   phase 2  S / pi (every wave its quadrant), ksum / pi, vsum / 2, filters and bias go to
+//            LDS tables;
 //   phase 3  per chunk of 64 tokens: wave w computes the linear branch of 16 tokens
-//            (v_mfma_f32_16x16x32_bf16) into an fp32 LDS tile; then every thread adds the
-//            convolution for 8 channels of a token on the vector ALU and stores 16 bytes,
-//            8 lanes per 128-byte output line.
+//            (v_mfma_f32_16x16x32) into an fp32 LDS tile; then every thread adds the
+//            convolution for 8 channels of two tokens with two-element dot products on the raw
+//            16-bit pairs and stores 16 bytes per token, 8 lanes per 128-byte output line.
 #pragma once
 
 #include "apply_mfma.hpp"

@@ -1,6 +1,7 @@
-// Pass 1 (any dtype, fp32 vector ALU): normalise K per token and reduce over a
+// Pass 1 on the vector ALU (any dtype): normalise K per token and reduce over a
 // chunk of tokens to a partial state (K_hat^T V, K_hat column sum, V column sum),
-// then a fixed-order combine of the partials.  Sec. 3.1 (reassociation of
+// then a fixed-order combine of the partials.  fp32 products; with 16-bit I/O and heads of
+// 64 channels or more, two-element dot products on pairs of tokens.  Sec. 3.1 (reassociation of
 // kernel-based linear attention) and the sums of Eq. 3 of the paper.
 #pragma once
 
