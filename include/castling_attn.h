@@ -31,9 +31,10 @@
  *   - DWConv: zero "same" padding, stride 1, cross-correlation (no flip).
  *   - io_dtype is the type of q, k, v, dw_weight, dw_bias and out.  Accumulation
  *     is fp32 in all cases; bf16 and fp16 outputs are rounded to nearest even (fp16
- *     results beyond 65504 in magnitude become infinity).  bf16 with d = 64 (and d = 32
- *     for the first half) runs on the matrix cores; fp32, fp16 and the other head
- *     widths run on the vector ALUs.
+ *     results beyond 65504 in magnitude become infinity).  bf16 and fp16 with d = 64, and
+ *     with d = 32 where the head count is even, run on the matrix cores; fp32 and the
+ *     other head widths run on the vector ALUs, at the next of the widths 16, 32, 64, 128
+ *     with zero features in the gap (d = 96 costs about what d = 128 does).
  *   - The caller owns every tensor.  A handle owns only its workspace (partial
  *     states + final state), allocated by create and freed by destroy.
  *   - forward / reduce / apply only enqueue work on `stream` (a hipStream_t, NULL
@@ -78,7 +79,7 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
 enum { CASTLING_FLAG_KEEP_STATE = 1 };
 
 typedef struct {
-    int32_t B, heads, N, d;   /* d in {16, 32, 64, 128} */
+    int32_t B, heads, N, d;   /* d: a multiple of 8, at most 128 */
     int32_t grid_h, grid_w;   /* N must equal extra_tokens + grid_h * grid_w */
     int32_t dw_kernel;        /* odd, 1..9 */
     int32_t io_dtype;         /* castling_dtype_t */

@@ -21,6 +21,7 @@ struct ApplyParams {
     // unit ([unit][split][StateLayout::SIZE], as pass 1 leaves them); the block sums them in
     // index order while it loads them (small problems: saves the combine launch)
     int n_partials;
+    int d_valid;  // features per head in memory (<= D: narrower heads are padded with zeros)
 };
 
 constexpr int kApplyTH = 4;   // tile rows
@@ -90,7 +91,8 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
         const int tok = idx / LPR, part = idx % LPR;
         const int y = ty0 - RAD + tok / HW, x = tx0 - RAD + tok % HW;
         uint4 val = make_uint4(0u, 0u, 0u, 0u);
-        if (idx < HH * HW * LPR && y >= 0 && y < p.grid_h && x >= 0 && x < p.grid_w)
+        if (idx < HH * HW * LPR && part * VEC < p.d_valid && y >= 0 && y < p.grid_h && x >= 0 &&
+            x < p.grid_w)
             val = *reinterpret_cast<const uint4*>(
                 v + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + part * VEC);
         return val;
@@ -99,11 +101,11 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
         if (p.do_dwconv) {
 #pragma unroll
             for (int i = 0; i < HALO_PIECES; ++i) halo_pre[i] = halo_piece(tid + 256 * i);
-            const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
+            const T* wh = w + static_cast<size_t>(head) * p.d_valid * KS * KS;
 #pragma unroll
             for (int i = 0; i < W_PIECES; ++i) {
                 const int idx = tid + 256 * i;
-                w_pre[i] = idx < D * KS * KS ? wh[idx] : T{};
+                w_pre[i] = idx < p.d_valid * KS * KS ? wh[idx] : T{};
             }
         }
     }
@@ -130,7 +132,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
                 if (tl >= kApplyTokens) break;  // narrow rows: fewer threads than 256 are needed
                 const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
                 float qx[VEC];
-                if (y < p.grid_h && x < p.grid_w) {
+                if (y < p.grid_h && x < p.grid_w && lcol < p.d_valid) {
                     IO<T>::load16(q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol, qx);
                 } else {
     #pragma unroll
@@ -204,7 +206,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
                 if (tl >= kApplyTokens) break;  // narrow rows: fewer threads than 256 are needed
                 const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
                 uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-                if (y < p.grid_h && x < p.grid_w)
+                if (y < p.grid_h && x < p.grid_w && lcol < p.d_valid)
                     raw = *reinterpret_cast<const uint4*>(
                         q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol);
                 const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -262,7 +264,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             }
 #pragma unroll
             for (int i = 0; i < W_PIECES; ++i) {
-                const int idx = tid + 256 * i;
+                const int idx = tid + 256 * i;  // (w_pre is zero past the head's d_valid channels)
                 if (idx < D * KS * KS)
                     wt[(idx % (KS * KS)) * D + idx / (KS * KS)] = IO<T>::to_f32(w_pre[i]);
             }
@@ -270,10 +272,10 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             for (int idx = tid; idx < HH * HW * LPR; idx += 256)
                 *reinterpret_cast<uint4*>(vh + static_cast<size_t>(idx / LPR) * D + (idx % LPR) * VEC) =
                     halo_piece(idx);
-            const T* wh = w + static_cast<size_t>(head) * D * KS * KS;
+            const T* wh = w + static_cast<size_t>(head) * p.d_valid * KS * KS;
             for (int idx = tid; idx < D * KS * KS; idx += 256) {
                 const int c = idx / (KS * KS), tap = idx % (KS * KS);
-                wt[tap * D + c] = IO<T>::to_f32(wh[idx]);
+                wt[tap * D + c] = c < p.d_valid ? IO<T>::to_f32(wh[idx]) : 0.f;
             }
         }
         __syncthreads();
@@ -281,7 +283,8 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
         float dw[4][RJ];
 #pragma unroll
         for (int j = 0; j < RJ; ++j) {
-            const float b0 = bias ? IO<T>::to_f32(bias[head * D + tj * RJ + j]) : 0.f;
+            const int ch = tj * RJ + j;
+            const float b0 = (bias && ch < p.d_valid) ? IO<T>::to_f32(bias[head * p.d_valid + ch]) : 0.f;
 #pragma unroll
             for (int t = 0; t < 4; ++t) dw[t][j] = b0;
         }
@@ -320,7 +323,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int x = tx0 + my_col0 + t;
-            if (x < p.grid_w) {
+            if (x < p.grid_w && tj * RJ < p.d_valid) {  // (d_valid is a multiple of the piece)
                 T* o = out + out_off + (static_cast<long long>(y) * p.grid_w + x) * p.out.n + tj * RJ;
                 __attribute__((aligned(16))) T tmp[RJ];
 #pragma unroll

@@ -77,7 +77,8 @@ struct castling_attn {
     int chunk;
     TensorStrides in_st, out_st;  // element strides of q/k/v and of out (defaults resolved)
     size_t in_span, out_span;     // bytes from the first to one past the last element addressed
-    int state_size;     // floats per unit
+    int dpad;           // width the kernels run at: 16 / 32 / 64 / 128, narrower heads zero-padded
+    int state_size;     // floats per unit (of width dpad)
     bool mfma_reduce;   // bf16 / fp16, d = 32 or 64: K_hat^T V on the matrix cores
     bool mfma_apply;    // bf16 / fp16, d = 64: q.S and the DWConv on the matrix cores
     bool half16;        // the 16-bit format is fp16 (else bf16)
@@ -113,7 +114,7 @@ void launch_reduce_generic(castling_attn* h, const void* k, const void* v, hipSt
 {
     hipLaunchKernelGGL((reduce_generic_kernel<T, D>), dim3(h->n_split, h->units), dim3(256), 0, s,
                        static_cast<const T*>(k), static_cast<const T*>(v), h->partial, h->desc.N,
-                       h->n_split, h->chunk, h->desc.eps, h->desc.heads, h->in_st);
+                       h->n_split, h->chunk, h->desc.eps, h->desc.heads, h->in_st, h->desc.d);
 }
 
 // w != nullptr: extra grid rows build the DWConv weight operand table.
@@ -159,7 +160,7 @@ void launch_combine(castling_attn* h, hipStream_t s)
 int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hipStream_t s,
               bool defer_combine = false)
 {
-    const int d = h->desc.d;
+    const int d = h->dpad;
     h->state_valid = true;
     h->apply_ready = true;
     h->partials_pending = false;
@@ -260,6 +261,7 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     p.in = h->in_st;
     p.out = h->out_st;
     p.n_partials = h->partials_pending ? h->n_split : 1;
+    p.d_valid = d.d;
     const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
     hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, h->units),
                        dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
@@ -367,7 +369,7 @@ hipError_t do_apply_view(castling_attn* h, bool launch, const void* q, const voi
             default: return apply_mfma<9>(h, launch, q, v, w, bias, out, s);
         }
     }
-    return dispatch_type_width(h->desc.io_dtype, h->desc.d, [&](auto t, auto dc) {
+    return dispatch_type_width(h->desc.io_dtype, h->dpad, [&](auto t, auto dc) {
         return apply_generic_ks<decltype(t), decltype(dc)::value>(h, launch, q, v, w, bias, out, s);
     });
 }
@@ -549,7 +551,7 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE)) return CASTLING_ERR_INVALID_ARG;
     if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16 && d->io_dtype != CASTLING_F16)
         return CASTLING_ERR_UNSUPPORTED;
-    if (d->d != 16 && d->d != 32 && d->d != 64 && d->d != 128) return CASTLING_ERR_UNSUPPORTED;
+    if (d->d % 8 != 0 || d->d > 128) return CASTLING_ERR_UNSUPPORTED;
     if (d->dw_kernel > 9) return CASTLING_ERR_UNSUPPORTED;
     // grid.y carries the unit index; keep element offsets inside int64 comfortably
     if (static_cast<int64_t>(d->B) * d->heads > 65535) return CASTLING_ERR_UNSUPPORTED;
@@ -608,7 +610,8 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         h->in_span = span(h->in_st);
         h->out_span = span(h->out_st);
     }
-    h->state_size = desc->d * desc->d + 2 * desc->d;
+    h->dpad = desc->d <= 16 ? 16 : desc->d <= 32 ? 32 : desc->d <= 64 ? 64 : 128;
+    h->state_size = h->dpad * h->dpad + 2 * h->dpad;
 
     // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 / fp16 on the vector-ALU kernels (A/B measurements)
     const char* force = getenv("CASTLING_ATTN_FORCE_GENERIC");
@@ -885,7 +888,7 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
 int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream)
 {
     if (!h || !host_f32 || !h->state_valid) return CASTLING_ERR_INVALID_ARG;
-    const int D = h->desc.d, D1 = D + 1;
+    const int D = h->desc.d, D1 = D + 1, P = h->dpad;  // the workspace holds width-P records
     if (bytes != sizeof(float) * static_cast<size_t>(h->units) * D1 * D1)
         return CASTLING_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -900,10 +903,10 @@ int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, voi
         const float* r = raw.get() + static_cast<size_t>(u) * h->state_size;
         float* m = dst + static_cast<size_t>(u) * D1 * D1;
         for (int i = 0; i < D; ++i) {
-            for (int j = 0; j < D; ++j) m[i * D1 + j] = r[i * D + j];
-            m[i * D1 + D] = r[D * D + i];
+            for (int j = 0; j < D; ++j) m[i * D1 + j] = r[i * P + j];
+            m[i * D1 + D] = r[P * P + i];
         }
-        for (int j = 0; j < D; ++j) m[D * D1 + j] = r[D * D + D + j];
+        for (int j = 0; j < D; ++j) m[D * D1 + j] = r[P * P + P + j];
         m[D * D1 + D] = static_cast<float>(h->desc.N);
     }
     return CASTLING_OK;

@@ -10,13 +10,14 @@
 
 namespace castling {
 
-// This thread's 16 raw bytes of token row n (zeros for n >= n_end).
+// This thread's 16 raw bytes of token row n, features lcol .. (zeros for n >= n_end and for
+// features >= d_valid: heads narrower than the kernel's width are padded with zero features).
 template <typename T>
 __device__ __forceinline__ uint4 load_row_piece(const T* base, int n, int n_end, long long tok_stride,
-                                                int lcol)
+                                                int lcol, int d_valid)
 {
-    return n < n_end ? *reinterpret_cast<const uint4*>(base + n * tok_stride + lcol)
-                     : make_uint4(0u, 0u, 0u, 0u);
+    return (n < n_end && lcol < d_valid) ? *reinterpret_cast<const uint4*>(base + n * tok_stride + lcol)
+                                         : make_uint4(0u, 0u, 0u, 0u);
 }
 
 // Tokens per LDS tile of the reduce loop (256 threads, 16 bytes each).
@@ -45,7 +46,7 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
                                                       const T* __restrict__ vb, int n_begin,
                                                       int n_end, long long tok_stride, float eps,
                                                       float* out, float (*kh)[D], float (*vv)[D],
-                                                      float* red)
+                                                      float* red, int d_valid)
 {
     constexpr int VEC = IO<T>::VEC;  // elements per 16-byte load
     constexpr int LPR = D / VEC;     // lanes that share one token row
@@ -73,8 +74,8 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
 
     // the rows of the next tile are loaded while this one is multiplied: with few tokens per
     // block the loop is a chain of memory latencies otherwise
-    uint4 kraw = load_row_piece(kb, n_begin + lrow, n_end, tok_stride, lcol);
-    uint4 vraw = load_row_piece(vb, n_begin + lrow, n_end, tok_stride, lcol);
+    uint4 kraw = load_row_piece(kb, n_begin + lrow, n_end, tok_stride, lcol, d_valid);
+    uint4 vraw = load_row_piece(vb, n_begin + lrow, n_end, tok_stride, lcol, d_valid);
     uint32_t ones = 0u;  // (1, 1) in the 16-bit format
     if constexpr (kPairs) {
         using X = typename std::conditional<std::is_same<T, f16_t>::value, F16Fmt, Bf16Fmt>::type;
@@ -111,8 +112,8 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
                 vv16[2 * e] = vsrc[e];
             }
         }
-        kraw = load_row_piece(kb, n0 + TILE + lrow, n_end, tok_stride, lcol);  // (zeros past the end)
-        vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, tok_stride, lcol);
+        kraw = load_row_piece(kb, n0 + TILE + lrow, n_end, tok_stride, lcol, d_valid);  // (zeros past the end)
+        vraw = load_row_piece(vb, n0 + TILE + lrow, n_end, tok_stride, lcol, d_valid);
         __syncthreads();
 
         if constexpr (!kPairs) {
@@ -182,13 +183,13 @@ __device__ __forceinline__ void reduce_generic_tokens(const T* __restrict__ kb,
 
 // grid = (n_split, units), block = 256.
 // Block (s, u) reduces tokens [s*chunk, min(N, (s+1)*chunk)) of unit u and writes
-// partial[u][s][StateLayout<D>::SIZE].
+// partial[u][s][StateLayout<D>::SIZE].  d_valid <= D: features per head in memory.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict__ k,
                                                               const T* __restrict__ v,
                                                               float* __restrict__ partial, int N,
                                                               int n_split, int chunk, float eps,
-                                                              int heads, TensorStrides st)
+                                                              int heads, TensorStrides st, int d_valid)
 {
     constexpr int TILE = reduce_generic_tile<T, D>();
     using L = StateLayout<D>;
@@ -200,7 +201,7 @@ __global__ __launch_bounds__(256) void reduce_generic_kernel(const T* __restrict
     const long long off = unit_offset(unit, heads, st);
     reduce_generic_tokens<T, D>(k + off, v + off, n_begin, min(N, n_begin + chunk), st.n, eps,
                                 partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE,
-                                kh, vv, red);
+                                kh, vv, red, d_valid);
 }
 
 // grid = (ceil(SIZE/256), units), block = 256.  state[u][i] = sum over splits in

@@ -82,6 +82,8 @@ EXTRA_WORKLOADS = (
     Workload("x_f16_b64_h8_d64_n196_k3", "f16", 64, 8, 64, 14, 14, 3),
     Workload("x_bf16_b8_h16_d32_n4096_k5", "bf16", 8, 16, 32, 64, 64, 5),
     Workload("x_bf16_b64_h16_d32_n196_k3", "bf16", 64, 16, 32, 14, 14, 3),
+    Workload("x_bf16_b32_h1_d96_n3136_k3", "bf16", 32, 1, 96, 56, 56, 3),
+    Workload("x_bf16_b32_h4_d96_n196_k3", "bf16", 32, 4, 96, 14, 14, 3),
 )
 
 

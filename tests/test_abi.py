@@ -45,7 +45,8 @@ def test_validate_accepts_benchmark_workloads():
     ("B", 0, b.ERR_INVALID_ARG), ("heads", -1, b.ERR_INVALID_ARG), ("N", 195, b.ERR_INVALID_ARG),
     ("grid_w", 13, b.ERR_INVALID_ARG), ("dw_kernel", 4, b.ERR_INVALID_ARG),
     ("dw_kernel", 0, b.ERR_INVALID_ARG), ("dw_kernel", 11, b.ERR_UNSUPPORTED),
-    ("d", 48, b.ERR_UNSUPPORTED), ("d", 256, b.ERR_UNSUPPORTED), ("d", 0, b.ERR_INVALID_ARG),
+    ("d", 20, b.ERR_UNSUPPORTED), ("d", 136, b.ERR_UNSUPPORTED), ("d", 256, b.ERR_UNSUPPORTED),
+    ("d", 0, b.ERR_INVALID_ARG),
     ("io_dtype", 7, b.ERR_UNSUPPORTED),
     ("norm", 2, b.ERR_INVALID_ARG), ("branches", 8, b.ERR_INVALID_ARG),
     ("eps", -1.0, b.ERR_INVALID_ARG), ("eps", float("nan"), b.ERR_INVALID_ARG),
@@ -55,6 +56,12 @@ def test_validate_rejects(field, value, status):
     d = good()
     setattr(d, field, value)
     assert b.validate(d) == status
+
+
+@pytest.mark.parametrize("d", [8, 16, 24, 48, 64, 96, 120, 128])
+@pytest.mark.parametrize("dtype", ["bf16", "f16", "f32"])
+def test_validate_accepts_head_widths_in_steps_of_eight(d, dtype):
+    assert b.validate(b.make_desc(2, 4, 196, d, 14, 14, 3, dtype)) == b.OK
 
 
 def test_validate_strides():

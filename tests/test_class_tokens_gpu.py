@@ -23,6 +23,8 @@ CASES = [
     (Workload("c_f32_d32_14x14_k3", "f32", 1, 4, 32, 14, 14, 3), 1),
     (Workload("c_bf16_d32_9x11_k5", "bf16", 1, 2, 32, 9, 11, 5), 3),
     (Workload("c_f16_d128_6x7_k3", "f16", 1, 2, 128, 6, 7, 3), 1),
+    (Workload("c_bf16_d96_7x7_k3", "bf16", 1, 2, 96, 7, 7, 3), 1),
+    (Workload("c_f32_d48_8x8_k5", "f32", 1, 2, 48, 8, 8, 5), 2),
 ]
 
 

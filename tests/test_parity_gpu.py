@@ -72,8 +72,26 @@ WIDE = [
     Workload("w_f16_d64_1x40_k1", "f16", 1, 2, 64, 1, 40, 1),
 ]
 
+# head widths between the kernels' own (any multiple of 8 up to 128): the vector-ALU kernels run
+# them at the next width of theirs with zero features in the gap; 96 is the width of the last
+# stage of a pooling-attention backbone; one shape with several token splits per unit
+ANY_WIDTH = [
+    Workload("aw_bf16_d96_14x14_k3", "bf16", 2, 3, 96, 14, 14, 3),
+    Workload("aw_f32_d96_9x21_k5", "f32", 1, 2, 96, 9, 21, 5),
+    Workload("aw_f16_d96_7x7_k7", "f16", 2, 2, 96, 7, 7, 7),
+    Workload("aw_bf16_d48_13x19_k9", "bf16", 1, 3, 48, 13, 19, 9),
+    Workload("aw_f32_d24_14x14_k3", "f32", 2, 2, 24, 14, 14, 3),
+    Workload("aw_f16_d40_10x12_k5", "f16", 1, 4, 40, 10, 12, 5),
+    Workload("aw_bf16_d8_16x16_k3", "bf16", 1, 5, 8, 16, 16, 3),
+    Workload("aw_f32_d8_6x20_k1", "f32", 1, 2, 8, 6, 20, 1),
+    Workload("aw_bf16_d120_6x20_k3", "bf16", 1, 2, 120, 6, 20, 3),
+    Workload("aw_f32_d72_5x33_k7", "f32", 1, 1, 72, 5, 33, 7),
+    Workload("aw_bf16_d96_40x44_k5", "bf16", 1, 2, 96, 40, 44, 5),
+    Workload("aw_f32_d56_36x40_k3", "f32", 1, 1, 56, 36, 40, 3),
+]
 
-@pytest.mark.parametrize("wl", WIDE, ids=lambda w: w.name)
+
+@pytest.mark.parametrize("wl", WIDE + ANY_WIDTH, ids=lambda w: w.name)
 @pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
 def test_wide_shapes_and_fp16(oracle, wl, norm):
     x = inputs.make_inputs(wl, seed=31, with_bias=True)
