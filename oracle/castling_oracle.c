@@ -322,6 +322,96 @@ void oracle_forward(const double* q, const double* k, const double* v,
 }
 
 /* ------------------------------------------------------------------------
+ * Downsampling attention layers (Sec. 3.1, attention designs; Table 1, last row): the queries
+ * are pooled after their projection, K and V keep every token, and the pooled query is added
+ * to the result (residual connection).  The pooling operator itself runs before the layer:
+ * q holds Nq = ceil(H/s) * ceil(W/s) pooled queries per unit, query (y, x) of that grid
+ * standing at position (s*y, s*x) of the H x W token grid.
+ *
+ * Readings where the paper is silent: the N x N matrix M_DW of Eq. 9 keeps the rows of the
+ * positions the queries stand at, i.e. the DWConv is evaluated with stride s; the residual adds
+ * the pooled query as given (not its unit row), after the normaliser.
+ * ---------------------------------------------------------------------- */
+
+/* The definition, all rows: q, out [B][heads][Nq][d]; k, v [B][heads][H*W][d]. */
+void oracle_forward_pooled_explicit(const double* q, const double* k, const double* v,
+                                    const double* w, const double* bias,
+                                    int B, int heads, int H, int W, int d, int ks, int s,
+                                    int residual, int norm_mode, unsigned branches, double eps,
+                                    double* out)
+{
+    const int N = H * W;
+    const int Hq = (H + s - 1) / s, Wq = (W + s - 1) / s, Nq = Hq * Wq;
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* lin = (double*)malloc(sizeof(double) * d);
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < heads; ++h) {
+            const size_t kv = ((size_t)b * heads + h) * (size_t)N * d;
+            const size_t qo = ((size_t)b * heads + h) * (size_t)Nq * d;
+            oracle_l2_normalize(k + kv, N, d, eps, kh);
+            for (int t = 0; t < Nq; ++t) {
+                const double* qrow = q + qo + (size_t)t * d;
+                for (int c = 0; c < d; ++c) lin[c] = 0.0;
+                if (branches & ORACLE_BRANCH_LINEAR)
+                    explicit_row(qrow, kh, v + kv, N, d, norm_mode, eps, lin);
+                for (int c = 0; c < d; ++c) {
+                    double val = lin[c];
+                    if (branches & ORACLE_BRANCH_DWCONV)
+                        val += dwconv_at(v, w, bias, heads, H, W, d, ks, 0, b, h, s * (t / Wq),
+                                         s * (t % Wq), c);
+                    if (residual) val += qrow[c];
+                    out[qo + (size_t)t * d + c] = val;
+                }
+            }
+        }
+    free(kh);
+    free(lin);
+}
+
+/* The same with the reassociated state (any N). */
+void oracle_forward_pooled(const double* q, const double* k, const double* v,
+                           const double* w, const double* bias,
+                           int B, int heads, int H, int W, int d, int ks, int s,
+                           int residual, int norm_mode, unsigned branches, double eps, double* out)
+{
+    const int N = H * W;
+    const int Hq = (H + s - 1) / s, Wq = (W + s - 1) / s, Nq = Hq * Wq;
+    const int d1 = d + 1;
+    const int64_t units = (int64_t)B * heads;
+    double* state = (double*)malloc(sizeof(double) * (size_t)units * d1 * d1);
+    if (branches & ORACLE_BRANCH_LINEAR) oracle_state(k, v, B, heads, N, d, eps, state);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t u = 0; u < units; ++u) {
+        const int b = (int)(u / heads), h = (int)(u % heads);
+        const double* M = state + (size_t)u * d1 * d1;
+        double* qh = (double*)malloc(sizeof(double) * d);
+        for (int t = 0; t < Nq; ++t) {
+            const double* qrow = q + ((size_t)u * Nq + t) * d;
+            double* o = out + ((size_t)u * Nq + t) * d;
+            for (int c = 0; c < d; ++c) o[c] = 0.0;
+            if (branches & ORACLE_BRANCH_LINEAR) {
+                oracle_l2_normalize(qrow, 1, d, eps, qh);
+                double den = 0.5 * M[d * d1 + d];
+                for (int i = 0; i < d; ++i) den += qh[i] * M[i * d1 + d] / ORACLE_PI;
+                for (int j = 0; j < d; ++j) {
+                    double num = 0.5 * M[d * d1 + j];
+                    for (int i = 0; i < d; ++i) num += qh[i] * M[i * d1 + j] / ORACLE_PI;
+                    o[j] = (norm_mode == 0) ? num / den : num;
+                }
+            }
+            for (int c = 0; c < d; ++c) {
+                if (branches & ORACLE_BRANCH_DWCONV)
+                    o[c] += dwconv_at(v, w, bias, heads, H, W, d, ks, 0, b, h, s * (t / Wq),
+                                      s * (t % Wq), c);
+                if (residual) o[c] += qrow[c];
+            }
+        }
+        free(qh);
+    }
+    free(state);
+}
+
+/* ------------------------------------------------------------------------
  * Training-time companions of the layer (Sec. 3.2.2, Eq. 10) and the exact
  * angular kernel it approximates (Eq. 4-5), as O(N^2) attention.
  *

@@ -44,6 +44,9 @@ def lib():
         L.oracle_forward_explicit.argtypes = fwd + [_dp]
         L.oracle_forward.argtypes = fwd + [_dp]
         L.oracle_forward_explicit_rows.argtypes = fwd + [_ip, _ip, C.c_int64, _dp]
+        pooled = [_dp] * 5 + [C.c_int] * 9 + [C.c_uint, C.c_double, _dp]
+        L.oracle_forward_pooled_explicit.argtypes = pooled
+        L.oracle_forward_pooled.argtypes = pooled
         L.oracle_state.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _dp]
         L.oracle_softmax_probs.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_double,
                                            C.c_double, _dp]
@@ -160,6 +163,34 @@ def forward_explicit_rows(q, k, v, w, bias, grid_h, grid_w, units, tokens, norm=
     out = np.empty_like(out_sorted)
     out[order] = out_sorted
     return out
+
+
+def _pooled(fn, q, k, v, w, bias, grid_h, grid_w, pool, residual, norm, branches, eps):
+    q, k, v, w = _f64(q), _f64(k), _f64(v), _f64(w)
+    bias = None if bias is None else _f64(bias)
+    B, heads, N, d = k.shape
+    nq = -(-grid_h // pool) * -(-grid_w // pool)
+    assert v.shape == k.shape and N == grid_h * grid_w and q.shape == (B, heads, nq, d)
+    assert w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    out = np.empty(q.shape, dtype=np.float64)
+    fn(_p(q), _p(k), _p(v), _p(w), _p(bias), B, heads, grid_h, grid_w, d, w.shape[2], int(pool),
+       int(bool(residual)), int(norm), int(branches), float(eps), _p(out))
+    return out
+
+
+def forward_pooled_explicit(q, k, v, w, bias, grid_h, grid_w, pool=2, residual=True,
+                            norm=NORM_ROWSUM, branches=BRANCH_ALL, eps=DEFAULT_EPS):
+    """Downsampling layer by its definition: pooled queries on every pool-th row and column of
+    the grid of K and V, DWConv rows of those positions, optional residual query; small N."""
+    return _pooled(lib().oracle_forward_pooled_explicit, q, k, v, w, bias, grid_h, grid_w, pool,
+                   residual, norm, branches, eps)
+
+
+def forward_pooled(q, k, v, w, bias, grid_h, grid_w, pool=2, residual=True, norm=NORM_ROWSUM,
+                   branches=BRANCH_ALL, eps=DEFAULT_EPS):
+    """The same by the reassociated form; any N."""
+    return _pooled(lib().oracle_forward_pooled, q, k, v, w, bias, grid_h, grid_w, pool, residual,
+                   norm, branches, eps)
 
 
 def state(k, v, eps=DEFAULT_EPS):
