@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--pairwise", choices=("sparse", "angular"), default=None,
                     help="time castling_attn_pairwise (masked softmax branch of Eq. 10 / exact "
                          "angular-kernel attention) instead of the layer; MFMA roofline")
+    ap.add_argument("--downsample", action="store_true",
+                    help="the workload as a downsampling layer: queries pooled to every second "
+                         "row and column, residual query (dense layout)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three 256 MiB device-to-device copies: a kernel of known "
@@ -122,6 +125,9 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    nq = -(-wl.grid_h // 2) * -(-wl.grid_w // 2) if args.downsample else wl.N
+    if args.downsample and (args.layout != "dense" or args.pairwise):
+        sys.exit("bench.py: --downsample goes with the dense layout of the layer")
     # distinct seeded input sets, all resident before timing starts
     sets = []
     for s in range(args.sets):
@@ -135,6 +141,9 @@ def main():
             t["out"] = torch.empty((wl.B, wl.N, wl.heads * wl.d), dtype=x["q"].dtype, device=dev)
         else:
             t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+            if args.downsample:  # the pooled queries: as many rows of the drawn ones
+                x["q"] = x["q"][:, :, :nq].contiguous()
+                t["q"] = x["q"].to(dev)
             t["out"] = torch.empty_like(t["q"])
         sets.append(t)
         if s == 0:
@@ -152,6 +161,10 @@ def main():
         attn = binding.CastlingAttn.for_workload(
             wl, in_strides=binding.fused_qkv_strides(wl.heads, wl.N, wl.d),
             out_strides=binding.token_major_strides(wl.heads, wl.N, wl.d))
+    elif args.downsample:
+        attn = binding.CastlingAttn(binding.make_desc(
+            wl.B, wl.heads, wl.N, wl.d, wl.grid_h, wl.grid_w, wl.dw_kernel, wl.dtype,
+            flags=binding.FLAG_RESIDUAL_Q, q_pool=2))
     else:
         attn = binding.CastlingAttn.for_workload(wl)
     stream = torch.cuda.Stream()
@@ -222,12 +235,15 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = wl.tokens * args.steps / elapsed
     tensor_bytes = wl.elems * wl.itemsize
+    q_bytes = tensor_bytes * nq // wl.N  # Q and out have one row per query
+    layer_bytes = 2 * tensor_bytes + 2 * q_bytes
     if attn.num_launches() == 1:
         # the whole layer in one kernel: it reads Q, K, V once and writes out (4 tensors)
-        kernels = {"fused_forward": (4 * tensor_bytes, forward_ms)}
+        kernels = {"fused_forward": (layer_bytes, forward_ms)}
     else:
         # algorithmic bytes: apply reads Q and V and writes out (3 tensors); reduce reads K and V
-        kernels = {"apply": (3 * tensor_bytes, apply_ms), "reduce": (2 * tensor_bytes, reduce_ms)}
+        kernels = {"apply": (tensor_bytes + 2 * q_bytes, apply_ms),
+                   "reduce": (2 * tensor_bytes, reduce_ms)}
     dominant = max(kernels, key=lambda n: kernels[n][1])
     dom_bytes, dom_ms = kernels[dominant]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
@@ -238,8 +254,8 @@ def main():
         "algorithmic_bytes": dom_bytes, "kernel_ms": round(dom_ms, 5),
         "reduce_ms": round(reduce_ms, 5), "apply_ms": round(apply_ms, 5),
         "staged_step_ms": round(staged_ms, 5),
-        "layer_algorithmic_gbs_4tensor": round(4 * tensor_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "layer_frac_of_peak_4tensor": round(4 * tensor_bytes / (ms_per_step * 1e-3) / 1e9
+        "layer_algorithmic_gbs_4tensor": round(layer_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "layer_frac_of_peak_4tensor": round(layer_bytes / (ms_per_step * 1e-3) / 1e9
                                             / HBM_PEAK_GBS, 4),
         "d2d_copy_gbs_same_run": round(copy_gbs, 1),
     }
@@ -253,14 +269,15 @@ def main():
         nb = max(1, min(wl.B, int(wl.B * 20.0 / max(est_s, 1e-9))))
         xs = {n: inputs.to_f64(host0[n][:nb]) for n in ("q", "k", "v")}
         w64 = inputs.to_f64(host0["w"])
+        oracle_fwd = oracle.forward_pooled if args.downsample else oracle.forward
         c0 = time.perf_counter()
-        oracle.forward(xs["q"], xs["k"], xs["v"], w64, None, wl.grid_h, wl.grid_w)
+        oracle_fwd(xs["q"], xs["k"], xs["v"], w64, None, wl.grid_h, wl.grid_w)
         first = time.perf_counter() - c0
         # repeat whole passes up to about 10 s of CPU work (at most 200 passes)
         reps = max(1, min(200, int(10.0 / max(first, 1e-6))))
         c0 = time.perf_counter()
         for _ in range(reps):
-            oracle.forward(xs["q"], xs["k"], xs["v"], w64, None, wl.grid_h, wl.grid_w)
+            oracle_fwd(xs["q"], xs["k"], xs["v"], w64, None, wl.grid_h, wl.grid_w)
         c1 = time.perf_counter() - c0
         cpu_baseline = {
             "value": round(reps * nb * wl.N / c1, 1), "unit": "tokens/s",
@@ -280,7 +297,7 @@ def main():
         "dtype": wl.dtype if wl.dtype != "f32" else "f32", "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "d": wl.d, "N": wl.N,
                    "grid": [wl.grid_h, wl.grid_w], "dw_kernel": wl.dw_kernel,
-                   "layout": args.layout,
+                   "layout": args.layout, "queries_per_unit": nq,
                    "input_sets_rotated": len(sets), "reduce_splits": n_split,
                    "kernels_per_forward": launches},
         "roofline": roofline, "cpu_baseline": cpu_baseline,

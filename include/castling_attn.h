@@ -75,8 +75,12 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
 
 /* desc.flags.  KEEP_STATE: castling_attn_forward always leaves the fp32 state in the workspace
  * for castling_attn_get_state.  Without it a forward of a small problem does not spend memory
- * writes, or a launch, on a copy nobody reads.  castling_attn_reduce always leaves the state. */
-enum { CASTLING_FLAG_KEEP_STATE = 1 };
+ * writes, or a launch, on a copy nobody reads.  castling_attn_reduce always leaves the state.
+ * RESIDUAL_Q: the query as stored (not its unit row) is added to each output row after the
+ * normaliser -- the residual connection of the pooled query in downsampling attention layers
+ * (Sec. 3.1, attention designs; Table 1, last row).  Needs the linear branch
+ * (CASTLING_ERR_INVALID_ARG otherwise); runs on the vector-ALU kernels. */
+enum { CASTLING_FLAG_KEEP_STATE = 1, CASTLING_FLAG_RESIDUAL_Q = 2 };
 
 typedef struct {
     int32_t B, heads, N, d;   /* d: a multiple of 8, at most 128 */
@@ -96,6 +100,20 @@ typedef struct {
     int64_t out_stride_b, out_stride_h, out_stride_n;
     uint32_t flags;           /* bitmask of CASTLING_FLAG_* */
     int32_t extra_tokens;     /* tokens in front of the grid (class tokens), 0..64 */
+    /* Downsampling layers (Sec. 3.1: queries pooled after their projection, K and V on every
+     * token).  0 or 1: one query per token.  2: q and out hold Nq = ceil(grid_h/2) *
+     * ceil(grid_w/2) tokens per unit, row-major over that coarser grid; query (y, x) stands at
+     * position (2y, 2x) of the token grid, where its DWConv row is taken (a DWConv of stride 2;
+     * the paper does not say how M_DW of Eq. 9 shrinks).  The pooling operator itself runs
+     * before this library.  k, v keep N tokens and the in strides.  Runs on the vector-ALU
+     * kernels in pass 2; extra_tokens must be 0 (CASTLING_ERR_UNSUPPORTED otherwise, as for
+     * other values of q_pool, and for shapes whose tile of V exceeds the LDS of a block). */
+    int32_t q_pool;
+    int32_t reserved0;        /* must be 0 */
+    /* q_pool = 2: element strides of q (rules as above; all 0 = contiguous [B][heads][Nq][d]);
+     * the default of the out strides is then contiguous [B][heads][Nq][d] too.  Must be 0
+     * otherwise (q shares the in strides). */
+    int64_t q_stride_b, q_stride_h, q_stride_n;
 } castling_attn_desc_t;
 
 /* Host-only check of a descriptor (no GPU needed).  Sec. 3.2.1 fixes the shapes:

@@ -20,6 +20,7 @@ F32, BF16, F16 = 0, 1, 2
 NORM_ROWSUM, NORM_NONE = 0, 1
 BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
 FLAG_KEEP_STATE = 1
+FLAG_RESIDUAL_Q = 2
 
 EXPORTS = (
     "castling_attn_validate", "castling_attn_create", "castling_attn_forward",
@@ -38,7 +39,9 @@ class Desc(C.Structure):
                 ("eps", C.c_float),
                 ("in_stride_b", C.c_int64), ("in_stride_h", C.c_int64), ("in_stride_n", C.c_int64),
                 ("out_stride_b", C.c_int64), ("out_stride_h", C.c_int64),
-                ("out_stride_n", C.c_int64), ("flags", C.c_uint32), ("extra_tokens", C.c_int32)]
+                ("out_stride_n", C.c_int64), ("flags", C.c_uint32), ("extra_tokens", C.c_int32),
+                ("q_pool", C.c_int32), ("reserved0", C.c_int32),
+                ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_n", C.c_int64)]
 
 
 PAIR_SPARSE_SOFTMAX, PAIR_ANGULAR = 0, 1
@@ -112,15 +115,17 @@ def token_major_strides(heads, N, d):
 
 def make_desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm=NORM_ROWSUM,
               branches=BRANCH_ALL, eps=0.0, in_strides=None, out_strides=None, flags=0,
-              extra_tokens=0) -> Desc:
+              extra_tokens=0, q_pool=0, q_strides=None) -> Desc:
     """in_strides / out_strides: (batch, head, token) element strides of q, k, v and of out;
-    None = contiguous [B][heads][N][d]."""
+    None = contiguous [B][heads][N][d].  q_pool = 2: q and out hold the pooled queries of a
+    downsampling layer (q_strides: their strides, None = contiguous)."""
     if isinstance(io_dtype, str):
         io_dtype = {"f32": F32, "bf16": BF16, "f16": F16}[io_dtype]
     ins = tuple(in_strides) if in_strides is not None else (0, 0, 0)
     outs = tuple(out_strides) if out_strides is not None else (0, 0, 0)
+    qs = tuple(q_strides) if q_strides is not None else (0, 0, 0)
     return Desc(B, heads, N, d, grid_h, grid_w, dw_kernel, io_dtype, norm, branches, eps,
-                *ins, *outs, flags, extra_tokens)
+                *ins, *outs, flags, extra_tokens, q_pool, 0, *qs)
 
 
 def validate(desc: Desc) -> int:

@@ -22,6 +22,12 @@ struct ApplyParams {
     // index order while it loads them (small problems: saves the combine launch)
     int n_partials;
     int d_valid;  // features per head in memory (<= D: narrower heads are padded with zeros)
+    // Downsampling layers (pooled queries, Sec. 3.1): grid_h x grid_w above is the grid of the
+    // queries and of out, q has strides of its own, and query (y, x) stands at position
+    // (S*y, S*x) of the vgrid_h x vgrid_w grid of V (S = the kernel's stride; S = 1: same grid).
+    TensorStrides qs;
+    int vgrid_h, vgrid_w;
+    int residual_q;  // 1: the query as stored is added to the result (residual connection)
 };
 
 constexpr int kApplyTH = 4;   // tile rows
@@ -30,7 +36,7 @@ constexpr int kApplyTokens = kApplyTH * kApplyTW;
 constexpr int kQtStride = kApplyTokens + 4;  // floats; keeps float4 rows aligned
 
 // Dynamic LDS the kernel needs, in bytes.
-template <typename T, int D, int KS>
+template <typename T, int D, int KS, int S = 1>
 constexpr size_t apply_generic_lds_bytes()
 {
     using L = StateLayout<D>;
@@ -38,7 +44,7 @@ constexpr size_t apply_generic_lds_bytes()
     const size_t phase_a =
         sizeof(T) == 4 ? sizeof(float) * (L::SIZE + D * kQtStride)
                        : 4 * (static_cast<size_t>(D / 2) * D + D / 2 + D + (D / 2) * kQtStride + kApplyTokens);
-    const size_t halo = sizeof(T) * (kApplyTH + KS - 1) * (kApplyTW + KS - 1) * D;
+    const size_t halo = sizeof(T) * (S * (kApplyTH - 1) + KS) * (S * (kApplyTW - 1) + KS) * D;
     const size_t phase_b = ((halo + 15) / 16) * 16 + sizeof(float) * KS * KS * D;
     return phase_a > phase_b ? phase_a : phase_b;
 }
@@ -47,8 +53,8 @@ constexpr size_t apply_generic_lds_bytes()
 // the grid) of unit `unit`; thread (tt, tj) = (tid / 16, tid % 16) owns tokens
 // (row tt/4, columns 4*(tt%4)..+3) and channels tj*D/16..+D/16-1.  `state`: the unit's state
 // record(s), see ApplyParams::n_partials (global memory or LDS).  lds_raw: the block's dynamic
-// LDS of apply_generic_lds_bytes<T, D, KS>() bytes.
-template <typename T, int D, int KS>
+// LDS of apply_generic_lds_bytes<T, D, KS, S>() bytes.  S: stride of the queries on the grid of V.
+template <typename T, int D, int KS, int S = 1>
 __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, const T* __restrict__ v,
                                                    const T* __restrict__ w,
                                                    const T* __restrict__ bias, const float* state,
@@ -60,8 +66,8 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
     constexpr int LPR = D / VEC;
     constexpr int RJ = D / 16;  // channels per thread
     constexpr int RAD = KS / 2;
-    constexpr int HH = kApplyTH + KS - 1;  // halo tile rows
-    constexpr int HW = kApplyTW + KS - 1;  // halo tile columns
+    constexpr int HH = S * (kApplyTH - 1) + KS;  // halo tile rows
+    constexpr int HW = S * (kApplyTW - 1) + KS;  // halo tile columns
     using L = StateLayout<D>;
 
     const int tid = threadIdx.x;
@@ -71,6 +77,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
     const int tt = tid / 16, tj = tid % 16;
     const int my_row = tt / 4, my_col0 = (tt % 4) * 4;
     const long long in_off = unit_offset(unit, heads, p.in);
+    const long long q_off = unit_offset(unit, heads, p.qs);
     const long long out_off = unit_offset(unit, heads, p.out);
 
     float res[4][RJ];
@@ -89,12 +96,12 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
     T w_pre[kPrefetch ? W_PIECES : 1];
     auto halo_piece = [&](int idx) {
         const int tok = idx / LPR, part = idx % LPR;
-        const int y = ty0 - RAD + tok / HW, x = tx0 - RAD + tok % HW;
+        const int y = S * ty0 - RAD + tok / HW, x = S * tx0 - RAD + tok % HW;
         uint4 val = make_uint4(0u, 0u, 0u, 0u);
-        if (idx < HH * HW * LPR && part * VEC < p.d_valid && y >= 0 && y < p.grid_h && x >= 0 &&
-            x < p.grid_w)
+        if (idx < HH * HW * LPR && part * VEC < p.d_valid && y >= 0 && y < p.vgrid_h && x >= 0 &&
+            x < p.vgrid_w)
             val = *reinterpret_cast<const uint4*>(
-                v + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + part * VEC);
+                v + in_off + (static_cast<long long>(y) * p.vgrid_w + x) * p.in.n + part * VEC);
         return val;
     };
     if constexpr (kPrefetch) {
@@ -133,7 +140,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
                 const int y = ty0 + tl / kApplyTW, x = tx0 + tl % kApplyTW;
                 float qx[VEC];
                 if (y < p.grid_h && x < p.grid_w && lcol < p.d_valid) {
-                    IO<T>::load16(q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol, qx);
+                    IO<T>::load16(q + q_off + (static_cast<long long>(y) * p.grid_w + x) * p.qs.n + lcol, qx);
                 } else {
     #pragma unroll
                     for (int e = 0; e < VEC; ++e) qx[e] = 0.f;
@@ -208,7 +215,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
                 uint4 raw = make_uint4(0u, 0u, 0u, 0u);
                 if (y < p.grid_h && x < p.grid_w && lcol < p.d_valid)
                     raw = *reinterpret_cast<const uint4*>(
-                        q + in_off + (static_cast<long long>(y) * p.grid_w + x) * p.in.n + lcol);
+                        q + q_off + (static_cast<long long>(y) * p.grid_w + x) * p.qs.n + lcol);
                 const uint32_t rw[4] = {raw.x, raw.y, raw.z, raw.w};
                 float ss = 0.f;
 #pragma unroll
@@ -295,15 +302,15 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             for (int dx = 0; dx < KS; ++dx)
 #pragma unroll
                 for (int j = 0; j < RJ; ++j) wr[dx][j] = wt[(dy * KS + dx) * D + tj * RJ + j];
-            const T* row = vh + (static_cast<size_t>(my_row + dy) * HW + my_col0) * D + tj * RJ;
+            const T* row = vh + (static_cast<size_t>(S * my_row + dy) * HW + S * my_col0) * D + tj * RJ;
 #pragma unroll
-            for (int xx = 0; xx < KS + 3; ++xx) {
+            for (int xx = 0; xx < KS + 3 * S; ++xx) {
                 float vin[RJ];
 #pragma unroll
                 for (int j = 0; j < RJ; ++j) vin[j] = IO<T>::to_f32(row[xx * D + j]);
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
-                    const int dx = xx - t;
+                    const int dx = xx - S * t;
                     if (dx >= 0 && dx < KS) {
 #pragma unroll
                         for (int j = 0; j < RJ; ++j) dw[t][j] = fmaf(wr[dx][j], vin[j], dw[t][j]);
@@ -326,6 +333,11 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             if (x < p.grid_w && tj * RJ < p.d_valid) {  // (d_valid is a multiple of the piece)
                 T* o = out + out_off + (static_cast<long long>(y) * p.grid_w + x) * p.out.n + tj * RJ;
                 __attribute__((aligned(16))) T tmp[RJ];
+                if (p.residual_q) {
+                    const T* qr = q + q_off + (static_cast<long long>(y) * p.grid_w + x) * p.qs.n + tj * RJ;
+#pragma unroll
+                    for (int j = 0; j < RJ; ++j) res[t][j] += IO<T>::to_f32(qr[j]);
+                }
 #pragma unroll
                 for (int j = 0; j < RJ; ++j) tmp[j] = IO<T>::from_f32(res[t][j]);
                 constexpr int BYTES = sizeof(T) * RJ;
@@ -347,7 +359,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
 }
 
 // grid = (tiles_x * tiles_y, units), block = 256, dynamic LDS = apply_generic_lds_bytes.
-template <typename T, int D, int KS>
+template <typename T, int D, int KS, int S = 1>
 __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict__ q,
                                                              const T* __restrict__ v,
                                                              const T* __restrict__ w,
@@ -358,7 +370,7 @@ __global__ __launch_bounds__(256) void apply_generic_kernel(const T* __restrict_
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     const int unit = blockIdx.y;
-    apply_generic_tile<T, D, KS>(q, v, w, bias,
+    apply_generic_tile<T, D, KS, S>(q, v, w, bias,
                                  state + static_cast<size_t>(unit) * p.n_partials * StateLayout<D>::SIZE,
                                  out, heads, p, unit, blockIdx.x, lds_raw);
 }

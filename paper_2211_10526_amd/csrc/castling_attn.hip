@@ -39,6 +39,8 @@ int hip_fail(hipError_t e)
         if (e_ != hipSuccess) return hip_fail(e_); \
     } while (0)
 
+constexpr size_t kMaxLdsBytes = 160 * 1024;  // LDS of one compute unit
+
 size_t dtype_size(int dt) { return dt == CASTLING_F32 ? 4 : 2; }
 
 // f(T{}, integral_constant<int, D>{}) for the handle's I/O type and head width
@@ -76,7 +78,12 @@ struct castling_attn {
     int n_split;
     int chunk;
     TensorStrides in_st, out_st;  // element strides of q/k/v and of out (defaults resolved)
+    TensorStrides q_st;           // of q: in_st, or its own where the queries are pooled
     size_t in_span, out_span;     // bytes from the first to one past the last element addressed
+    size_t q_span;
+    int pool;                     // stride of the queries on the token grid (1 or 2)
+    int qgrid_h, qgrid_w, nq;     // grid and count of the queries (= of the rows of out)
+    bool residual_q;
     int dpad;           // width the kernels run at: 16 / 32 / 64 / 128, narrower heads zero-padded
     int state_size;     // floats per unit (of width dpad)
     bool mfma_reduce;   // bf16 / fp16, d = 32 or 64: K_hat^T V on the matrix cores
@@ -237,14 +244,15 @@ int do_reduce(castling_attn* h, const void* k, const void* v, const void* w, hip
 
 // ------------------------------------------------------------------ apply
 // launch = false: set the kernel's LDS attribute and record its LDS size (create time)
-template <typename T, int D, int KS>
+template <typename T, int D, int KS, int S>
 hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const void* v,
                          const void* w, const void* bias, void* out, hipStream_t s)
 {
-    constexpr size_t lds = apply_generic_lds_bytes<T, D, KS>();
+    constexpr size_t lds = apply_generic_lds_bytes<T, D, KS, S>();
     if (!launch) {
         h->apply_lds = lds;
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_generic_kernel<T, D, KS>),
+        if (lds > kMaxLdsBytes) return hipSuccess;  // create reports the shape as unsupported
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&apply_generic_kernel<T, D, KS, S>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize,
                                    static_cast<int>(lds));
     }
@@ -262,8 +270,12 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     p.out = h->out_st;
     p.n_partials = h->partials_pending ? h->n_split : 1;
     p.d_valid = d.d;
+    p.qs = h->q_st;
+    p.vgrid_h = S == 1 ? p.grid_h : d.grid_h;
+    p.vgrid_w = S == 1 ? p.grid_w : d.grid_w;
+    p.residual_q = h->residual_q;
     const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
-    hipLaunchKernelGGL((apply_generic_kernel<T, D, KS>), dim3(p.tiles_x * tiles_y, h->units),
+    hipLaunchKernelGGL((apply_generic_kernel<T, D, KS, S>), dim3(p.tiles_x * tiles_y, h->units),
                        dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
                        static_cast<const T*>(w), static_cast<const T*>(bias),
                        h->partials_pending ? h->partial : h->state, static_cast<T*>(out), d.heads, p);
@@ -347,12 +359,21 @@ template <typename T, int D>
 hipError_t apply_generic_ks(castling_attn* h, bool launch, const void* q, const void* v,
                             const void* w, const void* bias, void* out, hipStream_t s)
 {
+    if (h->pool == 2) {
+        switch (h->view.ks) {
+            case 1: return apply_generic<T, D, 1, 2>(h, launch, q, v, w, bias, out, s);
+            case 3: return apply_generic<T, D, 3, 2>(h, launch, q, v, w, bias, out, s);
+            case 5: return apply_generic<T, D, 5, 2>(h, launch, q, v, w, bias, out, s);
+            case 7: return apply_generic<T, D, 7, 2>(h, launch, q, v, w, bias, out, s);
+            default: return apply_generic<T, D, 9, 2>(h, launch, q, v, w, bias, out, s);
+        }
+    }
     switch (h->view.ks) {
-        case 1: return apply_generic<T, D, 1>(h, launch, q, v, w, bias, out, s);
-        case 3: return apply_generic<T, D, 3>(h, launch, q, v, w, bias, out, s);
-        case 5: return apply_generic<T, D, 5>(h, launch, q, v, w, bias, out, s);
-        case 7: return apply_generic<T, D, 7>(h, launch, q, v, w, bias, out, s);
-        default: return apply_generic<T, D, 9>(h, launch, q, v, w, bias, out, s);
+        case 1: return apply_generic<T, D, 1, 1>(h, launch, q, v, w, bias, out, s);
+        case 3: return apply_generic<T, D, 3, 1>(h, launch, q, v, w, bias, out, s);
+        case 5: return apply_generic<T, D, 5, 1>(h, launch, q, v, w, bias, out, s);
+        case 7: return apply_generic<T, D, 7, 1>(h, launch, q, v, w, bias, out, s);
+        default: return apply_generic<T, D, 9, 1>(h, launch, q, v, w, bias, out, s);
     }
 }
 
@@ -383,7 +404,7 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
     const castling_attn_desc_t& d = h->desc;
     const int extra = d.extra_tokens;
     const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const ApplyView grid_view = {d.grid_h, d.grid_w, d.dw_kernel, d.branches};
+    const ApplyView grid_view = {h->qgrid_h, h->qgrid_w, d.dw_kernel, d.branches};
     const ApplyView extra_view = {1, extra, 1, CASTLING_BRANCH_LINEAR};
     h->view = grid_view;
     if (!launch) {
@@ -512,7 +533,7 @@ int check_apply_args(castling_attn_t h, const void* q, const void* v, const void
     if ((lin && !q) || (dw && (!v || !dw_weight))) return CASTLING_ERR_INVALID_ARG;
     if (misaligned(out) || (lin && misaligned(q)) || (dw && (misaligned(v) || misaligned(dw_weight))))
         return CASTLING_ERR_INVALID_ARG;
-    if ((lin && overlaps(out, h->out_span, q, h->in_span)) ||
+    if ((lin && overlaps(out, h->out_span, q, h->q_span)) ||
         (dw && overlaps(out, h->out_span, v, h->in_span)))
         return CASTLING_ERR_ALIAS;
     return CASTLING_OK;
@@ -548,7 +569,8 @@ int castling_attn_validate(const castling_attn_desc_t* d)
         return CASTLING_ERR_INVALID_ARG;
     if (d->branches & ~static_cast<uint32_t>(CASTLING_BRANCH_ALL)) return CASTLING_ERR_INVALID_ARG;
     if (!(d->eps >= 0.0f)) return CASTLING_ERR_INVALID_ARG;
-    if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE)) return CASTLING_ERR_INVALID_ARG;
+    if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE | CASTLING_FLAG_RESIDUAL_Q))
+        return CASTLING_ERR_INVALID_ARG;
     if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16 && d->io_dtype != CASTLING_F16)
         return CASTLING_ERR_UNSUPPORTED;
     if (d->d % 8 != 0 || d->d > 128) return CASTLING_ERR_UNSUPPORTED;
@@ -557,9 +579,17 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     if (static_cast<int64_t>(d->B) * d->heads > 65535) return CASTLING_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(d->B) * d->heads * d->N * d->d > (int64_t(1) << 40))
         return CASTLING_ERR_UNSUPPORTED;
+    if (d->q_pool < 0 || d->reserved0 != 0) return CASTLING_ERR_INVALID_ARG;
+    if (d->q_pool > 2 || (d->q_pool == 2 && d->extra_tokens != 0)) return CASTLING_ERR_UNSUPPORTED;
+    if (d->q_pool != 2 && (d->q_stride_b != 0 || d->q_stride_h != 0 || d->q_stride_n != 0))
+        return CASTLING_ERR_INVALID_ARG;
+    if ((d->flags & CASTLING_FLAG_RESIDUAL_Q) && d->branches != 0 &&
+        !(d->branches & CASTLING_BRANCH_LINEAR))
+        return CASTLING_ERR_INVALID_ARG;
     const int64_t es = static_cast<int64_t>(dtype_size(d->io_dtype));
-    const int64_t sets[2][3] = {{d->in_stride_b, d->in_stride_h, d->in_stride_n},
-                                {d->out_stride_b, d->out_stride_h, d->out_stride_n}};
+    const int64_t sets[3][3] = {{d->in_stride_b, d->in_stride_h, d->in_stride_n},
+                                {d->out_stride_b, d->out_stride_h, d->out_stride_n},
+                                {d->q_stride_b, d->q_stride_h, d->q_stride_n}};
     for (const auto& s : sets) {
         const bool dense = s[0] == 0 && s[1] == 0 && s[2] == 0;  // contiguous default
         if (!dense) {
@@ -598,17 +628,29 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->apply_ready = false;
     {
         const castling_attn_desc_t& d = h->desc;
-        const TensorStrides dense = {static_cast<long long>(d.heads) * d.N * d.d,
-                                     static_cast<long long>(d.N) * d.d, d.d};
-        h->in_st = d.in_stride_n ? TensorStrides{d.in_stride_b, d.in_stride_h, d.in_stride_n} : dense;
-        h->out_st =
-            d.out_stride_n ? TensorStrides{d.out_stride_b, d.out_stride_h, d.out_stride_n} : dense;
-        auto span = [&](const TensorStrides& s) {
-            return static_cast<size_t>((d.B - 1) * s.b + (d.heads - 1) * s.h + (d.N - 1) * s.n + d.d) *
+        h->pool = d.q_pool == 2 ? 2 : 1;
+        h->qgrid_h = (d.grid_h + h->pool - 1) / h->pool;
+        h->qgrid_w = (d.grid_w + h->pool - 1) / h->pool;
+        h->nq = h->pool == 1 ? d.N : h->qgrid_h * h->qgrid_w;
+        h->residual_q = (d.flags & CASTLING_FLAG_RESIDUAL_Q) != 0;
+        auto dense = [&](int n) {
+            return TensorStrides{static_cast<long long>(d.heads) * n * d.d,
+                                 static_cast<long long>(n) * d.d, d.d};
+        };
+        h->in_st = d.in_stride_n ? TensorStrides{d.in_stride_b, d.in_stride_h, d.in_stride_n}
+                                 : dense(d.N);
+        h->out_st = d.out_stride_n ? TensorStrides{d.out_stride_b, d.out_stride_h, d.out_stride_n}
+                                   : dense(h->nq);
+        h->q_st = h->pool == 1 ? h->in_st
+                  : d.q_stride_n ? TensorStrides{d.q_stride_b, d.q_stride_h, d.q_stride_n}
+                                 : dense(h->nq);
+        auto span = [&](const TensorStrides& s, int n) {
+            return static_cast<size_t>((d.B - 1) * s.b + (d.heads - 1) * s.h + (n - 1) * s.n + d.d) *
                    dtype_size(d.io_dtype);
         };
-        h->in_span = span(h->in_st);
-        h->out_span = span(h->out_st);
+        h->in_span = span(h->in_st, d.N);
+        h->out_span = span(h->out_st, h->nq);
+        h->q_span = span(h->q_st, h->nq);
     }
     h->dpad = desc->d <= 16 ? 16 : desc->d <= 32 ? 32 : desc->d <= 64 ? 64 : 128;
     h->state_size = h->dpad * h->dpad + 2 * h->dpad;
@@ -619,14 +661,16 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
                             !(force && force[0] == '1');
     h->half16 = desc->io_dtype == CASTLING_F16;
     h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
-    h->mfma_apply = allow_mfma && desc->d == 64;
+    // pooled or residual queries: pass 2 on the vector-ALU kernel (pass 1 is the same work)
+    const bool plain_q = h->pool == 1 && !h->residual_q;
+    h->mfma_apply = allow_mfma && desc->d == 64 && plain_q;
     h->apply_units = h->units;
     h->apply_heads = desc->heads;
     h->apply_in = h->in_st;
     h->apply_out = h->out_st;
     h->in_skew = h->out_skew = 0;
     h->pair = h->pair_reduce = false;
-    if (allow_mfma && desc->d == 32 && desc->heads % 2 == 0) {
+    if (allow_mfma && desc->d == 32 && desc->heads % 2 == 0 && plain_q) {
         // two neighbouring heads of 32 channels as one unit of 64 for pass 2: the second half of
         // a token row lies one head stride further on instead of 64 bytes
         const long long in_skew = h->in_st.h * 2 - 64, out_skew = h->out_st.h * 2 - 64;
@@ -805,12 +849,13 @@ int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* para
                    !(params->scale == params->scale) || (params->normalize & ~1)))
         return CASTLING_ERR_INVALID_ARG;
     if (kept && (reinterpret_cast<uintptr_t>(kept) & 7u)) return CASTLING_ERR_INVALID_ARG;
-    if (overlaps(out, h->out_span, q, h->in_span) || overlaps(out, h->out_span, k, h->in_span) ||
+    if (overlaps(out, h->out_span, q, h->q_span) || overlaps(out, h->out_span, k, h->in_span) ||
         overlaps(out, h->out_span, v, h->in_span))
         return CASTLING_ERR_ALIAS;
     const castling_attn_desc_t& d = h->desc;
     const bool half = d.io_dtype == CASTLING_F16;
-    if ((d.io_dtype != CASTLING_BF16 && !half) || d.d != 64) return CASTLING_ERR_UNSUPPORTED;
+    if ((d.io_dtype != CASTLING_BF16 && !half) || d.d != 64 || h->pool != 1)
+        return CASTLING_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     PairParams p = {};
     p.N = d.N;

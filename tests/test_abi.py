@@ -50,7 +50,7 @@ def test_validate_accepts_benchmark_workloads():
     ("io_dtype", 7, b.ERR_UNSUPPORTED),
     ("norm", 2, b.ERR_INVALID_ARG), ("branches", 8, b.ERR_INVALID_ARG),
     ("eps", -1.0, b.ERR_INVALID_ARG), ("eps", float("nan"), b.ERR_INVALID_ARG),
-    ("flags", 2, b.ERR_INVALID_ARG),
+    ("flags", 8, b.ERR_INVALID_ARG),
 ])
 def test_validate_rejects(field, value, status):
     d = good()
@@ -89,6 +89,30 @@ def test_validate_strides():
     assert b.validate(b.make_desc(1, 1, 1 << 24, 64, 4096, 4096, 3, "bf16")) == b.OK
     # pass 2 counts 4 x 16 pieces of the grid in 32 bits: 65535 units of a 262144 x 1 grid
     assert b.validate(b.make_desc(255, 257, 1 << 18, 16, 1 << 18, 1, 3, "bf16")) == b.ERR_UNSUPPORTED
+
+
+def test_validate_downsampling_fields():
+    mk = lambda **kw: b.make_desc(2, 4, 196, 64, 14, 14, 3, "bf16", **kw)
+    assert C.sizeof(b.Desc) == 136
+    assert b.validate(mk(q_pool=1)) == b.OK
+    assert b.validate(mk(q_pool=2, flags=b.FLAG_RESIDUAL_Q)) == b.OK
+    assert b.validate(mk(q_pool=2, q_strides=(49 * 4 * 72, 72, 4 * 72))) == b.OK
+    assert b.validate(mk(q_pool=3)) == b.ERR_UNSUPPORTED
+    assert b.validate(mk(q_pool=-1)) == b.ERR_INVALID_ARG
+    # pooled queries and class tokens together are not covered
+    assert b.validate(b.make_desc(2, 4, 197, 64, 14, 14, 3, "bf16", extra_tokens=1, q_pool=2)) \
+        == b.ERR_UNSUPPORTED
+    # q has strides of its own only where it is pooled; they follow the rules of the others
+    assert b.validate(mk(q_strides=(49 * 4 * 64, 64, 4 * 64))) == b.ERR_INVALID_ARG
+    assert b.validate(mk(q_pool=2, q_strides=(49 * 4 * 64, 60, 4 * 64))) == b.ERR_INVALID_ARG
+    assert b.validate(mk(q_pool=2, q_strides=(49 * 4 * 64, 64, 32))) == b.ERR_INVALID_ARG
+    # the residual query belongs to the attention branch
+    assert b.validate(mk(flags=b.FLAG_RESIDUAL_Q, branches=b.BRANCH_DWCONV)) == b.ERR_INVALID_ARG
+    assert b.validate(mk(flags=b.FLAG_RESIDUAL_Q, branches=b.BRANCH_LINEAR)) == b.OK
+    assert b.validate(mk(flags=4)) == b.ERR_INVALID_ARG
+    d = mk()
+    d.reserved0 = 1
+    assert b.validate(d) == b.ERR_INVALID_ARG
 
 
 def test_validate_null_and_strerror():
