@@ -412,6 +412,207 @@ void oracle_forward_pooled(const double* q, const double* k, const double* v,
 }
 
 /* ------------------------------------------------------------------------
+ * Backward pass of the layer: the gradients of a scalar loss with respect to q, k, v, the
+ * DWConv filters and their bias, given g = dLoss/dout.  The paper trains the layer (Sec. 4.1)
+ * and prints no gradient formulas: these are the derivatives of the forward definition
+ * above (Eq. 3, 8, 9 with the same readings), by the chain rule.
+ *
+ *   x_hat = x / max(|x|, eps)  =>  dx = (dx_hat - x_hat (x_hat . dx_hat)) / |x|   if |x| >= eps,
+ *                                  dx = dx_hat / eps                             otherwise
+ *   A_tj = 1/2 + q_hat_t . k_hat_j / pi,  r_t = sum_j A_tj,  lin_t = sum_j A_tj v_j [/ r_t]
+ *   dLoss/dA_tj = (g_t . v_j - g_t . lin_t) / r_t   (normalised)    or   g_t . v_j   (not)
+ *
+ * dw [heads][d][ks][ks] and dbias [heads][d] (may be NULL) are sums over the batch.
+ * residual != 0: the forward added q_t to out_t, so dq_t gains g_t.
+ * ---------------------------------------------------------------------- */
+
+/* J^T applied to a gradient with respect to the unit row of x. */
+static void normalize_backward(const double* x, const double* dxh, int d, double eps, double* dx)
+{
+    double ss = 0.0;
+    for (int c = 0; c < d; ++c) ss += x[c] * x[c];
+    const double nrm = sqrt(ss);
+    if (nrm < eps) {
+        for (int c = 0; c < d; ++c) dx[c] = dxh[c] / eps;
+        return;
+    }
+    double dot = 0.0;
+    for (int c = 0; c < d; ++c) dot += (x[c] / nrm) * dxh[c];
+    for (int c = 0; c < d; ++c) dx[c] = (dxh[c] - (x[c] / nrm) * dot) / nrm;
+}
+
+/* The DWConv term's share: dv, dw, dbias gain their sums over the grid tokens of every unit. */
+static void dwconv_backward(const double* v, const double* w, const double* g,
+                            int B, int heads, int H, int W, int d, int ks, int extra,
+                            double* dv, double* dw, double* dbias)
+{
+    const int r = ks / 2;
+    const size_t N = (size_t)extra + (size_t)H * W;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < heads; ++h) {
+            const size_t base = ((size_t)b * heads + h) * N * d;
+            for (int y = 0; y < H; ++y)
+                for (int x = 0; x < W; ++x) {
+                    const double* gt = g + base + ((size_t)extra + (size_t)y * W + x) * d;
+                    for (int c = 0; c < d; ++c) {
+                        if (dbias) dbias[h * d + c] += gt[c];
+                        for (int dy = 0; dy < ks; ++dy)
+                            for (int dx = 0; dx < ks; ++dx) {
+                                const int yy = y + dy - r, xx = x + dx - r;
+                                if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
+                                const size_t src = base + ((size_t)extra + (size_t)yy * W + xx) * d + c;
+                                const size_t wi = (((size_t)h * d + c) * ks + dy) * ks + dx;
+                                dv[src] += w[wi] * gt[c];
+                                dw[wi] += gt[c] * v[src];
+                            }
+                    }
+                }
+        }
+}
+
+/* By the definition: explicit N x N similarity, O(N^2 d) per head. */
+void oracle_backward_explicit(const double* q, const double* k, const double* v, const double* w,
+                              const double* g, int B, int heads, int H, int W, int d, int ks,
+                              int norm_mode, unsigned branches, double eps, int extra, int residual,
+                              double* dq, double* dk, double* dv, double* dw, double* dbias)
+{
+    const int N = extra + H * W;
+    const size_t total = (size_t)B * heads * N * d;
+    memset(dq, 0, sizeof(double) * total);
+    memset(dk, 0, sizeof(double) * total);
+    memset(dv, 0, sizeof(double) * total);
+    memset(dw, 0, sizeof(double) * (size_t)heads * d * ks * ks);
+    if (dbias) memset(dbias, 0, sizeof(double) * (size_t)heads * d);
+    double* qh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* dkh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* A = (double*)malloc(sizeof(double) * N);
+    double* lin = (double*)malloc(sizeof(double) * d);
+    double* dqh = (double*)malloc(sizeof(double) * d);
+    for (int64_t u = 0; u < (int64_t)B * heads; ++u) {
+        const size_t base = (size_t)u * N * d;
+        if (!(branches & ORACLE_BRANCH_LINEAR)) break;
+        oracle_l2_normalize(q + base, N, d, eps, qh);
+        oracle_l2_normalize(k + base, N, d, eps, kh);
+        memset(dkh, 0, sizeof(double) * (size_t)N * d);
+        for (int t = 0; t < N; ++t) {
+            const double* gt = g + base + (size_t)t * d;
+            double r = 0.0;
+            for (int c = 0; c < d; ++c) lin[c] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                double x = 0.0;
+                for (int c = 0; c < d; ++c) x += qh[(size_t)t * d + c] * kh[(size_t)j * d + c];
+                A[j] = 0.5 + x / ORACLE_PI;
+                r += A[j];
+                for (int c = 0; c < d; ++c) lin[c] += A[j] * v[base + (size_t)j * d + c];
+            }
+            const double scale = (norm_mode == 0) ? 1.0 / r : 1.0;
+            double g_lin = 0.0;  /* g_t . lin_t of the normalised form */
+            for (int c = 0; c < d; ++c) g_lin += gt[c] * lin[c] * scale;
+            for (int c = 0; c < d; ++c) dqh[c] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                double g_v = 0.0;
+                for (int c = 0; c < d; ++c) g_v += gt[c] * v[base + (size_t)j * d + c];
+                const double dA = (norm_mode == 0) ? (g_v - g_lin) / r : g_v;
+                for (int c = 0; c < d; ++c) {
+                    dv[base + (size_t)j * d + c] += A[j] * scale * gt[c];
+                    dqh[c] += dA * kh[(size_t)j * d + c] / ORACLE_PI;
+                    dkh[(size_t)j * d + c] += dA * qh[(size_t)t * d + c] / ORACLE_PI;
+                }
+            }
+            normalize_backward(q + base + (size_t)t * d, dqh, d, eps, dq + base + (size_t)t * d);
+        }
+        for (int j = 0; j < N; ++j)
+            normalize_backward(k + base + (size_t)j * d, dkh + (size_t)j * d, d, eps,
+                               dk + base + (size_t)j * d);
+    }
+    if (branches & ORACLE_BRANCH_DWCONV)
+        dwconv_backward(v, w, g, B, heads, H, W, d, ks, extra, dv, dw, dbias);
+    if (residual)
+        for (size_t i = 0; i < total; ++i) dq[i] += g[i];
+    free(qh); free(kh); free(dkh); free(A); free(lin); free(dqh);
+}
+
+/* The same through the reassociated state (any N): with a_t = dLoss/dnum_t and
+ * b_t = dLoss/dden_t of Eq. 3's numerator and denominator,
+ *   dq_hat_t = (S a_t + ksum b_t) / pi,   S' = sum_t q_hat_t^T a_t,   kb' = sum_t q_hat_t b_t,
+ *   dv_j = k_hat_j S' / pi + (sum_t a_t) / 2,   dk_hat_j = (S' v_j + kb') / pi.            */
+void oracle_backward(const double* q, const double* k, const double* v, const double* w,
+                     const double* g, int B, int heads, int H, int W, int d, int ks,
+                     int norm_mode, unsigned branches, double eps, int extra, int residual,
+                     double* dq, double* dk, double* dv, double* dw, double* dbias)
+{
+    const int N = extra + H * W;
+    const int d1 = d + 1;
+    const int64_t units = (int64_t)B * heads;
+    const size_t total = (size_t)units * N * d;
+    memset(dq, 0, sizeof(double) * total);
+    memset(dk, 0, sizeof(double) * total);
+    memset(dv, 0, sizeof(double) * total);
+    memset(dw, 0, sizeof(double) * (size_t)heads * d * ks * ks);
+    if (dbias) memset(dbias, 0, sizeof(double) * (size_t)heads * d);
+    if (branches & ORACLE_BRANCH_LINEAR) {
+        double* state = (double*)malloc(sizeof(double) * (size_t)units * d1 * d1);
+        oracle_state(k, v, B, heads, N, d, eps, state);
+#pragma omp parallel for schedule(dynamic, 1)
+        for (int64_t u = 0; u < units; ++u) {
+            const size_t base = (size_t)u * N * d;
+            const double* M = state + (size_t)u * d1 * d1;
+            double* S2 = (double*)calloc((size_t)d * d + 2 * (size_t)d, sizeof(double));
+            double* kb2 = S2 + (size_t)d * d;
+            double* va2 = kb2 + d;
+            double* tmp = (double*)malloc(sizeof(double) * 4 * (size_t)d);
+            double *xh = tmp, *a = tmp + d, *dxh = tmp + 2 * d, *lin = tmp + 3 * d;
+            for (int t = 0; t < N; ++t) {
+                const double* gt = g + base + (size_t)t * d;
+                oracle_l2_normalize(q + base + (size_t)t * d, 1, d, eps, xh);
+                double den = 0.5 * M[d * d1 + d];
+                for (int i = 0; i < d; ++i) den += xh[i] * M[i * d1 + d] / ORACLE_PI;
+                double bt = 0.0;
+                for (int j = 0; j < d; ++j) {
+                    double num = 0.5 * M[d * d1 + j];
+                    for (int i = 0; i < d; ++i) num += xh[i] * M[i * d1 + j] / ORACLE_PI;
+                    lin[j] = (norm_mode == 0) ? num / den : num;
+                    a[j] = (norm_mode == 0) ? gt[j] / den : gt[j];
+                    if (norm_mode == 0) bt -= gt[j] * lin[j] / den;
+                }
+                for (int i = 0; i < d; ++i) {
+                    double s = M[i * d1 + d] * bt;
+                    for (int j = 0; j < d; ++j) s += M[i * d1 + j] * a[j];
+                    dxh[i] = s / ORACLE_PI;
+                    for (int j = 0; j < d; ++j) S2[(size_t)i * d + j] += xh[i] * a[j];
+                    kb2[i] += xh[i] * bt;
+                }
+                for (int j = 0; j < d; ++j) va2[j] += a[j];
+                normalize_backward(q + base + (size_t)t * d, dxh, d, eps, dq + base + (size_t)t * d);
+            }
+            for (int j = 0; j < N; ++j) {
+                const double* vj = v + base + (size_t)j * d;
+                oracle_l2_normalize(k + base + (size_t)j * d, 1, d, eps, xh);
+                for (int c = 0; c < d; ++c) {
+                    double s = 0.0;
+                    for (int i = 0; i < d; ++i) s += xh[i] * S2[(size_t)i * d + c];
+                    dv[base + (size_t)j * d + c] = s / ORACLE_PI + 0.5 * va2[c];
+                }
+                for (int i = 0; i < d; ++i) {
+                    double s = kb2[i];
+                    for (int c = 0; c < d; ++c) s += S2[(size_t)i * d + c] * vj[c];
+                    dxh[i] = s / ORACLE_PI;
+                }
+                normalize_backward(k + base + (size_t)j * d, dxh, d, eps, dk + base + (size_t)j * d);
+            }
+            free(S2);
+            free(tmp);
+        }
+        free(state);
+    }
+    if (branches & ORACLE_BRANCH_DWCONV)
+        dwconv_backward(v, w, g, B, heads, H, W, d, ks, extra, dv, dw, dbias);
+    if (residual)
+        for (size_t i = 0; i < total; ++i) dq[i] += g[i];
+}
+
+/* ------------------------------------------------------------------------
  * Training-time companions of the layer (Sec. 3.2.2, Eq. 10) and the exact
  * angular kernel it approximates (Eq. 4-5), as O(N^2) attention.
  *

@@ -47,6 +47,9 @@ def lib():
         pooled = [_dp] * 5 + [C.c_int] * 9 + [C.c_uint, C.c_double, _dp]
         L.oracle_forward_pooled_explicit.argtypes = pooled
         L.oracle_forward_pooled.argtypes = pooled
+        bwd = [_dp] * 5 + [C.c_int] * 7 + [C.c_uint, C.c_double, C.c_int, C.c_int] + [_dp] * 5
+        L.oracle_backward_explicit.argtypes = bwd
+        L.oracle_backward.argtypes = bwd
         L.oracle_state.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _dp]
         L.oracle_softmax_probs.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_double,
                                            C.c_double, _dp]
@@ -191,6 +194,35 @@ def forward_pooled(q, k, v, w, bias, grid_h, grid_w, pool=2, residual=True, norm
     """The same by the reassociated form; any N."""
     return _pooled(lib().oracle_forward_pooled, q, k, v, w, bias, grid_h, grid_w, pool, residual,
                    norm, branches, eps)
+
+
+def _backward(fn, q, k, v, w, g, grid_h, grid_w, norm, branches, eps, extra, residual, with_bias):
+    q, k, v, w, g = _f64(q), _f64(k), _f64(v), _f64(w), _f64(g)
+    B, heads, N, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and g.shape == q.shape
+    assert N == extra + grid_h * grid_w and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    dq, dk, dv = (np.empty(q.shape, dtype=np.float64) for _ in range(3))
+    dw = np.empty(w.shape, dtype=np.float64)
+    dbias = np.empty((heads, d), dtype=np.float64) if with_bias else None
+    fn(_p(q), _p(k), _p(v), _p(w), _p(g), B, heads, grid_h, grid_w, d, w.shape[2], int(norm),
+       int(branches), float(eps), int(extra), int(bool(residual)), _p(dq), _p(dk), _p(dv), _p(dw),
+       _p(dbias))
+    return dq, dk, dv, dw, dbias
+
+
+def backward_explicit(q, k, v, w, g, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_ALL,
+                      eps=DEFAULT_EPS, extra=0, residual=False, with_bias=True):
+    """Gradients (dq, dk, dv, dw, dbias) of the layer given g = dLoss/dout, by differentiating
+    the definition (explicit N x N similarity); small N only."""
+    return _backward(lib().oracle_backward_explicit, q, k, v, w, g, grid_h, grid_w, norm, branches,
+                     eps, extra, residual, with_bias)
+
+
+def backward(q, k, v, w, g, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_ALL,
+             eps=DEFAULT_EPS, extra=0, residual=False, with_bias=True):
+    """The same through the reassociated state; any N."""
+    return _backward(lib().oracle_backward, q, k, v, w, g, grid_h, grid_w, norm, branches, eps,
+                     extra, residual, with_bias)
 
 
 def state(k, v, eps=DEFAULT_EPS):
