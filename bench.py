@@ -54,6 +54,9 @@ def parse_args():
     ap.add_argument("--downsample", action="store_true",
                     help="the workload as a downsampling layer: queries pooled to every second "
                          "row and column, residual query (dense layout)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time castling_attn_backward (gradients of q, k, v, filters, bias) "
+                         "instead of the forward layer (dense layout)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three 256 MiB device-to-device copies: a kernel of known "
@@ -109,6 +112,75 @@ def bench_pairwise(args, wl, sets, binding, inputs, torch):
     }))
 
 
+def bench_backward(args, wl, sets, host0, binding, inputs, torch):
+    """K calls of castling_attn_backward over the rotating input sets (the forward's `out`
+    buffers stand in for grad_out); one JSON line.  Algorithmic bytes of a backward: q, k, v,
+    grad_out read and the three gradients written once (7 tensors)."""
+    dev = sets[0]["q"].device
+    attn = binding.CastlingAttn.for_workload(wl, flags=binding.FLAG_TRAINING)
+    stream = torch.cuda.Stream()
+    for t in sets:
+        t["g"] = torch.randn(t["q"].shape, device=dev).to(t["q"].dtype)
+    grads = [torch.empty_like(sets[0]["q"]) for _ in range(3)]
+    gw = torch.empty(sets[0]["w"].shape, dtype=torch.float32, device=dev)
+    gb = torch.empty((wl.heads, wl.d), dtype=torch.float32, device=dev)
+
+    def call(t):
+        attn.backward(t["q"], t["k"], t["v"], t["w"], t["g"], *grads, gw, gb, stream=stream)
+
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            call(sets[i % len(sets)])
+        stream.synchronize()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record(stream)
+        for i in range(args.steps):
+            call(sets[i % len(sets)])
+        e1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        event_ms = e0.elapsed_time(e1) / args.steps
+    nbytes = 7 * wl.elems * wl.itemsize
+    achieved = nbytes / (event_ms * 1e-3) / 1e9
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        nb = 1
+        xs = {n: inputs.to_f64(host0[n][:nb]) for n in ("q", "k", "v")}
+        g64 = inputs.to_f64(sets[0]["g"][:nb].cpu())
+        w64 = inputs.to_f64(host0["w"])
+        c0 = time.perf_counter()
+        oracle.backward(xs["q"], xs["k"], xs["v"], w64, g64, wl.grid_h, wl.grid_w)
+        first = time.perf_counter() - c0
+        reps = max(1, min(200, int(10.0 / max(first, 1e-6))))
+        c0 = time.perf_counter()
+        for _ in range(reps):
+            oracle.backward(xs["q"], xs["k"], xs["v"], w64, g64, wl.grid_h, wl.grid_w)
+        c1 = time.perf_counter() - c0
+        cpu_baseline = {"value": round(reps * nb * wl.N / c1, 1), "unit": "tokens/s",
+                        "cores": oracle.num_threads(), "kind": "oracle",
+                        "sample": f"{nb} of {wl.B} batch images of the workload, {reps} passes of "
+                                  f"the oracle's backward, fp64, {c1:.2f} s"}
+    attn.destroy()
+    print(json.dumps({
+        "metric": "linear-angular attention backward tokens/s per layer",
+        "value": round(wl.tokens * args.steps / elapsed, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(elapsed * 1e3 / args.steps, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": wl.dtype,
+        "data": "synthetic",
+        "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "d": wl.d, "N": wl.N,
+                   "grid": [wl.grid_h, wl.grid_w], "dw_kernel": wl.dw_kernel, "op": "backward",
+                   "input_sets_rotated": len(sets)},
+        "roofline": {"bound": "hbm", "kernel": "backward (all launches)", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": None, "algorithmic_bytes": nbytes, "kernel_ms": round(event_ms, 5)},
+        "cpu_baseline": cpu_baseline,
+    }))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -157,6 +229,10 @@ def main():
         del cx, cy
     if args.pairwise:
         return bench_pairwise(args, wl, sets, binding, inputs, torch)
+    if args.backward:
+        if args.layout != "dense" or args.downsample:
+            sys.exit("bench.py: --backward goes with the dense layout of the ordinary layer")
+        return bench_backward(args, wl, sets, host0, binding, inputs, torch)
     if args.layout == "fused":
         attn = binding.CastlingAttn.for_workload(
             wl, in_strides=binding.fused_qkv_strides(wl.heads, wl.N, wl.d),

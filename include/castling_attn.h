@@ -79,8 +79,10 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
  * RESIDUAL_Q: the query as stored (not its unit row) is added to each output row after the
  * normaliser -- the residual connection of the pooled query in downsampling attention layers
  * (Sec. 3.1, attention designs; Table 1, last row).  Needs the linear branch
- * (CASTLING_ERR_INVALID_ARG otherwise); runs on the vector-ALU kernels. */
-enum { CASTLING_FLAG_KEEP_STATE = 1, CASTLING_FLAG_RESIDUAL_Q = 2 };
+ * (CASTLING_ERR_INVALID_ARG otherwise); runs on the vector-ALU kernels.
+ * TRAINING: create also allocates what castling_attn_backward needs (one more tensor of the
+ * span of q and a few small buffers); not with q_pool = 2 (CASTLING_ERR_UNSUPPORTED). */
+enum { CASTLING_FLAG_KEEP_STATE = 1, CASTLING_FLAG_RESIDUAL_Q = 2, CASTLING_FLAG_TRAINING = 4 };
 
 typedef struct {
     int32_t B, heads, N, d;   /* d: a multiple of 8, at most 128 */
@@ -145,6 +147,24 @@ int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* 
  * there are used. */
 int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const void* dw_weight,
                         const void* dw_bias, void* out, void* stream);
+
+/* Backward pass: the gradients of a scalar loss with respect to q, k, v, the DWConv filters and
+ * their bias, given grad_out = dLoss/dout -- the derivatives of Eq. 9 (linear terms of Eq. 8,
+ * normaliser of Eq. 3, DWConv term) with the readings above, for training the layer (Sec. 4.1;
+ * the paper prints no gradient formulas).  The handle must have been created with
+ * CASTLING_FLAG_TRAINING (CASTLING_ERR_INVALID_ARG otherwise).
+ * grad_out has the type and strides of out; grad_q, grad_k, grad_v the type and strides of q, k,
+ * v; grad_w [heads][d][ks][ks] and grad_bias [heads][d] (may be NULL) are fp32, contiguous, sums
+ * over the batch.  All are overwritten, none accumulated into.  A branch that is off in the
+ * descriptor contributes nothing: without the linear branch grad_q and grad_k are zeros,
+ * without the DWConv branch grad_w and grad_bias (where given) are zeros and dw_weight may be
+ * NULL.  With RESIDUAL_Q grad_q includes grad_out.  The forward pass is not needed
+ * beforehand: pass 1 is recomputed.  Afterwards the handle holds no state to apply or fetch.
+ * Pointers 16-byte aligned; no gradient may overlap an input or another gradient
+ * (CASTLING_ERR_ALIAS).  Only enqueues work on `stream`. */
+int castling_attn_backward(castling_attn_t h, const void* q, const void* k, const void* v,
+                           const void* dw_weight, const void* grad_out, void* grad_q, void* grad_k,
+                           void* grad_v, float* grad_w, float* grad_bias, void* stream);
 
 /* Registers the DWConv filters (the M_DW of Eq. 9) for later castling_attn_apply calls that
  * pass dw_weight = NULL, so that repeated applies with fixed filters skip their per-call

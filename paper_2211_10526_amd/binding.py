@@ -21,13 +21,14 @@ NORM_ROWSUM, NORM_NONE = 0, 1
 BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
 FLAG_KEEP_STATE = 1
 FLAG_RESIDUAL_Q = 2
+FLAG_TRAINING = 4
 
 EXPORTS = (
     "castling_attn_validate", "castling_attn_create", "castling_attn_forward",
     "castling_attn_reduce", "castling_attn_apply", "castling_attn_prepare_weights",
     "castling_attn_destroy",
     "castling_attn_workspace_bytes", "castling_attn_get_state", "castling_attn_num_splits",
-    "castling_attn_num_launches", "castling_attn_pairwise",
+    "castling_attn_num_launches", "castling_attn_pairwise", "castling_attn_backward",
     "castling_attn_strerror",
 )
 
@@ -87,6 +88,7 @@ def lib():
         L.castling_attn_num_splits.argtypes = [vp]
         L.castling_attn_num_launches.argtypes = [vp]
         L.castling_attn_pairwise.argtypes = [vp, C.POINTER(PairParams)] + [vp] * 6
+        L.castling_attn_backward.argtypes = [vp] * 12
         L.castling_attn_strerror.argtypes = [C.c_int]
         L.castling_attn_strerror.restype = C.c_char_p
         _lib = L
@@ -171,6 +173,13 @@ class CastlingAttn:
         _check(lib().castling_attn_apply(self._h, _ptr(q), _ptr(v), _ptr(w), _ptr(bias),
                                          _ptr(out), _stream_ptr(stream)))
         return out
+
+    def backward(self, q, k, v, w, grad_out, grad_q, grad_k, grad_v, grad_w, grad_bias=None,
+                 stream=None):
+        """castling_attn_backward; grad_w / grad_bias: fp32 device tensors."""
+        _check(lib().castling_attn_backward(self._h, _ptr(q), _ptr(k), _ptr(v), _ptr(w),
+                                            _ptr(grad_out), _ptr(grad_q), _ptr(grad_k), _ptr(grad_v),
+                                            _ptr(grad_w), _ptr(grad_bias), _stream_ptr(stream)))
 
     def pairwise(self, mode, q, k, v, out, kept=None, normalize=True, scale=1.0, threshold=0.0,
                  accumulate=False, stream=None):

@@ -1,0 +1,362 @@
+// Backward pass of the layer on the vector ALU (any I/O type, fp32 arithmetic): the gradients of
+// Eq. 3 / 8 / 9 with respect to q, k, v, the DWConv filters and their bias, given g = dLoss/dout.
+//
+// With num_t = vsum / 2 + q_hat_t S / pi and den_t = N / 2 + q_hat_t . ksum / pi (Eq. 3 after the
+// reassociation of Sec. 3.1), a_t = dLoss/dnum_t = g_t / den_t and
+// b_t = dLoss/dden_t = -(g_t . lin_t) / den_t  (a_t = g_t, b_t = 0 without the normaliser):
+//   dq_hat_t = (S a_t + ksum b_t) / pi
+//   S' = sum_t q_hat_t^T a_t,   kb' = sum_t q_hat_t b_t,   va' = sum_t a_t
+//   dv_j     = k_hat_j S' / pi + va' / 2 + (DWConv of g with the filters turned by 180 degrees)
+//   dk_hat_j = (S' v_j + kb') / pi
+//   dx = (dx_hat - x_hat (x_hat . dx_hat)) / |x|   (dx_hat / eps where |x| < eps)
+// S', va' are what pass 1 computes from (q, a) in place of (k, v), and dv is what pass 2 computes
+// from (k, g) with that state: both reuse the forward kernels.  This file holds the rest: the
+// per-row kernel (a, b, dq; dk), the filter gradient and small helpers.
+#pragma once
+
+#include "apply_generic.hpp"
+#include "common.hpp"
+
+namespace castling {
+
+struct BwdRowsParams {
+    int N;           // tokens per unit
+    int tiles;       // ceil(N / 64)
+    int norm_none;
+    int residual_q;  // QUERY: dq gains g
+    int d_valid;     // features per head in memory (<= D)
+    float eps;
+    TensorStrides in, out;  // of q, k, v, a and the gradients of q, k; of g
+};
+
+constexpr int kBwdTokens = 64;             // tokens per block
+constexpr int kBwdTStride = kBwdTokens + 4;  // floats; keeps float4 rows aligned
+
+template <int D>
+constexpr size_t bwd_rows_lds_bytes()
+{
+    // M [D][D+1], vec [D], vs [D], xt [D][68], at [D][68], inv / small / b [64] each
+    return sizeof(float) * (static_cast<size_t>(D) * (D + 1) + 2 * D + 2 * D * kBwdTStride + 3 * kBwdTokens);
+}
+
+// grid = (ceil(N / 64), units), block = 256, dynamic LDS = bwd_rows_lds_bytes<D>().
+// QUERY: x = q.  Recomputes num, den of the unit's tokens from `state` (the forward state),
+//   writes a (type T, layout of q) to `a_out`, this tile's share of kb' to
+//   kb_part[unit][tile][D], and dq to `dx`.
+// !QUERY: x = k, `y` = v, `state` = (S', -, -) and `vec` = kb' of the unit ([units][D]): writes dk.
+// Thread (tt, tj) = (tid / 16, tid % 16) owns tokens 4 tt .. 4 tt + 3 and features tj D/16 .. .
+template <typename T, int D, bool QUERY>
+__global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
+                                                       const T* __restrict__ y,
+                                                       const float* __restrict__ state,
+                                                       const float* __restrict__ vec,
+                                                       T* __restrict__ a_out,
+                                                       float* __restrict__ kb_part,
+                                                       T* __restrict__ dx, int heads, BwdRowsParams p)
+{
+    constexpr int VEC = IO<T>::VEC;
+    constexpr int LPR = D / VEC;
+    constexpr int RJ = D / 16;
+    constexpr int MS = D + 1;  // row stride of M: the second product walks its columns
+    using L = StateLayout<D>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    float* M = reinterpret_cast<float*>(lds_raw);
+    float* vk = M + D * MS;             // ksum / pi   (kb' / pi)
+    float* vs = vk + D;                 // vsum / 2
+    float* xt = vs + D;                 // unit rows of x, transposed [D][68]
+    float* at = xt + D * kBwdTStride;   // a (or v), transposed [D][68]
+    float* inv = at + D * kBwdTStride;  // 1 / max(|x|, eps)
+    float* small = inv + kBwdTokens;    // 1 where |x| < eps
+    float* bs = small + kBwdTokens;     // b_t
+
+    const int tid = threadIdx.x;
+    const int unit = blockIdx.y, tile = blockIdx.x;
+    const int n0 = tile * kBwdTokens;
+    const int tt = tid / 16, tj = tid % 16;
+    const long long in_off = unit_offset(unit, heads, p.in);
+    const long long out_off = unit_offset(unit, heads, p.out);
+
+    const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
+    for (int i = tid; i < D * D; i += 256) M[(i / D) * MS + i % D] = gs[L::S + i] * kInvPi;
+    for (int i = tid; i < D; i += 256) {
+        vk[i] = (QUERY ? gs[L::KSUM + i] : vec[static_cast<size_t>(unit) * D + i]) * kInvPi;
+        vs[i] = 0.5f * gs[L::VSUM + i];
+    }
+
+    // rows of x -> unit rows, transposed; !QUERY: rows of y (= v) -> at
+    constexpr int ROWS = 256 / LPR;
+    constexpr int PASSES = (kBwdTokens + ROWS - 1) / ROWS;
+    const int lcol = (tid % LPR) * VEC;
+#pragma unroll
+    for (int pass = 0; pass < PASSES; ++pass) {
+        const int tl = pass * ROWS + tid / LPR;
+        if (tl >= kBwdTokens) break;
+        const int n = n0 + tl;
+        float xv[VEC], yv[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) xv[e] = yv[e] = 0.f;
+        if (n < p.N && lcol < p.d_valid) {
+            IO<T>::load16(x + in_off + n * p.in.n + lcol, xv);
+            if (!QUERY) IO<T>::load16(y + in_off + n * p.in.n + lcol, yv);
+        }
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) ss += xv[e] * xv[e];
+        ss = group_sum<LPR>(ss);
+        const float nrm = sqrtf(ss);
+        const float r = 1.0f / fmaxf(nrm, p.eps);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            xt[(lcol + e) * kBwdTStride + tl] = xv[e] * r;
+            if (!QUERY) at[(lcol + e) * kBwdTStride + tl] = yv[e];
+        }
+        if (tid % LPR == 0) {
+            inv[tl] = r;
+            small[tl] = nrm < p.eps ? 1.f : 0.f;
+            if (!QUERY) bs[tl] = 1.f;
+        }
+    }
+    __syncthreads();
+
+    float gown[4][RJ] = {};  // QUERY: g of the own tokens and features (for the residual)
+    if (QUERY) {
+        // forward quantities of the own tokens: num (own features), den
+        float num[4][RJ], den[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) num[t][j] = 0.f;
+#pragma unroll 4
+        for (int i = 0; i < D; ++i) {
+            const float4 x4 = *reinterpret_cast<const float4*>(xt + i * kBwdTStride + tt * 4);
+            const float xa[4] = {x4.x, x4.y, x4.z, x4.w};
+            const float ki = vk[i];
+            float m[RJ];
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) m[j] = M[i * MS + tj * RJ + j];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                den[t] = fmaf(xa[t], ki, den[t]);
+#pragma unroll
+                for (int j = 0; j < RJ; ++j) num[t][j] = fmaf(xa[t], m[j], num[t][j]);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int n = n0 + tt * 4 + t;
+            const bool live = n < p.N && tj * RJ < p.d_valid;
+            const T* gr = y + out_off + n * p.out.n + tj * RJ;  // y = g
+            float gl = 0.f;
+            const float rden = 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) {
+                gown[t][j] = live ? IO<T>::to_f32(gr[j]) : 0.f;
+                gl = fmaf(gown[t][j], (vs[tj * RJ + j] + num[t][j]) * rden, gl);
+            }
+            gl = group_sum<16>(gl);  // g_t . lin_t over all features
+            const float bt = p.norm_none ? 0.f : -gl * rden;
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) {
+                const float av = p.norm_none ? gown[t][j] : gown[t][j] * rden;
+                at[(tj * RJ + j) * kBwdTStride + tt * 4 + t] = av;
+                if (live) a_out[in_off + n * p.in.n + tj * RJ + j] = IO<T>::from_f32(av);
+            }
+            if (tj == 0) bs[tt * 4 + t] = n < p.N ? bt : 0.f;
+        }
+        __syncthreads();
+        // this tile's share of kb' = sum_t q_hat_t b_t
+        if (tid < D) {
+            float s = 0.f;
+#pragma unroll 8
+            for (int t = 0; t < kBwdTokens; ++t) s = fmaf(xt[tid * kBwdTStride + t], bs[t], s);
+            kb_part[(static_cast<size_t>(unit) * p.tiles + tile) * D + tid] = s;
+        }
+    }
+
+    // dx_hat (own tokens, own features i) = sum_c M[i][c] at[c][t] + vk[i] b_t
+    float dxh[4][RJ];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int j = 0; j < RJ; ++j) dxh[t][j] = vk[tj * RJ + j] * bs[tt * 4 + t];
+#pragma unroll 4
+    for (int c = 0; c < D; ++c) {
+        const float4 a4 = *reinterpret_cast<const float4*>(at + c * kBwdTStride + tt * 4);
+        const float aa[4] = {a4.x, a4.y, a4.z, a4.w};
+        float m[RJ];
+#pragma unroll
+        for (int j = 0; j < RJ; ++j) m[j] = M[(tj * RJ + j) * MS + c];
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) dxh[t][j] = fmaf(aa[t], m[j], dxh[t][j]);
+    }
+    // back through the normalisation, store
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int tl = tt * 4 + t, n = n0 + tl;
+        float xh[RJ], dot = 0.f;
+#pragma unroll
+        for (int j = 0; j < RJ; ++j) {
+            xh[j] = xt[(tj * RJ + j) * kBwdTStride + tl];
+            dot = fmaf(xh[j], dxh[t][j], dot);
+        }
+        dot = group_sum<16>(dot);
+        if (small[tl] != 0.f) dot = 0.f;  // below the floor the row is x / eps: no projection
+        if (n < p.N && tj * RJ < p.d_valid) {
+            T* o = dx + in_off + n * p.in.n + tj * RJ;
+#pragma unroll
+            for (int j = 0; j < RJ; ++j) {
+                float r = (dxh[t][j] - xh[j] * dot) * inv[tl];
+                if (QUERY && p.residual_q) r += gown[t][j];
+                o[j] = IO<T>::from_f32(r);
+            }
+        }
+    }
+}
+
+// grid = (units), block = 128: kb[unit][i] = sum over tiles of kb_part[unit][tile][i], in order.
+__global__ __launch_bounds__(128) void bwd_vec_combine_kernel(const float* __restrict__ kb_part,
+                                                              float* __restrict__ kb, int tiles, int D)
+{
+    const int i = threadIdx.x;
+    if (i >= D) return;
+    const float* src = kb_part + static_cast<size_t>(blockIdx.x) * tiles * D + i;
+    float s = 0.f;
+    for (int t = 0; t < tiles; ++t) s += src[static_cast<size_t>(t) * D];
+    kb[static_cast<size_t>(blockIdx.x) * D + i] = s;
+}
+
+// grid = (ceil(n / 256)), block = 256: the filters [heads * d][ks][ks] turned by 180 degrees.
+template <typename T>
+__global__ __launch_bounds__(256) void flip_filters_kernel(const T* __restrict__ w, T* __restrict__ out,
+                                                           int n, int taps)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int ch = i / taps, e = i % taps;
+    out[i] = w[ch * taps + (taps - 1 - e)];
+}
+
+// grid = (ceil(n / 256)), block = 256
+__global__ __launch_bounds__(256) void fill_zero_f32_kernel(float* __restrict__ p, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0.f;
+}
+
+struct BwdFilterParams {
+    int grid_h, grid_w;
+    int tiles_x, n_tiles;  // 4 x 16 tiles of the grid
+    int chunks;            // blocks per unit; block c takes tiles c, c + chunks, ...
+    int d_valid;
+    TensorStrides in, out;  // of v; of g
+};
+
+template <typename T, int D, int KS>
+constexpr size_t bwd_filter_lds_bytes()
+{
+    return sizeof(T) * (kApplyTH + KS - 1) * (kApplyTW + KS - 1) * D;
+}
+
+// Filter and bias gradients: dw[c][dy][dx] = sum over tokens of g[t][c] v[t + (dy, dx) - r][c],
+// dbias[c] = sum of g[t][c].  grid = (chunks, units), block = 256, dynamic LDS =
+// bwd_filter_lds_bytes.  Thread (part, c) = (tid / D, tid % D) accumulates the taps
+// part, part + 256 / D, ... of channel c (tap KS * KS is the bias) over the block's tiles and
+// writes them to part_out[unit][chunk][tap][D]; v, g point at the first grid token.
+template <typename T, int D, int KS>
+__global__ __launch_bounds__(256) void bwd_filter_kernel(const T* __restrict__ v,
+                                                         const T* __restrict__ g,
+                                                         float* __restrict__ part_out, int heads,
+                                                         BwdFilterParams p)
+{
+    constexpr int VEC = IO<T>::VEC;
+    constexpr int LPR = D / VEC;
+    constexpr int RAD = KS / 2;
+    constexpr int HH = kApplyTH + KS - 1, HW = kApplyTW + KS - 1;
+    constexpr int TPC = 256 / D;                    // threads per channel
+    constexpr int NT = KS * KS + 1;                 // taps and the bias
+    constexpr int TAPS = (NT + TPC - 1) / TPC;      // per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    T* vh = reinterpret_cast<T*>(lds_raw);  // [HH][HW][D], zero outside the grid
+
+    const int tid = threadIdx.x;
+    const int unit = blockIdx.y;
+    const int c = tid % D, part = tid / D;
+    const long long in_off = unit_offset(unit, heads, p.in);
+    const long long out_off = unit_offset(unit, heads, p.out);
+
+    int tap_off[TAPS];  // LDS element offset of the tap relative to the token, -1: bias, -2: none
+#pragma unroll
+    for (int i = 0; i < TAPS; ++i) {
+        const int e = part + TPC * i;
+        tap_off[i] = e < KS * KS ? ((e / KS) * HW + e % KS) * D : (e == KS * KS ? -1 : -2);
+    }
+    float acc[TAPS];
+#pragma unroll
+    for (int i = 0; i < TAPS; ++i) acc[i] = 0.f;
+
+    for (int tile = blockIdx.x; tile < p.n_tiles; tile += p.chunks) {
+        const int ty0 = (tile / p.tiles_x) * kApplyTH, tx0 = (tile % p.tiles_x) * kApplyTW;
+        __syncthreads();  // the previous tile's reads are done
+        for (int idx = tid; idx < HH * HW * LPR; idx += 256) {
+            const int tok = idx / LPR, piece = idx % LPR;
+            const int yy = ty0 - RAD + tok / HW, xx = tx0 - RAD + tok % HW;
+            uint4 val = make_uint4(0u, 0u, 0u, 0u);
+            if (piece * VEC < p.d_valid && yy >= 0 && yy < p.grid_h && xx >= 0 && xx < p.grid_w)
+                val = *reinterpret_cast<const uint4*>(
+                    v + in_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.in.n + piece * VEC);
+            *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tok) * D + piece * VEC) = val;
+        }
+        __syncthreads();
+#pragma unroll 1
+        for (int ty = 0; ty < kApplyTH; ++ty) {
+            const int yy = ty0 + ty;
+            if (yy >= p.grid_h) break;
+#pragma unroll 4
+            for (int tx = 0; tx < kApplyTW; ++tx) {
+                const int xx = tx0 + tx;
+                float gv = 0.f;
+                if (xx < p.grid_w && c < p.d_valid)
+                    gv = IO<T>::to_f32(g[out_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.out.n + c]);
+                const T* base = vh + (ty * HW + tx) * D + c;
+#pragma unroll
+                for (int i = 0; i < TAPS; ++i) {
+                    const float vv = tap_off[i] >= 0 ? IO<T>::to_f32(base[tap_off[i]])
+                                                     : (tap_off[i] == -1 ? 1.f : 0.f);
+                    acc[i] = fmaf(gv, vv, acc[i]);
+                }
+            }
+        }
+    }
+    float* o = part_out + (static_cast<size_t>(unit) * p.chunks + blockIdx.x) * NT * D;
+#pragma unroll
+    for (int i = 0; i < TAPS; ++i) {
+        const int e = part + TPC * i;
+        if (e < NT) o[e * D + c] = acc[i];
+    }
+}
+
+// grid = (ceil(heads * d * (taps + 1) / 256)), block = 256: sums the partial filter gradients
+// over the batch and the chunks, in order, into dw [heads][d][taps] and dbias [heads][d] (may
+// be null).  part: [B * heads][chunks][taps + 1][D].
+__global__ __launch_bounds__(256) void bwd_filter_combine_kernel(const float* __restrict__ part,
+                                                                 float* __restrict__ dw,
+                                                                 float* __restrict__ dbias, int B,
+                                                                 int heads, int d, int D, int taps,
+                                                                 int chunks)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int nt = taps + 1;
+    if (i >= heads * d * nt) return;
+    const int e = i % nt, ch = (i / nt) % d, h = i / (nt * d);
+    float s = 0.f;
+    for (int b = 0; b < B; ++b) {
+        const float* src = part + (static_cast<size_t>(b) * heads + h) * chunks * nt * D + e * D + ch;
+        for (int k = 0; k < chunks; ++k) s += src[static_cast<size_t>(k) * nt * D];
+    }
+    if (e < taps) dw[(static_cast<size_t>(h) * d + ch) * taps + e] = s;
+    else if (dbias) dbias[h * d + ch] = s;
+}
+
+}  // namespace castling

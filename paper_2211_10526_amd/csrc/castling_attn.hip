@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -12,6 +13,7 @@
 
 #include "apply_generic.hpp"
 #include "apply_mfma.hpp"
+#include "backward.hpp"
 #include "common.hpp"
 #include "fused_small.hpp"
 #include "pairwise.hpp"
@@ -111,6 +113,21 @@ struct castling_attn {
     float* vhalf;
     bf16_t* wfrag;
     const void* prepared_w;  // filters registered by castling_attn_prepare_weights
+    // The backward pass runs pass 2 on other tensors: q := k, v := g (layout of out), out := dv
+    // (layout of v), without the normaliser.  generic: on the vector-ALU kernel even where the
+    // handle's pass 2 is on the matrix cores (the layouts of v and out differ).
+    struct {
+        bool on, generic;
+        TensorStrides q, v, out;
+    } ov;
+    // backward workspace (CASTLING_FLAG_TRAINING; part of the one allocation)
+    bool training;
+    void* a_buf;        // a_t = dLoss/dnum_t, I/O type, layout and span of q
+    float* kb_part;     // [units][row tiles][dpad]
+    float* kb;          // [units][dpad]
+    void* wflip;        // filters turned by 180 degrees
+    float* fpart;       // [units][filter chunks][ks*ks + 1][dpad]
+    int row_tiles, filter_chunks;
 };
 
 namespace {
@@ -262,18 +279,18 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     p.grid_h = h->view.grid_h;
     p.grid_w = h->view.grid_w;
     p.tiles_x = (p.grid_w + kApplyTW - 1) / kApplyTW;
-    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.norm_none = h->ov.on || d.norm == CASTLING_NORM_NONE;
     p.do_linear = (h->view.branches & CASTLING_BRANCH_LINEAR) != 0;
     p.do_dwconv = (h->view.branches & CASTLING_BRANCH_DWCONV) != 0;
     p.eps = d.eps;
-    p.in = h->in_st;
-    p.out = h->out_st;
+    p.in = h->ov.on ? h->ov.v : h->in_st;
+    p.out = h->ov.on ? h->ov.out : h->out_st;
     p.n_partials = h->partials_pending ? h->n_split : 1;
     p.d_valid = d.d;
-    p.qs = h->q_st;
+    p.qs = h->ov.on ? h->ov.q : h->q_st;
     p.vgrid_h = S == 1 ? p.grid_h : d.grid_h;
     p.vgrid_w = S == 1 ? p.grid_w : d.grid_w;
-    p.residual_q = h->residual_q;
+    p.residual_q = h->residual_q && !h->ov.on;
     const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
     hipLaunchKernelGGL((apply_generic_kernel<T, D, KS, S>), dim3(p.tiles_x * tiles_y, h->units),
                        dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
@@ -303,7 +320,7 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     p.grid_h = h->view.grid_h;
     p.grid_w = h->view.grid_w;
     p.strips = (p.grid_w + kStripW - 1) / kStripW;
-    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.norm_none = h->ov.on || d.norm == CASTLING_NORM_NONE;
     p.do_linear = LIN;
     p.do_dwconv = DW;
     p.eps = d.eps;
@@ -381,7 +398,7 @@ hipError_t apply_generic_ks(castling_attn* h, bool launch, const void* q, const 
 hipError_t do_apply_view(castling_attn* h, bool launch, const void* q, const void* v, const void* w,
                          const void* bias, void* out, hipStream_t s)
 {
-    if (h->mfma_apply) {
+    if (h->mfma_apply && !(h->ov.on && h->ov.generic)) {
         switch (h->view.ks) {
             case 1: return apply_mfma<1>(h, launch, q, v, w, bias, out, s);
             case 3: return apply_mfma<3>(h, launch, q, v, w, bias, out, s);
@@ -423,8 +440,10 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
         return p ? static_cast<const unsigned char*>(p) + static_cast<size_t>(extra) * tok_stride * es
                  : nullptr;
     };
-    hipError_t e = do_apply_view(h, true, skip(q, h->in_st.n), skip(v, h->in_st.n), w, bias,
-                                 const_cast<void*>(skip(out, h->out_st.n)), s);
+    const TensorStrides& out_st = h->ov.on ? h->ov.out : h->out_st;
+    hipError_t e = do_apply_view(h, true, skip(q, h->ov.on ? h->ov.q.n : h->q_st.n),
+                                 skip(v, h->ov.on ? h->ov.v.n : h->in_st.n), w, bias,
+                                 const_cast<void*>(skip(out, out_st.n)), s);
     if (e != hipSuccess || extra == 0) return e;
     if (lin) {
         h->view = extra_view;
@@ -436,10 +455,91 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
         using T = decltype(t);
         const int pieces = extra * d.d / IO<T>::VEC;
         hipLaunchKernelGGL(zero_rows_kernel<T>, dim3((pieces + 255) / 256, h->units), dim3(256), 0, s,
-                           static_cast<T*>(out), extra, d.d, d.heads, h->out_st);
+                           static_cast<T*>(out), extra, d.d, d.heads, out_st);
         return 0;
     });
     return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ backward
+// launch = false: set the kernels' LDS attributes, record the largest in *lds (create time)
+template <typename T, int D>
+hipError_t bwd_rows(castling_attn* h, bool launch, bool query, const void* x, const void* y,
+                    void* dx, size_t* lds, hipStream_t s)
+{
+    constexpr size_t bytes = bwd_rows_lds_bytes<D>();
+    if (!launch) {
+        if (bytes > *lds) *lds = bytes;
+        if (bytes > kMaxLdsBytes) return hipSuccess;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_rows_kernel<T, D, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           static_cast<int>(bytes));
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_rows_kernel<T, D, false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    }
+    const castling_attn_desc_t& d = h->desc;
+    BwdRowsParams p = {};
+    p.N = d.N;
+    p.tiles = h->row_tiles;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.residual_q = h->residual_q;
+    p.d_valid = d.d;
+    p.eps = d.eps;
+    p.in = h->in_st;
+    p.out = h->out_st;
+    const dim3 grid(h->row_tiles, h->units);
+    if (query)
+        hipLaunchKernelGGL((bwd_rows_kernel<T, D, true>), grid, dim3(256), bytes, s,
+                           static_cast<const T*>(x), static_cast<const T*>(y), h->state, nullptr,
+                           static_cast<T*>(h->a_buf), h->kb_part, static_cast<T*>(dx), d.heads, p);
+    else
+        hipLaunchKernelGGL((bwd_rows_kernel<T, D, false>), grid, dim3(256), bytes, s,
+                           static_cast<const T*>(x), static_cast<const T*>(y), h->state, h->kb,
+                           nullptr, nullptr, static_cast<T*>(dx), d.heads, p);
+    return hipGetLastError();
+}
+
+template <typename T, int D, int KS>
+hipError_t bwd_filter_ks(castling_attn* h, bool launch, const void* v, const void* g, size_t* lds,
+                         hipStream_t s)
+{
+    constexpr size_t bytes = bwd_filter_lds_bytes<T, D, KS>();
+    if (!launch) {
+        if (bytes > *lds) *lds = bytes;
+        if (bytes > kMaxLdsBytes) return hipSuccess;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_filter_kernel<T, D, KS>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    }
+    const castling_attn_desc_t& d = h->desc;
+    BwdFilterParams p = {};
+    p.grid_h = d.grid_h;
+    p.grid_w = d.grid_w;
+    p.tiles_x = (d.grid_w + kApplyTW - 1) / kApplyTW;
+    p.n_tiles = p.tiles_x * ((d.grid_h + kApplyTH - 1) / kApplyTH);
+    p.chunks = h->filter_chunks;
+    p.d_valid = d.d;
+    p.in = h->in_st;
+    p.out = h->out_st;
+    // the class tokens in front of the grid take no part in the convolution
+    const T* vg = static_cast<const T*>(v) + static_cast<long long>(d.extra_tokens) * h->in_st.n;
+    const T* gg = static_cast<const T*>(g) + static_cast<long long>(d.extra_tokens) * h->out_st.n;
+    hipLaunchKernelGGL((bwd_filter_kernel<T, D, KS>), dim3(h->filter_chunks, h->units), dim3(256),
+                       bytes, s, vg, gg, h->fpart, d.heads, p);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+hipError_t bwd_filter(castling_attn* h, bool launch, const void* v, const void* g, size_t* lds,
+                      hipStream_t s)
+{
+    switch (h->desc.dw_kernel) {
+        case 1: return bwd_filter_ks<T, D, 1>(h, launch, v, g, lds, s);
+        case 3: return bwd_filter_ks<T, D, 3>(h, launch, v, g, lds, s);
+        case 5: return bwd_filter_ks<T, D, 5>(h, launch, v, g, lds, s);
+        case 7: return bwd_filter_ks<T, D, 7>(h, launch, v, g, lds, s);
+        default: return bwd_filter_ks<T, D, 9>(h, launch, v, g, lds, s);
+    }
 }
 
 // ------------------------------------------------------------------ one-kernel path
@@ -569,7 +669,8 @@ int castling_attn_validate(const castling_attn_desc_t* d)
         return CASTLING_ERR_INVALID_ARG;
     if (d->branches & ~static_cast<uint32_t>(CASTLING_BRANCH_ALL)) return CASTLING_ERR_INVALID_ARG;
     if (!(d->eps >= 0.0f)) return CASTLING_ERR_INVALID_ARG;
-    if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE | CASTLING_FLAG_RESIDUAL_Q))
+    if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE | CASTLING_FLAG_RESIDUAL_Q |
+                                          CASTLING_FLAG_TRAINING))
         return CASTLING_ERR_INVALID_ARG;
     if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16 && d->io_dtype != CASTLING_F16)
         return CASTLING_ERR_UNSUPPORTED;
@@ -581,6 +682,7 @@ int castling_attn_validate(const castling_attn_desc_t* d)
         return CASTLING_ERR_UNSUPPORTED;
     if (d->q_pool < 0 || d->reserved0 != 0) return CASTLING_ERR_INVALID_ARG;
     if (d->q_pool > 2 || (d->q_pool == 2 && d->extra_tokens != 0)) return CASTLING_ERR_UNSUPPORTED;
+    if (d->q_pool == 2 && (d->flags & CASTLING_FLAG_TRAINING)) return CASTLING_ERR_UNSUPPORTED;
     if (d->q_pool != 2 && (d->q_stride_b != 0 || d->q_stride_h != 0 || d->q_stride_n != 0))
         return CASTLING_ERR_INVALID_ARG;
     if ((d->flags & CASTLING_FLAG_RESIDUAL_Q) && d->branches != 0 &&
@@ -726,6 +828,44 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
             return CASTLING_ERR_UNSUPPORTED;
         }
     }
+    // backward pass: LDS attributes of its kernels, and of the vector-ALU pass 2 it may need
+    h->training = (desc->flags & CASTLING_FLAG_TRAINING) != 0;
+    h->ov.on = h->ov.generic = false;
+    size_t a_bytes = 0, kbp_bytes = 0, kb_bytes = 0, wflip_bytes = 0, fpart_bytes = 0;
+    if (e == hipSuccess && h->training) {
+        size_t lds = 0;
+        const size_t keep = h->apply_lds;
+        h->ov.on = h->ov.generic = true;
+        h->ov.q = h->ov.v = h->ov.out = h->in_st;
+        e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+        lds = h->apply_lds;
+        h->apply_lds = keep;
+        h->ov.on = h->ov.generic = false;
+        if (e == hipSuccess)
+            e = dispatch_type_width(desc->io_dtype, h->dpad, [&](auto t, auto dc) {
+                using T = decltype(t);
+                constexpr int D = decltype(dc)::value;
+                hipError_t r = bwd_rows<T, D>(h, false, true, nullptr, nullptr, nullptr, &lds, nullptr);
+                if (r == hipSuccess) r = bwd_filter<T, D>(h, false, nullptr, nullptr, &lds, nullptr);
+                return r;
+            });
+        if (e == hipSuccess && lds > kMaxLdsBytes) {
+            delete h;
+            return CASTLING_ERR_UNSUPPORTED;
+        }
+        const int taps1 = desc->dw_kernel * desc->dw_kernel + 1;
+        const int n_tiles = ((desc->grid_w + kApplyTW - 1) / kApplyTW) *
+                            ((desc->grid_h + kApplyTH - 1) / kApplyTH);
+        h->row_tiles = (desc->N + kBwdTokens - 1) / kBwdTokens;
+        h->filter_chunks = std::max(1, std::min(n_tiles, 2048 / h->units));
+        a_bytes = align_up(h->in_span, 256);
+        kbp_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->row_tiles * h->dpad, 256);
+        kb_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->dpad, 256);
+        wflip_bytes = align_up(dtype_size(desc->io_dtype) * static_cast<size_t>(desc->heads) * desc->d *
+                                   (taps1 - 1), 256);
+        fpart_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->filter_chunks * taps1 *
+                                   h->dpad, 256);
+    }
     // one allocation, 256-byte aligned parts
     const size_t partial_bytes =
         h->pair_reduce ? align_up(sizeof(float) * static_cast<size_t>(h->apply_units) * h->n_split *
@@ -741,8 +881,8 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         wfrag_bytes =
             align_up(static_cast<size_t>(desc->heads) * 4 * desc->dw_kernel * 3 * 64 * 8, 256);
     }
-    h->workspace_bytes =
-        partial_bytes + state_bytes + sfrag_bytes + kfrag_bytes + vhalf_bytes + wfrag_bytes;
+    h->workspace_bytes = partial_bytes + state_bytes + sfrag_bytes + kfrag_bytes + vhalf_bytes +
+                         wfrag_bytes + a_bytes + kbp_bytes + kb_bytes + wflip_bytes + fpart_bytes;
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->workspace), h->workspace_bytes);
     if (e != hipSuccess) {
         delete h;
@@ -760,6 +900,16 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->vhalf = reinterpret_cast<float*>(p);
     p += vhalf_bytes;
     h->wfrag = reinterpret_cast<bf16_t*>(p);
+    p += wfrag_bytes;
+    h->a_buf = p;
+    p += a_bytes;
+    h->kb_part = reinterpret_cast<float*>(p);
+    p += kbp_bytes;
+    h->kb = reinterpret_cast<float*>(p);
+    p += kb_bytes;
+    h->wflip = p;
+    p += wflip_bytes;
+    h->fpart = reinterpret_cast<float*>(p);
     if (!h->mfma_apply && h->n_split == 1) h->partial = h->state;  // see do_reduce
     // Small vector-ALU problems: every apply block sums the few partial states itself instead of
     // waiting for a combine launch (cfg1: three launches become two).  Not when the caller wants
@@ -928,6 +1078,117 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
         return CASTLING_OK;
     }
     return castling_attn_apply(h, q, v, dw_weight, dw_bias, out, stream);
+}
+
+int castling_attn_backward(castling_attn_t h, const void* q, const void* k, const void* v,
+                           const void* dw_weight, const void* grad_out, void* grad_q, void* grad_k,
+                           void* grad_v, float* grad_w, float* grad_bias, void* stream)
+{
+    if (!h || !h->training) return CASTLING_ERR_INVALID_ARG;
+    const castling_attn_desc_t& d = h->desc;
+    const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    if (!q || !k || !v || !grad_out || !grad_q || !grad_k || !grad_v || (dw && (!dw_weight || !grad_w)))
+        return CASTLING_ERR_INVALID_ARG;
+    const void* ptrs[] = {q, k, v, grad_out, grad_q, grad_k, grad_v, dw ? dw_weight : nullptr};
+    for (const void* ptr : ptrs)
+        if (misaligned(ptr)) return CASTLING_ERR_INVALID_ARG;
+    // no gradient may overlap an input or another gradient
+    const void* ins[] = {q, k, v, grad_out};
+    const size_t in_bytes[] = {h->in_span, h->in_span, h->in_span, h->out_span};
+    void* outs[] = {grad_q, grad_k, grad_v};
+    for (int o = 0; o < 3; ++o) {
+        for (int i = 0; i < 4; ++i)
+            if (overlaps(outs[o], h->in_span, ins[i], in_bytes[i])) return CASTLING_ERR_ALIAS;
+        for (int o2 = o + 1; o2 < 3; ++o2)
+            if (outs[o] == outs[o2]) return CASTLING_ERR_ALIAS;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t es = dtype_size(d.io_dtype);
+    const int taps = d.dw_kernel * d.dw_kernel;
+    h->state_valid = false;  // the workspace ends up holding the state of (q, a), not of (k, v)
+    h->apply_ready = false;
+    h->partials_pending = false;
+    int st = CASTLING_OK;
+    hipError_t e = hipSuccess;
+    auto typed = [&](auto&& f) { return dispatch_type_width(d.io_dtype, h->dpad, f); };
+    if (lin) {
+        // forward state of (k, v); a, b, dq per query row; the state of (q, a); kb'
+        st = do_reduce(h, k, v, nullptr, s);
+        if (st != CASTLING_OK) return st;
+        e = typed([&](auto t, auto dc) {
+            return bwd_rows<decltype(t), decltype(dc)::value>(h, true, true, q, grad_out, grad_q,
+                                                               nullptr, s);
+        });
+        HIP_TRY(e);
+        hipLaunchKernelGGL(bwd_vec_combine_kernel, dim3(h->units), dim3(128), 0, s, h->kb_part, h->kb,
+                           h->row_tiles, h->dpad);
+        HIP_TRY(hipGetLastError());
+        st = do_reduce(h, q, h->a_buf, nullptr, s);
+        if (st != CASTLING_OK) return st;
+        h->state_valid = false;
+        // dk per key row from the state of (q, a)
+        e = typed([&](auto t, auto dc) {
+            return bwd_rows<decltype(t), decltype(dc)::value>(h, true, false, k, v, grad_k, nullptr, s);
+        });
+        HIP_TRY(e);
+    } else {
+        // no attention branch: q and k do not reach the output
+        typed([&](auto t, auto) {
+            using T = decltype(t);
+            const int pieces = d.N * d.d / IO<T>::VEC;
+            for (void* gp : {grad_q, grad_k})
+                hipLaunchKernelGGL(zero_rows_kernel<T>, dim3((pieces + 255) / 256, h->units), dim3(256),
+                                   0, s, static_cast<T*>(gp), d.N, d.d, d.heads, h->in_st);
+            return 0;
+        });
+        HIP_TRY(hipGetLastError());
+    }
+    // dv: pass 2 on (k, g) with the state of (q, a), the filters turned by 180 degrees, no
+    // normaliser, no bias; written in the layout of v
+    if (dw) {
+        const int n = d.heads * d.d * taps;
+        typed([&](auto t, auto) {
+            using T = decltype(t);
+            hipLaunchKernelGGL(flip_filters_kernel<T>, dim3((n + 255) / 256), dim3(256), 0, s,
+                               static_cast<const T*>(dw_weight), static_cast<T*>(h->wflip), n, taps);
+            return 0;
+        });
+        HIP_TRY(hipGetLastError());
+    }
+    h->ov.on = true;
+    h->ov.q = h->in_st;
+    h->ov.v = h->out_st;
+    h->ov.out = h->in_st;
+    h->ov.generic = h->in_st.b != h->out_st.b || h->in_st.h != h->out_st.h || h->in_st.n != h->out_st.n;
+    h->apply_ready = lin;
+    e = do_apply(h, true, k, grad_out, dw ? h->wflip : nullptr, nullptr, grad_v, s);
+    h->ov.on = false;
+    h->apply_ready = false;
+    HIP_TRY(e);
+    if (dw) {
+        e = typed([&](auto t, auto dc) {
+            size_t unused = 0;
+            return bwd_filter<decltype(t), decltype(dc)::value>(h, true, v, grad_out, &unused, s);
+        });
+        HIP_TRY(e);
+        const int n = d.heads * d.d * (taps + 1);
+        hipLaunchKernelGGL(bwd_filter_combine_kernel, dim3((n + 255) / 256), dim3(256), 0, s, h->fpart,
+                           grad_w, grad_bias, d.B, d.heads, d.d, h->dpad, taps, h->filter_chunks);
+        HIP_TRY(hipGetLastError());
+    } else {
+        if (grad_w) {
+            const int n = d.heads * d.d * taps;
+            hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, grad_w, n);
+        }
+        if (grad_bias) {
+            const int n = d.heads * d.d;
+            hipLaunchKernelGGL(fill_zero_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, grad_bias, n);
+        }
+        HIP_TRY(hipGetLastError());
+    }
+    (void)es;
+    return CASTLING_OK;
 }
 
 int castling_attn_get_state(castling_attn_t h, void* host_f32, size_t bytes, void* stream)

@@ -15,6 +15,14 @@ TOL = {"f32": 1e-4, "bf16": 1e-2, "f16": 1e-3}
 # 1e-2).  The state is an intermediate, not an output of the layer.
 STATE_TOL = {"f32": 1e-4, "bf16": 1e-2, "f16": 2.5e-3}
 
+# Gradients: the forward output is dominated by exactly accumulated terms (vsum / 2, the
+# convolution) with the state-dependent part a correction; a gradient with respect to q or k is
+# linear in the state K_hat^T V (or Q_hat^T a) throughout, so it inherits the state's error
+# (k_hat, and a = g / den, rounded to the I/O type before the contraction) on top of its own
+# output rounding: two to three roundings of 2^-9 (bf16) in a row, about 4.5 standard deviations
+# at the maximum over 10^5 .. 10^6 elements.  fp32 I/O keeps fp32 products: the forward's bound.
+GRAD_TOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2.5e-3}
+
 
 def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     """max_i |g_i - o_i| / max(|o_i|, rms(o)): the layer's parity metric."""

@@ -109,7 +109,8 @@ def test_validate_downsampling_fields():
     # the residual query belongs to the attention branch
     assert b.validate(mk(flags=b.FLAG_RESIDUAL_Q, branches=b.BRANCH_DWCONV)) == b.ERR_INVALID_ARG
     assert b.validate(mk(flags=b.FLAG_RESIDUAL_Q, branches=b.BRANCH_LINEAR)) == b.OK
-    assert b.validate(mk(flags=4)) == b.ERR_INVALID_ARG
+    assert b.validate(mk(flags=b.FLAG_TRAINING)) == b.OK
+    assert b.validate(mk(flags=8)) == b.ERR_INVALID_ARG
     d = mk()
     d.reserved0 = 1
     assert b.validate(d) == b.ERR_INVALID_ARG
@@ -139,3 +140,4 @@ def test_validate_null_and_strerror():
     assert L.castling_attn_apply(None, None, None, None, None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_prepare_weights(None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_get_state(None, None, 0, None) == b.ERR_INVALID_ARG
+    assert L.castling_attn_backward(*([None] * 12)) == b.ERR_INVALID_ARG
