@@ -124,7 +124,9 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             float* qt = st + L::SIZE;                       // q_hat transposed: [D][kQtStride]
             const float* gs = state;
             if (p.n_partials == 1) {
-                for (int i = tid; i < L::SIZE; i += 256) st[i] = gs[i] * (i < L::VSUM ? kInvPi : 0.5f);
+                block_stage<L::SIZE, float>(
+                    tid, [&](int i) { return gs[i]; },
+                    [&](int i, float s) { st[i] = s * (i < L::VSUM ? kInvPi : 0.5f); });
             } else {
                 for (int i = tid; i < L::SIZE; i += 256)
                     st[i] = sum_partials(gs + i, p.n_partials, L::SIZE) * (i < L::VSUM ? kInvPi : 0.5f);
@@ -195,10 +197,20 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             auto entry = [&](int i) {
                 return p.n_partials == 1 ? gs[i] : sum_partials(gs + i, p.n_partials, L::SIZE);
             };
-            for (int idx = tid; idx < (D / 2) * D; idx += 256) {
-                const int ip = idx / D, j = idx % D;
-                st2[idx] = X::pack(entry(L::S + (2 * ip) * D + j) * tscale,
-                                   entry(L::S + (2 * ip + 1) * D + j) * tscale);
+            if (p.n_partials == 1) {
+                block_stage<(D / 2) * D, float2>(
+                    tid,
+                    [&](int idx) {
+                        const int ip = idx / D, j = idx % D;
+                        return make_float2(gs[L::S + (2 * ip) * D + j], gs[L::S + (2 * ip + 1) * D + j]);
+                    },
+                    [&](int idx, float2 s) { st2[idx] = X::pack(s.x * tscale, s.y * tscale); });
+            } else {
+                for (int idx = tid; idx < (D / 2) * D; idx += 256) {
+                    const int ip = idx / D, j = idx % D;
+                    st2[idx] = X::pack(entry(L::S + (2 * ip) * D + j) * tscale,
+                                       entry(L::S + (2 * ip + 1) * D + j) * tscale);
+                }
             }
             for (int idx = tid; idx < D / 2; idx += 256)
                 ks2[idx] = X::pack(entry(L::KSUM + 2 * idx) * tscale, entry(L::KSUM + 2 * idx + 1) * tscale);

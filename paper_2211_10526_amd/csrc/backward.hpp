@@ -29,6 +29,50 @@ struct BwdRowsParams {
     TensorStrides in, out;  // of q, k, v, a and the gradients of q, k; of g
 };
 
+// R consecutive elements at p (R * sizeof(T) a power of two; p aligned to min(that, 16) bytes)
+// as one access, widened to fp32 / narrowed from it.
+template <typename T, int R>
+__device__ __forceinline__ void load_piece(const T* p, float (&x)[R])
+{
+    constexpr int BYTES = sizeof(T) * R;
+    __attribute__((aligned(16))) T tmp[R];
+    if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+        for (int c = 0; c < BYTES / 16; ++c)
+            reinterpret_cast<uint4*>(tmp)[c] = reinterpret_cast<const uint4*>(p)[c];
+    } else if constexpr (BYTES == 8) {
+        *reinterpret_cast<uint2*>(tmp) = *reinterpret_cast<const uint2*>(p);
+    } else if constexpr (BYTES == 4) {
+        *reinterpret_cast<uint32_t*>(tmp) = *reinterpret_cast<const uint32_t*>(p);
+    } else {
+        static_assert(BYTES == 2, "piece of one thread");
+        tmp[0] = *p;
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j) x[j] = IO<T>::to_f32(tmp[j]);
+}
+
+template <typename T, int R>
+__device__ __forceinline__ void store_piece(T* p, const float (&x)[R])
+{
+    constexpr int BYTES = sizeof(T) * R;
+    __attribute__((aligned(16))) T tmp[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) tmp[j] = IO<T>::from_f32(x[j]);
+    if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+        for (int c = 0; c < BYTES / 16; ++c)
+            reinterpret_cast<uint4*>(p)[c] = reinterpret_cast<const uint4*>(tmp)[c];
+    } else if constexpr (BYTES == 8) {
+        *reinterpret_cast<uint2*>(p) = *reinterpret_cast<const uint2*>(tmp);
+    } else if constexpr (BYTES == 4) {
+        *reinterpret_cast<uint32_t*>(p) = *reinterpret_cast<const uint32_t*>(tmp);
+    } else {
+        static_assert(BYTES == 2, "piece of one thread");
+        *p = tmp[0];
+    }
+}
+
 constexpr int kBwdTokens = 64;             // tokens per block
 constexpr int kBwdTStride = kBwdTokens + 4;  // floats; keeps float4 rows aligned
 
@@ -77,10 +121,12 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
     const long long out_off = unit_offset(unit, heads, p.out);
 
     const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
-    for (int i = tid; i < D * D; i += 256) M[(i / D) * MS + i % D] = gs[L::S + i] * kInvPi;
-    for (int i = tid; i < D; i += 256) {
-        vk[i] = (QUERY ? gs[L::KSUM + i] : vec[static_cast<size_t>(unit) * D + i]) * kInvPi;
-        vs[i] = 0.5f * gs[L::VSUM + i];
+    block_stage<D * D, float>(
+        tid, [&](int i) { return gs[L::S + i]; },
+        [&](int i, float s) { M[(i / D) * MS + i % D] = s * kInvPi; });
+    if (tid < D) {
+        vk[tid] = (QUERY ? gs[L::KSUM + tid] : vec[static_cast<size_t>(unit) * D + tid]) * kInvPi;
+        vs[tid] = 0.5f * gs[L::VSUM + tid];
     }
 
     // rows of x -> unit rows, transposed; !QUERY: rows of y (= v) -> at
@@ -145,22 +191,21 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
         for (int t = 0; t < 4; ++t) {
             const int n = n0 + tt * 4 + t;
             const bool live = n < p.N && tj * RJ < p.d_valid;
-            const T* gr = y + out_off + n * p.out.n + tj * RJ;  // y = g
+            if (live) load_piece<T, RJ>(y + out_off + n * p.out.n + tj * RJ, gown[t]);  // y = g
             float gl = 0.f;
             const float rden = 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
 #pragma unroll
-            for (int j = 0; j < RJ; ++j) {
-                gown[t][j] = live ? IO<T>::to_f32(gr[j]) : 0.f;
+            for (int j = 0; j < RJ; ++j)
                 gl = fmaf(gown[t][j], (vs[tj * RJ + j] + num[t][j]) * rden, gl);
-            }
             gl = group_sum<16>(gl);  // g_t . lin_t over all features
             const float bt = p.norm_none ? 0.f : -gl * rden;
+            float av[RJ];
 #pragma unroll
             for (int j = 0; j < RJ; ++j) {
-                const float av = p.norm_none ? gown[t][j] : gown[t][j] * rden;
-                at[(tj * RJ + j) * kBwdTStride + tt * 4 + t] = av;
-                if (live) a_out[in_off + n * p.in.n + tj * RJ + j] = IO<T>::from_f32(av);
+                av[j] = p.norm_none ? gown[t][j] : gown[t][j] * rden;
+                at[(tj * RJ + j) * kBwdTStride + tt * 4 + t] = av[j];
             }
+            if (live) store_piece<T, RJ>(a_out + in_off + n * p.in.n + tj * RJ, av);
             if (tj == 0) bs[tt * 4 + t] = n < p.N ? bt : 0.f;
         }
         __syncthreads();
@@ -204,13 +249,13 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
         dot = group_sum<16>(dot);
         if (small[tl] != 0.f) dot = 0.f;  // below the floor the row is x / eps: no projection
         if (n < p.N && tj * RJ < p.d_valid) {
-            T* o = dx + in_off + n * p.in.n + tj * RJ;
+            float r[RJ];
 #pragma unroll
             for (int j = 0; j < RJ; ++j) {
-                float r = (dxh[t][j] - xh[j] * dot) * inv[tl];
-                if (QUERY && p.residual_q) r += gown[t][j];
-                o[j] = IO<T>::from_f32(r);
+                r[j] = (dxh[t][j] - xh[j] * dot) * inv[tl];
+                if (QUERY && p.residual_q) r[j] += gown[t][j];
             }
+            store_piece<T, RJ>(dx + in_off + n * p.in.n + tj * RJ, r);
         }
     }
 }
@@ -222,9 +267,7 @@ __global__ __launch_bounds__(128) void bwd_vec_combine_kernel(const float* __res
     const int i = threadIdx.x;
     if (i >= D) return;
     const float* src = kb_part + static_cast<size_t>(blockIdx.x) * tiles * D + i;
-    float s = 0.f;
-    for (int t = 0; t < tiles; ++t) s += src[static_cast<size_t>(t) * D];
-    kb[static_cast<size_t>(blockIdx.x) * D + i] = s;
+    kb[static_cast<size_t>(blockIdx.x) * D + i] = sum_partials(src, tiles, D);
 }
 
 // grid = (ceil(n / 256)), block = 256: the filters [heads * d][ks][ks] turned by 180 degrees.
@@ -256,14 +299,20 @@ struct BwdFilterParams {
 template <typename T, int D, int KS>
 constexpr size_t bwd_filter_lds_bytes()
 {
-    return sizeof(T) * (kApplyTH + KS - 1) * (kApplyTW + KS - 1) * D;
+    return sizeof(T) * ((kApplyTH + KS - 1) * (kApplyTW + KS - 1) + kApplyTokens) * D;
 }
 
 // Filter and bias gradients: dw[c][dy][dx] = sum over tokens of g[t][c] v[t + (dy, dx) - r][c],
 // dbias[c] = sum of g[t][c].  grid = (chunks, units), block = 256, dynamic LDS =
-// bwd_filter_lds_bytes.  Thread (part, c) = (tid / D, tid % D) accumulates the taps
-// part, part + 256 / D, ... of channel c (tap KS * KS is the bias) over the block's tiles and
-// writes them to part_out[unit][chunk][tap][D]; v, g point at the first grid token.
+// bwd_filter_lds_bytes.  Thread (part, c) = (tid / (D/2), 2 (tid % (D/2))) accumulates the taps
+// part, part + 512 / D, ... of channels c, c + 1 over the block's tiles (and the sum of g, the
+// bias gradient, as tap KS * KS) and writes them to part_out[unit][chunk][tap][D]; v, g point
+// at the first grid token.
+template <typename T>
+struct alignas(2 * sizeof(T)) ChannelPair {
+    T a, b;
+};
+
 template <typename T, int D, int KS>
 __global__ __launch_bounds__(256) void bwd_filter_kernel(const T* __restrict__ v,
                                                          const T* __restrict__ g,
@@ -274,27 +323,31 @@ __global__ __launch_bounds__(256) void bwd_filter_kernel(const T* __restrict__ v
     constexpr int LPR = D / VEC;
     constexpr int RAD = KS / 2;
     constexpr int HH = kApplyTH + KS - 1, HW = kApplyTW + KS - 1;
-    constexpr int TPC = 256 / D;                    // threads per channel
-    constexpr int NT = KS * KS + 1;                 // taps and the bias
-    constexpr int TAPS = (NT + TPC - 1) / TPC;      // per thread
+    using Pair = ChannelPair<T>;
+    constexpr int TPC = 512 / D;                     // threads per pair of channels
+    constexpr int NT = KS * KS + 1;                  // taps and the bias
+    constexpr int TAPS = (KS * KS + TPC - 1) / TPC;  // per thread
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
     T* vh = reinterpret_cast<T*>(lds_raw);  // [HH][HW][D], zero outside the grid
+    T* gt = vh + HH * HW * D;               // [4 x 16 tokens][D], zero outside the grid
 
     const int tid = threadIdx.x;
     const int unit = blockIdx.y;
-    const int c = tid % D, part = tid / D;
+    const int c = 2 * (tid % (D / 2)), part = tid / (D / 2);
     const long long in_off = unit_offset(unit, heads, p.in);
     const long long out_off = unit_offset(unit, heads, p.out);
 
-    int tap_off[TAPS];  // LDS element offset of the tap relative to the token, -1: bias, -2: none
+    // LDS element offset of the thread's taps relative to a token (taps past the last one read
+    // tap 0 and are dropped at the end)
+    int tap_off[TAPS];
 #pragma unroll
     for (int i = 0; i < TAPS; ++i) {
         const int e = part + TPC * i;
-        tap_off[i] = e < KS * KS ? ((e / KS) * HW + e % KS) * D : (e == KS * KS ? -1 : -2);
+        tap_off[i] = e < KS * KS ? ((e / KS) * HW + e % KS) * D : 0;
     }
-    float acc[TAPS];
+    float acc[TAPS][2], gsum[2] = {0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < TAPS; ++i) acc[i] = 0.f;
+    for (int i = 0; i < TAPS; ++i) acc[i][0] = acc[i][1] = 0.f;
 
     for (int tile = blockIdx.x; tile < p.n_tiles; tile += p.chunks) {
         const int ty0 = (tile / p.tiles_x) * kApplyTH, tx0 = (tile % p.tiles_x) * kApplyTW;
@@ -308,24 +361,32 @@ __global__ __launch_bounds__(256) void bwd_filter_kernel(const T* __restrict__ v
                     v + in_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.in.n + piece * VEC);
             *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tok) * D + piece * VEC) = val;
         }
+        for (int idx = tid; idx < kApplyTokens * LPR; idx += 256) {
+            const int tok = idx / LPR, piece = idx % LPR;
+            const int yy = ty0 + tok / kApplyTW, xx = tx0 + tok % kApplyTW;
+            uint4 val = make_uint4(0u, 0u, 0u, 0u);
+            if (piece * VEC < p.d_valid && yy < p.grid_h && xx < p.grid_w)
+                val = *reinterpret_cast<const uint4*>(
+                    g + out_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.out.n + piece * VEC);
+            *reinterpret_cast<uint4*>(gt + static_cast<size_t>(tok) * D + piece * VEC) = val;
+        }
         __syncthreads();
-#pragma unroll 1
-        for (int ty = 0; ty < kApplyTH; ++ty) {
-            const int yy = ty0 + ty;
-            if (yy >= p.grid_h) break;
-#pragma unroll 4
-            for (int tx = 0; tx < kApplyTW; ++tx) {
-                const int xx = tx0 + tx;
-                float gv = 0.f;
-                if (xx < p.grid_w && c < p.d_valid)
-                    gv = IO<T>::to_f32(g[out_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.out.n + c]);
-                const T* base = vh + (ty * HW + tx) * D + c;
+#pragma unroll 2
+        for (int tok = 0; tok < kApplyTokens; ++tok) {
+            // all LDS reads of a token first, then the arithmetic: the reads overlap each other
+            const Pair gp = *reinterpret_cast<const Pair*>(gt + tok * D + c);
+            const T* base = vh + ((tok / kApplyTW) * HW + tok % kApplyTW) * D + c;
+            Pair vp[TAPS];
 #pragma unroll
-                for (int i = 0; i < TAPS; ++i) {
-                    const float vv = tap_off[i] >= 0 ? IO<T>::to_f32(base[tap_off[i]])
-                                                     : (tap_off[i] == -1 ? 1.f : 0.f);
-                    acc[i] = fmaf(gv, vv, acc[i]);
-                }
+            for (int i = 0; i < TAPS; ++i) vp[i] = *reinterpret_cast<const Pair*>(base + tap_off[i]);
+            __builtin_amdgcn_sched_barrier(0);
+            const float g0 = IO<T>::to_f32(gp.a), g1 = IO<T>::to_f32(gp.b);
+            gsum[0] += g0;
+            gsum[1] += g1;
+#pragma unroll
+            for (int i = 0; i < TAPS; ++i) {
+                acc[i][0] = fmaf(g0, IO<T>::to_f32(vp[i].a), acc[i][0]);
+                acc[i][1] = fmaf(g1, IO<T>::to_f32(vp[i].b), acc[i][1]);
             }
         }
     }
@@ -333,7 +394,14 @@ __global__ __launch_bounds__(256) void bwd_filter_kernel(const T* __restrict__ v
 #pragma unroll
     for (int i = 0; i < TAPS; ++i) {
         const int e = part + TPC * i;
-        if (e < NT) o[e * D + c] = acc[i];
+        if (e < KS * KS) {
+            o[e * D + c] = acc[i][0];
+            o[e * D + c + 1] = acc[i][1];
+        }
+    }
+    if (part == 0) {
+        o[KS * KS * D + c] = gsum[0];
+        o[KS * KS * D + c + 1] = gsum[1];
     }
 }
 
@@ -349,11 +417,11 @@ __global__ __launch_bounds__(256) void bwd_filter_combine_kernel(const float* __
     const int i = blockIdx.x * 256 + threadIdx.x;
     const int nt = taps + 1;
     if (i >= heads * d * nt) return;
-    const int e = i % nt, ch = (i / nt) % d, h = i / (nt * d);
+    const int ch = i % d, e = (i / d) % nt, h = i / (nt * d);  // neighbours read neighbours
     float s = 0.f;
     for (int b = 0; b < B; ++b) {
         const float* src = part + (static_cast<size_t>(b) * heads + h) * chunks * nt * D + e * D + ch;
-        for (int k = 0; k < chunks; ++k) s += src[static_cast<size_t>(k) * nt * D];
+        s += sum_partials(src, chunks, static_cast<size_t>(nt) * D);
     }
     if (e < taps) dw[(static_cast<size_t>(h) * d + ch) * taps + e] = s;
     else if (dbias) dbias[h * d + ch] = s;

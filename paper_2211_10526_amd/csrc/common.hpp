@@ -119,6 +119,30 @@ struct StateLayout {
     static constexpr int SIZE = D * D + 2 * D;
 };
 
+// store(i, load(i)) for i = tid, tid + 256, ... < N by the 256 threads of a block, with the loads
+// of up to sixteen items in flight per thread before the first store (a plain loop of this kind
+// is compiled to one load, one wait, one store per iteration: a chain of memory latencies).
+template <int N, typename V, typename LoadFn, typename StoreFn>
+__device__ __forceinline__ void block_stage(int tid, LoadFn&& load, StoreFn&& store)
+{
+    constexpr int IT = (N + 255) / 256;
+    constexpr int B = IT < 16 ? IT : 16;
+#pragma unroll 1
+    for (int b0 = 0; b0 < IT; b0 += B) {
+        V r[B];
+#pragma unroll
+        for (int k = 0; k < B; ++k) {
+            const int i = tid + 256 * (b0 + k);
+            r[k] = i < N ? load(i) : V{};
+        }
+#pragma unroll
+        for (int k = 0; k < B; ++k) {
+            const int i = tid + 256 * (b0 + k);
+            if (i < N) store(i, r[k]);
+        }
+    }
+}
+
 // Sum of `n` partials that lie `stride` floats apart, in index order, with the loads
 // of sixteen partials in flight at a time (the order of the additions is fixed).
 __device__ __forceinline__ float sum_partials(const float* p, int n, size_t stride)
