@@ -28,6 +28,7 @@ struct ApplyParams {
     TensorStrides qs;
     int vgrid_h, vgrid_w;
     int residual_q;  // 1: the query as stored is added to the result (residual connection)
+    float lin_scale; // factor on the linear branch where there is no normaliser (1 in the forward)
 };
 
 constexpr int kApplyTH = 4;   // tile rows
@@ -175,7 +176,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             }
     #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const float rden = p.norm_none ? 1.0f : 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
+                const float rden = p.norm_none ? p.lin_scale : 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
     #pragma unroll
                 for (int j = 0; j < RJ; ++j) res[t][j] = (st[L::VSUM + tj * RJ + j] + res[t][j]) * rden;
             }
@@ -259,7 +260,7 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
             for (int t = 0; t < 4; ++t) {
                 const float inv = invl[tt * 4 + t] * unsc;
                 const float rden =
-                    p.norm_none ? 1.0f : 1.0f / (0.5f * static_cast<float>(p.N) + inv * den[t]);
+                    p.norm_none ? p.lin_scale : 1.0f / (0.5f * static_cast<float>(p.N) + inv * den[t]);
 #pragma unroll
                 for (int j = 0; j < RJ; ++j) res[t][j] = (vh[tj * RJ + j] + inv * res[t][j]) * rden;
             }

@@ -52,6 +52,7 @@ struct ApplyMfmaParams {
     // Pairs of 32-wide heads run as one 64-channel unit: bytes to add to the address of the
     // second half of a token row (channels 32..63 belong to the next head); 0 otherwise
     uint32_t in_skew, out_skew;
+    float lin_scale;  // factor on the linear branch where there is no normaliser (1 in the forward)
 };
 
 constexpr int kStripW = 16;
@@ -571,8 +572,8 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                         float inv = fminf(__builtin_amdgcn_rsqf(ssr), inv_eps);
                         if constexpr (X::kHalf) inv *= unsc;  // the tables are scaled down
                         if (p.norm_none) {
-                            alpha[hh][r] = inv;
-                            beta[hh][r] = 1.0f;
+                            alpha[hh][r] = inv * p.lin_scale;
+                            beta[hh][r] = p.lin_scale;
                         } else {
                             const float rden = __builtin_amdgcn_rcpf(half_n + inv * dr);
                             alpha[hh][r] = inv * rden;

@@ -26,6 +26,11 @@ struct BwdRowsParams {
     int residual_q;  // QUERY: dq gains g
     int d_valid;     // features per head in memory (<= D)
     float eps;
+    // a is stored times ascale (N with the normaliser: a_t = g_t / den_t is of the order g / N,
+    // below the normal range of fp16 for long sequences; 1 without), so the state of (q, a) is
+    // ascale times S', va'.  mscale: factor on the state matrix as it is loaded (1/pi for the
+    // forward state, 1/(pi ascale) for the state of (q, a)).
+    float ascale, mscale;
     TensorStrides in, out;  // of q, k, v, a and the gradients of q, k; of g
 };
 
@@ -123,7 +128,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
     const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
     block_stage<D * D, float>(
         tid, [&](int i) { return gs[L::S + i]; },
-        [&](int i, float s) { M[(i / D) * MS + i % D] = s * kInvPi; });
+        [&](int i, float s) { M[(i / D) * MS + i % D] = s * p.mscale; });
     if (tid < D) {
         vk[tid] = (QUERY ? gs[L::KSUM + tid] : vec[static_cast<size_t>(unit) * D + tid]) * kInvPi;
         vs[tid] = 0.5f * gs[L::VSUM + tid];
@@ -202,8 +207,9 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
             float av[RJ];
 #pragma unroll
             for (int j = 0; j < RJ; ++j) {
-                av[j] = p.norm_none ? gown[t][j] : gown[t][j] * rden;
-                at[(tj * RJ + j) * kBwdTStride + tt * 4 + t] = av[j];
+                const float a0 = p.norm_none ? gown[t][j] : gown[t][j] * rden;
+                at[(tj * RJ + j) * kBwdTStride + tt * 4 + t] = a0;
+                av[j] = a0 * p.ascale;
             }
             if (live) store_piece<T, RJ>(a_out + in_off + n * p.in.n + tj * RJ, av);
             if (tj == 0) bs[tt * 4 + t] = n < p.N ? bt : 0.f;

@@ -119,6 +119,7 @@ struct castling_attn {
     struct {
         bool on, generic;
         TensorStrides q, v, out;
+        float lin_scale;  // factor on the linear branch (the state of (q, a) is scaled, see backward.hpp)
     } ov;
     // backward workspace (CASTLING_FLAG_TRAINING; part of the one allocation)
     bool training;
@@ -291,6 +292,7 @@ hipError_t apply_generic(castling_attn* h, bool launch, const void* q, const voi
     p.vgrid_h = S == 1 ? p.grid_h : d.grid_h;
     p.vgrid_w = S == 1 ? p.grid_w : d.grid_w;
     p.residual_q = h->residual_q && !h->ov.on;
+    p.lin_scale = h->ov.on ? h->ov.lin_scale : 1.0f;
     const int tiles_y = (p.grid_h + kApplyTH - 1) / kApplyTH;
     hipLaunchKernelGGL((apply_generic_kernel<T, D, KS, S>), dim3(p.tiles_x * tiles_y, h->units),
                        dim3(256), lds, s, static_cast<const T*>(q), static_cast<const T*>(v),
@@ -328,6 +330,7 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     p.out = h->apply_out;
     p.in_skew = h->in_skew;
     p.out_skew = h->out_skew;
+    p.lin_scale = h->ov.on ? h->ov.lin_scale : 1.0f;
     if (DW && w) {
         const int threads = h->apply_heads * 4 * KS * 3 * 64;
         hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0, s,
@@ -462,6 +465,12 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
 }
 
 // ------------------------------------------------------------------ backward
+// the factor a = dLoss/dnum is stored with (see BwdRowsParams)
+float bwd_a_scale(const castling_attn* h)
+{
+    return h->desc.norm == CASTLING_NORM_NONE ? 1.0f : static_cast<float>(h->desc.N);
+}
+
 // launch = false: set the kernels' LDS attributes, record the largest in *lds (create time)
 template <typename T, int D>
 hipError_t bwd_rows(castling_attn* h, bool launch, bool query, const void* x, const void* y,
@@ -486,6 +495,8 @@ hipError_t bwd_rows(castling_attn* h, bool launch, bool query, const void* x, co
     p.residual_q = h->residual_q;
     p.d_valid = d.d;
     p.eps = d.eps;
+    p.ascale = bwd_a_scale(h);
+    p.mscale = query ? kInvPi : kInvPi / p.ascale;
     p.in = h->in_st;
     p.out = h->out_st;
     const dim3 grid(h->row_tiles, h->units);
@@ -837,6 +848,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         const size_t keep = h->apply_lds;
         h->ov.on = h->ov.generic = true;
         h->ov.q = h->ov.v = h->ov.out = h->in_st;
+        h->ov.lin_scale = 1.0f;
         e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
         lds = h->apply_lds;
         h->apply_lds = keep;
@@ -1160,6 +1172,7 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
     h->ov.q = h->in_st;
     h->ov.v = h->out_st;
     h->ov.out = h->in_st;
+    h->ov.lin_scale = 1.0f / bwd_a_scale(h);
     h->ov.generic = h->in_st.b != h->out_st.b || h->in_st.h != h->out_st.h || h->in_st.n != h->out_st.n;
     h->apply_ready = lin;
     e = do_apply(h, true, k, grad_out, dw ? h->wflip : nullptr, nullptr, grad_v, s);

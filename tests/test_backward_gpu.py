@@ -188,3 +188,18 @@ def test_backward_needs_a_training_handle_and_distinct_buffers():
     attn.destroy()
     assert b.validate(b.make_desc(1, 1, 196, 64, 14, 14, 3, "bf16", q_pool=2,
                                   flags=b.FLAG_TRAINING)) == b.ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("name", ["cfg5_bf16_b2_h12_d64_n16384_k9", "x_f16_b2_h12_d64_n16384_k9",
+                                  "cfg1_f32_b1_h4_d32_n196_k3"])
+def test_gradients_at_benchmark_size(oracle, name):
+    """The largest benchmark workload (and its fp16 twin: a = g / den is of the order 1e-4 there,
+    stored scaled) in the configuration bench.py --backward times, every element against the
+    oracle's reassociated backward (itself pinned to the definition)."""
+    wl = inputs.workload(name)
+    x = draw(wl, 0, seed=96)
+    q, k, v, w, _ = oracle_inputs(x)
+    print(f"case backward full size {wl.name}", flush=True)
+    want = oracle.backward(q, k, v, w, inputs.to_f64(x["g"]), wl.grid_h, wl.grid_w)
+    got = run(wl, x)
+    check(got, want, GRAD_TOL[wl.dtype], wl.name)
