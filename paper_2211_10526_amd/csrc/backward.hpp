@@ -16,6 +16,7 @@
 
 #include "apply_generic.hpp"
 #include "common.hpp"
+#include "formats.hpp"
 
 namespace castling {
 
@@ -263,6 +264,267 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
             }
             store_piece<T, RJ>(dx + in_off + n * p.in.n + tj * RJ, r);
         }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The per-row kernel on the matrix cores (16-bit I/O, D = 32 or 64): the two D x D products of a
+// tile of 64 rows run as 16x16x32 MFMAs, wave w on rows 16 w .. 16 w + 15.  Operands: rows as
+// stored (exact) and the state matrix times table_scale rounded once to the I/O format, as in
+// the forward's pass 2 -- here followed by a second 16-bit term holding what the rounding cut off
+// (M = M_hi + M_lo, a = a_hi + a_lo; the lo x lo products are dropped), since a gradient has no
+// exactly accumulated part to hide the operand rounding behind.  The block
+// loads the state once and walks `tiles_per_block` tiles; every row buffer in LDS is private
+// to one wave.  kb_part holds one share per wave: [unit][4 tiles][D].
+// MFMA layouts (lane l): A[m][k]: m = l % 16, k = 8 (l / 16) + 0..7;  B[k][n]: n = l % 16, same k;
+// C[m][n]: n = l % 16, m = 4 (l / 16) + r, r = 0..3.
+// Orders the LDS accesses of one wave for the compiler where a buffer is written through one type
+// and read through another (the hardware runs a wave's LDS instructions in order).
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_wave_barrier();
+    asm volatile("" ::: "memory");
+}
+
+template <int D>
+constexpr size_t bwd_rows_mfma_lds_bytes()
+{
+    return 2 * (4 * static_cast<size_t>(D) * (D + 8) + 4 * kBwdTokens * (D + 8)) +
+           sizeof(float) * (2 * D + 4 * 4 * 16);
+}
+
+template <typename X, int D, bool QUERY>
+__global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __restrict__ x,
+                                                            const uint16_t* __restrict__ y,
+                                                            const float* __restrict__ state,
+                                                            const float* __restrict__ vec,
+                                                            uint16_t* __restrict__ a_out,
+                                                            float* __restrict__ kb_part,
+                                                            uint16_t* __restrict__ dx, int heads,
+                                                            BwdRowsParams p, int tiles_per_block)
+{
+    constexpr int P = D + 8;  // row pitch of the LDS tiles, 16-bit elements
+    constexpr int NT = D / 16, KSTEPS = D / 32;
+    constexpr int PIECES = D / 8;        // 16-byte pieces per row
+    constexpr int RP = 64 / PIECES;      // rows one pass of a wave loads
+    constexpr int PASSES = 16 / RP;
+    using L = StateLayout<D>;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint16_t* Ms = reinterpret_cast<uint16_t*>(lds_raw);  // [D][P]  M[i][c], rounded
+    uint16_t* Mt = Ms + D * P;                            // [D][P]  M[i][c] at [c][i]
+    uint16_t* Msl = Mt + D * P;                           // the same two for M minus its rounding
+    uint16_t* Mtl = Msl + D * P;
+    uint16_t* xr = Mtl + D * P;                           // [64][P] rows of x as stored
+    uint16_t* ar = xr + kBwdTokens * P;                   // [64][P] rows of a (times ascale) / of v
+    uint16_t* al = ar + kBwdTokens * P;                   // [64][P] a minus its rounding (QUERY)
+    uint16_t* gr = al + kBwdTokens * P;                   // [64][P] rows of g; then the result rows
+    float* vk = reinterpret_cast<float*>(gr + kBwdTokens * P);  // ksum / pi  (kb' / pi)
+    float* vs = vk + D;                                          // vsum / 2
+    float* rowf = vs + D;                                        // [wave][inv, den, small, b][16]
+
+    const int tid = threadIdx.x, wave = tid / 64, lane = tid % 64;
+    const int unit = blockIdx.y;
+    const long long in_off = unit_offset(unit, heads, p.in);
+    const long long out_off = unit_offset(unit, heads, p.out);
+    const float ts = X::table_scale(p.N), us = X::table_unscale(p.N);
+    const float post = us / p.ascale;
+
+    const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
+    block_stage<D * D, float>(
+        tid, [&](int i) { return gs[L::S + i]; },
+        [&](int i, float s) {
+            const uint16_t m = static_cast<uint16_t>(X::pack(s * ts, 0.f));
+            const uint16_t ml = static_cast<uint16_t>(X::pack(s * ts - X::one(m), 0.f));
+            Ms[(i / D) * P + i % D] = m;
+            Mt[(i % D) * P + i / D] = m;
+            Msl[(i / D) * P + i % D] = ml;
+            Mtl[(i % D) * P + i / D] = ml;
+        });
+    if (tid < D) {
+        vk[tid] = (QUERY ? gs[L::KSUM + tid] : vec[static_cast<size_t>(unit) * D + tid]) * kInvPi;
+        vs[tid] = 0.5f * gs[L::VSUM + tid];
+    }
+    __syncthreads();
+
+    float* w_inv = rowf + wave * 64;
+    float* w_den = w_inv + 16;
+    float* w_small = w_den + 16;
+    float* w_b = w_small + 16;
+    const int cl = lane % 16, g4 = lane / 16;       // MFMA layouts
+    const int lrow = lane / PIECES, piece = lane % PIECES;  // row I/O
+    uint16_t* my_x = xr + wave * 16 * P;
+    uint16_t* my_a = ar + wave * 16 * P;
+    uint16_t* my_al = al + wave * 16 * P;
+    uint16_t* my_g = gr + wave * 16 * P;
+
+    for (int it = 0; it < tiles_per_block; ++it) {
+        const int tile = blockIdx.x * tiles_per_block + it;
+        if (tile >= p.tiles) break;
+        const int n0 = tile * kBwdTokens + wave * 16;
+
+        // ---- rows in: x -> xr, g -> gr (QUERY) or v -> ar; norms, den
+        u32x4_t xkeep[PASSES];
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int row = ps * RP + lrow, n = n0 + row;
+            u32x4_t xv = {0u, 0u, 0u, 0u}, yv = {0u, 0u, 0u, 0u};
+            if (n < p.N) {
+                xv = *reinterpret_cast<const u32x4_t*>(x + in_off + n * p.in.n + piece * 8);
+                yv = QUERY ? *reinterpret_cast<const u32x4_t*>(y + out_off + n * p.out.n + piece * 8)
+                           : *reinterpret_cast<const u32x4_t*>(y + in_off + n * p.in.n + piece * 8);
+            }
+            xkeep[ps] = xv;
+            *reinterpret_cast<u32x4_t*>(my_x + row * P + piece * 8) = xv;
+            *reinterpret_cast<u32x4_t*>((QUERY ? my_g : my_a) + row * P + piece * 8) = yv;
+            float ss = 0.f, qk = 0.f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lo = X::lo(xv[e]), hi = X::hi(xv[e]);
+                ss = fmaf(lo, lo, fmaf(hi, hi, ss));
+                qk = fmaf(lo, vk[piece * 8 + 2 * e], fmaf(hi, vk[piece * 8 + 2 * e + 1], qk));
+            }
+            ss = row_group_sum<PIECES>(ss);
+            qk = row_group_sum<PIECES>(qk);
+            const float nrm = sqrtf(ss);
+            const float r = 1.0f / fmaxf(nrm, p.eps);
+            if (piece == 0) {
+                w_inv[row] = r;
+                w_den[row] = 0.5f * static_cast<float>(p.N) + r * qk;
+                w_small[row] = nrm < p.eps ? 1.f : 0.f;
+                w_b[row] = 1.f;
+            }
+        }
+        wave_lds_fence();
+        float inv_r[4], b_r[4], small_r[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            inv_r[r] = w_inv[4 * g4 + r];
+            small_r[r] = w_small[4 * g4 + r];
+            b_r[r] = 1.f;
+        }
+
+        float gC[NT][4];  // QUERY: g in the C layout (kept for the residual)
+        if (QUERY) {
+            // ---- num = vs + inv us (q M): product 1, B = columns of M read from Mt
+            f32x4_t acc1[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc1[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KSTEPS; ++ks) {
+                const u32x4_t A = *reinterpret_cast<const u32x4_t*>(my_x + cl * P + ks * 32 + 8 * g4);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int off = (nt * 16 + cl) * P + ks * 32 + 8 * g4;
+                    acc1[nt] = X::mfma16(A, *reinterpret_cast<const u32x4_t*>(Mt + off), acc1[nt]);
+                    acc1[nt] = X::mfma16(A, *reinterpret_cast<const u32x4_t*>(Mtl + off), acc1[nt]);
+                }
+            }
+            float rden[4], gl[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) rden[r] = 1.0f / w_den[4 * g4 + r];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int c = nt * 16 + cl;
+                    gC[nt][r] = X::one(my_g[(4 * g4 + r) * P + c]);
+                    const float lin = (vs[c] + inv_r[r] * us * acc1[nt][r]) * rden[r];
+                    gl[r] = fmaf(gC[nt][r], lin, gl[r]);
+                }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                gl[r] = row_group_sum<16>(gl[r]);  // g_t . lin_t over all features
+                b_r[r] = p.norm_none ? 0.f : -gl[r] * rden[r];
+                if (cl == 0) w_b[4 * g4 + r] = b_r[r];
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float a0 = (p.norm_none ? gC[nt][r] : gC[nt][r] * rden[r]) * p.ascale;
+                    const uint16_t ah = static_cast<uint16_t>(X::pack(a0, 0.f));
+                    my_a[(4 * g4 + r) * P + nt * 16 + cl] = ah;
+                    my_al[(4 * g4 + r) * P + nt * 16 + cl] =
+                        static_cast<uint16_t>(X::pack(a0 - X::one(ah), 0.f));
+                }
+            wave_lds_fence();
+            // ---- rows of a out; this wave's share of kb' = sum_t q_hat_t b_t
+            float kbp[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                const int row = ps * RP + lrow, n = n0 + row;
+                if (n < p.N)
+                    *reinterpret_cast<u32x4_t*>(a_out + in_off + n * p.in.n + piece * 8) =
+                        *reinterpret_cast<const u32x4_t*>(my_a + row * P + piece * 8);
+                const float wgt = w_inv[row] * w_b[row];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    kbp[2 * e] = fmaf(X::lo(xkeep[ps][e]), wgt, kbp[2 * e]);
+                    kbp[2 * e + 1] = fmaf(X::hi(xkeep[ps][e]), wgt, kbp[2 * e + 1]);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int m = PIECES; m < 64; m <<= 1) kbp[e] += __shfl_xor(kbp[e], m, 64);
+            if (lrow == 0) {
+                float* o = kb_part + ((static_cast<size_t>(unit) * p.tiles + tile) * 4 + wave) * D + piece * 8;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[e] = kbp[e];
+            }
+        }
+
+        // ---- dx_hat = post (a M^T) + vk b: product 2, B = rows of M
+        f32x4_t acc2[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc2[nt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KSTEPS; ++ks) {
+            const u32x4_t A = *reinterpret_cast<const u32x4_t*>(my_a + cl * P + ks * 32 + 8 * g4);
+            u32x4_t Al = {0u, 0u, 0u, 0u};
+            if (QUERY) Al = *reinterpret_cast<const u32x4_t*>(my_al + cl * P + ks * 32 + 8 * g4);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const int off = (nt * 16 + cl) * P + ks * 32 + 8 * g4;
+                const u32x4_t B = *reinterpret_cast<const u32x4_t*>(Ms + off);
+                acc2[nt] = X::mfma16(A, B, acc2[nt]);
+                acc2[nt] = X::mfma16(A, *reinterpret_cast<const u32x4_t*>(Msl + off), acc2[nt]);
+                if (QUERY) acc2[nt] = X::mfma16(Al, B, acc2[nt]);  // (rows of v are exact as stored)
+            }
+        }
+        float dxh[NT][4], xh[NT][4], dot[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = nt * 16 + cl;
+                dxh[nt][r] = fmaf(acc2[nt][r], post, vk[i] * b_r[r]);
+                xh[nt][r] = X::one(my_x[(4 * g4 + r) * P + i]) * inv_r[r];
+                dot[r] = fmaf(xh[nt][r], dxh[nt][r], dot[r]);
+            }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            dot[r] = row_group_sum<16>(dot[r]);
+            if (small_r[r] != 0.f) dot[r] = 0.f;  // below the floor the row is x / eps: no projection
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float res = (dxh[nt][r] - xh[nt][r] * dot[r]) * inv_r[r];
+                if (QUERY && p.residual_q) res += gC[nt][r];
+                my_g[(4 * g4 + r) * P + nt * 16 + cl] = static_cast<uint16_t>(X::pack(res, 0.f));
+            }
+        wave_lds_fence();
+        // ---- result rows out
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int row = ps * RP + lrow, n = n0 + row;
+            if (n < p.N)
+                *reinterpret_cast<u32x4_t*>(dx + in_off + n * p.in.n + piece * 8) =
+                    *reinterpret_cast<const u32x4_t*>(my_g + row * P + piece * 8);
+        }
+        wave_lds_fence();
     }
 }
 

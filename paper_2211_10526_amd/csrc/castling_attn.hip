@@ -129,6 +129,8 @@ struct castling_attn {
     void* wflip;        // filters turned by 180 degrees
     float* fpart;       // [units][filter chunks][ks*ks + 1][dpad]
     int row_tiles, filter_chunks;
+    bool mfma_rows;     // dq / dk on the matrix cores (16-bit, d = 32 or 64)
+    int kb_parts;       // shares of kb' per unit
 };
 
 namespace {
@@ -472,10 +474,59 @@ float bwd_a_scale(const castling_attn* h)
 }
 
 // launch = false: set the kernels' LDS attributes, record the largest in *lds (create time)
+template <typename X, int D>
+hipError_t bwd_rows_mfma(castling_attn* h, bool launch, bool query, const void* x, const void* y,
+                         void* dx, size_t* lds, hipStream_t s, const BwdRowsParams& p)
+{
+    constexpr size_t bytes = bwd_rows_mfma_lds_bytes<D>();
+    if (!launch) {
+        if (bytes > *lds) *lds = bytes;
+        hipError_t e = hipFuncSetAttribute(
+            reinterpret_cast<const void*>(&bwd_rows_mfma_kernel<X, D, true>),
+            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+        if (e != hipSuccess) return e;
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_rows_mfma_kernel<X, D, false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
+    }
+    // the block loads the state once: several tiles per block where there are many
+    const long long all = static_cast<long long>(h->row_tiles) * h->units;
+    const int tpb = static_cast<int>(std::max(1ll, std::min(8ll, all / 2048)));
+    const dim3 grid((h->row_tiles + tpb - 1) / tpb, h->units);
+    auto u16 = [](const void* ptr) { return static_cast<const uint16_t*>(ptr); };
+    if (query)
+        hipLaunchKernelGGL((bwd_rows_mfma_kernel<X, D, true>), grid, dim3(256), bytes, s, u16(x), u16(y),
+                           h->state, nullptr, static_cast<uint16_t*>(h->a_buf), h->kb_part,
+                           static_cast<uint16_t*>(dx), h->desc.heads, p, tpb);
+    else
+        hipLaunchKernelGGL((bwd_rows_mfma_kernel<X, D, false>), grid, dim3(256), bytes, s, u16(x), u16(y),
+                           h->state, h->kb, nullptr, nullptr, static_cast<uint16_t*>(dx),
+                           h->desc.heads, p, tpb);
+    return hipGetLastError();
+}
+
 template <typename T, int D>
 hipError_t bwd_rows(castling_attn* h, bool launch, bool query, const void* x, const void* y,
                     void* dx, size_t* lds, hipStream_t s)
 {
+    if constexpr (sizeof(T) == 2 && (D == 32 || D == 64)) {
+        if (h->mfma_rows) {
+            BwdRowsParams p = {};
+            if (launch) {
+                const castling_attn_desc_t& d = h->desc;
+                p.N = d.N;
+                p.tiles = h->row_tiles;
+                p.norm_none = d.norm == CASTLING_NORM_NONE;
+                p.residual_q = h->residual_q;
+                p.d_valid = d.d;
+                p.eps = d.eps;
+                p.ascale = bwd_a_scale(h);
+                p.in = h->in_st;
+                p.out = h->out_st;
+            }
+            return h->half16 ? bwd_rows_mfma<F16Fmt, D>(h, launch, query, x, y, dx, lds, s, p)
+                             : bwd_rows_mfma<Bf16Fmt, D>(h, launch, query, x, y, dx, lds, s, p);
+        }
+    }
     constexpr size_t bytes = bwd_rows_lds_bytes<D>();
     if (!launch) {
         if (bytes > *lds) *lds = bytes;
@@ -843,6 +894,8 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->training = (desc->flags & CASTLING_FLAG_TRAINING) != 0;
     h->ov.on = h->ov.generic = false;
     size_t a_bytes = 0, kbp_bytes = 0, kb_bytes = 0, wflip_bytes = 0, fpart_bytes = 0;
+    // CASTLING_ATTN_FORCE_GENERIC=1 keeps the per-row kernels of the backward off the matrix cores too
+    h->mfma_rows = allow_mfma && (desc->d == 32 || desc->d == 64);
     if (e == hipSuccess && h->training) {
         size_t lds = 0;
         const size_t keep = h->apply_lds;
@@ -869,9 +922,10 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         const int n_tiles = ((desc->grid_w + kApplyTW - 1) / kApplyTW) *
                             ((desc->grid_h + kApplyTH - 1) / kApplyTH);
         h->row_tiles = (desc->N + kBwdTokens - 1) / kBwdTokens;
+        h->kb_parts = h->mfma_rows ? 4 * h->row_tiles : h->row_tiles;
         h->filter_chunks = std::max(1, std::min(n_tiles, 2048 / h->units));
         a_bytes = align_up(h->in_span, 256);
-        kbp_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->row_tiles * h->dpad, 256);
+        kbp_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->kb_parts * h->dpad, 256);
         kb_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->dpad, 256);
         wflip_bytes = align_up(dtype_size(desc->io_dtype) * static_cast<size_t>(desc->heads) * desc->d *
                                    (taps1 - 1), 256);
@@ -1134,7 +1188,7 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         });
         HIP_TRY(e);
         hipLaunchKernelGGL(bwd_vec_combine_kernel, dim3(h->units), dim3(128), 0, s, h->kb_part, h->kb,
-                           h->row_tiles, h->dpad);
+                           h->kb_parts, h->dpad);
         HIP_TRY(hipGetLastError());
         st = do_reduce(h, q, h->a_buf, nullptr, s);
         if (st != CASTLING_OK) return st;
