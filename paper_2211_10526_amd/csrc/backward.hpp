@@ -528,14 +528,26 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
     }
 }
 
-// grid = (units), block = 128: kb[unit][i] = sum over tiles of kb_part[unit][tile][i], in order.
-__global__ __launch_bounds__(128) void bwd_vec_combine_kernel(const float* __restrict__ kb_part,
-                                                              float* __restrict__ kb, int tiles, int D)
+// grid = (units), block = 1024: kb[unit][i] = sum over the shares kb_part[unit][share][i].  The
+// 1024 / D slices of the block each sum a contiguous run of shares in order; slice 0 adds the
+// slice sums in order (a fixed order of additions: the result is deterministic).
+__global__ __launch_bounds__(1024) void bwd_vec_combine_kernel(const float* __restrict__ kb_part,
+                                                               float* __restrict__ kb, int parts, int D)
 {
-    const int i = threadIdx.x;
-    if (i >= D) return;
-    const float* src = kb_part + static_cast<size_t>(blockIdx.x) * tiles * D + i;
-    kb[static_cast<size_t>(blockIdx.x) * D + i] = sum_partials(src, tiles, D);
+    __shared__ float red[1024];
+    const int tid = threadIdx.x;
+    const int i = tid % D, sl = tid / D, nsl = 1024 / D;
+    const int per = (parts + nsl - 1) / nsl;
+    const int p0 = sl * per;
+    const int cnt = parts - p0 < per ? parts - p0 : per;
+    const float* src = kb_part + (static_cast<size_t>(blockIdx.x) * parts + p0) * D + i;
+    red[tid] = cnt > 0 ? sum_partials(src, cnt, D) : 0.f;
+    __syncthreads();
+    if (sl == 0) {
+        float s = red[i];
+        for (int k = 1; k < nsl; ++k) s += red[k * D + i];
+        kb[static_cast<size_t>(blockIdx.x) * D + i] = s;
+    }
 }
 
 // grid = (ceil(n / 256)), block = 256: the filters [heads * d][ks][ks] turned by 180 degrees.
@@ -564,113 +576,220 @@ struct BwdFilterParams {
     TensorStrides in, out;  // of v; of g
 };
 
-template <typename T, int D, int KS>
-constexpr size_t bwd_filter_lds_bytes()
-{
-    return sizeof(T) * ((kApplyTH + KS - 1) * (kApplyTW + KS - 1) + kApplyTokens) * D;
-}
-
-// Filter and bias gradients: dw[c][dy][dx] = sum over tokens of g[t][c] v[t + (dy, dx) - r][c],
-// dbias[c] = sum of g[t][c].  grid = (chunks, units), block = 256, dynamic LDS =
-// bwd_filter_lds_bytes.  Thread (part, c) = (tid / (D/2), 2 (tid % (D/2))) accumulates the taps
-// part, part + 512 / D, ... of channels c, c + 1 over the block's tiles (and the sum of g, the
-// bias gradient, as tap KS * KS) and writes them to part_out[unit][chunk][tap][D]; v, g point
-// at the first grid token.
 template <typename T>
 struct alignas(2 * sizeof(T)) ChannelPair {
     T a, b;
 };
 
+constexpr int kBwdFilterThreads = 512;
+
+// 16-byte piece idx of a tile's LDS image: the halo tile of v ([HH][HW][D], zero outside the
+// grid) and behind it the 4 x 16 tile of g.
 template <typename T, int D, int KS>
-__global__ __launch_bounds__(256) void bwd_filter_kernel(const T* __restrict__ v,
-                                                         const T* __restrict__ g,
-                                                         float* __restrict__ part_out, int heads,
-                                                         BwdFilterParams p)
+__device__ __forceinline__ uint4 bwd_filter_piece(const T* __restrict__ v, const T* __restrict__ g,
+                                                  const BwdFilterParams& p, long long in_off,
+                                                  long long out_off, int tile, int idx)
 {
     constexpr int VEC = IO<T>::VEC;
     constexpr int LPR = D / VEC;
-    constexpr int RAD = KS / 2;
+    constexpr int HH = kApplyTH + KS - 1, HW = kApplyTW + KS - 1;
+    const int ty0 = (tile / p.tiles_x) * kApplyTH, tx0 = (tile % p.tiles_x) * kApplyTW;
+    const int tok = idx / LPR, piece = idx % LPR;
+    const bool halo = tok < HH * HW;
+    const int gtok = tok - HH * HW;
+    const int yy = halo ? ty0 - KS / 2 + tok / HW : ty0 + gtok / kApplyTW;
+    const int xx = halo ? tx0 - KS / 2 + tok % HW : tx0 + gtok % kApplyTW;
+    uint4 val = make_uint4(0u, 0u, 0u, 0u);
+    if (idx < (HH * HW + kApplyTokens) * LPR && piece * VEC < p.d_valid && yy >= 0 && yy < p.grid_h &&
+        xx >= 0 && xx < p.grid_w) {
+        const long long at = (static_cast<long long>(yy) * p.grid_w + xx);
+        val = halo ? *reinterpret_cast<const uint4*>(v + in_off + at * p.in.n + piece * VEC)
+                   : *reinterpret_cast<const uint4*>(g + out_off + at * p.out.n + piece * VEC);
+    }
+    return val;
+}
+
+// Two LDS images (the next tile's loads are in flight while this one is worked on) where a
+// thread holds few pieces of an image and both fit.
+template <typename T, int D, int KS>
+constexpr bool bwd_filter_double_buffered()
+{
+    const size_t image = sizeof(T) * ((kApplyTH + KS - 1) * (kApplyTW + KS - 1) + kApplyTokens) * D;
+    return image / 16 <= 6 * kBwdFilterThreads && 2 * image <= 100 * 1024;
+}
+
+template <typename T, int D, int KS>
+constexpr size_t bwd_filter_lds_bytes()
+{
+    // halo tile of v and tile of g; afterwards the block's sums [KS * KS + 1][D] in fp32
+    const size_t tiles = sizeof(T) * ((kApplyTH + KS - 1) * (kApplyTW + KS - 1) + kApplyTokens) * D *
+                         (bwd_filter_double_buffered<T, D, KS>() ? 2 : 1);
+    const size_t sums = sizeof(float) * (KS * KS + 1) * D;
+    return tiles > sums ? tiles : sums;
+}
+
+// Filter and bias gradients: dw[c][dy][dx] = sum over tokens of g[t][c] v[t + (dy, dx) - r][c],
+// dbias[c] = sum of g[t][c].  grid = (chunks, units), block = 512, dynamic LDS =
+// bwd_filter_lds_bytes; v, g point at the first grid token.  The block walks its 4 x 16 tiles
+// (halo tile of v and tile of g in LDS).  A thread owns two channels, one tile row ty and the
+// filter rows dy = part / 4, part / 4 + TPC / 4, ... (part = tid / (D / 2), TPC = 1024 / D parts):
+// per tile and half row it reads 8 tokens of g's row ty and, per filter row, the KS + 7 tokens
+// of v's row ty + dy they meet, and slides the one over the other in registers.  At the end the four tile
+// rows meet in LDS in the order ty = 0, 1, 2, 3 (a fixed order of additions) and the block writes
+// part_out[unit][chunk][tap][D] (tap KS * KS: the sum of g, the bias gradient).
+template <typename T, int D, int KS>
+__global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_kernel(const T* __restrict__ v,
+                                                                       const T* __restrict__ g,
+                                                                       float* __restrict__ part_out,
+                                                                       int heads, BwdFilterParams p)
+{
+    constexpr int NTHR = kBwdFilterThreads;
+    constexpr int VEC = IO<T>::VEC;
+    constexpr int LPR = D / VEC;
     constexpr int HH = kApplyTH + KS - 1, HW = kApplyTW + KS - 1;
     using Pair = ChannelPair<T>;
-    constexpr int TPC = 512 / D;                     // threads per pair of channels
-    constexpr int NT = KS * KS + 1;                  // taps and the bias
-    constexpr int TAPS = (KS * KS + TPC - 1) / TPC;  // per thread
+    constexpr int TPC = 2 * NTHR / D;              // threads per pair of channels
+    constexpr int DYS = TPC / 4;                   // filter rows taken at a time
+    constexpr int IPT = (KS + DYS - 1) / DYS;      // filter rows per thread
+    constexpr int NT = KS * KS + 1;                // taps and the bias
+    static_assert(TPC % 4 == 0, "a thread keeps one tile row");
     extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-    T* vh = reinterpret_cast<T*>(lds_raw);  // [HH][HW][D], zero outside the grid
-    T* gt = vh + HH * HW * D;               // [4 x 16 tokens][D], zero outside the grid
+    T* vh = reinterpret_cast<T*>(lds_raw);  // image(s): [HH][HW][D] of v, then [4 x 16][D] of g
 
     const int tid = threadIdx.x;
     const int unit = blockIdx.y;
     const int c = 2 * (tid % (D / 2)), part = tid / (D / 2);
+    const int ty = part % 4, dy0 = part / 4;
     const long long in_off = unit_offset(unit, heads, p.in);
     const long long out_off = unit_offset(unit, heads, p.out);
 
-    // LDS element offset of the thread's taps relative to a token (taps past the last one read
-    // tap 0 and are dropped at the end)
-    int tap_off[TAPS];
+    float acc[IPT][KS][2], gsum[2] = {0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < TAPS; ++i) {
-        const int e = part + TPC * i;
-        tap_off[i] = e < KS * KS ? ((e / KS) * HW + e % KS) * D : 0;
-    }
-    float acc[TAPS][2], gsum[2] = {0.f, 0.f};
+    for (int i = 0; i < IPT; ++i)
 #pragma unroll
-    for (int i = 0; i < TAPS; ++i) acc[i][0] = acc[i][1] = 0.f;
+        for (int dx = 0; dx < KS; ++dx) acc[i][dx][0] = acc[i][dx][1] = 0.f;
 
-    for (int tile = blockIdx.x; tile < p.n_tiles; tile += p.chunks) {
-        const int ty0 = (tile / p.tiles_x) * kApplyTH, tx0 = (tile % p.tiles_x) * kApplyTW;
-        __syncthreads();  // the previous tile's reads are done
-        for (int idx = tid; idx < HH * HW * LPR; idx += 256) {
-            const int tok = idx / LPR, piece = idx % LPR;
-            const int yy = ty0 - RAD + tok / HW, xx = tx0 - RAD + tok % HW;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (piece * VEC < p.d_valid && yy >= 0 && yy < p.grid_h && xx >= 0 && xx < p.grid_w)
-                val = *reinterpret_cast<const uint4*>(
-                    v + in_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.in.n + piece * VEC);
-            *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tok) * D + piece * VEC) = val;
-        }
-        for (int idx = tid; idx < kApplyTokens * LPR; idx += 256) {
-            const int tok = idx / LPR, piece = idx % LPR;
-            const int yy = ty0 + tok / kApplyTW, xx = tx0 + tok % kApplyTW;
-            uint4 val = make_uint4(0u, 0u, 0u, 0u);
-            if (piece * VEC < p.d_valid && yy < p.grid_h && xx < p.grid_w)
-                val = *reinterpret_cast<const uint4*>(
-                    g + out_off + (static_cast<long long>(yy) * p.grid_w + xx) * p.out.n + piece * VEC);
-            *reinterpret_cast<uint4*>(gt + static_cast<size_t>(tok) * D + piece * VEC) = val;
+    constexpr bool DB = bwd_filter_double_buffered<T, D, KS>();
+    constexpr int IMAGE = (HH * HW + kApplyTokens) * D;     // elements of one LDS image
+    constexpr int PIECES = (IMAGE / VEC + NTHR - 1) / NTHR;  // 16-byte pieces per thread
+    uint4 pre[DB ? PIECES : 1];
+    int buf = 0;
+    if constexpr (DB) {
+        if (blockIdx.x < p.n_tiles) {
+#pragma unroll
+            for (int k = 0; k < PIECES; ++k)
+                pre[k] = bwd_filter_piece<T, D, KS>(v, g, p, in_off, out_off, blockIdx.x, tid + NTHR * k);
+#pragma unroll
+            for (int k = 0; k < PIECES; ++k)
+                if (tid + NTHR * k < IMAGE / VEC)
+                    *reinterpret_cast<uint4*>(vh + static_cast<size_t>(tid + NTHR * k) * VEC) = pre[k];
         }
         __syncthreads();
-#pragma unroll 2
-        for (int tok = 0; tok < kApplyTokens; ++tok) {
-            // all LDS reads of a token first, then the arithmetic: the reads overlap each other
-            const Pair gp = *reinterpret_cast<const Pair*>(gt + tok * D + c);
-            const T* base = vh + ((tok / kApplyTW) * HW + tok % kApplyTW) * D + c;
-            Pair vp[TAPS];
+    }
+    for (int tile = blockIdx.x; tile < p.n_tiles; tile += p.chunks) {
+        if constexpr (DB) {
+            // the next tile's loads go out now and land in the other image after this tile's work
+            if (tile + p.chunks < p.n_tiles) {
 #pragma unroll
-            for (int i = 0; i < TAPS; ++i) vp[i] = *reinterpret_cast<const Pair*>(base + tap_off[i]);
-            __builtin_amdgcn_sched_barrier(0);
-            const float g0 = IO<T>::to_f32(gp.a), g1 = IO<T>::to_f32(gp.b);
-            gsum[0] += g0;
-            gsum[1] += g1;
+                for (int k = 0; k < PIECES; ++k)
+                    pre[k] = bwd_filter_piece<T, D, KS>(v, g, p, in_off, out_off, tile + p.chunks,
+                                                        tid + NTHR * k);
+            }
+        } else {
+            __syncthreads();  // the previous tile's reads are done
+            block_stage<IMAGE / VEC, uint4, NTHR, 6>(
+                tid,
+                [&](int idx) { return bwd_filter_piece<T, D, KS>(v, g, p, in_off, out_off, tile, idx); },
+                [&](int idx, uint4 val) {
+                    *reinterpret_cast<uint4*>(vh + static_cast<size_t>(idx) * VEC) = val;
+                });
+            __syncthreads();
+        }
+        const T* vcur = vh + buf * IMAGE;
+        const T* gcur = vcur + HH * HW * D;
+
+        // half a tile row at a time (fewer registers): 8 tokens of g against KS + 7 tokens of v
+#pragma unroll 1
+        for (int half = 0; half < 2; ++half) {
+            constexpr int TXH = kApplyTW / 2, WINH = TXH + KS - 1;
+            float g0[TXH], g1[TXH];
 #pragma unroll
-            for (int i = 0; i < TAPS; ++i) {
-                acc[i][0] = fmaf(g0, IO<T>::to_f32(vp[i].a), acc[i][0]);
-                acc[i][1] = fmaf(g1, IO<T>::to_f32(vp[i].b), acc[i][1]);
+            for (int tx = 0; tx < TXH; ++tx) {
+                const Pair gp = *reinterpret_cast<const Pair*>(gcur + (ty * kApplyTW + half * TXH + tx) * D + c);
+                g0[tx] = IO<T>::to_f32(gp.a);
+                g1[tx] = IO<T>::to_f32(gp.b);
+            }
+            if (dy0 == 0) {
+#pragma unroll
+                for (int tx = 0; tx < TXH; ++tx) {
+                    gsum[0] += g0[tx];
+                    gsum[1] += g1[tx];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < IPT; ++i) {
+                const int dy = dy0 + DYS * i;
+                if (dy < KS) {  // (the same for all lanes of a wave where D >= 32)
+                    float w0[WINH], w1[WINH];
+#pragma unroll
+                    for (int x = 0; x < WINH; ++x) {
+                        const Pair wp = *reinterpret_cast<const Pair*>(
+                            vcur + ((ty + dy) * HW + half * TXH + x) * D + c);
+                        w0[x] = IO<T>::to_f32(wp.a);
+                        w1[x] = IO<T>::to_f32(wp.b);
+                    }
+#pragma unroll
+                    for (int tx = 0; tx < TXH; ++tx)
+#pragma unroll
+                        for (int dx = 0; dx < KS; ++dx) {
+                            acc[i][dx][0] = fmaf(g0[tx], w0[tx + dx], acc[i][dx][0]);
+                            acc[i][dx][1] = fmaf(g1[tx], w1[tx + dx], acc[i][dx][1]);
+                        }
+                }
+                __builtin_amdgcn_sched_barrier(0);  // one window in registers at a time
             }
         }
-    }
-    float* o = part_out + (static_cast<size_t>(unit) * p.chunks + blockIdx.x) * NT * D;
+        if constexpr (DB) {
+            if (tile + p.chunks < p.n_tiles) {
+                T* vnext = vh + (buf ^ 1) * IMAGE;
 #pragma unroll
-    for (int i = 0; i < TAPS; ++i) {
-        const int e = part + TPC * i;
-        if (e < KS * KS) {
-            o[e * D + c] = acc[i][0];
-            o[e * D + c + 1] = acc[i][1];
+                for (int k = 0; k < PIECES; ++k)
+                    if (tid + NTHR * k < IMAGE / VEC)
+                        *reinterpret_cast<uint4*>(vnext + static_cast<size_t>(tid + NTHR * k) * VEC) = pre[k];
+            }
+            __syncthreads();
+            buf ^= 1;
         }
     }
-    if (part == 0) {
-        o[KS * KS * D + c] = gsum[0];
-        o[KS * KS * D + c + 1] = gsum[1];
+
+    // the four tile rows of a tap meet in LDS, in order
+    __syncthreads();
+    float* sums = reinterpret_cast<float*>(lds_raw);  // [NT][D]
+#pragma unroll 1
+    for (int ph = 0; ph < 4; ++ph) {
+        if (ty == ph) {
+#pragma unroll
+            for (int i = 0; i < IPT; ++i) {
+                const int dy = dy0 + DYS * i;
+                if (dy < KS) {
+#pragma unroll
+                    for (int dx = 0; dx < KS; ++dx) {
+                        float* s = sums + (dy * KS + dx) * D + c;
+                        s[0] = ph == 0 ? acc[i][dx][0] : s[0] + acc[i][dx][0];
+                        s[1] = ph == 0 ? acc[i][dx][1] : s[1] + acc[i][dx][1];
+                    }
+                }
+            }
+            if (dy0 == 0) {
+                float* s = sums + KS * KS * D + c;
+                s[0] = ph == 0 ? gsum[0] : s[0] + gsum[0];
+                s[1] = ph == 0 ? gsum[1] : s[1] + gsum[1];
+            }
+        }
+        __syncthreads();
     }
+    float* o = part_out + (static_cast<size_t>(unit) * p.chunks + blockIdx.x) * NT * D;
+    for (int idx = tid; idx < NT * D; idx += NTHR) o[idx] = sums[idx];
 }
 
 // grid = (ceil(heads * d * (taps + 1) / 256)), block = 256: sums the partial filter gradients

@@ -567,6 +567,11 @@ hipError_t bwd_filter_ks(castling_attn* h, bool launch, const void* v, const voi
                          hipStream_t s)
 {
     constexpr size_t bytes = bwd_filter_lds_bytes<T, D, KS>();
+    if constexpr (bytes > kMaxLdsBytes) {
+        // more LDS than a compute unit has: create refuses the shape, no kernel is built for it
+        if (bytes > *lds) *lds = bytes;
+        return launch ? hipErrorInvalidValue : hipSuccess;
+    } else {
     if (!launch) {
         if (bytes > *lds) *lds = bytes;
         if (bytes > kMaxLdsBytes) return hipSuccess;
@@ -586,9 +591,11 @@ hipError_t bwd_filter_ks(castling_attn* h, bool launch, const void* v, const voi
     // the class tokens in front of the grid take no part in the convolution
     const T* vg = static_cast<const T*>(v) + static_cast<long long>(d.extra_tokens) * h->in_st.n;
     const T* gg = static_cast<const T*>(g) + static_cast<long long>(d.extra_tokens) * h->out_st.n;
-    hipLaunchKernelGGL((bwd_filter_kernel<T, D, KS>), dim3(h->filter_chunks, h->units), dim3(256),
+    hipLaunchKernelGGL((bwd_filter_kernel<T, D, KS>), dim3(h->filter_chunks, h->units),
+                       dim3(kBwdFilterThreads),
                        bytes, s, vg, gg, h->fpart, d.heads, p);
     return hipGetLastError();
+    }
 }
 
 template <typename T, int D>
@@ -923,7 +930,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
                             ((desc->grid_h + kApplyTH - 1) / kApplyTH);
         h->row_tiles = (desc->N + kBwdTokens - 1) / kBwdTokens;
         h->kb_parts = h->mfma_rows ? 4 * h->row_tiles : h->row_tiles;
-        h->filter_chunks = std::max(1, std::min(n_tiles, 2048 / h->units));
+        h->filter_chunks = std::max(1, std::min(n_tiles, 1024 / h->units));
         a_bytes = align_up(h->in_span, 256);
         kbp_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->kb_parts * h->dpad, 256);
         kb_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->dpad, 256);
@@ -1187,7 +1194,7 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
                                                                nullptr, s);
         });
         HIP_TRY(e);
-        hipLaunchKernelGGL(bwd_vec_combine_kernel, dim3(h->units), dim3(128), 0, s, h->kb_part, h->kb,
+        hipLaunchKernelGGL(bwd_vec_combine_kernel, dim3(h->units), dim3(1024), 0, s, h->kb_part, h->kb,
                            h->kb_parts, h->dpad);
         HIP_TRY(hipGetLastError());
         st = do_reduce(h, q, h->a_buf, nullptr, s);

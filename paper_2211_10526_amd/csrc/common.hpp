@@ -119,25 +119,25 @@ struct StateLayout {
     static constexpr int SIZE = D * D + 2 * D;
 };
 
-// store(i, load(i)) for i = tid, tid + 256, ... < N by the 256 threads of a block, with the loads
-// of up to sixteen items in flight per thread before the first store (a plain loop of this kind
+// store(i, load(i)) for i = tid, tid + NTHR, ... < N by the NTHR threads of a block, with the loads
+// of up to MAXB items in flight per thread before the first store (a plain loop of this kind
 // is compiled to one load, one wait, one store per iteration: a chain of memory latencies).
-template <int N, typename V, typename LoadFn, typename StoreFn>
+template <int N, typename V, int NTHR = 256, int MAXB = 16, typename LoadFn, typename StoreFn>
 __device__ __forceinline__ void block_stage(int tid, LoadFn&& load, StoreFn&& store)
 {
-    constexpr int IT = (N + 255) / 256;
-    constexpr int B = IT < 16 ? IT : 16;
+    constexpr int IT = (N + NTHR - 1) / NTHR;
+    constexpr int B = IT < MAXB ? IT : MAXB;
 #pragma unroll 1
     for (int b0 = 0; b0 < IT; b0 += B) {
         V r[B];
 #pragma unroll
         for (int k = 0; k < B; ++k) {
-            const int i = tid + 256 * (b0 + k);
+            const int i = tid + NTHR * (b0 + k);
             r[k] = i < N ? load(i) : V{};
         }
 #pragma unroll
         for (int k = 0; k < B; ++k) {
-            const int i = tid + 256 * (b0 + k);
+            const int i = tid + NTHR * (b0 + k);
             if (i < N) store(i, r[k]);
         }
     }
