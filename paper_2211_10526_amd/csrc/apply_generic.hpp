@@ -289,14 +289,18 @@ __device__ __forceinline__ void apply_generic_tile(const T* __restrict__ q, cons
                     wt[(idx % (KS * KS)) * D + idx / (KS * KS)] = IO<T>::to_f32(w_pre[i]);
             }
         } else {
-            for (int idx = tid; idx < HH * HW * LPR; idx += 256)
-                *reinterpret_cast<uint4*>(vh + static_cast<size_t>(idx / LPR) * D + (idx % LPR) * VEC) =
-                    halo_piece(idx);
+            // (the loads of a thread go out in batches: see block_stage)
+            block_stage<HH * HW * LPR, uint4, 256, 8>(
+                tid, [&](int idx) { return halo_piece(idx); },
+                [&](int idx, uint4 val) {
+                    *reinterpret_cast<uint4*>(vh + static_cast<size_t>(idx / LPR) * D + (idx % LPR) * VEC) = val;
+                });
             const T* wh = w + static_cast<size_t>(head) * p.d_valid * KS * KS;
-            for (int idx = tid; idx < D * KS * KS; idx += 256) {
-                const int c = idx / (KS * KS), tap = idx % (KS * KS);
-                wt[tap * D + c] = c < p.d_valid ? IO<T>::to_f32(wh[idx]) : 0.f;
-            }
+            block_stage<D * KS * KS, T, 256, 8>(
+                tid, [&](int idx) { return idx / (KS * KS) < p.d_valid ? wh[idx] : T{}; },
+                [&](int idx, T val) {
+                    wt[(idx % (KS * KS)) * D + idx / (KS * KS)] = IO<T>::to_f32(val);
+                });
         }
         __syncthreads();
 
