@@ -1,5 +1,5 @@
-// Backward pass of the layer on the vector ALU (any I/O type, fp32 arithmetic): the gradients of
-// Eq. 3 / 8 / 9 with respect to q, k, v, the DWConv filters and their bias, given g = dLoss/dout.
+// Backward pass of the layer: the gradients of Eq. 3 / 8 / 9 with respect to q, k, v, the DWConv
+// filters and their bias, given g = dLoss/dout.
 //
 // With num_t = vsum / 2 + q_hat_t S / pi and den_t = N / 2 + q_hat_t . ksum / pi (Eq. 3 after the
 // reassociation of Sec. 3.1), a_t = dLoss/dnum_t = g_t / den_t and
@@ -11,7 +11,8 @@
 //   dx = (dx_hat - x_hat (x_hat . dx_hat)) / |x|   (dx_hat / eps where |x| < eps)
 // S', va' are what pass 1 computes from (q, a) in place of (k, v), and dv is what pass 2 computes
 // from (k, g) with that state: both reuse the forward kernels.  This file holds the rest: the
-// per-row kernel (a, b, dq; dk), the filter gradient and small helpers.
+// per-row kernel (a, b, dq; dk) in a vector-ALU form (any I/O type and head width, fp32 products)
+// and a matrix-core form (16-bit, 32 or 64 channels), the filter gradient and small helpers.
 #pragma once
 
 #include "apply_generic.hpp"
