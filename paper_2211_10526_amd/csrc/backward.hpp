@@ -358,6 +358,24 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
     uint16_t* my_al = al + wave * 16 * P;
     uint16_t* my_g = gr + wave * 16 * P;
 
+    // the rows of a tile are loaded one tile ahead: their latency passes behind the previous
+    // tile's work
+    u32x4_t xnext[PASSES], ynext[PASSES];
+    auto fetch_rows = [&](int tile) {
+#pragma unroll
+        for (int ps = 0; ps < PASSES; ++ps) {
+            const int n = tile * kBwdTokens + wave * 16 + ps * RP + lrow;
+            xnext[ps] = u32x4_t{0u, 0u, 0u, 0u};
+            ynext[ps] = u32x4_t{0u, 0u, 0u, 0u};
+            if (tile < p.tiles && n < p.N) {
+                xnext[ps] = *reinterpret_cast<const u32x4_t*>(x + in_off + n * p.in.n + piece * 8);
+                ynext[ps] = QUERY ? *reinterpret_cast<const u32x4_t*>(y + out_off + n * p.out.n + piece * 8)
+                                  : *reinterpret_cast<const u32x4_t*>(y + in_off + n * p.in.n + piece * 8);
+            }
+        }
+    };
+    fetch_rows(blockIdx.x * tiles_per_block);
+
     for (int it = 0; it < tiles_per_block; ++it) {
         const int tile = blockIdx.x * tiles_per_block + it;
         if (tile >= p.tiles) break;
@@ -367,13 +385,8 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
         u32x4_t xkeep[PASSES];
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
-            const int row = ps * RP + lrow, n = n0 + row;
-            u32x4_t xv = {0u, 0u, 0u, 0u}, yv = {0u, 0u, 0u, 0u};
-            if (n < p.N) {
-                xv = *reinterpret_cast<const u32x4_t*>(x + in_off + n * p.in.n + piece * 8);
-                yv = QUERY ? *reinterpret_cast<const u32x4_t*>(y + out_off + n * p.out.n + piece * 8)
-                           : *reinterpret_cast<const u32x4_t*>(y + in_off + n * p.in.n + piece * 8);
-            }
+            const int row = ps * RP + lrow;
+            const u32x4_t xv = xnext[ps], yv = ynext[ps];
             xkeep[ps] = xv;
             *reinterpret_cast<u32x4_t*>(my_x + row * P + piece * 8) = xv;
             *reinterpret_cast<u32x4_t*>((QUERY ? my_g : my_a) + row * P + piece * 8) = yv;
@@ -395,6 +408,7 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
                 w_b[row] = 1.f;
             }
         }
+        if (it + 1 < tiles_per_block) fetch_rows(tile + 1);
         wave_lds_fence();
         float inv_r[4], b_r[4], small_r[4];
 #pragma unroll
