@@ -807,26 +807,38 @@ __global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_kernel(const T* 
     for (int idx = tid; idx < NT * D; idx += NTHR) o[idx] = sums[idx];
 }
 
-// grid = (ceil(heads * d * (taps + 1) / 256)), block = 256: sums the partial filter gradients
-// over the batch and the chunks, in order, into dw [heads][d][taps] and dbias [heads][d] (may
-// be null).  part: [B * heads][chunks][taps + 1][D].
+// grid = (ceil(heads * d * (taps + 1) / 16)), block = 256: sums the partial filter gradients over
+// the batch and the chunks into dw [heads][d][taps] and dbias [heads][d] (may be null).  part:
+// [B * heads][chunks][taps + 1][D].  Thread (slice, out) = (tid / 16, tid % 16): the 16 slices
+// take runs of the batch, each in order; slice 0 adds the slice sums in order (fixed order of
+// additions).
 __global__ __launch_bounds__(256) void bwd_filter_combine_kernel(const float* __restrict__ part,
                                                                  float* __restrict__ dw,
                                                                  float* __restrict__ dbias, int B,
                                                                  int heads, int d, int D, int taps,
                                                                  int chunks)
 {
-    const int i = blockIdx.x * 256 + threadIdx.x;
+    __shared__ float red[256];
+    const int tid = threadIdx.x;
+    const int i = blockIdx.x * 16 + tid % 16, sl = tid / 16;
     const int nt = taps + 1;
-    if (i >= heads * d * nt) return;
+    const bool live = i < heads * d * nt;
     const int ch = i % d, e = (i / d) % nt, h = i / (nt * d);  // neighbours read neighbours
+    const int per = (B + 15) / 16;
     float s = 0.f;
-    for (int b = 0; b < B; ++b) {
-        const float* src = part + (static_cast<size_t>(b) * heads + h) * chunks * nt * D + e * D + ch;
-        s += sum_partials(src, chunks, static_cast<size_t>(nt) * D);
+    if (live) {
+        for (int b = sl * per; b < B && b < (sl + 1) * per; ++b) {
+            const float* src = part + (static_cast<size_t>(b) * heads + h) * chunks * nt * D + e * D + ch;
+            s += sum_partials(src, chunks, static_cast<size_t>(nt) * D);
+        }
     }
-    if (e < taps) dw[(static_cast<size_t>(h) * d + ch) * taps + e] = s;
-    else if (dbias) dbias[h * d + ch] = s;
+    red[tid] = s;
+    __syncthreads();
+    if (sl == 0 && live) {
+        for (int k = 1; k < 16; ++k) s += red[k * 16 + tid];
+        if (e < taps) dw[(static_cast<size_t>(h) * d + ch) * taps + e] = s;
+        else if (dbias) dbias[h * d + ch] = s;
+    }
 }
 
 }  // namespace castling

@@ -490,7 +490,7 @@ hipError_t bwd_rows_mfma(castling_attn* h, bool launch, bool query, const void* 
     }
     // the block loads the state once: several tiles per block where there are many
     const long long all = static_cast<long long>(h->row_tiles) * h->units;
-    const int tpb = static_cast<int>(std::max(1ll, std::min(8ll, all / 2048)));
+    const int tpb = static_cast<int>(std::max(1ll, std::min(8ll, all / 1024)));
     const dim3 grid((h->row_tiles + tpb - 1) / tpb, h->units);
     auto u16 = [](const void* ptr) { return static_cast<const uint16_t*>(ptr); };
     if (query)
@@ -1247,7 +1247,7 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         });
         HIP_TRY(e);
         const int n = d.heads * d.d * (taps + 1);
-        hipLaunchKernelGGL(bwd_filter_combine_kernel, dim3((n + 255) / 256), dim3(256), 0, s, h->fpart,
+        hipLaunchKernelGGL(bwd_filter_combine_kernel, dim3((n + 15) / 16), dim3(256), 0, s, h->fpart,
                            grad_w, grad_bias, d.B, d.heads, d.d, h->dpad, taps, h->filter_chunks);
         HIP_TRY(hipGetLastError());
     } else {
