@@ -810,8 +810,8 @@ __global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_kernel(const T* 
 // grid = (ceil(heads * d * (taps + 1) / 16)), block = 256: sums the partial filter gradients over
 // the batch and the chunks into dw [heads][d][taps] and dbias [heads][d] (may be null).  part:
 // [B * heads][chunks][taps + 1][D].  Thread (slice, out) = (tid / 16, tid % 16): the 16 slices
-// take runs of the batch, each in order; slice 0 adds the slice sums in order (fixed order of
-// additions).
+// take runs of the (batch, chunk) pairs, each in order; slice 0 adds the slice sums in order (a
+// fixed order of additions).
 __global__ __launch_bounds__(256) void bwd_filter_combine_kernel(const float* __restrict__ part,
                                                                  float* __restrict__ dw,
                                                                  float* __restrict__ dbias, int B,
@@ -824,12 +824,15 @@ __global__ __launch_bounds__(256) void bwd_filter_combine_kernel(const float* __
     const int nt = taps + 1;
     const bool live = i < heads * d * nt;
     const int ch = i % d, e = (i / d) % nt, h = i / (nt * d);  // neighbours read neighbours
-    const int per = (B + 15) / 16;
+    const int items = B * chunks;  // (batch, chunk) pairs, batch-major
+    const int per = (items + 15) / 16;
     float s = 0.f;
     if (live) {
-        for (int b = sl * per; b < B && b < (sl + 1) * per; ++b) {
-            const float* src = part + (static_cast<size_t>(b) * heads + h) * chunks * nt * D + e * D + ch;
-            s += sum_partials(src, chunks, static_cast<size_t>(nt) * D);
+        const int m1 = items < (sl + 1) * per ? items : (sl + 1) * per;
+#pragma unroll 4
+        for (int m = sl * per; m < m1; ++m) {
+            const int b = m / chunks, k = m % chunks;
+            s += part[((static_cast<size_t>(b) * heads + h) * chunks + k) * nt * D + e * D + ch];
         }
     }
     red[tid] = s;
