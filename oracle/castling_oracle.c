@@ -612,6 +612,91 @@ void oracle_backward(const double* q, const double* k, const double* v, const do
         for (size_t i = 0; i < total; ++i) dq[i] += g[i];
 }
 
+/* Backward of the downsampling layer (pooled queries on every s-th row and column, residual
+ * query): the derivatives of oracle_forward_pooled_explicit by the chain rule, explicit Nq x N
+ * similarity.  q, g, dq: [B][heads][Nq][d]; k, v, dk, dv: [B][heads][H*W][d]. */
+void oracle_backward_pooled_explicit(const double* q, const double* k, const double* v,
+                                     const double* w, const double* g, int B, int heads, int H, int W,
+                                     int d, int ks, int s, int residual, int norm_mode,
+                                     unsigned branches, double eps, double* dq, double* dk, double* dv,
+                                     double* dw, double* dbias)
+{
+    const int N = H * W, r = ks / 2;
+    const int Hq = (H + s - 1) / s, Wq = (W + s - 1) / s, Nq = Hq * Wq;
+    const size_t kv_total = (size_t)B * heads * N * d, q_total = (size_t)B * heads * Nq * d;
+    memset(dq, 0, sizeof(double) * q_total);
+    memset(dk, 0, sizeof(double) * kv_total);
+    memset(dv, 0, sizeof(double) * kv_total);
+    memset(dw, 0, sizeof(double) * (size_t)heads * d * ks * ks);
+    if (dbias) memset(dbias, 0, sizeof(double) * (size_t)heads * d);
+    double* qh = (double*)malloc(sizeof(double) * (size_t)Nq * d);
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* dkh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* A = (double*)malloc(sizeof(double) * N);
+    double* lin = (double*)malloc(sizeof(double) * d);
+    double* dqh = (double*)malloc(sizeof(double) * d);
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < heads; ++h) {
+            const size_t kv = ((size_t)b * heads + h) * (size_t)N * d;
+            const size_t qo = ((size_t)b * heads + h) * (size_t)Nq * d;
+            if (branches & ORACLE_BRANCH_LINEAR) {
+                oracle_l2_normalize(q + qo, Nq, d, eps, qh);
+                oracle_l2_normalize(k + kv, N, d, eps, kh);
+                memset(dkh, 0, sizeof(double) * (size_t)N * d);
+                for (int t = 0; t < Nq; ++t) {
+                    const double* gt = g + qo + (size_t)t * d;
+                    double rs = 0.0;
+                    for (int c = 0; c < d; ++c) lin[c] = 0.0;
+                    for (int j = 0; j < N; ++j) {
+                        double x = 0.0;
+                        for (int c = 0; c < d; ++c) x += qh[(size_t)t * d + c] * kh[(size_t)j * d + c];
+                        A[j] = 0.5 + x / ORACLE_PI;
+                        rs += A[j];
+                        for (int c = 0; c < d; ++c) lin[c] += A[j] * v[kv + (size_t)j * d + c];
+                    }
+                    const double scale = (norm_mode == 0) ? 1.0 / rs : 1.0;
+                    double g_lin = 0.0;
+                    for (int c = 0; c < d; ++c) g_lin += gt[c] * lin[c] * scale;
+                    for (int c = 0; c < d; ++c) dqh[c] = 0.0;
+                    for (int j = 0; j < N; ++j) {
+                        double g_v = 0.0;
+                        for (int c = 0; c < d; ++c) g_v += gt[c] * v[kv + (size_t)j * d + c];
+                        const double dA = (norm_mode == 0) ? (g_v - g_lin) / rs : g_v;
+                        for (int c = 0; c < d; ++c) {
+                            dv[kv + (size_t)j * d + c] += A[j] * scale * gt[c];
+                            dqh[c] += dA * kh[(size_t)j * d + c] / ORACLE_PI;
+                            dkh[(size_t)j * d + c] += dA * qh[(size_t)t * d + c] / ORACLE_PI;
+                        }
+                    }
+                    normalize_backward(q + qo + (size_t)t * d, dqh, d, eps, dq + qo + (size_t)t * d);
+                }
+                for (int j = 0; j < N; ++j)
+                    normalize_backward(k + kv + (size_t)j * d, dkh + (size_t)j * d, d, eps,
+                                       dk + kv + (size_t)j * d);
+            }
+            if (branches & ORACLE_BRANCH_DWCONV)
+                for (int t = 0; t < Nq; ++t) {
+                    const double* gt = g + qo + (size_t)t * d;
+                    const int y = s * (t / Wq), x = s * (t % Wq);
+                    for (int c = 0; c < d; ++c) {
+                        if (dbias) dbias[h * d + c] += gt[c];
+                        for (int dy = 0; dy < ks; ++dy)
+                            for (int dx = 0; dx < ks; ++dx) {
+                                const int yy = y + dy - r, xx = x + dx - r;
+                                if (yy < 0 || yy >= H || xx < 0 || xx >= W) continue;
+                                const size_t src = kv + ((size_t)yy * W + xx) * d + c;
+                                const size_t wi = (((size_t)h * d + c) * ks + dy) * ks + dx;
+                                dv[src] += w[wi] * gt[c];
+                                dw[wi] += gt[c] * v[src];
+                            }
+                    }
+                }
+        }
+    if (residual)
+        for (size_t i = 0; i < q_total; ++i) dq[i] += g[i];
+    free(qh); free(kh); free(dkh); free(A); free(lin); free(dqh);
+}
+
 /* ------------------------------------------------------------------------
  * Training-time companions of the layer (Sec. 3.2.2, Eq. 10) and the exact
  * angular kernel it approximates (Eq. 4-5), as O(N^2) attention.

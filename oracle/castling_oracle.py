@@ -50,6 +50,8 @@ def lib():
         bwd = [_dp] * 5 + [C.c_int] * 7 + [C.c_uint, C.c_double, C.c_int, C.c_int] + [_dp] * 5
         L.oracle_backward_explicit.argtypes = bwd
         L.oracle_backward.argtypes = bwd
+        L.oracle_backward_pooled_explicit.argtypes = \
+            [_dp] * 5 + [C.c_int] * 9 + [C.c_uint, C.c_double] + [_dp] * 5
         L.oracle_state.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _dp]
         L.oracle_softmax_probs.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_double,
                                            C.c_double, _dp]
@@ -223,6 +225,26 @@ def backward(q, k, v, w, g, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_AL
     """The same through the reassociated state; any N."""
     return _backward(lib().oracle_backward, q, k, v, w, g, grid_h, grid_w, norm, branches, eps,
                      extra, residual, with_bias)
+
+
+def backward_pooled_explicit(q, k, v, w, g, grid_h, grid_w, pool=2, residual=True, norm=NORM_ROWSUM,
+                             branches=BRANCH_ALL, eps=DEFAULT_EPS, with_bias=True):
+    """Gradients (dq, dk, dv, dw, dbias) of the downsampling layer (forward_pooled_explicit) given
+    g = dLoss/dout [B, heads, Nq, d], by differentiating its definition; small N only."""
+    q, k, v, w, g = _f64(q), _f64(k), _f64(v), _f64(w), _f64(g)
+    B, heads, N, d = k.shape
+    nq = -(-grid_h // pool) * -(-grid_w // pool)
+    assert v.shape == k.shape and N == grid_h * grid_w and q.shape == (B, heads, nq, d)
+    assert g.shape == q.shape and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    dq = np.empty(q.shape, dtype=np.float64)
+    dk, dv = np.empty(k.shape, dtype=np.float64), np.empty(k.shape, dtype=np.float64)
+    dw = np.empty(w.shape, dtype=np.float64)
+    dbias = np.empty((heads, d), dtype=np.float64) if with_bias else None
+    lib().oracle_backward_pooled_explicit(
+        _p(q), _p(k), _p(v), _p(w), _p(g), B, heads, grid_h, grid_w, d, w.shape[2], int(pool),
+        int(bool(residual)), int(norm), int(branches), float(eps), _p(dq), _p(dk), _p(dv), _p(dw),
+        _p(dbias))
+    return dq, dk, dv, dw, dbias
 
 
 def state(k, v, eps=DEFAULT_EPS):

@@ -131,3 +131,56 @@ def test_reassociated_backward_at_a_larger_size(oracle):
         for x, y in zip(a, f):
             np.testing.assert_allclose(y, x, rtol=1e-9, atol=1e-10)
     assert oracle.backward(q, k, v, w, g, H, W, extra=extra, with_bias=False)[4] is None
+
+
+POOLED = [(2, 2, 6, 8, 4, 3, 2), (1, 3, 7, 5, 3, 5, 2), (1, 1, 9, 9, 2, 3, 3), (1, 2, 1, 6, 4, 3, 2)]
+
+
+@pytest.mark.parametrize("case", POOLED)
+@pytest.mark.parametrize("norm", [0, 1])
+@pytest.mark.parametrize("branches", [3, 1, 2])
+def test_pooled_gradients_equal_autograd_of_the_definition(oracle, case, norm, branches):
+    """Downsampling layer: pooled queries against all keys, DWConv of stride `pool`, residual
+    query -- in plain torch ops (matmul, conv2d with a stride), differentiated by autograd."""
+    B, heads, H, W, d, ks, pool = case
+    r = np.random.default_rng(85)
+    hq, wq = -(-H // pool), -(-W // pool)
+    q, g = r.normal(size=(B, heads, hq * wq, d)), r.normal(size=(B, heads, hq * wq, d))
+    k, v = r.normal(size=(B, heads, H * W, d)), r.normal(size=(B, heads, H * W, d))
+    w, bias = r.normal(size=(heads, d, ks, ks)) * 0.3, r.normal(size=(heads, d))
+    eps = 0.9 * math.sqrt(d)
+    residual = bool(branches & 1)
+    tq, tk, tv, tw, tb = (torch.tensor(a, requires_grad=True) for a in (q, k, v, w, bias))
+    out = torch.zeros_like(tq)
+    if branches & 1:
+        qh = tq / torch.clamp(tq.norm(dim=-1, keepdim=True), min=eps)
+        kh = tk / torch.clamp(tk.norm(dim=-1, keepdim=True), min=eps)
+        A = 0.5 + qh @ kh.transpose(-1, -2) / PI
+        lin = A @ tv
+        out = out + (lin / A.sum(-1, keepdim=True) if norm == 0 else lin)
+    if branches & 2:
+        x = tv.reshape(B, heads, H, W, d).permute(0, 1, 4, 2, 3).reshape(B, heads * d, H, W)
+        y = torch.nn.functional.conv2d(x, tw.reshape(heads * d, 1, ks, ks), tb.reshape(-1), stride=pool,
+                                       padding=ks // 2, groups=heads * d)
+        out = out + y.reshape(B, heads, d, hq, wq).permute(0, 1, 3, 4, 2).reshape(B, heads, hq * wq, d)
+    if residual:
+        out = out + tq
+    np.testing.assert_allclose(
+        out.detach().numpy(),
+        oracle.forward_pooled_explicit(q, k, v, w, bias, H, W, pool=pool, residual=residual, norm=norm,
+                                       branches=branches, eps=eps), atol=1e-12)
+    (out * torch.tensor(g)).sum().backward()
+    want = [t.grad.numpy() if t.grad is not None else np.zeros(t.shape) for t in (tq, tk, tv, tw, tb)]
+    got = oracle.backward_pooled_explicit(q, k, v, w, g, H, W, pool=pool, residual=residual, norm=norm,
+                                          branches=branches, eps=eps)
+    for name, a, b in zip(("dq", "dk", "dv", "dw", "dbias"), got, want):
+        np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-10, err_msg=name)
+
+
+def test_pooled_backward_with_stride_one_is_the_ordinary_backward(oracle):
+    B, heads, H, W, d, ks, extra = CASES[0]
+    q, k, v, w, bias, g = draw(86, *CASES[0])
+    a = oracle.backward_explicit(q, k, v, w, g, H, W, residual=True)
+    b = oracle.backward_pooled_explicit(q, k, v, w, g, H, W, pool=1, residual=True)
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(y, x, atol=1e-12)
