@@ -81,7 +81,7 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
  * (Sec. 3.1, attention designs; Table 1, last row).  Needs the linear branch
  * (CASTLING_ERR_INVALID_ARG otherwise); runs on the vector-ALU kernels.
  * TRAINING: create also allocates what castling_attn_backward needs (one more tensor of the
- * span of q and a few small buffers); not with q_pool = 2 (CASTLING_ERR_UNSUPPORTED). */
+ * span of q, three of the span of k with q_pool = 2, and a few small buffers). */
 enum { CASTLING_FLAG_KEEP_STATE = 1, CASTLING_FLAG_RESIDUAL_Q = 2, CASTLING_FLAG_TRAINING = 4 };
 
 typedef struct {
@@ -154,7 +154,7 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
  * the paper prints no gradient formulas).  The handle must have been created with
  * CASTLING_FLAG_TRAINING (CASTLING_ERR_INVALID_ARG otherwise).
  * grad_out has the type and strides of out; grad_q, grad_k, grad_v the type and strides of q, k,
- * v; grad_w [heads][d][ks][ks] and grad_bias [heads][d] (may be NULL) are fp32, contiguous, sums
+ * v (with q_pool = 2, grad_out and grad_q hold one row per pooled query); grad_w [heads][d][ks][ks] and grad_bias [heads][d] (may be NULL) are fp32, contiguous, sums
  * over the batch.  All are overwritten, none accumulated into.  A branch that is off in the
  * descriptor contributes nothing: without the linear branch grad_q and grad_k are zeros,
  * without the DWConv branch grad_w and grad_bias (where given) are zeros and dw_weight may be

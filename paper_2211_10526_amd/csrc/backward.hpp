@@ -22,8 +22,9 @@
 namespace castling {
 
 struct BwdRowsParams {
-    int N;           // tokens per unit
-    int tiles;       // ceil(N / 64)
+    int N;           // tokens per unit of k and v (the sums of Eq. 3 run over them)
+    int rows;        // rows this launch walks: N, or the number of pooled queries
+    int tiles;       // ceil(rows / 64)
     int norm_none;
     int residual_q;  // QUERY: dq gains g
     int d_valid;     // features per head in memory (<= D)
@@ -33,8 +34,22 @@ struct BwdRowsParams {
     // ascale times S', va'.  mscale: factor on the state matrix as it is loaded (1/pi for the
     // forward state, 1/(pi ascale) for the state of (q, a)).
     float ascale, mscale;
-    TensorStrides in, out;  // of q, k, v, a and the gradients of q, k; of g
+    TensorStrides in, out;  // of k, v, a and the gradient of k; of g
+    TensorStrides xs;       // of x and dx: those of q (QUERY) or `in`
+    // Downsampling layers (QUERY, up_s = 2): query row t = (yq, xq) of the up_wq-wide coarse grid
+    // stands at token (up_s yq) up_w + up_s xq of the fine grid; a is written to that row of
+    // its buffer and q, g are copied to the same row of q_up, g_up (all three with the layout
+    // `in`, zero elsewhere), so that the later passes run on the fine grid as they are.
+    int up_s, up_wq, up_w;
+    void* q_up;
+    void* g_up;
 };
+
+// row of the a buffer for query row n (see BwdRowsParams::up_s)
+__device__ __forceinline__ int bwd_a_row(const BwdRowsParams& p, int n)
+{
+    return p.up_s ? (n / p.up_wq) * p.up_s * p.up_w + (n % p.up_wq) * p.up_s : n;
+}
 
 // R consecutive elements at p (R * sizeof(T) a power of two; p aligned to min(that, 16) bytes)
 // as one access, widened to fp32 / narrowed from it.
@@ -126,6 +141,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
     const int tt = tid / 16, tj = tid % 16;
     const long long in_off = unit_offset(unit, heads, p.in);
     const long long out_off = unit_offset(unit, heads, p.out);
+    const long long x_off = unit_offset(unit, heads, p.xs);
 
     const float* gs = state + static_cast<size_t>(unit) * L::SIZE;
     block_stage<D * D, float>(
@@ -148,9 +164,13 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
         float xv[VEC], yv[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) xv[e] = yv[e] = 0.f;
-        if (n < p.N && lcol < p.d_valid) {
-            IO<T>::load16(x + in_off + n * p.in.n + lcol, xv);
+        if (n < p.rows && lcol < p.d_valid) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(x + x_off + n * p.xs.n + lcol);
+            IO<T>::widen16(raw, xv);
             if (!QUERY) IO<T>::load16(y + in_off + n * p.in.n + lcol, yv);
+            if (QUERY && p.up_s)  // the query row on its place in the fine grid
+                *reinterpret_cast<uint4*>(static_cast<T*>(p.q_up) + in_off +
+                                          bwd_a_row(p, n) * p.in.n + lcol) = raw;
         }
         float ss = 0.f;
 #pragma unroll
@@ -197,7 +217,7 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int n = n0 + tt * 4 + t;
-            const bool live = n < p.N && tj * RJ < p.d_valid;
+            const bool live = n < p.rows && tj * RJ < p.d_valid;
             if (live) load_piece<T, RJ>(y + out_off + n * p.out.n + tj * RJ, gown[t]);  // y = g
             float gl = 0.f;
             const float rden = 1.0f / (0.5f * static_cast<float>(p.N) + den[t]);
@@ -213,8 +233,12 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
                 at[(tj * RJ + j) * kBwdTStride + tt * 4 + t] = a0;
                 av[j] = a0 * p.ascale;
             }
-            if (live) store_piece<T, RJ>(a_out + in_off + n * p.in.n + tj * RJ, av);
-            if (tj == 0) bs[tt * 4 + t] = n < p.N ? bt : 0.f;
+            if (live) {
+                const long long at = in_off + bwd_a_row(p, n) * p.in.n + tj * RJ;
+                store_piece<T, RJ>(a_out + at, av);
+                if (p.up_s) store_piece<T, RJ>(static_cast<T*>(p.g_up) + at, gown[t]);
+            }
+            if (tj == 0) bs[tt * 4 + t] = n < p.rows ? bt : 0.f;
         }
         __syncthreads();
         // this tile's share of kb' = sum_t q_hat_t b_t
@@ -256,14 +280,14 @@ __global__ __launch_bounds__(256) void bwd_rows_kernel(const T* __restrict__ x,
         }
         dot = group_sum<16>(dot);
         if (small[tl] != 0.f) dot = 0.f;  // below the floor the row is x / eps: no projection
-        if (n < p.N && tj * RJ < p.d_valid) {
+        if (n < p.rows && tj * RJ < p.d_valid) {
             float r[RJ];
 #pragma unroll
             for (int j = 0; j < RJ; ++j) {
                 r[j] = (dxh[t][j] - xh[j] * dot) * inv[tl];
                 if (QUERY && p.residual_q) r[j] += gown[t][j];
             }
-            store_piece<T, RJ>(dx + in_off + n * p.in.n + tj * RJ, r);
+            store_piece<T, RJ>(dx + x_off + n * p.xs.n + tj * RJ, r);
         }
     }
 }
@@ -327,6 +351,7 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
     const int unit = blockIdx.y;
     const long long in_off = unit_offset(unit, heads, p.in);
     const long long out_off = unit_offset(unit, heads, p.out);
+    const long long x_off = unit_offset(unit, heads, p.xs);
     const float ts = X::table_scale(p.N), us = X::table_unscale(p.N);
     const float post = us / p.ascale;
 
@@ -367,8 +392,8 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
             const int n = tile * kBwdTokens + wave * 16 + ps * RP + lrow;
             xnext[ps] = u32x4_t{0u, 0u, 0u, 0u};
             ynext[ps] = u32x4_t{0u, 0u, 0u, 0u};
-            if (tile < p.tiles && n < p.N) {
-                xnext[ps] = *reinterpret_cast<const u32x4_t*>(x + in_off + n * p.in.n + piece * 8);
+            if (tile < p.tiles && n < p.rows) {
+                xnext[ps] = *reinterpret_cast<const u32x4_t*>(x + x_off + n * p.xs.n + piece * 8);
                 ynext[ps] = QUERY ? *reinterpret_cast<const u32x4_t*>(y + out_off + n * p.out.n + piece * 8)
                                   : *reinterpret_cast<const u32x4_t*>(y + in_off + n * p.in.n + piece * 8);
             }
@@ -388,6 +413,11 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
             const int row = ps * RP + lrow;
             const u32x4_t xv = xnext[ps], yv = ynext[ps];
             xkeep[ps] = xv;
+            if (QUERY && p.up_s && n0 + row < p.rows) {  // q and g on their place in the fine grid
+                const long long at = in_off + bwd_a_row(p, n0 + row) * p.in.n + piece * 8;
+                *reinterpret_cast<u32x4_t*>(static_cast<uint16_t*>(p.q_up) + at) = xv;
+                *reinterpret_cast<u32x4_t*>(static_cast<uint16_t*>(p.g_up) + at) = yv;
+            }
             *reinterpret_cast<u32x4_t*>(my_x + row * P + piece * 8) = xv;
             *reinterpret_cast<u32x4_t*>((QUERY ? my_g : my_a) + row * P + piece * 8) = yv;
             float ss = 0.f, qk = 0.f;
@@ -468,8 +498,8 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
 #pragma unroll
             for (int ps = 0; ps < PASSES; ++ps) {
                 const int row = ps * RP + lrow, n = n0 + row;
-                if (n < p.N)
-                    *reinterpret_cast<u32x4_t*>(a_out + in_off + n * p.in.n + piece * 8) =
+                if (n < p.rows)
+                    *reinterpret_cast<u32x4_t*>(a_out + in_off + bwd_a_row(p, n) * p.in.n + piece * 8) =
                         *reinterpret_cast<const u32x4_t*>(my_a + row * P + piece * 8);
                 const float wgt = w_inv[row] * w_b[row];
 #pragma unroll
@@ -535,8 +565,8 @@ __global__ __launch_bounds__(256) void bwd_rows_mfma_kernel(const uint16_t* __re
 #pragma unroll
         for (int ps = 0; ps < PASSES; ++ps) {
             const int row = ps * RP + lrow, n = n0 + row;
-            if (n < p.N)
-                *reinterpret_cast<u32x4_t*>(dx + in_off + n * p.in.n + piece * 8) =
+            if (n < p.rows)
+                *reinterpret_cast<u32x4_t*>(dx + x_off + n * p.xs.n + piece * 8) =
                     *reinterpret_cast<const u32x4_t*>(my_g + row * P + piece * 8);
         }
         wave_lds_fence();
@@ -574,6 +604,23 @@ __global__ __launch_bounds__(256) void flip_filters_kernel(const T* __restrict__
     if (i >= n) return;
     const int ch = i / taps, e = i % taps;
     out[i] = w[ch * taps + (taps - 1 - e)];
+}
+
+// grid = (ceil(rows * d / VEC / 256), units), block = 256: row t = (yq, xq) of a wq-wide coarse grid
+// of `src` to token (2 yq) w + 2 xq of `dst` (16-byte pieces).
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const T* __restrict__ src, T* __restrict__ dst,
+                                                           int rows, int d, int heads, TensorStrides ss,
+                                                           TensorStrides ds, int wq, int w)
+{
+    constexpr int VEC = IO<T>::VEC;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    const int per_row = d / VEC;
+    if (i >= rows * per_row) return;
+    const int t = i / per_row, piece = i % per_row;
+    const long long to = (t / wq) * 2ll * w + (t % wq) * 2;
+    *reinterpret_cast<uint4*>(dst + unit_offset(blockIdx.y, heads, ds) + to * ds.n + piece * VEC) =
+        *reinterpret_cast<const uint4*>(src + unit_offset(blockIdx.y, heads, ss) + t * ss.n + piece * VEC);
 }
 
 // grid = (ceil(n / 256)), block = 256

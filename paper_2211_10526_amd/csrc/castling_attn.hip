@@ -128,7 +128,9 @@ struct castling_attn {
     float* kb;          // [units][dpad]
     void* wflip;        // filters turned by 180 degrees
     float* fpart;       // [units][filter chunks][ks*ks + 1][dpad]
-    int row_tiles, filter_chunks;
+    int row_tiles, qrow_tiles, filter_chunks;  // 64-row tiles of the tokens / of the queries
+    void* q_up;         // q_pool = 2: q and g on their places in the fine grid (layout of k, v;
+    void* g_up;         //   zero elsewhere, like a_buf), see BwdRowsParams
     bool mfma_rows;     // dq / dk on the matrix cores (16-bit, d = 32 or 64)
     int kb_parts;       // shares of kb' per unit
 };
@@ -381,7 +383,7 @@ template <typename T, int D>
 hipError_t apply_generic_ks(castling_attn* h, bool launch, const void* q, const void* v,
                             const void* w, const void* bias, void* out, hipStream_t s)
 {
-    if (h->pool == 2) {
+    if (h->pool == 2 && !h->ov.on) {
         switch (h->view.ks) {
             case 1: return apply_generic<T, D, 1, 2>(h, launch, q, v, w, bias, out, s);
             case 3: return apply_generic<T, D, 3, 2>(h, launch, q, v, w, bias, out, s);
@@ -426,7 +428,9 @@ hipError_t do_apply(castling_attn* h, bool launch, const void* q, const void* v,
     const castling_attn_desc_t& d = h->desc;
     const int extra = d.extra_tokens;
     const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const ApplyView grid_view = {h->qgrid_h, h->qgrid_w, d.dw_kernel, d.branches};
+    // (the backward's pass 2 always runs on the grid of k and v)
+    const ApplyView grid_view = {h->ov.on ? d.grid_h : h->qgrid_h, h->ov.on ? d.grid_w : h->qgrid_w,
+                                 d.dw_kernel, d.branches};
     const ApplyView extra_view = {1, extra, 1, CASTLING_BRANCH_LINEAR};
     h->view = grid_view;
     if (!launch) {
@@ -474,6 +478,33 @@ float bwd_a_scale(const castling_attn* h)
 }
 
 // launch = false: set the kernels' LDS attributes, record the largest in *lds (create time)
+// parameters of a per-row launch: the query side (rows of q, possibly pooled) or the key side
+BwdRowsParams bwd_rows_params(const castling_attn* h, bool query)
+{
+    const castling_attn_desc_t& d = h->desc;
+    BwdRowsParams p = {};
+    p.N = d.N;
+    p.rows = query ? h->nq : d.N;
+    p.tiles = query ? h->qrow_tiles : h->row_tiles;
+    p.norm_none = d.norm == CASTLING_NORM_NONE;
+    p.residual_q = h->residual_q;
+    p.d_valid = d.d;
+    p.eps = d.eps;
+    p.ascale = bwd_a_scale(h);
+    p.mscale = query ? kInvPi : kInvPi / p.ascale;
+    p.in = h->in_st;
+    p.out = h->out_st;
+    p.xs = query ? h->q_st : h->in_st;
+    if (query && h->pool == 2) {
+        p.up_s = 2;
+        p.up_wq = h->qgrid_w;
+        p.up_w = d.grid_w;
+        p.q_up = h->q_up;
+        p.g_up = h->g_up;
+    }
+    return p;
+}
+
 template <typename X, int D>
 hipError_t bwd_rows_mfma(castling_attn* h, bool launch, bool query, const void* x, const void* y,
                          void* dx, size_t* lds, hipStream_t s, const BwdRowsParams& p)
@@ -489,9 +520,9 @@ hipError_t bwd_rows_mfma(castling_attn* h, bool launch, bool query, const void* 
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
     }
     // the block loads the state once: several tiles per block where there are many
-    const long long all = static_cast<long long>(h->row_tiles) * h->units;
+    const long long all = static_cast<long long>(p.tiles) * h->units;
     const int tpb = static_cast<int>(std::max(1ll, std::min(8ll, all / 1024)));
-    const dim3 grid((h->row_tiles + tpb - 1) / tpb, h->units);
+    const dim3 grid((p.tiles + tpb - 1) / tpb, h->units);
     auto u16 = [](const void* ptr) { return static_cast<const uint16_t*>(ptr); };
     if (query)
         hipLaunchKernelGGL((bwd_rows_mfma_kernel<X, D, true>), grid, dim3(256), bytes, s, u16(x), u16(y),
@@ -510,19 +541,7 @@ hipError_t bwd_rows(castling_attn* h, bool launch, bool query, const void* x, co
 {
     if constexpr (sizeof(T) == 2 && (D == 32 || D == 64)) {
         if (h->mfma_rows) {
-            BwdRowsParams p = {};
-            if (launch) {
-                const castling_attn_desc_t& d = h->desc;
-                p.N = d.N;
-                p.tiles = h->row_tiles;
-                p.norm_none = d.norm == CASTLING_NORM_NONE;
-                p.residual_q = h->residual_q;
-                p.d_valid = d.d;
-                p.eps = d.eps;
-                p.ascale = bwd_a_scale(h);
-                p.in = h->in_st;
-                p.out = h->out_st;
-            }
+            const BwdRowsParams p = launch ? bwd_rows_params(h, query) : BwdRowsParams{};
             return h->half16 ? bwd_rows_mfma<F16Fmt, D>(h, launch, query, x, y, dx, lds, s, p)
                              : bwd_rows_mfma<Bf16Fmt, D>(h, launch, query, x, y, dx, lds, s, p);
         }
@@ -539,18 +558,8 @@ hipError_t bwd_rows(castling_attn* h, bool launch, bool query, const void* x, co
                                    hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
     }
     const castling_attn_desc_t& d = h->desc;
-    BwdRowsParams p = {};
-    p.N = d.N;
-    p.tiles = h->row_tiles;
-    p.norm_none = d.norm == CASTLING_NORM_NONE;
-    p.residual_q = h->residual_q;
-    p.d_valid = d.d;
-    p.eps = d.eps;
-    p.ascale = bwd_a_scale(h);
-    p.mscale = query ? kInvPi : kInvPi / p.ascale;
-    p.in = h->in_st;
-    p.out = h->out_st;
-    const dim3 grid(h->row_tiles, h->units);
+    const BwdRowsParams p = bwd_rows_params(h, query);
+    const dim3 grid(p.tiles, h->units);
     if (query)
         hipLaunchKernelGGL((bwd_rows_kernel<T, D, true>), grid, dim3(256), bytes, s,
                            static_cast<const T*>(x), static_cast<const T*>(y), h->state, nullptr,
@@ -587,10 +596,10 @@ hipError_t bwd_filter_ks(castling_attn* h, bool launch, const void* v, const voi
     p.chunks = h->filter_chunks;
     p.d_valid = d.d;
     p.in = h->in_st;
-    p.out = h->out_st;
+    p.out = h->pool == 2 ? h->in_st : h->out_st;  // (pooled queries: g comes on the fine grid)
     // the class tokens in front of the grid take no part in the convolution
     const T* vg = static_cast<const T*>(v) + static_cast<long long>(d.extra_tokens) * h->in_st.n;
-    const T* gg = static_cast<const T*>(g) + static_cast<long long>(d.extra_tokens) * h->out_st.n;
+    const T* gg = static_cast<const T*>(g) + static_cast<long long>(d.extra_tokens) * p.out.n;
     hipLaunchKernelGGL((bwd_filter_kernel<T, D, KS>), dim3(h->filter_chunks, h->units),
                        dim3(kBwdFilterThreads),
                        bytes, s, vg, gg, h->fpart, d.heads, p);
@@ -751,7 +760,6 @@ int castling_attn_validate(const castling_attn_desc_t* d)
         return CASTLING_ERR_UNSUPPORTED;
     if (d->q_pool < 0 || d->reserved0 != 0) return CASTLING_ERR_INVALID_ARG;
     if (d->q_pool > 2 || (d->q_pool == 2 && d->extra_tokens != 0)) return CASTLING_ERR_UNSUPPORTED;
-    if (d->q_pool == 2 && (d->flags & CASTLING_FLAG_TRAINING)) return CASTLING_ERR_UNSUPPORTED;
     if (d->q_pool != 2 && (d->q_stride_b != 0 || d->q_stride_h != 0 || d->q_stride_n != 0))
         return CASTLING_ERR_INVALID_ARG;
     if ((d->flags & CASTLING_FLAG_RESIDUAL_Q) && d->branches != 0 &&
@@ -929,9 +937,10 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         const int n_tiles = ((desc->grid_w + kApplyTW - 1) / kApplyTW) *
                             ((desc->grid_h + kApplyTH - 1) / kApplyTH);
         h->row_tiles = (desc->N + kBwdTokens - 1) / kBwdTokens;
-        h->kb_parts = h->mfma_rows ? 4 * h->row_tiles : h->row_tiles;
+        h->qrow_tiles = (h->nq + kBwdTokens - 1) / kBwdTokens;
+        h->kb_parts = h->mfma_rows ? 4 * h->qrow_tiles : h->qrow_tiles;
         h->filter_chunks = std::max(1, std::min(n_tiles, 1024 / h->units));
-        a_bytes = align_up(h->in_span, 256);
+        a_bytes = align_up(h->in_span, 256) * (h->pool == 2 ? 3 : 1);  // a; pooled: + q_up, g_up
         kbp_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->kb_parts * h->dpad, 256);
         kb_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->dpad, 256);
         wflip_bytes = align_up(dtype_size(desc->io_dtype) * static_cast<size_t>(desc->heads) * desc->d *
@@ -975,6 +984,19 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->wfrag = reinterpret_cast<bf16_t*>(p);
     p += wfrag_bytes;
     h->a_buf = p;
+    h->q_up = h->g_up = nullptr;
+    if (h->training && h->pool == 2) {
+        // the three hold rows only where pooled queries stand; the rest stays zero for good
+        h->q_up = p + a_bytes / 3;
+        h->g_up = p + 2 * (a_bytes / 3);
+        e = hipMemset(p, 0, a_bytes);
+        if (e == hipSuccess) e = hipStreamSynchronize(nullptr);  // before any stream's kernels
+        if (e != hipSuccess) {
+            (void)hipFree(h->workspace);
+            delete h;
+            return hip_fail(e);
+        }
+    }
     p += a_bytes;
     h->kb_part = reinterpret_cast<float*>(p);
     p += kbp_bytes;
@@ -1168,17 +1190,21 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         if (misaligned(ptr)) return CASTLING_ERR_INVALID_ARG;
     // no gradient may overlap an input or another gradient
     const void* ins[] = {q, k, v, grad_out};
-    const size_t in_bytes[] = {h->in_span, h->in_span, h->in_span, h->out_span};
+    const size_t in_bytes[] = {h->q_span, h->in_span, h->in_span, h->out_span};
     void* outs[] = {grad_q, grad_k, grad_v};
+    const size_t out_bytes[] = {h->q_span, h->in_span, h->in_span};
     for (int o = 0; o < 3; ++o) {
         for (int i = 0; i < 4; ++i)
-            if (overlaps(outs[o], h->in_span, ins[i], in_bytes[i])) return CASTLING_ERR_ALIAS;
+            if (overlaps(outs[o], out_bytes[o], ins[i], in_bytes[i])) return CASTLING_ERR_ALIAS;
         for (int o2 = o + 1; o2 < 3; ++o2)
             if (outs[o] == outs[o2]) return CASTLING_ERR_ALIAS;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t es = dtype_size(d.io_dtype);
     const int taps = d.dw_kernel * d.dw_kernel;
+    // pooled queries: the query-side kernel puts q, a, g on their places in the fine grid (zero
+    // elsewhere) and the later passes run on the grid of k and v as they are
+    const bool pooled = h->pool == 2;
     h->state_valid = false;  // the workspace ends up holding the state of (q, a), not of (k, v)
     h->apply_ready = false;
     h->partials_pending = false;
@@ -1197,7 +1223,7 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         hipLaunchKernelGGL(bwd_vec_combine_kernel, dim3(h->units), dim3(1024), 0, s, h->kb_part, h->kb,
                            h->kb_parts, h->dpad);
         HIP_TRY(hipGetLastError());
-        st = do_reduce(h, q, h->a_buf, nullptr, s);
+        st = do_reduce(h, pooled ? h->q_up : q, h->a_buf, nullptr, s);
         if (st != CASTLING_OK) return st;
         h->state_valid = false;
         // dk per key row from the state of (q, a)
@@ -1209,10 +1235,11 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         // no attention branch: q and k do not reach the output
         typed([&](auto t, auto) {
             using T = decltype(t);
-            const int pieces = d.N * d.d / IO<T>::VEC;
-            for (void* gp : {grad_q, grad_k})
-                hipLaunchKernelGGL(zero_rows_kernel<T>, dim3((pieces + 255) / 256, h->units), dim3(256),
-                                   0, s, static_cast<T*>(gp), d.N, d.d, d.heads, h->in_st);
+            const int per_row = d.d / IO<T>::VEC;
+            hipLaunchKernelGGL(zero_rows_kernel<T>, dim3((h->nq * per_row + 255) / 256, h->units),
+                               dim3(256), 0, s, static_cast<T*>(grad_q), h->nq, d.d, d.heads, h->q_st);
+            hipLaunchKernelGGL(zero_rows_kernel<T>, dim3((d.N * per_row + 255) / 256, h->units),
+                               dim3(256), 0, s, static_cast<T*>(grad_k), d.N, d.d, d.heads, h->in_st);
             return 0;
         });
         HIP_TRY(hipGetLastError());
@@ -1231,19 +1258,35 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
     }
     h->ov.on = true;
     h->ov.q = h->in_st;
-    h->ov.v = h->out_st;
+    h->ov.v = pooled ? h->in_st : h->out_st;
     h->ov.out = h->in_st;
     h->ov.lin_scale = 1.0f / bwd_a_scale(h);
-    h->ov.generic = h->in_st.b != h->out_st.b || h->in_st.h != h->out_st.h || h->in_st.n != h->out_st.n;
+    h->ov.generic = h->ov.v.b != h->in_st.b || h->ov.v.h != h->in_st.h || h->ov.v.n != h->in_st.n;
     h->apply_ready = lin;
-    e = do_apply(h, true, k, grad_out, dw ? h->wflip : nullptr, nullptr, grad_v, s);
+    const void* g_fine = grad_out;
+    if (pooled) {
+        g_fine = h->g_up;
+        if (!lin) {
+            // no query-side kernel has run: place g on the fine grid here
+            e = dispatch_type_width(d.io_dtype, h->dpad, [&](auto t, auto) {
+                using T = decltype(t);
+                const int pieces = h->nq * (d.d / IO<T>::VEC);
+                hipLaunchKernelGGL(scatter_rows_kernel<T>, dim3((pieces + 255) / 256, h->units), dim3(256),
+                                   0, s, static_cast<const T*>(grad_out), static_cast<T*>(h->g_up), h->nq,
+                                   d.d, d.heads, h->out_st, h->in_st, h->qgrid_w, d.grid_w);
+                return hipGetLastError();
+            });
+            HIP_TRY(e);
+        }
+    }
+    e = do_apply(h, true, k, g_fine, dw ? h->wflip : nullptr, nullptr, grad_v, s);
     h->ov.on = false;
     h->apply_ready = false;
     HIP_TRY(e);
     if (dw) {
         e = typed([&](auto t, auto dc) {
             size_t unused = 0;
-            return bwd_filter<decltype(t), decltype(dc)::value>(h, true, v, grad_out, &unused, s);
+            return bwd_filter<decltype(t), decltype(dc)::value>(h, true, v, g_fine, &unused, s);
         });
         HIP_TRY(e);
         const int n = d.heads * d.d * (taps + 1);

@@ -172,3 +172,80 @@ def test_shapes_whose_tile_of_v_exceeds_the_lds_are_refused():
         b.CastlingAttn(d)
     assert e.value.status == b.ERR_UNSUPPORTED
     b.CastlingAttn(b.make_desc(1, 1, 64 * 64, 128, 64, 64, 3, "f32", q_pool=2)).destroy()
+
+
+# ---------------------------------------------------------------- backward of the downsampling layer
+from parity_util import GRAD_TOL  # noqa: E402
+
+BACKWARD = [CASES[0], CASES[1], CASES[2], CASES[3], CASES[4], CASES[6], CASES[8],
+            Workload("ds_bf16_d64_30x34_k5", "bf16", 1, 2, 64, 30, 34, 5)]
+
+
+def run_backward(wl, x, g, residual=True, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, fused=False):
+    dev = torch.device("cuda:0")
+    B, H, N, d = wl.B, wl.heads, wl.N, wl.d
+    nq = coarse(wl).N
+    flags = b.FLAG_TRAINING | (b.FLAG_RESIDUAL_Q if residual else 0)
+    kw = dict(norm=norm, branches=branches, flags=flags, q_pool=2)
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
+    t["g"] = g.to(dev)
+    if fused:  # q, g token-major; k, v slices of one fused tensor, and so their gradients
+        dt = x["q"].dtype
+        kv = torch.full((B, N, 2, H, d), float("nan"), dtype=dt, device=dev)
+        kv[:, :, 0], kv[:, :, 1] = (x[n].to(dev).permute(0, 2, 1, 3) for n in ("k", "v"))
+        t["k"], t["v"] = kv[:, :, 0], kv[:, :, 1]
+        t["q"] = x["q"].to(dev).permute(0, 2, 1, 3).contiguous()
+        t["g"] = g.to(dev).permute(0, 2, 1, 3).contiguous()
+        dkv = torch.full_like(kv, float("nan"))
+        gk, gv = dkv[:, :, 0], dkv[:, :, 1]
+        gq = torch.full_like(t["q"], float("nan"))
+        kw.update(in_strides=(N * 2 * H * d, d, 2 * H * d), q_strides=b.token_major_strides(H, nq, d),
+                  out_strides=b.token_major_strides(H, nq, d))
+    else:
+        gq = torch.full_like(t["q"], float("nan"))
+        gk, gv = (torch.full_like(t["k"], float("nan")) for _ in range(2))
+    gw = torch.full(t["w"].shape, float("nan"), dtype=torch.float32, device=dev)
+    gb = torch.full((H, d), float("nan"), dtype=torch.float32, device=dev)
+    attn = b.CastlingAttn(b.make_desc(B, H, N, d, wl.grid_h, wl.grid_w, wl.dw_kernel, wl.dtype, **kw))
+    outs = []
+    for rep in range(2):  # the buffers that hold rows on the fine grid are reused as they are
+        attn.backward(t["q"], t["k"], t["v"], t["w"], t["g"], gq, gk, gv, gw, gb)
+        torch.cuda.synchronize()
+        res = [a.permute(0, 2, 1, 3).contiguous() if fused else a for a in (gq, gk, gv)]
+        outs.append([inputs.to_f64(a) for a in res] + [gw.double().cpu().numpy(), gb.double().cpu().numpy()])
+    attn.destroy()
+    assert all(np.array_equal(a, c) for a, c in zip(outs[0], outs[1]))
+    return outs[0]
+
+
+@pytest.mark.parametrize("wl", BACKWARD, ids=lambda w: w.name)
+@pytest.mark.parametrize("norm", [b.NORM_ROWSUM, b.NORM_NONE])
+def test_downsampling_backward_against_definition(oracle, wl, norm):
+    x = draw(wl, seed=75)
+    g = inputs.make_inputs(coarse(wl), seed=1075)["v"]
+    q, k, v, w, _ = oracle_inputs(x)
+    for branches, residual in ((b.BRANCH_ALL, True), (b.BRANCH_LINEAR, False), (b.BRANCH_DWCONV, False)):
+        print(f"case downsampling backward {wl.name} norm={norm} branches={branches}", flush=True)
+        want = oracle.backward_pooled_explicit(q, k, v, w, inputs.to_f64(g), wl.grid_h, wl.grid_w,
+                                               residual=residual, norm=norm, branches=branches)
+        got = run_backward(wl, x, g, residual=residual, norm=norm, branches=branches)
+        for name, a, o in zip(("dq", "dk", "dv", "dw", "dbias"), got, want):
+            assert np.isfinite(a).all(), (wl.name, name)
+            if np.sqrt(np.mean(o * o)) < 1e-9:
+                assert np.abs(a).max() < 2e-3, (wl.name, name)
+                continue
+            err = rel_err(a, o)
+            print(f"  {name} err {err:.2e}", flush=True)
+            assert err <= GRAD_TOL[wl.dtype], (wl.name, norm, branches, name, err)
+
+
+@pytest.mark.parametrize("wl", [CASES[0], CASES[2], CASES[4]], ids=lambda w: w.name)
+def test_downsampling_backward_in_projection_adjacent_layouts(oracle, wl):
+    x = draw(wl, seed=76)
+    g = inputs.make_inputs(coarse(wl), seed=1076)["v"]
+    q, k, v, w, _ = oracle_inputs(x)
+    print(f"case downsampling backward layouts {wl.name}", flush=True)
+    want = oracle.backward_pooled_explicit(q, k, v, w, inputs.to_f64(g), wl.grid_h, wl.grid_w)
+    got = run_backward(wl, x, g, fused=True)
+    for name, a, o in zip(("dq", "dk", "dv", "dw", "dbias"), got, want):
+        assert rel_err(a, o) <= GRAD_TOL[wl.dtype], (wl.name, name)
