@@ -707,7 +707,6 @@ __global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_kernel(const T* 
 {
     constexpr int NTHR = kBwdFilterThreads;
     constexpr int VEC = IO<T>::VEC;
-    constexpr int LPR = D / VEC;
     constexpr int HH = kApplyTH + KS - 1, HW = kApplyTW + KS - 1;
     using Pair = ChannelPair<T>;
     constexpr int TPC = 2 * NTHR / D;              // threads per pair of channels
@@ -737,7 +736,7 @@ __global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_kernel(const T* 
     uint4 pre[DB ? PIECES : 1];
     int buf = 0;
     if constexpr (DB) {
-        if (blockIdx.x < p.n_tiles) {
+        if (static_cast<int>(blockIdx.x) < p.n_tiles) {
 #pragma unroll
             for (int k = 0; k < PIECES; ++k)
                 pre[k] = bwd_filter_piece<T, D, KS>(v, g, p, in_off, out_off, blockIdx.x, tid + NTHR * k);

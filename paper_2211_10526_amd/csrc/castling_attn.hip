@@ -1200,7 +1200,6 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
             if (outs[o] == outs[o2]) return CASTLING_ERR_ALIAS;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const size_t es = dtype_size(d.io_dtype);
     const int taps = d.dw_kernel * d.dw_kernel;
     // pooled queries: the query-side kernel puts q, a, g on their places in the fine grid (zero
     // elsewhere) and the later passes run on the grid of k and v as they are
@@ -1304,7 +1303,6 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         }
         HIP_TRY(hipGetLastError());
     }
-    (void)es;
     return CASTLING_OK;
 }
 
