@@ -112,16 +112,22 @@ def bench_pairwise(args, wl, sets, binding, inputs, torch):
     }))
 
 
-def bench_backward(args, wl, sets, host0, binding, inputs, torch):
-    """K calls of castling_attn_backward over the rotating input sets (the forward's `out`
-    buffers stand in for grad_out); one JSON line.  Algorithmic bytes of a backward: q, k, v,
-    grad_out read and the three gradients written once (7 tensors)."""
+def bench_backward(args, wl, sets, host0, binding, inputs, torch, nq):
+    """K calls of castling_attn_backward over the rotating input sets; one JSON line.
+    Algorithmic bytes of a backward: q, k, v, grad_out read and the three gradients written once
+    (7 tensors; with --downsample q, grad_out and grad_q have a row per pooled query)."""
     dev = sets[0]["q"].device
-    attn = binding.CastlingAttn.for_workload(wl, flags=binding.FLAG_TRAINING)
+    if args.downsample:
+        attn = binding.CastlingAttn(binding.make_desc(
+            wl.B, wl.heads, wl.N, wl.d, wl.grid_h, wl.grid_w, wl.dw_kernel, wl.dtype,
+            flags=binding.FLAG_RESIDUAL_Q | binding.FLAG_TRAINING, q_pool=2))
+    else:
+        attn = binding.CastlingAttn.for_workload(wl, flags=binding.FLAG_TRAINING)
     stream = torch.cuda.Stream()
     for t in sets:
         t["g"] = torch.randn(t["q"].shape, device=dev).to(t["q"].dtype)
-    grads = [torch.empty_like(sets[0]["q"]) for _ in range(3)]
+    grads = [torch.empty_like(sets[0]["q"]), torch.empty_like(sets[0]["k"]),
+             torch.empty_like(sets[0]["k"])]
     gw = torch.empty(sets[0]["w"].shape, dtype=torch.float32, device=dev)
     gb = torch.empty((wl.heads, wl.d), dtype=torch.float32, device=dev)
 
@@ -143,7 +149,8 @@ def bench_backward(args, wl, sets, host0, binding, inputs, torch):
         torch.cuda.synchronize()
         elapsed = time.perf_counter() - t0
         event_ms = e0.elapsed_time(e1) / args.steps
-    nbytes = 7 * wl.elems * wl.itemsize
+    tensor_bytes = wl.elems * wl.itemsize
+    nbytes = 4 * tensor_bytes + 3 * (tensor_bytes * nq // wl.N)
     achieved = nbytes / (event_ms * 1e-3) / 1e9
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -152,13 +159,18 @@ def bench_backward(args, wl, sets, host0, binding, inputs, torch):
         xs = {n: inputs.to_f64(host0[n][:nb]) for n in ("q", "k", "v")}
         g64 = inputs.to_f64(sets[0]["g"][:nb].cpu())
         w64 = inputs.to_f64(host0["w"])
+        if args.downsample:  # (the oracle has the definition only: O(Nq N d) per unit)
+            oracle_bwd = lambda: oracle.backward_pooled_explicit(xs["q"], xs["k"], xs["v"], w64, g64,
+                                                                 wl.grid_h, wl.grid_w)
+        else:
+            oracle_bwd = lambda: oracle.backward(xs["q"], xs["k"], xs["v"], w64, g64, wl.grid_h, wl.grid_w)
         c0 = time.perf_counter()
-        oracle.backward(xs["q"], xs["k"], xs["v"], w64, g64, wl.grid_h, wl.grid_w)
+        oracle_bwd()
         first = time.perf_counter() - c0
         reps = max(1, min(200, int(10.0 / max(first, 1e-6))))
         c0 = time.perf_counter()
         for _ in range(reps):
-            oracle.backward(xs["q"], xs["k"], xs["v"], w64, g64, wl.grid_h, wl.grid_w)
+            oracle_bwd()
         c1 = time.perf_counter() - c0
         cpu_baseline = {"value": round(reps * nb * wl.N / c1, 1), "unit": "tokens/s",
                         "cores": oracle.num_threads(), "kind": "oracle",
@@ -173,6 +185,7 @@ def bench_backward(args, wl, sets, host0, binding, inputs, torch):
         "data": "synthetic",
         "config": {"workload": wl.name, "B": wl.B, "heads": wl.heads, "d": wl.d, "N": wl.N,
                    "grid": [wl.grid_h, wl.grid_w], "dw_kernel": wl.dw_kernel, "op": "backward",
+                   "queries_per_unit": nq,
                    "input_sets_rotated": len(sets)},
         "roofline": {"bound": "hbm", "kernel": "backward (all launches)", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -230,9 +243,9 @@ def main():
     if args.pairwise:
         return bench_pairwise(args, wl, sets, binding, inputs, torch)
     if args.backward:
-        if args.layout != "dense" or args.downsample:
-            sys.exit("bench.py: --backward goes with the dense layout of the ordinary layer")
-        return bench_backward(args, wl, sets, host0, binding, inputs, torch)
+        if args.layout != "dense":
+            sys.exit("bench.py: --backward goes with the dense layout")
+        return bench_backward(args, wl, sets, host0, binding, inputs, torch, nq)
     if args.layout == "fused":
         attn = binding.CastlingAttn.for_workload(
             wl, in_strides=binding.fused_qkv_strides(wl.heads, wl.N, wl.d),
