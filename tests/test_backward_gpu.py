@@ -232,3 +232,55 @@ def test_gradients_at_the_edges(oracle, case):
     want = oracle.backward(q, k, v, w, inputs.to_f64(x["g"]), wl.grid_h, wl.grid_w, extra=extra)
     got = run(wl, x, extra=extra)
     check(got, want, GRAD_TOL[wl.dtype], wl.name)
+
+
+@pytest.mark.parametrize("wl", [CASES[0], CASES[1], CASES[2]], ids=lambda w: w.name)
+def test_backward_in_a_captured_graph(oracle, wl):
+    """backward() only enqueues kernels (no allocation, synchronisation or memset), so a
+    training step can capture it in a HIP graph: every replay, with eager work and
+    synchronisations in between and new inputs written into the captured buffers, reproduces
+    the eager gradients bit for bit."""
+    dev = torch.device("cuda:0")
+    xs = [draw(wl, 0, seed=98 + i) for i in range(3)]
+    names = ("q", "k", "v", "w", "g")
+    bufs = {n: torch.empty_like(xs[0][n], device=dev) for n in names}
+
+    def grads():
+        return [torch.full_like(bufs["q"], float("nan")) for _ in range(3)] + \
+               [torch.full(bufs["w"].shape, float("nan"), dtype=torch.float32, device=dev),
+                torch.full((wl.heads, wl.d), float("nan"), dtype=torch.float32, device=dev)]
+
+    captured, eager = grads(), grads()
+    attn = b.CastlingAttn.for_workload(wl, flags=b.FLAG_TRAINING)
+    side = torch.cuda.Stream()
+    for n in names:
+        bufs[n].copy_(xs[0][n])
+    torch.cuda.synchronize()
+    args = [bufs[n] for n in names]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        attn.backward(*args, *captured, stream=side)  # warm-up
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            attn.backward(*args, *captured, stream=torch.cuda.current_stream())
+    for i, x in enumerate(xs):
+        print(f"case backward graph replay {wl.name} #{i}", flush=True)
+        for n in names:
+            bufs[n].copy_(x[n])
+        torch.cuda.synchronize()
+        for t in captured:
+            t.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        attn.backward(*args, *eager)
+        torch.cuda.synchronize()
+        for a, c in zip(captured, eager):
+            assert torch.equal(a.view(torch.int32 if a.element_size() == 4 else torch.int16),
+                               c.view(torch.int32 if c.element_size() == 4 else torch.int16))
+        q, k, v, w, _ = oracle_inputs(x)
+        want = oracle.backward(q, k, v, w, inputs.to_f64(x["g"]), wl.grid_h, wl.grid_w)
+        got = [inputs.to_f64(t) if t.dtype != torch.float32 or wl.dtype == "f32" else t.double().cpu().numpy()
+               for t in captured]
+        check(got, want, GRAD_TOL[wl.dtype], (wl.name, "graph", i))
+    del graph
+    attn.destroy()
