@@ -853,6 +853,182 @@ __global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_kernel(const T* 
     for (int idx = tid; idx < NT * D; idx += NTHR) o[idx] = sums[idx];
 }
 
+// ---------------------------------------------------------------------------------------------
+// The filter gradient for 16-bit I/O on two-element dot products (v_dot2c_f32_bf16 / _f16): the
+// sum over tokens runs over pairs of neighbouring tokens of one channel, so LDS holds the tiles
+// channel-major (tokens of a channel contiguous, two per 32-bit word; the channel stride is an odd
+// number of words: lanes = channels read conflict-free) -- the staging transposes the 16-byte
+// pieces of 8 channels into eight 2-byte writes.  A thread owns one channel, one tile row ty
+// and the filter rows dy = part / 4, part / 4 + TPC / 4, ... (part = tid / D, TPC = 512 / D); per
+// tile it reads the 8 words of g's row ty and, per filter row, the words of v's row ty + dy, forms
+// the odd-aligned pairs with one funnel shift each, and does 8 dot products per tap (half the
+// FMAs of the fp32 form and no conversions).  Same partial layout, same fixed order of additions
+// as bwd_filter_kernel.
+template <int D, int KS>
+struct FilterDot2Layout {
+    static constexpr int HH = kApplyTH + KS - 1, HW = kApplyTW + KS - 1;
+    static constexpr int ROW = HW / 2;                 // words per halo row of one channel
+    static constexpr int CS = (HH * ROW) | 1;          // words per channel of v (odd)
+    static constexpr int GS = (kApplyTokens / 2) | 1;  // words per channel of g (odd)
+    static constexpr int IMAGE = D * (CS + GS);        // words of one image
+    static constexpr int ITEMS = (HH * HW + kApplyTokens) * (D / 8);  // 16-byte pieces of one image
+    static constexpr int PIECES = (ITEMS + kBwdFilterThreads - 1) / kBwdFilterThreads;
+    static constexpr bool DB = PIECES <= 6 && 2 * IMAGE * 4 <= 110 * 1024;
+    static_assert(HW % 2 == 0, "rows hold whole pairs of tokens");
+};
+
+template <int D, int KS>
+constexpr size_t bwd_filter_dot2_lds_bytes()
+{
+    using L = FilterDot2Layout<D, KS>;
+    const size_t tiles = static_cast<size_t>(L::IMAGE) * 4 * (L::DB ? 2 : 1);
+    const size_t sums = sizeof(float) * (KS * KS + 1) * D;
+    return tiles > sums ? tiles : sums;
+}
+
+template <typename X, int D, int KS>
+__global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_dot2_kernel(
+    const uint16_t* __restrict__ v, const uint16_t* __restrict__ g, float* __restrict__ part_out,
+    int heads, BwdFilterParams p)
+{
+    using L = FilterDot2Layout<D, KS>;
+    constexpr int NTHR = kBwdFilterThreads;
+    constexpr int HH = L::HH, HW = L::HW, ROW = L::ROW, CS = L::CS, GS = L::GS;
+    constexpr int TPC = NTHR / D;                  // threads per channel
+    constexpr int DYS = TPC / 4;                   // filter rows taken at a time
+    constexpr int IPT = (KS + DYS - 1) / DYS;      // filter rows per thread
+    constexpr int NT = KS * KS + 1;                // taps and the bias
+    constexpr bool DB = L::DB;
+    constexpr int PIECES = L::PIECES;
+    static_assert(TPC % 4 == 0, "a thread keeps one tile row");
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+    uint32_t* img = reinterpret_cast<uint32_t*>(lds_raw);
+
+    const int tid = threadIdx.x;
+    const int unit = blockIdx.y;
+    const int c = tid % D, part = tid / D;
+    const int ty = part % 4, dy0 = part / 4;
+    const long long in_off = unit_offset(unit, heads, p.in);
+    const long long out_off = unit_offset(unit, heads, p.out);
+    const uint32_t ones = opaque_u32(X::kOneLo | X::kOneHi);  // (kept out of the inline constants)
+
+    float acc[IPT][KS], gsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < IPT; ++i)
+#pragma unroll
+        for (int dx = 0; dx < KS; ++dx) acc[i][dx] = 0.f;
+
+    // piece idx of a tile's image from global memory / into the channel-major LDS image
+    auto load_piece16 = [&](int tile, int idx) {
+        return bwd_filter_piece<uint16_t, D, KS>(v, g, p, in_off, out_off, tile, idx);
+    };
+    auto store_piece16 = [&](uint32_t* dst_img, int idx, uint4 val) {
+        if (idx >= L::ITEMS) return;
+        const int tok = idx / (D / 8), piece = idx % (D / 8);
+        const bool halo = tok < HH * HW;
+        const int t2 = halo ? tok : tok - HH * HW;
+        uint16_t* base = reinterpret_cast<uint16_t*>(dst_img + (halo ? 0 : D * CS)) + t2;
+        const int cs2 = 2 * (halo ? CS : GS);  // channel stride in 16-bit elements
+        const uint32_t w[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            base[(piece * 8 + 2 * e) * cs2] = static_cast<uint16_t>(w[e]);
+            base[(piece * 8 + 2 * e + 1) * cs2] = static_cast<uint16_t>(w[e] >> 16);
+        }
+    };
+
+    uint4 pre[DB ? PIECES : 1];
+    int buf = 0;
+    if constexpr (DB) {
+        if (static_cast<int>(blockIdx.x) < p.n_tiles) {
+#pragma unroll
+            for (int k = 0; k < PIECES; ++k) pre[k] = load_piece16(blockIdx.x, tid + NTHR * k);
+#pragma unroll
+            for (int k = 0; k < PIECES; ++k) store_piece16(img, tid + NTHR * k, pre[k]);
+        }
+        __syncthreads();
+    }
+    for (int tile = blockIdx.x; tile < p.n_tiles; tile += p.chunks) {
+        if constexpr (DB) {
+            // the next tile's loads go out now and land in the other image after this tile's work
+            if (tile + p.chunks < p.n_tiles) {
+#pragma unroll
+                for (int k = 0; k < PIECES; ++k) pre[k] = load_piece16(tile + p.chunks, tid + NTHR * k);
+            }
+        } else {
+            __syncthreads();  // the previous tile's reads are done
+            block_stage<L::ITEMS, uint4, NTHR, 6>(
+                tid, [&](int idx) { return load_piece16(tile, idx); },
+                [&](int idx, uint4 val) { store_piece16(img, idx, val); });
+            __syncthreads();
+        }
+        const uint32_t* vcur = img + buf * L::IMAGE + c * CS;
+        const uint32_t* gcur = img + buf * L::IMAGE + D * CS + c * GS + ty * (kApplyTW / 2);
+
+        uint32_t G[kApplyTW / 2];  // pairs of tokens of g's row ty
+#pragma unroll
+        for (int j = 0; j < kApplyTW / 2; ++j) G[j] = gcur[j];
+        if (dy0 == 0) {
+#pragma unroll
+            for (int j = 0; j < kApplyTW / 2; ++j) gsum = X::dot2(G[j], ones, gsum);
+        }
+#pragma unroll
+        for (int i = 0; i < IPT; ++i) {
+            const int dy = dy0 + DYS * i;
+            if (dy < KS) {  // (the same for all lanes of a wave where D >= 64)
+                const uint32_t* row = vcur + (ty + dy) * ROW;
+                uint32_t E[ROW], O[ROW - 1];  // pairs starting at even / at odd tokens
+#pragma unroll
+                for (int j = 0; j < ROW; ++j) E[j] = row[j];
+#pragma unroll
+                for (int j = 0; j + 1 < ROW; ++j) O[j] = __builtin_amdgcn_alignbit(E[j + 1], E[j], 16);
+#pragma unroll
+                for (int dx = 0; dx < KS; ++dx)
+#pragma unroll
+                    for (int pr = 0; pr < kApplyTW / 2; ++pr)
+                        acc[i][dx] = X::dot2(G[pr], (dx % 2) ? O[pr + dx / 2] : E[pr + dx / 2], acc[i][dx]);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // one row in registers at a time
+        }
+        if constexpr (DB) {
+            if (tile + p.chunks < p.n_tiles) {
+#pragma unroll
+                for (int k = 0; k < PIECES; ++k)
+                    store_piece16(img + (buf ^ 1) * L::IMAGE, tid + NTHR * k, pre[k]);
+            }
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    // the four tile rows of a tap meet in LDS, in order
+    __syncthreads();
+    float* sums = reinterpret_cast<float*>(lds_raw);  // [NT][D]
+#pragma unroll 1
+    for (int ph = 0; ph < 4; ++ph) {
+        if (ty == ph) {
+#pragma unroll
+            for (int i = 0; i < IPT; ++i) {
+                const int dy = dy0 + DYS * i;
+                if (dy < KS) {
+#pragma unroll
+                    for (int dx = 0; dx < KS; ++dx) {
+                        float* s = sums + (dy * KS + dx) * D + c;
+                        *s = ph == 0 ? acc[i][dx] : *s + acc[i][dx];
+                    }
+                }
+            }
+            if (dy0 == 0) {
+                float* s = sums + KS * KS * D + c;
+                *s = ph == 0 ? gsum : *s + gsum;
+            }
+        }
+        __syncthreads();
+    }
+    float* o = part_out + (static_cast<size_t>(unit) * p.chunks + blockIdx.x) * NT * D;
+    for (int idx = tid; idx < NT * D; idx += NTHR) o[idx] = sums[idx];
+}
+
 // grid = (ceil(heads * d * (taps + 1) / 16)), block = 256: sums the partial filter gradients over
 // the batch and the chunks into dw [heads][d][taps] and dbias [heads][d] (may be null).  part:
 // [B * heads][chunks][taps + 1][D].  Thread (slice, out) = (tid / 16, tid % 16): the 16 slices
