@@ -982,10 +982,11 @@ __global__ __launch_bounds__(kBwdFilterThreads) void bwd_filter_dot2_kernel(
                 for (int j = 0; j < ROW; ++j) E[j] = row[j];
 #pragma unroll
                 for (int j = 0; j + 1 < ROW; ++j) O[j] = __builtin_amdgcn_alignbit(E[j + 1], E[j], 16);
+                // (consecutive dot products go to different accumulators: no chain of dependent ones)
 #pragma unroll
-                for (int dx = 0; dx < KS; ++dx)
+                for (int pr = 0; pr < kApplyTW / 2; ++pr)
 #pragma unroll
-                    for (int pr = 0; pr < kApplyTW / 2; ++pr)
+                    for (int dx = 0; dx < KS; ++dx)
                         acc[i][dx] = X::dot2(G[pr], (dx % 2) ? O[pr + dx / 2] : E[pr + dx / 2], acc[i][dx]);
             }
             __builtin_amdgcn_sched_barrier(0);  // one row in registers at a time
