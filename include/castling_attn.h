@@ -81,7 +81,9 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
  * (Sec. 3.1, attention designs; Table 1, last row).  Needs the linear branch
  * (CASTLING_ERR_INVALID_ARG otherwise); runs on the vector-ALU kernels.
  * TRAINING: create also allocates what castling_attn_backward needs (one more tensor of the
- * span of q, three of the span of k with q_pool = 2, and a few small buffers). */
+ * span of q, three of the span of k with q_pool = 2, and a few small buffers); shapes whose
+ * backward tiles exceed the LDS of a block (fp32, d = 128, 9 x 9 filters) are refused with
+ * CASTLING_ERR_UNSUPPORTED. */
 enum { CASTLING_FLAG_KEEP_STATE = 1, CASTLING_FLAG_RESIDUAL_Q = 2, CASTLING_FLAG_TRAINING = 4 };
 
 typedef struct {
@@ -174,7 +176,7 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
 int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void* stream);
 
 /* Training-time companions of the layer as O(N^2) attention on the matrix cores (16-bit I/O
- * with d = 64 only, else CASTLING_ERR_UNSUPPORTED).  Shapes, strides and eps come from the handle.
+ * with d = 64 and one query per token only, else CASTLING_ERR_UNSUPPORTED).  Shapes, strides and eps come from the handle.
  *   CASTLING_PAIR_SPARSE_SOFTMAX  out = Mask_thr(Softmax(scale * A B^T)) V, the auxiliary branch
  *       of Eq. 10 (Sec. 3.2.2).  Mask_thr(x) = x if x > thr else 0.  A, B = unit rows of q, k
  *       (normalize = 1, the rows the angular branch uses) or q, k themselves (normalize = 0);
