@@ -614,39 +614,26 @@ template <typename T, int D, int KS>
 hipError_t bwd_filter_ks(castling_attn* h, bool launch, const void* v, const void* g, size_t* lds,
                          hipStream_t s)
 {
+    constexpr size_t bytes = bwd_filter_lds_bytes<T, D, KS>();
     if constexpr (sizeof(T) == 2 && bwd_filter_dot2_lds_bytes<D, KS>() <= kMaxLdsBytes) {
         return h->half16 ? bwd_filter_dot2<F16Fmt, D, KS>(h, launch, v, g, lds, s)
                          : bwd_filter_dot2<Bf16Fmt, D, KS>(h, launch, v, g, lds, s);
-    }
-    constexpr size_t bytes = bwd_filter_lds_bytes<T, D, KS>();
-    if constexpr (bytes > kMaxLdsBytes) {
+    } else if constexpr (bytes > kMaxLdsBytes) {
         // more LDS than a compute unit has: create refuses the shape, no kernel is built for it
         if (bytes > *lds) *lds = bytes;
         return launch ? hipErrorInvalidValue : hipSuccess;
     } else {
-    if (!launch) {
-        if (bytes > *lds) *lds = bytes;
-        if (bytes > kMaxLdsBytes) return hipSuccess;
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_filter_kernel<T, D, KS>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(bytes));
-    }
-    const castling_attn_desc_t& d = h->desc;
-    BwdFilterParams p = {};
-    p.grid_h = d.grid_h;
-    p.grid_w = d.grid_w;
-    p.tiles_x = (d.grid_w + kApplyTW - 1) / kApplyTW;
-    p.n_tiles = p.tiles_x * ((d.grid_h + kApplyTH - 1) / kApplyTH);
-    p.chunks = h->filter_chunks;
-    p.d_valid = d.d;
-    p.in = h->in_st;
-    p.out = h->pool == 2 ? h->in_st : h->out_st;  // (pooled queries: g comes on the fine grid)
-    // the class tokens in front of the grid take no part in the convolution
-    const T* vg = static_cast<const T*>(v) + static_cast<long long>(d.extra_tokens) * h->in_st.n;
-    const T* gg = static_cast<const T*>(g) + static_cast<long long>(d.extra_tokens) * p.out.n;
-    hipLaunchKernelGGL((bwd_filter_kernel<T, D, KS>), dim3(h->filter_chunks, h->units),
-                       dim3(kBwdFilterThreads),
-                       bytes, s, vg, gg, h->fpart, d.heads, p);
-    return hipGetLastError();
+        if (!launch) {
+            if (bytes > *lds) *lds = bytes;
+            return hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_filter_kernel<T, D, KS>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       static_cast<int>(bytes));
+        }
+        const T *vg, *gg;
+        const BwdFilterParams p = bwd_filter_params<T>(h, kApplyTH, v, g, &vg, &gg);
+        hipLaunchKernelGGL((bwd_filter_kernel<T, D, KS>), dim3(h->filter_chunks, h->units),
+                           dim3(kBwdFilterThreads), bytes, s, vg, gg, h->fpart, h->desc.heads, p);
+        return hipGetLastError();
     }
 }
 
