@@ -197,8 +197,9 @@ def bench_backward(args, wl, sets, host0, binding, inputs, torch, nq):
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on one GPU only (the layer's units are independent; "
-              "see DESIGN.md for how it would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the layer's (batch, head) units are "
+              "independent and would shard over GPUs without communication). Run with --gpus 1.",
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
