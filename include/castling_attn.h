@@ -83,8 +83,19 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
  * TRAINING: create also allocates what castling_attn_backward needs (one more tensor of the
  * span of q, three of the span of k with q_pool = 2, and a few small buffers); shapes whose
  * backward tiles exceed the LDS of a block (fp32, d = 128, 9 x 9 filters) are refused with
- * CASTLING_ERR_UNSUPPORTED. */
-enum { CASTLING_FLAG_KEEP_STATE = 1, CASTLING_FLAG_RESIDUAL_Q = 2, CASTLING_FLAG_TRAINING = 4 };
+ * CASTLING_ERR_UNSUPPORTED.
+ * SEPARATE_PASSES: castling_attn_forward enqueues pass 1, the sum of its partial states and pass 2
+ * as the separate launches castling_attn_reduce + castling_attn_apply would, instead of one
+ * kernel (for measurements and for tests of those kernels; results agree to rounding).
+ * VECTOR_ALU: 16-bit types stay on the vector-ALU kernels that fp32 uses (the fallback path;
+ * for measurements and tests). */
+enum {
+    CASTLING_FLAG_KEEP_STATE = 1,
+    CASTLING_FLAG_RESIDUAL_Q = 2,
+    CASTLING_FLAG_TRAINING = 4,
+    CASTLING_FLAG_SEPARATE_PASSES = 8,
+    CASTLING_FLAG_VECTOR_ALU = 16
+};
 
 typedef struct {
     int32_t B, heads, N, d;   /* d: a multiple of 8, at most 128 */
@@ -93,7 +104,7 @@ typedef struct {
     int32_t io_dtype;         /* castling_dtype_t */
     int32_t norm;             /* castling_norm_t */
     uint32_t branches;        /* bitmask of CASTLING_BRANCH_*; 0 is read as CASTLING_BRANCH_ALL */
-    float eps;                /* floor of the L2 norm; 0 is read as 1e-12 */
+    float eps;                /* floor of the L2 norm; 0 is read as 1e-12; otherwise at least FLT_MIN */
     /* Element strides between consecutive batches, heads and tokens of q, k, v (one set for
      * all three) and of out.  All three of a set 0 = contiguous [B][heads][N][d], i.e.
      * {heads*N*d, N*d, d}.  Each must be a positive multiple of 16 bytes, the token stride at

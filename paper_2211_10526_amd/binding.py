@@ -22,6 +22,8 @@ BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
 FLAG_KEEP_STATE = 1
 FLAG_RESIDUAL_Q = 2
 FLAG_TRAINING = 4
+FLAG_SEPARATE_PASSES = 8
+FLAG_VECTOR_ALU = 16
 
 EXPORTS = (
     "castling_attn_validate", "castling_attn_create", "castling_attn_forward",

@@ -7,9 +7,11 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <cfloat>
 #include <cstring>
 #include <memory>
 #include <new>
+#include <vector>
 
 #include "apply_generic.hpp"
 #include "apply_mfma.hpp"
@@ -19,6 +21,7 @@
 #include "pairwise.hpp"
 #include "reduce_generic.hpp"
 #include "reduce_mfma.hpp"
+#include "stream_fwd_host.hpp"
 
 using namespace castling;
 
@@ -111,8 +114,17 @@ struct castling_attn {
     bf16_t* sfrag;      // MFMA path: operand tables, see apply_mfma.hpp
     bf16_t* kfrag;
     float* vhalf;
-    bf16_t* wfrag;
+    bf16_t* wfrag;      // filter operand table of the call in progress (rebuilt by every call that passes filters)
+    bf16_t* wfrag_reg;  // filter operand table of castling_attn_prepare_weights; nothing else writes it
     const void* prepared_w;  // filters registered by castling_attn_prepare_weights
+    bool use_registered;     // the apply launch in progress reads wfrag_reg
+    // one-launch forward (stream_fwd.hpp)
+    bool stream;        // forward() runs it
+    int s_cr, s_rchunk, s_ca, s_ncs, s_nw, s_blocks;
+    uint32_t* kpair;    // [units][32]: pairs of the K_hat column sum in the I/O format
+    uint32_t* s_tasks;  // task lists, queue offsets, counters
+    uint32_t* s_qoff;
+    uint32_t* s_counters;
     // The backward pass runs pass 2 on other tensors: q := k, v := g (layout of out), out := dv
     // (layout of v), without the normaliser.  generic: on the vector-ALU kernel even where the
     // handle's pass 2 is on the matrix cores (the layouts of v and out differ).
@@ -167,6 +179,8 @@ void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const vo
     ex.ks = h->desc.dw_kernel;
     ex.tscale = X::table_scale(h->desc.N);
     ex.pair_skew = h->in_skew;
+    ex.write_state = 1;
+    ex.kpair = nullptr;
     const int per_row = h->n_split * 64 * kReduceWaves;
     const int wthreads = heads * 4 * ex.ks * 3 * 64;
     const int wrows = w ? (wthreads + per_row - 1) / per_row : 0;
@@ -348,7 +362,8 @@ hipError_t apply_mfma_branches(castling_attn* h, bool launch, const void* q, con
     auto go = [&](auto kernel) {
         hipLaunchKernelGGL(kernel, dim3(blocks), dim3(64 * kApplyWaves), kApplyMfmaLdsBytes, s,
                            static_cast<const bf16_t*>(q), static_cast<const bf16_t*>(v),
-                           static_cast<const bf16_t*>(bias), h->sfrag, h->kfrag, h->vhalf, h->wfrag,
+                           static_cast<const bf16_t*>(bias), h->sfrag, h->kfrag, h->vhalf,
+                           h->use_registered ? h->wfrag_reg : h->wfrag,
                            static_cast<bf16_t*>(out), h->apply_heads, total_steps, p);
     };
     if constexpr (kPairKernel) {
@@ -724,6 +739,99 @@ hipError_t do_fused(castling_attn* h, bool launch, const void* q, const void* k,
     }
 }
 
+
+// ------------------------------------------------------------------ one-launch forward
+// Chunk sizes and task lists of the one-launch forward for this handle (create time).
+hipError_t plan_stream(castling_attn* h, std::vector<uint32_t>& tasks, uint32_t (&qoff)[kStreamQueues + 1])
+{
+    const castling_attn_desc_t& d = h->desc;
+    const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    int per_cu = 0;
+    hipError_t e = stream_forward_prepare(d.dw_kernel, lin, dw, h->half16, &per_cu);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) {
+        h->stream = false;
+        return hipSuccess;
+    }
+    // workgroups: what the device holds at once, a multiple of the queue count
+    h->s_blocks = std::min(per_cu, 2) * h->num_cus / kStreamQueues * kStreamQueues;
+    if (h->s_blocks < kStreamQueues) {
+        h->stream = false;
+        return hipSuccess;
+    }
+    // pass 1: chunks of about 512 tokens (a multiple of what the four waves stage per round)
+    const int round = kReduceWaves * kReduceIterTokens;
+    int cr = std::max(1, std::min(64, (d.N + 255) / 512));
+    h->s_rchunk = ((d.N + cr - 1) / cr + round - 1) / round * round;
+    h->s_cr = (d.N + h->s_rchunk - 1) / h->s_rchunk;
+    h->s_ncs = h->s_cr > 1 ? (kCombineEntries + 255) / 256 : 0;
+    // pass 2: chunks of about 8 steps (4 rows x 16 columns each)
+    const int steps = ((d.grid_w + 15) / 16) * ((d.grid_h + 3) / 4);
+    h->s_ca = std::max(1, std::min(kTaskMaxChunks - 1, (steps + 4) / 8));
+    h->s_nw = dw ? (d.heads * 4 * d.dw_kernel * 3 * 64 + kWeightEntriesPerTask - 1) / kWeightEntriesPerTask : 0;
+    if (h->s_nw >= kTaskMaxChunks) {
+        h->stream = false;
+        return hipSuccess;
+    }
+    // pass 1 runs ahead of pass 2 by as many units as keep their V rows within half an L2 (2 MB)
+    const long long v_unit = static_cast<long long>(d.N) * h->in_st.n * 2;
+    const int lookahead = static_cast<int>(std::max(1ll, std::min(8ll, (2ll << 20) / std::max(1ll, v_unit))));
+    build_stream_tasks(h->units, h->s_cr, h->s_ca, h->s_ncs, h->s_nw, lookahead, lin, tasks, qoff);
+    return hipSuccess;
+}
+
+// filters == nullptr: the registered operand table is current
+hipError_t do_stream(castling_attn* h, const void* q, const void* k, const void* v, const void* filters,
+                     const void* bias, void* out, hipStream_t s)
+{
+    const castling_attn_desc_t& d = h->desc;
+    const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
+    const bool dw = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
+    StreamArgs a = {};
+    a.q = static_cast<const bf16_t*>(q);
+    a.k = static_cast<const bf16_t*>(k);
+    a.v = static_cast<const bf16_t*>(v);
+    a.w = static_cast<const bf16_t*>(filters);
+    a.bias = static_cast<const bf16_t*>(bias);
+    a.out = static_cast<bf16_t*>(out);
+    a.partial = h->partial;
+    a.state = h->state;
+    a.sfrag = h->sfrag;
+    a.kpair = h->kpair;
+    a.vhalf = h->vhalf;
+    a.wfrag = filters ? h->wfrag : h->wfrag_reg;
+    a.tasks = h->s_tasks;
+    a.queue_off = h->s_qoff;
+    a.counters = h->s_counters;
+    a.units = h->units;
+    a.heads = d.heads;
+    a.N = d.N;
+    a.H = d.grid_h;
+    a.W = d.grid_w;
+    a.strips = (d.grid_w + 15) / 16;
+    a.spc = (d.grid_h + 3) / 4;
+    a.cr = h->s_cr;
+    a.r_chunk = h->s_rchunk;
+    a.ca = h->s_ca;
+    a.ncs = h->s_ncs;
+    a.nw = (dw && filters) ? h->s_nw : 0;
+    a.norm_none = d.norm == CASTLING_NORM_NONE;
+    // the fp32 state is only for castling_attn_get_state: written when asked for, or when small
+    a.write_state = (d.flags & CASTLING_FLAG_KEEP_STATE) != 0 || h->units <= 64;
+    a.eps = d.eps;
+    a.lin_scale = 1.0f;
+    a.tscale = h->half16 ? F16Fmt::table_scale(d.N) : Bf16Fmt::table_scale(d.N);
+    a.unscale = h->half16 ? F16Fmt::table_unscale(d.N) : Bf16Fmt::table_unscale(d.N);
+    a.in = h->in_st;
+    a.out_st = h->out_st;
+    a.spin_limit = 1 << 22;
+    h->state_valid = lin && a.write_state;
+    h->apply_ready = false;   // the tables of this path are not the ones apply() reads
+    h->partials_pending = false;
+    return stream_forward_launch(d.dw_kernel, lin, dw, h->half16, a, h->s_blocks, s);
+}
+
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
@@ -776,9 +884,11 @@ int castling_attn_validate(const castling_attn_desc_t* d)
     if (d->norm != CASTLING_NORM_ROWSUM && d->norm != CASTLING_NORM_NONE)
         return CASTLING_ERR_INVALID_ARG;
     if (d->branches & ~static_cast<uint32_t>(CASTLING_BRANCH_ALL)) return CASTLING_ERR_INVALID_ARG;
-    if (!(d->eps >= 0.0f)) return CASTLING_ERR_INVALID_ARG;
+    // the kernels form 1 / eps: a floor below the smallest normal float would make it infinite
+    if (!(d->eps >= 0.0f) || (d->eps > 0.0f && d->eps < FLT_MIN)) return CASTLING_ERR_INVALID_ARG;
     if (d->flags & ~static_cast<uint32_t>(CASTLING_FLAG_KEEP_STATE | CASTLING_FLAG_RESIDUAL_Q |
-                                          CASTLING_FLAG_TRAINING))
+                                          CASTLING_FLAG_TRAINING | CASTLING_FLAG_SEPARATE_PASSES |
+                                          CASTLING_FLAG_VECTOR_ALU))
         return CASTLING_ERR_INVALID_ARG;
     if (d->io_dtype != CASTLING_F32 && d->io_dtype != CASTLING_BF16 && d->io_dtype != CASTLING_F16)
         return CASTLING_ERR_UNSUPPORTED;
@@ -864,10 +974,8 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->dpad = desc->d <= 16 ? 16 : desc->d <= 32 ? 32 : desc->d <= 64 ? 64 : 128;
     h->state_size = h->dpad * h->dpad + 2 * h->dpad;
 
-    // CASTLING_ATTN_FORCE_GENERIC=1 keeps bf16 / fp16 on the vector-ALU kernels (A/B measurements)
-    const char* force = getenv("CASTLING_ATTN_FORCE_GENERIC");
     const bool allow_mfma = (desc->io_dtype == CASTLING_BF16 || desc->io_dtype == CASTLING_F16) &&
-                            !(force && force[0] == '1');
+                            !(desc->flags & CASTLING_FLAG_VECTOR_ALU);
     h->half16 = desc->io_dtype == CASTLING_F16;
     h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
     // pooled or residual queries: pass 2 on the vector-ALU kernel (pass 1 is the same work)
@@ -897,18 +1005,16 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
             h->pair_reduce = in_skew == 0;
         }
     }
-    // CASTLING_ATTN_NO_FUSED=1 keeps forward() on the two-pass path at small N (A/B measurements)
-    const char* nofuse = getenv("CASTLING_ATTN_NO_FUSED");
-    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs &&
-               !(nofuse && nofuse[0] == '1');
+    const bool separate = (desc->flags & CASTLING_FLAG_SEPARATE_PASSES) != 0;
+    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs && !separate;
+    // the one-launch forward: heads of 64 channels, every token on the grid, enough units to give
+    // each of the eight task queues whole units
+    h->stream = h->mfma_apply && !h->pair && !h->fused && !separate && desc->extra_tokens == 0 &&
+                h->units >= kStreamQueues;
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
     // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
-    int target_blocks = kTargetReduceBlocks;
-    if (const char* tb = getenv("CASTLING_ATTN_REDUCE_BLOCKS")) {  // tuning aid
-        const int v = atoi(tb);
-        if (v > 0) target_blocks = v;
-    }
+    const int target_blocks = kTargetReduceBlocks;
     const int reduce_units = h->pair_reduce ? h->apply_units : h->units;
     int n_split = target_blocks / reduce_units;  // never one block more than fits at once
     const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
@@ -927,6 +1033,9 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     if (e == hipSuccess) e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
     if (e == hipSuccess && h->fused)
         e = do_fused(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    std::vector<uint32_t> s_tasks;
+    uint32_t s_qoff[kStreamQueues + 1] = {};
+    if (e == hipSuccess && h->stream) e = plan_stream(h, s_tasks, s_qoff);
     if (e == hipSuccess) {
         int max_lds = 0;
         e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
@@ -993,8 +1102,17 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
         wfrag_bytes =
             align_up(static_cast<size_t>(desc->heads) * 4 * desc->dw_kernel * 3 * 64 * 8, 256);
     }
-    h->workspace_bytes = partial_bytes + state_bytes + sfrag_bytes + kfrag_bytes + vhalf_bytes +
-                         wfrag_bytes + a_bytes + kbp_bytes + kb_bytes + wflip_bytes + fpart_bytes;
+    size_t partial_bytes_all = partial_bytes, kpair_bytes = 0, tasks_bytes = 0, ctr_bytes = 0;
+    if (h->stream) {
+        partial_bytes_all = std::max(partial_bytes, align_up(sizeof(float) * static_cast<size_t>(h->units) *
+                                                                 h->s_cr * StateLayout<64>::SIZE, 256));
+        kpair_bytes = align_up(sizeof(uint32_t) * static_cast<size_t>(h->units) * 32, 256);
+        tasks_bytes = align_up(sizeof(uint32_t) * (s_tasks.size() + kStreamQueues + 1), 256);
+        ctr_bytes = align_up(sizeof(uint32_t) * stream_counter_words(h->units), 256);
+    }
+    h->workspace_bytes = partial_bytes_all + state_bytes + sfrag_bytes + kfrag_bytes + vhalf_bytes +
+                         2 * wfrag_bytes + a_bytes + kbp_bytes + kb_bytes + wflip_bytes + fpart_bytes +
+                         kpair_bytes + tasks_bytes + ctr_bytes;
     if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->workspace), h->workspace_bytes);
     if (e != hipSuccess) {
         delete h;
@@ -1002,7 +1120,7 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     }
     unsigned char* p = h->workspace;
     h->partial = reinterpret_cast<float*>(p);
-    p += partial_bytes;
+    p += partial_bytes_all;
     h->state = reinterpret_cast<float*>(p);
     p += state_bytes;
     h->sfrag = reinterpret_cast<bf16_t*>(p);
@@ -1013,6 +1131,28 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     p += vhalf_bytes;
     h->wfrag = reinterpret_cast<bf16_t*>(p);
     p += wfrag_bytes;
+    h->wfrag_reg = reinterpret_cast<bf16_t*>(p);
+    p += wfrag_bytes;
+    h->kpair = reinterpret_cast<uint32_t*>(p);
+    p += kpair_bytes;
+    h->s_tasks = reinterpret_cast<uint32_t*>(p);
+    h->s_qoff = h->s_tasks + s_tasks.size();
+    p += tasks_bytes;
+    h->s_counters = reinterpret_cast<uint32_t*>(p);
+    p += ctr_bytes;
+    if (h->stream) {
+        // task lists and zeroed counters, in place before any stream's kernels
+        e = hipMemcpy(h->s_tasks, s_tasks.data(), sizeof(uint32_t) * s_tasks.size(), hipMemcpyHostToDevice);
+        if (e == hipSuccess)
+            e = hipMemcpy(h->s_qoff, s_qoff, sizeof(s_qoff), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipMemset(h->s_counters, 0, ctr_bytes);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) {
+            (void)hipFree(h->workspace);
+            delete h;
+            return hip_fail(e);
+        }
+    }
     h->a_buf = p;
     h->q_up = h->g_up = nullptr;
     if (h->training && h->pool == 2) {
@@ -1067,7 +1207,7 @@ int castling_attn_num_launches(castling_attn_t h)
     if (!h) return 0;
     const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
     const int extra = h->desc.extra_tokens > 0 ? 1 : 0;  // the tokens off the grid: one more launch
-    if (h->fused) return 1;
+    if (h->fused || h->stream) return 1;
     if (!lin) return 1 + extra;
     return ((h->n_split == 1 && !h->pair) || h->sum_in_apply ? 2 : 3) + extra;
 }
@@ -1087,7 +1227,7 @@ int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void
         const int threads = h->apply_heads * 4 * d.dw_kernel * 3 * 64;
         hipLaunchKernelGGL(dwconv_weight_frag_kernel, dim3((threads + 255) / 256), dim3(256), 0,
                            static_cast<hipStream_t>(stream), static_cast<const bf16_t*>(dw_weight),
-                           h->wfrag, h->apply_heads, d.dw_kernel);
+                           h->wfrag_reg, h->apply_heads, d.dw_kernel);
         HIP_TRY(hipGetLastError());
     }
     h->prepared_w = dw_weight;
@@ -1104,9 +1244,12 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
     if (st != CASTLING_OK) return st;
     if ((h->desc.branches & CASTLING_BRANCH_LINEAR) && !h->apply_ready)
         return CASTLING_ERR_INVALID_ARG;  // no reduce has left a state to apply
-    // the matrix-core path already holds the registered filters in its operand table
-    HIP_TRY(do_apply(h, true, q, v, (registered && h->mfma_apply) ? nullptr : w, dw_bias, out,
-                     static_cast<hipStream_t>(stream)));
+    // the matrix-core path already holds the registered filters in an operand table of their own
+    h->use_registered = registered && h->mfma_apply;
+    const hipError_t e = do_apply(h, true, q, v, h->use_registered ? nullptr : w, dw_bias, out,
+                                  static_cast<hipStream_t>(stream));
+    h->use_registered = false;
+    HIP_TRY(e);
     return CASTLING_OK;
 }
 
@@ -1180,10 +1323,23 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
     int st = check_apply_args(h, q, v, dw_weight, out);
     if (st != CASTLING_OK) return st;
     const castling_attn_desc_t& d = h->desc;
+    const size_t es = dtype_size(d.io_dtype);
+    if ((d.branches & CASTLING_BRANCH_DWCONV) &&
+        (overlaps(out, h->out_span, dw_weight, static_cast<size_t>(d.heads) * d.d * d.dw_kernel * d.dw_kernel * es) ||
+         (dw_bias && overlaps(out, h->out_span, dw_bias, static_cast<size_t>(d.heads) * d.d * es))))
+        return CASTLING_ERR_ALIAS;
     if (d.branches & CASTLING_BRANCH_LINEAR) {
         if (!k || !v || misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
         if (overlaps(out, h->out_span, k, h->in_span) || overlaps(out, h->out_span, v, h->in_span))
             return CASTLING_ERR_ALIAS;
+    }
+    if (h->stream) {
+        // filters registered by prepare_weights and passed again: their operand table is ready
+        const bool reg = (d.branches & CASTLING_BRANCH_DWCONV) && dw_weight == h->prepared_w;
+        HIP_TRY(do_stream(h, q, k, v, reg ? nullptr : dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
+        return CASTLING_OK;
+    }
+    if (d.branches & CASTLING_BRANCH_LINEAR) {
         if (h->fused) {
             HIP_TRY(do_fused(h, true, q, k, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
             return CASTLING_OK;
