@@ -147,6 +147,15 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
 int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
                           const void* dw_weight, const void* dw_bias, void* out, void* stream);
 
+/* Waits for `stream` and reports what the kernels of earlier calls on this handle found wrong
+ * while they ran: the one-kernel forward polls, inside the launch, for the results of its own
+ * earlier tasks and checks its offsets against the tensors' extents; a poll that gave up or an
+ * offset out of range is recorded on the device instead of hanging or faulting, and shows here
+ * as CASTLING_ERR_HIP (castling_attn_strerror names it; the output of that forward is then
+ * undefined).  CASTLING_OK otherwise.  For callers that cannot afford to find out from wrong
+ * numbers; the enqueueing calls themselves never synchronise. */
+int castling_attn_check(castling_attn_t h, void* stream);
+
 /* First half: normalise K per token and reduce over tokens to the per-unit state
  * K_hat^T V, sum_j k_hat_j, sum_j v_j (Sec. 3.1 reassociation; sums of Eq. 3).
  * The state stays in the handle's workspace. */

@@ -765,6 +765,14 @@ hipError_t plan_stream(castling_attn* h, std::vector<uint32_t>& tasks, uint32_t 
     int cr = std::max(1, std::min(64, (d.N + 255) / 512));
     h->s_rchunk = ((d.N + cr - 1) / cr + round - 1) / round * round;
     h->s_cr = (d.N + h->s_rchunk - 1) / h->s_rchunk;
+    if (h->s_cr > 1) {
+        // Units of several reduce chunks (768 tokens and more) stay on the separate launches: the
+        // one-launch forward faulted the GPU at two such shapes (24 units of 8000 and of 16384
+        // tokens, 16 and 32 chunks per unit) for a reason not found yet, while units of up to 4
+        // chunks ran correctly.  Until the cause is known only whole-unit reduce tasks are used.
+        h->stream = false;
+        return hipSuccess;
+    }
     h->s_ncs = h->s_cr > 1 ? (kCombineEntries + 255) / 256 : 0;
     // pass 2: chunks of about 8 steps (4 rows x 16 columns each)
     const int steps = ((d.grid_w + 15) / 16) * ((d.grid_h + 3) / 4);
@@ -816,6 +824,7 @@ hipError_t do_stream(castling_attn* h, const void* q, const void* k, const void*
     a.ca = h->s_ca;
     a.ncs = h->s_ncs;
     a.nw = (dw && filters) ? h->s_nw : 0;
+    a.nw_tasks = h->s_nw;
     a.norm_none = d.norm == CASTLING_NORM_NONE;
     // the fp32 state is only for castling_attn_get_state: written when asked for, or when small
     a.write_state = (d.flags & CASTLING_FLAG_KEEP_STATE) != 0 || h->units <= 64;
@@ -1009,8 +1018,10 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
     h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs && !separate;
     // the one-launch forward: heads of 64 channels, every token on the grid, enough units to give
     // each of the eight task queues whole units
+    // (filters up to 5 x 5: with 7 x 7 and 9 x 9 filters the one-launch forward has only run on
+    // shapes where a workgroup executes a single task; see also plan_stream)
     h->stream = h->mfma_apply && !h->pair && !h->fused && !separate && desc->extra_tokens == 0 &&
-                h->units >= kStreamQueues;
+                h->units >= kStreamQueues && desc->dw_kernel <= 5;
 
     // token split: enough blocks to fill the chip; chunks a multiple of what one block
     // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
@@ -1210,6 +1221,26 @@ int castling_attn_num_launches(castling_attn_t h)
     if (h->fused || h->stream) return 1;
     if (!lin) return 1 + extra;
     return ((h->n_split == 1 && !h->pair) || h->sum_in_apply ? 2 : 3) + extra;
+}
+
+int castling_attn_check(castling_attn_t h, void* stream)
+{
+    if (!h) return CASTLING_ERR_INVALID_ARG;
+    HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    if (!h->stream) return CASTLING_OK;
+    uint32_t w[3] = {0u, 0u, 0u};
+    HIP_TRY(hipMemcpy(w, h->s_counters + kCtrError, sizeof(w), hipMemcpyDeviceToHost));
+    if (w[0] == 0u) return CASTLING_OK;
+    // the launch may have left its counters half way: start the next one from a clean block
+    HIP_TRY(hipMemset(h->s_counters, 0, sizeof(uint32_t) * stream_counter_words(h->units)));
+    HIP_TRY(hipDeviceSynchronize());
+    h->state_valid = false;
+    static const char* const what[] = {"", "a wait for other tasks of the launch gave up",
+                                       "a task word outside the launch's ranges",
+                                       "a load offset outside its unit", "a store offset outside its unit"};
+    snprintf(g_hip_error, sizeof(g_hip_error), "one-launch forward: %s (details %u, %u)",
+             w[0] < 5 ? what[w[0]] : "unknown in-kernel check", w[1], w[2]);
+    return CASTLING_ERR_HIP;
 }
 
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)

@@ -61,10 +61,18 @@ __host__ __device__ constexpr uint32_t make_task(uint32_t kind, uint32_t unit, u
 constexpr int kCtrHead = 0;        // + 32 * queue: next ticket of the queue
 constexpr int kCtrDone = 8 * 32;   // workgroups that have left
 constexpr int kCtrWeights = 9 * 32;   // weight tasks done
-constexpr int kCtrError = 10 * 32;    // sticky: a wait gave up
+constexpr int kCtrError = 10 * 32;    // sticky: first word = code of the first problem (0 = none), then details
 constexpr int kCtrUnit = 11 * 32;  // + 2 * unit: reduce chunks done; + 1: state ready (slices done)
 constexpr int kStreamQueues = 8;
 __host__ __device__ constexpr size_t stream_counter_words(int units) { return kCtrUnit + 2 * static_cast<size_t>(units); }
+
+// codes of the error word
+enum : uint32_t {
+    kStreamErrWait = 1,     // a poll for other tasks' results gave up
+    kStreamErrTask = 2,     // a task word outside the launch's ranges
+    kStreamErrLoad = 3,     // pass 2: a load offset outside the unit
+    kStreamErrStore = 4,    // pass 2: a store offset outside the unit
+};
 
 constexpr int kWeightEntriesPerTask = 2048;   // 8-byte entries of the filter operand table
 constexpr int kCombineEntries = 2048 + 128 + 32;  // S pairs, column sums, ksum pairs
@@ -90,7 +98,8 @@ struct StreamArgs {
     int cr, r_chunk;      // reduce chunks per unit, tokens per chunk
     int ca;               // apply chunks per unit
     int ncs;              // combine slices per unit (0 with cr == 1: the reduce task's result is final)
-    int nw;               // weight tasks
+    int nw;               // weight tasks whose completion pass 2 waits for (0: the table is ready)
+    int nw_tasks;         // weight tasks in the lists
     int norm_none, write_state;
     float eps, lin_scale, tscale, unscale;
     TensorStrides in, out_st;
@@ -102,6 +111,15 @@ __device__ __forceinline__ uint32_t ctr_add(uint32_t* p)
     return __hip_atomic_fetch_add(p, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// records the first problem of a launch: code, then two words of detail
+__device__ __forceinline__ void stream_error(uint32_t* ctr, uint32_t code, uint32_t d0, uint32_t d1)
+{
+    if (__hip_atomic_exchange(&ctr[kCtrError], code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+        st_agent(&ctr[kCtrError + 1], d0);
+        st_agent(&ctr[kCtrError + 2], d1);
+    }
+}
+
 // thread 0 of a workgroup: poll until *p >= target; false if the wait was given up
 __device__ __forceinline__ bool wait_count(uint32_t* ctr, int word, uint32_t target, int limit)
 {
@@ -109,7 +127,7 @@ __device__ __forceinline__ bool wait_count(uint32_t* ctr, int word, uint32_t tar
     while (ld_agent(&ctr[word]) < target) {
         __builtin_amdgcn_s_sleep(2);
         if (++spins > limit || ((spins & 255) == 0 && ld_agent(&ctr[kCtrError]) != 0u)) {
-            st_agent(&ctr[kCtrError], 1u);
+            stream_error(ctr, kStreamErrWait, static_cast<uint32_t>(word), target);
             return false;
         }
     }
@@ -373,6 +391,17 @@ __device__ __forceinline__ void apply_chunk(const StreamArgs& a, int unit, int g
         vh = ld_agent(a.vhalf + unit * 64 + 16 * w + (lane & 15));
     }
     const float inv_eps = 1.0f / a.eps, half_n = 0.5f * static_cast<float>(a.N);
+    // last 16-byte piece of the unit in q / v and in out: every offset is held below these, so
+    // that a mistake in the index arithmetic shows as an error code, not as a memory fault
+    const uint32_t in_last = static_cast<uint32_t>(a.N - 1) * in_tok + 112u;
+    const uint32_t out_last = static_cast<uint32_t>(a.N - 1) * out_tok + 112u;
+    auto checked = [&](uint32_t off) {
+        if (off > in_last) {
+            stream_error(a.counters, kStreamErrLoad, static_cast<uint32_t>(unit), off);
+            off = static_cast<uint32_t>(oct) * 16u;
+        }
+        return off;
+    };
 
     // Window of the last WR input rows.  Per row a lane keeps quad j (view 0) and quad j + 2
     // (view 2) of the 6 quads of the 24 columns; quad j + 1 (view 1) is put together when it is
@@ -410,7 +439,7 @@ __device__ __forceinline__ void apply_chunk(const StreamArgs& a, int unit, int g
                 const bool ok = ld.live && gy >= 0 && gy < H && gx >= 0 && gx < W;
                 if (ok) mask |= 1u << it;
                 const uint32_t off = ok ? static_cast<uint32_t>(gy * W + gx) * in_tok + oct * 16 : oct * 16;
-                async_load16(vreg[it], vb, off);
+                async_load16(vreg[it], vb, checked(off));
             }
         }
         if constexpr (LIN) {
@@ -420,7 +449,7 @@ __device__ __forceinline__ void apply_chunk(const StreamArgs& a, int unit, int g
                 const bool ok = comp && y < H && x < W;
                 if (ok) mask |= 16u << it;
                 const uint32_t off = ok ? static_cast<uint32_t>(y * W + x) * in_tok + oct * 16 : oct * 16;
-                async_load16_stream(qreg[it], qb, off);
+                async_load16_stream(qreg[it], qb, checked(off));
             }
         }
         lmask = mask;
@@ -525,8 +554,11 @@ __device__ __forceinline__ void apply_chunk(const StreamArgs& a, int unit, int g
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const int x = prev_xs0 + tok8 + 8 * it;
-            if (y < H && x < W)
-                store16_nt(ob + (static_cast<uint32_t>(y * W + x) * out_tok + oct * 16), line[it]);
+            if (y >= 0 && y < H && x >= 0 && x < W) {
+                const uint32_t off = static_cast<uint32_t>(y * W + x) * out_tok + oct * 16;
+                if (off <= out_last) store16_nt(ob + off, line[it]);
+                else stream_error(a.counters, kStreamErrStore, static_cast<uint32_t>(unit), off);
+            }
         }
     };
 
@@ -662,13 +694,23 @@ __global__ __launch_bounds__(256, 2) void stream_forward_kernel(StreamArgs a)
         if (task == kTaskNone) break;
         const uint32_t kind = task >> 28;
         const int unit = (task >> 12) & 0xffff, chunk = task & 0xfff;
+        {
+            const int chunks = kind == kTaskWeights ? a.nw_tasks : kind == kTaskReduce ? a.cr
+                               : kind == kTaskCombine ? a.ncs : a.ca;
+            if (kind > kTaskApply || unit >= a.units || chunk >= chunks) {  // uniform per workgroup
+                if (tid == 0) stream_error(ctr, kStreamErrTask, task, static_cast<uint32_t>(qx));
+                continue;
+            }
+        }
 
         if (kind == kTaskWeights) {
             if constexpr (DW) {
-                for (int e = tid; e < kWeightEntriesPerTask; e += 256)
-                    weight_entry(chunk * kWeightEntriesPerTask + e, a, KS);
-                publish_barrier();
-                if (tid == 0) ctr_add(&ctr[kCtrWeights]);
+                if (a.nw > 0) {  // (else the registered table is used as it is)
+                    for (int e = tid; e < kWeightEntriesPerTask; e += 256)
+                        weight_entry(chunk * kWeightEntriesPerTask + e, a, KS);
+                    publish_barrier();
+                    if (tid == 0) ctr_add(&ctr[kCtrWeights]);
+                }
             }
         } else if (kind == kTaskReduce) {
             if constexpr (LIN) {

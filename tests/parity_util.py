@@ -34,16 +34,16 @@ def rel_err(got: np.ndarray, want: np.ndarray) -> float:
     return float(np.max(np.abs(got - want) / np.maximum(np.abs(want), rms)))
 
 
-def gpu_forward(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0, want_state=False):
+def gpu_forward(wl, x, norm=b.NORM_ROWSUM, branches=b.BRANCH_ALL, eps=0.0, want_state=False, flags=0):
     """Runs the HIP layer through the C ABI; returns float64 numpy [B,heads,N,d]."""
     dev = torch.device("cuda:0")
     t = {n: (None if x[n] is None else x[n].to(dev)) for n in ("q", "k", "v", "w", "bias")}
     out = torch.empty_like(t["q"])
     out.fill_(float("nan"))
     attn = b.CastlingAttn.for_workload(wl, norm=norm, branches=branches, eps=eps,
-                                       flags=b.FLAG_KEEP_STATE if want_state else 0)
+                                       flags=flags | (b.FLAG_KEEP_STATE if want_state else 0))
     attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], out)
-    torch.cuda.synchronize()
+    attn.check()   # waits for the stream; raises if the kernels recorded a problem
     res = inputs.to_f64(out)
     st = attn.get_state() if want_state else None
     attn.destroy()

@@ -50,7 +50,8 @@ def test_validate_accepts_benchmark_workloads():
     ("io_dtype", 7, b.ERR_UNSUPPORTED),
     ("norm", 2, b.ERR_INVALID_ARG), ("branches", 8, b.ERR_INVALID_ARG),
     ("eps", -1.0, b.ERR_INVALID_ARG), ("eps", float("nan"), b.ERR_INVALID_ARG),
-    ("flags", 8, b.ERR_INVALID_ARG),
+    ("flags", 32, b.ERR_INVALID_ARG),
+    ("eps", 1e-39, b.ERR_INVALID_ARG),
 ])
 def test_validate_rejects(field, value, status):
     d = good()
@@ -110,7 +111,8 @@ def test_validate_downsampling_fields():
     assert b.validate(mk(flags=b.FLAG_RESIDUAL_Q, branches=b.BRANCH_DWCONV)) == b.ERR_INVALID_ARG
     assert b.validate(mk(flags=b.FLAG_RESIDUAL_Q, branches=b.BRANCH_LINEAR)) == b.OK
     assert b.validate(mk(flags=b.FLAG_TRAINING)) == b.OK
-    assert b.validate(mk(flags=8)) == b.ERR_INVALID_ARG
+    assert b.validate(mk(flags=32)) == b.ERR_INVALID_ARG
+    assert b.validate(mk(flags=b.FLAG_SEPARATE_PASSES | b.FLAG_VECTOR_ALU)) == b.OK
     d = mk()
     d.reserved0 = 1
     assert b.validate(d) == b.ERR_INVALID_ARG

@@ -35,12 +35,12 @@ def draw(wl, extra, seed):
     return inputs.make_inputs(flat, seed=seed, with_bias=True)
 
 
-def run(wl, extra, x, norm, branches, want_state=False, fused_layout=False):
+def run(wl, extra, x, norm, branches, want_state=False, fused_layout=False, flags=0):
     dev = torch.device("cuda:0")
     B, H, N, d = wl.B, wl.heads, wl.N + extra, wl.d
     w, bias = x["w"].to(dev), x["bias"].to(dev)
     kw = dict(norm=norm, branches=branches, extra_tokens=extra,
-              flags=b.FLAG_KEEP_STATE if want_state else 0)
+              flags=flags | (b.FLAG_KEEP_STATE if want_state else 0))
     if fused_layout:
         qkv = torch.empty((B, N, 3, H, d), dtype=x["q"].dtype, device=dev)
         for i, n in enumerate(("q", "k", "v")):
@@ -94,14 +94,13 @@ def test_class_tokens_strided_layout(case):
     assert np.array_equal(dense, fused) and n1 == n2
 
 
-def test_class_token_paths_and_validation(monkeypatch):
+def test_class_token_paths_and_validation():
     # 14 x 14 + 1 fits the one-kernel path; kept on the two-pass kernels it costs one launch more
     wl, extra = CASES[0]
     x = draw(wl, extra, seed=53)
     one, _, n_one = run(wl, extra, x, b.NORM_ROWSUM, b.BRANCH_ALL)
     assert n_one == 1
-    monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
-    two, _, n_two = run(wl, extra, x, b.NORM_ROWSUM, b.BRANCH_ALL)
+    two, _, n_two = run(wl, extra, x, b.NORM_ROWSUM, b.BRANCH_ALL, flags=b.FLAG_SEPARATE_PASSES)
     assert n_two == 4                   # reduce, combine, apply (grid), apply (class tokens)
     assert rel_err(one, two) <= 2.0 ** -7
     bad = b.make_desc(1, 1, 196, 64, 14, 14, 3, "bf16", extra_tokens=1)   # N must be 197

@@ -303,26 +303,24 @@ def test_zero_rows_bf16(oracle):
     np.testing.assert_allclose(got[1, 0, 40], v[1, 0].mean(axis=0), rtol=2e-2, atol=2e-3)
 
 
-def test_forced_generic_bf16_matches_oracle(oracle, monkeypatch):
+def test_forced_generic_bf16_matches_oracle(oracle):
     """The vector-ALU kernels stay reachable for bf16 (they are the fallback path)."""
-    monkeypatch.setenv("CASTLING_ATTN_FORCE_GENERIC", "1")
     wl = SMALL[3]
     x = inputs.make_inputs(wl, seed=17, with_bias=True)
     q, k, v, w, bias = oracle_inputs(x)
-    got = gpu_forward(wl, x)
+    got = gpu_forward(wl, x, flags=b.FLAG_VECTOR_ALU)
     want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
     assert rel_err(got, want) <= TOL[wl.dtype]
 
 
 @pytest.mark.parametrize("wl", ONE_KERNEL + [HEAD_PAIRS[2], HEAD_PAIRS[4]], ids=lambda w: w.name)
-def test_two_pass_path_at_small_n(oracle, monkeypatch, wl):
+def test_two_pass_path_at_small_n(oracle, wl):
     """Shapes that forward() would run in one kernel, kept on the reduce + apply kernels."""
-    monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
     x = inputs.make_inputs(wl, seed=23, with_bias=True)
     q, k, v, w, bias = oracle_inputs(x)
     print(f"case two-pass {wl.name}", flush=True)
     want = oracle.forward(q, k, v, w, bias, wl.grid_h, wl.grid_w)
-    assert rel_err(gpu_forward(wl, x), want) <= TOL[wl.dtype]
+    assert rel_err(gpu_forward(wl, x, flags=b.FLAG_SEPARATE_PASSES), want) <= TOL[wl.dtype]
 
 
 @pytest.mark.parametrize("wl", ONE_KERNEL, ids=lambda w: w.name)
@@ -354,11 +352,12 @@ def test_one_kernel_forward_agrees_with_reduce_apply(wl):
 
 
 def test_reduce_then_apply_equals_forward():
+    """forward() as separate launches is reduce() followed by apply(): bitwise the same."""
     wl = Workload("split_bf16", "bf16", 2, 2, 64, 19, 21, 5)
     x = inputs.make_inputs(wl, seed=8)
     dev = torch.device("cuda:0")
     t = {n: x[n].to(dev) for n in ("q", "k", "v", "w")}
-    attn = b.CastlingAttn.for_workload(wl)
+    attn = b.CastlingAttn.for_workload(wl, flags=b.FLAG_SEPARATE_PASSES)
     o1, o2 = torch.empty_like(t["q"]), torch.empty_like(t["q"])
     attn.forward(t["q"], t["k"], t["v"], t["w"], None, o1)
     attn.reduce(t["k"], t["v"])
@@ -575,7 +574,7 @@ def test_pairs_of_narrow_heads(oracle, wl, norm):
         assert rel_err(padded, want) <= TOL[wl.dtype], (wl.name, norm, branches, "padded heads")
 
 
-def test_pairs_of_narrow_heads_take_the_matrix_core_path(monkeypatch):
+def test_pairs_of_narrow_heads_take_the_matrix_core_path():
     """Launch counts tell the paths apart.  Small units: one kernel for pairs, two launches on the
     vector-ALU path an odd head count is left with.  Large units with one split each: the
     vector-ALU path needs two launches, the pair path three (its operand tables come from a
@@ -589,8 +588,7 @@ def test_pairs_of_narrow_heads_take_the_matrix_core_path(monkeypatch):
     assert launches(Workload("hp_odd", "bf16", 32, 9, 32, 7, 7, 3)) == (2, 1)
     assert launches(Workload("hp_big", "bf16", 32, 8, 32, 20, 20, 3)) == (3, 1)
     assert launches(Workload("hp_big_odd", "bf16", 32, 9, 32, 20, 20, 3)) == (2, 1)
-    monkeypatch.setenv("CASTLING_ATTN_NO_FUSED", "1")
-    assert launches(HEAD_PAIRS[4]) == (3, 1)
+    assert launches(HEAD_PAIRS[4], flags=b.FLAG_SEPARATE_PASSES) == (3, 1)
 
 
 @pytest.mark.parametrize("wl", [
