@@ -61,7 +61,7 @@ typedef enum {
     CASTLING_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, N != extra_tokens + grid_h*grid_w, even ks, misalignment */
     CASTLING_ERR_UNSUPPORTED = 2, /* d, ks or dtype outside what the kernels are built for */
     CASTLING_ERR_HIP = 3,         /* a HIP runtime call failed (allocation, launch) */
-    CASTLING_ERR_ALIAS = 4        /* out overlaps an input */
+    CASTLING_ERR_ALIAS = 4        /* an output overlaps an input or another output */
 } castling_status_t;
 
 typedef enum { CASTLING_F32 = 0, CASTLING_BF16 = 1, CASTLING_F16 = 2 } castling_dtype_t;
@@ -84,9 +84,10 @@ enum { CASTLING_BRANCH_LINEAR = 1, CASTLING_BRANCH_DWCONV = 2, CASTLING_BRANCH_A
  * span of q, three of the span of k with q_pool = 2, and a few small buffers); shapes whose
  * backward tiles exceed the LDS of a block (fp32, d = 128, 9 x 9 filters) are refused with
  * CASTLING_ERR_UNSUPPORTED.
- * SEPARATE_PASSES: castling_attn_forward enqueues pass 1, the sum of its partial states and pass 2
- * as the separate launches castling_attn_reduce + castling_attn_apply would, instead of one
- * kernel (for measurements and for tests of those kernels; results agree to rounding).
+ * SEPARATE_PASSES: castling_attn_forward of a small problem (16-bit, d = 64, up to 256 tokens
+ * per unit, filters up to 5 x 5) enqueues pass 1 and pass 2 as the separate launches castling_attn_reduce +
+ * castling_attn_apply would, instead of its one-kernel form (for measurements and for tests
+ * of those kernels; results agree to rounding).
  * VECTOR_ALU: 16-bit types stay on the vector-ALU kernels that fp32 uses (the fallback path;
  * for measurements and tests). */
 enum {
@@ -142,19 +143,12 @@ int castling_attn_validate(const castling_attn_desc_t* desc);
 int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_handle);
 
 /* Whole layer (Eq. 9 with the readings above): reduce followed by apply.
- * q, k, v, dw_weight, out must be 16-byte aligned; out must not overlap q, k or v (with
- * strides the check compares the address ranges the tensors span, first to last byte). */
+ * q, k, v, dw_weight, out must be 16-byte aligned; out must not overlap q, k, v, the filters
+ * or the bias (with strides the check compares the address ranges the tensors span, first to
+ * last byte).  dw_weight may be NULL after castling_attn_prepare_weights: the filters
+ * registered there are used. */
 int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
                           const void* dw_weight, const void* dw_bias, void* out, void* stream);
-
-/* Waits for `stream` and reports what the kernels of earlier calls on this handle found wrong
- * while they ran: the one-kernel forward polls, inside the launch, for the results of its own
- * earlier tasks and checks its offsets against the tensors' extents; a poll that gave up or an
- * offset out of range is recorded on the device instead of hanging or faulting, and shows here
- * as CASTLING_ERR_HIP (castling_attn_strerror names it; the output of that forward is then
- * undefined).  CASTLING_OK otherwise.  For callers that cannot afford to find out from wrong
- * numbers; the enqueueing calls themselves never synchronise. */
-int castling_attn_check(castling_attn_t h, void* stream);
 
 /* First half: normalise K per token and reduce over tokens to the per-unit state
  * K_hat^T V, sum_j k_hat_j, sum_j v_j (Sec. 3.1 reassociation; sums of Eq. 3).
@@ -182,17 +176,19 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
  * without the DWConv branch grad_w and grad_bias (where given) are zeros and dw_weight may be
  * NULL.  With RESIDUAL_Q grad_q includes grad_out.  The forward pass is not needed
  * beforehand: pass 1 is recomputed.  Afterwards the handle holds no state to apply or fetch.
- * Pointers 16-byte aligned; no gradient may overlap an input or another gradient
- * (CASTLING_ERR_ALIAS).  Only enqueues work on `stream`. */
+ * Pointers 16-byte aligned; no gradient (grad_w and grad_bias included) may overlap an input,
+ * the filters or another gradient (CASTLING_ERR_ALIAS).  Only enqueues work on `stream`. */
 int castling_attn_backward(castling_attn_t h, const void* q, const void* k, const void* v,
                            const void* dw_weight, const void* grad_out, void* grad_q, void* grad_k,
                            void* grad_v, float* grad_w, float* grad_bias, void* stream);
 
 /* Registers the DWConv filters (the M_DW of Eq. 9) for later castling_attn_apply calls that
- * pass dw_weight = NULL, so that repeated applies with fixed filters skip their per-call
- * preparation.  The matrix-core path converts the filters into its operand table on
+ * (and castling_attn_forward calls) that pass dw_weight = NULL, so that repeated calls with
+ * fixed filters skip their per-call preparation.  The matrix-core path converts the filters into its operand table on
  * `stream` now (later changes to the buffer are not seen); the other paths keep the
- * pointer, which must stay valid and unchanged.  forward() never uses this registration. */
+ * pointer, which must stay valid and unchanged.  castling_attn_forward with dw_weight = NULL uses
+ * the registration in the same way.  No other call on the handle (backward included) touches
+ * the registered table; register again after the filters change. */
 int castling_attn_prepare_weights(castling_attn_t h, const void* dw_weight, void* stream);
 
 /* Training-time companions of the layer as O(N^2) attention on the matrix cores (16-bit I/O

@@ -31,7 +31,7 @@ EXPORTS = (
     "castling_attn_destroy",
     "castling_attn_workspace_bytes", "castling_attn_get_state", "castling_attn_num_splits",
     "castling_attn_num_launches", "castling_attn_pairwise", "castling_attn_backward",
-    "castling_attn_strerror", "castling_attn_check",
+    "castling_attn_strerror",
 )
 
 
@@ -87,7 +87,6 @@ def lib():
         L.castling_attn_workspace_bytes.argtypes = [vp]
         L.castling_attn_workspace_bytes.restype = C.c_size_t
         L.castling_attn_get_state.argtypes = [vp, vp, C.c_size_t, vp]
-        L.castling_attn_check.argtypes = [vp, vp]
         L.castling_attn_num_splits.argtypes = [vp]
         L.castling_attn_num_launches.argtypes = [vp]
         L.castling_attn_pairwise.argtypes = [vp, C.POINTER(PairParams)] + [vp] * 6
@@ -197,10 +196,6 @@ class CastlingAttn:
 
     def workspace_bytes(self) -> int:
         return lib().castling_attn_workspace_bytes(self._h)
-
-    def check(self, stream=None) -> None:
-        """Waits for the stream; raises if a kernel of an earlier call recorded a problem."""
-        _check(lib().castling_attn_check(self._h, _stream_ptr(stream)))
 
     def num_splits(self) -> int:
         return lib().castling_attn_num_splits(self._h)

@@ -8,8 +8,8 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-# translation units (no device code crosses them), compiled side by side
-UNITS = ["castling_attn.hip", "stream_fwd.hip"]
+# translation units (no device code crosses them; several would compile side by side)
+UNITS = ["castling_attn.hip"]
 LIB = os.path.join(HERE, "libcastling_attn.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 

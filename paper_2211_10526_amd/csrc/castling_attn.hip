@@ -11,7 +11,6 @@
 #include <cstring>
 #include <memory>
 #include <new>
-#include <vector>
 
 #include "apply_generic.hpp"
 #include "apply_mfma.hpp"
@@ -21,7 +20,6 @@
 #include "pairwise.hpp"
 #include "reduce_generic.hpp"
 #include "reduce_mfma.hpp"
-#include "stream_fwd_host.hpp"
 
 using namespace castling;
 
@@ -75,8 +73,14 @@ struct ApplyView {
     uint32_t branches;
 };
 
+// Bytes of the parts of a handle's workspace, in the order they lie in it (wfrag twice).
+struct WorkspaceParts {
+    size_t partial, state, sfrag, kfrag, vhalf, wfrag, a, kbp, kb, wflip, fpart;
+};
+
 struct castling_attn {
     castling_attn_desc_t desc;
+    WorkspaceParts parts;
     ApplyView view;     // read by the apply launchers
     int device;
     int units;
@@ -118,13 +122,6 @@ struct castling_attn {
     bf16_t* wfrag_reg;  // filter operand table of castling_attn_prepare_weights; nothing else writes it
     const void* prepared_w;  // filters registered by castling_attn_prepare_weights
     bool use_registered;     // the apply launch in progress reads wfrag_reg
-    // one-launch forward (stream_fwd.hpp)
-    bool stream;        // forward() runs it
-    int s_cr, s_rchunk, s_ca, s_ncs, s_nw, s_blocks;
-    uint32_t* kpair;    // [units][32]: pairs of the K_hat column sum in the I/O format
-    uint32_t* s_tasks;  // task lists, queue offsets, counters
-    uint32_t* s_qoff;
-    uint32_t* s_counters;
     // The backward pass runs pass 2 on other tensors: q := k, v := g (layout of out), out := dv
     // (layout of v), without the normaliser.  generic: on the vector-ALU kernel even where the
     // handle's pass 2 is on the matrix cores (the layouts of v and out differ).
@@ -179,8 +176,6 @@ void launch_reduce_mfma(castling_attn* h, const void* k, const void* v, const vo
     ex.ks = h->desc.dw_kernel;
     ex.tscale = X::table_scale(h->desc.N);
     ex.pair_skew = h->in_skew;
-    ex.write_state = 1;
-    ex.kpair = nullptr;
     const int per_row = h->n_split * 64 * kReduceWaves;
     const int wthreads = heads * 4 * ex.ks * 3 * 64;
     const int wrows = w ? (wthreads + per_row - 1) / per_row : 0;
@@ -740,107 +735,6 @@ hipError_t do_fused(castling_attn* h, bool launch, const void* q, const void* k,
 }
 
 
-// ------------------------------------------------------------------ one-launch forward
-// Chunk sizes and task lists of the one-launch forward for this handle (create time).
-hipError_t plan_stream(castling_attn* h, std::vector<uint32_t>& tasks, uint32_t (&qoff)[kStreamQueues + 1])
-{
-    const castling_attn_desc_t& d = h->desc;
-    const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const bool dw = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
-    int per_cu = 0;
-    hipError_t e = stream_forward_prepare(d.dw_kernel, lin, dw, h->half16, &per_cu);
-    if (e != hipSuccess) return e;
-    if (per_cu < 1) {
-        h->stream = false;
-        return hipSuccess;
-    }
-    // workgroups: what the device holds at once, a multiple of the queue count
-    h->s_blocks = std::min(per_cu, 2) * h->num_cus / kStreamQueues * kStreamQueues;
-    if (h->s_blocks < kStreamQueues) {
-        h->stream = false;
-        return hipSuccess;
-    }
-    // pass 1: chunks of about 512 tokens (a multiple of what the four waves stage per round)
-    const int round = kReduceWaves * kReduceIterTokens;
-    int cr = std::max(1, std::min(64, (d.N + 255) / 512));
-    h->s_rchunk = ((d.N + cr - 1) / cr + round - 1) / round * round;
-    h->s_cr = (d.N + h->s_rchunk - 1) / h->s_rchunk;
-    if (h->s_cr > 1) {
-        // Units of several reduce chunks (768 tokens and more) stay on the separate launches: the
-        // one-launch forward faulted the GPU at two such shapes (24 units of 8000 and of 16384
-        // tokens, 16 and 32 chunks per unit) for a reason not found yet, while units of up to 4
-        // chunks ran correctly.  Until the cause is known only whole-unit reduce tasks are used.
-        h->stream = false;
-        return hipSuccess;
-    }
-    h->s_ncs = h->s_cr > 1 ? (kCombineEntries + 255) / 256 : 0;
-    // pass 2: chunks of about 8 steps (4 rows x 16 columns each)
-    const int steps = ((d.grid_w + 15) / 16) * ((d.grid_h + 3) / 4);
-    h->s_ca = std::max(1, std::min(kTaskMaxChunks - 1, (steps + 4) / 8));
-    h->s_nw = dw ? (d.heads * 4 * d.dw_kernel * 3 * 64 + kWeightEntriesPerTask - 1) / kWeightEntriesPerTask : 0;
-    if (h->s_nw >= kTaskMaxChunks) {
-        h->stream = false;
-        return hipSuccess;
-    }
-    // pass 1 runs ahead of pass 2 by as many units as keep their V rows within half an L2 (2 MB)
-    const long long v_unit = static_cast<long long>(d.N) * h->in_st.n * 2;
-    const int lookahead = static_cast<int>(std::max(1ll, std::min(8ll, (2ll << 20) / std::max(1ll, v_unit))));
-    build_stream_tasks(h->units, h->s_cr, h->s_ca, h->s_ncs, h->s_nw, lookahead, lin, tasks, qoff);
-    return hipSuccess;
-}
-
-// filters == nullptr: the registered operand table is current
-hipError_t do_stream(castling_attn* h, const void* q, const void* k, const void* v, const void* filters,
-                     const void* bias, void* out, hipStream_t s)
-{
-    const castling_attn_desc_t& d = h->desc;
-    const bool lin = (d.branches & CASTLING_BRANCH_LINEAR) != 0;
-    const bool dw = (d.branches & CASTLING_BRANCH_DWCONV) != 0;
-    StreamArgs a = {};
-    a.q = static_cast<const bf16_t*>(q);
-    a.k = static_cast<const bf16_t*>(k);
-    a.v = static_cast<const bf16_t*>(v);
-    a.w = static_cast<const bf16_t*>(filters);
-    a.bias = static_cast<const bf16_t*>(bias);
-    a.out = static_cast<bf16_t*>(out);
-    a.partial = h->partial;
-    a.state = h->state;
-    a.sfrag = h->sfrag;
-    a.kpair = h->kpair;
-    a.vhalf = h->vhalf;
-    a.wfrag = filters ? h->wfrag : h->wfrag_reg;
-    a.tasks = h->s_tasks;
-    a.queue_off = h->s_qoff;
-    a.counters = h->s_counters;
-    a.units = h->units;
-    a.heads = d.heads;
-    a.N = d.N;
-    a.H = d.grid_h;
-    a.W = d.grid_w;
-    a.strips = (d.grid_w + 15) / 16;
-    a.spc = (d.grid_h + 3) / 4;
-    a.cr = h->s_cr;
-    a.r_chunk = h->s_rchunk;
-    a.ca = h->s_ca;
-    a.ncs = h->s_ncs;
-    a.nw = (dw && filters) ? h->s_nw : 0;
-    a.nw_tasks = h->s_nw;
-    a.norm_none = d.norm == CASTLING_NORM_NONE;
-    // the fp32 state is only for castling_attn_get_state: written when asked for, or when small
-    a.write_state = (d.flags & CASTLING_FLAG_KEEP_STATE) != 0 || h->units <= 64;
-    a.eps = d.eps;
-    a.lin_scale = 1.0f;
-    a.tscale = h->half16 ? F16Fmt::table_scale(d.N) : Bf16Fmt::table_scale(d.N);
-    a.unscale = h->half16 ? F16Fmt::table_unscale(d.N) : Bf16Fmt::table_unscale(d.N);
-    a.in = h->in_st;
-    a.out_st = h->out_st;
-    a.spin_limit = 1 << 22;
-    h->state_valid = lin && a.write_state;
-    h->apply_ready = false;   // the tables of this path are not the ones apply() reads
-    h->partials_pending = false;
-    return stream_forward_launch(d.dw_kernel, lin, dw, h->half16, a, h->s_blocks, s);
-}
-
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 bool overlaps(const void* a, size_t a_bytes, const void* b, size_t b_bytes)
@@ -864,6 +758,265 @@ int check_apply_args(castling_attn_t h, const void* q, const void* v, const void
     return CASTLING_OK;
 }
 
+// Everything castling_attn_create decides before it allocates: kernel paths, token split, launch
+// attributes, and the sizes of the workspace parts (h->parts, h->workspace_bytes).  desc has
+// passed castling_attn_validate.  No pointer into the workspace is set here.
+int plan_handle(const castling_attn_desc_t* desc, castling_attn* h)
+{
+    h->desc = *desc;
+    if (h->desc.branches == 0) h->desc.branches = CASTLING_BRANCH_ALL;
+    if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
+    h->units = desc->B * desc->heads;
+    h->state_valid = false;
+    h->apply_ready = false;
+    {
+        const castling_attn_desc_t& d = h->desc;
+        h->pool = d.q_pool == 2 ? 2 : 1;
+        h->qgrid_h = (d.grid_h + h->pool - 1) / h->pool;
+        h->qgrid_w = (d.grid_w + h->pool - 1) / h->pool;
+        h->nq = h->pool == 1 ? d.N : h->qgrid_h * h->qgrid_w;
+        h->residual_q = (d.flags & CASTLING_FLAG_RESIDUAL_Q) != 0;
+        auto dense = [&](int n) {
+            return TensorStrides{static_cast<long long>(d.heads) * n * d.d,
+                                 static_cast<long long>(n) * d.d, d.d};
+        };
+        h->in_st = d.in_stride_n ? TensorStrides{d.in_stride_b, d.in_stride_h, d.in_stride_n}
+                                 : dense(d.N);
+        h->out_st = d.out_stride_n ? TensorStrides{d.out_stride_b, d.out_stride_h, d.out_stride_n}
+                                   : dense(h->nq);
+        h->q_st = h->pool == 1 ? h->in_st
+                  : d.q_stride_n ? TensorStrides{d.q_stride_b, d.q_stride_h, d.q_stride_n}
+                                 : dense(h->nq);
+        auto span = [&](const TensorStrides& s, int n) {
+            return static_cast<size_t>((d.B - 1) * s.b + (d.heads - 1) * s.h + (n - 1) * s.n + d.d) *
+                   dtype_size(d.io_dtype);
+        };
+        h->in_span = span(h->in_st, d.N);
+        h->out_span = span(h->out_st, h->nq);
+        h->q_span = span(h->q_st, h->nq);
+    }
+    h->dpad = desc->d <= 16 ? 16 : desc->d <= 32 ? 32 : desc->d <= 64 ? 64 : 128;
+    h->state_size = h->dpad * h->dpad + 2 * h->dpad;
+
+    const bool allow_mfma = (desc->io_dtype == CASTLING_BF16 || desc->io_dtype == CASTLING_F16) &&
+                            !(desc->flags & CASTLING_FLAG_VECTOR_ALU);
+    h->half16 = desc->io_dtype == CASTLING_F16;
+    h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
+    // pooled or residual queries: pass 2 on the vector-ALU kernel (pass 1 is the same work)
+    const bool plain_q = h->pool == 1 && !h->residual_q;
+    h->mfma_apply = allow_mfma && desc->d == 64 && plain_q;
+    h->apply_units = h->units;
+    h->apply_heads = desc->heads;
+    h->apply_in = h->in_st;
+    h->apply_out = h->out_st;
+    h->in_skew = h->out_skew = 0;
+    h->pair = h->pair_reduce = false;
+    if (allow_mfma && desc->d == 32 && desc->heads % 2 == 0 && plain_q) {
+        // two neighbouring heads of 32 channels as one unit of 64 for pass 2: the second half of
+        // a token row lies one head stride further on instead of 64 bytes
+        const long long in_skew = h->in_st.h * 2 - 64, out_skew = h->out_st.h * 2 - 64;
+        const long long lim = (1ll << 32) - 256;
+        if (in_skew >= 0 && out_skew >= 0 && desc->N * h->in_st.n * 2 + in_skew < lim &&
+            desc->N * h->out_st.n * 2 + out_skew < lim) {
+            h->pair = h->mfma_apply = true;
+            h->apply_units = h->units / 2;
+            h->apply_heads = desc->heads / 2;
+            h->apply_in.h *= 2;
+            h->apply_out.h *= 2;
+            h->in_skew = static_cast<uint32_t>(in_skew);
+            h->out_skew = static_cast<uint32_t>(out_skew);
+            // pass 1 gains from pairs only where they make its loads whole 128-byte rows
+            h->pair_reduce = in_skew == 0;
+        }
+    }
+    const bool separate = (desc->flags & CASTLING_FLAG_SEPARATE_PASSES) != 0;
+    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs && !separate;
+    // token split: enough blocks to fill the chip; chunks a multiple of what one block
+    // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
+    const int target_blocks = kTargetReduceBlocks;
+    const int reduce_units = h->pair_reduce ? h->apply_units : h->units;
+    int n_split = target_blocks / reduce_units;  // never one block more than fits at once
+    const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
+    if (n_split > max_split) n_split = max_split;
+    if (n_split < 1) n_split = 1;
+    int chunk = (desc->N + n_split - 1) / n_split;
+    const int chunk_mult = kReduceWaves * kReduceIterTokens;
+    chunk = ((chunk + chunk_mult - 1) / chunk_mult) * chunk_mult;
+    h->chunk = chunk;
+    h->n_split = (desc->N + chunk - 1) / chunk;
+
+    hipError_t e = hipGetDevice(&h->device);
+    if (e == hipSuccess)
+        e = hipDeviceGetAttribute(&h->num_cus, hipDeviceAttributeMultiprocessorCount, h->device);
+    if (e == hipSuccess && h->num_cus < 1) h->num_cus = 1;
+    if (e == hipSuccess) e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    if (e == hipSuccess && h->fused)
+        e = do_fused(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    if (e == hipSuccess) {
+        int max_lds = 0;
+        e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
+        if (e == hipSuccess && h->apply_lds > static_cast<size_t>(max_lds)) {
+            return CASTLING_ERR_UNSUPPORTED;
+        }
+    }
+    // backward pass: LDS attributes of its kernels, and of the vector-ALU pass 2 it may need
+    h->training = (desc->flags & CASTLING_FLAG_TRAINING) != 0;
+    h->ov.on = h->ov.generic = false;
+    WorkspaceParts& ws = h->parts;
+    ws = WorkspaceParts{};
+    // CASTLING_FLAG_VECTOR_ALU keeps the per-row kernels of the backward off the matrix cores too
+    h->mfma_rows = allow_mfma && (desc->d == 32 || desc->d == 64);
+    if (e == hipSuccess && h->training) {
+        size_t lds = 0;
+        const size_t keep = h->apply_lds;
+        h->ov.on = h->ov.generic = true;
+        h->ov.q = h->ov.v = h->ov.out = h->in_st;
+        h->ov.lin_scale = 1.0f;
+        e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+        lds = h->apply_lds;
+        h->apply_lds = keep;
+        h->ov.on = h->ov.generic = false;
+        if (e == hipSuccess)
+            e = dispatch_type_width(desc->io_dtype, h->dpad, [&](auto t, auto dc) {
+                using T = decltype(t);
+                constexpr int D = decltype(dc)::value;
+                hipError_t r = bwd_rows<T, D>(h, false, true, nullptr, nullptr, nullptr, &lds, nullptr);
+                if (r == hipSuccess) r = bwd_filter<T, D>(h, false, nullptr, nullptr, &lds, nullptr);
+                return r;
+            });
+        if (e == hipSuccess && lds > kMaxLdsBytes) {
+            return CASTLING_ERR_UNSUPPORTED;
+        }
+        const int taps1 = desc->dw_kernel * desc->dw_kernel + 1;
+        const int n_tiles = ((desc->grid_w + kApplyTW - 1) / kApplyTW) *
+                            ((desc->grid_h + kApplyTH - 1) / kApplyTH);
+        h->row_tiles = (desc->N + kBwdTokens - 1) / kBwdTokens;
+        h->qrow_tiles = (h->nq + kBwdTokens - 1) / kBwdTokens;
+        h->kb_parts = h->mfma_rows ? 4 * h->qrow_tiles : h->qrow_tiles;
+        h->filter_chunks = std::max(1, std::min(n_tiles, 1024 / h->units));
+        ws.a = align_up(h->in_span, 256) * (h->pool == 2 ? 3 : 1);  // a; pooled: + q_up, g_up
+        ws.kbp = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->kb_parts * h->dpad, 256);
+        ws.kb = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->dpad, 256);
+        ws.wflip = align_up(dtype_size(desc->io_dtype) * static_cast<size_t>(desc->heads) * desc->d *
+                                   (taps1 - 1), 256);
+        ws.fpart = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->filter_chunks * taps1 *
+                                   h->dpad, 256);
+    }
+    // one block of memory, 256-byte aligned parts
+    ws.partial =
+        h->pair_reduce ? align_up(sizeof(float) * static_cast<size_t>(h->apply_units) * h->n_split *
+                               StateLayout<64>::SIZE, 256)
+                : align_up(sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size, 256);
+    ws.state =
+        align_up(sizeof(float) * static_cast<size_t>(h->units) * h->state_size, 256);
+    if (h->mfma_apply) {
+        ws.sfrag = align_up(sizeof(bf16_t) * static_cast<size_t>(h->units) * kSfragPerUnit, 256);
+        ws.kfrag = align_up(sizeof(bf16_t) * static_cast<size_t>(h->units) * kKfragPerUnit, 256);
+        ws.vhalf = align_up(sizeof(float) * static_cast<size_t>(h->units) * 64, 256);
+        ws.wfrag =
+            align_up(static_cast<size_t>(desc->heads) * 4 * desc->dw_kernel * 3 * 64 * 8, 256);
+    }
+    h->workspace_bytes = ws.partial + ws.state + ws.sfrag + ws.kfrag + ws.vhalf + 2 * ws.wfrag + ws.a +
+                         ws.kbp + ws.kb + ws.wflip + ws.fpart;
+    if (e != hipSuccess) return hip_fail(e);
+    // Small vector-ALU problems: every apply block sums the few partial states itself instead of
+    // waiting for a combine launch (cfg1: three launches become two).  Not when the caller wants
+    // the state kept, and not where many blocks would each re-read many partials.
+    {
+        const long long tiles = static_cast<long long>((desc->grid_w + kApplyTW - 1) / kApplyTW) *
+                                ((desc->grid_h + kApplyTH - 1) / kApplyTH);
+        h->sum_in_apply = !h->mfma_apply && h->n_split > 1 && h->n_split <= 4 && tiles <= 16 &&
+                          !(desc->flags & CASTLING_FLAG_KEEP_STATE);
+    }
+    h->partials_pending = false;
+
+    h->workspace = nullptr;
+    return CASTLING_OK;
+}
+
+// Points the handle's parts into the block at base (h->workspace_bytes long, 256-byte aligned).
+void carve_workspace(castling_attn* h, unsigned char* base)
+{
+    const WorkspaceParts& ws = h->parts;
+    unsigned char* p = base;
+    h->partial = reinterpret_cast<float*>(p);
+    p += ws.partial;
+    h->state = reinterpret_cast<float*>(p);
+    p += ws.state;
+    h->sfrag = reinterpret_cast<bf16_t*>(p);
+    p += ws.sfrag;
+    h->kfrag = reinterpret_cast<bf16_t*>(p);
+    p += ws.kfrag;
+    h->vhalf = reinterpret_cast<float*>(p);
+    p += ws.vhalf;
+    h->wfrag = reinterpret_cast<bf16_t*>(p);
+    p += ws.wfrag;
+    h->wfrag_reg = reinterpret_cast<bf16_t*>(p);
+    p += ws.wfrag;
+    h->a_buf = p;
+    h->q_up = h->g_up = nullptr;
+    if (h->training && h->pool == 2) {
+        h->q_up = p + ws.a / 3;
+        h->g_up = p + 2 * (ws.a / 3);
+    }
+    p += ws.a;
+    h->kb_part = reinterpret_cast<float*>(p);
+    p += ws.kbp;
+    h->kb = reinterpret_cast<float*>(p);
+    p += ws.kb;
+    h->wflip = p;
+    p += ws.wflip;
+    h->fpart = reinterpret_cast<float*>(p);
+    if (!h->mfma_apply && h->n_split == 1) h->partial = h->state;  // see do_reduce
+}
+
+int forward_impl(castling_attn* h, const void* q, const void* k, const void* v,
+                          const void* dw_weight, const void* dw_bias, void* out, void* stream)
+{
+    if (!h) return CASTLING_ERR_INVALID_ARG;
+    // dw_weight == NULL: the filters registered by castling_attn_prepare_weights
+    const bool registered = !dw_weight && h->prepared_w;
+    const void* w = registered ? h->prepared_w : dw_weight;
+    // every argument is checked before anything is enqueued
+    int st = check_apply_args(h, q, v, w, out);
+    if (st != CASTLING_OK) return st;
+    const castling_attn_desc_t& d = h->desc;
+    const size_t es = dtype_size(d.io_dtype);
+    if ((d.branches & CASTLING_BRANCH_DWCONV) &&
+        (overlaps(out, h->out_span, w, static_cast<size_t>(d.heads) * d.d * d.dw_kernel * d.dw_kernel * es) ||
+         (dw_bias && overlaps(out, h->out_span, dw_bias, static_cast<size_t>(d.heads) * d.d * es))))
+        return CASTLING_ERR_ALIAS;
+    if (d.branches & CASTLING_BRANCH_LINEAR) {
+        if (!k || !v || misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
+        if (overlaps(out, h->out_span, k, h->in_span) || overlaps(out, h->out_span, v, h->in_span))
+            return CASTLING_ERR_ALIAS;
+    }
+    if (d.branches & CASTLING_BRANCH_LINEAR) {
+        if (h->fused) {
+            HIP_TRY(do_fused(h, true, q, k, v, w, dw_bias, out, static_cast<hipStream_t>(stream)));
+            return CASTLING_OK;
+        }
+        // the combine launch also prepares the weight operands of the MFMA apply kernel, unless
+        // the registered filters' table is the one to use
+        const bool fuse_w = h->mfma_apply && (d.branches & CASTLING_BRANCH_DWCONV);
+        st = do_reduce(h, k, v, fuse_w && !registered ? w : nullptr, static_cast<hipStream_t>(stream),
+                       h->sum_in_apply);
+        if (st != CASTLING_OK) return st;
+        if (fuse_w) {
+            h->use_registered = registered;
+            const hipError_t e = do_apply(h, true, q, v, nullptr, dw_bias, out, static_cast<hipStream_t>(stream));
+            h->use_registered = false;
+            HIP_TRY(e);
+            return CASTLING_OK;
+        }
+    }
+    if (h->fused) {  // convolution branch alone
+        HIP_TRY(do_fused(h, true, q, k, v, w, dw_bias, out, static_cast<hipStream_t>(stream)));
+        return CASTLING_OK;
+    }
+    return castling_attn_apply(h, q, v, dw_weight, dw_bias, out, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -875,7 +1028,7 @@ const char* castling_attn_strerror(int status)
         case CASTLING_ERR_INVALID_ARG: return "invalid argument";
         case CASTLING_ERR_UNSUPPORTED: return "unsupported shape or dtype";
         case CASTLING_ERR_HIP: return g_hip_error;
-        case CASTLING_ERR_ALIAS: return "output overlaps an input";
+        case CASTLING_ERR_ALIAS: return "an output overlaps an input or another output";
         default: return "unknown status";
     }
 }
@@ -948,229 +1101,20 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
 
     castling_attn* h = new (std::nothrow) castling_attn();
     if (!h) return hip_fail(hipErrorOutOfMemory);
-    h->desc = *desc;
-    if (h->desc.branches == 0) h->desc.branches = CASTLING_BRANCH_ALL;
-    if (h->desc.eps == 0.0f) h->desc.eps = 1e-12f;
-    h->units = desc->B * desc->heads;
-    h->state_valid = false;
-    h->apply_ready = false;
-    {
-        const castling_attn_desc_t& d = h->desc;
-        h->pool = d.q_pool == 2 ? 2 : 1;
-        h->qgrid_h = (d.grid_h + h->pool - 1) / h->pool;
-        h->qgrid_w = (d.grid_w + h->pool - 1) / h->pool;
-        h->nq = h->pool == 1 ? d.N : h->qgrid_h * h->qgrid_w;
-        h->residual_q = (d.flags & CASTLING_FLAG_RESIDUAL_Q) != 0;
-        auto dense = [&](int n) {
-            return TensorStrides{static_cast<long long>(d.heads) * n * d.d,
-                                 static_cast<long long>(n) * d.d, d.d};
-        };
-        h->in_st = d.in_stride_n ? TensorStrides{d.in_stride_b, d.in_stride_h, d.in_stride_n}
-                                 : dense(d.N);
-        h->out_st = d.out_stride_n ? TensorStrides{d.out_stride_b, d.out_stride_h, d.out_stride_n}
-                                   : dense(h->nq);
-        h->q_st = h->pool == 1 ? h->in_st
-                  : d.q_stride_n ? TensorStrides{d.q_stride_b, d.q_stride_h, d.q_stride_n}
-                                 : dense(h->nq);
-        auto span = [&](const TensorStrides& s, int n) {
-            return static_cast<size_t>((d.B - 1) * s.b + (d.heads - 1) * s.h + (n - 1) * s.n + d.d) *
-                   dtype_size(d.io_dtype);
-        };
-        h->in_span = span(h->in_st, d.N);
-        h->out_span = span(h->out_st, h->nq);
-        h->q_span = span(h->q_st, h->nq);
+    st = plan_handle(desc, h);
+    if (st != CASTLING_OK) {
+        delete h;
+        return st;
     }
-    h->dpad = desc->d <= 16 ? 16 : desc->d <= 32 ? 32 : desc->d <= 64 ? 64 : 128;
-    h->state_size = h->dpad * h->dpad + 2 * h->dpad;
-
-    const bool allow_mfma = (desc->io_dtype == CASTLING_BF16 || desc->io_dtype == CASTLING_F16) &&
-                            !(desc->flags & CASTLING_FLAG_VECTOR_ALU);
-    h->half16 = desc->io_dtype == CASTLING_F16;
-    h->mfma_reduce = allow_mfma && (desc->d == 32 || desc->d == 64);
-    // pooled or residual queries: pass 2 on the vector-ALU kernel (pass 1 is the same work)
-    const bool plain_q = h->pool == 1 && !h->residual_q;
-    h->mfma_apply = allow_mfma && desc->d == 64 && plain_q;
-    h->apply_units = h->units;
-    h->apply_heads = desc->heads;
-    h->apply_in = h->in_st;
-    h->apply_out = h->out_st;
-    h->in_skew = h->out_skew = 0;
-    h->pair = h->pair_reduce = false;
-    if (allow_mfma && desc->d == 32 && desc->heads % 2 == 0 && plain_q) {
-        // two neighbouring heads of 32 channels as one unit of 64 for pass 2: the second half of
-        // a token row lies one head stride further on instead of 64 bytes
-        const long long in_skew = h->in_st.h * 2 - 64, out_skew = h->out_st.h * 2 - 64;
-        const long long lim = (1ll << 32) - 256;
-        if (in_skew >= 0 && out_skew >= 0 && desc->N * h->in_st.n * 2 + in_skew < lim &&
-            desc->N * h->out_st.n * 2 + out_skew < lim) {
-            h->pair = h->mfma_apply = true;
-            h->apply_units = h->units / 2;
-            h->apply_heads = desc->heads / 2;
-            h->apply_in.h *= 2;
-            h->apply_out.h *= 2;
-            h->in_skew = static_cast<uint32_t>(in_skew);
-            h->out_skew = static_cast<uint32_t>(out_skew);
-            // pass 1 gains from pairs only where they make its loads whole 128-byte rows
-            h->pair_reduce = in_skew == 0;
-        }
-    }
-    const bool separate = (desc->flags & CASTLING_FLAG_SEPARATE_PASSES) != 0;
-    h->fused = h->mfma_apply && desc->N <= kFusedMaxTokens && desc->dw_kernel <= kFusedMaxKs && !separate;
-    // the one-launch forward: heads of 64 channels, every token on the grid, enough units to give
-    // each of the eight task queues whole units
-    // (filters up to 5 x 5: with 7 x 7 and 9 x 9 filters the one-launch forward has only run on
-    // shapes where a workgroup executes a single task; see also plan_stream)
-    h->stream = h->mfma_apply && !h->pair && !h->fused && !separate && desc->extra_tokens == 0 &&
-                h->units >= kStreamQueues && desc->dw_kernel <= 5;
-
-    // token split: enough blocks to fill the chip; chunks a multiple of what one block
-    // stages per iteration (128 tokens for the MFMA kernel, at most 64 for the generic one)
-    const int target_blocks = kTargetReduceBlocks;
-    const int reduce_units = h->pair_reduce ? h->apply_units : h->units;
-    int n_split = target_blocks / reduce_units;  // never one block more than fits at once
-    const int max_split = (desc->N + kMinChunkTokens - 1) / kMinChunkTokens;
-    if (n_split > max_split) n_split = max_split;
-    if (n_split < 1) n_split = 1;
-    int chunk = (desc->N + n_split - 1) / n_split;
-    const int chunk_mult = kReduceWaves * kReduceIterTokens;
-    chunk = ((chunk + chunk_mult - 1) / chunk_mult) * chunk_mult;
-    h->chunk = chunk;
-    h->n_split = (desc->N + chunk - 1) / chunk;
-
-    hipError_t e = hipGetDevice(&h->device);
-    if (e == hipSuccess)
-        e = hipDeviceGetAttribute(&h->num_cus, hipDeviceAttributeMultiprocessorCount, h->device);
-    if (e == hipSuccess && h->num_cus < 1) h->num_cus = 1;
-    if (e == hipSuccess) e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-    if (e == hipSuccess && h->fused)
-        e = do_fused(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-    std::vector<uint32_t> s_tasks;
-    uint32_t s_qoff[kStreamQueues + 1] = {};
-    if (e == hipSuccess && h->stream) e = plan_stream(h, s_tasks, s_qoff);
-    if (e == hipSuccess) {
-        int max_lds = 0;
-        e = hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, h->device);
-        if (e == hipSuccess && h->apply_lds > static_cast<size_t>(max_lds)) {
-            delete h;
-            return CASTLING_ERR_UNSUPPORTED;
-        }
-    }
-    // backward pass: LDS attributes of its kernels, and of the vector-ALU pass 2 it may need
-    h->training = (desc->flags & CASTLING_FLAG_TRAINING) != 0;
-    h->ov.on = h->ov.generic = false;
-    size_t a_bytes = 0, kbp_bytes = 0, kb_bytes = 0, wflip_bytes = 0, fpart_bytes = 0;
-    // CASTLING_ATTN_FORCE_GENERIC=1 keeps the per-row kernels of the backward off the matrix cores too
-    h->mfma_rows = allow_mfma && (desc->d == 32 || desc->d == 64);
-    if (e == hipSuccess && h->training) {
-        size_t lds = 0;
-        const size_t keep = h->apply_lds;
-        h->ov.on = h->ov.generic = true;
-        h->ov.q = h->ov.v = h->ov.out = h->in_st;
-        h->ov.lin_scale = 1.0f;
-        e = do_apply(h, false, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
-        lds = h->apply_lds;
-        h->apply_lds = keep;
-        h->ov.on = h->ov.generic = false;
-        if (e == hipSuccess)
-            e = dispatch_type_width(desc->io_dtype, h->dpad, [&](auto t, auto dc) {
-                using T = decltype(t);
-                constexpr int D = decltype(dc)::value;
-                hipError_t r = bwd_rows<T, D>(h, false, true, nullptr, nullptr, nullptr, &lds, nullptr);
-                if (r == hipSuccess) r = bwd_filter<T, D>(h, false, nullptr, nullptr, &lds, nullptr);
-                return r;
-            });
-        if (e == hipSuccess && lds > kMaxLdsBytes) {
-            delete h;
-            return CASTLING_ERR_UNSUPPORTED;
-        }
-        const int taps1 = desc->dw_kernel * desc->dw_kernel + 1;
-        const int n_tiles = ((desc->grid_w + kApplyTW - 1) / kApplyTW) *
-                            ((desc->grid_h + kApplyTH - 1) / kApplyTH);
-        h->row_tiles = (desc->N + kBwdTokens - 1) / kBwdTokens;
-        h->qrow_tiles = (h->nq + kBwdTokens - 1) / kBwdTokens;
-        h->kb_parts = h->mfma_rows ? 4 * h->qrow_tiles : h->qrow_tiles;
-        h->filter_chunks = std::max(1, std::min(n_tiles, 1024 / h->units));
-        a_bytes = align_up(h->in_span, 256) * (h->pool == 2 ? 3 : 1);  // a; pooled: + q_up, g_up
-        kbp_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->kb_parts * h->dpad, 256);
-        kb_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->dpad, 256);
-        wflip_bytes = align_up(dtype_size(desc->io_dtype) * static_cast<size_t>(desc->heads) * desc->d *
-                                   (taps1 - 1), 256);
-        fpart_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * h->filter_chunks * taps1 *
-                                   h->dpad, 256);
-    }
-    // one allocation, 256-byte aligned parts
-    const size_t partial_bytes =
-        h->pair_reduce ? align_up(sizeof(float) * static_cast<size_t>(h->apply_units) * h->n_split *
-                               StateLayout<64>::SIZE, 256)
-                : align_up(sizeof(float) * static_cast<size_t>(h->units) * h->n_split * h->state_size, 256);
-    const size_t state_bytes =
-        align_up(sizeof(float) * static_cast<size_t>(h->units) * h->state_size, 256);
-    size_t sfrag_bytes = 0, kfrag_bytes = 0, vhalf_bytes = 0, wfrag_bytes = 0;
-    if (h->mfma_apply) {
-        sfrag_bytes = align_up(sizeof(bf16_t) * static_cast<size_t>(h->units) * kSfragPerUnit, 256);
-        kfrag_bytes = align_up(sizeof(bf16_t) * static_cast<size_t>(h->units) * kKfragPerUnit, 256);
-        vhalf_bytes = align_up(sizeof(float) * static_cast<size_t>(h->units) * 64, 256);
-        wfrag_bytes =
-            align_up(static_cast<size_t>(desc->heads) * 4 * desc->dw_kernel * 3 * 64 * 8, 256);
-    }
-    size_t partial_bytes_all = partial_bytes, kpair_bytes = 0, tasks_bytes = 0, ctr_bytes = 0;
-    if (h->stream) {
-        partial_bytes_all = std::max(partial_bytes, align_up(sizeof(float) * static_cast<size_t>(h->units) *
-                                                                 h->s_cr * StateLayout<64>::SIZE, 256));
-        kpair_bytes = align_up(sizeof(uint32_t) * static_cast<size_t>(h->units) * 32, 256);
-        tasks_bytes = align_up(sizeof(uint32_t) * (s_tasks.size() + kStreamQueues + 1), 256);
-        ctr_bytes = align_up(sizeof(uint32_t) * stream_counter_words(h->units), 256);
-    }
-    h->workspace_bytes = partial_bytes_all + state_bytes + sfrag_bytes + kfrag_bytes + vhalf_bytes +
-                         2 * wfrag_bytes + a_bytes + kbp_bytes + kb_bytes + wflip_bytes + fpart_bytes +
-                         kpair_bytes + tasks_bytes + ctr_bytes;
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&h->workspace), h->workspace_bytes);
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&h->workspace), h->workspace_bytes);
     if (e != hipSuccess) {
         delete h;
         return hip_fail(e);
     }
-    unsigned char* p = h->workspace;
-    h->partial = reinterpret_cast<float*>(p);
-    p += partial_bytes_all;
-    h->state = reinterpret_cast<float*>(p);
-    p += state_bytes;
-    h->sfrag = reinterpret_cast<bf16_t*>(p);
-    p += sfrag_bytes;
-    h->kfrag = reinterpret_cast<bf16_t*>(p);
-    p += kfrag_bytes;
-    h->vhalf = reinterpret_cast<float*>(p);
-    p += vhalf_bytes;
-    h->wfrag = reinterpret_cast<bf16_t*>(p);
-    p += wfrag_bytes;
-    h->wfrag_reg = reinterpret_cast<bf16_t*>(p);
-    p += wfrag_bytes;
-    h->kpair = reinterpret_cast<uint32_t*>(p);
-    p += kpair_bytes;
-    h->s_tasks = reinterpret_cast<uint32_t*>(p);
-    h->s_qoff = h->s_tasks + s_tasks.size();
-    p += tasks_bytes;
-    h->s_counters = reinterpret_cast<uint32_t*>(p);
-    p += ctr_bytes;
-    if (h->stream) {
-        // task lists and zeroed counters, in place before any stream's kernels
-        e = hipMemcpy(h->s_tasks, s_tasks.data(), sizeof(uint32_t) * s_tasks.size(), hipMemcpyHostToDevice);
-        if (e == hipSuccess)
-            e = hipMemcpy(h->s_qoff, s_qoff, sizeof(s_qoff), hipMemcpyHostToDevice);
-        if (e == hipSuccess) e = hipMemset(h->s_counters, 0, ctr_bytes);
-        if (e == hipSuccess) e = hipDeviceSynchronize();
-        if (e != hipSuccess) {
-            (void)hipFree(h->workspace);
-            delete h;
-            return hip_fail(e);
-        }
-    }
-    h->a_buf = p;
-    h->q_up = h->g_up = nullptr;
+    carve_workspace(h, h->workspace);
     if (h->training && h->pool == 2) {
-        // the three hold rows only where pooled queries stand; the rest stays zero for good
-        h->q_up = p + a_bytes / 3;
-        h->g_up = p + 2 * (a_bytes / 3);
-        e = hipMemset(p, 0, a_bytes);
+        // a, q_up, g_up hold rows only where pooled queries stand; the rest stays zero for good
+        e = hipMemset(h->a_buf, 0, h->parts.a);
         if (e == hipSuccess) e = hipStreamSynchronize(nullptr);  // before any stream's kernels
         if (e != hipSuccess) {
             (void)hipFree(h->workspace);
@@ -1178,25 +1122,6 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
             return hip_fail(e);
         }
     }
-    p += a_bytes;
-    h->kb_part = reinterpret_cast<float*>(p);
-    p += kbp_bytes;
-    h->kb = reinterpret_cast<float*>(p);
-    p += kb_bytes;
-    h->wflip = p;
-    p += wflip_bytes;
-    h->fpart = reinterpret_cast<float*>(p);
-    if (!h->mfma_apply && h->n_split == 1) h->partial = h->state;  // see do_reduce
-    // Small vector-ALU problems: every apply block sums the few partial states itself instead of
-    // waiting for a combine launch (cfg1: three launches become two).  Not when the caller wants
-    // the state kept, and not where many blocks would each re-read many partials.
-    {
-        const long long tiles = static_cast<long long>((desc->grid_w + kApplyTW - 1) / kApplyTW) *
-                                ((desc->grid_h + kApplyTH - 1) / kApplyTH);
-        h->sum_in_apply = !h->mfma_apply && h->n_split > 1 && h->n_split <= 4 && tiles <= 16 &&
-                          !(desc->flags & CASTLING_FLAG_KEEP_STATE);
-    }
-    h->partials_pending = false;
     *out_handle = h;
     return CASTLING_OK;
 }
@@ -1218,29 +1143,9 @@ int castling_attn_num_launches(castling_attn_t h)
     if (!h) return 0;
     const bool lin = (h->desc.branches & CASTLING_BRANCH_LINEAR) != 0;
     const int extra = h->desc.extra_tokens > 0 ? 1 : 0;  // the tokens off the grid: one more launch
-    if (h->fused || h->stream) return 1;
+    if (h->fused) return 1;
     if (!lin) return 1 + extra;
     return ((h->n_split == 1 && !h->pair) || h->sum_in_apply ? 2 : 3) + extra;
-}
-
-int castling_attn_check(castling_attn_t h, void* stream)
-{
-    if (!h) return CASTLING_ERR_INVALID_ARG;
-    HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
-    if (!h->stream) return CASTLING_OK;
-    uint32_t w[3] = {0u, 0u, 0u};
-    HIP_TRY(hipMemcpy(w, h->s_counters + kCtrError, sizeof(w), hipMemcpyDeviceToHost));
-    if (w[0] == 0u) return CASTLING_OK;
-    // the launch may have left its counters half way: start the next one from a clean block
-    HIP_TRY(hipMemset(h->s_counters, 0, sizeof(uint32_t) * stream_counter_words(h->units)));
-    HIP_TRY(hipDeviceSynchronize());
-    h->state_valid = false;
-    static const char* const what[] = {"", "a wait for other tasks of the launch gave up",
-                                       "a task word outside the launch's ranges",
-                                       "a load offset outside its unit", "a store offset outside its unit"};
-    snprintf(g_hip_error, sizeof(g_hip_error), "one-launch forward: %s (details %u, %u)",
-             w[0] < 5 ? what[w[0]] : "unknown in-kernel check", w[1], w[2]);
-    return CASTLING_ERR_HIP;
 }
 
 int castling_attn_reduce(castling_attn_t h, const void* k, const void* v, void* stream)
@@ -1350,46 +1255,7 @@ int castling_attn_pairwise(castling_attn_t h, const castling_pair_params_t* para
 int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
                           const void* dw_weight, const void* dw_bias, void* out, void* stream)
 {
-    // every argument is checked before anything is enqueued
-    int st = check_apply_args(h, q, v, dw_weight, out);
-    if (st != CASTLING_OK) return st;
-    const castling_attn_desc_t& d = h->desc;
-    const size_t es = dtype_size(d.io_dtype);
-    if ((d.branches & CASTLING_BRANCH_DWCONV) &&
-        (overlaps(out, h->out_span, dw_weight, static_cast<size_t>(d.heads) * d.d * d.dw_kernel * d.dw_kernel * es) ||
-         (dw_bias && overlaps(out, h->out_span, dw_bias, static_cast<size_t>(d.heads) * d.d * es))))
-        return CASTLING_ERR_ALIAS;
-    if (d.branches & CASTLING_BRANCH_LINEAR) {
-        if (!k || !v || misaligned(k) || misaligned(v)) return CASTLING_ERR_INVALID_ARG;
-        if (overlaps(out, h->out_span, k, h->in_span) || overlaps(out, h->out_span, v, h->in_span))
-            return CASTLING_ERR_ALIAS;
-    }
-    if (h->stream) {
-        // filters registered by prepare_weights and passed again: their operand table is ready
-        const bool reg = (d.branches & CASTLING_BRANCH_DWCONV) && dw_weight == h->prepared_w;
-        HIP_TRY(do_stream(h, q, k, v, reg ? nullptr : dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
-        return CASTLING_OK;
-    }
-    if (d.branches & CASTLING_BRANCH_LINEAR) {
-        if (h->fused) {
-            HIP_TRY(do_fused(h, true, q, k, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
-            return CASTLING_OK;
-        }
-        // the combine launch also prepares the weight operands of the MFMA apply kernel
-        const bool fuse_w = h->mfma_apply && (d.branches & CASTLING_BRANCH_DWCONV);
-        st = do_reduce(h, k, v, fuse_w ? dw_weight : nullptr, static_cast<hipStream_t>(stream),
-                       h->sum_in_apply);
-        if (st != CASTLING_OK) return st;
-        if (fuse_w) {
-            HIP_TRY(do_apply(h, true, q, v, nullptr, dw_bias, out, static_cast<hipStream_t>(stream)));
-            return CASTLING_OK;
-        }
-    }
-    if (h->fused) {  // convolution branch alone
-        HIP_TRY(do_fused(h, true, q, k, v, dw_weight, dw_bias, out, static_cast<hipStream_t>(stream)));
-        return CASTLING_OK;
-    }
-    return castling_attn_apply(h, q, v, dw_weight, dw_bias, out, stream);
+    return forward_impl(h, q, k, v, dw_weight, dw_bias, out, stream);
 }
 
 int castling_attn_backward(castling_attn_t h, const void* q, const void* k, const void* v,
@@ -1416,6 +1282,25 @@ int castling_attn_backward(castling_attn_t h, const void* q, const void* k, cons
         for (int o2 = o + 1; o2 < 3; ++o2)
             if (outs[o] == outs[o2]) return CASTLING_ERR_ALIAS;
     }
+    // ... the fp32 filter and bias gradients included, and no gradient may overlap the filters
+    const size_t w_elems = static_cast<size_t>(d.heads) * d.d * d.dw_kernel * d.dw_kernel;
+    const size_t b_elems = static_cast<size_t>(d.heads) * d.d;
+    const size_t es = dtype_size(d.io_dtype);
+    const void* fouts[] = {grad_w, grad_bias};
+    const size_t fout_bytes[] = {w_elems * sizeof(float), b_elems * sizeof(float)};
+    for (int f = 0; f < 2; ++f) {
+        if (!fouts[f]) continue;
+        for (int i = 0; i < 4; ++i)
+            if (overlaps(fouts[f], fout_bytes[f], ins[i], in_bytes[i])) return CASTLING_ERR_ALIAS;
+        for (int o = 0; o < 3; ++o)
+            if (overlaps(fouts[f], fout_bytes[f], outs[o], out_bytes[o])) return CASTLING_ERR_ALIAS;
+        if (dw && overlaps(fouts[f], fout_bytes[f], dw_weight, w_elems * es)) return CASTLING_ERR_ALIAS;
+    }
+    if (grad_w && grad_bias && overlaps(grad_w, fout_bytes[0], grad_bias, fout_bytes[1]))
+        return CASTLING_ERR_ALIAS;
+    if (dw)
+        for (int o = 0; o < 3; ++o)
+            if (overlaps(outs[o], out_bytes[o], dw_weight, w_elems * es)) return CASTLING_ERR_ALIAS;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int taps = d.dw_kernel * d.dw_kernel;
     // pooled queries: the query-side kernel puts q, a, g on their places in the fine grid (zero

@@ -195,16 +195,6 @@ __device__ __forceinline__ void static_for(F&& f)
 // wait stricter, never too weak.
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-// A pointer every lane of the wave holds alike, moved to scalar registers (the value of lane 0).
-template <typename T>
-__device__ __forceinline__ T* wave_uniform(T* p)
-{
-    const uint64_t x = reinterpret_cast<uint64_t>(p);
-    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x));
-    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x >> 32));
-    return reinterpret_cast<T*>((static_cast<uint64_t>(hi) << 32) | lo);
-}
-
 // base: wave-uniform pointer (scalar registers), offset: per-lane byte offset
 __device__ __forceinline__ void async_load16(u32x4_t& dst, const void* base, uint32_t offset)
 {

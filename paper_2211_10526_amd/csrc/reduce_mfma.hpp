@@ -60,54 +60,24 @@ struct ReduceExtras {
     int units, heads, ks;
     float tscale;  // table scale of the I/O format for this N
     uint32_t pair_skew;  // PAIR: bytes to add to the address of channels 32..63 of a token row
-    int write_state;     // with state != nullptr: 0 = build the tables only, leave the fp32 state unwritten
-    uint32_t* kpair;     // with state != nullptr and not null: [unit][32] pairs (ksum[2i], ksum[2i+1]) * tscale
 };
 
-// Device-scope stores and loads (relaxed atomics: no cache maintenance, the value is written to /
-// read from the level all compute units of the device share).  Results that another workgroup
-// of the same launch reads go through these.
-__device__ __forceinline__ void st_agent(float* p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_agent(uint32_t* p, uint32_t v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float ld_agent(const float* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// LDS bytes reduce_mfma_block needs
-template <int D>
-constexpr int reduce_mfma_lds_bytes()
-{
-    constexpr int NW = kReduceWaves, MT = D / 32;
-    constexpr int stage = NW * 2 * kReduceIterTokens * (D * 2 + 32);
-    constexpr int tree = (NW / 2) * MT * MT * 16 * 64 * 4;
-    constexpr int sums = NW * 64 * 16 * 4 + D * 4;
-    return (stage > tree ? stage : tree) > sums ? (stage > tree ? stage : tree) : sums;
-}
-
-// The work of one block of 64 * kReduceWaves threads: tokens [n_begin, n_end) of `unit` reduced to
-// one partial state at `out` (StateLayout<D>), with device-scope stores.  `lds`: at least
-// reduce_mfma_lds_bytes<D>() bytes, 16-byte aligned; the function starts and ends with no
-// barrier of its own pending (callers that reuse the LDS put a barrier in between).
+// grid = (n_split, units [+ weight rows]), block = 64 * kReduceWaves.  Same partial layout
+// as the generic kernel: partial[u][s][StateLayout<D>::SIZE].
 // PAIR (D = 64): a unit is two heads of 32 channels (whole 128-byte token rows when the heads
 // are neighbours in memory); each half of a K row is normalised on its own, and of the 64 x 64
 // product only the two diagonal 32 x 32 blocks mean anything.
 template <int D, typename X, bool PAIR = false>
-__device__ __forceinline__ void reduce_mfma_block(
-    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ out_partial, int N,
-    int n_begin, int n_end, float eps, int heads, const TensorStrides& st, const ReduceExtras& ex,
-    int unit, unsigned char* lds)
+__global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
+    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
+    int n_split, int chunk, float eps, int heads, TensorStrides st, ReduceExtras ex)
 {
+    if (static_cast<int>(blockIdx.y) >= ex.units) {  // weight rows (uniform per block)
+        const int row = blockIdx.y - ex.units;
+        dwconv_weight_frag((row * gridDim.x + blockIdx.x) * (64 * kReduceWaves) + threadIdx.x, ex.w,
+                           ex.wfrag, ex.heads, ex.ks);
+        return;
+    }
     constexpr int NW = kReduceWaves;
     constexpr int MT = D / 32;               // 32-wide tiles per side of S
     constexpr int LPR = D / 8;               // lanes per token row
@@ -124,21 +94,24 @@ __device__ __forceinline__ void reduce_mfma_block(
                                   ? (STAGE_BYTES > TREE_BYTES ? STAGE_BYTES : TREE_BYTES)
                                   : SUMS_BYTES;
     using L = StateLayout<D>;
-    static_assert(LDS_BYTES == reduce_mfma_lds_bytes<D>(), "LDS size helper out of step");
 
-    // (opaque to the optimiser: a caller that loops over such jobs keeps nothing derived from it)
-    const int tid = static_cast<int>(opaque_u32(threadIdx.x));
+    __shared__ __attribute__((aligned(16))) unsigned char lds[LDS_BYTES];
+
+    const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int chunk = n_end - n_begin;
+    const int unit = blockIdx.y;
+    const int split = blockIdx.x;
+    const int n_begin = split * chunk;
+    const int n_end = min(N, n_begin + chunk);
     // each wave takes a contiguous slice, a multiple of the iteration size
     const int per_wave = ((chunk + NW * kReduceIterTokens - 1) / (NW * kReduceIterTokens)) *
                          kReduceIterTokens;
     const int w_begin = n_begin + wave * per_wave;
     const int w_end = min(n_end, w_begin + per_wave);
 
-    const bf16_t* kb = wave_uniform(k + unit_offset(unit, heads, st));
-    const bf16_t* vb = wave_uniform(v + unit_offset(unit, heads, st));
+    const bf16_t* kb = k + unit_offset(unit, heads, st);
+    const bf16_t* vb = v + unit_offset(unit, heads, st);
     const uint32_t tok_bytes = static_cast<uint32_t>(st.n) * 2;  // the host keeps N * tok_bytes below 4 GiB
     unsigned char* ks_tile = lds + wave * 2 * TILE_BYTES;
     unsigned char* vs_tile = ks_tile + TILE_BYTES;
@@ -274,7 +247,7 @@ __device__ __forceinline__ void reduce_mfma_block(
             sums[(wave * 64 + lane) * 16 + 8 + e] = vsum[e];
         }
         __syncthreads();
-        float* out = out_partial;
+        float* out = partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE;
         if (tid < 2 * D) {
             const int which = tid / D;          // 0: ksum, 1: vsum
             const int f = tid % D;              // feature
@@ -283,12 +256,11 @@ __device__ __forceinline__ void reduce_mfma_block(
             for (int w = 0; w < NW; ++w)
                 for (int r = 0; r < TPL; ++r)
                     s += sums[(w * 64 + r * LPR + lc) * 16 + which * 8 + e];
-            if (out) st_agent(&out[(which ? L::VSUM : L::KSUM) + f], s);
+            out[(which ? L::VSUM : L::KSUM) + f] = s;
             if constexpr (D == 64) {
                 if (ex.state) {  // final result: fp32 state, vsum / 2, and ksum kept for the table below
-                    if (ex.write_state)
-                        st_agent(&ex.state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f], s);
-                    if (which) st_agent(&ex.vhalf[unit * 64 + f], 0.5f * s);
+                    ex.state[static_cast<size_t>(unit) * L::SIZE + (which ? L::VSUM : L::KSUM) + f] = s;
+                    if (which) ex.vhalf[unit * 64 + f] = 0.5f * s;
                     else sums[NW * 64 * 16 + f] = s;
                 }
             }
@@ -297,14 +269,11 @@ __device__ __forceinline__ void reduce_mfma_block(
         if constexpr (D == 64) {
             if (ex.state) {
                 // ksum operand table: entry (ks, lane, e2) holds ksum[32 ks + 8 (lane / 16) + 2 e2 .. +1] * scale
-                if (ex.kpair && tid < 32)
-                    st_agent(&ex.kpair[unit * 32 + tid], X::pack(sums[NW * 64 * 16 + 2 * tid] * ex.tscale,
-                                                                 sums[NW * 64 * 16 + 2 * tid + 1] * ex.tscale));
                 uint32_t* dst = reinterpret_cast<uint32_t*>(ex.kfrag + static_cast<size_t>(unit) * kKfragPerUnit);
-                for (int u = tid; ex.kfrag && u < kKfragPerUnit / 2; u += 64 * NW) {
+                for (int u = tid; u < kKfragPerUnit / 2; u += 64 * NW) {
                     const int e2 = u & 3, fl = (u >> 2) & 63, ks = u >> 8;
                     const int i0 = 32 * ks + 8 * (fl >> 4) + 2 * e2;
-                    st_agent(&dst[u], X::pack(sums[NW * 64 * 16 + i0] * ex.tscale, sums[NW * 64 * 16 + i0 + 1] * ex.tscale));
+                    dst[u] = X::pack(sums[NW * 64 * 16 + i0] * ex.tscale, sums[NW * 64 * 16 + i0 + 1] * ex.tscale);
                 }
                 __syncthreads();
             }
@@ -349,16 +318,16 @@ __device__ __forceinline__ void reduce_mfma_block(
             __syncthreads();
         }
         if (wave == 0) {
-            float* out = out_partial + L::S;
+            float* out = partial + (static_cast<size_t>(unit) * n_split + split) * L::SIZE + L::S;
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int nt = 0; nt < MT; ++nt)
 #pragma unroll
-                    for (int r = 0; out_partial && r < 16; ++r) {
+                    for (int r = 0; r < 16; ++r) {
                         const int i = 32 * mt + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
                         const int j = 32 * nt + (lane % 32);
-                        st_agent(&out[i * D + j], acc[mt][nt][r]);
+                        out[i * D + j] = acc[mt][nt][r];
                     }
             if constexpr (D == 64) {
                 if (ex.state) {
@@ -373,38 +342,18 @@ __device__ __forceinline__ void reduce_mfma_block(
                             for (int r = 0; r < 16; ++r) {
                                 const int i = 32 * mt + (r / 4) * 8 + (lane / 32) * 4 + (r % 4);
                                 const int j = 32 * nt + (lane % 32);
-                                if (ex.write_state) st_agent(&st[i * D + j], acc[mt][nt][r]);
+                                st[i * D + j] = acc[mt][nt][r];
                                 if ((r & 1) == 0) {
                                     // table entry ((j/16)*2 + i/32, lane' = ((i%32)/8)*16 + j%16, (i%8)/2)
                                     const int t = (((j >> 4) * 2 + (i >> 5)) * 64 + (((i & 31) >> 3) * 16 + (j & 15))) * 4 +
                                                   ((i & 7) >> 1);
-                                    st_agent(&sf[t], X::pack(acc[mt][nt][r] * ex.tscale, acc[mt][nt][r + 1] * ex.tscale));
+                                    sf[t] = X::pack(acc[mt][nt][r] * ex.tscale, acc[mt][nt][r + 1] * ex.tscale);
                                 }
                             }
                 }
             }
         }
     }
-}
-
-// grid = (n_split, units [+ weight rows]), block = 64 * kReduceWaves.  Same partial layout
-// as the generic kernel: partial[u][s][StateLayout<D>::SIZE].
-template <int D, typename X, bool PAIR = false>
-__global__ __launch_bounds__(64 * kReduceWaves) void reduce_mfma_kernel(
-    const bf16_t* __restrict__ k, const bf16_t* __restrict__ v, float* __restrict__ partial, int N,
-    int n_split, int chunk, float eps, int heads, TensorStrides st, ReduceExtras ex)
-{
-    if (static_cast<int>(blockIdx.y) >= ex.units) {  // weight rows (uniform per block)
-        const int row = blockIdx.y - ex.units;
-        dwconv_weight_frag((row * gridDim.x + blockIdx.x) * (64 * kReduceWaves) + threadIdx.x, ex.w,
-                           ex.wfrag, ex.heads, ex.ks);
-        return;
-    }
-    __shared__ __attribute__((aligned(16))) unsigned char lds[reduce_mfma_lds_bytes<D>()];
-    const int unit = blockIdx.y, split = blockIdx.x;
-    const int n_begin = split * chunk;
-    reduce_mfma_block<D, X, PAIR>(k, v, partial + (static_cast<size_t>(unit) * n_split + split) * StateLayout<D>::SIZE,
-                                  N, n_begin, min(N, n_begin + chunk), eps, heads, st, ex, unit, lds);
 }
 
 }  // namespace castling

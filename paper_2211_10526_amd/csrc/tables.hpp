@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void combine_pair_frag_kernel(
     }
 }
 
-static __global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* __restrict__ w,
+__global__ __launch_bounds__(256) void dwconv_weight_frag_kernel(const bf16_t* __restrict__ w,
                                                                  bf16_t* __restrict__ wfrag,
                                                                  int heads, int ks)
 {

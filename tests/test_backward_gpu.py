@@ -191,6 +191,19 @@ def test_backward_needs_a_training_handle_and_distinct_buffers():
     with pytest.raises(b.CastlingError) as e:
         attn.backward(t["q"], t["k"], t["v"], None, t["g"], gq, gk, gv, gw)
     assert e.value.status == b.ERR_INVALID_ARG
+    # the fp32 filter and bias gradients are outputs like the others
+    gb = torch.empty(t["w"].shape[:2], dtype=torch.float32, device=dev)
+    as_f32 = t["q"].view(torch.float32).reshape(-1)
+    bad = [dict(gw=as_f32[:gw.numel()]),                       # grad_w inside q
+           dict(gw=gq.view(torch.float32).reshape(-1)[:gw.numel()]),  # grad_w inside grad_q
+           dict(gb=gw.reshape(-1)[:gb.numel()]),               # grad_bias inside grad_w
+           dict(gw=t["w"].view(torch.float32).reshape(-1)) if t["w"].element_size() == 4 else
+           dict(gb=t["g"].view(torch.float32).reshape(-1)[:gb.numel()])]   # inside grad_out
+    for kw in bad:
+        with pytest.raises(b.CastlingError) as e:
+            attn.backward(t["q"], t["k"], t["v"], t["w"], t["g"], gq, gk, gv, kw.get("gw", gw),
+                          kw.get("gb", gb))
+        assert e.value.status == b.ERR_ALIAS, list(kw)
     attn.destroy()
 
 

@@ -388,6 +388,40 @@ def test_apply_with_registered_weights(wl):
     assert torch.equal(o1.view(view), o2.view(view))
 
 
+@pytest.mark.parametrize("wl", [SMALL[10], SMALL[14], SMALL[0]], ids=lambda w: w.name)
+def test_registered_weights_survive_other_calls(wl):
+    """The operand table of prepare_weights belongs to the registration alone: a backward pass
+    (which runs pass 2 with the filters turned by 180 degrees) and a forward with other filters
+    in between leave it as it was; forward(w = None) uses it like apply(w = None)."""
+    x = inputs.make_inputs(wl, seed=19, with_bias=True)
+    dev = torch.device("cuda:0")
+    t = {n: x[n].to(dev) for n in ("q", "k", "v", "w", "bias")}
+    other_w = (t["w"].float() * -1.7 + 0.05).to(t["w"].dtype)
+    attn = b.CastlingAttn.for_workload(wl, flags=b.FLAG_TRAINING)
+    o_ref, o_reg, f_ref, f_reg, scratch = (torch.empty_like(t["q"]) for _ in range(5))
+    attn.reduce(t["k"], t["v"])
+    attn.apply(t["q"], t["v"], t["w"], t["bias"], o_ref)
+    attn.forward(t["q"], t["k"], t["v"], t["w"], t["bias"], f_ref)
+    with pytest.raises(b.CastlingError) as e:          # nothing registered yet
+        attn.forward(t["q"], t["k"], t["v"], None, t["bias"], scratch)
+    assert e.value.status == b.ERR_INVALID_ARG
+    attn.prepare_weights(t["w"])
+    print(f"case registered weights {wl.name}", flush=True)
+    grads = [torch.empty_like(t["q"]) for _ in range(3)]
+    gw = torch.empty(t["w"].shape, dtype=torch.float32, device=dev)
+    attn.backward(t["q"], t["k"], t["v"], other_w, t["v"], grads[0], grads[1], grads[2], gw)
+    attn.forward(t["q"], t["k"], t["v"], other_w, t["bias"], scratch)
+    attn.reduce(t["k"], t["v"])
+    attn.apply(t["q"], t["v"], None, t["bias"], o_reg)
+    attn.forward(t["q"], t["k"], t["v"], None, t["bias"], f_reg)
+    torch.cuda.synchronize()
+    attn.destroy()
+    view = torch.int16 if wl.dtype != "f32" else torch.int32
+    assert torch.equal(o_ref.view(view), o_reg.view(view))
+    assert torch.equal(f_ref.view(view), f_reg.view(view))
+    assert not torch.equal(scratch.view(view), f_ref.view(view))
+
+
 @pytest.mark.parametrize("wl", [SMALL[0], SMALL[15], SMALL[10]], ids=lambda w: w.name)
 def test_apply_needs_a_reduce(wl):
     """apply() uses what reduce() left in the handle; before any reduce, and after a forward that
