@@ -61,7 +61,8 @@ typedef enum {
     CASTLING_ERR_INVALID_ARG = 1, /* null pointer, non-positive size, N != extra_tokens + grid_h*grid_w, even ks, misalignment */
     CASTLING_ERR_UNSUPPORTED = 2, /* d, ks or dtype outside what the kernels are built for */
     CASTLING_ERR_HIP = 3,         /* a HIP runtime call failed (allocation, launch) */
-    CASTLING_ERR_ALIAS = 4        /* an output overlaps an input or another output */
+    CASTLING_ERR_ALIAS = 4,       /* an output overlaps an input or another output */
+    CASTLING_ERR_TOO_LARGE = 5    /* castling_attn_forward_static: more scratch memory needed than it holds */
 } castling_status_t;
 
 typedef enum { CASTLING_F32 = 0, CASTLING_BF16 = 1, CASTLING_F16 = 2 } castling_dtype_t;
@@ -149,6 +150,29 @@ int castling_attn_create(const castling_attn_desc_t* desc, castling_attn_t* out_
  * registered there are used. */
 int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const void* v,
                           const void* dw_weight, const void* dw_bias, void* out, void* stream);
+
+/* castling_attn_forward for callers that cannot allocate device memory or keep a handle: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, checks and results as castling_attn_create(desc) + castling_attn_forward +
+ * castling_attn_destroy (bitwise the same output: the same kernels run), but the workspace is
+ * a fixed array of CASTLING_STATIC_SCRATCH_BYTES inside the library's device image, one copy
+ * per GPU, held from the time the library is loaded on that GPU until the process ends.  The
+ * call allocates and frees nothing on the device.
+ *   - A problem whose workspace (castling_attn_workspace_bytes of a handle for desc) is larger
+ *     is refused with CASTLING_ERR_TOO_LARGE before anything is enqueued; the five benchmark
+ *     workloads fit.  CASTLING_FLAG_TRAINING is refused (CASTLING_ERR_INVALID_ARG); dw_weight
+ *     must be given (there is no registration); the state cannot be fetched afterwards.
+ *   - All calls on one GPU share that GPU's array, whatever their streams or threads: calls
+ *     that overlap in time on one GPU race.  Nothing in the array needs clearing between
+ *     calls: every call writes each part before it reads it, also after a call of another
+ *     shape.
+ *   - The first call on a device looks up the array's address, and a call with a descriptor
+ *     other than the last one sets kernel attributes; make one call per descriptor outside
+ *     graph capture first.  Repeated calls with the same descriptor only enqueue launches. */
+#define CASTLING_STATIC_SCRATCH_BYTES (32u << 20)
+int castling_attn_forward_static(const castling_attn_desc_t* desc, const void* q, const void* k,
+                                 const void* v, const void* dw_weight, const void* dw_bias,
+                                 void* out, void* stream);
 
 /* First half: normalise K per token and reduce over tokens to the per-unit state
  * K_hat^T V, sum_j k_hat_j, sum_j v_j (Sec. 3.1 reassociation; sums of Eq. 3).

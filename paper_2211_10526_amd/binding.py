@@ -15,7 +15,8 @@ import numpy as np
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libcastling_attn.so")
 
-OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_ALIAS = 0, 1, 2, 3, 4
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_HIP, ERR_ALIAS, ERR_TOO_LARGE = 0, 1, 2, 3, 4, 5
+STATIC_SCRATCH_BYTES = 32 << 20
 F32, BF16, F16 = 0, 1, 2
 NORM_ROWSUM, NORM_NONE = 0, 1
 BRANCH_LINEAR, BRANCH_DWCONV, BRANCH_ALL = 1, 2, 3
@@ -31,7 +32,7 @@ EXPORTS = (
     "castling_attn_destroy",
     "castling_attn_workspace_bytes", "castling_attn_get_state", "castling_attn_num_splits",
     "castling_attn_num_launches", "castling_attn_pairwise", "castling_attn_backward",
-    "castling_attn_strerror",
+    "castling_attn_strerror", "castling_attn_forward_static",
 )
 
 
@@ -80,6 +81,7 @@ def lib():
         L.castling_attn_validate.argtypes = [C.POINTER(Desc)]
         L.castling_attn_create.argtypes = [C.POINTER(Desc), C.POINTER(vp)]
         L.castling_attn_forward.argtypes = [vp] * 8
+        L.castling_attn_forward_static.argtypes = [C.POINTER(Desc)] + [vp] * 7
         L.castling_attn_reduce.argtypes = [vp] * 4
         L.castling_attn_apply.argtypes = [vp] * 7
         L.castling_attn_prepare_weights.argtypes = [vp] * 3
@@ -146,6 +148,13 @@ def _stream_ptr(stream):
         import torch
         stream = torch.cuda.current_stream()
     return C.c_void_p(stream.cuda_stream)
+
+
+def forward_static(desc: Desc, q, k, v, w, bias, out, stream=None):
+    """castling_attn_forward_static: the forward without a handle or device allocation."""
+    _check(lib().castling_attn_forward_static(C.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(w),
+                                              _ptr(bias), _ptr(out), _stream_ptr(stream)))
+    return out
 
 
 class CastlingAttn:

@@ -10,6 +10,7 @@
 #include <cfloat>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 
 #include "apply_generic.hpp"
@@ -22,6 +23,9 @@
 #include "reduce_mfma.hpp"
 
 using namespace castling;
+
+// Scratch memory of castling_attn_forward_static: one copy per GPU, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[CASTLING_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -970,6 +974,33 @@ void carve_workspace(castling_attn* h, unsigned char* base)
     if (!h->mfma_apply && h->n_split == 1) h->partial = h->state;  // see do_reduce
 }
 
+// ------------------------------------------------------------------ scratch without allocation
+// Workspace of castling_attn_forward_static.  The name is a host-side stand-in for the symbol:
+// host code uses the per-device address from hipGetSymbolAddress, never the name itself.
+constexpr size_t kStaticScratchBytes = CASTLING_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+unsigned char* g_static_base[kMaxDevices];  // per device: where its copy of `scratch` lies
+bool g_static_plan_valid = false;
+castling_attn_desc_t g_static_desc;
+castling_attn g_static_plan;
+
+// The address of the current device's copy of the array (looked up once per device).
+hipError_t static_scratch_base(int device, unsigned char** out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_base[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || (reinterpret_cast<uintptr_t>(p) & 255u) != 0) return hipErrorInvalidSymbol;
+        g_static_base[device] = static_cast<unsigned char*>(p);
+    }
+    *out = g_static_base[device];
+    return hipSuccess;
+}
+
 int forward_impl(castling_attn* h, const void* q, const void* k, const void* v,
                           const void* dw_weight, const void* dw_bias, void* out, void* stream)
 {
@@ -1029,6 +1060,9 @@ const char* castling_attn_strerror(int status)
         case CASTLING_ERR_UNSUPPORTED: return "unsupported shape or dtype";
         case CASTLING_ERR_HIP: return g_hip_error;
         case CASTLING_ERR_ALIAS: return "an output overlaps an input or another output";
+        case CASTLING_ERR_TOO_LARGE:
+            return "the problem needs more scratch memory than castling_attn_forward_static holds "
+                   "(CASTLING_STATIC_SCRATCH_BYTES); use a handle";
         default: return "unknown status";
     }
 }
@@ -1256,6 +1290,39 @@ int castling_attn_forward(castling_attn_t h, const void* q, const void* k, const
                           const void* dw_weight, const void* dw_bias, void* out, void* stream)
 {
     return forward_impl(h, q, k, v, dw_weight, dw_bias, out, stream);
+}
+
+int castling_attn_forward_static(const castling_attn_desc_t* desc, const void* q, const void* k,
+                                 const void* v, const void* dw_weight, const void* dw_bias, void* out,
+                                 void* stream)
+{
+    int st = castling_attn_validate(desc);
+    if (st != CASTLING_OK) return st;
+    if (desc->flags & CASTLING_FLAG_TRAINING) return CASTLING_ERR_INVALID_ARG;  // no backward here
+    int device = -1;
+    HIP_TRY(hipGetDevice(&device));
+    // the plan of the last descriptor seen on this device is kept: a repeated call makes no
+    // HIP call besides its launches
+    castling_attn h{};
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (g_static_plan_valid && g_static_plan.device == device &&
+            std::memcmp(&g_static_desc, desc, sizeof(*desc)) == 0) {
+            h = g_static_plan;
+        } else {
+            g_static_plan_valid = false;
+            st = plan_handle(desc, &h);
+            if (st != CASTLING_OK) return st;
+            g_static_plan = h;
+            std::memcpy(&g_static_desc, desc, sizeof(*desc));
+            g_static_plan_valid = true;
+        }
+    }
+    if (h.workspace_bytes > kStaticScratchBytes) return CASTLING_ERR_TOO_LARGE;
+    unsigned char* base = nullptr;
+    HIP_TRY(static_scratch_base(device, &base));
+    carve_workspace(&h, base);
+    return forward_impl(&h, q, k, v, dw_weight, dw_bias, out, stream);
 }
 
 int castling_attn_backward(castling_attn_t h, const void* q, const void* k, const void* v,
