@@ -34,12 +34,6 @@
 #include "common.hpp"
 #include "reduce_mfma.hpp"
 
-#ifndef TRACE_POINT
-#define TRACE_POINT(id)
-#define TRACE_DECL
-#define TRACE_DUMP
-#endif
-
 namespace castling {
 
 
@@ -147,11 +141,7 @@ __device__ __forceinline__ void store16_stream(void* p, uint32_t a, uint32_t b, 
 {
     typedef __attribute__((ext_vector_type(4))) uint32_t v4;
     const v4 val = {a, b, c, d};
-#if defined(CASTLING_NO_NT) || defined(CASTLING_NO_NT_STORE)
-    *reinterpret_cast<v4*>(p) = val;
-#else
     __builtin_nontemporal_store(val, reinterpret_cast<v4*>(p));
-#endif
 }
 
 // 8-byte transposing LDS read (see lds_operand_tr in reduce_mfma.hpp for the lane roles)
@@ -162,14 +152,8 @@ __device__ __forceinline__ uint2 lds_read_tr8(const unsigned char* addr)
     return __builtin_bit_cast(uint2, r);
 }
 
-#ifndef CASTLING_APPLY_PREFETCH
-#define CASTLING_APPLY_PREFETCH 2
-#endif
-constexpr int kApplyPrefetch = CASTLING_APPLY_PREFETCH;  // stages whose global loads are in flight
-#ifndef CASTLING_LINEAR_PREFETCH
-#define CASTLING_LINEAR_PREFETCH 4
-#endif
-constexpr int kLinearPrefetch = CASTLING_LINEAR_PREFETCH;  // the same for the linear waves' q
+constexpr int kApplyPrefetch = 2;   // stages whose global loads are in flight
+constexpr int kLinearPrefetch = 4;  // the same for the linear waves' q
 
 // what a wave needs to know about a stage after its cursor has moved on
 struct StageSnap {
@@ -197,7 +181,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     static_assert(PD % 2 == 0, "the two-deep LDS rings assume an even prefetch depth");
 
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    TRACE_DECL
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -209,13 +192,9 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
     const uint32_t in_tok = static_cast<uint32_t>(p.in.n) * 2;    // bytes between tokens
     const uint32_t out_tok = static_cast<uint32_t>(p.out.n) * 2;
 
-#ifndef CASTLING_NO_XCD_REMAP
     // consecutive workgroups go to the 8 XCDs in turn: give each XCD a contiguous step range
     const int lblock = (gridDim.x % 8 == 0) ? (blockIdx.x % 8) * (gridDim.x / 8) + blockIdx.x / 8
                                             : static_cast<int>(blockIdx.x);
-#else
-    const int lblock = blockIdx.x;
-#endif
     const int s_begin = static_cast<int>(static_cast<long long>(lblock) * total_steps / gridDim.x);
     const int s_end = static_cast<int>(static_cast<long long>(lblock + 1) * total_steps / gridDim.x);
 
@@ -401,18 +380,14 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             static_for<PD>([&](auto slot) {
                 if (s + decltype(slot)::value >= n_stages) return;
                 constexpr int b2 = decltype(slot)::value & 1;
-                TRACE_POINT(1);
                 // the output tile two stages back is complete
                 stage_v(slot, fsnap[b2], out_base + b2 * kOutBytes, vt_base + b2 * kVtBytes);
                 fsnap[b2] = snap[decltype(slot)::value];
-                TRACE_POINT(4);
                 // refill the slot that was just drained (past the end the cursor stands still and
                 // the loads repeat the last stage's: the count of loads in flight stays fixed)
                 issue_loads(slot, ld);
                 ld.advance(spc, p.strips, NCH);
-                TRACE_POINT(5);
                 lds_barrier();
-                TRACE_POINT(6);
             });
         }
         // the last two tiles: a pass with nothing to stage but the stores
@@ -492,7 +467,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             constexpr int PAR = decltype(par_c)::value;
             if constexpr (LIN) {
                 wait_async_loads<YOUNGER>(qreg[slot][0], qreg[slot][1]);
-                TRACE_POINT(21);
                 busy[PAR] = snap[slot].computes;
                 if (!snap[slot].computes) return;
                 const int unit = snap[slot].unit;
@@ -548,7 +522,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                             acc[PAR][nt] = X::mfma16(a[ks], sf[nt][ks], acc[PAR][nt]);
                     }
                 }
-                TRACE_POINT(22);
             }
         };
 
@@ -580,7 +553,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                             beta[hh][r] = rden;
                         }
                     }
-                TRACE_POINT(23);
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt) {
                     const int hh = PAIR ? (nt >> 1) : 0;
@@ -609,7 +581,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                 constexpr int i = decltype(i_c)::value;          // stage s + i, slot i, parity i % 2
                 if (s + i >= n_stages) return;
                 constexpr int next = (i + 1) % LPD;
-                TRACE_POINT(2);
                 if (s + i + 1 < n_stages) {
                     products(std::integral_constant<int, next>{}, std::integral_constant<int, next & 1>{});
                     // refill the slot just read (past the end the cursor stands still and the
@@ -617,12 +588,9 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     issue_loads(std::integral_constant<int, next>{}, ld);
                     ld.advance(spc, p.strips, NCH);
                 }
-                TRACE_POINT(4);
                 finish(std::integral_constant<int, i & 1>{},
                        reinterpret_cast<float*>(lin_base + (i & 1) * kLinBytes));
-                TRACE_POINT(5);
                 lds_barrier();
-                TRACE_POINT(6);
             });
         }
         lds_barrier();
@@ -671,7 +639,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                             s16x4_t,
                             *reinterpret_cast<const uint2*>(vt + r * kVtRowStride + m * kVtQuadStride + vt_lane));
             }
-            TRACE_POINT(12);
             if (!cu.computes(NCH)) return;
 
             f32x4_t acc[4];
@@ -688,7 +655,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                     acc[rr][0] = acc[rr][1] = acc[rr][2] = acc[rr][3] = bias_dw;
                 }
             }
-            TRACE_POINT(13);
             if constexpr (DW) {
                 // input row (yo - RAD + i) is ring row (4 (ph + 1) + i) mod WR
 #pragma unroll
@@ -699,7 +665,6 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
                         for (int rr = 0; rr < 4; ++rr)
                             acc[rr] = X::mfma4(tw[dy][m], win[(4 * (ph + 1) + rr + dy) % WR][m], acc[rr]);
             }
-            TRACE_POINT(14);
             // results go to the LDS output tile [row][channel][token]
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
@@ -717,19 +682,15 @@ __global__ __launch_bounds__(64 * kApplyWaves) void apply_mfma_kernel(
             static_for<NCH>([&](auto ph) {
                 if (s + decltype(ph)::value < n_stages) {
                     const int b2 = (s + decltype(ph)::value) & 1;
-                    TRACE_POINT(11);
                     consume(ph, cs, vt_base + b2 * kVtBytes,
                             reinterpret_cast<const float*>(lin_base + b2 * kLinBytes),
                             out_base + b2 * kOutBytes);
-                    TRACE_POINT(15);
                     cs.advance(spc, p.strips, NCH);
                     lds_barrier();
-                    TRACE_POINT(16);
                 }
             });
         }
     }
-    TRACE_DUMP
 }
 
 }  // namespace castling

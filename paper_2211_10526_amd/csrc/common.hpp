@@ -204,11 +204,7 @@ __device__ __forceinline__ void async_load16(u32x4_t& dst, const void* base, uin
 // re-used lines (the V halo columns) out of the L2
 __device__ __forceinline__ void async_load16_stream(u32x4_t& dst, const void* base, uint32_t offset)
 {
-#ifdef CASTLING_NO_NT
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(offset), "s"(base) : "memory");
-#else
     asm volatile("global_load_dwordx4 %0, %1, %2 nt" : "=v"(dst) : "v"(offset), "s"(base) : "memory");
-#endif
 }
 template <int YOUNGER>
 __device__ __forceinline__ void wait_async_loads(u32x4_t& a, u32x4_t& b, u32x4_t& c)

@@ -107,8 +107,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     uint32_t* const wl = reinterpret_cast<uint32_t*>(lds + kFusedWOff);
     float* const bl = reinterpret_cast<float*>(lds + kFusedBiasOff);
     float* const vhalf = reinterpret_cast<float*>(lds + kFusedVhalfOff);
-    TRACE_DECL
-    TRACE_POINT(1);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -178,7 +176,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         *reinterpret_cast<u32x4_t*>(vtile + kFusedMaxTokens * PITCH + tid * 16) = zero;
     }
     // ---- phase 1: normalise K, stage k_hat and V, accumulate K_hat^T V
-    TRACE_POINT(2);
     f32x16_t acc[2][2];
     float ksum[8], vsum[8];
     if constexpr (LIN) {
@@ -204,7 +201,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         if constexpr (LIN)
             wait_async_loads<YOUNGER + 4>(kraw[it][0], kraw[it][1], kraw[it][2], kraw[it][3]);
         wait_async_loads<YOUNGER>(vraw[it][0], vraw[it][1], vraw[it][2], vraw[it][3]);
-        TRACE_POINT(3);
         if (n0 >= N) {  // uniform per wave
             if constexpr (it == 0) issue_q_loads();
             return;
@@ -265,7 +261,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         if constexpr (it == 0) issue_q_loads();
     });
     __syncthreads();  // V is staged; the k_hat tiles are dead
-    TRACE_POINT(4);
 
     // ---- between the passes: four block barriers.  Scratch, as byte offsets from `un`:
     //   [0, 32 KB)   exchange slots of the tree (round 1: 8 KB per wave, round 2: 4 KB per wave)
@@ -418,7 +413,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
     __syncthreads();
 
     // ---- phase 3
-    TRACE_POINT(6);
     u32x4_t sf[4][2], kf[2];
     float vh[4] = {0.f, 0.f, 0.f, 0.f};
     if constexpr (LIN) {
@@ -467,7 +461,6 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         if (64 * c >= N) return;  // uniform per block
         if constexpr (LIN) {
             wait_async_loads<2 * (3 - c)>(qraw[c][0], qraw[c][1]);
-            TRACE_POINT(7);
             if (64 * c + 16 * wave < N) {  // uniform per wave
                 const bool qok = 64 * c + 16 * wave + tl < N;
                 const u32x4_t zero = {0u, 0u, 0u, 0u};
@@ -620,12 +613,9 @@ __global__ __launch_bounds__(256, 2) void fused_small_kernel(
         if constexpr (LIN) {
             if (64 * (c + 1) < N) __syncthreads();  // the next chunk overwrites the linear tile
         }
-        TRACE_POINT(9);
     });
     // loads that were never waited for (chunks past N) must land before the registers die
     if constexpr (LIN) wait_async_loads<0>(qraw[3][0], qraw[3][1]);
-    TRACE_POINT(10);
-    TRACE_DUMP
 }
 
 }  // namespace castling

@@ -17,15 +17,9 @@
 
 namespace castling {
 
-#ifndef CASTLING_REDUCE_WAVES
-#define CASTLING_REDUCE_WAVES 4
-#endif
-constexpr int kReduceWaves = CASTLING_REDUCE_WAVES;
+constexpr int kReduceWaves = 4;
 constexpr int kReduceIterTokens = 32;  // tokens one wave stages per iteration
-#ifndef CASTLING_REDUCE_PREFETCH
-#define CASTLING_REDUCE_PREFETCH 2
-#endif
-constexpr int kReducePrefetch = CASTLING_REDUCE_PREFETCH;  // iterations whose loads are in flight
+constexpr int kReducePrefetch = 2;  // iterations whose loads are in flight
 
 // One MFMA operand (8 consecutive tokens of one feature per lane) from a
 // [token][feature] bf16 tile in LDS with `pitch` bytes per token row.
