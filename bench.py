@@ -26,14 +26,46 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (scaled by a copy kernel of known size); see profiles/.
-# workload name -> bytes, filled in from the committed summaries.
-MEASURED_TRAFFIC_BYTES: dict[str, float] = {
-    # apply kernel: FETCH_SIZE 61360 KiB x 2.0 + WRITE_SIZE 49150 KiB x 1.0
-    # (profiles/mfma_kernels_cfg5_pmc_traffic.md)
-    "cfg5_bf16_b2_h12_d64_n16384_k9": (61360 * 2.0 + 49150) * 1024.0,
-}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (scaled by a copy kernel
+# of known size) are read from this committed summary; it names the sources it was measured on.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "forward_pmc_traffic.txt")
+KERNEL_SOURCES = ("apply_mfma.hpp", "reduce_mfma.hpp", "fused_small.hpp", "tables.hpp", "formats.hpp",
+                  "common.hpp", "apply_generic.hpp", "reduce_generic.hpp")
+
+
+def kernel_source_digest() -> str:
+    """sha256 over the forward kernels' source files (what a traffic figure is valid for)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2211_10526_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload: str):
+    """{kernel: bytes per launch} for the workload from the committed PMC summary, and a note.
+    Lines: `workload kernel FETCH_SIZE_KiB WRITE_SIZE_KiB fetch_scale write_scale`; a header line
+    `sources <sha256>` names the kernel sources the counters were read on.  Figures measured on
+    other sources than the ones in the tree are not reported."""
+    if not os.path.exists(TRAFFIC_FILE):
+        return None, "no committed PMC summary"
+    digest, rows = None, {}
+    with open(TRAFFIC_FILE) as f:
+        for line in f:
+            parts = line.split()
+            if not parts or parts[0].startswith("#"):
+                continue
+            if parts[0] == "sources":
+                digest = parts[1]
+            elif parts[0] == workload and len(parts) >= 6:
+                fetch, write, fs, ws = (float(x) for x in parts[2:6])
+                rows[parts[1]] = (fetch * fs + write * ws) * 1024.0
+    if not rows:
+        return None, "workload not in the committed PMC summary"
+    if digest != kernel_source_digest():
+        return None, "kernel sources changed since the committed PMC summary was measured"
+    return rows, None
 
 
 def parse_args():
@@ -57,6 +89,9 @@ def parse_args():
     ap.add_argument("--backward", action="store_true",
                     help="time castling_attn_backward (gradients of q, k, v, filters, bias) "
                          "instead of the forward layer (dense layout)")
+    ap.add_argument("--per-call-filters", action="store_true",
+                    help="pass the DWConv filters to every forward (their operand table is then "
+                         "rebuilt per call) instead of registering them once before timing")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="first run three 256 MiB device-to-device copies: a kernel of known "
@@ -259,8 +294,15 @@ def main():
         attn = binding.CastlingAttn.for_workload(wl)
     stream = torch.cuda.Stream()
 
+    # The DWConv filters are constants of the model at inference: they are registered once (their
+    # matrix-core operand table is built here, outside the timed region) and every forward uses
+    # the registration.  --per-call-filters passes them to each forward instead.
+    if not args.per_call_filters:
+        attn.prepare_weights(sets[0]["w"], stream=stream)
+
     def fwd(t):
-        attn.forward(t["q"], t["k"], t["v"], t["w"], None, t["out"], stream=stream)
+        attn.forward(t["q"], t["k"], t["v"], t["w"] if args.per_call_filters else None, None,
+                     t["out"], stream=stream)
 
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
@@ -337,10 +379,15 @@ def main():
     dominant = max(kernels, key=lambda n: kernels[n][1])
     dom_bytes, dom_ms = kernels[dominant]
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    # measured HBM bytes per launch (dense layout of the plain layer only)
+    traffic, traffic_note = (measured_traffic(wl.name) if args.layout == "dense" and not args.downsample
+                             else (None, "no PMC summary for this layout"))
     roofline = {
         "bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+        "traffic": traffic.get(dominant) if traffic else None,
+        "traffic_per_kernel": traffic, "traffic_forward": sum(traffic.values()) if traffic else None,
+        "traffic_note": traffic_note,
         "algorithmic_bytes": dom_bytes, "kernel_ms": round(dom_ms, 5),
         "reduce_ms": round(reduce_ms, 5), "apply_ms": round(apply_ms, 5),
         "staged_step_ms": round(staged_ms, 5),
@@ -389,7 +436,8 @@ def main():
                    "grid": [wl.grid_h, wl.grid_w], "dw_kernel": wl.dw_kernel,
                    "layout": args.layout, "queries_per_unit": nq,
                    "input_sets_rotated": len(sets), "reduce_splits": n_split,
-                   "kernels_per_forward": launches},
+                   "kernels_per_forward": launches,
+                   "filters": "per call" if args.per_call_filters else "registered once"},
         "roofline": roofline, "cpu_baseline": cpu_baseline,
     }
     print(json.dumps(line))
