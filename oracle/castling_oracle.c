@@ -26,6 +26,10 @@
  *                           linear attention; Eq. 3 sums)
  *   oracle_forward          fast path: Eq. 3 with phi(x) = [x/|x| / sqrt(pi);
  *                           1/sqrt(2)] so that phi(q).phi(k) = 1/2 + q.k/pi
+ *   oracle_backward_explicit, oracle_backward, oracle_backward_explicit_rows
+ *                           gradients of the layer (the paper prints none: the chain rule on
+ *                           the definition above), by the N x N definition, through the
+ *                           reassociated state, and by the definition on selected rows
  *   oracle_softmax_probs    the softmax attention map inside Eq. 10
  *   oracle_sparse_attn      Eq. 10 (masked softmax attention) applied to V
  *   oracle_angular_attn     attention with the exact angular kernel, Eq. 4-5
@@ -531,6 +535,114 @@ void oracle_backward_explicit(const double* q, const double* k, const double* v,
     if (residual)
         for (size_t i = 0; i < total; ++i) dq[i] += g[i];
     free(qh); free(kh); free(dkh); free(A); free(lin); free(dqh);
+}
+
+/* The definition's gradients on selected rows, any N: row i of dq_rows, dk_rows, dv_rows is the
+ * gradient with respect to token tokens[i] of unit units[i] (unit = b*heads + h; rows of one
+ * unit must be adjacent in the lists).  Per unit every query row's r_t and g_t . lin_t come from
+ * the explicit similarities (O(N^2 d)); then dq of a selected token is a sum over all keys, dk
+ * and dv of a selected token sums over all queries.  Nothing of the reassociated form (no state,
+ * no a_t / b_t split) is used.  The filter and bias gradients are not sampled: the DWConv
+ * term's share in oracle_backward is already the definition at any N. */
+void oracle_backward_explicit_rows(const double* q, const double* k, const double* v,
+                                   const double* w, const double* g, int B, int heads, int H, int W,
+                                   int d, int ks, int norm_mode, unsigned branches, double eps,
+                                   int extra, int residual, const int64_t* units,
+                                   const int64_t* tokens, int64_t nrows,
+                                   double* dq_rows, double* dk_rows, double* dv_rows)
+{
+    const int N = extra + H * W;
+    const int rad = ks / 2;
+    (void)B;
+    double* qh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* kh = (double*)malloc(sizeof(double) * (size_t)N * d);
+    double* rsum = (double*)malloc(sizeof(double) * N);   /* r_t = sum_j A_tj */
+    double* glin = (double*)malloc(sizeof(double) * N);   /* g_t . lin_t (normalised form) */
+    int64_t cached_unit = -1;
+    for (int64_t i = 0; i < nrows; ++i) {
+        const int64_t u = units[i];
+        const int s = (int)tokens[i];
+        const int h = (int)(u % heads);
+        const size_t base = (size_t)u * (size_t)N * d;
+        double* dq = dq_rows + (size_t)i * d;
+        double* dk = dk_rows + (size_t)i * d;
+        double* dv = dv_rows + (size_t)i * d;
+        for (int c = 0; c < d; ++c) dq[c] = dk[c] = dv[c] = 0.0;
+        if (branches & ORACLE_BRANCH_LINEAR) {
+            if (u != cached_unit) {
+                oracle_l2_normalize(q + base, N, d, eps, qh);
+                oracle_l2_normalize(k + base, N, d, eps, kh);
+#pragma omp parallel for schedule(static)
+                for (int t = 0; t < N; ++t) {
+                    double lin[d];  /* per iteration, so per thread */
+                    double r = 0.0;
+                    for (int c = 0; c < d; ++c) lin[c] = 0.0;
+                    for (int j = 0; j < N; ++j) {
+                        double x = 0.0;
+                        for (int c = 0; c < d; ++c) x += qh[(size_t)t * d + c] * kh[(size_t)j * d + c];
+                        const double a = 0.5 + x / ORACLE_PI;
+                        r += a;
+                        for (int c = 0; c < d; ++c) lin[c] += a * v[base + (size_t)j * d + c];
+                    }
+                    double gl = 0.0;
+                    for (int c = 0; c < d; ++c) gl += g[base + (size_t)t * d + c] * lin[c] / r;
+                    rsum[t] = r;
+                    glin[t] = gl;
+                }
+                cached_unit = u;
+            }
+            /* token s as a query: dLoss/dq_hat_s = sum_j dA_sj k_hat_j / pi */
+            {
+                double dqh[d];
+                const double* gs = g + base + (size_t)s * d;
+                for (int c = 0; c < d; ++c) dqh[c] = 0.0;
+                for (int j = 0; j < N; ++j) {
+                    double g_v = 0.0;
+                    for (int c = 0; c < d; ++c) g_v += gs[c] * v[base + (size_t)j * d + c];
+                    const double dA = (norm_mode == 0) ? (g_v - glin[s]) / rsum[s] : g_v;
+                    for (int c = 0; c < d; ++c) dqh[c] += dA * kh[(size_t)j * d + c] / ORACLE_PI;
+                }
+                normalize_backward(q + base + (size_t)s * d, dqh, d, eps, dq);
+            }
+            /* token s as a key: dv_s = sum_t A_ts g_t [/ r_t], dLoss/dk_hat_s = sum_t dA_ts q_hat_t / pi */
+            {
+                double dkh[d];
+                const double* vs = v + base + (size_t)s * d;
+                for (int c = 0; c < d; ++c) dkh[c] = 0.0;
+                for (int t = 0; t < N; ++t) {
+                    const double* gt = g + base + (size_t)t * d;
+                    double x = 0.0, g_v = 0.0;
+                    for (int c = 0; c < d; ++c) {
+                        x += qh[(size_t)t * d + c] * kh[(size_t)s * d + c];
+                        g_v += gt[c] * vs[c];
+                    }
+                    const double a = 0.5 + x / ORACLE_PI;
+                    const double scale = (norm_mode == 0) ? 1.0 / rsum[t] : 1.0;
+                    const double dA = (norm_mode == 0) ? (g_v - glin[t]) / rsum[t] : g_v;
+                    for (int c = 0; c < d; ++c) {
+                        dv[c] += a * scale * gt[c];
+                        dkh[c] += dA * qh[(size_t)t * d + c] / ORACLE_PI;
+                    }
+                }
+                normalize_backward(k + base + (size_t)s * d, dkh, d, eps, dk);
+            }
+        }
+        /* DWConv term: v_s enters the output rows whose window covers it */
+        if ((branches & ORACLE_BRANCH_DWCONV) && s >= extra) {
+            const int ys = (s - extra) / W, xs = (s - extra) % W;
+            for (int dy = 0; dy < ks; ++dy)
+                for (int dx = 0; dx < ks; ++dx) {
+                    const int yo = ys - (dy - rad), xo = xs - (dx - rad);
+                    if (yo < 0 || yo >= H || xo < 0 || xo >= W) continue;
+                    const double* go = g + base + ((size_t)extra + (size_t)yo * W + xo) * d;
+                    for (int c = 0; c < d; ++c)
+                        dv[c] += w[(((size_t)h * d + c) * ks + dy) * ks + dx] * go[c];
+                }
+        }
+        if (residual)
+            for (int c = 0; c < d; ++c) dq[c] += g[base + (size_t)s * d + c];
+    }
+    free(qh); free(kh); free(rsum); free(glin);
 }
 
 /* The same through the reassociated state (any N): with a_t = dLoss/dnum_t and

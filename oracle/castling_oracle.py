@@ -50,6 +50,10 @@ def lib():
         bwd = [_dp] * 5 + [C.c_int] * 7 + [C.c_uint, C.c_double, C.c_int, C.c_int] + [_dp] * 5
         L.oracle_backward_explicit.argtypes = bwd
         L.oracle_backward.argtypes = bwd
+        L.oracle_backward_explicit_rows.argtypes = \
+            [_dp] * 5 + [C.c_int] * 7 + [C.c_uint, C.c_double, C.c_int, C.c_int] + \
+            [_ip, _ip, C.c_int64] + [_dp] * 3
+        L.oracle_backward_explicit_rows.restype = None
         L.oracle_backward_pooled_explicit.argtypes = \
             [_dp] * 5 + [C.c_int] * 9 + [C.c_uint, C.c_double] + [_dp] * 5
         L.oracle_state.argtypes = [_dp, _dp, C.c_int, C.c_int, C.c_int, C.c_int, C.c_double, _dp]
@@ -225,6 +229,34 @@ def backward(q, k, v, w, g, grid_h, grid_w, norm=NORM_ROWSUM, branches=BRANCH_AL
     """The same through the reassociated state; any N."""
     return _backward(lib().oracle_backward, q, k, v, w, g, grid_h, grid_w, norm, branches, eps,
                      extra, residual, with_bias)
+
+
+def backward_explicit_rows(q, k, v, w, g, grid_h, grid_w, units, tokens, norm=NORM_ROWSUM,
+                           branches=BRANCH_ALL, eps=DEFAULT_EPS, extra=0, residual=False):
+    """Gradient rows (dq, dk, dv), each [nrows, d], with respect to the selected tokens
+    (unit = b*heads + h, token), by differentiating the definition; any N, O(N^2 d) per unit
+    that has a selected row.  Uses nothing of the reassociated form."""
+    q, k, v, w, g = _f64(q), _f64(k), _f64(v), _f64(w), _f64(g)
+    B, heads, N, d = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and g.shape == q.shape
+    assert N == extra + grid_h * grid_w and w.shape[:2] == (heads, d) and w.shape[2] == w.shape[3]
+    units = np.ascontiguousarray(units, dtype=np.int64)
+    tokens = np.ascontiguousarray(tokens, dtype=np.int64)
+    assert units.shape == tokens.shape and units.ndim == 1
+    assert units.min() >= 0 and units.max() < B * heads and tokens.min() >= 0 and tokens.max() < N
+    order = np.argsort(units, kind="stable")      # rows of one unit next to each other
+    us, ts = np.ascontiguousarray(units[order]), np.ascontiguousarray(tokens[order])
+    rows = [np.empty((len(us), d), dtype=np.float64) for _ in range(3)]
+    lib().oracle_backward_explicit_rows(
+        _p(q), _p(k), _p(v), _p(w), _p(g), B, heads, grid_h, grid_w, d, w.shape[2], int(norm),
+        int(branches), float(eps), int(extra), int(bool(residual)), us.ctypes.data_as(_ip),
+        ts.ctypes.data_as(_ip), len(us), _p(rows[0]), _p(rows[1]), _p(rows[2]))
+    out = []
+    for r in rows:
+        o = np.empty_like(r)
+        o[order] = r
+        out.append(o)
+    return tuple(out)
 
 
 def backward_pooled_explicit(q, k, v, w, g, grid_h, grid_w, pool=2, residual=True, norm=NORM_ROWSUM,

@@ -208,18 +208,37 @@ def test_backward_needs_a_training_handle_and_distinct_buffers():
 
 
 @pytest.mark.parametrize("name", ["cfg5_bf16_b2_h12_d64_n16384_k9", "x_f16_b2_h12_d64_n16384_k9",
-                                  "cfg1_f32_b1_h4_d32_n196_k3"])
+                                  "cfg1_f32_b1_h4_d32_n196_k3", "cfg2_bf16_b64_h8_d64_n196_k3",
+                                  "cfg3_bf16_b32_h6_d64_n784_k3_outliers",
+                                  "cfg4_bf16_b8_h8_d64_n4096_k5"])
 def test_gradients_at_benchmark_size(oracle, name):
-    """The largest benchmark workload (and its fp16 twin: a = g / den is of the order 1e-4 there,
-    stored scaled) in the configuration bench.py --backward times, every element against the
-    oracle's reassociated backward (itself pinned to the definition)."""
+    """The benchmark workloads (and the fp16 twin of the largest: a = g / den is of the order
+    1e-4 there, stored scaled) in the configuration bench.py --backward times.  Every element
+    against the oracle's reassociated backward, and sampled rows of dq, dk, dv against the
+    gradient of the definition itself (explicit N x N similarities, nothing of the reassociated
+    derivation that oracle and kernels share)."""
     wl = inputs.workload(name)
     x = draw(wl, 0, seed=96)
     q, k, v, w, _ = oracle_inputs(x)
+    g = inputs.to_f64(x["g"])
     print(f"case backward full size {wl.name}", flush=True)
-    want = oracle.backward(q, k, v, w, inputs.to_f64(x["g"]), wl.grid_h, wl.grid_w)
+    want = oracle.backward(q, k, v, w, g, wl.grid_h, wl.grid_w)
+    # first and last unit; corners and interior of the grid, first and last token
+    N, W = wl.N, wl.grid_w
+    toks = np.array([0, 1, W - 1, W, N // 2 + 3, N - W, N - 1])
+    units = np.repeat([0, wl.units - 1], len(toks))
+    tokens = np.tile(toks, 2)
+    rows = oracle.backward_explicit_rows(q, k, v, w, g, wl.grid_h, wl.grid_w, units, tokens)
+    for name_, full, r in zip(("dq", "dk", "dv"), want, rows):
+        # the oracle's two forms agree at full size far below any kernel tolerance
+        np.testing.assert_allclose(full.reshape(wl.units, N, wl.d)[units, tokens], r, rtol=1e-7,
+                                   atol=1e-9 * np.abs(full).max(), err_msg=name_)
     got = run(wl, x)
     check(got, want, GRAD_TOL[wl.dtype], wl.name)
+    for name_, a, full, r in zip(("dq", "dk", "dv"), got, want, rows):
+        rms = np.sqrt(np.mean(full * full))
+        err = np.max(np.abs(a.reshape(wl.units, N, wl.d)[units, tokens] - r) / np.maximum(np.abs(r), rms))
+        assert err <= GRAD_TOL[wl.dtype], (wl.name, name_, err)
 
 
 EDGES = [

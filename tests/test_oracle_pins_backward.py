@@ -79,6 +79,47 @@ def test_gradients_equal_autograd_of_the_definition(oracle, case, norm, branches
             np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-10, err_msg=f"{fn.__name__} {name}")
 
 
+@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("norm", [0, 1])
+@pytest.mark.parametrize("branches", [3, 1, 2])
+def test_sampled_gradient_rows_equal_autograd_of_the_definition(oracle, case, norm, branches):
+    """backward_explicit_rows (the full-size check of the kernels' gradients) on every token of
+    every unit, asked for in a scrambled order, against autograd through the plain torch forward."""
+    B, heads, H, W, d, ks, extra = case
+    q, k, v, w, bias, g = draw(85, *case)
+    eps = 0.9 * math.sqrt(d)
+    residual = branches & 1
+    tq, tk, tv, tw, tb = (torch.tensor(a, requires_grad=True) for a in (q, k, v, w, bias))
+    out = torch_forward(tq, tk, tv, tw, tb, H, W, norm, branches, eps, extra, residual)
+    (out * torch.tensor(g)).sum().backward()
+    want = [t.grad.numpy() if t.grad is not None else np.zeros(t.shape) for t in (tq, tk, tv)]
+    N = extra + H * W
+    r = np.random.default_rng(5)
+    pick = r.permutation(B * heads * N)
+    units, tokens = pick // N, pick % N
+    got = oracle.backward_explicit_rows(q, k, v, w, g, H, W, units, tokens, norm=norm,
+                                        branches=branches, eps=eps, extra=extra, residual=residual)
+    for name, a, b in zip(("dq", "dk", "dv"), got, want):
+        np.testing.assert_allclose(a, b.reshape(B * heads, N, d)[units, tokens], rtol=1e-9, atol=1e-10,
+                                   err_msg=name)
+
+
+def test_sampled_gradient_rows_at_a_larger_size(oracle):
+    """A few rows of two units against the full explicit backward (itself pinned above), on a
+    shape where the filter is wider than the grid's short side."""
+    case = (1, 3, 4, 33, 16, 9, 2)
+    B, heads, H, W, d, ks, extra = case
+    q, k, v, w, bias, g = draw(86, *case)
+    N = extra + H * W
+    units = np.array([2, 0, 2, 0, 2, 0])
+    tokens = np.array([0, 1, N - 1, extra, extra + W, 57])
+    for norm in (0, 1):
+        full = oracle.backward_explicit(q, k, v, w, g, H, W, norm=norm, extra=extra)
+        rows = oracle.backward_explicit_rows(q, k, v, w, g, H, W, units, tokens, norm=norm, extra=extra)
+        for a, b in zip(rows, full[:3]):
+            np.testing.assert_allclose(a, b.reshape(B * heads, N, d)[units, tokens], rtol=1e-10, atol=1e-12)
+
+
 @pytest.mark.parametrize("case", CASES[:2])
 @pytest.mark.parametrize("norm", [0, 1])
 def test_directional_derivatives_by_central_differences(oracle, case, norm):
