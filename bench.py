@@ -388,6 +388,9 @@ def main():
         "traffic": traffic.get(dominant) if traffic else None,
         "traffic_per_kernel": traffic, "traffic_forward": sum(traffic.values()) if traffic else None,
         "traffic_note": traffic_note,
+        # all measured bytes of one forward over the step time: what the memory system delivers
+        "traffic_forward_gbs": (round(sum(traffic.values()) / (ms_per_step * 1e-3) / 1e9, 1)
+                                if traffic else None),
         "algorithmic_bytes": dom_bytes, "kernel_ms": round(dom_ms, 5),
         "reduce_ms": round(reduce_ms, 5), "apply_ms": round(apply_ms, 5),
         "staged_step_ms": round(staged_ms, 5),
