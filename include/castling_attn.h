@@ -200,8 +200,10 @@ int castling_attn_apply(castling_attn_t h, const void* q, const void* v, const v
  * without the DWConv branch grad_w and grad_bias (where given) are zeros and dw_weight may be
  * NULL.  With RESIDUAL_Q grad_q includes grad_out.  The forward pass is not needed
  * beforehand: pass 1 is recomputed.  Afterwards the handle holds no state to apply or fetch.
- * Pointers 16-byte aligned; no gradient (grad_w and grad_bias included) may overlap an input,
- * the filters or another gradient (CASTLING_ERR_ALIAS).  Only enqueues work on `stream`. */
+ * Pointers 16-byte aligned; no gradient (grad_w and grad_bias included) may overlap an input
+ * or the filters, grad_w and grad_bias may not overlap any other gradient, and grad_q, grad_k,
+ * grad_v must be three different pointers (CASTLING_ERR_ALIAS); their address ranges may
+ * interleave, as slices of one fused [B][N][3][heads][d] gradient tensor do.  Only enqueues work on `stream`. */
 int castling_attn_backward(castling_attn_t h, const void* q, const void* k, const void* v,
                            const void* dw_weight, const void* grad_out, void* grad_q, void* grad_k,
                            void* grad_v, float* grad_w, float* grad_bias, void* stream);
