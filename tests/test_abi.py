@@ -122,7 +122,7 @@ def test_validate_null_and_strerror():
     L = b.lib()
     assert L.castling_attn_validate(None) == b.ERR_INVALID_ARG
     assert b.strerror(b.OK) == "ok"
-    for s in (1, 2, 3, 4, 99):
+    for s in (1, 2, 3, 4, 5, 99):
         assert isinstance(b.strerror(s), str) and b.strerror(s)
     # create refuses a bad descriptor before it allocates anything
     h = C.c_void_p(123)
@@ -143,3 +143,16 @@ def test_validate_null_and_strerror():
     assert L.castling_attn_prepare_weights(None, None, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_get_state(None, None, 0, None) == b.ERR_INVALID_ARG
     assert L.castling_attn_backward(*([None] * 12)) == b.ERR_INVALID_ARG
+    # the forward without allocation checks its descriptor before it touches the device
+    assert L.castling_attn_forward_static(None, *([None] * 7)) == b.ERR_INVALID_ARG
+    assert L.castling_attn_forward_static(C.byref(d), *([None] * 7)) == b.ERR_INVALID_ARG
+    t = good()
+    t.flags = b.FLAG_TRAINING
+    assert L.castling_attn_forward_static(C.byref(t), *([None] * 7)) == b.ERR_INVALID_ARG
+    assert "scratch" in b.strerror(b.ERR_TOO_LARGE) and b.ERR_TOO_LARGE == 5
+    import os
+    import re
+    header = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include",
+                               "castling_attn.h")).read()
+    m = re.search(r"#define CASTLING_STATIC_SCRATCH_BYTES \((\d+)u << (\d+)\)", header)
+    assert m and b.STATIC_SCRATCH_BYTES == int(m.group(1)) << int(m.group(2))
